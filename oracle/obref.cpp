@@ -1,0 +1,300 @@
+// obref -- CPU oracle for the 1-bit LAMB compression-stage step.  Test infrastructure only:
+// see obref.h for what may load it and for the list of readings it fixes.
+//
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC obref.cpp -o libobref.so
+// Every loop below is scalar and in the order the paper states the step; T is float for the
+// oracle proper and double for the shadow the algebraic pins use.
+#include "obref.h"
+
+#include <cmath>
+#include <vector>
+
+namespace {
+
+// clip(x, a, b) := min{max{x, a}, b} as printed under eq. (1); NaN -> a.
+template <class T>
+inline T clip(T x, T a, T b) {
+  T y = (x > a) ? x : a;
+  return (y < b) ? y : b;
+}
+
+inline bool get_bit(const uint8_t* bits, int64_t i) { return (bits[i >> 3] >> (i & 7)) & 1u; }
+
+// C[z]: sign bits and one scale, scale = ||z||_2/sqrt(n) so that the decompressed vector
+// keeps the L2 norm of z (Section 2).  Error feedback of Algorithm 1 lines 7 and 10.
+template <class T>
+void compress_chunk(const T* z, int64_t n, uint8_t* bits, T* scale, T* err) {
+  double S = 0.0;
+  for (int64_t i = 0; i < n; ++i) S += (double)z[i] * (double)z[i];
+  const T s = (T)std::sqrt(S / (double)n);
+  for (int64_t i = 0; i < n; i += 8) {
+    unsigned byte = 0;
+    for (int j = 0; j < 8; ++j) {
+      const T zi = z[i + j];
+      const bool b = (zi >= (T)0);
+      if (b) byte |= (1u << j);
+      const T d = b ? s : -s;
+      err[i + j] = zi - d;
+    }
+    bits[i >> 3] = (uint8_t)byte;
+  }
+  *scale = s;
+}
+
+template <class T>
+void decompress_chunk(const uint8_t* bits, T scale, int64_t n, T* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = get_bit(bits, i) ? scale : -scale;
+}
+
+// Algorithm 1 lines 6-7 (+ A.5.2 momentum scaling), chunk by chunk (A.7.1).
+template <class T>
+void compress_local(int64_t n_pad, int64_t L, const int64_t* off, int32_t W, const T* mom_scale,
+                    T beta1, const T* g, const T* m, T* err, uint8_t* bits, T* scales) {
+  const T omb1 = (T)1 - beta1;
+  // z = k*(beta1*m + (1-beta1)*g) + err, written over err
+  for (int64_t l = 0; l < L; ++l) {
+    const T k = mom_scale ? mom_scale[l] : (T)1;
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+      const T mloc = beta1 * m[i] + omb1 * g[i];
+      err[i] = k * mloc + err[i];
+    }
+  }
+  for (int64_t i = off[L]; i < n_pad; ++i) {
+    const T mloc = beta1 * m[i] + omb1 * g[i];
+    err[i] = mloc + err[i];
+  }
+  const int64_t n_c = n_pad / W;
+  for (int32_t c = 0; c < W; ++c)
+    compress_chunk<T>(err + c * n_c, n_c, bits + c * (n_c / 8), scales + c, err + c * n_c);
+}
+
+// Algorithm 1 line 10 on one chunk.
+template <class T>
+void server_reduce(int64_t n_c, int32_t W, const uint8_t* bits_in, const T* scales_in,
+                   T* err_server, uint8_t* bits_out, T* scale_out) {
+  const T invW = (T)1 / (T)W;
+  for (int64_t j = 0; j < n_c; ++j) {
+    T acc = (T)0;
+    for (int32_t w = 0; w < W; ++w) {
+      const T s = scales_in[w];
+      acc = acc + (get_bit(bits_in + (int64_t)w * (n_c / 8), j) ? s : -s);
+    }
+    err_server[j] = acc * invW + err_server[j];
+  }
+  compress_chunk<T>(err_server, n_c, bits_out, scale_out, err_server);
+}
+
+// Algorithm 1 line 13 (+ A.5.2: divide the global momentum by the layer's coefficient).
+template <class T>
+void global_momentum(int64_t n_pad, int64_t L, const int64_t* off, int32_t W, const T* mom_scale,
+                     const uint8_t* bits_all, const T* server_scales, T* mt) {
+  const int64_t n_c = n_pad / W;
+  for (int64_t l = 0; l < L; ++l) {
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+      const T s = server_scales[i / n_c];
+      const T d = get_bit(bits_all, i) ? s : -s;
+      mt[i] = mom_scale ? d / mom_scale[l] : d;
+    }
+  }
+  for (int64_t i = off[L]; i < n_pad; ++i) mt[i] = (T)0;
+}
+
+// Algorithm 1 lines 15-20.
+template <class T>
+void ratios_dense(int64_t L, const int64_t* off, T beta1, T beta2, T r_min, T r_max, T r_thr,
+                  const T* mt, const T* m, T* v_fresh, const T* v_frozen, const T* c_avg,
+                  T* r_prev, T* coeff_c) {
+  const T omb1 = (T)1 - beta1;
+  const T omb2 = (T)1 - beta2;
+  for (int64_t l = 0; l < L; ++l) {
+    T r = (T)0;
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+      const T gr = (mt[i] - beta1 * m[i]) / omb1;         // line 15
+      const T vf = beta2 * v_fresh[i] + omb2 * (gr * gr);  // line 16
+      v_fresh[i] = vf;
+      const T q = v_frozen[i] / vf;                        // line 17 (max element)
+      if (q > r) r = q;
+    }
+    const T lo = ((T)1 - r_thr) * r_prev[l];
+    const T hi = ((T)1 + r_thr) * r_prev[l];
+    r = clip<T>(r, lo, hi);       // line 18
+    r = clip<T>(r, r_min, r_max); // line 19
+    r_prev[l] = r;
+    coeff_c[l] = r * c_avg[l];    // line 20
+  }
+}
+
+// Algorithm 1 line 21; commits the global momentum (line 13).
+template <class T>
+void apply_dense(int64_t L, const int64_t* off, T eta, T lr, const T* mt, const T* coeff_c,
+                 const T* v_frozen, T* x, T* m) {
+  for (int64_t l = 0; l < L; ++l) {
+    const T a = lr * coeff_c[l];
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+      const T u = mt[i] / (std::sqrt(v_frozen[i]) + eta);
+      x[i] = x[i] - a * u;
+      m[i] = mt[i];
+    }
+  }
+}
+
+// eq. (1) per tensor, then line 2 of Algorithm 1.
+template <class T>
+void warmup_step(int64_t L, const int64_t* off, T beta1, T beta2, T beta3, T eta, T c_min, T c_max,
+                 T wd, T lr, const T* g, T* m, T* v, T* x, T* c_out, T* c_avg) {
+  const T omb1 = (T)1 - beta1, omb2 = (T)1 - beta2, omb3 = (T)1 - beta3;
+  std::vector<T> u;
+  for (int64_t l = 0; l < L; ++l) {
+    const int64_t a = off[l], n = off[l + 1] - off[l];
+    u.assign((size_t)n, (T)0);
+    double Sx = 0.0, Su = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+      const int64_t i = a + j;
+      m[i] = beta1 * m[i] + omb1 * g[i];
+      v[i] = beta2 * v[i] + omb2 * (g[i] * g[i]);
+      T ui = m[i] / (std::sqrt(v[i]) + eta);
+      if (wd != (T)0) ui = ui + wd * x[i];
+      u[(size_t)j] = ui;
+      Sx += (double)x[i] * (double)x[i];
+      Su += (double)ui * (double)ui;
+    }
+    const T nx = (T)std::sqrt(Sx), nu = (T)std::sqrt(Su);
+    const T c = clip<T>(nx / nu, c_min, c_max);
+    const T step = lr * c;
+    for (int64_t j = 0; j < n; ++j) x[a + j] = x[a + j] - step * u[(size_t)j];
+    c_out[l] = c;
+    c_avg[l] = beta3 * c_avg[l] + omb3 * c;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t obref_padded_len(int64_t n, int32_t W) {
+  const int64_t q = 256 * (int64_t)W;
+  return ((n + q - 1) / q) * q;
+}
+
+void obref_compress_chunk(const float* z, int64_t n, uint8_t* bits, float* scale, float* err) {
+  compress_chunk<float>(z, n, bits, scale, err);
+}
+void obref64_compress_chunk(const double* z, int64_t n, uint8_t* bits, double* scale, double* err) {
+  compress_chunk<double>(z, n, bits, scale, err);
+}
+void obref_decompress_chunk(const uint8_t* bits, float scale, int64_t n, float* out) {
+  decompress_chunk<float>(bits, scale, n, out);
+}
+void obref64_decompress_chunk(const uint8_t* bits, double scale, int64_t n, double* out) {
+  decompress_chunk<double>(bits, scale, n, out);
+}
+
+void obref_compress_local(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                          const float* mom_scale, float beta1, const float* g, const float* m,
+                          float* err, uint8_t* bits, float* scales) {
+  compress_local<float>(n_pad, L, off, W, mom_scale, beta1, g, m, err, bits, scales);
+}
+void obref64_compress_local(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                            const double* mom_scale, double beta1, const double* g, const double* m,
+                            double* err, uint8_t* bits, double* scales) {
+  compress_local<double>(n_pad, L, off, W, mom_scale, beta1, g, m, err, bits, scales);
+}
+
+void obref_server_reduce(int64_t n_c, int32_t W, const uint8_t* bits_in, const float* scales_in,
+                         float* err_server, uint8_t* bits_out, float* scale_out) {
+  server_reduce<float>(n_c, W, bits_in, scales_in, err_server, bits_out, scale_out);
+}
+void obref64_server_reduce(int64_t n_c, int32_t W, const uint8_t* bits_in, const double* scales_in,
+                           double* err_server, uint8_t* bits_out, double* scale_out) {
+  server_reduce<double>(n_c, W, bits_in, scales_in, err_server, bits_out, scale_out);
+}
+
+void obref_global_momentum(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                           const float* mom_scale, const uint8_t* bits_all,
+                           const float* server_scales, float* mt) {
+  global_momentum<float>(n_pad, L, off, W, mom_scale, bits_all, server_scales, mt);
+}
+void obref64_global_momentum(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                             const double* mom_scale, const uint8_t* bits_all,
+                             const double* server_scales, double* mt) {
+  global_momentum<double>(n_pad, L, off, W, mom_scale, bits_all, server_scales, mt);
+}
+
+void obref_ratios_dense(int64_t L, const int64_t* off, float beta1, float beta2, float r_min,
+                        float r_max, float r_thr, const float* mt, const float* m, float* v_fresh,
+                        const float* v_frozen, const float* c_avg, float* r_prev, float* coeff_c) {
+  ratios_dense<float>(L, off, beta1, beta2, r_min, r_max, r_thr, mt, m, v_fresh, v_frozen, c_avg,
+                      r_prev, coeff_c);
+}
+void obref64_ratios_dense(int64_t L, const int64_t* off, double beta1, double beta2, double r_min,
+                          double r_max, double r_thr, const double* mt, const double* m,
+                          double* v_fresh, const double* v_frozen, const double* c_avg,
+                          double* r_prev, double* coeff_c) {
+  ratios_dense<double>(L, off, beta1, beta2, r_min, r_max, r_thr, mt, m, v_fresh, v_frozen, c_avg,
+                       r_prev, coeff_c);
+}
+
+void obref_apply_dense(int64_t L, const int64_t* off, float eta, float lr, const float* mt,
+                       const float* coeff_c, const float* v_frozen, float* x, float* m) {
+  apply_dense<float>(L, off, eta, lr, mt, coeff_c, v_frozen, x, m);
+}
+void obref64_apply_dense(int64_t L, const int64_t* off, double eta, double lr, const double* mt,
+                         const double* coeff_c, const double* v_frozen, double* x, double* m) {
+  apply_dense<double>(L, off, eta, lr, mt, coeff_c, v_frozen, x, m);
+}
+
+void obref_layer_ratios(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                        const float* mom_scale, float beta1, float beta2, float r_min, float r_max,
+                        float r_thr, const uint8_t* bits_all, const float* server_scales,
+                        const float* m, float* v_fresh, const float* v_frozen, const float* c_avg,
+                        float* r_prev, float* coeff_c) {
+  std::vector<float> mt((size_t)n_pad);
+  global_momentum<float>(n_pad, L, off, W, mom_scale, bits_all, server_scales, mt.data());
+  ratios_dense<float>(L, off, beta1, beta2, r_min, r_max, r_thr, mt.data(), m, v_fresh, v_frozen,
+                      c_avg, r_prev, coeff_c);
+}
+
+void obref_decompress_apply(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                            const float* mom_scale, float eta, float lr, const uint8_t* bits_all,
+                            const float* server_scales, const float* coeff_c, const float* v_frozen,
+                            float* x, float* m) {
+  std::vector<float> mt((size_t)n_pad);
+  global_momentum<float>(n_pad, L, off, W, mom_scale, bits_all, server_scales, mt.data());
+  apply_dense<float>(L, off, eta, lr, mt.data(), coeff_c, v_frozen, x, m);
+}
+
+void obref_warmup_step(int64_t L, const int64_t* off, float beta1, float beta2, float beta3,
+                       float eta, float c_min, float c_max, float weight_decay, float lr,
+                       const float* g, float* m, float* v, float* x, float* c_out, float* c_avg) {
+  warmup_step<float>(L, off, beta1, beta2, beta3, eta, c_min, c_max, weight_decay, lr, g, m, v, x,
+                     c_out, c_avg);
+}
+void obref64_warmup_step(int64_t L, const int64_t* off, double beta1, double beta2, double beta3,
+                         double eta, double c_min, double c_max, double weight_decay, double lr,
+                         const double* g, double* m, double* v, double* x, double* c_out,
+                         double* c_avg) {
+  warmup_step<double>(L, off, beta1, beta2, beta3, eta, c_min, c_max, weight_decay, lr, g, m, v, x,
+                      c_out, c_avg);
+}
+
+void obref_momentum_scale(int64_t L, const int64_t* off, const float* m, float* mom_scale) {
+  std::vector<double> sigma((size_t)L, 0.0);
+  double sum = 0.0;
+  int64_t cnt = 0;
+  for (int64_t l = 0; l < L; ++l) {
+    const int64_t n = off[l + 1] - off[l];
+    if (n <= 0) continue;
+    double S = 0.0;
+    for (int64_t i = off[l]; i < off[l + 1]; ++i) S += (double)m[i] * (double)m[i];
+    sigma[(size_t)l] = std::sqrt(S / (double)n);
+    sum += sigma[(size_t)l];
+    ++cnt;
+  }
+  const double mean = cnt ? sum / (double)cnt : 0.0;
+  for (int64_t l = 0; l < L; ++l) {
+    const double s = sigma[(size_t)l];
+    mom_scale[l] = (s > 0.0) ? (float)(mean / s) : 1.0f;
+  }
+}
+
+}  // extern "C"
