@@ -1,0 +1,164 @@
+/*
+ * libonebitlamb -- the compression-stage optimizer step of 1-bit LAMB (arXiv 2104.06069,
+ * Algorithm 1) and the LAMB warmup step (eq. (1)) over one GPU's flat fp32 parameter buffer,
+ * as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * Model of the data
+ * -----------------
+ * All tensors of the model are viewed as one contiguous 1-D fp32 buffer ("momentum fusion",
+ * Appendix A.5.1) described by `layer_offsets` (L+1 entries, tightly packed, no alignment
+ * between tensors).  "Layer" means tensor: each has its own coefficients (Section 2).
+ *   N      = layer_offsets[L]            real parameters
+ *   W      = num_workers                 = number of chunks of the compressed allreduce (Section 5)
+ *   N_pad  = N rounded up to 256*W       length of every N-sized buffer
+ *   n_c    = N_pad / W                   chunk length (a multiple of 256)
+ * Elements [N, N_pad) are padding: they take part in chunk scales and error feedback like any
+ * other element (with momentum-scale coefficient 1) but belong to no layer, so the ratio, the
+ * parameter update and the momentum commit never touch them.  The caller zero-fills the
+ * padding of every buffer once (and of each gradient).
+ *
+ * Compression operator C[.] (Section 2: "+-1 signs and a scale"; the paper gives no formula or
+ * wire format, this library fixes them):
+ *   scale = ||z||_2 / sqrt(n) per chunk (keeps the L2 norm of the chunk), accumulated in fp64;
+ *   bit   = (z >= 0) as an IEEE compare (+0, -0 -> 1; NaN -> 0); 1 decodes to +scale, 0 to -scale;
+ *   packed stream: element i is bit (i % 32) of the little-endian uint32 word i / 32.
+ *
+ * Conventions
+ * -----------
+ * - Pointers named in ob_lamb_state and the packed/scales/grad arguments are DEVICE pointers,
+ *   owned by the caller, 16-byte aligned.  ob_lamb_config and its layer_offsets are HOST memory,
+ *   copied by ob_lamb_create.
+ * - Every step call validates its arguments on the host, enqueues kernels on `hip_stream`
+ *   (a hipStream_t passed as void*; NULL = the default stream) and returns without
+ *   synchronising.  On error nothing is enqueued and a negative ob_status is returned.
+ * - All arithmetic is IEEE binary32 with one rounding per operation (no fused multiply-add),
+ *   except the two sum-of-squares reductions (chunk scales, LAMB norms), which accumulate in
+ *   binary64 in a fixed order: results are bit-reproducible from run to run.
+ * - A context owns a small device workspace (partial sums, per-layer maxima, tile tables).
+ *   Calls on one context must not overlap in time (use one stream, or order them yourself).
+ * - Call order of one compression step:
+ *     ob_lamb_compress_local -> [exchange] -> ob_lamb_server_reduce -> [exchange]
+ *     -> ob_lamb_layer_ratios -> ob_lamb_decompress_apply.
+ *   ob_lamb_layer_ratios must precede ob_lamb_decompress_apply in the same step (the former
+ *   needs the previous momentum that the latter overwrites).
+ */
+#ifndef ONEBITLAMB_H
+#define ONEBITLAMB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ob_lamb_ctx ob_lamb_ctx; /* opaque */
+
+typedef enum ob_status {
+  OB_OK = 0,
+  OB_ERR_NULL = -1,  /* a required pointer is NULL */
+  OB_ERR_ARG = -2,   /* a size, offset table or hyper-parameter is invalid */
+  OB_ERR_ALIGN = -3, /* a device pointer is not 16-byte aligned */
+  OB_ERR_STATE = -4, /* reserved */
+  OB_ERR_HIP = -5    /* a HIP runtime call failed (see ob_lamb_last_hip_error) */
+} ob_status;
+
+typedef struct ob_lamb_config {
+  int64_t num_layers;           /* L >= 1 */
+  const int64_t* layer_offsets; /* host, L+1 entries, [0] = 0, non-decreasing (empty layers allowed) */
+  int32_t num_workers;          /* W >= 1 */
+  int32_t server_chunk;         /* chunk this rank serves, 0..W-1 (informational; see server_reduce) */
+  float beta1, beta2, beta3;    /* momentum, variance, coefficient moving average (Algorithm 1 line 1) */
+  float eta;                    /* added to sqrt(v) in eq. (1) and in line 21; 0 = line 21 as printed */
+  float c_min, c_max;           /* clip of LAMB's coefficient in eq. (1) (warmup only) */
+  float r_min, r_max;           /* Algorithm 1 line 19 */
+  float r_threshold;            /* Algorithm 1 line 18 */
+  float weight_decay;           /* warmup only: u += wd * x; 0 = eq. (1) as printed */
+} ob_lamb_config;
+
+/* Device pointers, caller-owned, fp32.  N-sized arrays have N_pad elements. */
+typedef struct ob_lamb_state {
+  float* x;          /* [N_pad] parameters */
+  float* m;          /* [N_pad] momentum: the global m_{t-1} of Algorithm 1 line 13 */
+  float* v_fresh;    /* [N_pad] variance, kept up to date (eq. (1) in warmup; line 16 afterwards) */
+  float* v_frozen;   /* [N_pad] v_{T_w}: variance stored at the end of warmup (line 3) */
+  float* err_worker; /* [N_pad] delta^(i): this worker's compression error (line 7) */
+  float* err_server; /* [n_c]   delta-bar: server error of the chunk this rank serves (line 10) */
+  float* c_avg;      /* [L] moving average of LAMB's coefficient (line 2), frozen after warmup */
+  float* r_prev;     /* [L] r_{t-1}^(l), starts at 1 (line 1) */
+  float* coeff_c;    /* [L] out: c_t^(l); warmup: eq. (1)'s c; compression stage: line 20 */
+  float* mom_scale;  /* [L] momentum-scale coefficients of Appendix A.5.2, or NULL (= all ones) */
+} ob_lamb_state;
+
+/* Creates a context on the current HIP device: copies the configuration, builds the tile tables
+ * and allocates the workspace (blocking; uses hipMalloc/hipMemcpy).  *out is NULL on error. */
+ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out);
+/* Frees the context and its device memory (blocking).  NULL is ignored. */
+void ob_lamb_destroy(ob_lamb_ctx* ctx);
+
+int64_t ob_lamb_num_params(const ob_lamb_ctx* ctx); /* N     */
+int64_t ob_lamb_padded_len(const ob_lamb_ctx* ctx); /* N_pad */
+int64_t ob_lamb_chunk_len(const ob_lamb_ctx* ctx);  /* n_c   */
+/* Static helper: N_pad for given N and W without a context (0 if an argument is invalid). */
+int64_t ob_lamb_padded_len_for(int64_t n, int32_t num_workers);
+const char* ob_lamb_status_string(ob_status s);
+/* Text of the last HIP error seen by this context ("" if none). */
+const char* ob_lamb_last_hip_error(const ob_lamb_ctx* ctx);
+
+/* eq. (1) on every layer with the already averaged gradient `grad` [N_pad], then Algorithm 1
+ * line 2: m, v_fresh, x updated; coeff_c <- c_t; c_avg <- beta3*c_avg + (1-beta3)*c_t.
+ * No bias correction; ||.|| is the L2 norm of the layer, x taken before the update. */
+ob_status ob_lamb_warmup_step(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad,
+                              float lr, void* hip_stream);
+
+/* Algorithm 1 line 3, end of warmup: v_frozen <- v_fresh (over N_pad), r_prev <- 1. */
+ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_stream);
+
+/* Algorithm 1 lines 6-7 over the whole flat buffer, with Appendix A.5.2's momentum scaling:
+ *   z = k_l * (beta1*m + (1-beta1)*grad) + err_worker;   per chunk c: scales_out[c], bits;
+ *   err_worker <- z - C[z].
+ * grad: [N_pad] this worker's local gradient.  packed_out: [N_pad/32] words.  scales_out: [W].
+ * Reads m, does not modify it. */
+ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad,
+                                 uint32_t* packed_out, float* scales_out, void* hip_stream);
+
+/* Algorithm 1 line 10 on the one chunk this rank serves:
+ *   zb = (sum_{w=0..W-1, in this order} +-scales_in[w]) * (1/W) + err_server;
+ *   packed_out, *scale_out = C[zb];  err_server <- zb - C[zb].
+ * packed_in: W consecutive blocks of n_c/32 words, block w = what worker w sent for this chunk.
+ * scales_in: [W].  packed_out: [n_c/32].  scale_out: [1].  (All device pointers; packed_out may
+ * point into the packed_all buffer of the next two calls.) */
+ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                                const uint32_t* packed_in, const float* scales_in,
+                                uint32_t* packed_out, float* scale_out, void* hip_stream);
+
+/* Algorithm 1 lines 13-20 per layer, from the W recompressed server chunks
+ * (packed_all [N_pad/32] words, server_scales [W]):
+ *   m_t = decompress / k_l;  g = (m_t - beta1*m)/(1-beta1);  v_fresh <- beta2*v_fresh + (1-beta2)*g^2;
+ *   r = max over the layer of v_frozen/v_fresh (NaN skipped, starts at 0);
+ *   r <- clip(r, (1-thr)*r_prev, (1+thr)*r_prev); r <- clip(r, r_min, r_max);
+ *   r_prev <- r;  coeff_c <- r * c_avg.
+ * Updates v_fresh, r_prev, coeff_c.  Does not touch m or x. */
+ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                               const uint32_t* packed_all, const float* server_scales,
+                               void* hip_stream);
+
+/* Algorithm 1 lines 13 and 21: with m_t as above and coeff_c from ob_lamb_layer_ratios,
+ *   x <- x - (lr*coeff_c) * m_t / (sqrt(v_frozen) + eta);   m <- m_t. */
+ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                                   const uint32_t* packed_all, const float* server_scales,
+                                   float lr, void* hip_stream);
+
+/* ---- per-kernel timing (diagnostics; used by the benchmark) ----
+ * While enabled, every kernel launch of this context is bracketed by HIP events on its stream.
+ * ob_lamb_profile_read synchronises, aggregates by kernel and clears the record.
+ * Returns the number of distinct kernels; fills up to `cap` entries of each array.
+ * names[i] points to a static string. */
+ob_status ob_lamb_profile_enable(ob_lamb_ctx* ctx, int on);
+int32_t ob_lamb_profile_read(ob_lamb_ctx* ctx, int32_t cap, const char** names,
+                             double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ONEBITLAMB_H */

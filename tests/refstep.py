@@ -1,0 +1,90 @@
+"""Host-side mirror of the device step, driving the CPU oracle on numpy arrays (tests only)."""
+import numpy as np
+
+from oracle.obref import Ref
+
+F32 = Ref(np.float32)
+
+HYPER = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3, r_min=0.5,
+             r_max=4.0, r_threshold=0.1, weight_decay=0.0)
+
+
+class RefStep:
+    def __init__(self, layer_offsets, num_workers, server_chunk=0, mom_scale=None, **hyper):
+        self.off = np.asarray(layer_offsets, dtype=np.int64)
+        self.L = self.off.size - 1
+        self.N = int(self.off[-1])
+        self.W, self.c = int(num_workers), int(server_chunk)
+        q = 256 * self.W
+        self.n_pad = max(q, (self.N + q - 1) // q * q)
+        self.n_c = self.n_pad // self.W
+        self.h = dict(HYPER)
+        self.h.update(hyper)
+        z = lambda n: np.zeros(n, np.float32)
+        self.t = dict(x=z(self.n_pad), m=z(self.n_pad), v_fresh=z(self.n_pad), v_frozen=z(self.n_pad),
+                      err_worker=z(self.n_pad), err_server=z(self.n_c), c_avg=z(self.L),
+                      r_prev=np.ones(self.L, np.float32), coeff_c=z(self.L))
+        self.mom_scale = None if mom_scale is None else np.ascontiguousarray(mom_scale, np.float32)
+        self.bits_local = self.scales_local = None
+        self.bits_in = np.zeros(self.W * self.n_c // 8, np.uint8)
+        self.scales_in = z(self.W)
+        self.bits_all = np.zeros(self.n_pad // 8, np.uint8)
+        self.server_scales = z(self.W)
+
+    def load_state(self, st):
+        for k, v in st.items():
+            if k in self.t and v is not None:
+                self.t[k][...] = np.asarray(v, dtype=np.float32)
+
+    # wire buffers from generated words (uint32 / int32 arrays)
+    def set_foreign_in(self, words, scales):
+        self.bits_in[...] = np.ascontiguousarray(words).view(np.uint8)
+        self.scales_in[...] = scales
+
+    def set_foreign_all(self, words, scales):
+        self.bits_all[...] = np.ascontiguousarray(words).view(np.uint8)
+        self.server_scales[...] = scales
+
+    def warmup_step(self, g, lr):
+        h, t = self.h, self.t
+        t["coeff_c"][...] = F32.warmup_step(self.off, h["beta1"], h["beta2"], h["beta3"], h["eta"],
+                                            h["c_min"], h["c_max"], h["weight_decay"], lr, g, t["m"],
+                                            t["v_fresh"], t["x"], t["c_avg"])
+
+    def freeze(self):
+        self.t["v_frozen"][...] = self.t["v_fresh"]
+        self.t["r_prev"][...] = 1.0
+
+    def compress_local(self, g):
+        self.bits_local, self.scales_local = F32.compress_local(
+            self.off, self.W, self.mom_scale, self.h["beta1"], g, self.t["m"], self.t["err_worker"])
+
+    def gather(self):
+        b = self.n_c // 8
+        self.bits_in[self.c * b:(self.c + 1) * b] = self.bits_local[self.c * b:(self.c + 1) * b]
+        self.scales_in[self.c] = self.scales_local[self.c]
+
+    def server_reduce(self):
+        b = self.n_c // 8
+        bo, so = F32.server_reduce(self.W, self.bits_in, self.scales_in, self.t["err_server"])
+        self.bits_all[self.c * b:(self.c + 1) * b] = bo
+        self.server_scales[self.c] = so
+
+    def layer_ratios(self):
+        h, t = self.h, self.t
+        t["coeff_c"][...] = F32.layer_ratios(self.off, self.W, self.mom_scale, h["beta1"], h["beta2"],
+                                             h["r_min"], h["r_max"], h["r_threshold"], self.bits_all,
+                                             self.server_scales, t["m"], t["v_fresh"], t["v_frozen"],
+                                             t["c_avg"], t["r_prev"])
+
+    def decompress_apply(self, lr):
+        t = self.t
+        F32.decompress_apply(self.off, self.W, self.mom_scale, self.h["eta"], lr, self.bits_all,
+                             self.server_scales, t["coeff_c"], t["v_frozen"], t["x"], t["m"])
+
+    def step(self, g, lr):
+        self.compress_local(g)
+        self.gather()
+        self.server_reduce()
+        self.layer_ratios()
+        self.decompress_apply(lr)

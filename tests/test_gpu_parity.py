@@ -1,0 +1,326 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  Bar: packed sign words bit-exact; fp32 state within 1e-6 relative per element
+(|gpu - ref| <= 1e-6 * max(|ref|, rms(ref))); trajectories within 1e-4 relative in parameter L2.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from tests.refstep import HYPER, RefStep  # noqa: E402
+from workloads import Streams, make_config, gradient, init_state, foreign_worker_chunks, foreign_server_chunks  # noqa: E402
+from workloads.shapes import ParamList, padded_len  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+
+
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU visible")
+
+
+def DeviceStep(*a, **k):
+    from paper_2104_06069_amd.step import DeviceStep as D
+    return D(*a, **k)
+
+
+def assert_close(gpu, ref, what, rel=REL):
+    gpu = np.asarray(gpu); ref = np.asarray(ref)
+    assert gpu.shape == ref.shape, what
+    fin = np.isfinite(ref)
+    # non-finite values must agree exactly (NaN with NaN, +-Inf with the same Inf)
+    assert np.array_equal(np.isnan(gpu), np.isnan(ref)), f"{what}: NaN pattern differs"
+    inf = np.isinf(ref)
+    assert np.array_equal(gpu[inf], ref[inf]), f"{what}: Inf pattern differs"
+    if not fin.any():
+        return 0
+    r = ref[fin].astype(np.float64); g = gpu[fin].astype(np.float64)
+    rms = np.sqrt(np.mean(r * r))
+    tol = rel * np.maximum(np.abs(r), rms)
+    bad = np.abs(g - r) > tol
+    assert not bad.any(), (f"{what}: {bad.sum()} of {r.size} beyond {rel} relative; worst "
+                           f"{np.max(np.abs(g - r) / np.maximum(np.abs(r), rms)):.3e}")
+    return int(np.count_nonzero(g != r))
+
+
+def words_of(t):
+    return t.detach().cpu().numpy().view(np.uint8)
+
+
+def make_case(name):
+    """-> cfg dict (plist, W, n_pad, n_c, grad, server_chunk, mom_scale flag)"""
+    if name in ("tiny", "bert_mini"):
+        cfg = make_config(name)
+        cfg["server_chunk"] = 0 if name == "tiny" else 5
+        cfg["use_k"] = (name == "bert_mini")
+        return cfg
+    if name == "odd":      # 1-, 2-, 3-element and empty tensors, boundaries unaligned to 4, W = 3
+        sizes = [1, 2, 3, 0, 4099, 5, 0, 0, 1024, 2, 4866, 1]
+    elif name == "w1":     # a single chunk; several tiles and a ragged tail
+        sizes = [3000, 1, 9000, 777]
+    elif name == "small":  # N below one 256-element span
+        sizes = [7, 90, 3]
+    else:
+        raise KeyError(name)
+    W = {"odd": 3, "w1": 1, "small": 2}[name]
+    pl = ParamList(name, [(f"t{i}", s) for i, s in enumerate(sizes)])
+    n_pad = padded_len(pl.N, W)
+    return dict(name=name, plist=pl, W=W, n_pad=n_pad, n_c=n_pad // W, grad="student_t3",
+                steps=3, server_chunk=W - 1, use_k=(name != "w1"))
+
+
+def start_pair(cfg, seed=0, warm_state=True):
+    """Oracle-side and device-side steps with identical, non-trivial state."""
+    st = Streams(seed)
+    pl = cfg["plist"]
+    k = None
+    if cfg.get("use_k"):
+        k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0)
+    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **HYPER)
+    assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
+    s = init_state(st, cfg)
+    if warm_state:  # non-zero momentum and errors so that every term is exercised
+        s["m"] = st.normal("m0", 0, cfg["n_pad"], 1e-4); s["m"][pl.N:] = 0
+        s["err_worker"] = st.normal("ew0", 0, cfg["n_pad"], 5e-5)
+        s["err_server"] = st.normal("es0", 0, cfg["n_c"], 5e-5)
+    ref.load_state(s)
+    dev.load_state(ref.t)
+    return st, ref, dev
+
+
+def sync_dev_from_ref(ref, dev):
+    dev.load_state(ref.t)
+    dev.t["coeff_c"].copy_(torch.from_numpy(ref.t["coeff_c"]))
+
+
+def push_wire(ref, dev):
+    dev.packed_in.copy_(torch.from_numpy(ref.bits_in.view(np.int32)))
+    dev.scales_in.copy_(torch.from_numpy(ref.scales_in))
+    dev.packed_all.copy_(torch.from_numpy(ref.bits_all.view(np.int32)))
+    dev.server_scales.copy_(torch.from_numpy(ref.server_scales))
+
+
+CASES = ["small", "odd", "w1", "tiny", "bert_mini"]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_phasewise_single_step(case):
+    """Each call is fed the oracle's outputs of the previous phase; signs must be bit-exact."""
+    _need_gpu()
+    cfg = make_case(case)
+    st, ref, dev = start_pair(cfg)
+    g = gradient(st, cfg, 0)
+    gd = torch.from_numpy(g).to(dev.device)
+    lr = 2e-3
+
+    # phase 1: worker side (Algorithm 1 lines 6-7)
+    ref.compress_local(g)
+    dev.compress_local(gd)
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local), "worker sign words"
+    assert_close(dev.scales_local.cpu().numpy(), ref.scales_local, "worker scales")
+    assert_close(dev.get("err_worker"), ref.t["err_worker"], "worker error")
+    assert np.array_equal(dev.get("m"), ref.t["m"])  # untouched
+
+    # phase 2: server side (line 10) on identical inputs
+    fw, fs = foreign_worker_chunks(st, cfg, 0)
+    ref.set_foreign_in(fw, fs)
+    ref.gather()
+    sync_dev_from_ref(ref, dev)
+    push_wire(ref, dev)
+    fa, fss = foreign_server_chunks(st, cfg, 0)
+    ref.set_foreign_all(fa, fss)
+    dev.packed_all.copy_(torch.from_numpy(ref.bits_all.view(np.int32)))
+    dev.server_scales.copy_(torch.from_numpy(ref.server_scales))
+    ref.server_reduce()
+    dev.server_reduce()
+    assert np.array_equal(words_of(dev.packed_all), ref.bits_all), "server sign words"
+    assert_close(dev.server_scales.cpu().numpy(), ref.server_scales, "server scales")
+    assert_close(dev.get("err_server"), ref.t["err_server"], "server error")
+
+    # phase 3: ratios (lines 13-20)
+    sync_dev_from_ref(ref, dev)
+    push_wire(ref, dev)
+    ref.layer_ratios()
+    dev.layer_ratios()
+    assert_close(dev.get("v_fresh"), ref.t["v_fresh"], "v_fresh")
+    assert_close(dev.get("r_prev"), ref.t["r_prev"], "r")
+    assert_close(dev.get("coeff_c"), ref.t["coeff_c"], "c")
+    assert np.array_equal(dev.get("m"), ref.t["m"]) and np.array_equal(dev.get("x"), ref.t["x"])
+
+    # phase 4: update (lines 13, 21)
+    sync_dev_from_ref(ref, dev)
+    ref.decompress_apply(lr)
+    dev.decompress_apply(lr)
+    assert_close(dev.get("x"), ref.t["x"], "x")
+    assert_close(dev.get("m"), ref.t["m"], "m")
+    # padding never touched by the layer-wise phases
+    N = ref.N
+    assert np.array_equal(dev.get("x")[N:], ref.t["x"][N:]) and np.all(dev.get("m")[N:] == 0)
+    dev.close()
+
+
+def run_trajectory(cfg, steps, seed=0):
+    st, ref, dev = start_pair(cfg, seed=seed, warm_state=False)
+    stats = dict(word_mismatch_steps=0, scale_ulp_steps=0)
+    for t in range(steps):
+        g = gradient(st, cfg, t)
+        lr = 1e-3 * (1 + t % 5)
+        fw, fs = foreign_worker_chunks(st, cfg, t)
+        fa, fss = foreign_server_chunks(st, cfg, t)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        dev.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+        dev.scales_in.copy_(torch.from_numpy(fs))
+        dev.packed_all.copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
+        dev.server_scales.copy_(torch.from_numpy(fss))
+        ref.step(g, lr)
+        dev.step(torch.from_numpy(g).to(dev.device), lr)
+        same_words = (np.array_equal(words_of(dev.packed_local), ref.bits_local)
+                      and np.array_equal(words_of(dev.packed_all), ref.bits_all))
+        same_scales = (np.array_equal(dev.scales_local.cpu().numpy(), ref.scales_local)
+                       and np.array_equal(dev.server_scales.cpu().numpy(), ref.server_scales))
+        stats["word_mismatch_steps"] += (not same_words)
+        stats["scale_ulp_steps"] += (not same_scales)
+        # a sign may differ only after a scale differed in its last bit at an earlier step
+        if stats["scale_ulp_steps"] == 0:
+            assert same_words, f"step {t}: sign words differ although all scales were bit-equal"
+    return ref, dev, stats
+
+
+@pytest.mark.parametrize("case,steps", [("tiny", 10), ("bert_mini", 100), ("odd", 30)])
+def test_trajectory(case, steps):
+    """The device feeds itself for `steps` steps; the oracle does the same on the host."""
+    _need_gpu()
+    cfg = make_case(case)
+    ref, dev, stats = run_trajectory(cfg, steps)
+    x_ref = ref.t["x"][:ref.N].astype(np.float64)
+    x_gpu = dev.get("x")[:ref.N].astype(np.float64)
+    rel = np.linalg.norm(x_gpu - x_ref) / np.linalg.norm(x_ref)
+    print(f"{case}: {steps} steps, relative L2 error of x = {rel:.3e}, {stats}")
+    assert rel <= 1e-4
+    if stats["scale_ulp_steps"] == 0:
+        for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev"):
+            assert np.array_equal(dev.get(k), ref.t[k]), k
+    else:
+        for k in ("x", "m", "v_fresh", "r_prev"):
+            assert_close(dev.get(k), ref.t[k], k, rel=1e-4)
+    dev.close()
+
+
+@pytest.mark.parametrize("case", ["odd", "bert_mini", "small"])
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+def test_warmup_and_freeze(case, wd):
+    """eq. (1) with the moving average of c, then the end-of-warmup snapshot."""
+    _need_gpu()
+    cfg = make_case(case)
+    st = Streams(3)
+    pl = cfg["plist"]
+    hyper = dict(HYPER); hyper["weight_decay"] = wd
+    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **hyper)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], **hyper)
+    s = init_state(st, cfg)
+    s["v_fresh"][...] = 0
+    s["c_avg"][...] = 0
+    ref.load_state(s); dev.load_state(ref.t)
+    for t in range(5):
+        g = gradient(st, cfg, t)
+        ref.warmup_step(g, 1e-3 * (t + 1))
+        dev.warmup_step(torch.from_numpy(g).to(dev.device), 1e-3 * (t + 1))
+        for k in ("m", "v_fresh", "x", "coeff_c", "c_avg"):
+            assert_close(dev.get(k), ref.t[k], f"step {t}: {k}")
+    ref.freeze(); dev.freeze()
+    assert np.array_equal(dev.get("v_frozen"), dev.get("v_fresh"))
+    assert np.all(dev.get("r_prev") == 1.0)
+    assert_close(dev.get("v_frozen"), ref.t["v_frozen"], "v_frozen")
+    # first compression step after the hand-off
+    g = gradient(st, cfg, 99)
+    fw, fs = foreign_worker_chunks(st, cfg, 0); fa, fss = foreign_server_chunks(st, cfg, 0)
+    ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+    push_wire(ref, dev)
+    ref.step(g, 1e-3); dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
+    for k in ("x", "m", "v_fresh", "r_prev", "coeff_c"):
+        assert_close(dev.get(k), ref.t[k], k)
+    dev.close()
+
+
+def test_degenerate_values():
+    """Zero chunks, NaN/Inf gradients, zero fresh variance, near-zero layers: IEEE behaviour of the
+    device matches the oracle's."""
+    _need_gpu()
+    cfg = make_case("odd")
+    st, ref, dev = start_pair(cfg, warm_state=False)
+    N = ref.N
+    # step 0: all-zero gradient and momentum -> every scale is 0, every bit is 1
+    g = np.zeros(cfg["n_pad"], np.float32)
+    fw, fs = foreign_worker_chunks(st, cfg, 0); fa, fss = foreign_server_chunks(st, cfg, 0)
+    fs[...] = 0
+    ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss); push_wire(ref, dev)
+    ref.step(g, 1e-3); dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+    assert np.all(ref.scales_local == 0) and np.all(ref.bits_local == 0xFF)
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
+    assert np.array_equal(words_of(dev.packed_all), ref.bits_all)
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev"):
+        assert_close(dev.get(k), ref.t[k], k)
+    # step 1: NaN and +-Inf in the gradient, zero fresh variance on some elements, a layer whose
+    # frozen variance is 0 as well (0/0), gradients of 1e-9 on one layer
+    g = gradient(st, cfg, 1)
+    g[5] = np.nan; g[4200] = np.inf; g[4300] = -np.inf
+    g[9000:9100] *= 1e-6
+    ref.t["v_fresh"][10:20] = 0; ref.t["m"][10:20] = 0
+    ref.t["v_fresh"][0] = 0; ref.t["v_frozen"][0] = 0
+    ref.t["v_frozen"][30] = np.nan; ref.t["v_frozen"][31] = np.inf   # NaN skipped by the max; Inf clipped
+    sync_dev_from_ref(ref, dev)
+    fw, fs = foreign_worker_chunks(st, cfg, 1); fa, fss = foreign_server_chunks(st, cfg, 1)
+    ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss); push_wire(ref, dev)
+    ref.step(g, 1e-3); dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
+    assert np.array_equal(words_of(dev.packed_all), ref.bits_all)
+    assert_close(dev.scales_local.cpu().numpy(), ref.scales_local, "scales with NaN/Inf")
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+        assert_close(dev.get(k), ref.t[k], k)
+    assert np.all(np.isfinite(dev.get("r_prev")))
+    dev.close()
+
+
+def test_bitwise_reproducible():
+    """Same inputs twice -> identical bits everywhere (fixed-order reductions, no float atomics)."""
+    _need_gpu()
+    cfg = make_case("bert_mini")
+    outs = []
+    for _ in range(2):
+        st, ref, dev = start_pair(cfg)
+        g = torch.from_numpy(gradient(st, cfg, 0)).to(dev.device)
+        fw, fs = foreign_worker_chunks(st, cfg, 0); fa, fss = foreign_server_chunks(st, cfg, 0)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss); push_wire(ref, dev)
+        dev.step(g, 1e-3)
+        outs.append({k: dev.get(k).copy() for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev")}
+                    | {"scales": dev.scales_local.cpu().numpy(), "w": words_of(dev.packed_local).copy()})
+        dev.close()
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], outs[1][k], equal_nan=True) if outs[0][k].dtype.kind == "f" \
+            else np.array_equal(outs[0][k], outs[1][k]), k
+
+
+def test_argument_errors():
+    """Host-side validation: nothing is enqueued and a negative status comes back."""
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    cfg = make_case("small")
+    st, ref, dev = start_pair(cfg)
+    g = torch.zeros(cfg["n_pad"], device=dev.device)
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_compress_local(dev.ctx, dev.state, None, dev.packed_local, dev.scales_local)
+    assert e.value.status == -1
+    with pytest.raises(ob.ObLambError) as e:   # misaligned gradient pointer
+        ob.ob_lamb_compress_local(dev.ctx, dev.state, g[1:], dev.packed_local, dev.scales_local)
+    assert e.value.status == -3
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_decompress_apply(dev.ctx, dev.state, dev.packed_all, dev.server_scales, float("nan"))
+    assert e.value.status == -2
+    x0 = dev.get("x").copy()
+    torch.cuda.synchronize()
+    assert np.array_equal(dev.get("x"), x0)
+    dev.close()
