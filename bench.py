@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the 1-bit LAMB compression-stage optimizer step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input already resident in
+HBM: compress_local -> (gather copy) -> server_reduce -> layer_ratios -> decompress_apply.
+Prints ONE JSON line (see the design doc for the fields).  `--gpus N` with N > 1 is refused: this
+build measures one GPU's share of the data-parallel step and uses no collectives.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# Algorithmic HBM bytes per element of one launch of each kernel: every input read once, every
+# output written once.  Units per launch: n_pad for the N-sized kernels, n_c for the server ones.
+KERNEL_BYTES = {
+    "momentum_z_sumsq": (16.0, "n_pad"),        # R g, m, err (12) + W z (4)
+    "sign_pack_error": (8.125, "n_pad"),        # R z (4) + W err (4) + W bits (1/8)
+    "server_unpack_avg": (None, "n_c"),         # W/8 + 8, filled in below
+    "server_sign_pack": (8.125, "n_c"),
+    "ratios_pass": (16.125, "n_pad"),           # R bits, m, v_fresh, v_frozen (12.125) + W v_fresh (4)
+    "decompress_apply": (16.125, "n_pad"),      # R bits, v_frozen, x (8.125) + W x, m (8)
+    "warmup_moments": (24.0, "n_pad"),          # R g, m, v, x (16) + W m, v (8)
+    "warmup_apply": (16.0, "n_pad"),            # R m, v, x (12) + W x (4)
+}
+
+
+def compulsory_step_bytes_per_param(W):
+    # compress_local 16.125 + server_reduce (0.125 + 8.125/W) + layer_ratios 16.125 + apply 12.0
+    return 16.125 + 0.125 + 8.125 / W + 16.125 + 12.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="bert_large")
+    ap.add_argument("--profile-steps", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy 10 times (for scaling rocprofv3 "
+                         "FETCH_SIZE/WRITE_SIZE readings) and exit")
+    ap.add_argument("--mom-scale", action="store_true", help="with Appendix A.5.2 momentum scaling")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU's share of the data-parallel step (no "
+              "collectives, no second GPU); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.calibrate_copy:
+        n = 1 << 28  # 2^28 fp32 = 1 GiB read + 1 GiB written per copy
+        a = torch.ones(n, device=dev); b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read": 4 * n, "bytes_written": 4 * n,
+                          "launches": 10}))
+        return
+
+    import paper_2104_06069_amd as ob
+    from paper_2104_06069_amd.step import DeviceStep
+    from workloads import (Streams, foreign_server_chunks, foreign_worker_chunks, gradient,
+                           init_state, make_config)
+
+    cfg = make_config(args.workload)
+    pl, W = cfg["plist"], cfg["W"]
+    hyper = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3, r_min=0.5,
+                 r_max=4.0, r_threshold=0.1, weight_decay=0.0)
+    server_chunk = W // 2
+    st = Streams(0, device="cuda:0")
+    mom_scale = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if args.mom_scale else None
+    ds = DeviceStep(pl.offsets, W, server_chunk, device="cuda:0", mom_scale=mom_scale, **hyper)
+    ds.load_state(init_state(st, cfg))
+    n_grads = 3
+    grads = [gradient(st, cfg, t) for t in range(n_grads)]
+    fw, fs = foreign_worker_chunks(st, cfg, 0)
+    fa, fss = foreign_server_chunks(st, cfg, 0)
+    ds.packed_in.copy_(fw); ds.scales_in.copy_(torch.from_numpy(fs))
+    ds.packed_all.copy_(fa); ds.server_scales.copy_(torch.from_numpy(fss))
+    lr = 1e-3
+    torch.cuda.synchronize()
+
+    host0 = None
+    if not args.no_cpu_baseline:
+        # host copy of the initial state and inputs for the CPU-baseline leg, taken before any step
+        host0 = dict(state={k: ds.get(k).copy() for k in
+                            ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev")},
+                     grads=[g.cpu().numpy() for g in grads[:2]],
+                     fw=ds.packed_in.cpu().numpy(), fs=fs.copy(), fa=ds.packed_all.cpu().numpy(),
+                     fss=fss.copy())
+
+    for t in range(args.warmup):
+        ds.step(grads[t % n_grads], lr)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        ds.step(grads[t % n_grads], lr)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-call times (events on the launch stream) and per-kernel durations (library's own events)
+    calls = {}
+    names = ["compress_local", "gather", "server_reduce", "layer_ratios", "decompress_apply"]
+    evs = []
+    for t in range(args.profile_steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        e[0].record(); ds.compress_local(grads[t % n_grads])
+        e[1].record(); ds.gather()
+        e[2].record(); ds.server_reduce()
+        e[3].record(); ds.layer_ratios()
+        e[4].record(); ds.decompress_apply(lr)
+        e[5].record()
+        evs.append(e)
+    torch.cuda.synchronize()
+    for i, nm in enumerate(names):
+        calls[nm] = round(float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])), 4)
+
+    ob.ob_lamb_profile_enable(ds.ctx, True)
+    for t in range(args.profile_steps):
+        ds.step(grads[t % n_grads], lr)
+    prof = ob.ob_lamb_profile_read(ds.ctx)
+    ob.ob_lamb_profile_enable(ds.ctx, False)
+    kern = {k: {"avg_ms": round(v[0] / v[1], 4), "launches": v[1]} for k, v in prof.items()}
+    KB = dict(KERNEL_BYTES)
+    KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
+    units = {"n_pad": ds.n_pad, "n_c": ds.n_c}
+    for k, v in kern.items():
+        if k in KB:
+            bpe, unit = KB[k]
+            v["algo_bytes"] = bpe * units[unit]
+            v["GBps"] = round(v["algo_bytes"] / (v["avg_ms"] * 1e-3) / 1e9, 1)
+    dom = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(kern[dom]["GBps"] / HBM_PEAK_GBS, 4),
+                "avg_launch_ms": kern[dom]["avg_ms"], "algo_bytes_per_launch": kern[dom]["algo_bytes"],
+                "traffic": traffic}
+
+    step_bytes = compulsory_step_bytes_per_param(W) * ds.n_pad
+    out = {
+        "metric": "1-bit LAMB compressed step: params/sec and % of HBM peak GB/s, 1 GPU",
+        "value": round(pl.N / (ms_per_step * 1e-3), 1), "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
+                   "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
+                   "mom_scale": bool(args.mom_scale)},
+        "step_compulsory_bytes": step_bytes,
+        "step_compulsory_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_pct_of_hbm_peak": round(100 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "roofline": roofline,
+        "calls_ms": calls,
+        "kernels": kern,
+    }
+
+    if host0 is not None:
+        out["cpu_baseline"] = cpu_baseline(cfg, server_chunk, hyper, mom_scale, host0, lr,
+                                           args.cpu_seconds)
+    ds.close()
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, server_chunk, hyper, mom_scale, h, lr, budget_s):
+    """The oracle as it stands, single thread, on the same workload: whole steps until `budget_s`
+    seconds of CPU work have been spent (at least one step, at most three)."""
+    import numpy as np
+    from tests.refstep import RefStep
+    ref = RefStep(cfg["plist"].offsets, cfg["W"], server_chunk, mom_scale=mom_scale, **hyper)
+    ref.load_state(h["state"])
+    ref.set_foreign_in(h["fw"], h["fs"])
+    ref.set_foreign_all(h["fa"], h["fss"])
+    times = []
+    while len(times) < 3 and (not times or sum(times) < budget_s):
+        g = h["grads"][len(times) % len(h["grads"])]
+        t0 = time.perf_counter()
+        ref.step(g, lr)
+        times.append(time.perf_counter() - t0)
+    sec = float(np.median(times))
+    return {"value": round(cfg["plist"].N / sec, 1), "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(times)} whole step(s) of the same workload, median {sec:.2f} s/step",
+            "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

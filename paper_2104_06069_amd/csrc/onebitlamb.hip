@@ -80,11 +80,6 @@ __device__ __forceinline__ float block_max(float v, float* lds /* [BLOCK/WAVE] *
   return r;
 }
 
-// Order-independent max on non-negative floats: their bit patterns order like unsigned ints.
-__device__ __forceinline__ void atomic_max_nonneg(float* addr, float v) {
-  if (v > 0.0f) atomicMax(reinterpret_cast<unsigned int*>(addr), __float_as_uint(v));
-}
-
 // off has L+2 entries, off[L+1] = INT64_MAX, so the walk stops at L (= padding) at the latest.
 __device__ __forceinline__ int walk_layer(int l, int64_t i, const int64_t* __restrict__ off) {
   while (i >= off[l + 1]) ++l;
@@ -249,16 +244,31 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
   for (int u = 0; u < U; ++u)
 #pragma unroll
     for (int k = 0; k < 4; ++k) acc[u][k] = 0.0f;
-  for (int w = 0; w < W; ++w) {
-    const float s = scales_in[w];
-    const uint32_t* row = packed_in + (int64_t)w * wpc;
+  // workers strictly in order 0..W-1 (the fp32 sum is order dependent); the loads of GROUP
+  // workers are issued together so that their latencies overlap
+  constexpr int GROUP = 8;
+  for (int w0 = 0; w0 < W; w0 += GROUP) {
+    unsigned int word[GROUP][U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        const unsigned int nib = row[(p.tile0 + o) >> 5] >> sh;
+    for (int j = 0; j < GROUP; ++j) {
+      const int w = (w0 + j < W) ? w0 + j : W - 1;
+      const uint32_t* row = packed_in + (int64_t)w * wpc;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc[u][k] = acc[u][k] + (((nib >> k) & 1u) ? s : -s);
+      for (int u = 0; u < U; ++u) {
+        const int o = u * SPAN + o0;
+        word[j][u] = (o < p.len) ? row[(p.tile0 + o) >> 5] : 0u;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < GROUP; ++j) {
+      if (w0 + j < W) {
+        const float s = scales_in[w0 + j];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const unsigned int nib = word[j][u] >> sh;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[u][k] = acc[u][k] + (((nib >> k) & 1u) ? s : -s);
+        }
       }
     }
   }
@@ -289,14 +299,15 @@ template <int U, bool HAS_K>
 __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
     const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
     const float* __restrict__ m, float* __restrict__ v_fresh, const float* __restrict__ v_frozen,
-    float* __restrict__ rmax, int64_t n_c, int tpc, float beta1, float omb1, float beta2, float omb2,
+    float* __restrict__ seg_max, int64_t n_c, int tpc, float beta1, float omb1, float beta2, float omb2,
     const float* __restrict__ mom_scale, const int64_t* __restrict__ off,
-    const int* __restrict__ first_layer, int L) {
+    const int* __restrict__ first_layer, const int* __restrict__ tile_seg0,
+    const int* __restrict__ seg_layer, int L) {
   constexpr int TILE = SPAN * U;
   __shared__ float lds[BLOCK / WAVE];
   const TilePos p = tile_pos<TILE>(n_c, tpc);
   const int l0 = first_layer[blockIdx.x];
-  if (l0 >= L) return;  // tile lies in the padding
+  if (l0 >= L) return;  // tile lies in the padding (it has no segment)
   const int o0 = threadIdx.x * 4;
   const int sh = 4 * (threadIdx.x & 7);
   const float ss = sscales[p.c];
@@ -333,9 +344,10 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
       }
     }
     r = block_max(r, lds);
-    if (threadIdx.x == 0) atomic_max_nonneg(rmax + l0, r);
+    if (threadIdx.x == 0) seg_max[tile_seg0[blockIdx.x]] = r;
   } else {
     const int64_t N = off[L];
+    // quotient of every element (kept in VZ), then one workgroup max per (tile, layer) segment
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int o = u * SPAN + o0;
@@ -344,6 +356,7 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int64_t i = p.tile0 + o + k;
+          float q = 0.0f;
           if (i < N) {
             l = walk_layer(l, i, off);
             const float sp = HAS_K ? ss / mom_scale[l] : ss;
@@ -351,33 +364,61 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
             const float gr = (mt - beta1 * M[u][k]) / omb1;
             const float vf = beta2 * VF[u][k] + omb2 * (gr * gr);
             v_fresh[i] = vf;
-            atomic_max_nonneg(rmax + l, VZ[u][k] / vf);
+            q = VZ[u][k] / vf;
+          }
+          VZ[u][k] = q;
+        }
+      }
+    }
+    const int s0 = tile_seg0[blockIdx.x], s1 = tile_seg0[blockIdx.x + 1];
+    for (int s = s0; s < s1; ++s) {
+      const int l = seg_layer[s];
+      const int64_t a = off[l], b = off[l + 1];
+      float r = 0.0f;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int o = u * SPAN + o0;
+        if (o < p.len) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int64_t i = p.tile0 + o + k;
+            if (i >= a && i < b && VZ[u][k] > r) r = VZ[u][k];
           }
         }
       }
+      r = block_max(r, lds);
+      if (threadIdx.x == 0) seg_max[s] = r;
     }
   }
 }
 
-// K6  Algorithm 1 lines 18-20 per layer; clears the per-layer maxima for the next step.
-__global__ __launch_bounds__(BLOCK) void k_ratios_finalize(float* __restrict__ rmax,
+// K6  per layer: max over the layer's segments (0 for an empty layer), then Algorithm 1 lines 18-20.
+__global__ __launch_bounds__(BLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
+                                                           const int* __restrict__ layer_seg0,
                                                            const float* __restrict__ c_avg,
                                                            float* __restrict__ r_prev,
-                                                           float* __restrict__ coeff_c, int L,
+                                                           float* __restrict__ coeff_c,
                                                            float one_m_thr, float one_p_thr,
                                                            float r_min, float r_max) {
-  const int l = blockIdx.x * BLOCK + threadIdx.x;
-  if (l >= L) return;
-  float r = rmax[l];
-  rmax[l] = 0.0f;
-  const float rp = r_prev[l];
-  const float lo = one_m_thr * rp, hi = one_p_thr * rp;
-  r = (r > lo) ? r : lo;
-  r = (r < hi) ? r : hi;
-  r = (r > r_min) ? r : r_min;
-  r = (r < r_max) ? r : r_max;
-  r_prev[l] = r;
-  coeff_c[l] = r * c_avg[l];
+  __shared__ float lds[BLOCK / WAVE];
+  const int l = blockIdx.x;
+  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
+  float r = 0.0f;
+  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
+    const float q = seg_max[s];
+    if (q > r) r = q;
+  }
+  r = block_max(r, lds);
+  if (threadIdx.x == 0) {
+    const float rp = r_prev[l];
+    const float lo = one_m_thr * rp, hi = one_p_thr * rp;
+    r = (r > lo) ? r : lo;
+    r = (r < hi) ? r : hi;
+    r = (r > r_min) ? r : r_min;
+    r = (r < r_max) ? r : r_max;
+    r_prev[l] = r;
+    coeff_c[l] = r * c_avg[l];
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -707,7 +748,7 @@ struct ob_lamb_ctx {
   double* d_partials = nullptr;   // [n_tiles]
   double* d_partials_srv = nullptr;  // [tpc_srv]
   double* d_seg_sums = nullptr;   // [2*n_segs]
-  float* d_rmax = nullptr;        // [L], zero between calls
+  float* d_seg_max = nullptr;     // [n_segs] per-segment max(v_frozen/v_fresh)
   // diagnostics
   bool profile = false;
   std::vector<ProfRec> prof;
@@ -889,7 +930,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
        alloc_zero(ctx, &ctx->d_partials, (size_t)n_tiles) &&
        alloc_zero(ctx, &ctx->d_partials_srv, (size_t)tpc_srv) &&
        alloc_zero(ctx, &ctx->d_seg_sums, 2 * (size_t)ctx->n_segs) &&
-       alloc_zero(ctx, &ctx->d_rmax, (size_t)L);
+       alloc_zero(ctx, &ctx->d_seg_max, (size_t)ctx->n_segs);
   if (!ok) {
     ob_lamb_destroy(ctx);
     return OB_ERR_HIP;
@@ -905,7 +946,7 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
     (void)hipEventDestroy(r.e1);
   }
   void* ptrs[] = {ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer, ctx->d_layer_seg0,
-                  ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_rmax};
+                  ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete ctx;
@@ -991,15 +1032,16 @@ ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   Launch la(ctx, hip_stream);
   if (st->mom_scale)
     OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, true>), ctx->n_tiles, packed_all, server_scales,
-              st->m, st->v_fresh, st->v_frozen, ctx->d_rmax, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-              ctx->beta2, ctx->omb2, st->mom_scale, ctx->d_off, ctx->d_first_layer, (int)ctx->L);
+              st->m, st->v_fresh, st->v_frozen, ctx->d_seg_max, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
+              ctx->beta2, ctx->omb2, st->mom_scale, ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0,
+              ctx->d_seg_layer, (int)ctx->L);
   else
     OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, false>), ctx->n_tiles, packed_all, server_scales,
-              st->m, st->v_fresh, st->v_frozen, ctx->d_rmax, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-              ctx->beta2, ctx->omb2, st->mom_scale, ctx->d_off, ctx->d_first_layer, (int)ctx->L);
-  OB_LAUNCH(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)((ctx->L + BLOCK - 1) / BLOCK), ctx->d_rmax,
-            st->c_avg, st->r_prev, st->coeff_c, (int)ctx->L, ctx->one_m_thr, ctx->one_p_thr, ctx->r_min,
-            ctx->r_max);
+              st->m, st->v_fresh, st->v_frozen, ctx->d_seg_max, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
+              ctx->beta2, ctx->omb2, st->mom_scale, ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0,
+              ctx->d_seg_layer, (int)ctx->L);
+  OB_LAUNCH(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, ctx->d_seg_max, ctx->d_layer_seg0,
+            st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr, ctx->r_min, ctx->r_max);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 

@@ -10,13 +10,14 @@ HYPER = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3,
 
 
 class RefStep:
-    def __init__(self, layer_offsets, num_workers, server_chunk=0, mom_scale=None, **hyper):
+    def __init__(self, layer_offsets, num_workers, server_chunk=0, mom_scale=None, n_pad=None, **hyper):
         self.off = np.asarray(layer_offsets, dtype=np.int64)
         self.L = self.off.size - 1
         self.N = int(self.off[-1])
         self.W, self.c = int(num_workers), int(server_chunk)
         q = 256 * self.W
-        self.n_pad = max(q, (self.N + q - 1) // q * q)
+        self.n_pad = max(q, (self.N + q - 1) // q * q) if n_pad is None else int(n_pad)
+        assert self.n_pad % q == 0 and self.n_pad >= self.N
         self.n_c = self.n_pad // self.W
         self.h = dict(HYPER)
         self.h.update(hyper)

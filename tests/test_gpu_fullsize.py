@@ -1,0 +1,140 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py
+times.  BERT-Large-shaped (W = 64 and W = 256): one whole step against the whole oracle.
+GPT-1.3B-shaped: the oracle recomputes windows of chunks (the compressor is chunk-local, the
+ratio/update are layer-local, so a window of whole chunks is an independent sub-problem for every
+layer that lies inside it) plus the served chunk.
+"""
+import time
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from tests.refstep import HYPER, RefStep  # noqa: E402
+from tests.test_gpu_parity import assert_close, words_of, _need_gpu, DeviceStep  # noqa: E402
+from workloads import Streams, make_config, gradient, init_state, foreign_worker_chunks, foreign_server_chunks  # noqa: E402
+from workloads.gen import layer_kappa  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+def device_setup(cfg, server_chunk, seed=0):
+    st = Streams(seed, device="cuda:0")
+    pl = cfg["plist"]
+    dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, **HYPER)
+    s = init_state(st, cfg)
+    # non-trivial momentum and errors, as after many steps
+    s["m"] = st.normal("m0", 0, cfg["n_pad"], 1e-4); s["m"][pl.N:] = 0
+    s["err_worker"] = st.normal("ew0", 0, cfg["n_pad"], 5e-5)
+    s["err_server"] = st.normal("es0", 0, cfg["n_c"], 5e-5)
+    dev.load_state(s)
+    g = gradient(st, cfg, 0, kappa=layer_kappa(st, cfg))
+    fw, fs = foreign_worker_chunks(st, cfg, 0)
+    fa, fss = foreign_server_chunks(st, cfg, 0)
+    dev.packed_in.copy_(fw); dev.scales_in.copy_(torch.from_numpy(fs))
+    dev.packed_all.copy_(fa); dev.server_scales.copy_(torch.from_numpy(fss))
+    torch.cuda.synchronize()
+    return st, dev, g
+
+
+@pytest.mark.parametrize("name", ["bert_large", "bert_large_w256"])
+def test_bert_large_whole_step(name):
+    _need_gpu()
+    cfg = make_config(name)
+    c = cfg["W"] // 2
+    st, dev, g = device_setup(cfg, c)
+    ref = RefStep(cfg["plist"].offsets, cfg["W"], c)
+    ref.load_state({k: dev.get(k) for k in ref.t})
+    ref.set_foreign_in(dev.packed_in.cpu().numpy(), dev.scales_in.cpu().numpy())
+    ref.set_foreign_all(dev.packed_all.cpu().numpy(), dev.server_scales.cpu().numpy())
+    gh = g.cpu().numpy()
+    lr = 2e-3
+    t0 = time.time()
+    ref.step(gh, lr)
+    print(f"{name}: oracle step {time.time() - t0:.1f} s", flush=True)
+    dev.step(g, lr)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local), "worker sign words"
+    assert_close(dev.scales_local.cpu().numpy(), ref.scales_local, "worker scales")
+    assert np.array_equal(words_of(dev.packed_all), ref.bits_all), "server sign words"
+    assert_close(dev.server_scales.cpu().numpy(), ref.server_scales, "server scales")
+    nd = {}
+    for k in ("err_worker", "err_server", "v_fresh", "r_prev", "coeff_c", "x", "m"):
+        nd[k] = assert_close(dev.get(k), ref.t[k], k)
+    print(f"{name}: elements not bit-equal (within 1e-6): {nd}", flush=True)
+    dev.close()
+
+
+def window_cfg(cfg, c0, c1):
+    """Sub-problem made of chunks [c0, c1): offsets clipped to the window."""
+    n_c = cfg["n_c"]
+    A, B = c0 * n_c, c1 * n_c
+    off = np.clip(cfg["plist"].offsets, A, B) - A
+    inside = (cfg["plist"].offsets[:-1] >= A) & (cfg["plist"].offsets[1:] <= B) & \
+             (cfg["plist"].offsets[1:] > cfg["plist"].offsets[:-1])
+    return A, B, off.astype(np.int64), inside
+
+
+def test_gpt_1p3b_windows():
+    _need_gpu()
+    cfg = make_config("gpt_1p3b")
+    W, n_c, pl = cfg["W"], cfg["n_c"], cfg["plist"]
+    c_srv = 77
+    st, dev, g = device_setup(cfg, c_srv)
+    lr = 2e-3
+    before = {k: dev.t[k].clone() for k in ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server",
+                                            "c_avg", "r_prev")}
+    fin_words, fin_scales = dev.packed_in.clone(), dev.scales_in.clone()
+    dev.step(g, lr)
+    torch.cuda.synchronize()
+    # windows: the first chunks (embedding start), chunks around the served one, the last chunks
+    # (small tensors, final LayerNorm, padding), and a stretch of a transformer block
+    whole = 0
+    for (c0, c1) in ((0, 2), (10, 13), (c_srv - 1, c_srv + 2), (W - 3, W)):
+        A, B, off, inside = window_cfg(cfg, c0, c1)
+        Wn = c1 - c0
+        srv_in = c0 <= c_srv < c1
+        ref = RefStep(off, Wn, (c_srv - c0) if srv_in else 0, n_pad=B - A)
+        assert ref.n_pad == B - A and ref.n_c == n_c
+        for k in ("x", "m", "v_fresh", "v_frozen", "err_worker"):
+            ref.t[k][...] = before[k][A:B].cpu().numpy()
+        ref.t["c_avg"][...] = before["c_avg"].cpu().numpy()
+        ref.t["r_prev"][...] = before["r_prev"].cpu().numpy()
+        gw = g[A:B].cpu().numpy()
+        ref.compress_local(gw)
+        assert np.array_equal(words_of(dev.packed_local[A // 32:B // 32]), ref.bits_local), (c0, "worker words")
+        assert_close(dev.scales_local[c0:c1].cpu().numpy(), ref.scales_local, "worker scales")
+        assert_close(dev.t["err_worker"][A:B].cpu().numpy(), ref.t["err_worker"], "worker error")
+        if srv_in:
+            ref.t["err_server"][...] = before["err_server"].cpu().numpy()
+            refs = RefStep(np.array([0, n_c]), W, c_srv, n_pad=W * n_c)   # served chunk, full fan-in
+            refs.t["err_server"][...] = before["err_server"].cpu().numpy()
+            refs.set_foreign_in(fin_words.cpu().numpy(), fin_scales.cpu().numpy())
+            b = n_c // 8
+            refs.bits_in[c_srv * b:(c_srv + 1) * b] = ref.bits_local[(c_srv - c0) * b:(c_srv - c0 + 1) * b]
+            refs.scales_in[c_srv] = ref.scales_local[c_srv - c0]
+            from oracle.obref import Ref
+            bo, so = Ref(np.float32).server_reduce(W, refs.bits_in, refs.scales_in, refs.t["err_server"])
+            wpc = n_c // 32
+            assert np.array_equal(words_of(dev.packed_all[c_srv * wpc:(c_srv + 1) * wpc]), bo), "server words"
+            assert_close(dev.server_scales[c_srv:c_srv + 1].cpu().numpy(), np.array([so]), "server scale")
+            assert_close(dev.get("err_server"), refs.t["err_server"], "server error")
+        # ratio and update from the device's packed_all / scales (inputs), window only
+        ref.set_foreign_all(dev.packed_all[A // 32:B // 32].cpu().numpy(),
+                            dev.server_scales[c0:c1].cpu().numpy())
+        ref.layer_ratios()
+        ref.decompress_apply(lr)
+        assert_close(dev.t["v_fresh"][A:B].cpu().numpy(), ref.t["v_fresh"], "v_fresh")
+        idx = np.nonzero(inside)[0]
+        whole += idx.size
+        assert_close(dev.get("r_prev")[idx], ref.t["r_prev"][idx], "r")
+        assert_close(dev.get("coeff_c")[idx], ref.t["coeff_c"][idx], "c")
+        offs = pl.offsets
+        for l in idx:
+            a, b_ = int(offs[l]) - A, int(offs[l + 1]) - A
+            assert_close(dev.t["x"][A + a:A + b_].cpu().numpy(), ref.t["x"][a:b_], f"x layer {l}")
+            assert np.array_equal(dev.t["m"][A + a:A + b_].cpu().numpy(), ref.t["m"][a:b_]), f"m layer {l}"
+        print(f"gpt window chunks [{c0},{c1}): {idx.size} whole layers checked", flush=True)
+    assert whole >= 12
+    dev.close()
