@@ -21,6 +21,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Algorithmic HBM bytes per element of one launch of each kernel: every input read once, every
 # output written once.  Units per launch: n_pad for the N-sized kernels, n_c for the server ones.
 KERNEL_BYTES = {
+    "compress_resident": (16.125, "n_pad"),     # R g, m, err (12) + W err (4) + W bits (1/8)
     "momentum_z_sumsq": (16.0, "n_pad"),        # R g, m, err (12) + W z (4)
     "sign_pack_error": (8.125, "n_pad"),        # R z (4) + W err (4) + W bits (1/8)
     "server_unpack_avg": (None, "n_c"),         # W/8 + 8, filled in below
@@ -168,7 +169,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
                    "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
-                   "mom_scale": bool(args.mom_scale)},
+                   "mom_scale": bool(args.mom_scale),
+                   "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx)},
         "step_compulsory_bytes": step_bytes,
         "step_compulsory_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_pct_of_hbm_peak": round(100 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
@@ -177,6 +179,7 @@ def main():
         "kernels": kern,
     }
 
+    ob.ob_lamb_check_device_status(ds.ctx, ds.stream)  # raises if a bounded device wait expired
     if host0 is not None:
         out["cpu_baseline"] = cpu_baseline(cfg, server_chunk, hyper, mom_scale, host0, lr,
                                            args.cpu_seconds)

@@ -59,7 +59,7 @@ typedef enum ob_status {
   OB_ERR_NULL = -1,  /* a required pointer is NULL */
   OB_ERR_ARG = -2,   /* a size, offset table or hyper-parameter is invalid */
   OB_ERR_ALIGN = -3, /* a device pointer is not 16-byte aligned */
-  OB_ERR_STATE = -4, /* reserved */
+  OB_ERR_STATE = -4, /* a bounded device-side wait expired (see ob_lamb_check_device_status) */
   OB_ERR_HIP = -5    /* a HIP runtime call failed (see ob_lamb_last_hip_error) */
 } ob_status;
 
@@ -148,6 +148,17 @@ ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st,
 ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                    const uint32_t* packed_all, const float* server_scales,
                                    float lr, void* hip_stream);
+
+/* ob_lamb_compress_local runs as ONE kernel that keeps z in registers across a per-chunk arrival
+ * barrier whenever the device can hold two chunks' worth of its workgroups (otherwise, or when the
+ * environment variable OB_LAMB_TWO_PASS=1 is set at ob_lamb_create, as two passes through memory;
+ * the results are bit-identical).  The barrier's waits are bounded; should one ever expire, the
+ * step's outputs are undefined and a device-side flag is raised.  ob_lamb_check_device_status
+ * synchronises `hip_stream`, reads that flag and returns OB_OK, or OB_ERR_STATE after re-arming
+ * the context to use the two-pass kernels from then on.  Call it whenever you synchronise anyway
+ * (e.g. once per logging interval).  ob_lamb_uses_single_pass reports the current choice (1/0). */
+ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream);
+int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx);
 
 /* ---- per-kernel timing (diagnostics; used by the benchmark) ----
  * While enabled, every kernel launch of this context is bracketed by HIP events on its stream.

@@ -65,6 +65,8 @@ def lib():
             "ob_lamb_server_reduce": (C.c_int, [vp, sp, vp, vp, vp, vp, vp]),
             "ob_lamb_layer_ratios": (C.c_int, [vp, sp, vp, vp, vp]),
             "ob_lamb_decompress_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
+            "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
+            "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
             "ob_lamb_profile_read": (i32, [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(i64)]),
@@ -167,6 +169,14 @@ def ob_lamb_decompress_apply(ctx, state, packed_all, server_scales, lr, stream=N
     _check(lib().ob_lamb_decompress_apply(ctx, C.byref(state), _addr(packed_all),
                                           _addr(server_scales), lr, _addr(stream)), ctx,
            "ob_lamb_decompress_apply")
+
+
+def ob_lamb_check_device_status(ctx, stream=None):
+    _check(lib().ob_lamb_check_device_status(ctx, _addr(stream)), ctx, "ob_lamb_check_device_status")
+
+
+def ob_lamb_uses_single_pass(ctx):
+    return bool(lib().ob_lamb_uses_single_pass(ctx))
 
 
 def ob_lamb_profile_enable(ctx, on):

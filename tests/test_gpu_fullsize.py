@@ -12,17 +12,23 @@ import pytest
 torch = pytest.importorskip("torch")
 
 from tests.refstep import HYPER, RefStep  # noqa: E402
-from tests.test_gpu_parity import assert_close, words_of, _need_gpu, DeviceStep  # noqa: E402
+from tests.test_gpu_parity import assert_close, words_of, _need_gpu, DeviceStep, finish  # noqa: E402
 from workloads import Streams, make_config, gradient, init_state, foreign_worker_chunks, foreign_server_chunks  # noqa: E402
 from workloads.gen import layer_kappa  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
 
-def device_setup(cfg, server_chunk, seed=0):
+def device_setup(cfg, server_chunk, seed=0, two_pass=False):
     st = Streams(seed, device="cuda:0")
     pl = cfg["plist"]
-    dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, **HYPER)
+    import paper_2104_06069_amd as ob
+    if two_pass:
+        dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, two_pass=True, **HYPER)
+    else:  # whatever the library selects for this size on this device
+        from paper_2104_06069_amd.step import DeviceStep as D
+        dev = D(pl.offsets, cfg["W"], server_chunk, **HYPER)
+    print(f"{cfg['name']}: single-pass worker compression = {ob.ob_lamb_uses_single_pass(dev.ctx)}", flush=True)
     s = init_state(st, cfg)
     # non-trivial momentum and errors, as after many steps
     s["m"] = st.normal("m0", 0, cfg["n_pad"], 1e-4); s["m"][pl.N:] = 0
@@ -38,12 +44,13 @@ def device_setup(cfg, server_chunk, seed=0):
     return st, dev, g
 
 
-@pytest.mark.parametrize("name", ["bert_large", "bert_large_w256"])
-def test_bert_large_whole_step(name):
+@pytest.mark.parametrize("name,two_pass", [("bert_large", False), ("bert_large_w256", False),
+                                           ("bert_large", True)])
+def test_bert_large_whole_step(name, two_pass):
     _need_gpu()
     cfg = make_config(name)
     c = cfg["W"] // 2
-    st, dev, g = device_setup(cfg, c)
+    st, dev, g = device_setup(cfg, c, two_pass=two_pass)
     ref = RefStep(cfg["plist"].offsets, cfg["W"], c)
     ref.load_state({k: dev.get(k) for k in ref.t})
     ref.set_foreign_in(dev.packed_in.cpu().numpy(), dev.scales_in.cpu().numpy())
@@ -63,7 +70,7 @@ def test_bert_large_whole_step(name):
     for k in ("err_worker", "err_server", "v_fresh", "r_prev", "coeff_c", "x", "m"):
         nd[k] = assert_close(dev.get(k), ref.t[k], k)
     print(f"{name}: elements not bit-equal (within 1e-6): {nd}", flush=True)
-    dev.close()
+    finish(dev)
 
 
 def window_cfg(cfg, c0, c1):
@@ -137,4 +144,4 @@ def test_gpt_1p3b_windows():
             assert np.array_equal(dev.t["m"][A + a:A + b_].cpu().numpy(), ref.t["m"][a:b_]), f"m layer {l}"
         print(f"gpt window chunks [{c0},{c1}): {idx.size} whole layers checked", flush=True)
     assert whole >= 12
-    dev.close()
+    finish(dev)

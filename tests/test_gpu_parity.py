@@ -21,9 +21,30 @@ def _need_gpu():
         pytest.skip("no GPU visible")
 
 
-def DeviceStep(*a, **k):
+def DeviceStep(*a, two_pass=False, **k):
+    """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
+    kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
+    import os
     from paper_2104_06069_amd.step import DeviceStep as D
-    return D(*a, **k)
+    import paper_2104_06069_amd as ob
+    old = os.environ.pop("OB_LAMB_TWO_PASS", None)
+    if two_pass:
+        os.environ["OB_LAMB_TWO_PASS"] = "1"
+    try:
+        d = D(*a, **k)
+    finally:
+        os.environ.pop("OB_LAMB_TWO_PASS", None)
+        if old is not None:
+            os.environ["OB_LAMB_TWO_PASS"] = old
+    assert ob.ob_lamb_uses_single_pass(d.ctx) == (not two_pass)
+    return d
+
+
+def finish(dev):
+    """No bounded device-side wait expired; then release the context."""
+    import paper_2104_06069_amd as ob
+    ob.ob_lamb_check_device_status(dev.ctx, dev.stream)
+    dev.close()
 
 
 def assert_close(gpu, ref, what, rel=REL):
@@ -71,7 +92,7 @@ def make_case(name):
                 steps=3, server_chunk=W - 1, use_k=(name != "w1"))
 
 
-def start_pair(cfg, seed=0, warm_state=True):
+def start_pair(cfg, seed=0, warm_state=True, two_pass=False):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -79,7 +100,7 @@ def start_pair(cfg, seed=0, warm_state=True):
     if cfg.get("use_k"):
         k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0)
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k)
-    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **HYPER)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, **HYPER)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -106,12 +127,13 @@ def push_wire(ref, dev):
 CASES = ["small", "odd", "w1", "tiny", "bert_mini"]
 
 
+@pytest.mark.parametrize("two_pass", [False, True], ids=["single_pass", "two_pass"])
 @pytest.mark.parametrize("case", CASES)
-def test_phasewise_single_step(case):
+def test_phasewise_single_step(case, two_pass):
     """Each call is fed the oracle's outputs of the previous phase; signs must be bit-exact."""
     _need_gpu()
     cfg = make_case(case)
-    st, ref, dev = start_pair(cfg)
+    st, ref, dev = start_pair(cfg, two_pass=two_pass)
     g = gradient(st, cfg, 0)
     gd = torch.from_numpy(g).to(dev.device)
     lr = 2e-3
@@ -159,11 +181,11 @@ def test_phasewise_single_step(case):
     # padding never touched by the layer-wise phases
     N = ref.N
     assert np.array_equal(dev.get("x")[N:], ref.t["x"][N:]) and np.all(dev.get("m")[N:] == 0)
-    dev.close()
+    finish(dev)
 
 
-def run_trajectory(cfg, steps, seed=0):
-    st, ref, dev = start_pair(cfg, seed=seed, warm_state=False)
+def run_trajectory(cfg, steps, seed=0, two_pass=False):
+    st, ref, dev = start_pair(cfg, seed=seed, warm_state=False, two_pass=two_pass)
     stats = dict(word_mismatch_steps=0, scale_ulp_steps=0)
     for t in range(steps):
         g = gradient(st, cfg, t)
@@ -189,12 +211,13 @@ def run_trajectory(cfg, steps, seed=0):
     return ref, dev, stats
 
 
-@pytest.mark.parametrize("case,steps", [("tiny", 10), ("bert_mini", 100), ("odd", 30)])
-def test_trajectory(case, steps):
+@pytest.mark.parametrize("case,steps,two_pass", [("tiny", 10, False), ("bert_mini", 100, False),
+                                                 ("odd", 30, False), ("bert_mini", 30, True)])
+def test_trajectory(case, steps, two_pass):
     """The device feeds itself for `steps` steps; the oracle does the same on the host."""
     _need_gpu()
     cfg = make_case(case)
-    ref, dev, stats = run_trajectory(cfg, steps)
+    ref, dev, stats = run_trajectory(cfg, steps, two_pass=two_pass)
     x_ref = ref.t["x"][:ref.N].astype(np.float64)
     x_gpu = dev.get("x")[:ref.N].astype(np.float64)
     rel = np.linalg.norm(x_gpu - x_ref) / np.linalg.norm(x_ref)
@@ -206,7 +229,7 @@ def test_trajectory(case, steps):
     else:
         for k in ("x", "m", "v_fresh", "r_prev"):
             assert_close(dev.get(k), ref.t[k], k, rel=1e-4)
-    dev.close()
+    finish(dev)
 
 
 @pytest.mark.parametrize("case", ["odd", "bert_mini", "small"])
@@ -243,7 +266,7 @@ def test_warmup_and_freeze(case, wd):
     assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
     for k in ("x", "m", "v_fresh", "r_prev", "coeff_c"):
         assert_close(dev.get(k), ref.t[k], k)
-    dev.close()
+    finish(dev)
 
 
 def test_degenerate_values():
@@ -282,7 +305,7 @@ def test_degenerate_values():
     for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
         assert_close(dev.get(k), ref.t[k], k)
     assert np.all(np.isfinite(dev.get("r_prev")))
-    dev.close()
+    finish(dev)
 
 
 def test_bitwise_reproducible():
@@ -298,7 +321,7 @@ def test_bitwise_reproducible():
         dev.step(g, 1e-3)
         outs.append({k: dev.get(k).copy() for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev")}
                     | {"scales": dev.scales_local.cpu().numpy(), "w": words_of(dev.packed_local).copy()})
-        dev.close()
+        finish(dev)
     for k in outs[0]:
         assert np.array_equal(outs[0][k], outs[1][k], equal_nan=True) if outs[0][k].dtype.kind == "f" \
             else np.array_equal(outs[0][k], outs[1][k]), k
@@ -323,4 +346,4 @@ def test_argument_errors():
     x0 = dev.get("x").copy()
     torch.cuda.synchronize()
     assert np.array_equal(dev.get("x"), x0)
-    dev.close()
+    finish(dev)
