@@ -18,24 +18,45 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# Algorithmic HBM bytes per element of one launch of each kernel: every input read once, every
-# output written once.  Units per launch: n_pad for the N-sized kernels, n_c for the server ones.
+# Algorithmic HBM bytes per element of one launch of each kernel (every input read once, every
+# output written once), by momentum representation.  Units per launch: n_pad for the N-sized
+# kernels, n_c for the server ones.
 KERNEL_BYTES = {
-    "compress_resident": (16.125, "n_pad"),     # R g, m, err (12) + W err (4) + W bits (1/8)
-    "momentum_z_sumsq": (16.0, "n_pad"),        # R g, m, err (12) + W z (4)
-    "sign_pack_error": (8.125, "n_pad"),        # R z (4) + W err (4) + W bits (1/8)
-    "server_unpack_avg": (None, "n_c"),         # W/8 + 8, filled in below
-    "server_sign_pack": (8.125, "n_c"),
-    "ratios_pass": (16.125, "n_pad"),           # R bits, m, v_fresh, v_frozen (12.125) + W v_fresh (4)
-    "decompress_apply": (16.125, "n_pad"),      # R bits, v_frozen, x (8.125) + W x, m (8)
-    "warmup_moments": (24.0, "n_pad"),          # R g, m, v, x (16) + W m, v (8)
-    "warmup_apply": (16.0, "n_pad"),            # R m, v, x (12) + W x (4)
+    "dense": {   # momentum read and written as an fp32 array
+        "compress_resident": (16.125, "n_pad"),  # R g, m, err (12) + W err (4) + W bits (1/8)
+        "momentum_z_sumsq": (16.0, "n_pad"),     # R g, m, err (12) + W z (4)
+        "ratios_pass": (16.125, "n_pad"),        # R bits, m, v_fresh, v_frozen (12.125) + W v_fresh (4)
+        "decompress_apply": (16.125, "n_pad"),   # R bits, v_frozen, x (8.125) + W x, m (8)
+    },
+    "packed": {  # momentum read from last step's sign words, never written as fp32
+        "compress_resident": (12.25, "n_pad"),   # R g, err (8) + m bits (1/8) + W err (4) + bits (1/8)
+        "momentum_z_sumsq": (12.125, "n_pad"),
+        "ratios_pass": (12.25, "n_pad"),         # R bits, m bits (1/4), v_fresh, v_frozen (8) + W v_fresh (4)
+        "decompress_apply": (12.125, "n_pad"),   # R bits, v_frozen, x (8.125) + W x (4)
+    },
+    "both": {
+        "sign_pack_error": (8.125, "n_pad"),     # R z (4) + W err (4) + W bits (1/8)
+        "server_unpack_avg": (None, "n_c"),      # W/8 + 8, filled in below
+        "server_sign_pack": (8.125, "n_c"),
+        "warmup_moments": (24.0, "n_pad"),       # R g, m, v, x (16) + W m, v (8)
+        "warmup_apply": (16.0, "n_pad"),         # R m, v, x (12) + W x (4)
+    },
 }
 
 
 def compulsory_step_bytes_per_param(W):
-    # compress_local 16.125 + server_reduce (0.125 + 8.125/W) + layer_ratios 16.125 + apply 12.0
+    """The step's compulsory bytes with an fp32 momentum array (the accounting this build was
+    specified against): compress_local 16.125 + server_reduce (0.125 + 8.125/W) + layer_ratios
+    16.125 + decompress_apply 12.0."""
     return 16.125 + 0.125 + 8.125 / W + 16.125 + 12.0
+
+
+def algorithmic_step_bytes_per_param(W, mode):
+    """What the three N-sized calls as implemented must move (each call's inputs once, outputs
+    once), plus the server call."""
+    k = KERNEL_BYTES[mode]
+    return (k["compress_resident"][0] + k["ratios_pass"][0] + k["decompress_apply"][0]
+            + 0.125 + 8.125 / W)
 
 
 def main():
@@ -51,6 +72,9 @@ def main():
                     help="only run a plain 1 GiB device copy 10 times (for scaling rocprofv3 "
                          "FETCH_SIZE/WRITE_SIZE readings) and exit")
     ap.add_argument("--mom-scale", action="store_true", help="with Appendix A.5.2 momentum scaling")
+    ap.add_argument("--dense-momentum", action="store_true",
+                    help="keep the momentum as an fp32 array (default: the 1-bit form it has after "
+                         "Algorithm 1 line 13; same results, 12 bytes/param less traffic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU's share of the data-parallel step (no "
@@ -86,16 +110,23 @@ def main():
     server_chunk = W // 2
     st = Streams(0, device="cuda:0")
     mom_scale = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if args.mom_scale else None
-    ds = DeviceStep(pl.offsets, W, server_chunk, device="cuda:0", mom_scale=mom_scale, **hyper)
+    mode = "dense" if args.dense_momentum else "packed"
+    ds = DeviceStep(pl.offsets, W, server_chunk, device="cuda:0", mom_scale=mom_scale,
+                    packed_momentum=(mode == "packed"), **hyper)
     ds.load_state(init_state(st, cfg))
     n_grads = 3
     grads = [gradient(st, cfg, t) for t in range(n_grads)]
     fw, fs = foreign_worker_chunks(st, cfg, 0)
-    fa, fss = foreign_server_chunks(st, cfg, 0)
     ds.packed_in.copy_(fw); ds.scales_in.copy_(torch.from_numpy(fs))
-    ds.packed_all.copy_(fa); ds.server_scales.copy_(torch.from_numpy(fss))
+    for i in range(len(ds._pa)):   # what the other ranks' servers send, for both buffer pairs
+        fa, fss = foreign_server_chunks(st, cfg, i)
+        ds._pa[i].copy_(fa); ds._ss[i].copy_(torch.from_numpy(fss))
     lr = 1e-3
     torch.cuda.synchronize()
+
+    def one_step(t):
+        ds.begin_step()
+        ds.step(grads[t % n_grads], lr)
 
     host0 = None
     if not args.no_cpu_baseline:
@@ -103,15 +134,15 @@ def main():
         host0 = dict(state={k: ds.get(k).copy() for k in
                             ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev")},
                      grads=[g.cpu().numpy() for g in grads[:2]],
-                     fw=ds.packed_in.cpu().numpy(), fs=fs.copy(), fa=ds.packed_all.cpu().numpy(),
-                     fss=fss.copy())
+                     fw=ds.packed_in.cpu().numpy(), fs=fs.copy(), fa=ds._pa[0].cpu().numpy(),
+                     fss=ds._ss[0].cpu().numpy())
 
     for t in range(args.warmup):
-        ds.step(grads[t % n_grads], lr)
+        one_step(t)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.steps):
-        ds.step(grads[t % n_grads], lr)
+        one_step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
@@ -122,6 +153,7 @@ def main():
     evs = []
     for t in range(args.profile_steps):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        ds.begin_step()
         e[0].record(); ds.compress_local(grads[t % n_grads])
         e[1].record(); ds.gather()
         e[2].record(); ds.server_reduce()
@@ -135,11 +167,12 @@ def main():
 
     ob.ob_lamb_profile_enable(ds.ctx, True)
     for t in range(args.profile_steps):
-        ds.step(grads[t % n_grads], lr)
+        one_step(t)
     prof = ob.ob_lamb_profile_read(ds.ctx)
     ob.ob_lamb_profile_enable(ds.ctx, False)
     kern = {k: {"avg_ms": round(v[0] / v[1], 4), "launches": v[1]} for k, v in prof.items()}
-    KB = dict(KERNEL_BYTES)
+    KB = dict(KERNEL_BYTES["both"])
+    KB.update(KERNEL_BYTES[mode])
     KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
     units = {"n_pad": ds.n_pad, "n_c": ds.n_c}
     for k, v in kern.items():
@@ -152,7 +185,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+            traffic = json.load(open(tpath)).get(f"{args.workload}:{mode}", {}).get(dom)
         except Exception:
             traffic = None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
@@ -161,6 +194,7 @@ def main():
                 "traffic": traffic}
 
     step_bytes = compulsory_step_bytes_per_param(W) * ds.n_pad
+    algo_bytes = algorithmic_step_bytes_per_param(W, mode) * ds.n_pad
     out = {
         "metric": "1-bit LAMB compressed step: params/sec and % of HBM peak GB/s, 1 GPU",
         "value": round(pl.N / (ms_per_step * 1e-3), 1), "unit": "params/s",
@@ -169,8 +203,11 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
                    "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
-                   "mom_scale": bool(args.mom_scale),
+                   "mom_scale": bool(args.mom_scale), "momentum": mode,
                    "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx)},
+        "step_algorithmic_bytes": algo_bytes,
+        "step_algorithmic_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_algorithmic_pct_of_hbm_peak": round(100 * algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "step_compulsory_bytes": step_bytes,
         "step_compulsory_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_pct_of_hbm_peak": round(100 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),

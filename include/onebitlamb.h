@@ -88,7 +88,26 @@ typedef struct ob_lamb_state {
   float* r_prev;     /* [L] r_{t-1}^(l), starts at 1 (line 1) */
   float* coeff_c;    /* [L] out: c_t^(l); warmup: eq. (1)'s c; compression stage: line 20 */
   float* mom_scale;  /* [L] momentum-scale coefficients of Appendix A.5.2, or NULL (= all ones) */
+  /* The momentum in the 1-bit form it has after Algorithm 1 line 13 (optional, see below). */
+  uint32_t* m_packed; /* [N_pad/32] sign words, or NULL */
+  float* m_scales;    /* [W] server scales they decode with, or NULL */
 } ob_lamb_state;
+
+/* Momentum representation.  After line 13 of any compression step the global momentum is exactly
+ * m[i] = (bit_i ? +s_c : -s_c) / k_l (0 in the padding), i.e. the step's packed_all/server_scales.
+ * The library therefore accepts it in either form:
+ *   - reads (ob_lamb_compress_local, ob_lamb_layer_ratios) use the dense array st->m if it is
+ *     non-NULL, else decode (st->m_packed, st->m_scales) on the fly -- 12 bytes per parameter
+ *     less HBM traffic per step, bit-identical results;
+ *   - ob_lamb_decompress_apply commits the new momentum to st->m if non-NULL, and to
+ *     (st->m_packed, st->m_scales) if non-NULL (a device copy of packed_all/server_scales, skipped
+ *     when st->m_packed == packed_all, e.g. when the caller alternates two packed_all buffers).
+ * The warmup step needs the dense array; the first compression step after warmup reads it, and a
+ * caller that wants the 1-bit form passes m = NULL from that step's ob_lamb_decompress_apply on.
+ * ob_lamb_momentum_dense writes the dense view of (m_packed, m_scales) into m_out [N_pad]
+ * (padding left untouched) for checkpoints or inspection. */
+ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* m_out,
+                                 void* hip_stream);
 
 /* Creates a context on the current HIP device: copies the configuration, builds the tile tables
  * and allocates the workspace (blocking; uses hipMalloc/hipMemcpy).  *out is NULL on error. */
@@ -118,7 +137,8 @@ ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_st
  *   z = k_l * (beta1*m + (1-beta1)*grad) + err_worker;   per chunk c: scales_out[c], bits;
  *   err_worker <- z - C[z].
  * grad: [N_pad] this worker's local gradient.  packed_out: [N_pad/32] words.  scales_out: [W].
- * Reads m, does not modify it. */
+ * Reads the momentum (dense or 1-bit form), does not modify it.  In the 1-bit form m_packed must
+ * not be the buffer packed_out (OB_ERR_ARG). */
 ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad,
                                  uint32_t* packed_out, float* scales_out, void* hip_stream);
 

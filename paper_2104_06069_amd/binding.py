@@ -33,7 +33,7 @@ class ObLambConfig(C.Structure):
 class ObLambState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev",
-                 "coeff_c", "mom_scale")]
+                 "coeff_c", "mom_scale", "m_packed", "m_scales")]
 
 
 def lib_path():
@@ -65,6 +65,7 @@ def lib():
             "ob_lamb_server_reduce": (C.c_int, [vp, sp, vp, vp, vp, vp, vp]),
             "ob_lamb_layer_ratios": (C.c_int, [vp, sp, vp, vp, vp]),
             "ob_lamb_decompress_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
+            "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
@@ -169,6 +170,11 @@ def ob_lamb_decompress_apply(ctx, state, packed_all, server_scales, lr, stream=N
     _check(lib().ob_lamb_decompress_apply(ctx, C.byref(state), _addr(packed_all),
                                           _addr(server_scales), lr, _addr(stream)), ctx,
            "ob_lamb_decompress_apply")
+
+
+def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):
+    _check(lib().ob_lamb_momentum_dense(ctx, C.byref(state), _addr(m_out), _addr(stream)), ctx,
+           "ob_lamb_momentum_dense")
 
 
 def ob_lamb_check_device_status(ctx, stream=None):

@@ -1,0 +1,970 @@
+// Device code of libonebitlamb (gfx950): every kernel of the compression-stage step of 1-bit LAMB
+// (arXiv 2104.06069, Algorithm 1) and of the LAMB warmup step (eq. (1)).  Included by
+// onebitlamb.hip only.
+//
+// Arithmetic contract: IEEE binary32, one rounding per operation (the build passes
+// -ffp-contract=off; hipcc's default divide and sqrt are correctly rounded), evaluated in the
+// operation order written below; the sum-of-squares reductions accumulate in binary64 in a fixed
+// order.  Never build with -ffast-math.
+//
+// Layout of the work.  The padded flat buffer is W chunks of n_c elements (n_c % 256 == 0).
+// Every N-sized kernel runs on "tiles": tile (c, b) is elements [c*n_c + b*TILE, +TILE) clipped
+// to the chunk, so a tile never crosses a chunk boundary and its length is a multiple of 256.
+// A workgroup of 256 threads owns one tile; thread t touches elements tile0 + u*1024 + 4*t + k
+// (u < U, k < 4) with 128-bit accesses, i.e. each wavefront-wide access covers 256 consecutive
+// elements = 8 consecutive 32-bit words of a packed sign stream.
+//
+// Layers (tensors) are arbitrary, unaligned ranges of the flat buffer.  A host-built table gives
+// the layer of each tile's first element (L = padding); a tile that lies inside one layer takes a
+// vectorised path with per-tile scalars, a tile that meets a layer boundary or the end of the
+// parameters takes a per-element path that walks the offset table.
+//
+// The momentum m_{t-1} has two sources: a dense fp32 array, or (template flag PACKED_M) the 1-bit
+// form it has had since line 13 of the previous step: m[i] = (bit ? +s_c : -s_c) / k_l for
+// i < N and 0 in the padding, where s_c is the previous step's server scale of chunk c.  Both give
+// the same bits: the dense array holds exactly those values.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace obk {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int BLOCK = 256;       // threads per workgroup (4 wavefronts of 64)
+constexpr int WAVE = 64;
+constexpr int SPAN = BLOCK * 4;  // elements one workgroup-wide 128-bit access covers
+#define OB_AGENT __HIP_MEMORY_SCOPE_AGENT
+
+// Every N-sized array is read once and written once per kernel: 128-bit nontemporal (streaming)
+// accesses, which measure ~10 % faster than plain ones on MI355X for these patterns.
+__device__ __forceinline__ v4f ld4(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+}
+__device__ __forceinline__ void st4(float* p, v4f v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+}
+
+// Sum of one double per thread over the workgroup, in a fixed order; result valid in thread 0.
+__device__ __forceinline__ double block_sum(double v, double* lds /* [BLOCK/WAVE] */) {
+#pragma unroll
+  for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
+  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+  __syncthreads();  // protects lds against the previous use
+  if (lane == 0) lds[wv] = v;
+  __syncthreads();
+  double r = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < BLOCK / WAVE; ++i) r += lds[i];
+  }
+  return r;
+}
+
+// Max of one non-NaN, non-negative float per thread over the workgroup; valid in thread 0.
+__device__ __forceinline__ float block_max(float v, float* lds /* [BLOCK/WAVE] */) {
+#pragma unroll
+  for (int o = WAVE / 2; o > 0; o >>= 1) {
+    const float w = __shfl_down(v, o, WAVE);
+    v = (w > v) ? w : v;
+  }
+  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+  __syncthreads();
+  if (lane == 0) lds[wv] = v;
+  __syncthreads();
+  float r = 0.0f;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < BLOCK / WAVE; ++i) r = (lds[i] > r) ? lds[i] : r;
+  }
+  return r;
+}
+
+// off has L+2 entries, off[L+1] = INT64_MAX, so the walk stops at L (= padding) at the latest.
+__device__ __forceinline__ int walk_layer(int l, int64_t i, const int64_t* __restrict__ off) {
+  while (i >= off[l + 1]) ++l;
+  return l;
+}
+
+// Sign nibble of the lane's 4 elements -> the 32-bit word of its 8-lane group (in every lane of
+// the group).  Element 4*lane + k of the 256-element span is bit 4*(lane%8) + k of word lane/8.
+__device__ __forceinline__ unsigned int gather_word(unsigned int nibble) {
+  unsigned int v = nibble << (4 * (threadIdx.x & 7));
+  v |= __shfl_xor(v, 1, WAVE);
+  v |= __shfl_xor(v, 2, WAVE);
+  v |= __shfl_xor(v, 4, WAVE);
+  return v;
+}
+
+// The lane's sign nibble (bits of its 4 elements at offset o of the tile) from a packed stream.
+__device__ __forceinline__ unsigned int load_nibble(const uint32_t* __restrict__ packed, int64_t i0) {
+  return (packed[i0 >> 5] >> (4 * (threadIdx.x & 7))) & 0xFu;
+}
+
+struct TilePos {
+  int c;          // chunk
+  int64_t tile0;  // first element
+  int len;        // elements in the tile (multiple of 256)
+};
+
+template <int TILE>
+__device__ __forceinline__ TilePos tile_pos(int64_t n_c, int tpc) {
+  TilePos p;
+  const int t = blockIdx.x;
+  p.c = t / tpc;
+  const int b = t - p.c * tpc;
+  const int64_t in_chunk = (int64_t)b * TILE;
+  p.tile0 = (int64_t)p.c * n_c + in_chunk;
+  const int64_t rest = n_c - in_chunk;
+  p.len = rest < TILE ? (int)rest : TILE;
+  return p;
+}
+
+// Per-layer tables (device pointers) shared by the layer-aware kernels.
+struct LayerTab {
+  const float* mom_scale;   // [L] k_l of Appendix A.5.2 (only read when HAS_K)
+  const int64_t* off;       // [L+2]
+  const int* first_layer;   // [tiles of the launching kernel's tile size]
+  int L;
+};
+
+// Momentum source in 1-bit form (only read when PACKED_M).
+struct PackedMom {
+  const uint32_t* bits;     // [N_pad/32]
+  const float* scales;      // [W]
+};
+
+// ---------------------------------------------------------------------------------------------
+// z = k_l * (beta1*m + (1-beta1)*g) + err       (Algorithm 1 lines 6-7, Appendix A.5.2)
+// Per-tile constants and the per-access evaluation, shared by the two-pass and single-pass kernels.
+// ---------------------------------------------------------------------------------------------
+template <bool HAS_K, bool PACKED_M>
+struct ZTile {
+  bool uniform, pad;
+  int l0;
+  float kt;      // k of the tile's layer (uniform tiles)
+  float bm;      // beta1 * |m| of the tile (uniform tiles, PACKED_M)
+  float s_prev;  // previous server scale of the chunk (PACKED_M)
+
+  __device__ __forceinline__ void init(const LayerTab& lt, const PackedMom& pm, const TilePos& p,
+                                       float beta1) {
+    uniform = true; pad = false; l0 = 0; kt = 1.0f; bm = 0.0f; s_prev = 0.0f;
+    if (PACKED_M) s_prev = pm.scales[p.c];
+    if (HAS_K || PACKED_M) {
+      l0 = lt.first_layer[blockIdx.x];
+      uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+      pad = (l0 >= lt.L);
+      if (uniform && !pad) {
+        if (HAS_K) kt = lt.mom_scale[l0];
+        if (PACKED_M) bm = beta1 * (HAS_K ? s_prev / kt : s_prev);
+      }
+    }
+  }
+
+  // G, E: gradient and carried error; M: dense momentum (ignored when PACKED_M); nib: the sign
+  // bits of the packed momentum (ignored otherwise); i0: flat index of the first element.
+  __device__ __forceinline__ v4f z(const LayerTab& lt, float beta1, float omb1, v4f G, v4f M,
+                                   unsigned int nib, v4f E, int64_t i0) const {
+    v4f r;
+    if (uniform) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float bmk;
+        if (PACKED_M) bmk = pad ? 0.0f : (((nib >> k) & 1u) ? bm : -bm);
+        else bmk = beta1 * M[k];
+        const float mloc = bmk + omb1 * G[k];
+        r[k] = HAS_K ? kt * mloc + E[k] : mloc + E[k];
+      }
+    } else {
+      int l = l0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        l = walk_layer(l, i0 + k, lt.off);
+        const bool real = (l < lt.L);
+        const float kk = (HAS_K && real) ? lt.mom_scale[l] : 1.0f;
+        float bmk;
+        if (PACKED_M) {
+          const float b = beta1 * (HAS_K ? s_prev / kk : s_prev);
+          bmk = real ? (((nib >> k) & 1u) ? b : -b) : 0.0f;
+        } else {
+          bmk = beta1 * M[k];
+        }
+        const float mloc = bmk + omb1 * G[k];
+        r[k] = HAS_K ? kk * mloc + E[k] : mloc + E[k];
+      }
+    }
+    return r;
+  }
+};
+
+// ---------------------------------------------------------------------------------------------
+// K1 (two-pass path)  z written over err, and the tile's sum of z^2 in fp64.
+// ---------------------------------------------------------------------------------------------
+template <int U, bool HAS_K, bool PACKED_M>
+__global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
+    const float* __restrict__ g, const float* __restrict__ m, PackedMom pm,
+    float* __restrict__ err, double* __restrict__ partials, int64_t n_c, int tpc, float beta1,
+    float omb1, LayerTab lt) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int o0 = threadIdx.x * 4;
+  v4f G[U], M[U], E[U];
+  unsigned int NB[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    M[u] = 0.0f; NB[u] = 0u;
+    if (o < p.len) {
+      G[u] = ld4(g + p.tile0 + o);
+      if (PACKED_M) NB[u] = load_nibble(pm.bits, p.tile0 + o);
+      else M[u] = ld4(m + p.tile0 + o);
+      E[u] = ld4(err + p.tile0 + o);
+    }
+  }
+  ZTile<HAS_K, PACKED_M> zt;
+  zt.init(lt, pm, p, beta1);
+  double acc = 0.0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      const v4f z = zt.z(lt, beta1, omb1, G[u], M[u], NB[u], E[u], p.tile0 + o);
+      st4(err + p.tile0 + o, z);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc += (double)z[k] * (double)z[k];
+    }
+  }
+  const double s = block_sum(acc, lds);
+  if (threadIdx.x == 0) partials[blockIdx.x] = s;
+}
+
+// scale[c] = sqrt(sum of the chunk's tile partials / n_c), summed in a fixed order.
+__global__ __launch_bounds__(BLOCK) void k_chunk_scale(const double* __restrict__ partials, int tpc,
+                                                       int64_t n_c, float* __restrict__ scales) {
+  __shared__ double lds[BLOCK / WAVE];
+  const int c = blockIdx.x;
+  double a = 0.0;
+  for (int j = threadIdx.x; j < tpc; j += BLOCK) a += partials[(int64_t)c * tpc + j];
+  const double S = block_sum(a, lds);
+  if (threadIdx.x == 0) scales[c] = (float)sqrt(S / (double)n_c);
+}
+
+// Sign, pack and error update of one 128-bit access held in registers (Algorithm 1 line 7/10).
+__device__ __forceinline__ void sign_pack_store(v4f z, float s, float* __restrict__ err,
+                                                uint32_t* __restrict__ packed, int64_t i0) {
+  unsigned int nib = 0;
+  v4f e;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const bool b = (z[k] >= 0.0f);
+    nib |= (b ? 1u : 0u) << k;
+    e[k] = z[k] - (b ? s : -s);
+  }
+  st4(err + i0, e);
+  const unsigned int word = gather_word(nib);
+  if ((threadIdx.x & 7) == 0) packed[i0 >> 5] = word;
+}
+
+// ---------------------------------------------------------------------------------------------
+// K2 (two-pass path)  bits = (z >= 0), packed; err <- z - (+-scale)
+// ---------------------------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ err,
+                                                           uint32_t* __restrict__ packed,
+                                                           const float* __restrict__ scales,
+                                                           int64_t n_c, int tpc) {
+  constexpr int TILE = SPAN * U;
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const float s = scales[p.c];
+  const int o0 = threadIdx.x * 4;
+  v4f Z[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) Z[u] = ld4(err + p.tile0 + o);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    // uniform over the wavefront (len is a multiple of 256), as the shuffles inside require
+    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + o);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-chunk arrival barrier of the single-pass kernels.
+//
+// Each workgroup of a chunk publishes one fp64 partial and arrives; the last one to arrive sums
+// the chunk's partials in a fixed order, turns the sum into the scale and publishes it; the others
+// wait for it.  Returns the chunk's scale to every thread.
+//
+// Progress: workgroups are dispatched in index order and a chunk's tiles are consecutive indices,
+// so the oldest unfinished chunk always has all of its tiles resident or dispatchable provided the
+// device can hold one chunk's workgroups at once; the host selects these kernels only when twice
+// that many fit.  Every wait is bounded by spin_limit polls: on expiry the workgroup raises
+// *errflag, uses whatever it last read and goes on to exit, and all later waits end at once.
+//
+// Synchronisation uses relaxed agent-scope atomics whose payload travels in the atomic itself
+// (partials: one double each; flag[c]: launch epoch in the high word, scale bits in the low word),
+// so no cache write-back/invalidate is needed; the store of the partial is complete (s_waitcnt)
+// before the arrival counter is incremented.  counter[c] grows by tpc per launch.
+// ---------------------------------------------------------------------------------------------
+struct ChunkSync {
+  double* partials;             // [tiles of the launching kernel]
+  unsigned long long* counter;  // [chunks]
+  unsigned long long* flag;     // [chunks]
+  unsigned int* errflag;        // [1]
+  unsigned int epoch;           // launch number, starts at 1
+  int spin_limit;
+};
+
+__device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int c, int tpc,
+                                                     int64_t n_c, double part, double* lds,
+                                                     unsigned long long* bc,
+                                                     float* __restrict__ scale_out) {
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&cs.partials[blockIdx.x], part, __ATOMIC_RELAXED, OB_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
+    const unsigned long long prev =
+        __hip_atomic_fetch_add(&cs.counter[c], 1ull, __ATOMIC_RELAXED, OB_AGENT);
+    *bc = (prev + 1ull == (unsigned long long)cs.epoch * (unsigned long long)tpc) ? 1ull : 0ull;
+  }
+  __syncthreads();
+  const bool last = (*bc != 0ull);
+  __syncthreads();
+  if (last) {
+    double a = 0.0;
+    for (int j = threadIdx.x; j < tpc; j += BLOCK)
+      a += __hip_atomic_load(&cs.partials[(int64_t)c * tpc + j], __ATOMIC_RELAXED, OB_AGENT);
+    const double S = block_sum(a, lds);
+    if (threadIdx.x == 0) {
+      const float sc = (float)sqrt(S / (double)n_c);
+      scale_out[c] = sc;
+      const unsigned long long f =
+          ((unsigned long long)cs.epoch << 32) | (unsigned long long)__float_as_uint(sc);
+      __hip_atomic_store(&cs.flag[c], f, __ATOMIC_RELAXED, OB_AGENT);
+      *bc = f;
+    }
+  } else if (threadIdx.x == 0) {
+    unsigned long long f = 0ull;
+    for (int it = 0;; ++it) {
+      f = __hip_atomic_load(&cs.flag[c], __ATOMIC_RELAXED, OB_AGENT);
+      if ((unsigned int)(f >> 32) == cs.epoch) break;
+      if (it >= cs.spin_limit) {
+        atomicOr(cs.errflag, 1u);
+        break;
+      }
+      if ((it & 63) == 63 && __hip_atomic_load(cs.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
+      __builtin_amdgcn_s_sleep(2);
+    }
+    *bc = f;
+  }
+  __syncthreads();
+  return __uint_as_float((unsigned int)(*bc & 0xffffffffull));
+}
+
+// ---------------------------------------------------------------------------------------------
+// K1+K2 in one pass: Algorithm 1 lines 6-7 with each input read once.  A workgroup computes z for
+// its tile (U*4 registers per thread), goes through the chunk barrier, then signs, packs and writes
+// the error from registers.  z never goes to memory.  Loads are issued G accesses at a time to
+// bound the staging registers.
+// ---------------------------------------------------------------------------------------------
+template <int U, int G, bool HAS_K, bool PACKED_M>
+__global__ __launch_bounds__(BLOCK, 4) void k_compress_resident(
+    const float* __restrict__ g, const float* __restrict__ m, PackedMom pm,
+    float* __restrict__ err, uint32_t* __restrict__ packed, float* __restrict__ scales,
+    ChunkSync cs, int64_t n_c, int tpc, float beta1, float omb1, LayerTab lt) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  __shared__ unsigned long long bc;
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int o0 = threadIdx.x * 4;
+  ZTile<HAS_K, PACKED_M> zt;
+  zt.init(lt, pm, p, beta1);
+  v4f Z[U];
+  double acc = 0.0;
+#pragma unroll
+  for (int u0 = 0; u0 < U; u0 += G) {
+    v4f Gr[G], M[G], E[G];
+    unsigned int NB[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int o = (u0 + j) * SPAN + o0;
+      M[j] = 0.0f; NB[j] = 0u;
+      if (o < p.len) {
+        Gr[j] = ld4(g + p.tile0 + o);
+        if (PACKED_M) NB[j] = load_nibble(pm.bits, p.tile0 + o);
+        else M[j] = ld4(m + p.tile0 + o);
+        E[j] = ld4(err + p.tile0 + o);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int o = (u0 + j) * SPAN + o0;
+      if (o < p.len) {
+        const v4f z = zt.z(lt, beta1, omb1, Gr[j], M[j], NB[j], E[j], p.tile0 + o);
+        Z[u0 + j] = z;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc += (double)z[k] * (double)z[k];
+      }
+    }
+  }
+  const double part = block_sum(acc, lds);
+  const float s = chunk_barrier_scale(cs, p.c, tpc, n_c, part, lds, &bc, scales);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + o);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K3  server: zb = (sum_w +-s_w, sequentially) * (1/W) + err_server   (Algorithm 1 line 10)
+// Workers strictly in order 0..W-1 (the fp32 sum is order dependent); the loads of GROUP workers
+// are issued together so that their latencies overlap.
+// ---------------------------------------------------------------------------------------------
+template <int U>
+__device__ __forceinline__ void server_average(const uint32_t* __restrict__ packed_in,
+                                               const float* __restrict__ scales_in, int64_t n_c,
+                                               int W, const TilePos& p, float (&acc)[U][4]) {
+  constexpr int GROUP = 8;
+  const int o0 = threadIdx.x * 4;
+  const int sh = 4 * (threadIdx.x & 7);
+  const int64_t wpc = n_c >> 5;  // words per worker block
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[u][k] = 0.0f;
+  for (int w0 = 0; w0 < W; w0 += GROUP) {
+    unsigned int word[GROUP][U];
+#pragma unroll
+    for (int j = 0; j < GROUP; ++j) {
+      const int w = (w0 + j < W) ? w0 + j : W - 1;
+      const uint32_t* row = packed_in + (int64_t)w * wpc;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int o = u * SPAN + o0;
+        word[j][u] = (o < p.len) ? row[(p.tile0 + o) >> 5] : 0u;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < GROUP; ++j) {
+      if (w0 + j < W) {
+        const float s = scales_in[w0 + j];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const unsigned int nib = word[j][u] >> sh;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[u][k] = acc[u][k] + (((nib >> k) & 1u) ? s : -s);
+        }
+      }
+    }
+  }
+}
+
+// two-pass form: zb written over err_server, tile partial of sum zb^2
+template <int U>
+__global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
+    const uint32_t* __restrict__ packed_in, const float* __restrict__ scales_in,
+    float* __restrict__ err_s, double* __restrict__ partials, int64_t n_c, int W, float invW) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x);  // one chunk: c == 0
+  const int o0 = threadIdx.x * 4;
+  float acc[U][4];
+  server_average<U>(packed_in, scales_in, n_c, W, p, acc);
+  double sq = 0.0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      const v4f e = ld4(err_s + p.tile0 + o);
+      v4f z;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        z[k] = acc[u][k] * invW + e[k];
+        sq += (double)z[k] * (double)z[k];
+      }
+      st4(err_s + p.tile0 + o, z);
+    }
+  }
+  const double s = block_sum(sq, lds);
+  if (threadIdx.x == 0) partials[blockIdx.x] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// K5  per layer: global momentum, reconstructed gradient, fresh variance, max(v_frozen/v_fresh)
+//     (Algorithm 1 lines 13, 15-17).  One maximum per (tile, layer) segment, no atomics.
+// With the previous momentum in 1-bit form the reconstructed gradient takes only two magnitudes
+// per tile, (s' - beta1 s)/(1-beta1) and (s' + beta1 s)/(1-beta1), whose squares are hoisted.
+// ---------------------------------------------------------------------------------------------
+template <int U, bool HAS_K, bool PACKED_M>
+__global__ __launch_bounds__(BLOCK) void k_ratios_pass(
+    const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
+    const float* __restrict__ m, PackedMom pm, float* __restrict__ v_fresh,
+    const float* __restrict__ v_frozen, float* __restrict__ seg_max, int64_t n_c, int tpc,
+    float beta1, float omb1, float beta2, float omb2, LayerTab lt,
+    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer) {
+  constexpr int TILE = SPAN * U;
+  __shared__ float lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int l0 = lt.first_layer[blockIdx.x];
+  const int L = lt.L;
+  if (l0 >= L) return;  // tile lies in the padding (it has no segment)
+  const int o0 = threadIdx.x * 4;
+  const float ss = sscales[p.c];
+  const float s_prev = PACKED_M ? pm.scales[p.c] : 0.0f;
+  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  unsigned int NB[U], OB[U];
+  v4f M[U], VF[U], VZ[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    M[u] = 0.0f; OB[u] = 0u;
+    if (o < p.len) {
+      NB[u] = load_nibble(packed, p.tile0 + o);
+      if (PACKED_M) OB[u] = load_nibble(pm.bits, p.tile0 + o);
+      else M[u] = ld4(m + p.tile0 + o);
+      VF[u] = ld4(v_fresh + p.tile0 + o);
+      VZ[u] = ld4(v_frozen + p.tile0 + o);
+    }
+  }
+  if (uniform) {
+    const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+    const float sp = HAS_K ? ss / kt : ss;
+    float t_same = 0.0f, t_diff = 0.0f;
+    if (PACKED_M) {
+      const float bm = beta1 * (HAS_K ? s_prev / kt : s_prev);
+      const float g_same = (sp - bm) / omb1;    // new and old momentum of equal sign
+      const float g_diff = (sp - (-bm)) / omb1; // of opposite sign
+      t_same = omb2 * (g_same * g_same);
+      t_diff = omb2 * (g_diff * g_diff);
+    }
+    float r = 0.0f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        v4f vf;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          float t;
+          if (PACKED_M) {
+            t = (((NB[u] ^ OB[u]) >> k) & 1u) ? t_diff : t_same;
+          } else {
+            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+            const float gr = (mt - beta1 * M[u][k]) / omb1;
+            t = omb2 * (gr * gr);
+          }
+          vf[k] = beta2 * VF[u][k] + t;
+          const float q = VZ[u][k] / vf[k];
+          if (q > r) r = q;
+        }
+        st4(v_fresh + p.tile0 + o, vf);
+      }
+    }
+    r = block_max(r, lds);
+    if (threadIdx.x == 0) seg_max[tile_seg0[blockIdx.x]] = r;
+  } else {
+    const int64_t N = lt.off[L];
+    // quotient of every element (kept in VZ), then one workgroup max per (tile, layer) segment
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        int l = l0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          float q = 0.0f;
+          if (i < N) {
+            l = walk_layer(l, i, lt.off);
+            const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
+            const float sp = HAS_K ? ss / kk : ss;
+            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+            float bmk;
+            if (PACKED_M) {
+              const float b = beta1 * (HAS_K ? s_prev / kk : s_prev);
+              bmk = ((OB[u] >> k) & 1u) ? b : -b;
+            } else {
+              bmk = beta1 * M[u][k];
+            }
+            const float gr = (mt - bmk) / omb1;
+            const float vf = beta2 * VF[u][k] + omb2 * (gr * gr);
+            v_fresh[i] = vf;
+            q = VZ[u][k] / vf;
+          }
+          VZ[u][k] = q;
+        }
+      }
+    }
+    const int s0 = tile_seg0[blockIdx.x], s1 = tile_seg0[blockIdx.x + 1];
+    for (int s = s0; s < s1; ++s) {
+      const int l = seg_layer[s];
+      const int64_t a = lt.off[l], b = lt.off[l + 1];
+      float r = 0.0f;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int o = u * SPAN + o0;
+        if (o < p.len) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int64_t i = p.tile0 + o + k;
+            if (i >= a && i < b && VZ[u][k] > r) r = VZ[u][k];
+          }
+        }
+      }
+      r = block_max(r, lds);
+      if (threadIdx.x == 0) seg_max[s] = r;
+    }
+  }
+}
+
+// K6  per layer: max over the layer's segments (0 for an empty layer), then Algorithm 1 lines 18-20.
+__global__ __launch_bounds__(BLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
+                                                           const int* __restrict__ layer_seg0,
+                                                           const float* __restrict__ c_avg,
+                                                           float* __restrict__ r_prev,
+                                                           float* __restrict__ coeff_c,
+                                                           float one_m_thr, float one_p_thr,
+                                                           float r_min, float r_max) {
+  __shared__ float lds[BLOCK / WAVE];
+  const int l = blockIdx.x;
+  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
+  float r = 0.0f;
+  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
+    const float q = seg_max[s];
+    if (q > r) r = q;
+  }
+  r = block_max(r, lds);
+  if (threadIdx.x == 0) {
+    const float rp = r_prev[l];
+    const float lo = one_m_thr * rp, hi = one_p_thr * rp;
+    r = (r > lo) ? r : lo;
+    r = (r < hi) ? r : hi;
+    r = (r > r_min) ? r : r_min;
+    r = (r < r_max) ? r : r_max;
+    r_prev[l] = r;
+    coeff_c[l] = r * c_avg[l];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K7  x <- x - (lr*c_l) * m_t/(sqrt(v_frozen)+eta);  m <- m_t (when WRITE_M)
+//     (Algorithm 1 lines 13, 21)
+// ---------------------------------------------------------------------------------------------
+template <int U, bool HAS_K, bool WRITE_M>
+__global__ __launch_bounds__(BLOCK) void k_decompress_apply(
+    const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
+    const float* __restrict__ v_frozen, float* __restrict__ x, float* __restrict__ m,
+    const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, LayerTab lt) {
+  constexpr int TILE = SPAN * U;
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int l0 = lt.first_layer[blockIdx.x];
+  const int L = lt.L;
+  if (l0 >= L) return;
+  const int o0 = threadIdx.x * 4;
+  const float ss = sscales[p.c];
+  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  unsigned int NB[U];
+  v4f X[U], VZ[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      NB[u] = load_nibble(packed, p.tile0 + o);
+      VZ[u] = ld4(v_frozen + p.tile0 + o);
+      X[u] = ld4(x + p.tile0 + o);
+    }
+  }
+  if (uniform) {
+    const float sp = HAS_K ? ss / lt.mom_scale[l0] : ss;
+    const float a = lr * coeff_c[l0];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        v4f xn, mn;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+          const float uu = mt / (sqrtf(VZ[u][k]) + eta);
+          xn[k] = X[u][k] - a * uu;
+          mn[k] = mt;
+        }
+        st4(x + p.tile0 + o, xn);
+        if (WRITE_M) st4(m + p.tile0 + o, mn);
+      }
+    }
+  } else {
+    const int64_t N = lt.off[L];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        int l = l0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          if (i < N) {
+            l = walk_layer(l, i, lt.off);
+            const float sp = HAS_K ? ss / lt.mom_scale[l] : ss;
+            const float a = lr * coeff_c[l];
+            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+            const float uu = mt / (sqrtf(VZ[u][k]) + eta);
+            x[i] = X[u][k] - a * uu;
+            if (WRITE_M) m[i] = mt;
+          }
+        }
+      }
+    }
+  }
+}
+
+// Dense view of a momentum held in 1-bit form: m[i] = (bit ? s_c : -s_c)/k_l for i < N (the
+// padding of m is left untouched).
+template <int U, bool HAS_K>
+__global__ __launch_bounds__(BLOCK) void k_momentum_dense(PackedMom pm, float* __restrict__ m,
+                                                          int64_t n_c, int tpc, LayerTab lt) {
+  constexpr int TILE = SPAN * U;
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int l0 = lt.first_layer[blockIdx.x];
+  const int L = lt.L;
+  if (l0 >= L) return;
+  const int o0 = threadIdx.x * 4;
+  const float ss = pm.scales[p.c];
+  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  const int64_t N = lt.off[L];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      const unsigned int nb = load_nibble(pm.bits, p.tile0 + o);
+      if (uniform) {
+        const float sp = HAS_K ? ss / lt.mom_scale[l0] : ss;
+        v4f mn;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mn[k] = ((nb >> k) & 1u) ? sp : -sp;
+        st4(m + p.tile0 + o, mn);
+      } else {
+        int l = l0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          if (i < N) {
+            l = walk_layer(l, i, lt.off);
+            const float sp = HAS_K ? ss / lt.mom_scale[l] : ss;
+            m[i] = ((nb >> k) & 1u) ? sp : -sp;
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K8  LAMB warmup step, eq. (1)
+//   a: m, v update; per (tile, layer) segment the fp64 sums of x^2 and u^2
+//   b: per layer: c = clip(||x||/||u||), c_avg moving average (Algorithm 1 line 2)
+//   c: x <- x - (lr*c) u, with u recomputed from the stored m, v (same operations, same value)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float lamb_u(float mn, float vn, float x, float eta, float wd) {
+  float u = mn / (sqrtf(vn) + eta);
+  if (wd != 0.0f) u = u + wd * x;
+  return u;
+}
+
+template <int U>
+__global__ __launch_bounds__(BLOCK) void k_warmup_moments(
+    const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,
+    const float* __restrict__ x, double* __restrict__ seg_sums /* [2*n_segs] */, int64_t n_c,
+    int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd, LayerTab lt,
+    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int l0 = lt.first_layer[blockIdx.x];
+  const int L = lt.L;
+  if (l0 >= L) return;
+  const int o0 = threadIdx.x * 4;
+  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  v4f G[U], M[U], V[U], X[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    G[u] = 0.0f; M[u] = 0.0f; V[u] = 0.0f; X[u] = 0.0f;
+    if (o < p.len) {
+      G[u] = ld4(g + p.tile0 + o);
+      M[u] = ld4(m + p.tile0 + o);
+      V[u] = ld4(v + p.tile0 + o);
+      X[u] = ld4(x + p.tile0 + o);
+    }
+  }
+  // new moments (kept in M, V)
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      M[u][k] = beta1 * M[u][k] + omb1 * G[u][k];
+      V[u][k] = beta2 * V[u][k] + omb2 * (G[u][k] * G[u][k]);
+    }
+  }
+  const int s0 = tile_seg0[blockIdx.x];
+  if (uniform) {
+    double sx = 0.0, su = 0.0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        st4(m + p.tile0 + o, M[u]);
+        st4(v + p.tile0 + o, V[u]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float uu = lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
+          sx += (double)X[u][k] * (double)X[u][k];
+          su += (double)uu * (double)uu;
+        }
+      }
+    }
+    sx = block_sum(sx, lds);
+    su = block_sum(su, lds);
+    if (threadIdx.x == 0) {
+      seg_sums[2 * (int64_t)s0] = sx;
+      seg_sums[2 * (int64_t)s0 + 1] = su;
+    }
+  } else {
+    const int64_t N = lt.off[L];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          if (i < N) {
+            m[i] = M[u][k];
+            v[i] = V[u][k];
+          }
+        }
+      }
+    }
+    const int s1 = tile_seg0[blockIdx.x + 1];
+    for (int s = s0; s < s1; ++s) {
+      const int l = seg_layer[s];
+      const int64_t a = lt.off[l], b = lt.off[l + 1];
+      double sx = 0.0, su = 0.0;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int o = u * SPAN + o0;
+        if (o < p.len) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int64_t i = p.tile0 + o + k;
+            if (i >= a && i < b) {
+              const float uu = lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
+              sx += (double)X[u][k] * (double)X[u][k];
+              su += (double)uu * (double)uu;
+            }
+          }
+        }
+      }
+      sx = block_sum(sx, lds);
+      su = block_sum(su, lds);
+      if (threadIdx.x == 0) {
+        seg_sums[2 * (int64_t)s] = sx;
+        seg_sums[2 * (int64_t)s + 1] = su;
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(BLOCK) void k_warmup_coeff(const double* __restrict__ seg_sums,
+                                                        const int* __restrict__ layer_seg0,
+                                                        float* __restrict__ coeff_c,
+                                                        float* __restrict__ c_avg, float c_min,
+                                                        float c_max, float beta3, float omb3) {
+  __shared__ double lds[BLOCK / WAVE];
+  const int l = blockIdx.x;
+  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
+  double sx = 0.0, su = 0.0;
+  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
+    sx += seg_sums[2 * (int64_t)s];
+    su += seg_sums[2 * (int64_t)s + 1];
+  }
+  sx = block_sum(sx, lds);
+  su = block_sum(su, lds);
+  if (threadIdx.x == 0) {
+    const float nx = (float)sqrt(sx), nu = (float)sqrt(su);
+    float c = nx / nu;
+    c = (c > c_min) ? c : c_min;
+    c = (c < c_max) ? c : c_max;
+    coeff_c[l] = c;
+    c_avg[l] = beta3 * c_avg[l] + omb3 * c;
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(BLOCK) void k_warmup_apply(
+    const float* __restrict__ m, const float* __restrict__ v, float* __restrict__ x,
+    const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, float wd,
+    LayerTab lt) {
+  constexpr int TILE = SPAN * U;
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int l0 = lt.first_layer[blockIdx.x];
+  const int L = lt.L;
+  if (l0 >= L) return;
+  const int o0 = threadIdx.x * 4;
+  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  v4f M[U], V[U], X[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      M[u] = ld4(m + p.tile0 + o);
+      V[u] = ld4(v + p.tile0 + o);
+      X[u] = ld4(x + p.tile0 + o);
+    }
+  }
+  if (uniform) {
+    const float a = lr * coeff_c[l0];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        v4f xn;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          xn[k] = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
+        st4(x + p.tile0 + o, xn);
+      }
+    }
+  } else {
+    const int64_t N = lt.off[L];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+        int l = l0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          if (i < N) {
+            l = walk_layer(l, i, lt.off);
+            const float a = lr * coeff_c[l];
+            x[i] = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
+          }
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(BLOCK) void k_fill(float* __restrict__ p, int64_t n, float v) {
+  const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+}  // namespace obk

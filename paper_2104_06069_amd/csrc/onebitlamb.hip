@@ -1,20 +1,8 @@
-// libonebitlamb: HIP kernels (gfx950) and C ABI for the compression-stage step of 1-bit LAMB
-// (arXiv 2104.06069, Algorithm 1) and the LAMB warmup step (eq. (1)).
+// libonebitlamb: host side of the C ABI (include/onebitlamb.h) -- context, tile tables, argument
+// validation and kernel launches.  The kernels live in ob_kernels.h.
 //
 // Build flags that the arithmetic depends on: -ffp-contract=off (one rounding per operation) and
 // hipcc's default correctly rounded fp32 divide/sqrt; never -ffast-math.
-//
-// Layout of the work.  The padded flat buffer is W chunks of n_c elements (n_c % 256 == 0).
-// Every N-sized kernel runs on "tiles": tile (c, b) is elements [c*n_c + b*TILE, +TILE) clipped
-// to the chunk, so a tile never crosses a chunk boundary and its length is a multiple of 256.
-// A workgroup of 256 threads owns one tile; thread t touches elements tile0 + u*1024 + 4*t + k
-// (u < U, k < 4) with 128-bit loads, i.e. each wavefront-wide access covers 256 consecutive
-// elements = 8 consecutive 32-bit words of the packed sign stream.
-//
-// Layers (tensors) are arbitrary, unaligned ranges of the flat buffer.  A host-built table gives
-// the layer of each tile's first element; a tile that lies inside one layer takes a vectorised
-// path with per-tile scalars, a tile that meets a layer boundary (or the padding) takes a
-// per-element path that walks the offset table.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -24,828 +12,24 @@
 #include <limits>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <vector>
 
+#include "ob_kernels.h"
 #include "onebitlamb.h"
+
+using namespace obk;
 
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int BLOCK = 256;          // threads per workgroup (4 wavefronts of 64)
-constexpr int WAVE = 64;
-constexpr int SPAN = BLOCK * 4;     // elements one workgroup-wide 128-bit access covers
-constexpr int U_MAIN = 4;           // accesses per thread per array in the N-sized kernels
-constexpr int U_SRV = 1;            // ... in the kernels over the single server chunk
-constexpr int U_RES = 16;           // ... in the single-pass worker compression (z stays in registers)
-constexpr int G_RES = 2;            // loads of the single-pass kernel are issued G_RES accesses at a time
+constexpr int U_MAIN = 4;   // 128-bit accesses per thread per array in the N-sized kernels
+constexpr int U_SRV = 1;    // ... in the kernels over the single server chunk
+constexpr int U_RES = 16;   // ... in the single-pass worker compression (z stays in registers)
+constexpr int G_RES = 2;    // the single-pass kernel issues its loads G_RES accesses at a time
 constexpr int TILE_MAIN = SPAN * U_MAIN;
 constexpr int TILE_SRV = SPAN * U_SRV;
 constexpr int TILE_RES = SPAN * U_RES;
-#define OB_AGENT __HIP_MEMORY_SCOPE_AGENT
 
-// ---------------------------------------------------------------------------------------------
-// device helpers
-// ---------------------------------------------------------------------------------------------
-// Every N-sized array is read once and written once per kernel: 128-bit nontemporal (streaming)
-// accesses, which measure ~10 % faster than plain ones on MI355X for these access patterns.
-__device__ __forceinline__ v4f ld4(const float* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-}
-__device__ __forceinline__ void st4(float* p, v4f v) {
-  __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
-}
-
-// Sum of one double per thread over the workgroup, in a fixed order; result valid in thread 0.
-__device__ __forceinline__ double block_sum(double v, double* lds /* [BLOCK/WAVE] */) {
-#pragma unroll
-  for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
-  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
-  __syncthreads();  // protects lds against the previous use
-  if (lane == 0) lds[wv] = v;
-  __syncthreads();
-  double r = 0.0;
-  if (threadIdx.x == 0) {
-#pragma unroll
-    for (int i = 0; i < BLOCK / WAVE; ++i) r += lds[i];
-  }
-  return r;
-}
-
-// Max of one non-NaN, non-negative float per thread over the workgroup; valid in thread 0.
-__device__ __forceinline__ float block_max(float v, float* lds /* [BLOCK/WAVE] */) {
-#pragma unroll
-  for (int o = WAVE / 2; o > 0; o >>= 1) {
-    const float w = __shfl_down(v, o, WAVE);
-    v = (w > v) ? w : v;
-  }
-  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
-  __syncthreads();
-  if (lane == 0) lds[wv] = v;
-  __syncthreads();
-  float r = 0.0f;
-  if (threadIdx.x == 0) {
-#pragma unroll
-    for (int i = 0; i < BLOCK / WAVE; ++i) r = (lds[i] > r) ? lds[i] : r;
-  }
-  return r;
-}
-
-// off has L+2 entries, off[L+1] = INT64_MAX, so the walk stops at L (= padding) at the latest.
-__device__ __forceinline__ int walk_layer(int l, int64_t i, const int64_t* __restrict__ off) {
-  while (i >= off[l + 1]) ++l;
-  return l;
-}
-
-// Sign nibble of the lane's 4 elements -> the 32-bit word of its 8-lane group (in every lane of
-// the group).  Element 4*lane + k of the 256-element span is bit 4*(lane%8) + k of word lane/8.
-__device__ __forceinline__ unsigned int gather_word(unsigned int nibble) {
-  unsigned int v = nibble << (4 * (threadIdx.x & 7));
-  v |= __shfl_xor(v, 1, WAVE);
-  v |= __shfl_xor(v, 2, WAVE);
-  v |= __shfl_xor(v, 4, WAVE);
-  return v;
-}
-
-struct TilePos {
-  int c;          // chunk
-  int64_t tile0;  // first element
-  int len;        // elements in the tile (multiple of 256)
-};
-
-template <int TILE>
-__device__ __forceinline__ TilePos tile_pos(int64_t n_c, int tpc) {
-  TilePos p;
-  const int t = blockIdx.x;
-  p.c = t / tpc;
-  const int b = t - p.c * tpc;
-  const int64_t in_chunk = (int64_t)b * TILE;
-  p.tile0 = (int64_t)p.c * n_c + in_chunk;
-  const int64_t rest = n_c - in_chunk;
-  p.len = rest < TILE ? (int)rest : TILE;
-  return p;
-}
-
-// ---------------------------------------------------------------------------------------------
-// K1  z = k_l*(beta1*m + (1-beta1)*g) + err  (Algorithm 1 lines 6-7, Appendix A.5.2), written over
-//     err, and the tile's sum of z^2 in fp64.
-// ---------------------------------------------------------------------------------------------
-template <int U, bool HAS_K>
-__global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
-    const float* __restrict__ g, const float* __restrict__ m, float* __restrict__ err,
-    double* __restrict__ partials, int64_t n_c, int tpc, float beta1, float omb1,
-    const float* __restrict__ mom_scale, const int64_t* __restrict__ off,
-    const int* __restrict__ first_layer, int L) {
-  constexpr int TILE = SPAN * U;
-  __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int o0 = threadIdx.x * 4;
-  v4f G[U], M[U], E[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      G[u] = ld4(g + p.tile0 + o);
-      M[u] = ld4(m + p.tile0 + o);
-      E[u] = ld4(err + p.tile0 + o);
-    }
-  }
-  bool uniform = true;
-  float kt = 1.0f;
-  int l0 = 0;
-  if (HAS_K) {
-    l0 = first_layer[blockIdx.x];
-    uniform = (p.tile0 + p.len <= off[l0 + 1]);
-    if (uniform && l0 < L) kt = mom_scale[l0];
-  }
-  double acc = 0.0;
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      v4f z;
-      if (!HAS_K) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) z[k] = (beta1 * M[u][k] + omb1 * G[u][k]) + E[u][k];
-      } else if (uniform) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) z[k] = kt * (beta1 * M[u][k] + omb1 * G[u][k]) + E[u][k];
-      } else {
-        int l = l0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          l = walk_layer(l, p.tile0 + o + k, off);
-          const float kk = (l < L) ? mom_scale[l] : 1.0f;
-          z[k] = kk * (beta1 * M[u][k] + omb1 * G[u][k]) + E[u][k];
-        }
-      }
-      st4(err + p.tile0 + o, z);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) acc += (double)z[k] * (double)z[k];
-    }
-  }
-  const double s = block_sum(acc, lds);
-  if (threadIdx.x == 0) partials[blockIdx.x] = s;
-}
-
-// scale[c] = sqrt(sum of the chunk's tile partials / n_c), summed in a fixed order.
-__global__ __launch_bounds__(BLOCK) void k_chunk_scale(const double* __restrict__ partials, int tpc,
-                                                       int64_t n_c, float* __restrict__ scales) {
-  __shared__ double lds[BLOCK / WAVE];
-  const int c = blockIdx.x;
-  double a = 0.0;
-  for (int j = threadIdx.x; j < tpc; j += BLOCK) a += partials[(int64_t)c * tpc + j];
-  const double S = block_sum(a, lds);
-  if (threadIdx.x == 0) scales[c] = (float)sqrt(S / (double)n_c);
-}
-
-// ---------------------------------------------------------------------------------------------
-// K2  bits = (z >= 0), packed; err <- z - (+-scale)   (Algorithm 1 line 7 / line 10)
-// ---------------------------------------------------------------------------------------------
-template <int U>
-__global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ err,
-                                                           uint32_t* __restrict__ packed,
-                                                           const float* __restrict__ scales,
-                                                           int64_t n_c, int tpc) {
-  constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const float s = scales[p.c];
-  const int o0 = threadIdx.x * 4;
-  v4f Z[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) Z[u] = ld4(err + p.tile0 + o);
-  }
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {  // uniform over the wavefront: len is a multiple of 256
-      unsigned int nib = 0;
-      v4f e;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const bool b = (Z[u][k] >= 0.0f);
-        nib |= (b ? 1u : 0u) << k;
-        e[k] = Z[u][k] - (b ? s : -s);
-      }
-      st4(err + p.tile0 + o, e);
-      const unsigned int word = gather_word(nib);
-      if ((threadIdx.x & 7) == 0) packed[(p.tile0 + o) >> 5] = word;
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// K1+K2 in one pass ("resident"): Algorithm 1 lines 6-7 with each input read once.
-//
-// A workgroup computes z for its tile (TILE_RES elements, 64 registers per thread), publishes the
-// tile's fp64 sum of squares and then waits until the whole chunk has arrived; the last workgroup
-// to arrive sums the chunk's partials in a fixed order and publishes the scale; everybody then
-// signs, packs and writes the error from registers.  z never goes to memory.
-//
-// Progress: workgroups are dispatched in index order and a chunk's tiles are consecutive indices,
-// so the oldest unfinished chunk always has all of its tiles resident or dispatchable provided the
-// device can hold one chunk's workgroups at once; the host only selects this kernel when twice
-// that many fit.  Every wait is bounded by spin_limit polls: on expiry the workgroup raises
-// *errflag, uses whatever scale it last read and exits, and all later waits end at once.
-//
-// Synchronisation uses relaxed agent-scope atomics whose payload travels in the atomic itself
-// (partials: one double each; flag[c]: epoch in the high word, scale bits in the low word), so no
-// cache write-back/invalidate is needed; the store of the partial is complete (s_waitcnt) before
-// the arrival counter is incremented.  counter[c] grows by tpc per launch; epoch numbers launches.
-// ---------------------------------------------------------------------------------------------
-template <int U, int G, bool HAS_K>
-__global__ __launch_bounds__(BLOCK, 4) void k_compress_resident(
-    const float* __restrict__ g, const float* __restrict__ m, float* __restrict__ err,
-    uint32_t* __restrict__ packed, float* __restrict__ scales, double* partials,
-    unsigned long long* counter, unsigned long long* flag, unsigned int* errflag, int64_t n_c,
-    int tpc, float beta1, float omb1, const float* __restrict__ mom_scale,
-    const int64_t* __restrict__ off, const int* __restrict__ first_layer, int L,
-    unsigned int epoch, int spin_limit) {
-  constexpr int TILE = SPAN * U;
-  __shared__ double lds[BLOCK / WAVE];
-  __shared__ unsigned long long bc;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int o0 = threadIdx.x * 4;
-  bool uniform = true;
-  float kt = 1.0f;
-  int l0 = 0;
-  if (HAS_K) {
-    l0 = first_layer[blockIdx.x];
-    uniform = (p.tile0 + p.len <= off[l0 + 1]);
-    if (uniform && l0 < L) kt = mom_scale[l0];
-  }
-  v4f Z[U];
-  double acc = 0.0;
-#pragma unroll
-  for (int u0 = 0; u0 < U; u0 += G) {
-    v4f Gr[G], M[G], E[G];
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const int o = (u0 + j) * SPAN + o0;
-      if (o < p.len) {
-        Gr[j] = ld4(g + p.tile0 + o);
-        M[j] = ld4(m + p.tile0 + o);
-        E[j] = ld4(err + p.tile0 + o);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const int o = (u0 + j) * SPAN + o0;
-      if (o < p.len) {
-        v4f z;
-        if (!HAS_K) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) z[k] = (beta1 * M[j][k] + omb1 * Gr[j][k]) + E[j][k];
-        } else if (uniform) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) z[k] = kt * (beta1 * M[j][k] + omb1 * Gr[j][k]) + E[j][k];
-        } else {
-          int l = l0;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            l = walk_layer(l, p.tile0 + o + k, off);
-            const float kk = (l < L) ? mom_scale[l] : 1.0f;
-            z[k] = kk * (beta1 * M[j][k] + omb1 * Gr[j][k]) + E[j][k];
-          }
-        }
-        Z[u0 + j] = z;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) acc += (double)z[k] * (double)z[k];
-      }
-    }
-  }
-  const double part = block_sum(acc, lds);
-  if (threadIdx.x == 0) {
-    __hip_atomic_store(&partials[blockIdx.x], part, __ATOMIC_RELAXED, OB_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the store is complete before the add
-    const unsigned long long prev =
-        __hip_atomic_fetch_add(&counter[p.c], 1ull, __ATOMIC_RELAXED, OB_AGENT);
-    bc = (prev + 1ull == (unsigned long long)epoch * (unsigned long long)tpc) ? 1ull : 0ull;
-  }
-  __syncthreads();
-  const bool last = (bc != 0ull);
-  __syncthreads();
-  if (last) {
-    double a = 0.0;
-    for (int j = threadIdx.x; j < tpc; j += BLOCK)
-      a += __hip_atomic_load(&partials[(int64_t)p.c * tpc + j], __ATOMIC_RELAXED, OB_AGENT);
-    const double S = block_sum(a, lds);
-    if (threadIdx.x == 0) {
-      const float sc = (float)sqrt(S / (double)n_c);
-      scales[p.c] = sc;
-      const unsigned long long f = ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(sc);
-      __hip_atomic_store(&flag[p.c], f, __ATOMIC_RELAXED, OB_AGENT);
-      bc = f;
-    }
-  } else if (threadIdx.x == 0) {
-    unsigned long long f = 0ull;
-    for (int it = 0;; ++it) {
-      f = __hip_atomic_load(&flag[p.c], __ATOMIC_RELAXED, OB_AGENT);
-      if ((unsigned int)(f >> 32) == epoch) break;
-      if (it >= spin_limit) {
-        atomicOr(errflag, 1u);
-        break;
-      }
-      if ((it & 63) == 63 && __hip_atomic_load(errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
-      __builtin_amdgcn_s_sleep(2);
-    }
-    bc = f;
-  }
-  __syncthreads();
-  const float s = __uint_as_float((unsigned int)(bc & 0xffffffffull));
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      unsigned int nib = 0;
-      v4f e;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const bool b = (Z[u][k] >= 0.0f);
-        nib |= (b ? 1u : 0u) << k;
-        e[k] = Z[u][k] - (b ? s : -s);
-      }
-      st4(err + p.tile0 + o, e);
-      const unsigned int word = gather_word(nib);
-      if ((threadIdx.x & 7) == 0) packed[(p.tile0 + o) >> 5] = word;
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// K3  server: zb = (sum_w +-s_w, sequentially) * (1/W) + err_server, written over err_server, and
-//     the tile's sum of zb^2   (Algorithm 1 line 10)
-// ---------------------------------------------------------------------------------------------
-template <int U>
-__global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
-    const uint32_t* __restrict__ packed_in, const float* __restrict__ scales_in,
-    float* __restrict__ err_s, double* __restrict__ partials, int64_t n_c, int W, float invW) {
-  constexpr int TILE = SPAN * U;
-  __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x);  // one chunk: c == 0
-  const int o0 = threadIdx.x * 4;
-  const int sh = 4 * (threadIdx.x & 7);
-  const int64_t wpc = n_c >> 5;  // words per worker block
-  float acc[U][4];
-#pragma unroll
-  for (int u = 0; u < U; ++u)
-#pragma unroll
-    for (int k = 0; k < 4; ++k) acc[u][k] = 0.0f;
-  // workers strictly in order 0..W-1 (the fp32 sum is order dependent); the loads of GROUP
-  // workers are issued together so that their latencies overlap
-  constexpr int GROUP = 8;
-  for (int w0 = 0; w0 < W; w0 += GROUP) {
-    unsigned int word[GROUP][U];
-#pragma unroll
-    for (int j = 0; j < GROUP; ++j) {
-      const int w = (w0 + j < W) ? w0 + j : W - 1;
-      const uint32_t* row = packed_in + (int64_t)w * wpc;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int o = u * SPAN + o0;
-        word[j][u] = (o < p.len) ? row[(p.tile0 + o) >> 5] : 0u;
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < GROUP; ++j) {
-      if (w0 + j < W) {
-        const float s = scales_in[w0 + j];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const unsigned int nib = word[j][u] >> sh;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) acc[u][k] = acc[u][k] + (((nib >> k) & 1u) ? s : -s);
-        }
-      }
-    }
-  }
-  double sq = 0.0;
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      const v4f e = ld4(err_s + p.tile0 + o);
-      v4f z;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        z[k] = acc[u][k] * invW + e[k];
-        sq += (double)z[k] * (double)z[k];
-      }
-      st4(err_s + p.tile0 + o, z);
-    }
-  }
-  const double s = block_sum(sq, lds);
-  if (threadIdx.x == 0) partials[blockIdx.x] = s;
-}
-
-// ---------------------------------------------------------------------------------------------
-// K5  per layer: reconstructed gradient, fresh variance, max(v_frozen/v_fresh)
-//     (Algorithm 1 lines 13, 15-17)
-// ---------------------------------------------------------------------------------------------
-template <int U, bool HAS_K>
-__global__ __launch_bounds__(BLOCK) void k_ratios_pass(
-    const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
-    const float* __restrict__ m, float* __restrict__ v_fresh, const float* __restrict__ v_frozen,
-    float* __restrict__ seg_max, int64_t n_c, int tpc, float beta1, float omb1, float beta2, float omb2,
-    const float* __restrict__ mom_scale, const int64_t* __restrict__ off,
-    const int* __restrict__ first_layer, const int* __restrict__ tile_seg0,
-    const int* __restrict__ seg_layer, int L) {
-  constexpr int TILE = SPAN * U;
-  __shared__ float lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = first_layer[blockIdx.x];
-  if (l0 >= L) return;  // tile lies in the padding (it has no segment)
-  const int o0 = threadIdx.x * 4;
-  const int sh = 4 * (threadIdx.x & 7);
-  const float ss = sscales[p.c];
-  const bool uniform = (p.tile0 + p.len <= off[l0 + 1]);
-  unsigned int NB[U];
-  v4f M[U], VF[U], VZ[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      NB[u] = packed[(p.tile0 + o) >> 5] >> sh;
-      M[u] = ld4(m + p.tile0 + o);
-      VF[u] = ld4(v_fresh + p.tile0 + o);
-      VZ[u] = ld4(v_frozen + p.tile0 + o);
-    }
-  }
-  if (uniform) {
-    const float sp = HAS_K ? ss / mom_scale[l0] : ss;
-    float r = 0.0f;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        v4f vf;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-          const float gr = (mt - beta1 * M[u][k]) / omb1;
-          vf[k] = beta2 * VF[u][k] + omb2 * (gr * gr);
-          const float q = VZ[u][k] / vf[k];
-          if (q > r) r = q;
-        }
-        st4(v_fresh + p.tile0 + o, vf);
-      }
-    }
-    r = block_max(r, lds);
-    if (threadIdx.x == 0) seg_max[tile_seg0[blockIdx.x]] = r;
-  } else {
-    const int64_t N = off[L];
-    // quotient of every element (kept in VZ), then one workgroup max per (tile, layer) segment
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        int l = l0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int64_t i = p.tile0 + o + k;
-          float q = 0.0f;
-          if (i < N) {
-            l = walk_layer(l, i, off);
-            const float sp = HAS_K ? ss / mom_scale[l] : ss;
-            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-            const float gr = (mt - beta1 * M[u][k]) / omb1;
-            const float vf = beta2 * VF[u][k] + omb2 * (gr * gr);
-            v_fresh[i] = vf;
-            q = VZ[u][k] / vf;
-          }
-          VZ[u][k] = q;
-        }
-      }
-    }
-    const int s0 = tile_seg0[blockIdx.x], s1 = tile_seg0[blockIdx.x + 1];
-    for (int s = s0; s < s1; ++s) {
-      const int l = seg_layer[s];
-      const int64_t a = off[l], b = off[l + 1];
-      float r = 0.0f;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int o = u * SPAN + o0;
-        if (o < p.len) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int64_t i = p.tile0 + o + k;
-            if (i >= a && i < b && VZ[u][k] > r) r = VZ[u][k];
-          }
-        }
-      }
-      r = block_max(r, lds);
-      if (threadIdx.x == 0) seg_max[s] = r;
-    }
-  }
-}
-
-// K6  per layer: max over the layer's segments (0 for an empty layer), then Algorithm 1 lines 18-20.
-__global__ __launch_bounds__(BLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
-                                                           const int* __restrict__ layer_seg0,
-                                                           const float* __restrict__ c_avg,
-                                                           float* __restrict__ r_prev,
-                                                           float* __restrict__ coeff_c,
-                                                           float one_m_thr, float one_p_thr,
-                                                           float r_min, float r_max) {
-  __shared__ float lds[BLOCK / WAVE];
-  const int l = blockIdx.x;
-  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
-  float r = 0.0f;
-  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
-    const float q = seg_max[s];
-    if (q > r) r = q;
-  }
-  r = block_max(r, lds);
-  if (threadIdx.x == 0) {
-    const float rp = r_prev[l];
-    const float lo = one_m_thr * rp, hi = one_p_thr * rp;
-    r = (r > lo) ? r : lo;
-    r = (r < hi) ? r : hi;
-    r = (r > r_min) ? r : r_min;
-    r = (r < r_max) ? r : r_max;
-    r_prev[l] = r;
-    coeff_c[l] = r * c_avg[l];
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// K7  x <- x - (lr*c_l) * m_t/(sqrt(v_frozen)+eta);  m <- m_t   (Algorithm 1 lines 13, 21)
-// ---------------------------------------------------------------------------------------------
-template <int U, bool HAS_K>
-__global__ __launch_bounds__(BLOCK) void k_decompress_apply(
-    const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
-    const float* __restrict__ v_frozen, float* __restrict__ x, float* __restrict__ m,
-    const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta,
-    const float* __restrict__ mom_scale, const int64_t* __restrict__ off,
-    const int* __restrict__ first_layer, int L) {
-  constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = first_layer[blockIdx.x];
-  if (l0 >= L) return;
-  const int o0 = threadIdx.x * 4;
-  const int sh = 4 * (threadIdx.x & 7);
-  const float ss = sscales[p.c];
-  const bool uniform = (p.tile0 + p.len <= off[l0 + 1]);
-  unsigned int NB[U];
-  v4f X[U], VZ[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      NB[u] = packed[(p.tile0 + o) >> 5] >> sh;
-      VZ[u] = ld4(v_frozen + p.tile0 + o);
-      X[u] = ld4(x + p.tile0 + o);
-    }
-  }
-  if (uniform) {
-    const float sp = HAS_K ? ss / mom_scale[l0] : ss;
-    const float a = lr * coeff_c[l0];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        v4f xn, mn;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-          const float uu = mt / (sqrtf(VZ[u][k]) + eta);
-          xn[k] = X[u][k] - a * uu;
-          mn[k] = mt;
-        }
-        st4(x + p.tile0 + o, xn);
-        st4(m + p.tile0 + o, mn);
-      }
-    }
-  } else {
-    const int64_t N = off[L];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        int l = l0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int64_t i = p.tile0 + o + k;
-          if (i < N) {
-            l = walk_layer(l, i, off);
-            const float sp = HAS_K ? ss / mom_scale[l] : ss;
-            const float a = lr * coeff_c[l];
-            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-            const float uu = mt / (sqrtf(VZ[u][k]) + eta);
-            x[i] = X[u][k] - a * uu;
-            m[i] = mt;
-          }
-        }
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// K8  LAMB warmup step, eq. (1)
-//   a: m, v update; per (tile, layer) segment the fp64 sums of x^2 and u^2
-//   b: per layer: c = clip(||x||/||u||), c_avg moving average (Algorithm 1 line 2)
-//   c: x <- x - (lr*c) u, with u recomputed from the stored m, v (same operations, same value)
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float lamb_u(float mn, float vn, float x, float eta, float wd) {
-  float u = mn / (sqrtf(vn) + eta);
-  if (wd != 0.0f) u = u + wd * x;
-  return u;
-}
-
-template <int U>
-__global__ __launch_bounds__(BLOCK) void k_warmup_moments(
-    const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,
-    const float* __restrict__ x, double* __restrict__ seg_sums /* [2*n_segs] */, int64_t n_c,
-    int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd,
-    const int64_t* __restrict__ off, const int* __restrict__ first_layer,
-    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer, int L) {
-  constexpr int TILE = SPAN * U;
-  __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = first_layer[blockIdx.x];
-  if (l0 >= L) return;
-  const int o0 = threadIdx.x * 4;
-  const bool uniform = (p.tile0 + p.len <= off[l0 + 1]);
-  v4f G[U], M[U], V[U], X[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      G[u] = ld4(g + p.tile0 + o);
-      M[u] = ld4(m + p.tile0 + o);
-      V[u] = ld4(v + p.tile0 + o);
-      X[u] = ld4(x + p.tile0 + o);
-    }
-  }
-  // new moments (kept in M, V)
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      M[u][k] = beta1 * M[u][k] + omb1 * G[u][k];
-      V[u][k] = beta2 * V[u][k] + omb2 * (G[u][k] * G[u][k]);
-    }
-  }
-  const int s0 = tile_seg0[blockIdx.x];
-  if (uniform) {
-    double sx = 0.0, su = 0.0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        st4(m + p.tile0 + o, M[u]);
-        st4(v + p.tile0 + o, V[u]);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float uu = lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
-          sx += (double)X[u][k] * (double)X[u][k];
-          su += (double)uu * (double)uu;
-        }
-      }
-    }
-    sx = block_sum(sx, lds);
-    su = block_sum(su, lds);
-    if (threadIdx.x == 0) {
-      seg_sums[2 * (int64_t)s0] = sx;
-      seg_sums[2 * (int64_t)s0 + 1] = su;
-    }
-  } else {
-    const int64_t N = off[L];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int64_t i = p.tile0 + o + k;
-          if (i < N) {
-            m[i] = M[u][k];
-            v[i] = V[u][k];
-          }
-        }
-      }
-    }
-    const int s1 = tile_seg0[blockIdx.x + 1];
-    for (int s = s0; s < s1; ++s) {
-      const int l = seg_layer[s];
-      const int64_t a = off[l], b = off[l + 1];
-      double sx = 0.0, su = 0.0;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int o = u * SPAN + o0;
-        if (o < p.len) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int64_t i = p.tile0 + o + k;
-            if (i >= a && i < b) {
-              const float uu = lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
-              sx += (double)X[u][k] * (double)X[u][k];
-              su += (double)uu * (double)uu;
-            }
-          }
-        }
-      }
-      sx = block_sum(sx, lds);
-      su = block_sum(su, lds);
-      if (threadIdx.x == 0) {
-        seg_sums[2 * (int64_t)s] = sx;
-        seg_sums[2 * (int64_t)s + 1] = su;
-      }
-    }
-  }
-}
-
-__global__ __launch_bounds__(BLOCK) void k_warmup_coeff(const double* __restrict__ seg_sums,
-                                                        const int* __restrict__ layer_seg0,
-                                                        float* __restrict__ coeff_c,
-                                                        float* __restrict__ c_avg, float c_min,
-                                                        float c_max, float beta3, float omb3) {
-  __shared__ double lds[BLOCK / WAVE];
-  const int l = blockIdx.x;
-  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
-  double sx = 0.0, su = 0.0;
-  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
-    sx += seg_sums[2 * (int64_t)s];
-    su += seg_sums[2 * (int64_t)s + 1];
-  }
-  sx = block_sum(sx, lds);
-  su = block_sum(su, lds);
-  if (threadIdx.x == 0) {
-    const float nx = (float)sqrt(sx), nu = (float)sqrt(su);
-    float c = nx / nu;
-    c = (c > c_min) ? c : c_min;
-    c = (c < c_max) ? c : c_max;
-    coeff_c[l] = c;
-    c_avg[l] = beta3 * c_avg[l] + omb3 * c;
-  }
-}
-
-template <int U>
-__global__ __launch_bounds__(BLOCK) void k_warmup_apply(
-    const float* __restrict__ m, const float* __restrict__ v, float* __restrict__ x,
-    const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, float wd,
-    const int64_t* __restrict__ off, const int* __restrict__ first_layer, int L) {
-  constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = first_layer[blockIdx.x];
-  if (l0 >= L) return;
-  const int o0 = threadIdx.x * 4;
-  const bool uniform = (p.tile0 + p.len <= off[l0 + 1]);
-  v4f M[U], V[U], X[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    if (o < p.len) {
-      M[u] = ld4(m + p.tile0 + o);
-      V[u] = ld4(v + p.tile0 + o);
-      X[u] = ld4(x + p.tile0 + o);
-    }
-  }
-  if (uniform) {
-    const float a = lr * coeff_c[l0];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        v4f xn;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-          xn[k] = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
-        st4(x + p.tile0 + o, xn);
-      }
-    }
-  } else {
-    const int64_t N = off[L];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        int l = l0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int64_t i = p.tile0 + o + k;
-          if (i < N) {
-            l = walk_layer(l, i, off);
-            const float a = lr * coeff_c[l];
-            x[i] = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
-          }
-        }
-      }
-    }
-  }
-}
-
-__global__ __launch_bounds__(BLOCK) void k_fill(float* __restrict__ p, int64_t n, float v) {
-  const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
-  if (i < n) p[i] = v;
-}
-
-// ---------------------------------------------------------------------------------------------
-// host side
-// ---------------------------------------------------------------------------------------------
 enum KernelId {
   KID_MOMENTUM_Z = 0,
   KID_COMPRESS_RESIDENT,
@@ -857,6 +41,7 @@ enum KernelId {
   KID_RATIOS_PASS,
   KID_RATIOS_FINALIZE,
   KID_APPLY,
+  KID_MOMENTUM_DENSE,
   KID_WARMUP_MOMENTS,
   KID_WARMUP_COEFF,
   KID_WARMUP_APPLY,
@@ -867,7 +52,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "momentum_dense", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "fill",             "copy"};
 
 struct ProfRec {
@@ -980,6 +165,47 @@ ob_status check_common(const ob_lamb_ctx* ctx, const ob_lamb_state* st) {
     if ((p) == nullptr) return OB_ERR_NULL; \
     if (misaligned(p)) return OB_ERR_ALIGN; \
   } while (0)
+
+// ---- small helpers for the entry points -------------------------------------------------------
+
+LayerTab layer_tab(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const int* first_layer) {
+  LayerTab lt;
+  lt.mom_scale = st->mom_scale;
+  lt.off = ctx->d_off;
+  lt.first_layer = first_layer;
+  lt.L = (int)ctx->L;
+  return lt;
+}
+
+// Calls f(std::bool_constant<a>, std::bool_constant<b>) so that kernels can take a and b as
+// template arguments.
+template <class F>
+void dispatch2(bool a, bool b, F f) {
+  if (a) {
+    if (b) f(std::true_type{}, std::true_type{});
+    else f(std::true_type{}, std::false_type{});
+  } else {
+    if (b) f(std::false_type{}, std::true_type{});
+    else f(std::false_type{}, std::false_type{});
+  }
+}
+
+// The momentum source of a call: dense st->m if given, else the 1-bit form.
+ob_status momentum_source(const ob_lamb_state* st, bool* packed, PackedMom* pm) {
+  pm->bits = nullptr;
+  pm->scales = nullptr;
+  if (st->m) {
+    if (misaligned(st->m)) return OB_ERR_ALIGN;
+    *packed = false;
+    return OB_OK;
+  }
+  if (!st->m_packed || !st->m_scales) return OB_ERR_NULL;
+  if (misaligned(st->m_packed)) return OB_ERR_ALIGN;
+  *packed = true;
+  pm->bits = st->m_packed;
+  pm->scales = st->m_scales;
+  return OB_OK;
+}
 
 }  // namespace
 
@@ -1104,7 +330,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     // kernel's comment); it is used only when twice that many fit, else the two-pass kernels run.
     int per_cu = 0, cus = 0;
     ok = hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                         &per_cu, k_compress_resident<U_RES, G_RES, true>, BLOCK, 0),
+                         &per_cu, k_compress_resident<U_RES, G_RES, true, false>, BLOCK, 0),
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
@@ -1157,15 +383,14 @@ ob_status ob_lamb_warmup_step(ob_lamb_ctx* ctx, const ob_lamb_state* st, const f
   if (!st->c_avg || !st->coeff_c) return OB_ERR_NULL;
   if (!std::isfinite(lr)) return OB_ERR_ARG;
   Launch la(ctx, hip_stream);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
   OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN>), ctx->n_tiles, grad, st->m, st->v_fresh,
             st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2,
-            ctx->eta, ctx->wd, ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer,
-            (int)ctx->L);
+            ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
   OB_LAUNCH(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, ctx->d_seg_sums, ctx->d_layer_seg0,
             st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3);
   OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN>), ctx->n_tiles, st->m, st->v_fresh, st->x,
-            st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, ctx->d_off, ctx->d_first_layer,
-            (int)ctx->L);
+            st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -1186,31 +411,37 @@ ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_st
 ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad,
                                  uint32_t* packed_out, float* scales_out, void* hip_stream) {
   if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(grad); REQUIRE_PTR(st->m); REQUIRE_PTR(st->err_worker); REQUIRE_PTR(packed_out);
+  REQUIRE_PTR(grad); REQUIRE_PTR(st->err_worker); REQUIRE_PTR(packed_out);
   if (!scales_out) return OB_ERR_NULL;
+  bool packed_m = false;
+  PackedMom pm;
+  if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
+  if (packed_m && st->m_packed == packed_out) return OB_ERR_ARG;  // would be overwritten while read
   Launch la(ctx, hip_stream);
   if (ctx->resident) {
     ctx->epoch += 1;
-    if (st->mom_scale)
-      OB_LAUNCH(la, KID_COMPRESS_RESIDENT, (k_compress_resident<U_RES, G_RES, true>), ctx->n_tiles_res, grad,
-                st->m, st->err_worker, packed_out, scales_out, ctx->d_partials_res, ctx->d_counter,
-                ctx->d_flag, ctx->d_errflag, ctx->n_c, ctx->tpc_res, ctx->beta1, ctx->omb1, st->mom_scale,
-                ctx->d_off, ctx->d_first_layer_res, (int)ctx->L, ctx->epoch, ctx->spin_limit);
-    else
-      OB_LAUNCH(la, KID_COMPRESS_RESIDENT, (k_compress_resident<U_RES, G_RES, false>), ctx->n_tiles_res, grad,
-                st->m, st->err_worker, packed_out, scales_out, ctx->d_partials_res, ctx->d_counter,
-                ctx->d_flag, ctx->d_errflag, ctx->n_c, ctx->tpc_res, ctx->beta1, ctx->omb1, st->mom_scale,
-                ctx->d_off, ctx->d_first_layer_res, (int)ctx->L, ctx->epoch, ctx->spin_limit);
+    ChunkSync cs;
+    cs.partials = ctx->d_partials_res;
+    cs.counter = ctx->d_counter;
+    cs.flag = ctx->d_flag;
+    cs.errflag = ctx->d_errflag;
+    cs.epoch = ctx->epoch;
+    cs.spin_limit = ctx->spin_limit;
+    const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_res);
+    dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
+      OB_LAUNCH(la, KID_COMPRESS_RESIDENT,
+                (k_compress_resident<U_RES, G_RES, decltype(hk)::value, decltype(pk)::value>),
+                ctx->n_tiles_res, grad, st->m, pm, st->err_worker, packed_out, scales_out, cs, ctx->n_c,
+                ctx->tpc_res, ctx->beta1, ctx->omb1, lt);
+    });
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
-  if (st->mom_scale)
-    OB_LAUNCH(la, KID_MOMENTUM_Z, (k_momentum_z_sumsq<U_MAIN, true>), ctx->n_tiles, grad, st->m,
-              st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, st->mom_scale,
-              ctx->d_off, ctx->d_first_layer, (int)ctx->L);
-  else
-    OB_LAUNCH(la, KID_MOMENTUM_Z, (k_momentum_z_sumsq<U_MAIN, false>), ctx->n_tiles, grad, st->m,
-              st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, st->mom_scale,
-              ctx->d_off, ctx->d_first_layer, (int)ctx->L);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
+    OB_LAUNCH(la, KID_MOMENTUM_Z, (k_momentum_z_sumsq<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
+              ctx->n_tiles, grad, st->m, pm, st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc,
+              ctx->beta1, ctx->omb1, lt);
+  });
   OB_LAUNCH(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out);
   OB_LAUNCH(la, KID_SIGN_PACK, (k_sign_pack_error<U_MAIN>), ctx->n_tiles, st->err_worker, packed_out,
             scales_out, ctx->n_c, ctx->tpc);
@@ -1235,19 +466,19 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
 ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, void* hip_stream) {
   if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->m); REQUIRE_PTR(st->v_fresh); REQUIRE_PTR(st->v_frozen);
+  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->v_fresh); REQUIRE_PTR(st->v_frozen);
   if (!server_scales || !st->c_avg || !st->r_prev || !st->coeff_c) return OB_ERR_NULL;
+  bool packed_m = false;
+  PackedMom pm;
+  if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
   Launch la(ctx, hip_stream);
-  if (st->mom_scale)
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, true>), ctx->n_tiles, packed_all, server_scales,
-              st->m, st->v_fresh, st->v_frozen, ctx->d_seg_max, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-              ctx->beta2, ctx->omb2, st->mom_scale, ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0,
-              ctx->d_seg_layer, (int)ctx->L);
-  else
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, false>), ctx->n_tiles, packed_all, server_scales,
-              st->m, st->v_fresh, st->v_frozen, ctx->d_seg_max, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-              ctx->beta2, ctx->omb2, st->mom_scale, ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0,
-              ctx->d_seg_layer, (int)ctx->L);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
+              ctx->n_tiles, packed_all, server_scales, st->m, pm, st->v_fresh, st->v_frozen, ctx->d_seg_max,
+              ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2, lt, ctx->d_tile_seg0,
+              ctx->d_seg_layer);
+  });
   OB_LAUNCH(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, ctx->d_seg_max, ctx->d_layer_seg0,
             st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr, ctx->r_min, ctx->r_max);
   return la.ok ? OB_OK : OB_ERR_HIP;
@@ -1256,18 +487,46 @@ ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
 ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                    const float* server_scales, float lr, void* hip_stream) {
   if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->m); REQUIRE_PTR(st->x); REQUIRE_PTR(st->v_frozen);
+  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->x); REQUIRE_PTR(st->v_frozen);
   if (!server_scales || !st->coeff_c) return OB_ERR_NULL;
   if (!std::isfinite(lr)) return OB_ERR_ARG;
+  if (st->m && misaligned(st->m)) return OB_ERR_ALIGN;
+  if (!st->m && !st->m_packed) return OB_ERR_NULL;  // the momentum has to be committed somewhere
+  if (st->m_packed && (!st->m_scales || misaligned(st->m_packed))) return st->m_scales ? OB_ERR_ALIGN : OB_ERR_NULL;
   Launch la(ctx, hip_stream);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch2(st->mom_scale != nullptr, st->m != nullptr, [&](auto hk, auto wm) {
+    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_MAIN, decltype(hk)::value, decltype(wm)::value>),
+              ctx->n_tiles, packed_all, server_scales, st->v_frozen, st->x, st->m, st->coeff_c, ctx->n_c,
+              ctx->tpc, lr, ctx->eta, lt);
+  });
+  if (st->m_packed && st->m_packed != packed_all) {  // commit the 1-bit form unless it already is in place
+    la.begin(KID_COPY);
+    if (la.ok)
+      la.ok = hip_ok(ctx, hipMemcpyAsync(st->m_packed, packed_all, (size_t)ctx->n_pad / 8,
+                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync") &&
+              hip_ok(ctx, hipMemcpyAsync(st->m_scales, server_scales, (size_t)ctx->W * sizeof(float),
+                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
+    la.end("copy");
+  }
+  return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* m_out, void* hip_stream) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(m_out); REQUIRE_PTR(st->m_packed);
+  if (!st->m_scales) return OB_ERR_NULL;
+  PackedMom pm;
+  pm.bits = st->m_packed;
+  pm.scales = st->m_scales;
+  Launch la(ctx, hip_stream);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
   if (st->mom_scale)
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_MAIN, true>), ctx->n_tiles, packed_all, server_scales,
-              st->v_frozen, st->x, st->m, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, st->mom_scale,
-              ctx->d_off, ctx->d_first_layer, (int)ctx->L);
+    OB_LAUNCH(la, KID_MOMENTUM_DENSE, (k_momentum_dense<U_MAIN, true>), ctx->n_tiles, pm, m_out, ctx->n_c,
+              ctx->tpc, lt);
   else
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_MAIN, false>), ctx->n_tiles, packed_all, server_scales,
-              st->v_frozen, st->x, st->m, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, st->mom_scale,
-              ctx->d_off, ctx->d_first_layer, (int)ctx->L);
+    OB_LAUNCH(la, KID_MOMENTUM_DENSE, (k_momentum_dense<U_MAIN, false>), ctx->n_tiles, pm, m_out, ctx->n_c,
+              ctx->tpc, lt);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 

@@ -11,6 +11,11 @@ One compression-stage step on one rank (Algorithm 1 lines 6-21):
     [scatter]                 stands in for the all-gather: the W recompressed chunks are resident
                               tensors; this rank's own output is written into its slot
     layer_ratios, decompress_apply
+
+With packed_momentum=True the momentum is kept in the 1-bit form it has after line 13: the step's
+packed_all/server_scales buffers ARE the momentum of the next step, so two such buffer pairs
+alternate (begin_step() switches to the pair that does not hold the momentum) and the dense array
+is only read by the first step after warmup.
 """
 import numpy as np
 import torch
@@ -22,7 +27,7 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
-                 **hyper):
+                 packed_momentum=False, **hyper):
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.W = int(num_workers)
@@ -45,17 +50,38 @@ class DeviceStep:
         self.scales_local = torch.zeros(self.W, **f32)
         self.packed_in = torch.zeros(self.W * (self.n_c // 32), **i32)  # what the served chunk receives
         self.scales_in = torch.zeros(self.W, **f32)
-        self.packed_all = torch.zeros(self.n_pad // 32, **i32)        # the W recompressed chunks
-        self.server_scales = torch.zeros(self.W, **f32)
-        self._refresh_state()
+        # the W recompressed chunks (two pairs when they double as the momentum)
+        self.packed_momentum = bool(packed_momentum)
+        npairs = 2 if self.packed_momentum else 1
+        self._pa = [torch.zeros(self.n_pad // 32, **i32) for _ in range(npairs)]
+        self._ss = [torch.zeros(self.W, **f32) for _ in range(npairs)]
+        self._cur = 0
+        self.m_is_packed = False   # True once a step has committed the momentum in 1-bit form
+
+    # the buffer pair of the current step
+    @property
+    def packed_all(self):
+        return self._pa[self._cur]
+
+    @property
+    def server_scales(self):
+        return self._ss[self._cur]
 
     def _dev(self, a):
         if isinstance(a, np.ndarray):
             a = torch.from_numpy(np.ascontiguousarray(a))
         return a.to(self.device).contiguous()
 
-    def _refresh_state(self):
-        self.state = ob.make_state(**self.t)
+    def _state(self, momentum):
+        """ob_lamb_state for one call.  momentum: 'read' (source of m_{t-1}) or 'commit'."""
+        b = dict(self.t)
+        if self.packed_momentum and momentum == "commit":
+            b["m"] = None                       # committed in place: packed_all is the momentum
+            b["m_packed"], b["m_scales"] = self.packed_all, self.server_scales
+        elif self.packed_momentum and self.m_is_packed:
+            b["m"] = None
+            b["m_packed"], b["m_scales"] = self._pa[1 - self._cur], self._ss[1 - self._cur]
+        return ob.make_state(**b)
 
     def close(self):
         if self.ctx is not None:
@@ -71,13 +97,18 @@ class DeviceStep:
 
     # ---- state upload / download (plumbing) --------------------------------------------------
     def load_state(self, st):
-        """st: dict of numpy arrays or torch tensors keyed like ob_lamb_state."""
+        """st: dict of numpy arrays or torch tensors keyed like ob_lamb_state (dense momentum)."""
         for k in _STATE_KEYS:
             if k in st and st[k] is not None:
                 self.t[k].copy_(self._dev(st[k]))
-        self._refresh_state()
+        if "m" in st and st["m"] is not None:
+            self.m_is_packed = False
 
     def get(self, k):
+        if k == "m" and self.m_is_packed:
+            # dense view of the 1-bit momentum (held by the pair of the step that committed it)
+            s = ob.make_state(**dict(self.t, m_packed=self.packed_all, m_scales=self.server_scales))
+            ob.ob_lamb_momentum_dense(self.ctx, s, self.t["m"], self.stream)
         return self.t[k].detach().cpu().numpy()
 
     @property
@@ -86,14 +117,19 @@ class DeviceStep:
 
     # ---- the calls ---------------------------------------------------------------------------
     def warmup_step(self, grad, lr):
-        ob.ob_lamb_warmup_step(self.ctx, self.state, grad, lr, self.stream)
+        ob.ob_lamb_warmup_step(self.ctx, self._state("read"), grad, lr, self.stream)
 
     def freeze(self):
-        ob.ob_lamb_freeze(self.ctx, self.state, self.stream)
+        ob.ob_lamb_freeze(self.ctx, self._state("read"), self.stream)
+
+    def begin_step(self):
+        """Select the wire buffers of the coming step: the pair that does not hold the momentum."""
+        if self.packed_momentum and self.m_is_packed:
+            self._cur = 1 - self._cur
 
     def compress_local(self, grad):
-        ob.ob_lamb_compress_local(self.ctx, self.state, grad, self.packed_local, self.scales_local,
-                                  self.stream)
+        ob.ob_lamb_compress_local(self.ctx, self._state("read"), grad, self.packed_local,
+                                  self.scales_local, self.stream)
 
     def gather(self):
         """Own chunk c of the worker output -> slot c of the server's input (device copies)."""
@@ -105,18 +141,23 @@ class DeviceStep:
     def server_reduce(self):
         """Writes the recompressed chunk straight into slot c of packed_all / server_scales."""
         wpc = self.n_c // 32
-        ob.ob_lamb_server_reduce(self.ctx, self.state, self.packed_in, self.scales_in,
+        ob.ob_lamb_server_reduce(self.ctx, self._state("read"), self.packed_in, self.scales_in,
                                  self.packed_all[self.c * wpc:], self.server_scales[self.c:],
                                  self.stream)
 
     def layer_ratios(self):
-        ob.ob_lamb_layer_ratios(self.ctx, self.state, self.packed_all, self.server_scales, self.stream)
+        ob.ob_lamb_layer_ratios(self.ctx, self._state("read"), self.packed_all, self.server_scales,
+                                self.stream)
 
     def decompress_apply(self, lr):
-        ob.ob_lamb_decompress_apply(self.ctx, self.state, self.packed_all, self.server_scales, lr,
-                                    self.stream)
+        ob.ob_lamb_decompress_apply(self.ctx, self._state("commit"), self.packed_all,
+                                    self.server_scales, lr, self.stream)
+        if self.packed_momentum:
+            self.m_is_packed = True
 
     def step(self, grad, lr):
+        """One compression-stage step into the current wire buffers (call begin_step() first and
+        fill packed_in / packed_all with what the other ranks sent)."""
         self.compress_local(grad)
         self.gather()
         self.server_reduce()

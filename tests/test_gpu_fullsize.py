@@ -19,15 +19,15 @@ from workloads.gen import layer_kappa  # noqa: E402
 pytestmark = pytest.mark.gpu
 
 
-def device_setup(cfg, server_chunk, seed=0, two_pass=False):
+def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False):
     st = Streams(seed, device="cuda:0")
     pl = cfg["plist"]
     import paper_2104_06069_amd as ob
     if two_pass:
-        dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, two_pass=True, **HYPER)
+        dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, two_pass=True, packed_momentum=packed, **HYPER)
     else:  # whatever the library selects for this size on this device
         from paper_2104_06069_amd.step import DeviceStep as D
-        dev = D(pl.offsets, cfg["W"], server_chunk, **HYPER)
+        dev = D(pl.offsets, cfg["W"], server_chunk, packed_momentum=packed, **HYPER)
     print(f"{cfg['name']}: single-pass worker compression = {ob.ob_lamb_uses_single_pass(dev.ctx)}", flush=True)
     s = init_state(st, cfg)
     # non-trivial momentum and errors, as after many steps
@@ -44,32 +44,41 @@ def device_setup(cfg, server_chunk, seed=0, two_pass=False):
     return st, dev, g
 
 
-@pytest.mark.parametrize("name,two_pass", [("bert_large", False), ("bert_large_w256", False),
-                                           ("bert_large", True)])
-def test_bert_large_whole_step(name, two_pass):
+@pytest.mark.parametrize("name,two_pass,packed", [("bert_large", False, False), ("bert_large_w256", False, False),
+                                                  ("bert_large", True, False), ("bert_large", False, True)])
+def test_bert_large_whole_step(name, two_pass, packed):
+    """Whole steps against the whole oracle; with the 1-bit momentum two steps, so that the second
+    one reads the momentum from the first one's packed output."""
     _need_gpu()
     cfg = make_config(name)
     c = cfg["W"] // 2
-    st, dev, g = device_setup(cfg, c, two_pass=two_pass)
+    st, dev, g = device_setup(cfg, c, two_pass=two_pass, packed=packed)
     ref = RefStep(cfg["plist"].offsets, cfg["W"], c)
     ref.load_state({k: dev.get(k) for k in ref.t})
-    ref.set_foreign_in(dev.packed_in.cpu().numpy(), dev.scales_in.cpu().numpy())
-    ref.set_foreign_all(dev.packed_all.cpu().numpy(), dev.server_scales.cpu().numpy())
-    gh = g.cpu().numpy()
     lr = 2e-3
-    t0 = time.time()
-    ref.step(gh, lr)
-    print(f"{name}: oracle step {time.time() - t0:.1f} s", flush=True)
-    dev.step(g, lr)
-    torch.cuda.synchronize()
-    assert np.array_equal(words_of(dev.packed_local), ref.bits_local), "worker sign words"
-    assert_close(dev.scales_local.cpu().numpy(), ref.scales_local, "worker scales")
-    assert np.array_equal(words_of(dev.packed_all), ref.bits_all), "server sign words"
-    assert_close(dev.server_scales.cpu().numpy(), ref.server_scales, "server scales")
-    nd = {}
-    for k in ("err_worker", "err_server", "v_fresh", "r_prev", "coeff_c", "x", "m"):
-        nd[k] = assert_close(dev.get(k), ref.t[k], k)
-    print(f"{name}: elements not bit-equal (within 1e-6): {nd}", flush=True)
+    for t in range(2 if packed else 1):
+        if t > 0:
+            dev.begin_step()
+            g = gradient(st, cfg, t)
+            fa, fss = foreign_server_chunks(st, cfg, t)
+            dev.packed_all.copy_(fa); dev.server_scales.copy_(torch.from_numpy(fss))
+            torch.cuda.synchronize()
+        ref.set_foreign_in(dev.packed_in.cpu().numpy(), dev.scales_in.cpu().numpy())
+        ref.set_foreign_all(dev.packed_all.cpu().numpy(), dev.server_scales.cpu().numpy())
+        gh = g.cpu().numpy()
+        t0 = time.time()
+        ref.step(gh, lr)
+        print(f"{name}: oracle step {time.time() - t0:.1f} s", flush=True)
+        dev.step(g, lr)
+        torch.cuda.synchronize()
+        assert np.array_equal(words_of(dev.packed_local), ref.bits_local), "worker sign words"
+        assert_close(dev.scales_local.cpu().numpy(), ref.scales_local, "worker scales")
+        assert np.array_equal(words_of(dev.packed_all), ref.bits_all), "server sign words"
+        assert_close(dev.server_scales.cpu().numpy(), ref.server_scales, "server scales")
+        nd = {}
+        for k in ("err_worker", "err_server", "v_fresh", "r_prev", "coeff_c", "x", "m"):
+            nd[k] = assert_close(dev.get(k), ref.t[k], k)
+        print(f"{name}: step {t}: elements not bit-equal (within 1e-6): {nd}", flush=True)
     finish(dev)
 
 

@@ -92,7 +92,7 @@ def make_case(name):
                 steps=3, server_chunk=W - 1, use_k=(name != "w1"))
 
 
-def start_pair(cfg, seed=0, warm_state=True, two_pass=False):
+def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -100,7 +100,7 @@ def start_pair(cfg, seed=0, warm_state=True, two_pass=False):
     if cfg.get("use_k"):
         k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0)
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k)
-    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, **HYPER)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, **HYPER)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -184,8 +184,8 @@ def test_phasewise_single_step(case, two_pass):
     finish(dev)
 
 
-def run_trajectory(cfg, steps, seed=0, two_pass=False):
-    st, ref, dev = start_pair(cfg, seed=seed, warm_state=False, two_pass=two_pass)
+def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False):
+    st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed)
     stats = dict(word_mismatch_steps=0, scale_ulp_steps=0)
     for t in range(steps):
         g = gradient(st, cfg, t)
@@ -193,6 +193,7 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False):
         fw, fs = foreign_worker_chunks(st, cfg, t)
         fa, fss = foreign_server_chunks(st, cfg, t)
         ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        dev.begin_step()
         dev.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
         dev.scales_in.copy_(torch.from_numpy(fs))
         dev.packed_all.copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
@@ -208,16 +209,25 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False):
         # a sign may differ only after a scale differed in its last bit at an earlier step
         if stats["scale_ulp_steps"] == 0:
             assert same_words, f"step {t}: sign words differ although all scales were bit-equal"
+            if t % 10 == 0 or t == steps - 1:
+                for k in ("x", "v_fresh", "err_worker", "r_prev"):
+                    assert np.array_equal(dev.get(k), ref.t[k]), (t, k)
+    assert dev.m_is_packed == packed
     return ref, dev, stats
 
 
-@pytest.mark.parametrize("case,steps,two_pass", [("tiny", 10, False), ("bert_mini", 100, False),
-                                                 ("odd", 30, False), ("bert_mini", 30, True)])
-def test_trajectory(case, steps, two_pass):
+@pytest.mark.parametrize("case,steps,two_pass,packed", [
+    ("tiny", 10, False, False), ("bert_mini", 100, False, False), ("odd", 30, False, False),
+    ("bert_mini", 30, True, False),
+    # momentum kept in its 1-bit form from the first step on
+    ("tiny", 10, False, True), ("bert_mini", 100, False, True), ("odd", 30, False, True),
+    ("bert_mini", 30, True, True), ("w1", 10, True, True), ("small", 10, False, True)])
+def test_trajectory(case, steps, two_pass, packed):
     """The device feeds itself for `steps` steps; the oracle does the same on the host."""
     _need_gpu()
     cfg = make_case(case)
-    ref, dev, stats = run_trajectory(cfg, steps, two_pass=two_pass)
+    ref, dev, stats = run_trajectory(cfg, steps, two_pass=two_pass, packed=packed,
+                                     warm_state=(case in ("odd", "w1")))
     x_ref = ref.t["x"][:ref.N].astype(np.float64)
     x_gpu = dev.get("x")[:ref.N].astype(np.float64)
     rel = np.linalg.norm(x_gpu - x_ref) / np.linalg.norm(x_ref)
@@ -334,16 +344,29 @@ def test_argument_errors():
     cfg = make_case("small")
     st, ref, dev = start_pair(cfg)
     g = torch.zeros(cfg["n_pad"], device=dev.device)
+    state = dev._state("read")
+    x0 = dev.get("x").copy()
     with pytest.raises(ob.ObLambError) as e:
-        ob.ob_lamb_compress_local(dev.ctx, dev.state, None, dev.packed_local, dev.scales_local)
+        ob.ob_lamb_compress_local(dev.ctx, state, None, dev.packed_local, dev.scales_local)
     assert e.value.status == -1
     with pytest.raises(ob.ObLambError) as e:   # misaligned gradient pointer
-        ob.ob_lamb_compress_local(dev.ctx, dev.state, g[1:], dev.packed_local, dev.scales_local)
+        ob.ob_lamb_compress_local(dev.ctx, state, g[1:], dev.packed_local, dev.scales_local)
     assert e.value.status == -3
     with pytest.raises(ob.ObLambError) as e:
-        ob.ob_lamb_decompress_apply(dev.ctx, dev.state, dev.packed_all, dev.server_scales, float("nan"))
+        ob.ob_lamb_decompress_apply(dev.ctx, state, dev.packed_all, dev.server_scales, float("nan"))
     assert e.value.status == -2
-    x0 = dev.get("x").copy()
+    # no momentum source at all / 1-bit momentum aliased with the output buffer
+    nom = ob.make_state(**dict(dev.t, m=None))
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_compress_local(dev.ctx, nom, g, dev.packed_local, dev.scales_local)
+    assert e.value.status == -1
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_decompress_apply(dev.ctx, nom, dev.packed_all, dev.server_scales, 1e-3)
+    assert e.value.status == -1
+    alias = ob.make_state(**dict(dev.t, m=None, m_packed=dev.packed_local, m_scales=dev.scales_local))
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_compress_local(dev.ctx, alias, g, dev.packed_local, dev.scales_local)
+    assert e.value.status == -2
     torch.cuda.synchronize()
     assert np.array_equal(dev.get("x"), x0)
     finish(dev)
