@@ -170,7 +170,7 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                    float lr, void* hip_stream);
 
 /* ob_lamb_compress_local runs as ONE kernel that keeps z in registers across a per-chunk arrival
- * barrier whenever the device can hold two chunks' worth of its workgroups (otherwise, or when the
+ * barrier whenever one chunk's workgroups fill at most 80 % of the device (otherwise, or when the
  * environment variable OB_LAMB_TWO_PASS=1 is set at ob_lamb_create, as two passes through memory;
  * the results are bit-identical).  The barrier's waits are bounded; should one ever expire, the
  * step's outputs are undefined and a device-side flag is raised.  ob_lamb_check_device_status

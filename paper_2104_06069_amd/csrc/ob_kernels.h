@@ -36,6 +36,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int BLOCK = 256;       // threads per workgroup (4 wavefronts of 64)
 constexpr int WAVE = 64;
 constexpr int SPAN = BLOCK * 4;  // elements one workgroup-wide 128-bit access covers
+constexpr int FBLOCK = 1024;     // threads per workgroup of the small per-layer / per-chunk finalize kernels
 #define OB_AGENT __HIP_MEMORY_SCOPE_AGENT
 
 // Every N-sized array is read once and written once per kernel: 128-bit nontemporal (streaming)
@@ -47,8 +48,10 @@ __device__ __forceinline__ void st4(float* p, v4f v) {
   __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
 }
 
-// Sum of one double per thread over the workgroup, in a fixed order; result valid in thread 0.
-__device__ __forceinline__ double block_sum(double v, double* lds /* [BLOCK/WAVE] */) {
+// Sum of one double per thread over a workgroup of NT threads, in a fixed order; result valid in
+// thread 0.  lds: [NT / WAVE] doubles.
+template <int NT = BLOCK>
+__device__ __forceinline__ double block_sum(double v, double* lds) {
 #pragma unroll
   for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
   const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
@@ -58,13 +61,15 @@ __device__ __forceinline__ double block_sum(double v, double* lds /* [BLOCK/WAVE
   double r = 0.0;
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int i = 0; i < BLOCK / WAVE; ++i) r += lds[i];
+    for (int i = 0; i < NT / WAVE; ++i) r += lds[i];
   }
   return r;
 }
 
-// Max of one non-NaN, non-negative float per thread over the workgroup; valid in thread 0.
-__device__ __forceinline__ float block_max(float v, float* lds /* [BLOCK/WAVE] */) {
+// Max of one non-NaN, non-negative float per thread over a workgroup of NT threads; valid in
+// thread 0.  lds: [NT / WAVE] floats.
+template <int NT = BLOCK>
+__device__ __forceinline__ float block_max(float v, float* lds) {
 #pragma unroll
   for (int o = WAVE / 2; o > 0; o >>= 1) {
     const float w = __shfl_down(v, o, WAVE);
@@ -77,7 +82,7 @@ __device__ __forceinline__ float block_max(float v, float* lds /* [BLOCK/WAVE] *
   float r = 0.0f;
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int i = 0; i < BLOCK / WAVE; ++i) r = (lds[i] > r) ? lds[i] : r;
+    for (int i = 0; i < NT / WAVE; ++i) r = (lds[i] > r) ? lds[i] : r;
   }
   return r;
 }
@@ -142,24 +147,33 @@ struct PackedMom {
 // ---------------------------------------------------------------------------------------------
 template <bool HAS_K, bool PACKED_M>
 struct ZTile {
-  bool uniform, pad;
-  int l0;
+  bool uniform;  // one set of constants serves the whole tile
+  bool pad;      // the whole tile lies in the padding
+  int l0;        // layer of the tile's first element (HAS_K)
   float kt;      // k of the tile's layer (uniform tiles)
-  float bm;      // beta1 * |m| of the tile (uniform tiles, PACKED_M)
+  float bm;      // beta1 * |m| (PACKED_M; for HAS_K only on uniform tiles)
   float s_prev;  // previous server scale of the chunk (PACKED_M)
+  int64_t N;
 
   __device__ __forceinline__ void init(const LayerTab& lt, const PackedMom& pm, const TilePos& p,
                                        float beta1) {
-    uniform = true; pad = false; l0 = 0; kt = 1.0f; bm = 0.0f; s_prev = 0.0f;
+    uniform = true; pad = false; l0 = 0; kt = 1.0f; bm = 0.0f; s_prev = 0.0f; N = 0;
     if (PACKED_M) s_prev = pm.scales[p.c];
-    if (HAS_K || PACKED_M) {
+    if (HAS_K) {
+      // k differs from layer to layer: the tile must lie inside one layer (or in the padding)
       l0 = lt.first_layer[blockIdx.x];
       uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
       pad = (l0 >= lt.L);
       if (uniform && !pad) {
-        if (HAS_K) kt = lt.mom_scale[l0];
-        if (PACKED_M) bm = beta1 * (HAS_K ? s_prev / kt : s_prev);
+        kt = lt.mom_scale[l0];
+        if (PACKED_M) bm = beta1 * (s_prev / kt);
       }
+    } else if (PACKED_M) {
+      // only the end of the parameters matters: the 1-bit momentum is 0 in the padding
+      N = lt.off[lt.L];
+      pad = (p.tile0 >= N);
+      uniform = pad || (p.tile0 + p.len <= N);
+      bm = beta1 * s_prev;
     }
   }
 
@@ -177,22 +191,30 @@ struct ZTile {
         const float mloc = bmk + omb1 * G[k];
         r[k] = HAS_K ? kt * mloc + E[k] : mloc + E[k];
       }
-    } else {
-      int l = l0;
+    } else if (HAS_K) {
+      int l = l0, lc = -1;
+      float kk = 1.0f, b = 0.0f;
+      bool real = false;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         l = walk_layer(l, i0 + k, lt.off);
-        const bool real = (l < lt.L);
-        const float kk = (HAS_K && real) ? lt.mom_scale[l] : 1.0f;
-        float bmk;
-        if (PACKED_M) {
-          const float b = beta1 * (HAS_K ? s_prev / kk : s_prev);
-          bmk = real ? (((nib >> k) & 1u) ? b : -b) : 0.0f;
-        } else {
-          bmk = beta1 * M[k];
+        if (l != lc) {  // constants of a layer are formed once per run of its elements
+          lc = l;
+          real = (l < lt.L);
+          kk = real ? lt.mom_scale[l] : 1.0f;
+          if (PACKED_M) b = beta1 * (s_prev / kk);
         }
+        float bmk;
+        if (PACKED_M) bmk = real ? (((nib >> k) & 1u) ? b : -b) : 0.0f;
+        else bmk = beta1 * M[k];
         const float mloc = bmk + omb1 * G[k];
-        r[k] = HAS_K ? kk * mloc + E[k] : mloc + E[k];
+        r[k] = kk * mloc + E[k];
+      }
+    } else {  // PACKED_M without k: the tile straddles the end of the parameters
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float bmk = (i0 + k < N) ? (((nib >> k) & 1u) ? bm : -bm) : 0.0f;
+        r[k] = (bmk + omb1 * G[k]) + E[k];
       }
     }
     return r;
@@ -242,13 +264,13 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
 }
 
 // scale[c] = sqrt(sum of the chunk's tile partials / n_c), summed in a fixed order.
-__global__ __launch_bounds__(BLOCK) void k_chunk_scale(const double* __restrict__ partials, int tpc,
-                                                       int64_t n_c, float* __restrict__ scales) {
-  __shared__ double lds[BLOCK / WAVE];
+__global__ __launch_bounds__(FBLOCK) void k_chunk_scale(const double* __restrict__ partials, int tpc,
+                                                        int64_t n_c, float* __restrict__ scales) {
+  __shared__ double lds[FBLOCK / WAVE];
   const int c = blockIdx.x;
   double a = 0.0;
-  for (int j = threadIdx.x; j < tpc; j += BLOCK) a += partials[(int64_t)c * tpc + j];
-  const double S = block_sum(a, lds);
+  for (int j = threadIdx.x; j < tpc; j += FBLOCK) a += partials[(int64_t)c * tpc + j];
+  const double S = block_sum<FBLOCK>(a, lds);
   if (threadIdx.x == 0) scales[c] = (float)sqrt(S / (double)n_c);
 }
 
@@ -303,8 +325,9 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
 //
 // Progress: workgroups are dispatched in index order and a chunk's tiles are consecutive indices,
 // so the oldest unfinished chunk always has all of its tiles resident or dispatchable provided the
-// device can hold one chunk's workgroups at once; the host selects these kernels only when twice
-// that many fit.  Every wait is bounded by spin_limit polls: on expiry the workgroup raises
+// device can hold one chunk's workgroups at once; the host selects these kernels only when a
+// chunk's workgroups take at most 80 % of the device's slots.
+// Every wait is bounded by spin_limit polls: on expiry the workgroup raises
 // *errflag, uses whatever it last read and goes on to exit, and all later waits end at once.
 //
 // Synchronisation uses relaxed agent-scope atomics whose payload travels in the atomic itself
@@ -372,8 +395,8 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int c,
 // the error from registers.  z never goes to memory.  Loads are issued G accesses at a time to
 // bound the staging registers.
 // ---------------------------------------------------------------------------------------------
-template <int U, int G, bool HAS_K, bool PACKED_M>
-__global__ __launch_bounds__(BLOCK, 4) void k_compress_resident(
+template <int U, int G, bool HAS_K, bool PACKED_M, int MINW = 4>
+__global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
     const float* __restrict__ g, const float* __restrict__ m, PackedMom pm,
     float* __restrict__ err, uint32_t* __restrict__ packed, float* __restrict__ scales,
     ChunkSync cs, int64_t n_c, int tpc, float beta1, float omb1, LayerTab lt) {
@@ -624,22 +647,22 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
 }
 
 // K6  per layer: max over the layer's segments (0 for an empty layer), then Algorithm 1 lines 18-20.
-__global__ __launch_bounds__(BLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
-                                                           const int* __restrict__ layer_seg0,
-                                                           const float* __restrict__ c_avg,
-                                                           float* __restrict__ r_prev,
-                                                           float* __restrict__ coeff_c,
-                                                           float one_m_thr, float one_p_thr,
-                                                           float r_min, float r_max) {
-  __shared__ float lds[BLOCK / WAVE];
+__global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
+                                                            const int* __restrict__ layer_seg0,
+                                                            const float* __restrict__ c_avg,
+                                                            float* __restrict__ r_prev,
+                                                            float* __restrict__ coeff_c,
+                                                            float one_m_thr, float one_p_thr,
+                                                            float r_min, float r_max) {
+  __shared__ float lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   float r = 0.0f;
-  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
+  for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
     const float q = seg_max[s];
     if (q > r) r = q;
   }
-  r = block_max(r, lds);
+  r = block_max<FBLOCK>(r, lds);
   if (threadIdx.x == 0) {
     const float rp = r_prev[l];
     const float lo = one_m_thr * rp, hi = one_p_thr * rp;
@@ -881,21 +904,21 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
   }
 }
 
-__global__ __launch_bounds__(BLOCK) void k_warmup_coeff(const double* __restrict__ seg_sums,
-                                                        const int* __restrict__ layer_seg0,
-                                                        float* __restrict__ coeff_c,
-                                                        float* __restrict__ c_avg, float c_min,
-                                                        float c_max, float beta3, float omb3) {
-  __shared__ double lds[BLOCK / WAVE];
+__global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restrict__ seg_sums,
+                                                         const int* __restrict__ layer_seg0,
+                                                         float* __restrict__ coeff_c,
+                                                         float* __restrict__ c_avg, float c_min,
+                                                         float c_max, float beta3, float omb3) {
+  __shared__ double lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   double sx = 0.0, su = 0.0;
-  for (int s = s0 + threadIdx.x; s < s1; s += BLOCK) {
+  for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
     sx += seg_sums[2 * (int64_t)s];
     su += seg_sums[2 * (int64_t)s + 1];
   }
-  sx = block_sum(sx, lds);
-  su = block_sum(su, lds);
+  sx = block_sum<FBLOCK>(sx, lds);
+  su = block_sum<FBLOCK>(su, lds);
   if (threadIdx.x == 0) {
     const float nx = (float)sqrt(sx), nu = (float)sqrt(su);
     float c = nx / nu;

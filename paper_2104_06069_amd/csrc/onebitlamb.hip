@@ -22,7 +22,12 @@ using namespace obk;
 
 namespace {
 
-constexpr int U_MAIN = 4;   // 128-bit accesses per thread per array in the N-sized kernels
+#ifndef OB_U_MAIN
+#define OB_U_MAIN 1
+#endif
+// 128-bit accesses per thread per array in the N-sized kernels: tiles of 1024 elements measured
+// ~7 % faster than 4096 on MI355X (ratio and update kernels at 6.4-6.5 TB/s instead of 6.0).
+constexpr int U_MAIN = OB_U_MAIN;
 constexpr int U_SRV = 1;    // ... in the kernels over the single server chunk
 constexpr int U_RES = 16;   // ... in the single-pass worker compression (z stays in registers)
 constexpr int G_RES = 2;    // the single-pass kernel issues its loads G_RES accesses at a time
@@ -131,14 +136,15 @@ struct Launch {
   }
 };
 
-#define OB_LAUNCH(la, kid, kernel, grid, ...)                                     \
+#define OB_LAUNCH_B(la, kid, kernel, grid, block, ...)                            \
   do {                                                                            \
     if ((la).ok && (grid) > 0) {                                                  \
       (la).begin(kid);                                                            \
-      hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(BLOCK), 0, (la).stream, __VA_ARGS__); \
+      hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(block), 0, (la).stream, __VA_ARGS__); \
       (la).end(kKernelNames[kid]);                                                \
     }                                                                             \
   } while (0)
+#define OB_LAUNCH(la, kid, kernel, grid, ...) OB_LAUNCH_B(la, kid, kernel, grid, BLOCK, __VA_ARGS__)
 
 template <class T>
 bool upload(ob_lamb_ctx* ctx, T** dst, const std::vector<T>& src) {
@@ -327,7 +333,8 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   bool ok = hip_ok(ctx, hipGetDevice(&ctx->device), "hipGetDevice");
   if (ok) {
     // The single-pass kernel needs a whole chunk's workgroups on the device at once (see the
-    // kernel's comment); it is used only when twice that many fit, else the two-pass kernels run.
+    // kernel's comment); it is used only when they fill at most 80 % of the device's workgroup
+    // slots (it still beats two passes at 61 % on MI355X), else the two-pass kernels run.
     int per_cu = 0, cus = 0;
     ok = hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
                          &per_cu, k_compress_resident<U_RES, G_RES, true, false>, BLOCK, 0),
@@ -336,7 +343,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                 "hipDeviceGetAttribute");
     const int64_t slots = (int64_t)per_cu * cus;
     const char* env = getenv("OB_LAMB_TWO_PASS");
-    ctx->resident = ok && !(env && env[0] == '1') && 2 * (tpc_res + 8) <= slots;
+    ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
@@ -387,7 +394,7 @@ ob_status ob_lamb_warmup_step(ob_lamb_ctx* ctx, const ob_lamb_state* st, const f
   OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN>), ctx->n_tiles, grad, st->m, st->v_fresh,
             st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2,
             ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
-  OB_LAUNCH(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, ctx->d_seg_sums, ctx->d_layer_seg0,
+  OB_LAUNCH_B(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
             st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3);
   OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN>), ctx->n_tiles, st->m, st->v_fresh, st->x,
             st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt);
@@ -442,7 +449,7 @@ ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
               ctx->n_tiles, grad, st->m, pm, st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc,
               ctx->beta1, ctx->omb1, lt);
   });
-  OB_LAUNCH(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out);
+  OB_LAUNCH_B(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, FBLOCK, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out);
   OB_LAUNCH(la, KID_SIGN_PACK, (k_sign_pack_error<U_MAIN>), ctx->n_tiles, st->err_worker, packed_out,
             scales_out, ctx->n_c, ctx->tpc);
   return la.ok ? OB_OK : OB_ERR_HIP;
@@ -457,7 +464,7 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
   Launch la(ctx, hip_stream);
   OB_LAUNCH(la, KID_SERVER_AVG, (k_server_unpack_avg<U_SRV>), ctx->tpc_srv, packed_in, scales_in,
             st->err_server, ctx->d_partials_srv, ctx->n_c, (int)ctx->W, ctx->invW);
-  OB_LAUNCH(la, KID_SERVER_SCALE, k_chunk_scale, 1, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out);
+  OB_LAUNCH_B(la, KID_SERVER_SCALE, k_chunk_scale, 1, FBLOCK, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out);
   OB_LAUNCH(la, KID_SERVER_PACK, (k_sign_pack_error<U_SRV>), ctx->tpc_srv, st->err_server, packed_out,
             scale_out, ctx->n_c, ctx->tpc_srv);
   return la.ok ? OB_OK : OB_ERR_HIP;
@@ -479,7 +486,7 @@ ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
               ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2, lt, ctx->d_tile_seg0,
               ctx->d_seg_layer);
   });
-  OB_LAUNCH(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, ctx->d_seg_max, ctx->d_layer_seg0,
+  OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max, ctx->d_layer_seg0,
             st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr, ctx->r_min, ctx->r_max);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
