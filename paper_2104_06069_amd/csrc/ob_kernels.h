@@ -103,9 +103,10 @@ __device__ __forceinline__ unsigned int gather_word(unsigned int nibble) {
   return v;
 }
 
-// The lane's sign nibble (bits of its 4 elements at offset o of the tile) from a packed stream.
-__device__ __forceinline__ unsigned int load_nibble(const uint32_t* __restrict__ packed, int64_t i0) {
-  return (packed[i0 >> 5] >> (4 * (threadIdx.x & 7))) & 0xFu;
+// The lane's sign nibble from a packed stream: the bits of elements span0 + 4*threadIdx.x + k,
+// span0 uniform and a multiple of 1024.
+__device__ __forceinline__ unsigned int load_nibble(const uint32_t* __restrict__ packed, int64_t span0) {
+  return ((packed + (span0 >> 5))[threadIdx.x >> 3] >> (4 * (threadIdx.x & 7))) & 0xFu;
 }
 
 struct TilePos {
@@ -154,10 +155,16 @@ struct ZTile {
   float bm;      // beta1 * |m| (PACKED_M; for HAS_K only on uniform tiles)
   float s_prev;  // previous server scale of the chunk (PACKED_M)
   int64_t N;
+  // layer cursor of the per-element path (HAS_K, tile meets a layer boundary)
+  int cur_l;
+  int64_t cur_end;
+  float cur_k, cur_b;
+  bool cur_real;
 
   __device__ __forceinline__ void init(const LayerTab& lt, const PackedMom& pm, const TilePos& p,
                                        float beta1) {
     uniform = true; pad = false; l0 = 0; kt = 1.0f; bm = 0.0f; s_prev = 0.0f; N = 0;
+    cur_l = 0; cur_end = 0; cur_k = 1.0f; cur_b = 0.0f; cur_real = false;
     if (PACKED_M) s_prev = pm.scales[p.c];
     if (HAS_K) {
       // k differs from layer to layer: the tile must lie inside one layer (or in the padding)
@@ -167,6 +174,13 @@ struct ZTile {
       if (uniform && !pad) {
         kt = lt.mom_scale[l0];
         if (PACKED_M) bm = beta1 * (s_prev / kt);
+      }
+      if (!uniform) {  // l0 < L here: a tile that starts in the padding is uniform
+        cur_l = l0;
+        cur_end = lt.off[l0 + 1];
+        cur_real = true;
+        cur_k = lt.mom_scale[l0];
+        if (PACKED_M) cur_b = beta1 * (s_prev / cur_k);
       }
     } else if (PACKED_M) {
       // only the end of the parameters matters: the 1-bit momentum is 0 in the padding
@@ -179,8 +193,9 @@ struct ZTile {
 
   // G, E: gradient and carried error; M: dense momentum (ignored when PACKED_M); nib: the sign
   // bits of the packed momentum (ignored otherwise); i0: flat index of the first element.
+  // Calls must come in increasing i0 for one thread (the per-element path keeps a cursor).
   __device__ __forceinline__ v4f z(const LayerTab& lt, float beta1, float omb1, v4f G, v4f M,
-                                   unsigned int nib, v4f E, int64_t i0) const {
+                                   unsigned int nib, v4f E, int64_t i0) {
     v4f r;
     if (uniform) {
 #pragma unroll
@@ -192,23 +207,25 @@ struct ZTile {
         r[k] = HAS_K ? kt * mloc + E[k] : mloc + E[k];
       }
     } else if (HAS_K) {
-      int l = l0, lc = -1;
-      float kk = 1.0f, b = 0.0f;
-      bool real = false;
+      // A thread's elements come in increasing order over the whole tile, so the layer cursor
+      // only moves forward and its constants are re-formed only when a boundary is crossed.
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        l = walk_layer(l, i0 + k, lt.off);
-        if (l != lc) {  // constants of a layer are formed once per run of its elements
-          lc = l;
-          real = (l < lt.L);
-          kk = real ? lt.mom_scale[l] : 1.0f;
-          if (PACKED_M) b = beta1 * (s_prev / kk);
+        const int64_t i = i0 + k;
+        if (i >= cur_end) {
+          do {
+            ++cur_l;
+            cur_end = lt.off[cur_l + 1];
+          } while (i >= cur_end);
+          cur_real = (cur_l < lt.L);
+          cur_k = cur_real ? lt.mom_scale[cur_l] : 1.0f;
+          if (PACKED_M) cur_b = beta1 * (s_prev / cur_k);
         }
         float bmk;
-        if (PACKED_M) bmk = real ? (((nib >> k) & 1u) ? b : -b) : 0.0f;
+        if (PACKED_M) bmk = cur_real ? (((nib >> k) & 1u) ? cur_b : -cur_b) : 0.0f;
         else bmk = beta1 * M[k];
         const float mloc = bmk + omb1 * G[k];
-        r[k] = kk * mloc + E[k];
+        r[k] = cur_k * mloc + E[k];
       }
     } else {  // PACKED_M without k: the tile straddles the end of the parameters
 #pragma unroll
@@ -241,7 +258,7 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
     M[u] = 0.0f; NB[u] = 0u;
     if (o < p.len) {
       G[u] = ld4(g + p.tile0 + o);
-      if (PACKED_M) NB[u] = load_nibble(pm.bits, p.tile0 + o);
+      if (PACKED_M) NB[u] = load_nibble(pm.bits, p.tile0 + u * SPAN);
       else M[u] = ld4(m + p.tile0 + o);
       E[u] = ld4(err + p.tile0 + o);
     }
@@ -275,8 +292,10 @@ __global__ __launch_bounds__(FBLOCK) void k_chunk_scale(const double* __restrict
 }
 
 // Sign, pack and error update of one 128-bit access held in registers (Algorithm 1 line 7/10).
+// span0: flat index of the first element of the workgroup-wide access (uniform, multiple of 1024);
+// the thread's elements are span0 + 4*threadIdx.x + k.
 __device__ __forceinline__ void sign_pack_store(v4f z, float s, float* __restrict__ err,
-                                                uint32_t* __restrict__ packed, int64_t i0) {
+                                                uint32_t* __restrict__ packed, int64_t span0) {
   unsigned int nib = 0;
   v4f e;
 #pragma unroll
@@ -285,9 +304,9 @@ __device__ __forceinline__ void sign_pack_store(v4f z, float s, float* __restric
     nib |= (b ? 1u : 0u) << k;
     e[k] = z[k] - (b ? s : -s);
   }
-  st4(err + i0, e);
+  st4(err + span0 + threadIdx.x * 4, e);
   const unsigned int word = gather_word(nib);
-  if ((threadIdx.x & 7) == 0) packed[i0 >> 5] = word;
+  if ((threadIdx.x & 7) == 0) (packed + (span0 >> 5))[threadIdx.x >> 3] = word;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -312,7 +331,7 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
     // uniform over the wavefront (len is a multiple of 256), as the shuffles inside require
-    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + o);
+    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + u * SPAN);
   }
 }
 
@@ -409,6 +428,8 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
   zt.init(lt, pm, p, beta1);
   v4f Z[U];
   double acc = 0.0;
+  // (Issuing the next group's loads before evaluating the current one, or a branch-free path for
+  // full tiles, measured no faster: the kernel is bound by the barrier, not by load latency.)
 #pragma unroll
   for (int u0 = 0; u0 < U; u0 += G) {
     v4f Gr[G], M[G], E[G];
@@ -419,7 +440,7 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
       M[j] = 0.0f; NB[j] = 0u;
       if (o < p.len) {
         Gr[j] = ld4(g + p.tile0 + o);
-        if (PACKED_M) NB[j] = load_nibble(pm.bits, p.tile0 + o);
+        if (PACKED_M) NB[j] = load_nibble(pm.bits, p.tile0 + (u0 + j) * SPAN);
         else M[j] = ld4(m + p.tile0 + o);
         E[j] = ld4(err + p.tile0 + o);
       }
@@ -440,7 +461,7 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
-    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + o);
+    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + u * SPAN);
   }
 }
 
@@ -548,8 +569,8 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
     const int o = u * SPAN + o0;
     M[u] = 0.0f; OB[u] = 0u;
     if (o < p.len) {
-      NB[u] = load_nibble(packed, p.tile0 + o);
-      if (PACKED_M) OB[u] = load_nibble(pm.bits, p.tile0 + o);
+      NB[u] = load_nibble(packed, p.tile0 + u * SPAN);
+      if (PACKED_M) OB[u] = load_nibble(pm.bits, p.tile0 + u * SPAN);
       else M[u] = ld4(m + p.tile0 + o);
       VF[u] = ld4(v_fresh + p.tile0 + o);
       VZ[u] = ld4(v_frozen + p.tile0 + o);
@@ -698,7 +719,7 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
     if (o < p.len) {
-      NB[u] = load_nibble(packed, p.tile0 + o);
+      NB[u] = load_nibble(packed, p.tile0 + u * SPAN);
       VZ[u] = ld4(v_frozen + p.tile0 + o);
       X[u] = ld4(x + p.tile0 + o);
     }
@@ -765,7 +786,7 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_dense(PackedMom pm, float* _
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
     if (o < p.len) {
-      const unsigned int nb = load_nibble(pm.bits, p.tile0 + o);
+      const unsigned int nb = load_nibble(pm.bits, p.tile0 + u * SPAN);
       if (uniform) {
         const float sp = HAS_K ? ss / lt.mom_scale[l0] : ss;
         v4f mn;
