@@ -217,6 +217,26 @@ def main():
     }
 
     ob.ob_lamb_check_device_status(ds.ctx, ds.stream)  # raises if a bounded device wait expired
+
+    # reference timings outside the headline metric: one uncompressed LAMB warmup step (eq. (1)) and
+    # the end-of-warmup momentum-scale generation (Appendix A.5.2), on the same buffers
+    def timed(fn, reps=5):
+        fn(); torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    ds.m_is_packed = False
+    wu_ms = timed(lambda: ds.warmup_step(grads[0], lr))
+    ms_ms = timed(lambda: ds.momentum_scale())
+    out["reference_calls"] = {
+        "warmup_step_ms": round(wu_ms, 4),
+        "warmup_step_GBps": round(40.0 * ds.n_pad / (wu_ms * 1e-3) / 1e9, 1),   # 24 + 16 B/elem, two passes
+        "warmup_step_params_per_s": round(pl.N / (wu_ms * 1e-3), 1),
+        "momentum_scale_ms": round(ms_ms, 4),
+        "momentum_scale_GBps": round(4.0 * ds.n_pad / (ms_ms * 1e-3) / 1e9, 1)}
     if host0 is not None:
         out["cpu_baseline"] = cpu_baseline(cfg, server_chunk, hyper, mom_scale, host0, lr,
                                            args.cpu_seconds)

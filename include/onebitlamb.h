@@ -169,6 +169,13 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                    const uint32_t* packed_all, const float* server_scales,
                                    float lr, void* hip_stream);
 
+/* Appendix A.5.2, end of warmup: forms the momentum-scale coefficients from the dense momentum
+ * st->m and writes them to st->mom_scale [L] (must be non-NULL here).  The paper gives no formula;
+ * this library takes sigma_l = ||m_l||_2 / sqrt(n_l), k_l = mean(sigma) / sigma_l with the mean over
+ * the non-empty layers, and k_l = 1 where sigma_l = 0 or the layer is empty, so that every layer
+ * enters the fused compression with the same RMS.  fp64 accumulation, one rounding to fp32. */
+ob_status ob_lamb_momentum_scale(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_stream);
+
 /* ob_lamb_compress_local runs as ONE kernel that keeps z in registers across a per-chunk arrival
  * barrier whenever one chunk's workgroups fill at most 80 % of the device (otherwise, or when the
  * environment variable OB_LAMB_TWO_PASS=1 is set at ob_lamb_create, as two passes through memory;

@@ -66,6 +66,7 @@ def lib():
             "ob_lamb_layer_ratios": (C.c_int, [vp, sp, vp, vp, vp]),
             "ob_lamb_decompress_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
+            "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
@@ -175,6 +176,10 @@ def ob_lamb_decompress_apply(ctx, state, packed_all, server_scales, lr, stream=N
 def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):
     _check(lib().ob_lamb_momentum_dense(ctx, C.byref(state), _addr(m_out), _addr(stream)), ctx,
            "ob_lamb_momentum_dense")
+
+
+def ob_lamb_momentum_scale(ctx, state, stream=None):
+    _check(lib().ob_lamb_momentum_scale(ctx, C.byref(state), _addr(stream)), ctx, "ob_lamb_momentum_scale")
 
 
 def ob_lamb_check_device_status(ctx, stream=None):

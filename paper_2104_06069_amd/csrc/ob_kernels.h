@@ -1006,6 +1006,94 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Momentum-scale coefficients of Appendix A.5.2, formed once at the end of warmup.  The paper gives
+// no formula; the reading taken: sigma_l = ||m_l||_2/sqrt(n_l), k_l = mean_l(sigma_l)/sigma_l over
+// the non-empty layers, 1 where sigma_l = 0 or the layer is empty (every layer's RMS becomes the
+// mean RMS before the fused buffer is compressed).
+//   a: per (tile, layer) segment the fp64 sum of m^2
+//   b: one workgroup: per-layer sigma, their mean (fixed order), k_l
+// ---------------------------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(BLOCK) void k_momentum_sumsq(const float* __restrict__ m,
+                                                          double* __restrict__ seg_sums,
+                                                          int64_t n_c, int tpc, LayerTab lt,
+                                                          const int* __restrict__ tile_seg0,
+                                                          const int* __restrict__ seg_layer) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const int l0 = lt.first_layer[blockIdx.x];
+  if (l0 >= lt.L) return;
+  const int o0 = threadIdx.x * 4;
+  v4f M[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    M[u] = 0.0f;
+    if (o < p.len) M[u] = ld4(m + p.tile0 + o);
+  }
+  const int s0 = tile_seg0[blockIdx.x], s1 = tile_seg0[blockIdx.x + 1];
+  for (int s = s0; s < s1; ++s) {
+    const int l = seg_layer[s];
+    const int64_t a = lt.off[l], b = lt.off[l + 1];
+    double acc = 0.0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          if (i >= a && i < b) acc += (double)M[u][k] * (double)M[u][k];
+        }
+      }
+    }
+    acc = block_sum(acc, lds);
+    if (threadIdx.x == 0) seg_sums[s] = acc;
+  }
+}
+
+// sigma[l] (fp64 scratch, [L]) from the segment sums; one workgroup per layer.
+__global__ __launch_bounds__(FBLOCK) void k_layer_rms(const double* __restrict__ seg_sums,
+                                                      const int* __restrict__ layer_seg0,
+                                                      const int64_t* __restrict__ off,
+                                                      double* __restrict__ sigma) {
+  __shared__ double lds[FBLOCK / WAVE];
+  const int l = blockIdx.x;
+  double a = 0.0;
+  for (int s = layer_seg0[l] + threadIdx.x; s < layer_seg0[l + 1]; s += FBLOCK) a += seg_sums[s];
+  a = block_sum<FBLOCK>(a, lds);
+  if (threadIdx.x == 0) {
+    const int64_t n = off[l + 1] - off[l];
+    sigma[l] = (n > 0) ? sqrt(a / (double)n) : 0.0;
+  }
+}
+
+// mean of sigma over the non-empty layers (one workgroup, fixed order), then k_l.
+__global__ __launch_bounds__(FBLOCK) void k_momentum_scale(const double* __restrict__ sigma,
+                                                           const int64_t* __restrict__ off, int L,
+                                                           float* __restrict__ mom_scale) {
+  __shared__ double lds[FBLOCK / WAVE];
+  __shared__ double mean_s;
+  double a = 0.0, cnt = 0.0;
+  for (int l = threadIdx.x; l < L; l += FBLOCK) {
+    if (off[l + 1] > off[l]) {
+      a += sigma[l];
+      cnt += 1.0;
+    }
+  }
+  a = block_sum<FBLOCK>(a, lds);
+  cnt = block_sum<FBLOCK>(cnt, lds);
+  if (threadIdx.x == 0) mean_s = (cnt > 0.0) ? a / cnt : 0.0;
+  __syncthreads();
+  const double mean = mean_s;
+  for (int l = threadIdx.x; l < L; l += FBLOCK) {
+    const double s = sigma[l];
+    mom_scale[l] = (s > 0.0) ? (float)(mean / s) : 1.0f;
+  }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_fill(float* __restrict__ p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
   if (i < n) p[i] = v;

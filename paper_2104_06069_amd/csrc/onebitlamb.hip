@@ -47,6 +47,7 @@ enum KernelId {
   KID_RATIOS_FINALIZE,
   KID_APPLY,
   KID_MOMENTUM_DENSE,
+  KID_MOMENTUM_SCALE,
   KID_WARMUP_MOMENTS,
   KID_WARMUP_COEFF,
   KID_WARMUP_APPLY,
@@ -57,7 +58,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "momentum_dense", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "fill",             "copy"};
 
 struct ProfRec {
@@ -88,6 +89,7 @@ struct ob_lamb_ctx {
   double* d_partials = nullptr;   // [n_tiles]
   double* d_partials_srv = nullptr;  // [tpc_srv]
   double* d_seg_sums = nullptr;   // [2*n_segs]
+  double* d_sigma = nullptr;      // [L] per-layer RMS (momentum-scale generation)
   float* d_seg_max = nullptr;     // [n_segs] per-segment max(v_frozen/v_fresh)
   // single-pass worker compression (k_compress_resident)
   bool resident = false;          // selected at create when the device can hold 2 chunks of tiles
@@ -355,6 +357,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
        alloc_zero(ctx, &ctx->d_partials, (size_t)n_tiles) &&
        alloc_zero(ctx, &ctx->d_partials_srv, (size_t)tpc_srv) &&
        alloc_zero(ctx, &ctx->d_seg_sums, 2 * (size_t)ctx->n_segs) &&
+       alloc_zero(ctx, &ctx->d_sigma, (size_t)L) &&
        alloc_zero(ctx, &ctx->d_seg_max, (size_t)ctx->n_segs);
   ok = ok && hip_ok(ctx, hipDeviceSynchronize(), "hipDeviceSynchronize");
   if (!ok) {
@@ -372,7 +375,7 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
     (void)hipEventDestroy(r.e1);
   }
   void* ptrs[] = {ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer, ctx->d_layer_seg0,
-                  ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max,
+                  ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max, ctx->d_sigma,
                   ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -534,6 +537,21 @@ ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, floa
   else
     OB_LAUNCH(la, KID_MOMENTUM_DENSE, (k_momentum_dense<U_MAIN, false>), ctx->n_tiles, pm, m_out, ctx->n_c,
               ctx->tpc, lt);
+  return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_momentum_scale(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_stream) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(st->m);
+  if (!st->mom_scale) return OB_ERR_NULL;
+  Launch la(ctx, hip_stream);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  OB_LAUNCH(la, KID_MOMENTUM_SCALE, (k_momentum_sumsq<U_MAIN>), ctx->n_tiles, st->m, ctx->d_seg_sums,
+            ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
+  OB_LAUNCH_B(la, KID_MOMENTUM_SCALE, k_layer_rms, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
+              ctx->d_off, ctx->d_sigma);
+  OB_LAUNCH_B(la, KID_MOMENTUM_SCALE, k_momentum_scale, 1, FBLOCK, ctx->d_sigma, ctx->d_off, (int)ctx->L,
+              st->mom_scale);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 

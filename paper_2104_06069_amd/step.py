@@ -122,6 +122,29 @@ class DeviceStep:
     def freeze(self):
         ob.ob_lamb_freeze(self.ctx, self._state("read"), self.stream)
 
+    def momentum_scale(self):
+        """End of warmup (Appendix A.5.2): form the per-layer coefficients from the dense momentum."""
+        if self.t["mom_scale"] is None:
+            self.t["mom_scale"] = torch.ones(self.L, device=self.device, dtype=torch.float32)
+        ob.ob_lamb_momentum_scale(self.ctx, self._state("read"), self.stream)
+
+    def train_step(self, t, warmup_steps, grad, lr, fill_wire=None, momentum_scaling=True):
+        """Step t of the two-stage schedule of Algorithm 1: LAMB for t < warmup_steps (the last of
+        them followed by the end-of-warmup snapshot), compression-stage steps afterwards.
+        fill_wire(self) is called once the step's wire buffers are selected, to place what the
+        other ranks sent (in a real job: the two collectives)."""
+        if t < warmup_steps:
+            self.warmup_step(grad, lr)
+            if t == warmup_steps - 1:
+                self.freeze()
+                if momentum_scaling:
+                    self.momentum_scale()
+            return
+        self.begin_step()
+        if fill_wire is not None:
+            fill_wire(self)
+        self.step(grad, lr)
+
     def begin_step(self):
         """Select the wire buffers of the coming step: the pair that does not hold the momentum."""
         if self.packed_momentum and self.m_is_packed:

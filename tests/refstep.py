@@ -56,6 +56,21 @@ class RefStep:
         self.t["v_frozen"][...] = self.t["v_fresh"]
         self.t["r_prev"][...] = 1.0
 
+    def momentum_scale(self):
+        self.mom_scale = F32.momentum_scale(self.off, self.t["m"])
+
+    def train_step(self, t, warmup_steps, g, lr, fill_wire=None, momentum_scaling=True):
+        if t < warmup_steps:
+            self.warmup_step(g, lr)
+            if t == warmup_steps - 1:
+                self.freeze()
+                if momentum_scaling:
+                    self.momentum_scale()
+            return
+        if fill_wire is not None:
+            fill_wire(self)
+        self.step(g, lr)
+
     def compress_local(self, g):
         self.bits_local, self.scales_local = F32.compress_local(
             self.off, self.W, self.mom_scale, self.h["beta1"], g, self.t["m"], self.t["err_worker"])

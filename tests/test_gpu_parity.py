@@ -370,3 +370,75 @@ def test_argument_errors():
     torch.cuda.synchronize()
     assert np.array_equal(dev.get("x"), x0)
     finish(dev)
+
+
+@pytest.mark.parametrize("case", ["odd", "bert_mini"])
+def test_momentum_scale_generation(case):
+    """Appendix A.5.2 coefficients from the momentum at the end of warmup."""
+    _need_gpu()
+    cfg = make_case(case)
+    cfg["use_k"] = False
+    st, ref, dev = start_pair(cfg)
+    # momentum with very different scales per layer (the case A.5.2 describes), one all-zero layer
+    m = st.normal("m_ms", 0, cfg["n_pad"], 1.0)
+    off = cfg["plist"].offsets
+    kap = st.uniform_host("kap_ms", 0, cfg["plist"].L, -6, 0)
+    for l in range(cfg["plist"].L):
+        m[off[l]:off[l + 1]] *= np.float32(10.0 ** kap[l])
+    m[off[1]:off[2]] = 0
+    m[cfg["plist"].N:] = 0
+    ref.t["m"][...] = m
+    dev.load_state(ref.t)
+    ref.momentum_scale(); dev.momentum_scale()
+    k_gpu = dev.t["mom_scale"].cpu().numpy()
+    assert_close(k_gpu, ref.mom_scale, "mom_scale")
+    assert k_gpu[1] == 1.0
+    finish(dev)
+
+
+@pytest.mark.parametrize("case,packed", [("bert_mini", True), ("odd", False)])
+def test_two_stage_schedule(case, packed):
+    """Algorithm 1 end to end: LAMB warmup with the moving average of c, the end-of-warmup snapshot
+    and momentum-scale generation, then compression-stage steps -- with the paper's warmup share
+    (16.7 %) and the shape of its learning-rate schedule, scaled down to 48 steps."""
+    _need_gpu()
+    from workloads import lr_seqlen128
+    cfg = make_case(case)
+    T, T_w = 48, 8
+    st = Streams(11)
+    pl = cfg["plist"]
+    hyper = dict(HYPER, c_min=1e-3)   # so that LAMB's coefficient is not clipped on every layer
+    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **hyper)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], packed_momentum=packed, **hyper)
+    s = init_state(st, cfg)
+    for k in ("v_fresh", "v_frozen", "c_avg"):
+        s[k][...] = 0          # Algorithm 1 line 1: m = v = 0, c_avg = 0
+    ref.load_state(s); dev.load_state(ref.t)
+    for t in range(T):
+        g = gradient(st, cfg, t)
+        lr = lr_seqlen128(t, rampup=4, decay_every=10)
+        fw, fs = foreign_worker_chunks(st, cfg, t); fa, fss = foreign_server_chunks(st, cfg, t)
+
+        def fill_ref(r):
+            r.set_foreign_in(fw, fs); r.set_foreign_all(fa, fss)
+
+        def fill_dev(d):
+            d.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+            d.scales_in.copy_(torch.from_numpy(fs))
+            d.packed_all.copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
+            d.server_scales.copy_(torch.from_numpy(fss))
+
+        ref.train_step(t, T_w, g, lr, fill_ref)
+        dev.train_step(t, T_w, torch.from_numpy(g).to(dev.device), lr, fill_dev)
+        if t == T_w - 1:
+            assert_close(dev.t["mom_scale"].cpu().numpy(), ref.mom_scale, "mom_scale at hand-off")
+            assert np.array_equal(dev.get("v_frozen"), dev.get("v_fresh"))
+            for k in ("c_avg", "m", "x", "v_fresh"):
+                assert_close(dev.get(k), ref.t[k], f"hand-off {k}")
+        if t >= T_w:
+            assert np.array_equal(words_of(dev.packed_local), ref.bits_local), t
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c", "c_avg"):
+        assert_close(dev.get(k), ref.t[k], k, rel=1e-5)
+    r = dev.get("r_prev")
+    assert np.all(r >= 0.5) and np.all(r <= 4.0)
+    finish(dev)

@@ -6,3 +6,4 @@ numbers and lays out tensors, nothing else.
 """
 from .shapes import CONFIGS, ParamList, bert_shaped, gpt_shaped, make_config, padded_len, tiny  # noqa: F401
 from .gen import Streams, gradient, init_state, foreign_worker_chunks, foreign_server_chunks  # noqa: F401
+from .schedule import lr_seqlen128, PAPER_SEQLEN128, PAPER_SEQLEN512  # noqa: F401
