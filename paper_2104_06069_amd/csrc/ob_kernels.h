@@ -106,19 +106,21 @@ __device__ __forceinline__ unsigned int gather_word(unsigned int nibble) {
 // The lane's sign nibble from a packed stream: the bits of elements span0 + 4*threadIdx.x + k,
 // span0 uniform and a multiple of 1024.
 __device__ __forceinline__ unsigned int load_nibble(const uint32_t* __restrict__ packed, int64_t span0) {
-  return ((packed + (span0 >> 5))[threadIdx.x >> 3] >> (4 * (threadIdx.x & 7))) & 0xFu;
+  return (packed + (span0 >> 5))[threadIdx.x >> 3] >> (4 * (threadIdx.x & 7));  // bits 0..3 are the lane's
 }
 
 struct TilePos {
+  int t;          // tile index (chunk-major)
   int c;          // chunk
   int64_t tile0;  // first element
   int len;        // elements in the tile (multiple of 256)
 };
 
+// Tile t of the tiling with TILE elements per tile and tpc tiles per chunk.
 template <int TILE>
-__device__ __forceinline__ TilePos tile_pos(int64_t n_c, int tpc) {
+__device__ __forceinline__ TilePos tile_pos(int64_t n_c, int tpc, int t) {
   TilePos p;
-  const int t = blockIdx.x;
+  p.t = t;
   p.c = t / tpc;
   const int b = t - p.c * tpc;
   const int64_t in_chunk = (int64_t)b * TILE;
@@ -130,16 +132,24 @@ __device__ __forceinline__ TilePos tile_pos(int64_t n_c, int tpc) {
 
 // Per-layer tables (device pointers) shared by the layer-aware kernels.
 struct LayerTab {
-  const float* mom_scale;   // [L] k_l of Appendix A.5.2 (only read when HAS_K)
-  const int64_t* off;       // [L+2]
-  const int* first_layer;   // [tiles of the launching kernel's tile size]
+  const float* __restrict__ mom_scale;   // [L] k_l of Appendix A.5.2 (only read when HAS_K)
+  const int64_t* __restrict__ off;       // [L+2]
+  const int* __restrict__ first_layer;   // [tiles of the launching kernel's tile size]
   int L;
+};
+
+// Restriction of a layer-wise kernel to a subset of the layers: the launch covers the tiles listed
+// in tile_list (NULL: all tiles, in order) and leaves the elements of layers with skip[l] != 0
+// alone (NULL: no layer is skipped).
+struct LayerSel {
+  const int* tile_list;
+  const unsigned char* skip;
 };
 
 // Momentum source in 1-bit form (only read when PACKED_M).
 struct PackedMom {
-  const uint32_t* bits;     // [N_pad/32]
-  const float* scales;      // [W]
+  const uint32_t* __restrict__ bits;     // [N_pad/32]
+  const float* __restrict__ scales;      // [W]
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -168,7 +178,7 @@ struct ZTile {
     if (PACKED_M) s_prev = pm.scales[p.c];
     if (HAS_K) {
       // k differs from layer to layer: the tile must lie inside one layer (or in the padding)
-      l0 = lt.first_layer[blockIdx.x];
+      l0 = lt.first_layer[p.t];
       uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
       pad = (l0 >= lt.L);
       if (uniform && !pad) {
@@ -248,7 +258,7 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
     float omb1, LayerTab lt) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
   const int o0 = threadIdx.x * 4;
   v4f G[U], M[U], E[U];
   unsigned int NB[U];
@@ -277,7 +287,7 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
     }
   }
   const double s = block_sum(acc, lds);
-  if (threadIdx.x == 0) partials[blockIdx.x] = s;
+  if (threadIdx.x == 0) partials[p.t] = s;
 }
 
 // scale[c] = sqrt(sum of the chunk's tile partials / n_c), summed in a fixed order.
@@ -318,7 +328,7 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
                                                            const float* __restrict__ scales,
                                                            int64_t n_c, int tpc) {
   constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
   const float s = scales[p.c];
   const int o0 = threadIdx.x * 4;
   v4f Z[U];
@@ -363,12 +373,12 @@ struct ChunkSync {
   int spin_limit;
 };
 
-__device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int c, int tpc,
+__device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int tile, int c, int tpc,
                                                      int64_t n_c, double part, double* lds,
                                                      unsigned long long* bc,
                                                      float* __restrict__ scale_out) {
   if (threadIdx.x == 0) {
-    __hip_atomic_store(&cs.partials[blockIdx.x], part, __ATOMIC_RELAXED, OB_AGENT);
+    __hip_atomic_store(&cs.partials[tile], part, __ATOMIC_RELAXED, OB_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
     const unsigned long long prev =
         __hip_atomic_fetch_add(&cs.counter[c], 1ull, __ATOMIC_RELAXED, OB_AGENT);
@@ -422,7 +432,7 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
   const int o0 = threadIdx.x * 4;
   ZTile<HAS_K, PACKED_M> zt;
   zt.init(lt, pm, p, beta1);
@@ -457,7 +467,7 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
     }
   }
   const double part = block_sum(acc, lds);
-  const float s = chunk_barrier_scale(cs, p.c, tpc, n_c, part, lds, &bc, scales);
+  const float s = chunk_barrier_scale(cs, p.t, p.c, tpc, n_c, part, lds, &bc, scales);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
@@ -516,7 +526,7 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
     float* __restrict__ err_s, double* __restrict__ partials, int64_t n_c, int W, float invW) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x);  // one chunk: c == 0
+  const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x, (int)blockIdx.x);  // one chunk: c == 0
   const int o0 = threadIdx.x * 4;
   float acc[U][4];
   server_average<U>(packed_in, scales_in, n_c, W, p, acc);
@@ -536,7 +546,7 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
     }
   }
   const double s = block_sum(sq, lds);
-  if (threadIdx.x == 0) partials[blockIdx.x] = s;
+  if (threadIdx.x == 0) partials[p.t] = s;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -544,48 +554,53 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
 //     (Algorithm 1 lines 13, 15-17).  One maximum per (tile, layer) segment, no atomics.
 // With the previous momentum in 1-bit form the reconstructed gradient takes only two magnitudes
 // per tile, (s' - beta1 s)/(1-beta1) and (s' + beta1 s)/(1-beta1), whose squares are hoisted.
+// The tile's registers and the two evaluation paths are shared with the fused ratio+update kernel.
 // ---------------------------------------------------------------------------------------------
+struct RatioArgs {
+  const uint32_t* __restrict__ packed;   // [N_pad/32] the W recompressed chunks
+  const float* __restrict__ sscales;     // [W] their scales
+  const float* __restrict__ m;           // dense previous momentum (unless PACKED_M)
+  PackedMom pm;                          // 1-bit previous momentum (PACKED_M)
+  float* __restrict__ v_fresh;
+  const float* __restrict__ v_frozen;
+  float beta1, omb1, beta2, omb2;
+};
+
 template <int U, bool HAS_K, bool PACKED_M>
-__global__ __launch_bounds__(BLOCK) void k_ratios_pass(
-    const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
-    const float* __restrict__ m, PackedMom pm, float* __restrict__ v_fresh,
-    const float* __restrict__ v_frozen, float* __restrict__ seg_max, int64_t n_c, int tpc,
-    float beta1, float omb1, float beta2, float omb2, LayerTab lt,
-    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer) {
-  constexpr int TILE = SPAN * U;
-  __shared__ float lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = lt.first_layer[blockIdx.x];
-  const int L = lt.L;
-  if (l0 >= L) return;  // tile lies in the padding (it has no segment)
-  const int o0 = threadIdx.x * 4;
-  const float ss = sscales[p.c];
-  const float s_prev = PACKED_M ? pm.scales[p.c] : 0.0f;
-  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+struct RatioTile {
   unsigned int NB[U], OB[U];
   v4f M[U], VF[U], VZ[U];
+
+  __device__ __forceinline__ void load(const RatioArgs& ra, const TilePos& p) {
+    const int o0 = threadIdx.x * 4;
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    M[u] = 0.0f; OB[u] = 0u;
-    if (o < p.len) {
-      NB[u] = load_nibble(packed, p.tile0 + u * SPAN);
-      if (PACKED_M) OB[u] = load_nibble(pm.bits, p.tile0 + u * SPAN);
-      else M[u] = ld4(m + p.tile0 + o);
-      VF[u] = ld4(v_fresh + p.tile0 + o);
-      VZ[u] = ld4(v_frozen + p.tile0 + o);
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      M[u] = 0.0f; OB[u] = 0u; NB[u] = 0u; VF[u] = 0.0f; VZ[u] = 0.0f;
+      if (o < p.len) {
+        NB[u] = load_nibble(ra.packed, p.tile0 + u * SPAN);
+        if (PACKED_M) OB[u] = load_nibble(ra.pm.bits, p.tile0 + u * SPAN);
+        else M[u] = ld4(ra.m + p.tile0 + o);
+        VF[u] = ld4(ra.v_fresh + p.tile0 + o);
+        VZ[u] = ld4(ra.v_frozen + p.tile0 + o);
+      }
     }
   }
-  if (uniform) {
-    const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+
+  // Tile inside layer l0: updates and stores v_fresh, returns the thread's max of v_frozen/v_fresh.
+  // VZ keeps v_frozen.
+  // ss, s_prev: new and previous server scale of the chunk; kt: k of the layer (1 without HAS_K).
+  __device__ __forceinline__ float uniform_pass(const RatioArgs& ra, const TilePos& p, float ss,
+                                                float s_prev, float kt) {
+    const int o0 = threadIdx.x * 4;
     const float sp = HAS_K ? ss / kt : ss;
     float t_same = 0.0f, t_diff = 0.0f;
     if (PACKED_M) {
-      const float bm = beta1 * (HAS_K ? s_prev / kt : s_prev);
-      const float g_same = (sp - bm) / omb1;    // new and old momentum of equal sign
-      const float g_diff = (sp - (-bm)) / omb1; // of opposite sign
-      t_same = omb2 * (g_same * g_same);
-      t_diff = omb2 * (g_diff * g_diff);
+      const float bm = ra.beta1 * (HAS_K ? s_prev / kt : s_prev);
+      const float g_same = (sp - bm) / ra.omb1;     // new and old momentum of equal sign
+      const float g_diff = (sp - (-bm)) / ra.omb1;  // of opposite sign
+      t_same = ra.omb2 * (g_same * g_same);
+      t_diff = ra.omb2 * (g_diff * g_diff);
     }
     float r = 0.0f;
 #pragma unroll
@@ -600,21 +615,27 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
             t = (((NB[u] ^ OB[u]) >> k) & 1u) ? t_diff : t_same;
           } else {
             const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-            const float gr = (mt - beta1 * M[u][k]) / omb1;
-            t = omb2 * (gr * gr);
+            const float gr = (mt - ra.beta1 * M[u][k]) / ra.omb1;
+            t = ra.omb2 * (gr * gr);
           }
-          vf[k] = beta2 * VF[u][k] + t;
+          vf[k] = ra.beta2 * VF[u][k] + t;
           const float q = VZ[u][k] / vf[k];
           if (q > r) r = q;
         }
-        st4(v_fresh + p.tile0 + o, vf);
+        st4(ra.v_fresh + p.tile0 + o, vf);
       }
     }
-    r = block_max(r, lds);
-    if (threadIdx.x == 0) seg_max[tile_seg0[blockIdx.x]] = r;
-  } else {
-    const int64_t N = lt.off[L];
-    // quotient of every element (kept in VZ), then one workgroup max per (tile, layer) segment
+    return r;
+  }
+
+  // Tile that meets a layer boundary or the end of the parameters: element by element, leaving
+  // the padding and the layers with skip[l] != 0 alone.  VZ is overwritten by the quotients
+  // (0 where nothing was computed).
+  __device__ __forceinline__ void element_pass(const RatioArgs& ra, const LayerTab& lt,
+                                               const TilePos& p, int l0, float ss, float s_prev,
+                                               const unsigned char* __restrict__ skip) {
+    const int o0 = threadIdx.x * 4;
+    const int64_t N = lt.off[lt.L];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int o = u * SPAN + o0;
@@ -626,57 +647,118 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(
           float q = 0.0f;
           if (i < N) {
             l = walk_layer(l, i, lt.off);
-            const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
-            const float sp = HAS_K ? ss / kk : ss;
-            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-            float bmk;
-            if (PACKED_M) {
-              const float b = beta1 * (HAS_K ? s_prev / kk : s_prev);
-              bmk = ((OB[u] >> k) & 1u) ? b : -b;
-            } else {
-              bmk = beta1 * M[u][k];
+            if (!(skip && skip[l])) {
+              const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
+              const float sp = HAS_K ? ss / kk : ss;
+              const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+              float bmk;
+              if (PACKED_M) {
+                const float b = ra.beta1 * (HAS_K ? s_prev / kk : s_prev);
+                bmk = ((OB[u] >> k) & 1u) ? b : -b;
+              } else {
+                bmk = ra.beta1 * M[u][k];
+              }
+              const float gr = (mt - bmk) / ra.omb1;
+              const float vf = ra.beta2 * VF[u][k] + ra.omb2 * (gr * gr);
+              ra.v_fresh[i] = vf;
+              q = VZ[u][k] / vf;
             }
-            const float gr = (mt - bmk) / omb1;
-            const float vf = beta2 * VF[u][k] + omb2 * (gr * gr);
-            v_fresh[i] = vf;
-            q = VZ[u][k] / vf;
           }
           VZ[u][k] = q;
         }
       }
     }
-    const int s0 = tile_seg0[blockIdx.x], s1 = tile_seg0[blockIdx.x + 1];
-    for (int s = s0; s < s1; ++s) {
-      const int l = seg_layer[s];
-      const int64_t a = lt.off[l], b = lt.off[l + 1];
-      float r = 0.0f;
+  }
+
+  // After element_pass: the thread's max of the quotients of elements in [a, b).
+  __device__ __forceinline__ float segment_max(const TilePos& p, int64_t a, int64_t b) const {
+    const int o0 = threadIdx.x * 4;
+    float r = 0.0f;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int o = u * SPAN + o0;
-        if (o < p.len) {
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) {
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int64_t i = p.tile0 + o + k;
-            if (i >= a && i < b && VZ[u][k] > r) r = VZ[u][k];
-          }
+        for (int k = 0; k < 4; ++k) {
+          const int64_t i = p.tile0 + o + k;
+          if (i >= a && i < b && VZ[u][k] > r) r = VZ[u][k];
         }
       }
+    }
+    return r;
+  }
+};
+
+template <int U, bool HAS_K, bool PACKED_M>
+__global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __restrict__ seg_max,
+                                                       int64_t n_c, int tpc, LayerTab lt,
+                                                       const int* __restrict__ tile_seg0,
+                                                       const int* __restrict__ seg_layer,
+                                                       LayerSel sel) {
+  constexpr int TILE = SPAN * U;
+  __shared__ float lds[BLOCK / WAVE];
+  const TilePos p =
+      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
+  const int l0 = lt.first_layer[p.t];
+  if (l0 >= lt.L) return;  // tile lies in the padding (it has no segment)
+  // every scalar the tile needs is requested before the streaming loads, so that nothing is
+  // looked up after they return (these workgroups are short: latency counts)
+  const float ss = ra.sscales[p.c];
+  const float s_prev = PACKED_M ? ra.pm.scales[p.c] : 0.0f;
+  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const int64_t l0_end = lt.off[l0 + 1];
+  const bool skip0 = sel.skip && sel.skip[l0];
+  const int s0 = tile_seg0[p.t];
+  RatioTile<U, HAS_K, PACKED_M> rt;
+  rt.load(ra, p);
+  const bool uniform = (p.tile0 + p.len <= l0_end);
+  if (uniform && skip0) return;
+  if (uniform) {
+    float r = rt.uniform_pass(ra, p, ss, s_prev, kt);
+    r = block_max(r, lds);
+    if (threadIdx.x == 0) seg_max[s0] = r;
+  } else {
+    rt.element_pass(ra, lt, p, l0, ss, s_prev, sel.skip);
+    const int s1 = tile_seg0[p.t + 1];
+    for (int s = s0; s < s1; ++s) {
+      const int l = seg_layer[s];
+      if (sel.skip && sel.skip[l]) continue;
+      float r = rt.segment_max(p, lt.off[l], lt.off[l + 1]);
       r = block_max(r, lds);
       if (threadIdx.x == 0) seg_max[s] = r;
     }
   }
 }
 
-// K6  per layer: max over the layer's segments (0 for an empty layer), then Algorithm 1 lines 18-20.
+// Algorithm 1 lines 18-20 for one layer given the raw ratio (thread 0 of a workgroup).
+__device__ __forceinline__ float ratio_clip_commit(float r, int l, const float* __restrict__ c_avg,
+                                                   float* __restrict__ r_prev,
+                                                   float* __restrict__ coeff_c, float one_m_thr,
+                                                   float one_p_thr, float r_min, float r_max) {
+  const float rp = r_prev[l];
+  const float lo = one_m_thr * rp, hi = one_p_thr * rp;
+  r = (r > lo) ? r : lo;
+  r = (r < hi) ? r : hi;
+  r = (r > r_min) ? r : r_min;
+  r = (r < r_max) ? r : r_max;
+  r_prev[l] = r;
+  const float c = r * c_avg[l];
+  coeff_c[l] = c;
+  return c;
+}
+
+// K6  per layer: max over the layer's segments (0 for an empty layer), then lines 18-20.
 __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
                                                             const int* __restrict__ layer_seg0,
                                                             const float* __restrict__ c_avg,
                                                             float* __restrict__ r_prev,
                                                             float* __restrict__ coeff_c,
                                                             float one_m_thr, float one_p_thr,
-                                                            float r_min, float r_max) {
+                                                            float r_min, float r_max,
+                                                            const unsigned char* __restrict__ skip) {
   __shared__ float lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
+  if (skip && skip[l]) return;
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   float r = 0.0f;
   for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
@@ -684,88 +766,115 @@ __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restr
     if (q > r) r = q;
   }
   r = block_max<FBLOCK>(r, lds);
-  if (threadIdx.x == 0) {
-    const float rp = r_prev[l];
-    const float lo = one_m_thr * rp, hi = one_p_thr * rp;
-    r = (r > lo) ? r : lo;
-    r = (r < hi) ? r : hi;
-    r = (r > r_min) ? r : r_min;
-    r = (r < r_max) ? r : r_max;
-    r_prev[l] = r;
-    coeff_c[l] = r * c_avg[l];
-  }
+  if (threadIdx.x == 0)
+    (void)ratio_clip_commit(r, l, c_avg, r_prev, coeff_c, one_m_thr, one_p_thr, r_min, r_max);
 }
 
 // ---------------------------------------------------------------------------------------------
 // K7  x <- x - (lr*c_l) * m_t/(sqrt(v_frozen)+eta);  m <- m_t (when WRITE_M)
 //     (Algorithm 1 lines 13, 21)
 // ---------------------------------------------------------------------------------------------
+struct ApplyArgs {
+  const uint32_t* __restrict__ packed;
+  const float* __restrict__ sscales;
+  const float* __restrict__ v_frozen;
+  float* __restrict__ x;
+  float* __restrict__ m;              // written when WRITE_M
+  const float* __restrict__ coeff_c;
+  float lr, eta;
+};
+
+// Tile inside layer l0 with coefficient c: update from registers.
 template <int U, bool HAS_K, bool WRITE_M>
-__global__ __launch_bounds__(BLOCK) void k_decompress_apply(
-    const uint32_t* __restrict__ packed, const float* __restrict__ sscales,
-    const float* __restrict__ v_frozen, float* __restrict__ x, float* __restrict__ m,
-    const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, LayerTab lt) {
-  constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = lt.first_layer[blockIdx.x];
-  const int L = lt.L;
-  if (l0 >= L) return;
+__device__ __forceinline__ void apply_uniform(const ApplyArgs& aa, const TilePos& p, float ss,
+                                              float kt, float c, const unsigned int (&NB)[U],
+                                              const v4f (&VZ)[U], const v4f (&X)[U]) {
   const int o0 = threadIdx.x * 4;
-  const float ss = sscales[p.c];
-  const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
-  unsigned int NB[U];
-  v4f X[U], VZ[U];
+  const float sp = HAS_K ? ss / kt : ss;
+  const float a = aa.lr * c;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
     if (o < p.len) {
-      NB[u] = load_nibble(packed, p.tile0 + u * SPAN);
-      VZ[u] = ld4(v_frozen + p.tile0 + o);
-      X[u] = ld4(x + p.tile0 + o);
+      v4f xn, mn;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+        const float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
+        xn[k] = X[u][k] - a * uu;
+        mn[k] = mt;
+      }
+      st4(aa.x + p.tile0 + o, xn);
+      if (WRITE_M) st4(aa.m + p.tile0 + o, mn);
     }
   }
-  if (uniform) {
-    const float sp = HAS_K ? ss / lt.mom_scale[l0] : ss;
-    const float a = lr * coeff_c[l0];
+}
+
+// Tile that meets a layer boundary: element by element, coefficients read from coeff_c.
+template <int U, bool HAS_K, bool WRITE_M>
+__device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerTab& lt,
+                                               const TilePos& p, int l0, float ss,
+                                               const unsigned char* __restrict__ skip,
+                                               bool only_skipped, const unsigned int (&NB)[U],
+                                               const v4f (&VZ)[U], const v4f (&X)[U]) {
+  const int o0 = threadIdx.x * 4;
+  const int64_t N = lt.off[lt.L];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        v4f xn, mn;
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      int l = l0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-          const float uu = mt / (sqrtf(VZ[u][k]) + eta);
-          xn[k] = X[u][k] - a * uu;
-          mn[k] = mt;
-        }
-        st4(x + p.tile0 + o, xn);
-        if (WRITE_M) st4(m + p.tile0 + o, mn);
-      }
-    }
-  } else {
-    const int64_t N = lt.off[L];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
-      if (o < p.len) {
-        int l = l0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int64_t i = p.tile0 + o + k;
-          if (i < N) {
-            l = walk_layer(l, i, lt.off);
+      for (int k = 0; k < 4; ++k) {
+        const int64_t i = p.tile0 + o + k;
+        if (i < N) {
+          l = walk_layer(l, i, lt.off);
+          const bool sk = skip && skip[l];
+          if (sk == only_skipped) {
             const float sp = HAS_K ? ss / lt.mom_scale[l] : ss;
-            const float a = lr * coeff_c[l];
+            const float a = aa.lr * aa.coeff_c[l];
             const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-            const float uu = mt / (sqrtf(VZ[u][k]) + eta);
-            x[i] = X[u][k] - a * uu;
-            if (WRITE_M) m[i] = mt;
+            const float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
+            aa.x[i] = X[u][k] - a * uu;
+            if (WRITE_M) aa.m[i] = mt;
           }
         }
       }
     }
   }
+}
+
+template <int U, bool HAS_K, bool WRITE_M>
+__global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_t n_c, int tpc,
+                                                            LayerTab lt, LayerSel sel) {
+  constexpr int TILE = SPAN * U;
+  const TilePos p =
+      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
+  const int l0 = lt.first_layer[p.t];
+  if (l0 >= lt.L) return;
+  // scalars first (see k_ratios_pass), then the streaming loads
+  const float ss = aa.sscales[p.c];
+  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const float c0 = aa.coeff_c[l0];
+  const int64_t l0_end = lt.off[l0 + 1];
+  const bool skip0 = sel.skip && sel.skip[l0];
+  const int o0 = threadIdx.x * 4;
+  unsigned int NB[U];
+  v4f X[U], VZ[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    NB[u] = 0u; X[u] = 0.0f; VZ[u] = 0.0f;
+    if (o < p.len) {
+      NB[u] = load_nibble(aa.packed, p.tile0 + u * SPAN);
+      VZ[u] = ld4(aa.v_frozen + p.tile0 + o);
+      X[u] = ld4(aa.x + p.tile0 + o);
+    }
+  }
+  const bool uniform = (p.tile0 + p.len <= l0_end);
+  if (uniform && skip0) return;
+  if (uniform) apply_uniform<U, HAS_K, WRITE_M>(aa, p, ss, kt, c0, NB, VZ, X);
+  else apply_elements<U, HAS_K, WRITE_M>(aa, lt, p, l0, ss, sel.skip, false, NB, VZ, X);
 }
 
 // Dense view of a momentum held in 1-bit form: m[i] = (bit ? s_c : -s_c)/k_l for i < N (the
@@ -774,8 +883,8 @@ template <int U, bool HAS_K>
 __global__ __launch_bounds__(BLOCK) void k_momentum_dense(PackedMom pm, float* __restrict__ m,
                                                           int64_t n_c, int tpc, LayerTab lt) {
   constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = lt.first_layer[blockIdx.x];
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
+  const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
@@ -829,8 +938,8 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = lt.first_layer[blockIdx.x];
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
+  const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
@@ -856,7 +965,7 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
       V[u][k] = beta2 * V[u][k] + omb2 * (G[u][k] * G[u][k]);
     }
   }
-  const int s0 = tile_seg0[blockIdx.x];
+  const int s0 = tile_seg0[p.t];
   if (uniform) {
     double sx = 0.0, su = 0.0;
 #pragma unroll
@@ -895,7 +1004,7 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
         }
       }
     }
-    const int s1 = tile_seg0[blockIdx.x + 1];
+    const int s1 = tile_seg0[p.t + 1];
     for (int s = s0; s < s1; ++s) {
       const int l = seg_layer[s];
       const int64_t a = lt.off[l], b = lt.off[l + 1];
@@ -956,8 +1065,8 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
     const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, float wd,
     LayerTab lt) {
   constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = lt.first_layer[blockIdx.x];
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
+  const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
@@ -1022,8 +1131,8 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_sumsq(const float* __restric
                                                           const int* __restrict__ seg_layer) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc);
-  const int l0 = lt.first_layer[blockIdx.x];
+  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
+  const int l0 = lt.first_layer[p.t];
   if (l0 >= lt.L) return;
   const int o0 = threadIdx.x * 4;
   v4f M[U];
@@ -1033,7 +1142,7 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_sumsq(const float* __restric
     M[u] = 0.0f;
     if (o < p.len) M[u] = ld4(m + p.tile0 + o);
   }
-  const int s0 = tile_seg0[blockIdx.x], s1 = tile_seg0[blockIdx.x + 1];
+  const int s0 = tile_seg0[p.t], s1 = tile_seg0[p.t + 1];
   for (int s = s0; s < s1; ++s) {
     const int l = seg_layer[s];
     const int64_t a = lt.off[l], b = lt.off[l + 1];

@@ -215,6 +215,72 @@ ob_status momentum_source(const ob_lamb_state* st, bool* packed, PackedMom* pm) 
   return OB_OK;
 }
 
+// launches of the ratio pass / finalize / update kernels over the layers selected by `sel`
+// (all layers when sel has no list): shared by the separate calls and by ob_lamb_ratios_apply.
+void launch_ratios(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                          const float* server_scales, bool packed_m, const PackedMom& pm, LayerSel sel,
+                          int n_launch_tiles) {
+  RatioArgs ra;
+  ra.packed = packed_all; ra.sscales = server_scales; ra.m = st->m; ra.pm = pm;
+  ra.v_fresh = st->v_fresh; ra.v_frozen = st->v_frozen;
+  ra.beta1 = ctx->beta1; ra.omb1 = ctx->omb1; ra.beta2 = ctx->beta2; ra.omb2 = ctx->omb2;
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
+              n_launch_tiles, ra, ctx->d_seg_max, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
+              sel);
+  });
+  OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
+              ctx->d_layer_seg0, st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr,
+              ctx->r_min, ctx->r_max, sel.skip);
+}
+
+void launch_apply(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                         const float* server_scales, float lr, LayerSel sel, int n_launch_tiles) {
+  ApplyArgs aa;
+  aa.packed = packed_all; aa.sscales = server_scales; aa.v_frozen = st->v_frozen; aa.x = st->x;
+  aa.m = st->m; aa.coeff_c = st->coeff_c; aa.lr = lr; aa.eta = ctx->eta;
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch2(st->mom_scale != nullptr, st->m != nullptr, [&](auto hk, auto wm) {
+    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_MAIN, decltype(hk)::value, decltype(wm)::value>),
+              n_launch_tiles, aa, ctx->n_c, ctx->tpc, lt, sel);
+  });
+}
+
+// commit of the 1-bit momentum (see ob_lamb_decompress_apply)
+void commit_packed_momentum(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                                   const uint32_t* packed_all, const float* server_scales) {
+  if (!(st->m_packed && st->m_packed != packed_all)) return;
+  la.begin(KID_COPY);
+  if (la.ok)
+    la.ok = hip_ok(ctx, hipMemcpyAsync(st->m_packed, packed_all, (size_t)ctx->n_pad / 8,
+                                       hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync") &&
+            hip_ok(ctx, hipMemcpyAsync(st->m_scales, server_scales, (size_t)ctx->W * sizeof(float),
+                                       hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
+  la.end("copy");
+}
+
+ob_status check_ratios_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                   const float* server_scales) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->v_fresh); REQUIRE_PTR(st->v_frozen);
+  if (!server_scales || !st->c_avg || !st->r_prev || !st->coeff_c) return OB_ERR_NULL;
+  return OB_OK;
+}
+
+ob_status check_apply_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                  const float* server_scales, float lr) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->x); REQUIRE_PTR(st->v_frozen);
+  if (!server_scales || !st->coeff_c) return OB_ERR_NULL;
+  if (!std::isfinite(lr)) return OB_ERR_ARG;
+  if (st->m && misaligned(st->m)) return OB_ERR_ALIGN;
+  if (!st->m && !st->m_packed) return OB_ERR_NULL;  // the momentum has to be committed somewhere
+  if (st->m_packed && !st->m_scales) return OB_ERR_NULL;
+  if (st->m_packed && misaligned(st->m_packed)) return OB_ERR_ALIGN;
+  return OB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -475,50 +541,21 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
 
 ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, void* hip_stream) {
-  if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->v_fresh); REQUIRE_PTR(st->v_frozen);
-  if (!server_scales || !st->c_avg || !st->r_prev || !st->coeff_c) return OB_ERR_NULL;
+  if (ob_status s = check_ratios_args(ctx, st, packed_all, server_scales)) return s;
   bool packed_m = false;
   PackedMom pm;
   if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
   Launch la(ctx, hip_stream);
-  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
-              ctx->n_tiles, packed_all, server_scales, st->m, pm, st->v_fresh, st->v_frozen, ctx->d_seg_max,
-              ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2, lt, ctx->d_tile_seg0,
-              ctx->d_seg_layer);
-  });
-  OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max, ctx->d_layer_seg0,
-            st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr, ctx->r_min, ctx->r_max);
+  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, LayerSel{nullptr, nullptr}, ctx->n_tiles);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
 ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                    const float* server_scales, float lr, void* hip_stream) {
-  if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->x); REQUIRE_PTR(st->v_frozen);
-  if (!server_scales || !st->coeff_c) return OB_ERR_NULL;
-  if (!std::isfinite(lr)) return OB_ERR_ARG;
-  if (st->m && misaligned(st->m)) return OB_ERR_ALIGN;
-  if (!st->m && !st->m_packed) return OB_ERR_NULL;  // the momentum has to be committed somewhere
-  if (st->m_packed && (!st->m_scales || misaligned(st->m_packed))) return st->m_scales ? OB_ERR_ALIGN : OB_ERR_NULL;
+  if (ob_status s = check_apply_args(ctx, st, packed_all, server_scales, lr)) return s;
   Launch la(ctx, hip_stream);
-  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  dispatch2(st->mom_scale != nullptr, st->m != nullptr, [&](auto hk, auto wm) {
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_MAIN, decltype(hk)::value, decltype(wm)::value>),
-              ctx->n_tiles, packed_all, server_scales, st->v_frozen, st->x, st->m, st->coeff_c, ctx->n_c,
-              ctx->tpc, lr, ctx->eta, lt);
-  });
-  if (st->m_packed && st->m_packed != packed_all) {  // commit the 1-bit form unless it already is in place
-    la.begin(KID_COPY);
-    if (la.ok)
-      la.ok = hip_ok(ctx, hipMemcpyAsync(st->m_packed, packed_all, (size_t)ctx->n_pad / 8,
-                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync") &&
-              hip_ok(ctx, hipMemcpyAsync(st->m_scales, server_scales, (size_t)ctx->W * sizeof(float),
-                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
-    la.end("copy");
-  }
+  launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles);
+  commit_packed_momentum(la, ctx, st, packed_all, server_scales);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
