@@ -2,7 +2,7 @@
 """Benchmark of the 1-bit LAMB compression-stage optimizer step on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input already resident in
-HBM: compress_local -> (gather copy) -> server_reduce -> layer_ratios -> decompress_apply.
+HBM: compress_local -> (gather copy) -> server_reduce -> ratios_apply (= layer_ratios + decompress_apply).
 Prints ONE JSON line (see the design doc for the fields).  `--gpus N` with N > 1 is refused: this
 build measures one GPU's share of the data-parallel step and uses no collectives.
 """
@@ -27,12 +27,14 @@ KERNEL_BYTES = {
         "momentum_z_sumsq": (16.0, "n_pad"),     # R g, m, err (12) + W z (4)
         "ratios_pass": (16.125, "n_pad"),        # R bits, m, v_fresh, v_frozen (12.125) + W v_fresh (4)
         "decompress_apply": (16.125, "n_pad"),   # R bits, v_frozen, x (8.125) + W x, m (8)
+        "ratios_apply_resident": (28.125, "fused"),  # R bits, m, v_fresh, v_frozen, x (16.125) + W v_fresh, x, m (12)
     },
     "packed": {  # momentum read from last step's sign words, never written as fp32
         "compress_resident": (12.25, "n_pad"),   # R g, err (8) + m bits (1/8) + W err (4) + bits (1/8)
         "momentum_z_sumsq": (12.125, "n_pad"),
         "ratios_pass": (12.25, "n_pad"),         # R bits, m bits (1/4), v_fresh, v_frozen (8) + W v_fresh (4)
         "decompress_apply": (12.125, "n_pad"),   # R bits, v_frozen, x (8.125) + W x (4)
+        "ratios_apply_resident": (20.25, "fused"),   # R bits x2, v_fresh, v_frozen, x (12.25) + W v_fresh, x (8)
     },
     "both": {
         "sign_pack_error": (8.125, "n_pad"),     # R z (4) + W err (4) + W bits (1/8)
@@ -51,12 +53,14 @@ def compulsory_step_bytes_per_param(W):
     return 16.125 + 0.125 + 8.125 / W + 16.125 + 12.0
 
 
-def algorithmic_step_bytes_per_param(W, mode):
-    """What the three N-sized calls as implemented must move (each call's inputs once, outputs
-    once), plus the server call."""
+def algorithmic_step_bytes_per_param(W, mode, fused_frac=0.0):
+    """What the N-sized calls as implemented must move (each call's inputs once, outputs once),
+    plus the server call.  fused_frac: share of the parameters whose ratio pass and update run as
+    one kernel (ob_lamb_ratios_apply), reading v_frozen and the sign words once."""
     k = KERNEL_BYTES[mode]
-    return (k["compress_resident"][0] + k["ratios_pass"][0] + k["decompress_apply"][0]
-            + 0.125 + 8.125 / W)
+    separate = k["ratios_pass"][0] + k["decompress_apply"][0]
+    return (k["compress_resident"][0] + fused_frac * k["ratios_apply_resident"][0]
+            + (1.0 - fused_frac) * separate + 0.125 + 8.125 / W)
 
 
 def main():
@@ -72,6 +76,9 @@ def main():
                     help="only run a plain 1 GiB device copy 10 times (for scaling rocprofv3 "
                          "FETCH_SIZE/WRITE_SIZE readings) and exit")
     ap.add_argument("--mom-scale", action="store_true", help="with Appendix A.5.2 momentum scaling")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="ob_lamb_layer_ratios + ob_lamb_decompress_apply instead of the fused "
+                         "ob_lamb_ratios_apply")
     ap.add_argument("--dense-momentum", action="store_true",
                     help="keep the momentum as an fp32 array (default: the 1-bit form it has after "
                          "Algorithm 1 line 13; same results, 12 bytes/param less traffic)")
@@ -112,7 +119,7 @@ def main():
     mom_scale = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if args.mom_scale else None
     mode = "dense" if args.dense_momentum else "packed"
     ds = DeviceStep(pl.offsets, W, server_chunk, device="cuda:0", mom_scale=mom_scale,
-                    packed_momentum=(mode == "packed"), **hyper)
+                    packed_momentum=(mode == "packed"), fused_apply=not args.separate_calls, **hyper)
     ds.load_state(init_state(st, cfg))
     n_grads = 3
     grads = [gradient(st, cfg, t) for t in range(n_grads)]
@@ -149,20 +156,20 @@ def main():
 
     # per-call times (events on the launch stream) and per-kernel durations (library's own events)
     calls = {}
-    names = ["compress_local", "gather", "server_reduce", "layer_ratios", "decompress_apply"]
+    tail = ([("ratios_apply", lambda: ds.ratios_apply(lr))] if ds.fused_apply else
+            [("layer_ratios", ds.layer_ratios), ("decompress_apply", lambda: ds.decompress_apply(lr))])
     evs = []
     for t in range(args.profile_steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
         ds.begin_step()
-        e[0].record(); ds.compress_local(grads[t % n_grads])
-        e[1].record(); ds.gather()
-        e[2].record(); ds.server_reduce()
-        e[3].record(); ds.layer_ratios()
-        e[4].record(); ds.decompress_apply(lr)
-        e[5].record()
+        seq = [("compress_local", lambda: ds.compress_local(grads[t % n_grads])), ("gather", ds.gather),
+               ("server_reduce", ds.server_reduce)] + tail
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(len(seq) + 1)]
+        for i, (_, fn) in enumerate(seq):
+            e[i].record(); fn()
+        e[len(seq)].record()
         evs.append(e)
     torch.cuda.synchronize()
-    for i, nm in enumerate(names):
+    for i, (nm, _) in enumerate(seq):
         calls[nm] = round(float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])), 4)
 
     ob.ob_lamb_profile_enable(ds.ctx, True)
@@ -174,7 +181,12 @@ def main():
     KB = dict(KERNEL_BYTES["both"])
     KB.update(KERNEL_BYTES[mode])
     KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
-    units = {"n_pad": ds.n_pad, "n_c": ds.n_c}
+    fused_params = ob.ob_lamb_fused_params(ds.ctx) if ds.fused_apply else 0
+    units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params}
+    if ds.fused_apply:   # the plain ratio/update kernels then cover only the remaining layers
+        for k in ("ratios_pass", "decompress_apply"):
+            KB[k] = (KB[k][0], "rest")
+        units["rest"] = ds.n_pad - fused_params
     for k, v in kern.items():
         if k in KB:
             bpe, unit = KB[k]
@@ -194,7 +206,7 @@ def main():
                 "traffic": traffic}
 
     step_bytes = compulsory_step_bytes_per_param(W) * ds.n_pad
-    algo_bytes = algorithmic_step_bytes_per_param(W, mode) * ds.n_pad
+    algo_bytes = algorithmic_step_bytes_per_param(W, mode, fused_params / float(ds.n_pad)) * ds.n_pad
     out = {
         "metric": "1-bit LAMB compressed step: params/sec and % of HBM peak GB/s, 1 GPU",
         "value": round(pl.N / (ms_per_step * 1e-3), 1), "unit": "params/s",
@@ -204,6 +216,8 @@ def main():
         "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
                    "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
                    "mom_scale": bool(args.mom_scale), "momentum": mode,
+                   "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
+                   "fused_params": fused_params,
                    "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx)},
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),

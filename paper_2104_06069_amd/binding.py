@@ -65,6 +65,9 @@ def lib():
             "ob_lamb_server_reduce": (C.c_int, [vp, sp, vp, vp, vp, vp, vp]),
             "ob_lamb_layer_ratios": (C.c_int, [vp, sp, vp, vp, vp]),
             "ob_lamb_decompress_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
+            "ob_lamb_ratios_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
+            "ob_lamb_fused_layers": (i64, [vp]),
+            "ob_lamb_fused_params": (i64, [vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
@@ -171,6 +174,19 @@ def ob_lamb_decompress_apply(ctx, state, packed_all, server_scales, lr, stream=N
     _check(lib().ob_lamb_decompress_apply(ctx, C.byref(state), _addr(packed_all),
                                           _addr(server_scales), lr, _addr(stream)), ctx,
            "ob_lamb_decompress_apply")
+
+
+def ob_lamb_ratios_apply(ctx, state, packed_all, server_scales, lr, stream=None):
+    _check(lib().ob_lamb_ratios_apply(ctx, C.byref(state), _addr(packed_all), _addr(server_scales),
+                                      lr, _addr(stream)), ctx, "ob_lamb_ratios_apply")
+
+
+def ob_lamb_fused_layers(ctx):
+    return int(lib().ob_lamb_fused_layers(ctx))
+
+
+def ob_lamb_fused_params(ctx):
+    return int(lib().ob_lamb_fused_params(ctx))
 
 
 def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):

@@ -815,8 +815,8 @@ template <int U, bool HAS_K, bool WRITE_M>
 __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerTab& lt,
                                                const TilePos& p, int l0, float ss,
                                                const unsigned char* __restrict__ skip,
-                                               bool only_skipped, const unsigned int (&NB)[U],
-                                               const v4f (&VZ)[U], const v4f (&X)[U]) {
+                                               const unsigned int (&NB)[U], const v4f (&VZ)[U],
+                                               const v4f (&X)[U]) {
   const int o0 = threadIdx.x * 4;
   const int64_t N = lt.off[lt.L];
 #pragma unroll
@@ -829,8 +829,7 @@ __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerT
         const int64_t i = p.tile0 + o + k;
         if (i < N) {
           l = walk_layer(l, i, lt.off);
-          const bool sk = skip && skip[l];
-          if (sk == only_skipped) {
+          if (!(skip && skip[l])) {
             const float sp = HAS_K ? ss / lt.mom_scale[l] : ss;
             const float a = aa.lr * aa.coeff_c[l];
             const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
@@ -874,7 +873,129 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
   const bool uniform = (p.tile0 + p.len <= l0_end);
   if (uniform && skip0) return;
   if (uniform) apply_uniform<U, HAS_K, WRITE_M>(aa, p, ss, kt, c0, NB, VZ, X);
-  else apply_elements<U, HAS_K, WRITE_M>(aa, lt, p, l0, ss, sel.skip, false, NB, VZ, X);
+  else apply_elements<U, HAS_K, WRITE_M>(aa, lt, p, l0, ss, sel.skip, NB, VZ, X);
+}
+
+// ---------------------------------------------------------------------------------------------
+// K5+K6+K7 in one pass for the layers that fit on the device: Algorithm 1 lines 13-21 with
+// v_frozen and the sign words read once.  A workgroup runs the ratio pass on its tile, keeps
+// v_frozen and the signs in registers, arrives at its layer's barrier, fetches x while the layer
+// completes, and applies the update from registers once the layer's coefficient c_t is published.
+//
+// The kernel covers the tiles that lie inside ONE "eligible" layer (a layer that has such tiles and
+// whose tiles fill at most 80 % of the device's workgroup slots), listed in position order.  The
+// few tiles where an eligible layer meets its neighbours are handled by the plain kernels launched
+// before (ratio pass, which leaves the maxima of those segments in seg_max) and after (update).
+//
+// Per-layer barrier: like the per-chunk one above, but the payload of a segment is its fp32
+// maximum of v_frozen/v_fresh (order-independent); the last of the layer's listed tiles to arrive
+// reduces ALL of the layer's segment maxima, applies the two clips (lines 18-19), commits r_prev
+// and coeff_c and publishes c_t in flag[l].  counter[l] grows by n_listed[l] per launch.  The
+// dispatch-order argument of the chunk barrier applies per layer; all waits are bounded (errflag).
+// ---------------------------------------------------------------------------------------------
+struct LayerSync {
+  float* seg_max;               // [segments of this kernel's tiling]
+  const int* layer_seg0;        // [L+1] segments of each layer
+  const int* n_listed;          // [L] tiles of the layer that this kernel covers
+  unsigned long long* counter;  // [L]
+  unsigned long long* flag;     // [L] (epoch << 32) | bits of c_t
+  unsigned int* errflag;
+  unsigned int epoch;
+  int spin_limit;
+  const float* c_avg;
+  float* r_prev;
+  float* coeff_c;
+  float one_m_thr, one_p_thr, r_min, r_max;
+};
+
+// Publishes segment s (of layer l) with maximum r and arrives; if this was the layer's last
+// listed tile, finishes the layer.  All threads call; r is valid in thread 0.
+__device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, int s, float r, float* lds,
+                                             unsigned long long* bc) {
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&ls.seg_max[s], r, __ATOMIC_RELAXED, OB_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
+    const unsigned long long prev =
+        __hip_atomic_fetch_add(&ls.counter[l], 1ull, __ATOMIC_RELAXED, OB_AGENT);
+    *bc = (prev + 1ull == (unsigned long long)ls.epoch * (unsigned long long)ls.n_listed[l]) ? 1ull : 0ull;
+  }
+  __syncthreads();
+  const bool last = (*bc != 0ull);
+  __syncthreads();
+  if (last) {
+    const int s0 = ls.layer_seg0[l], s1 = ls.layer_seg0[l + 1];
+    float q = 0.0f;
+    for (int j = s0 + threadIdx.x; j < s1; j += BLOCK) {
+      const float v = __hip_atomic_load(&ls.seg_max[j], __ATOMIC_RELAXED, OB_AGENT);
+      if (v > q) q = v;
+    }
+    q = block_max(q, lds);
+    if (threadIdx.x == 0) {
+      const float c = ratio_clip_commit(q, l, ls.c_avg, ls.r_prev, ls.coeff_c, ls.one_m_thr,
+                                        ls.one_p_thr, ls.r_min, ls.r_max);
+      const unsigned long long f =
+          ((unsigned long long)ls.epoch << 32) | (unsigned long long)__float_as_uint(c);
+      __hip_atomic_store(&ls.flag[l], f, __ATOMIC_RELAXED, OB_AGENT);
+    }
+  }
+}
+
+// Waits (bounded) until layer l's coefficient of this launch is published; returns it to all threads.
+__device__ __forceinline__ float layer_wait(const LayerSync& ls, int l, unsigned long long* bc) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long f = 0ull;
+    for (int it = 0;; ++it) {
+      f = __hip_atomic_load(&ls.flag[l], __ATOMIC_RELAXED, OB_AGENT);
+      if ((unsigned int)(f >> 32) == ls.epoch) break;
+      if (it >= ls.spin_limit) {
+        atomicOr(ls.errflag, 1u);
+        break;
+      }
+      if ((it & 63) == 63 && __hip_atomic_load(ls.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
+      __builtin_amdgcn_s_sleep(2);
+    }
+    *bc = f;
+  }
+  __syncthreads();
+  return __uint_as_float((unsigned int)(*bc & 0xffffffffull));
+}
+
+// Instantiated for the momentum in 1-bit form only: with a dense momentum the extra array the
+// tile must hold costs more (spills or occupancy) than the second read of v_frozen saves, so the
+// host then takes the two-kernel path.  5 workgroups per CU (<= 96 VGPRs at U = 8) measured best:
+// 4 leaves too few workgroup slots next to the ones waiting at a barrier, 6 and more spill.
+#ifndef OB_LB_MINW
+#define OB_LB_MINW 5
+#endif
+template <int U, bool HAS_K>
+__global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
+    RatioArgs ra, ApplyArgs aa, LayerSync ls, int64_t n_c, int tpc, LayerTab lt,
+    const int* __restrict__ tile_seg0, const int* __restrict__ tile_list) {
+  constexpr int TILE = SPAN * U;
+  __shared__ float lds[BLOCK / WAVE];
+  __shared__ unsigned long long bc;
+  const TilePos p = tile_pos<TILE>(n_c, tpc, tile_list[blockIdx.x]);
+  const int l0 = lt.first_layer[p.t];  // the (eligible) layer the tile lies in
+  const float ss = ra.sscales[p.c];
+  const float s_prev = ra.pm.scales[p.c];
+  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const int s0 = tile_seg0[p.t];       // the tile's only segment
+  const int o0 = threadIdx.x * 4;
+  RatioTile<U, HAS_K, true> rt;
+  rt.load(ra, p);
+  float r = rt.uniform_pass(ra, p, ss, s_prev, kt);
+  r = block_max(r, lds);
+  layer_arrive(ls, l0, s0, r, lds, &bc);
+  v4f X[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {  // x is fetched while the layer completes
+    const int o = u * SPAN + o0;
+    X[u] = 0.0f;
+    if (o < p.len) X[u] = ld4(aa.x + p.tile0 + o);
+  }
+  const float c = layer_wait(ls, l0, &bc);
+  apply_uniform<U, HAS_K, false>(aa, p, ss, kt, c, rt.NB, rt.VZ, X);
 }
 
 // Dense view of a momentum held in 1-bit form: m[i] = (bit ? s_c : -s_c)/k_l for i < N (the

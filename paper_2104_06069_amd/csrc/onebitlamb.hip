@@ -34,6 +34,11 @@ constexpr int G_RES = 2;    // the single-pass kernel issues its loads G_RES acc
 constexpr int TILE_MAIN = SPAN * U_MAIN;
 constexpr int TILE_SRV = SPAN * U_SRV;
 constexpr int TILE_RES = SPAN * U_RES;
+#ifndef OB_U_LB
+#define OB_U_LB 8
+#endif
+constexpr int U_LB = OB_U_LB;  // ... in the fused ratio+update kernel (v_frozen and signs stay in registers)
+constexpr int TILE_LB = SPAN * U_LB;
 
 enum KernelId {
   KID_MOMENTUM_Z = 0,
@@ -46,6 +51,7 @@ enum KernelId {
   KID_RATIOS_PASS,
   KID_RATIOS_FINALIZE,
   KID_APPLY,
+  KID_RATIOS_APPLY_RESIDENT,
   KID_MOMENTUM_DENSE,
   KID_MOMENTUM_SCALE,
   KID_WARMUP_MOMENTS,
@@ -58,7 +64,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "ratios_apply_resident", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "fill",             "copy"};
 
 struct ProfRec {
@@ -101,6 +107,29 @@ struct ob_lamb_ctx {
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
   unsigned int epoch = 0;
   int spin_limit = 1 << 20;
+  // fused ratio+update (k_ratios_apply_resident): its own tiling and the split of the layers into
+  // those it handles ("eligible": the layer's tiles fit on the device) and the rest
+  bool fused = false;             // at least one layer is eligible
+  int tpc_lb = 0, n_tiles_lb = 0, n_segs_lb = 0;
+  int n_fused_tiles = 0;          // TILE_LB tiles inside one eligible layer (the fused kernel's)
+  int n_bound_tiles = 0;          // TILE_LB tiles where an eligible layer meets a boundary
+  int n_plain_tiles = 0;          // TILE_MAIN tiles that hold a segment of a non-eligible layer
+  int64_t n_fused_layers = 0;
+  int64_t n_fused_params = 0;     // parameters in the eligible layers
+  int* d_first_layer_lb = nullptr;
+  int* d_tile_seg0_lb = nullptr;
+  int* d_seg_layer_lb = nullptr;
+  int* d_layer_seg0_lb = nullptr;
+  int* d_fused_tiles = nullptr;
+  int* d_bound_tiles = nullptr;
+  int* d_n_listed = nullptr;      // [L] fused-kernel tiles of each layer
+  int* d_plain_tiles = nullptr;
+  unsigned char* d_skip_plain = nullptr;   // [L] 1 for eligible layers (the plain kernels skip them)
+  unsigned char* d_skip_fused = nullptr;   // [L] 1 for the other layers
+  float* d_seg_max_lb = nullptr;           // [n_segs_lb]
+  unsigned long long* d_counter_lb = nullptr;  // [L]
+  unsigned long long* d_flag_lb = nullptr;     // [L]
+  unsigned int epoch_lb = 0;
   // diagnostics
   bool profile = false;
   std::vector<ProfRec> prof;
@@ -213,6 +242,48 @@ ob_status momentum_source(const ob_lamb_state* st, bool* packed, PackedMom* pm) 
   pm->bits = st->m_packed;
   pm->scales = st->m_scales;
   return OB_OK;
+}
+
+// Tables of one tiling of the padded buffer (tiles of `tile` elements inside each chunk): the layer
+// of each tile's first element (L = padding), the (tile, layer) segments in position order and
+// their grouping by layer.
+struct Tiling {
+  int64_t tpc = 0, n_tiles = 0;
+  std::vector<int> first, tile_seg0, seg_layer, layer_seg0;
+};
+
+bool build_tiling(int64_t tile, int64_t n_c, int64_t W, int64_t L, const std::vector<int64_t>& h_off,
+                  Tiling* out) {
+  out->tpc = (n_c + tile - 1) / tile;
+  out->n_tiles = out->tpc * W;
+  if (out->n_tiles > 0x7fffffff) return false;
+  out->first.resize((size_t)out->n_tiles);
+  out->tile_seg0.resize((size_t)out->n_tiles + 1);
+  out->seg_layer.clear();
+  out->layer_seg0.assign((size_t)L + 1, 0);
+  for (int64_t t = 0; t < out->n_tiles; ++t) {
+    const int64_t c = t / out->tpc, b = t % out->tpc;
+    const int64_t tile0 = c * n_c + b * tile;
+    const int64_t tile1 = std::min(tile0 + tile, (c + 1) * n_c);
+    // first layer: the non-empty layer that holds tile0 (binary search on the offsets)
+    int64_t lo = 0, hi = L + 1;  // h_off[lo] <= tile0 < h_off[hi]
+    while (hi - lo > 1) {
+      const int64_t mid = (lo + hi) / 2;
+      if (h_off[(size_t)mid] <= tile0) lo = mid; else hi = mid;
+    }
+    out->first[(size_t)t] = (int)lo;  // lo == L when tile0 >= N
+    out->tile_seg0[(size_t)t] = (int)out->seg_layer.size();
+    for (int64_t l = lo; l < L && h_off[(size_t)l] < tile1; ++l) {
+      const int64_t a = std::max(h_off[(size_t)l], tile0), e = std::min(h_off[(size_t)l + 1], tile1);
+      if (e > a) out->seg_layer.push_back((int)l);
+    }
+  }
+  out->tile_seg0[(size_t)out->n_tiles] = (int)out->seg_layer.size();
+  std::vector<int> count((size_t)L, 0);  // segments are ordered by position, hence grouped by layer
+  for (int l : out->seg_layer) ++count[(size_t)l];
+  for (int64_t l = 0; l < L; ++l)
+    out->layer_seg0[(size_t)l + 1] = out->layer_seg0[(size_t)l] + count[(size_t)l];
+  return true;
 }
 
 // launches of the ratio pass / finalize / update kernels over the layers selected by `sel`
@@ -342,46 +413,28 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   ctx->one_p_thr = 1.0f + ctx->r_thr;
   ctx->invW = 1.0f / (float)ctx->W;
 
-  const int64_t tpc = (ctx->n_c + TILE_MAIN - 1) / TILE_MAIN;
-  const int64_t n_tiles = tpc * ctx->W;
   const int64_t tpc_srv = (ctx->n_c + TILE_SRV - 1) / TILE_SRV;
-  if (n_tiles > 0x7fffffff || tpc_srv > 0x7fffffff) { delete ctx; return OB_ERR_ARG; }
-  ctx->tpc = (int)tpc;
-  ctx->n_tiles = (int)n_tiles;
+  if (tpc_srv > 0x7fffffff) { delete ctx; return OB_ERR_ARG; }
   ctx->tpc_srv = (int)tpc_srv;
 
-  // tile tables: layer of each tile's first element (L = padding) and the (tile, layer) segments
-  const int64_t* off = cfg->layer_offsets;
   std::vector<int64_t> h_off((size_t)L + 2);
-  for (int64_t l = 0; l <= L; ++l) h_off[(size_t)l] = off[l];
+  for (int64_t l = 0; l <= L; ++l) h_off[(size_t)l] = cfg->layer_offsets[l];
   h_off[(size_t)L + 1] = std::numeric_limits<int64_t>::max();
-  std::vector<int> first((size_t)n_tiles), tile_seg0((size_t)n_tiles + 1), seg_layer;
-  std::vector<int> layer_seg0((size_t)L + 1, 0);
-  for (int64_t t = 0; t < n_tiles; ++t) {
-    const int64_t c = t / tpc, b = t % tpc;
-    const int64_t tile0 = c * ctx->n_c + b * TILE_MAIN;
-    const int64_t tile1 = std::min(tile0 + TILE_MAIN, (c + 1) * ctx->n_c);
-    // first layer: the non-empty layer that holds tile0 (binary search on off)
-    int64_t lo = 0, hi = L + 1;  // h_off[lo] <= tile0 < h_off[hi]
-    while (hi - lo > 1) {
-      const int64_t mid = (lo + hi) / 2;
-      if (h_off[(size_t)mid] <= tile0) lo = mid; else hi = mid;
-    }
-    first[(size_t)t] = (int)lo;  // lo == L when tile0 >= N
-    tile_seg0[(size_t)t] = (int)seg_layer.size();
-    for (int64_t l = lo; l < L && off[l] < tile1; ++l) {
-      const int64_t a = std::max(off[l], tile0), e = std::min(off[l + 1], tile1);
-      if (e > a) seg_layer.push_back((int)l);
-    }
+  Tiling tm, tl;
+  if (!build_tiling(TILE_MAIN, ctx->n_c, ctx->W, L, h_off, &tm) ||
+      !build_tiling(TILE_LB, ctx->n_c, ctx->W, L, h_off, &tl)) {
+    delete ctx;
+    return OB_ERR_ARG;
   }
-  tile_seg0[(size_t)n_tiles] = (int)seg_layer.size();
-  ctx->n_segs = (int)seg_layer.size();
-  {
-    // segments are ordered by position, hence grouped by layer
-    std::vector<int> count((size_t)L, 0);
-    for (int l : seg_layer) ++count[(size_t)l];
-    for (int64_t l = 0; l < L; ++l) layer_seg0[(size_t)l + 1] = layer_seg0[(size_t)l] + count[(size_t)l];
-  }
+  const int64_t n_tiles = tm.n_tiles;
+  ctx->tpc = (int)tm.tpc;
+  ctx->n_tiles = (int)tm.n_tiles;
+  ctx->n_segs = (int)tm.seg_layer.size();
+  ctx->tpc_lb = (int)tl.tpc;
+  ctx->n_tiles_lb = (int)tl.n_tiles;
+  ctx->n_segs_lb = (int)tl.seg_layer.size();
+  const std::vector<int>&first = tm.first, &tile_seg0 = tm.tile_seg0, &seg_layer = tm.seg_layer,
+                        &layer_seg0 = tm.layer_seg0;
 
   // single-pass worker compression: its own (larger) tiles and the layer of each tile's start
   const int64_t tpc_res = (ctx->n_c + TILE_RES - 1) / TILE_RES;
@@ -413,6 +466,73 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }
+  // fused ratio+update: a layer is handled there when it has tiles that lie inside it and they all
+  // fit on the device at once (at most 80 % of the workgroup slots of that kernel); the plain
+  // kernels take the other layers (too large, smaller than a tile, or empty)
+  std::vector<unsigned char> skip_plain((size_t)L, 0), skip_fused((size_t)L, 1);
+  std::vector<int> fused_tiles, bound_tiles, plain_tiles, n_listed((size_t)L, 0);
+  if (ok) {
+    int per_cu = 0, cus = 0;
+    ok = hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                         &per_cu, k_ratios_apply_resident<U_LB, true>, BLOCK, 0),
+                "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
+         hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
+                "hipDeviceGetAttribute");
+    const int64_t slots = (int64_t)per_cu * cus;
+    const char* env = getenv("OB_LAMB_NO_FUSED_APPLY");
+    const bool allow = ok && !(env && env[0] == '1');
+    // OB_LAMB_FUSED_MAX_TILES=n lowers the limit (tests of the split between the two paths)
+    int64_t max_tiles = (4 * slots) / 5 - 8;
+    if (const char* mt = getenv("OB_LAMB_FUSED_MAX_TILES")) {
+      const long v = atol(mt);
+      if (v >= 0 && v < max_tiles) max_tiles = v;
+    }
+    // tiles of the fused kernel's tiling that lie inside one layer, per layer
+    auto inside_one_layer = [&](int64_t t) {
+      const int64_t c = t / tl.tpc, b = t % tl.tpc;
+      const int64_t tile0 = c * ctx->n_c + b * TILE_LB;
+      const int64_t tile1 = std::min(tile0 + (int64_t)TILE_LB, (c + 1) * ctx->n_c);
+      const int l = tl.first[(size_t)t];
+      return l < L && tile1 <= h_off[(size_t)l + 1];
+    };
+    for (int64_t t = 0; t < tl.n_tiles; ++t)
+      if (inside_one_layer(t)) ++n_listed[(size_t)tl.first[(size_t)t]];
+    for (int64_t l = 0; l < L; ++l) {
+      const bool elig = allow && n_listed[(size_t)l] >= 1 && n_listed[(size_t)l] <= max_tiles;
+      if (!elig) n_listed[(size_t)l] = 0;
+      skip_plain[(size_t)l] = elig ? 1 : 0;
+      skip_fused[(size_t)l] = elig ? 0 : 1;
+      ctx->n_fused_layers += elig ? 1 : 0;
+      ctx->n_fused_params += elig ? (h_off[(size_t)l + 1] - h_off[(size_t)l]) : 0;
+    }
+    ctx->fused = ctx->n_fused_layers > 0;
+    for (int64_t t = 0; t < tl.n_tiles; ++t) {
+      if (inside_one_layer(t)) {
+        if (skip_plain[(size_t)tl.first[(size_t)t]]) fused_tiles.push_back((int)t);
+        continue;
+      }
+      bool has = false;
+      for (int sgi = tl.tile_seg0[(size_t)t]; sgi < tl.tile_seg0[(size_t)t + 1]; ++sgi)
+        has = has || skip_plain[(size_t)tl.seg_layer[(size_t)sgi]];
+      if (has) bound_tiles.push_back((int)t);
+    }
+    for (int64_t t = 0; t < tm.n_tiles; ++t) {
+      bool has = false;
+      for (int sgi = tm.tile_seg0[(size_t)t]; sgi < tm.tile_seg0[(size_t)t + 1]; ++sgi)
+        has = has || !skip_plain[(size_t)tm.seg_layer[(size_t)sgi]];
+      if (has) plain_tiles.push_back((int)t);
+    }
+    ctx->n_fused_tiles = (int)fused_tiles.size();
+    ctx->n_bound_tiles = (int)bound_tiles.size();
+    ctx->n_plain_tiles = (int)plain_tiles.size();
+  }
+  ok = ok && upload(ctx, &ctx->d_first_layer_lb, tl.first) && upload(ctx, &ctx->d_tile_seg0_lb, tl.tile_seg0) &&
+       upload(ctx, &ctx->d_seg_layer_lb, tl.seg_layer) && upload(ctx, &ctx->d_layer_seg0_lb, tl.layer_seg0) &&
+       upload(ctx, &ctx->d_fused_tiles, fused_tiles) && upload(ctx, &ctx->d_bound_tiles, bound_tiles) &&
+       upload(ctx, &ctx->d_n_listed, n_listed) && upload(ctx, &ctx->d_plain_tiles, plain_tiles) &&
+       upload(ctx, &ctx->d_skip_plain, skip_plain) && upload(ctx, &ctx->d_skip_fused, skip_fused) &&
+       alloc_zero(ctx, &ctx->d_seg_max_lb, (size_t)ctx->n_segs_lb) &&
+       alloc_zero(ctx, &ctx->d_counter_lb, (size_t)L) && alloc_zero(ctx, &ctx->d_flag_lb, (size_t)L);
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
        alloc_zero(ctx, &ctx->d_counter, (size_t)ctx->W) && alloc_zero(ctx, &ctx->d_flag, (size_t)ctx->W) &&
@@ -442,7 +562,10 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
   }
   void* ptrs[] = {ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer, ctx->d_layer_seg0,
                   ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max, ctx->d_sigma,
-                  ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag};
+                  ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag,
+                  ctx->d_first_layer_lb, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, ctx->d_layer_seg0_lb,
+                  ctx->d_fused_tiles, ctx->d_bound_tiles, ctx->d_n_listed, ctx->d_plain_tiles, ctx->d_skip_plain, ctx->d_skip_fused, ctx->d_seg_max_lb,
+                  ctx->d_counter_lb, ctx->d_flag_lb};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete ctx;
@@ -559,6 +682,77 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, co
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
+ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                               const float* server_scales, float lr, void* hip_stream) {
+  if (ob_status s = check_ratios_args(ctx, st, packed_all, server_scales)) return s;
+  REQUIRE_PTR(st->x);
+  if (!std::isfinite(lr)) return OB_ERR_ARG;
+  bool packed_m = false;
+  PackedMom pm;
+  pm.bits = nullptr;
+  pm.scales = nullptr;
+  // momentum source: dense st->m if given (then it is also where the new momentum is written),
+  // else the 1-bit form of the previous step (then nothing is written: the new momentum is
+  // packed_all/server_scales themselves)
+  if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
+  if (packed_m && st->m_packed == packed_all) return OB_ERR_ARG;
+  Launch la(ctx, hip_stream);
+  if (!ctx->fused || !packed_m) {
+    // no layer fits on the device, or the momentum is a dense array (the fused kernel would have
+    // to hold it too, which costs more than the second read of v_frozen saves): two-kernel path
+    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, LayerSel{nullptr, nullptr}, ctx->n_tiles);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles);
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
+  RatioArgs ra;
+  ra.packed = packed_all; ra.sscales = server_scales; ra.m = st->m; ra.pm = pm;
+  ra.v_fresh = st->v_fresh; ra.v_frozen = st->v_frozen;
+  ra.beta1 = ctx->beta1; ra.omb1 = ctx->omb1; ra.beta2 = ctx->beta2; ra.omb2 = ctx->omb2;
+  ApplyArgs aa;
+  aa.packed = packed_all; aa.sscales = server_scales; aa.v_frozen = st->v_frozen; aa.x = st->x;
+  aa.m = st->m; aa.coeff_c = st->coeff_c; aa.lr = lr; aa.eta = ctx->eta;
+  const bool hk = st->mom_scale != nullptr;  // (here the momentum is in 1-bit form and st->m is NULL)
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_lb);
+  const LayerSel bound{ctx->d_bound_tiles, ctx->d_skip_fused};
+  // 1. the pieces of eligible layers in tiles that meet a layer boundary: ratio pass with the plain
+  //    kernel on the fused kernel's tiling; their maxima wait in seg_max for the layer barrier
+  if (hk)
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, true, true>), ctx->n_bound_tiles, ra, ctx->d_seg_max_lb,
+              ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
+  else
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, false, true>), ctx->n_bound_tiles, ra, ctx->d_seg_max_lb,
+              ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
+  // 2. layers that do not go through the fused kernel (too large for the device, smaller than a
+  //    tile, or empty -- the ratio of an empty layer, 0, still goes through the clips)
+  if (ctx->n_fused_layers < ctx->L) {
+    const LayerSel sel{ctx->d_plain_tiles, ctx->d_skip_plain};
+    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sel, ctx->n_plain_tiles);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, sel, ctx->n_plain_tiles);
+  }
+  // 3. the fused kernel over the tiles inside eligible layers
+  ctx->epoch_lb += 1;
+  LayerSync ls;
+  ls.seg_max = ctx->d_seg_max_lb; ls.layer_seg0 = ctx->d_layer_seg0_lb; ls.n_listed = ctx->d_n_listed;
+  ls.counter = ctx->d_counter_lb; ls.flag = ctx->d_flag_lb; ls.errflag = ctx->d_errflag;
+  ls.epoch = ctx->epoch_lb; ls.spin_limit = ctx->spin_limit;
+  ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
+  ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
+  if (hk)
+    OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT, (k_ratios_apply_resident<U_LB, true>), ctx->n_fused_tiles, ra, aa,
+              ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_fused_tiles);
+  else
+    OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT, (k_ratios_apply_resident<U_LB, false>), ctx->n_fused_tiles, ra, aa,
+              ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_fused_tiles);
+  // 4. update of the boundary pieces, with the coefficients the fused kernel committed
+  if (hk)
+    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, true, false>), ctx->n_bound_tiles, aa, ctx->n_c,
+              ctx->tpc_lb, lt, bound);
+  else
+    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, false, false>), ctx->n_bound_tiles, aa, ctx->n_c,
+              ctx->tpc_lb, lt, bound);
+  return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
 ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* m_out, void* hip_stream) {
   if (ob_status s = check_common(ctx, st)) return s;
   REQUIRE_PTR(m_out); REQUIRE_PTR(st->m_packed);
@@ -603,13 +797,20 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   // a bounded wait expired: the step that raised it produced undefined outputs.  Re-arm the
   // synchronisation state and fall back to the two-pass kernels for the rest of this context.
   ctx->resident = false;
+  ctx->fused = false;
   ctx->epoch = 0;
+  ctx->epoch_lb = 0;
+  (void)hipMemset(ctx->d_counter_lb, 0, sizeof(unsigned long long) * (size_t)ctx->L);
+  (void)hipMemset(ctx->d_flag_lb, 0, sizeof(unsigned long long) * (size_t)ctx->L);
   (void)hipMemset(ctx->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->W);
   (void)hipMemset(ctx->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->W);
   (void)hipMemset(ctx->d_errflag, 0, sizeof(unsigned int));
   (void)hipDeviceSynchronize();
   return OB_ERR_STATE;
 }
+
+int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->fused) ? ctx->n_fused_layers : 0; }
+int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->fused) ? ctx->n_fused_params : 0; }
 
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx) { return (ctx && ctx->resident) ? 1 : 0; }
 

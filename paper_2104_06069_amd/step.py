@@ -27,7 +27,7 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
-                 packed_momentum=False, **hyper):
+                 packed_momentum=False, fused_apply=False, **hyper):
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.W = int(num_workers)
@@ -52,6 +52,7 @@ class DeviceStep:
         self.scales_in = torch.zeros(self.W, **f32)
         # the W recompressed chunks (two pairs when they double as the momentum)
         self.packed_momentum = bool(packed_momentum)
+        self.fused_apply = bool(fused_apply)   # layer_ratios + decompress_apply as one call
         npairs = 2 if self.packed_momentum else 1
         self._pa = [torch.zeros(self.n_pad // 32, **i32) for _ in range(npairs)]
         self._ss = [torch.zeros(self.W, **f32) for _ in range(npairs)]
@@ -178,11 +179,20 @@ class DeviceStep:
         if self.packed_momentum:
             self.m_is_packed = True
 
+    def ratios_apply(self, lr):
+        ob.ob_lamb_ratios_apply(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
+                                self.stream)
+        if self.packed_momentum:
+            self.m_is_packed = True
+
     def step(self, grad, lr):
         """One compression-stage step into the current wire buffers (call begin_step() first and
         fill packed_in / packed_all with what the other ranks sent)."""
         self.compress_local(grad)
         self.gather()
         self.server_reduce()
-        self.layer_ratios()
-        self.decompress_apply(lr)
+        if self.fused_apply:
+            self.ratios_apply(lr)
+        else:
+            self.layer_ratios()
+            self.decompress_apply(lr)

@@ -21,21 +21,27 @@ def _need_gpu():
         pytest.skip("no GPU visible")
 
 
-def DeviceStep(*a, two_pass=False, **k):
+def DeviceStep(*a, two_pass=False, fused_max_tiles=None, **k):
     """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
     kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
     import os
     from paper_2104_06069_amd.step import DeviceStep as D
     import paper_2104_06069_amd as ob
     old = os.environ.pop("OB_LAMB_TWO_PASS", None)
+    old2 = os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
     if two_pass:
         os.environ["OB_LAMB_TWO_PASS"] = "1"
+    if fused_max_tiles is not None:
+        os.environ["OB_LAMB_FUSED_MAX_TILES"] = str(fused_max_tiles)
     try:
         d = D(*a, **k)
     finally:
         os.environ.pop("OB_LAMB_TWO_PASS", None)
+        os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
         if old is not None:
             os.environ["OB_LAMB_TWO_PASS"] = old
+        if old2 is not None:
+            os.environ["OB_LAMB_FUSED_MAX_TILES"] = old2
     assert ob.ob_lamb_uses_single_pass(d.ctx) == (not two_pass)
     return d
 
@@ -92,7 +98,8 @@ def make_case(name):
                 steps=3, server_chunk=W - 1, use_k=(name != "w1"))
 
 
-def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False):
+def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused=False,
+               fused_max_tiles=None):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -100,7 +107,8 @@ def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False):
     if cfg.get("use_k"):
         k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0)
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k)
-    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, **HYPER)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, fused_apply=fused,
+                     fused_max_tiles=fused_max_tiles, **HYPER)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -184,8 +192,10 @@ def test_phasewise_single_step(case, two_pass):
     finish(dev)
 
 
-def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False):
-    st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed)
+def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False, fused=False,
+                   fused_max_tiles=None):
+    st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed,
+                              fused=fused, fused_max_tiles=fused_max_tiles)
     stats = dict(word_mismatch_steps=0, scale_ulp_steps=0)
     for t in range(steps):
         g = gradient(st, cfg, t)
@@ -441,4 +451,32 @@ def test_two_stage_schedule(case, packed):
         assert_close(dev.get(k), ref.t[k], k, rel=1e-5)
     r = dev.get("r_prev")
     assert np.all(r >= 0.5) and np.all(r <= 4.0)
+    finish(dev)
+
+
+@pytest.mark.parametrize("case,steps,packed,max_tiles", [
+    ("bert_mini", 60, True, None),    # every layer in the fused kernel
+    ("bert_mini", 60, False, None),   # ... with the fp32 momentum read and written in place
+    ("bert_mini", 40, True, 2),       # layers over 2 tiles of 8192 go to the two-kernel path
+    ("bert_mini", 40, False, 1),
+    ("odd", 30, True, None),          # tiny tensors: every tile meets several layer boundaries
+    ("odd", 30, False, 0),            # nothing eligible: plain kernels behind the fused entry point
+    ("tiny", 10, True, None), ("w1", 10, True, 1), ("small", 10, False, None)])
+def test_trajectory_fused_ratios_apply(case, steps, packed, max_tiles):
+    """ob_lamb_ratios_apply (ratio pass, clips and update in one call, one kernel where the layer
+    fits on the device) against the oracle's separate phases."""
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    cfg = make_case(case)
+    ref, dev, stats = run_trajectory(cfg, steps, packed=packed, warm_state=(case in ("odd", "w1")),
+                                     fused=True, fused_max_tiles=max_tiles)
+    nf = ob.ob_lamb_fused_layers(dev.ctx)
+    print(f"{case}: {nf} of {cfg['plist'].L} layers in the fused kernel, {stats}")
+    if max_tiles == 0 or case in ("odd", "small", "w1"):   # no eligible layer holds a whole tile
+        assert nf == 0
+    else:
+        assert 0 < nf <= cfg["plist"].L
+    assert stats["scale_ulp_steps"] == 0 and stats["word_mismatch_steps"] == 0
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+        assert np.array_equal(dev.get(k), ref.t[k]), k
     finish(dev)
