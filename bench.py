@@ -79,6 +79,11 @@ def main():
     ap.add_argument("--separate-calls", action="store_true",
                     help="ob_lamb_layer_ratios + ob_lamb_decompress_apply instead of the fused "
                          "ob_lamb_ratios_apply")
+    ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
+                    help="mixed-precision variant: the gradient arrives in 16 bits (2 bytes/param less)")
+    ap.add_argument("--x-lp", choices=["none", "f16", "bf16"], default="none",
+                    help="mixed-precision variant: also write a 16-bit copy of the parameters "
+                         "(2 bytes/param more)")
     ap.add_argument("--dense-momentum", action="store_true",
                     help="keep the momentum as an fp32 array (default: the 1-bit form it has after "
                          "Algorithm 1 line 13; same results, 12 bytes/param less traffic)")
@@ -118,11 +123,18 @@ def main():
     st = Streams(0, device="cuda:0")
     mom_scale = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if args.mom_scale else None
     mode = "dense" if args.dense_momentum else "packed"
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "none": None}
     ds = DeviceStep(pl.offsets, W, server_chunk, device="cuda:0", mom_scale=mom_scale,
-                    packed_momentum=(mode == "packed"), fused_apply=not args.separate_calls, **hyper)
+                    packed_momentum=(mode == "packed"), fused_apply=not args.separate_calls,
+                    x_lp_dtype=tdt[args.x_lp], **hyper)
     ds.load_state(init_state(st, cfg))
     n_grads = 3
-    grads = [gradient(st, cfg, t) for t in range(n_grads)]
+    grads = [gradient(st, cfg, t).to(tdt[args.grad_dtype]) for t in range(n_grads)]
+    lp_variant = args.grad_dtype != "f32" or args.x_lp != "none"
+    if lp_variant and not args.no_cpu_baseline:
+        print("bench.py: the CPU-baseline leg covers the fp32 entry points; add --no-cpu-baseline "
+              "to time the mixed-precision variant", file=sys.stderr)
+        sys.exit(2)
     fw, fs = foreign_worker_chunks(st, cfg, 0)
     ds.packed_in.copy_(fw); ds.scales_in.copy_(torch.from_numpy(fs))
     for i in range(len(ds._pa)):   # what the other ranks' servers send, for both buffer pairs
@@ -181,6 +193,12 @@ def main():
     KB = dict(KERNEL_BYTES["both"])
     KB.update(KERNEL_BYTES[mode])
     KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
+    g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
+    x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
+    for k in ("compress_resident", "momentum_z_sumsq", "warmup_moments"):
+        KB[k] = (KB[k][0] - g_less, KB[k][1])
+    for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply"):
+        KB[k] = (KB[k][0] + x_more, KB[k][1])
     fused_params = ob.ob_lamb_fused_params(ds.ctx) if ds.fused_apply else 0
     units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params}
     if ds.fused_apply:   # the plain ratio/update kernels then cover only the remaining layers
@@ -190,14 +208,20 @@ def main():
     for k, v in kern.items():
         if k in KB:
             bpe, unit = KB[k]
-            v["algo_bytes"] = bpe * units[unit]
+            # "rest" is covered by two launches per call (tiles on the boundaries of the fused
+            # layers, then the remaining layers): per-launch mean
+            per_call = max(1, round(v["launches"] / args.profile_steps)) if unit == "rest" else 1
+            v["algo_bytes"] = bpe * units[unit] / per_call
             v["GBps"] = round(v["algo_bytes"] / (v["avg_ms"] * 1e-3) / 1e9, 1)
     dom = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"{args.workload}:{mode}", {}).get(dom)
+            key = f"{args.workload}:{mode}:{'fused' if ds.fused_apply else 'separate'}"
+            if lp_variant:
+                key += f":g{args.grad_dtype}:x{args.x_lp}"
+            traffic = json.load(open(tpath)).get(key, {}).get(dom)
         except Exception:
             traffic = None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
@@ -206,7 +230,8 @@ def main():
                 "traffic": traffic}
 
     step_bytes = compulsory_step_bytes_per_param(W) * ds.n_pad
-    algo_bytes = algorithmic_step_bytes_per_param(W, mode, fused_params / float(ds.n_pad)) * ds.n_pad
+    algo_bytes = (algorithmic_step_bytes_per_param(W, mode, fused_params / float(ds.n_pad))
+                  - g_less + x_more) * ds.n_pad
     out = {
         "metric": "1-bit LAMB compressed step: params/sec and % of HBM peak GB/s, 1 GPU",
         "value": round(pl.N / (ms_per_step * 1e-3), 1), "unit": "params/s",
@@ -216,6 +241,7 @@ def main():
         "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
                    "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
                    "mom_scale": bool(args.mom_scale), "momentum": mode,
+                   "grad_dtype": args.grad_dtype, "x_lp": args.x_lp,
                    "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
                    "fused_params": fused_params,
                    "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx)},
@@ -247,7 +273,7 @@ def main():
     ms_ms = timed(lambda: ds.momentum_scale())
     out["reference_calls"] = {
         "warmup_step_ms": round(wu_ms, 4),
-        "warmup_step_GBps": round(40.0 * ds.n_pad / (wu_ms * 1e-3) / 1e9, 1),   # 24 + 16 B/elem, two passes
+        "warmup_step_GBps": round((40.0 - g_less + x_more) * ds.n_pad / (wu_ms * 1e-3) / 1e9, 1),   # 24 + 16 B/elem, two passes
         "warmup_step_params_per_s": round(pl.N / (wu_ms * 1e-3), 1),
         "momentum_scale_ms": round(ms_ms, 4),
         "momentum_scale_GBps": round(4.0 * ds.n_pad / (ms_ms * 1e-3) / 1e9, 1)}

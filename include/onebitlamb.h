@@ -195,6 +195,36 @@ int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx);
  * enters the fused compression with the same RMS.  fp64 accumulation, one rounding to fp32. */
 ob_status ob_lamb_momentum_scale(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_stream);
 
+/* ---- Mixed-precision variant: 16-bit gradient in, 16-bit copy of the parameters out ----------
+ * The paper trains in FP16 (Section 6; its communication-volume figures are against FP16): the
+ * backward pass hands the optimizer a 16-bit gradient, possibly multiplied by a loss scale, and the
+ * forward pass reads a 16-bit copy of the parameters.  The `_lp` entry points below take and
+ * produce those directly, so that no separate cast pass over N elements is needed.  State and
+ * arithmetic stay binary32 and every other argument is as in the entry point of the same name:
+ *   gradient   g[i] = value(grad[i]) * grad_scale    (decode exact, one binary32 multiply; pass
+ *              the inverse loss scale, or 1).  grad: [N_pad] device, 16-byte aligned, of type
+ *              grad_dtype; OB_F32 requires grad_scale == 1 (OB_ERR_ARG otherwise) and is then the
+ *              plain entry point.
+ *   parameters x_lp[i] = x[i] after the update, rounded to nearest (ties to even) in x_dtype
+ *              (overflow -> infinity, NaN -> 0x7e00 / 0x7fc0), for every i that belongs to a
+ *              layer; the padding of x_lp is never written.  x_lp: [N_pad] device, 16-byte
+ *              aligned, or NULL for no copy (x_dtype is then ignored); OB_F32 is not accepted
+ *              for a non-NULL x_lp (OB_ERR_ARG): st->x is that array. */
+typedef enum ob_dtype { OB_F32 = 0, OB_F16 = 1, OB_BF16 = 2 } ob_dtype;
+
+ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const void* grad,
+                                 ob_dtype grad_dtype, float grad_scale, float lr, void* x_lp,
+                                 ob_dtype x_dtype, void* hip_stream);
+ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const void* grad,
+                                    ob_dtype grad_dtype, float grad_scale, uint32_t* packed_out,
+                                    float* scales_out, void* hip_stream);
+ob_status ob_lamb_decompress_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                                      const uint32_t* packed_all, const float* server_scales,
+                                      float lr, void* x_lp, ob_dtype x_dtype, void* hip_stream);
+ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                                  const uint32_t* packed_all, const float* server_scales, float lr,
+                                  void* x_lp, ob_dtype x_dtype, void* hip_stream);
+
 /* ob_lamb_compress_local runs as ONE kernel that keeps z in registers across a per-chunk arrival
  * barrier whenever one chunk's workgroups fill at most 80 % of the device (otherwise, or when the
  * environment variable OB_LAMB_TWO_PASS=1 is set at ob_lamb_create, as two passes through memory;

@@ -297,4 +297,55 @@ void obref_momentum_scale(int64_t L, const int64_t* off, const float* m, float* 
   }
 }
 
+namespace {
+struct LpFormat { int ebits, fbits; };
+inline LpFormat lp_format(int fmt) { return fmt == 1 ? LpFormat{5, 10} : LpFormat{8, 7}; }
+
+// value of a 16-bit pattern: (-1)^s * 2^(e-bias) * (1 + f/2^fbits), subnormals 2^(1-bias) * f/2^fbits
+double lp_value(int fmt, uint16_t b) {
+  const LpFormat F = lp_format(fmt);
+  const int bias = (1 << (F.ebits - 1)) - 1;
+  const int s = b >> 15;
+  const int e = (b >> F.fbits) & ((1 << F.ebits) - 1);
+  const int f = b & ((1 << F.fbits) - 1);
+  double v;
+  if (e == (1 << F.ebits) - 1) v = f ? std::nan("") : INFINITY;
+  else if (e == 0) v = std::ldexp((double)f, 1 - bias - F.fbits);
+  else v = std::ldexp((double)((1 << F.fbits) + f), e - bias - F.fbits);
+  return s ? -v : v;
+}
+
+uint16_t lp_nearest(int fmt, float x) {
+  const LpFormat F = lp_format(fmt);
+  const int bias = (1 << (F.ebits - 1)) - 1;
+  const int emax = bias, emin = 1 - bias;
+  const uint16_t exp_all = (uint16_t)(((1 << F.ebits) - 1) << F.fbits);
+  if (std::isnan(x)) return (uint16_t)(exp_all | (1 << (F.fbits - 1)));
+  const uint16_t sign = std::signbit(x) ? 0x8000 : 0;
+  const double a = std::fabs((double)x);
+  if (std::isinf(x)) return sign | exp_all;
+  if (a == 0.0) return sign;
+  int e;
+  (void)std::frexp(a, &e);   // a = m * 2^e, m in [0.5, 1)  ->  a in [2^(e-1), 2^e)
+  int ex = e - 1;
+  if (ex < emin) ex = emin;  // subnormal range shares the spacing of the smallest normal binade
+  // units of the last place at this exponent; nearbyint rounds ties to even (default mode)
+  double q = std::nearbyint(std::ldexp(a, F.fbits - ex));
+  if (q >= std::ldexp(1.0, F.fbits + 1)) { q /= 2.0; ex += 1; }   // rounded up into the next binade
+  if (ex > emax) return sign | exp_all;                              // overflow -> infinity
+  uint16_t bits;
+  if (q < std::ldexp(1.0, F.fbits)) bits = (uint16_t)q;            // subnormal (ex == emin) or zero
+  else bits = (uint16_t)(((ex + bias) << F.fbits) | ((int)q - (1 << F.fbits)));
+  return sign | bits;
+}
+}  // namespace
+
+void obref_lp_decode(int32_t fmt, int64_t n, const uint16_t* bits, float scale, float* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = (float)lp_value(fmt, bits[i]) * scale;
+}
+
+void obref_lp_round(int32_t fmt, int64_t n, const float* x, uint16_t* bits) {
+  for (int64_t i = 0; i < n; ++i) bits[i] = lp_nearest(fmt, x[i]);
+}
+
 }  // extern "C"

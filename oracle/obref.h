@@ -133,6 +133,20 @@ void obref64_warmup_step(int64_t L, const int64_t* off, double beta1, double bet
  * or the layer is empty; the mean runs over non-empty layers. */
 void obref_momentum_scale(int64_t L, const int64_t* off, const float* m, float* mom_scale);
 
+/* 16-bit storage formats of the mixed-precision variant (the paper trains in FP16, Section 6;
+ * its volume figures are against FP16 communication).  The arithmetic stays binary32: a 16-bit
+ * gradient is decoded exactly and multiplied once by grad_scale (the inverse loss scale), a
+ * 16-bit copy of the parameters is the binary32 value rounded to nearest, ties to even.
+ * fmt: 1 = IEEE binary16 (5 exponent bits, 10 fraction bits), 2 = bfloat16 (8, 7).
+ *   obref_lp_decode: out[i] = value(bits[i]) * scale       (binary32 multiply)
+ *   obref_lp_round:  bits[i] = nearest representable value of x[i] in the format; beyond the
+ *                    largest finite value by half a unit or more -> infinity; every NaN ->
+ *                    sign 0, all exponent bits, top fraction bit (0x7e00 / 0x7fc0).
+ * Both are written from the definition of the formats (fields decoded with ldexp; rounding by
+ * nearbyint on the value scaled to units of the last place), not from bit tricks. */
+void obref_lp_decode(int32_t fmt, int64_t n, const uint16_t* bits, float scale, float* out);
+void obref_lp_round(int32_t fmt, int64_t n, const float* x, uint16_t* bits);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,25 @@ def padded_len(n, W):
     return int(lib().obref_padded_len(int(n), int(W)))
 
 
+LP_F16, LP_BF16 = 1, 2   # 16-bit storage formats of obref_lp_*
+
+
+def lp_decode(fmt, bits, scale=1.0):
+    """uint16 patterns of binary16 (fmt 1) / bfloat16 (fmt 2) -> float32 values times scale."""
+    _chk(bits, np.uint16, name="bits")
+    out = np.empty(bits.size, dtype=np.float32)
+    lib().obref_lp_decode(C.c_int32(fmt), C.c_int64(bits.size), _p(bits), C.c_float(float(scale)), _p(out))
+    return out
+
+
+def lp_round(fmt, x):
+    """float32 -> uint16 patterns of the nearest binary16 / bfloat16 value (ties to even)."""
+    _chk(x, np.float32, name="x")
+    out = np.empty(x.size, dtype=np.uint16)
+    lib().obref_lp_round(C.c_int32(fmt), C.c_int64(x.size), _p(x), _p(out))
+    return out
+
+
 class Ref:
     """The oracle in one precision.  All methods update their array arguments in place."""
 

@@ -66,6 +66,10 @@ def lib():
             "ob_lamb_layer_ratios": (C.c_int, [vp, sp, vp, vp, vp]),
             "ob_lamb_decompress_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
             "ob_lamb_ratios_apply": (C.c_int, [vp, sp, vp, vp, f, vp]),
+            "ob_lamb_warmup_step_lp": (C.c_int, [vp, sp, vp, C.c_int, f, f, vp, C.c_int, vp]),
+            "ob_lamb_compress_local_lp": (C.c_int, [vp, sp, vp, C.c_int, f, vp, vp, vp]),
+            "ob_lamb_decompress_apply_lp": (C.c_int, [vp, sp, vp, vp, f, vp, C.c_int, vp]),
+            "ob_lamb_ratios_apply_lp": (C.c_int, [vp, sp, vp, vp, f, vp, C.c_int, vp]),
             "ob_lamb_fused_layers": (i64, [vp]),
             "ob_lamb_fused_params": (i64, [vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
@@ -179,6 +183,35 @@ def ob_lamb_decompress_apply(ctx, state, packed_all, server_scales, lr, stream=N
 def ob_lamb_ratios_apply(ctx, state, packed_all, server_scales, lr, stream=None):
     _check(lib().ob_lamb_ratios_apply(ctx, C.byref(state), _addr(packed_all), _addr(server_scales),
                                       lr, _addr(stream)), ctx, "ob_lamb_ratios_apply")
+
+
+# ---- mixed-precision variant: ob_dtype values and the _lp entry points ------------------------
+OB_F32, OB_F16, OB_BF16 = 0, 1, 2
+
+
+def ob_lamb_warmup_step_lp(ctx, state, grad, grad_dtype, grad_scale, lr, x_lp, x_dtype, stream=None):
+    _check(lib().ob_lamb_warmup_step_lp(ctx, C.byref(state), _addr(grad), int(grad_dtype), grad_scale,
+                                        lr, _addr(x_lp), int(x_dtype), _addr(stream)), ctx,
+           "ob_lamb_warmup_step_lp")
+
+
+def ob_lamb_compress_local_lp(ctx, state, grad, grad_dtype, grad_scale, packed_out, scales_out,
+                              stream=None):
+    _check(lib().ob_lamb_compress_local_lp(ctx, C.byref(state), _addr(grad), int(grad_dtype),
+                                           grad_scale, _addr(packed_out), _addr(scales_out),
+                                           _addr(stream)), ctx, "ob_lamb_compress_local_lp")
+
+
+def ob_lamb_decompress_apply_lp(ctx, state, packed_all, server_scales, lr, x_lp, x_dtype, stream=None):
+    _check(lib().ob_lamb_decompress_apply_lp(ctx, C.byref(state), _addr(packed_all),
+                                             _addr(server_scales), lr, _addr(x_lp), int(x_dtype),
+                                             _addr(stream)), ctx, "ob_lamb_decompress_apply_lp")
+
+
+def ob_lamb_ratios_apply_lp(ctx, state, packed_all, server_scales, lr, x_lp, x_dtype, stream=None):
+    _check(lib().ob_lamb_ratios_apply_lp(ctx, C.byref(state), _addr(packed_all), _addr(server_scales),
+                                         lr, _addr(x_lp), int(x_dtype), _addr(stream)), ctx,
+           "ob_lamb_ratios_apply_lp")
 
 
 def ob_lamb_fused_layers(ctx):

@@ -38,6 +38,9 @@ constexpr int WAVE = 64;
 constexpr int SPAN = BLOCK * 4;  // elements one workgroup-wide 128-bit access covers
 constexpr int FBLOCK = 1024;     // threads per workgroup of the small per-layer / per-chunk finalize kernels
 #define OB_AGENT __HIP_MEMORY_SCOPE_AGENT
+#ifndef OB_POLL_SLEEP
+#define OB_POLL_SLEEP 16  // s_sleep argument (units of 64 clocks) between two polls of a barrier flag
+#endif
 
 // Every N-sized array is read once and written once per kernel: 128-bit nontemporal (streaming)
 // accesses, which measure ~10 % faster than plain ones on MI355X for these patterns.
@@ -46,6 +49,53 @@ __device__ __forceinline__ v4f ld4(const float* p) {
 }
 __device__ __forceinline__ void st4(float* p, v4f v) {
   __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+}
+
+// 16-bit storage of the mixed-precision variant (the paper trains in FP16, Section 6): a gradient
+// may arrive as IEEE binary16 or bfloat16 and a 16-bit copy of the parameters may be written; all
+// arithmetic stays binary32.  GT / LPX are template flags so that the fp32-only instantiations
+// keep their code.
+typedef unsigned short v4h __attribute__((ext_vector_type(4)));
+
+struct GradSrc {
+  const void* __restrict__ p;   // float (GT == 0) or 16-bit patterns (GT == 1)
+  float scale;                  // g = value * scale (GT == 1 only; the inverse loss scale)
+  int bf16;                     // GT == 1: 0 = binary16, 1 = bfloat16
+};
+
+__device__ __forceinline__ float lp_to_float(unsigned short h, int bf16) {
+  if (bf16) return __uint_as_float((unsigned int)h << 16);
+  return (float)__builtin_bit_cast(_Float16, h);   // exact
+}
+
+// binary32 -> nearest 16-bit value, ties to even; NaN -> the format's canonical quiet NaN
+__device__ __forceinline__ unsigned short float_to_lp(float x, int bf16) {
+  if (bf16) {
+    const unsigned int u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)0x7fc0;
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+  }
+  if (x != x) return (unsigned short)0x7e00;
+  return __builtin_bit_cast(unsigned short, (_Float16)x);   // hardware convert, round to nearest even
+}
+
+// The thread's 4 gradient values at flat index i (a multiple of 4).
+template <int GT>
+__device__ __forceinline__ v4f load_grad(const GradSrc& gs, int64_t i) {
+  if (GT == 0) return ld4(reinterpret_cast<const float*>(gs.p) + i);
+  const v4h h = __builtin_nontemporal_load(
+      reinterpret_cast<const v4h*>(reinterpret_cast<const unsigned short*>(gs.p) + i));
+  v4f r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = lp_to_float(h[k], gs.bf16) * gs.scale;
+  return r;
+}
+
+__device__ __forceinline__ void st4_lp(void* __restrict__ base, int64_t i, v4f v, int bf16) {
+  v4h h;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) h[k] = float_to_lp(v[k], bf16);
+  __builtin_nontemporal_store(h, reinterpret_cast<v4h*>(reinterpret_cast<unsigned short*>(base) + i));
 }
 
 // Sum of one double per thread over a workgroup of NT threads, in a fixed order; result valid in
@@ -251,9 +301,9 @@ struct ZTile {
 // ---------------------------------------------------------------------------------------------
 // K1 (two-pass path)  z written over err, and the tile's sum of z^2 in fp64.
 // ---------------------------------------------------------------------------------------------
-template <int U, bool HAS_K, bool PACKED_M>
+template <int U, bool HAS_K, bool PACKED_M, int GT = 0>
 __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
-    const float* __restrict__ g, const float* __restrict__ m, PackedMom pm,
+    GradSrc g, const float* __restrict__ m, PackedMom pm,
     float* __restrict__ err, double* __restrict__ partials, int64_t n_c, int tpc, float beta1,
     float omb1, LayerTab lt) {
   constexpr int TILE = SPAN * U;
@@ -267,7 +317,7 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
     const int o = u * SPAN + o0;
     M[u] = 0.0f; NB[u] = 0u;
     if (o < p.len) {
-      G[u] = ld4(g + p.tile0 + o);
+      G[u] = load_grad<GT>(g, p.tile0 + o);
       if (PACKED_M) NB[u] = load_nibble(pm.bits, p.tile0 + u * SPAN);
       else M[u] = ld4(m + p.tile0 + o);
       E[u] = ld4(err + p.tile0 + o);
@@ -410,7 +460,7 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int ti
         break;
       }
       if ((it & 63) == 63 && __hip_atomic_load(cs.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
-      __builtin_amdgcn_s_sleep(2);
+      __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
     }
     *bc = f;
   }
@@ -424,9 +474,9 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int ti
 // the error from registers.  z never goes to memory.  Loads are issued G accesses at a time to
 // bound the staging registers.
 // ---------------------------------------------------------------------------------------------
-template <int U, int G, bool HAS_K, bool PACKED_M, int MINW = 4>
+template <int U, int G, bool HAS_K, bool PACKED_M, int MINW = 4, int GT = 0>
 __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
-    const float* __restrict__ g, const float* __restrict__ m, PackedMom pm,
+    GradSrc g, const float* __restrict__ m, PackedMom pm,
     float* __restrict__ err, uint32_t* __restrict__ packed, float* __restrict__ scales,
     ChunkSync cs, int64_t n_c, int tpc, float beta1, float omb1, LayerTab lt) {
   constexpr int TILE = SPAN * U;
@@ -449,7 +499,7 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
       const int o = (u0 + j) * SPAN + o0;
       M[j] = 0.0f; NB[j] = 0u;
       if (o < p.len) {
-        Gr[j] = ld4(g + p.tile0 + o);
+        Gr[j] = load_grad<GT>(g, p.tile0 + o);
         if (PACKED_M) NB[j] = load_nibble(pm.bits, p.tile0 + (u0 + j) * SPAN);
         else M[j] = ld4(m + p.tile0 + o);
         E[j] = ld4(err + p.tile0 + o);
@@ -782,10 +832,12 @@ struct ApplyArgs {
   float* __restrict__ m;              // written when WRITE_M
   const float* __restrict__ coeff_c;
   float lr, eta;
+  void* __restrict__ x_lp;            // 16-bit copy of the updated x (LPX)
+  int x_lp_bf16;
 };
 
 // Tile inside layer l0 with coefficient c: update from registers.
-template <int U, bool HAS_K, bool WRITE_M>
+template <int U, bool HAS_K, bool WRITE_M, bool LPX = false>
 __device__ __forceinline__ void apply_uniform(const ApplyArgs& aa, const TilePos& p, float ss,
                                               float kt, float c, const unsigned int (&NB)[U],
                                               const v4f (&VZ)[U], const v4f (&X)[U]) {
@@ -805,13 +857,14 @@ __device__ __forceinline__ void apply_uniform(const ApplyArgs& aa, const TilePos
         mn[k] = mt;
       }
       st4(aa.x + p.tile0 + o, xn);
+      if (LPX) st4_lp(aa.x_lp, p.tile0 + o, xn, aa.x_lp_bf16);
       if (WRITE_M) st4(aa.m + p.tile0 + o, mn);
     }
   }
 }
 
 // Tile that meets a layer boundary: element by element, coefficients read from coeff_c.
-template <int U, bool HAS_K, bool WRITE_M>
+template <int U, bool HAS_K, bool WRITE_M, bool LPX = false>
 __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerTab& lt,
                                                const TilePos& p, int l0, float ss,
                                                const unsigned char* __restrict__ skip,
@@ -834,7 +887,9 @@ __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerT
             const float a = aa.lr * aa.coeff_c[l];
             const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
             const float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
-            aa.x[i] = X[u][k] - a * uu;
+            const float xn = X[u][k] - a * uu;
+            aa.x[i] = xn;
+            if (LPX) reinterpret_cast<unsigned short*>(aa.x_lp)[i] = float_to_lp(xn, aa.x_lp_bf16);
             if (WRITE_M) aa.m[i] = mt;
           }
         }
@@ -843,7 +898,7 @@ __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerT
   }
 }
 
-template <int U, bool HAS_K, bool WRITE_M>
+template <int U, bool HAS_K, bool WRITE_M, bool LPX = false>
 __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_t n_c, int tpc,
                                                             LayerTab lt, LayerSel sel) {
   constexpr int TILE = SPAN * U;
@@ -872,8 +927,8 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
   }
   const bool uniform = (p.tile0 + p.len <= l0_end);
   if (uniform && skip0) return;
-  if (uniform) apply_uniform<U, HAS_K, WRITE_M>(aa, p, ss, kt, c0, NB, VZ, X);
-  else apply_elements<U, HAS_K, WRITE_M>(aa, lt, p, l0, ss, sel.skip, NB, VZ, X);
+  if (uniform) apply_uniform<U, HAS_K, WRITE_M, LPX>(aa, p, ss, kt, c0, NB, VZ, X);
+  else apply_elements<U, HAS_K, WRITE_M, LPX>(aa, lt, p, l0, ss, sel.skip, NB, VZ, X);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -953,7 +1008,7 @@ __device__ __forceinline__ float layer_wait(const LayerSync& ls, int l, unsigned
         break;
       }
       if ((it & 63) == 63 && __hip_atomic_load(ls.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
-      __builtin_amdgcn_s_sleep(2);
+      __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
     }
     *bc = f;
   }
@@ -968,7 +1023,7 @@ __device__ __forceinline__ float layer_wait(const LayerSync& ls, int l, unsigned
 #ifndef OB_LB_MINW
 #define OB_LB_MINW 5
 #endif
-template <int U, bool HAS_K>
+template <int U, bool HAS_K, bool LPX = false>
 __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
     RatioArgs ra, ApplyArgs aa, LayerSync ls, int64_t n_c, int tpc, LayerTab lt,
     const int* __restrict__ tile_seg0, const int* __restrict__ tile_list) {
@@ -995,7 +1050,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
     if (o < p.len) X[u] = ld4(aa.x + p.tile0 + o);
   }
   const float c = layer_wait(ls, l0, &bc);
-  apply_uniform<U, HAS_K, false>(aa, p, ss, kt, c, rt.NB, rt.VZ, X);
+  apply_uniform<U, HAS_K, false, LPX>(aa, p, ss, kt, c, rt.NB, rt.VZ, X);
 }
 
 // Dense view of a momentum held in 1-bit form: m[i] = (bit ? s_c : -s_c)/k_l for i < N (the
@@ -1051,9 +1106,9 @@ __device__ __forceinline__ float lamb_u(float mn, float vn, float x, float eta, 
   return u;
 }
 
-template <int U>
+template <int U, int GT = 0>
 __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
-    const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,
+    GradSrc g, float* __restrict__ m, float* __restrict__ v,
     const float* __restrict__ x, double* __restrict__ seg_sums /* [2*n_segs] */, int64_t n_c,
     int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd, LayerTab lt,
     const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer) {
@@ -1071,7 +1126,7 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     const int o = u * SPAN + o0;
     G[u] = 0.0f; M[u] = 0.0f; V[u] = 0.0f; X[u] = 0.0f;
     if (o < p.len) {
-      G[u] = ld4(g + p.tile0 + o);
+      G[u] = load_grad<GT>(g, p.tile0 + o);
       M[u] = ld4(m + p.tile0 + o);
       V[u] = ld4(v + p.tile0 + o);
       X[u] = ld4(x + p.tile0 + o);
@@ -1180,11 +1235,11 @@ __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restric
   }
 }
 
-template <int U>
+template <int U, bool LPX = false>
 __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
     const float* __restrict__ m, const float* __restrict__ v, float* __restrict__ x,
     const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, float wd,
-    LayerTab lt) {
+    LayerTab lt, void* __restrict__ x_lp, int x_lp_bf16) {
   constexpr int TILE = SPAN * U;
   const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
   const int l0 = lt.first_layer[p.t];
@@ -1213,6 +1268,7 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
         for (int k = 0; k < 4; ++k)
           xn[k] = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
         st4(x + p.tile0 + o, xn);
+        if (LPX) st4_lp(x_lp, p.tile0 + o, xn, x_lp_bf16);
       }
     }
   } else {
@@ -1228,7 +1284,9 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
           if (i < N) {
             l = walk_layer(l, i, lt.off);
             const float a = lr * coeff_c[l];
-            x[i] = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
+            const float xn = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
+            x[i] = xn;
+            if (LPX) reinterpret_cast<unsigned short*>(x_lp)[i] = float_to_lp(xn, x_lp_bf16);
           }
         }
       }

@@ -227,6 +227,43 @@ void dispatch2(bool a, bool b, F f) {
   }
 }
 
+// Calls f(std::bool_constant<a>).
+template <class F>
+void dispatch1(bool a, F f) {
+  if (a) f(std::true_type{});
+  else f(std::false_type{});
+}
+
+// Gradient argument of the _lp entry points -> kernel argument; *lp: 16-bit source.
+ob_status grad_source(const void* grad, int dtype, float scale, GradSrc* gs, bool* lp) {
+  if (!grad) return OB_ERR_NULL;
+  if (misaligned(grad)) return OB_ERR_ALIGN;
+  if (dtype != OB_F32 && dtype != OB_F16 && dtype != OB_BF16) return OB_ERR_ARG;
+  if (dtype == OB_F32 && scale != 1.0f) return OB_ERR_ARG;
+  if (!std::isfinite(scale)) return OB_ERR_ARG;
+  gs->p = grad;
+  gs->scale = scale;
+  gs->bf16 = (dtype == OB_BF16) ? 1 : 0;
+  *lp = (dtype != OB_F32);
+  return OB_OK;
+}
+
+// 16-bit parameter copy of the _lp entry points (NULL: none).
+struct XLp {
+  void* p = nullptr;
+  int bf16 = 0;
+};
+ob_status x_lp_target(void* x_lp, int dtype, XLp* out) {
+  out->p = nullptr;
+  out->bf16 = 0;
+  if (!x_lp) return OB_OK;
+  if (dtype != OB_F16 && dtype != OB_BF16) return OB_ERR_ARG;
+  if (misaligned(x_lp)) return OB_ERR_ALIGN;
+  out->p = x_lp;
+  out->bf16 = (dtype == OB_BF16) ? 1 : 0;
+  return OB_OK;
+}
+
 // The momentum source of a call: dense st->m if given, else the 1-bit form.
 ob_status momentum_source(const ob_lamb_state* st, bool* packed, PackedMom* pm) {
   pm->bits = nullptr;
@@ -306,15 +343,26 @@ void launch_ratios(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
               ctx->r_min, ctx->r_max, sel.skip);
 }
 
-void launch_apply(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
-                         const float* server_scales, float lr, LayerSel sel, int n_launch_tiles) {
+ApplyArgs apply_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                     const float* server_scales, float lr, const XLp& xl) {
   ApplyArgs aa;
   aa.packed = packed_all; aa.sscales = server_scales; aa.v_frozen = st->v_frozen; aa.x = st->x;
   aa.m = st->m; aa.coeff_c = st->coeff_c; aa.lr = lr; aa.eta = ctx->eta;
+  aa.x_lp = xl.p; aa.x_lp_bf16 = xl.bf16;
+  return aa;
+}
+
+void launch_apply(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                         const float* server_scales, float lr, LayerSel sel, int n_launch_tiles,
+                         const XLp& xl) {
+  const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
   dispatch2(st->mom_scale != nullptr, st->m != nullptr, [&](auto hk, auto wm) {
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_MAIN, decltype(hk)::value, decltype(wm)::value>),
-              n_launch_tiles, aa, ctx->n_c, ctx->tpc, lt, sel);
+    dispatch1(xl.p != nullptr, [&](auto lx) {
+      OB_LAUNCH(la, KID_APPLY,
+                (k_decompress_apply<U_MAIN, decltype(hk)::value, decltype(wm)::value, decltype(lx)::value>),
+                n_launch_tiles, aa, ctx->n_c, ctx->tpc, lt, sel);
+    });
   });
 }
 
@@ -462,7 +510,9 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
-    const int64_t slots = (int64_t)per_cu * cus;
+    // every instantiation is built for at least 4 workgroups per CU (its launch bounds); count no more
+    // than that, whatever this one reaches
+    const int64_t slots = (int64_t)std::min(per_cu, 4) * cus;
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }
@@ -478,7 +528,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
-    const int64_t slots = (int64_t)per_cu * cus;
+    const int64_t slots = (int64_t)std::min(per_cu, OB_LB_MINW) * cus;  // as above: the launch bound
     const char* env = getenv("OB_LAMB_NO_FUSED_APPLY");
     const bool allow = ok && !(env && env[0] == '1');
     // OB_LAMB_FUSED_MAX_TILES=n lowers the limit (tests of the split between the two paths)
@@ -575,22 +625,37 @@ int64_t ob_lamb_num_params(const ob_lamb_ctx* ctx) { return ctx ? ctx->N : 0; }
 int64_t ob_lamb_padded_len(const ob_lamb_ctx* ctx) { return ctx ? ctx->n_pad : 0; }
 int64_t ob_lamb_chunk_len(const ob_lamb_ctx* ctx) { return ctx ? ctx->n_c : 0; }
 
-ob_status ob_lamb_warmup_step(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad, float lr,
-                              void* hip_stream) {
+ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const void* grad,
+                                 ob_dtype grad_dtype, float grad_scale, float lr, void* x_lp,
+                                 ob_dtype x_dtype, void* hip_stream) {
   if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(grad); REQUIRE_PTR(st->x); REQUIRE_PTR(st->m); REQUIRE_PTR(st->v_fresh);
+  GradSrc gs;
+  bool lpg = false;
+  if (ob_status s = grad_source(grad, grad_dtype, grad_scale, &gs, &lpg)) return s;
+  XLp xl;
+  if (ob_status s = x_lp_target(x_lp, x_dtype, &xl)) return s;
+  REQUIRE_PTR(st->x); REQUIRE_PTR(st->m); REQUIRE_PTR(st->v_fresh);
   if (!st->c_avg || !st->coeff_c) return OB_ERR_NULL;
   if (!std::isfinite(lr)) return OB_ERR_ARG;
   Launch la(ctx, hip_stream);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN>), ctx->n_tiles, grad, st->m, st->v_fresh,
-            st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2,
-            ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
+  dispatch1(lpg, [&](auto lg) {
+    OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN, decltype(lg)::value ? 1 : 0>), ctx->n_tiles, gs,
+              st->m, st->v_fresh, st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
+              ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
+  });
   OB_LAUNCH_B(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
             st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3);
-  OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN>), ctx->n_tiles, st->m, st->v_fresh, st->x,
-            st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt);
+  dispatch1(xl.p != nullptr, [&](auto lx) {
+    OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN, decltype(lx)::value>), ctx->n_tiles, st->m,
+              st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt, xl.p, xl.bf16);
+  });
   return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_warmup_step(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad, float lr,
+                              void* hip_stream) {
+  return ob_lamb_warmup_step_lp(ctx, st, grad, OB_F32, 1.0f, lr, nullptr, OB_F32, hip_stream);
 }
 
 ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_stream) {
@@ -607,10 +672,14 @@ ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_st
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
-ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad,
-                                 uint32_t* packed_out, float* scales_out, void* hip_stream) {
+ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const void* grad,
+                                    ob_dtype grad_dtype, float grad_scale, uint32_t* packed_out,
+                                    float* scales_out, void* hip_stream) {
   if (ob_status s = check_common(ctx, st)) return s;
-  REQUIRE_PTR(grad); REQUIRE_PTR(st->err_worker); REQUIRE_PTR(packed_out);
+  GradSrc gs;
+  bool lpg = false;
+  if (ob_status s = grad_source(grad, grad_dtype, grad_scale, &gs, &lpg)) return s;
+  REQUIRE_PTR(st->err_worker); REQUIRE_PTR(packed_out);
   if (!scales_out) return OB_ERR_NULL;
   bool packed_m = false;
   PackedMom pm;
@@ -628,23 +697,34 @@ ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
     cs.spin_limit = ctx->spin_limit;
     const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_res);
     dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
-      OB_LAUNCH(la, KID_COMPRESS_RESIDENT,
-                (k_compress_resident<U_RES, G_RES, decltype(hk)::value, decltype(pk)::value>),
-                ctx->n_tiles_res, grad, st->m, pm, st->err_worker, packed_out, scales_out, cs, ctx->n_c,
-                ctx->tpc_res, ctx->beta1, ctx->omb1, lt);
+      dispatch1(lpg, [&](auto lg) {
+        OB_LAUNCH(la, KID_COMPRESS_RESIDENT,
+                  (k_compress_resident<U_RES, G_RES, decltype(hk)::value, decltype(pk)::value, 4,
+                                       decltype(lg)::value ? 1 : 0>),
+                  ctx->n_tiles_res, gs, st->m, pm, st->err_worker, packed_out, scales_out, cs, ctx->n_c,
+                  ctx->tpc_res, ctx->beta1, ctx->omb1, lt);
+      });
     });
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
   dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
-    OB_LAUNCH(la, KID_MOMENTUM_Z, (k_momentum_z_sumsq<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
-              ctx->n_tiles, grad, st->m, pm, st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc,
-              ctx->beta1, ctx->omb1, lt);
+    dispatch1(lpg, [&](auto lg) {
+      OB_LAUNCH(la, KID_MOMENTUM_Z,
+                (k_momentum_z_sumsq<U_MAIN, decltype(hk)::value, decltype(pk)::value, decltype(lg)::value ? 1 : 0>),
+                ctx->n_tiles, gs, st->m, pm, st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc,
+                ctx->beta1, ctx->omb1, lt);
+    });
   });
   OB_LAUNCH_B(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, FBLOCK, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out);
   OB_LAUNCH(la, KID_SIGN_PACK, (k_sign_pack_error<U_MAIN>), ctx->n_tiles, st->err_worker, packed_out,
             scales_out, ctx->n_c, ctx->tpc);
   return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, const float* grad,
+                                 uint32_t* packed_out, float* scales_out, void* hip_stream) {
+  return ob_lamb_compress_local_lp(ctx, st, grad, OB_F32, 1.0f, packed_out, scales_out, hip_stream);
 }
 
 ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_in,
@@ -673,18 +753,29 @@ ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
-ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
-                                   const float* server_scales, float lr, void* hip_stream) {
+ob_status ob_lamb_decompress_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                      const float* server_scales, float lr, void* x_lp, ob_dtype x_dtype,
+                                      void* hip_stream) {
   if (ob_status s = check_apply_args(ctx, st, packed_all, server_scales, lr)) return s;
+  XLp xl;
+  if (ob_status s = x_lp_target(x_lp, x_dtype, &xl)) return s;
   Launch la(ctx, hip_stream);
-  launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles);
+  launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles, xl);
   commit_packed_momentum(la, ctx, st, packed_all, server_scales);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
-ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
-                               const float* server_scales, float lr, void* hip_stream) {
+ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                   const float* server_scales, float lr, void* hip_stream) {
+  return ob_lamb_decompress_apply_lp(ctx, st, packed_all, server_scales, lr, nullptr, OB_F32, hip_stream);
+}
+
+ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                  const float* server_scales, float lr, void* x_lp, ob_dtype x_dtype,
+                                  void* hip_stream) {
   if (ob_status s = check_ratios_args(ctx, st, packed_all, server_scales)) return s;
+  XLp xl;
+  if (ob_status s = x_lp_target(x_lp, x_dtype, &xl)) return s;
   REQUIRE_PTR(st->x);
   if (!std::isfinite(lr)) return OB_ERR_ARG;
   bool packed_m = false;
@@ -701,16 +792,14 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
     // no layer fits on the device, or the momentum is a dense array (the fused kernel would have
     // to hold it too, which costs more than the second read of v_frozen saves): two-kernel path
     launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, LayerSel{nullptr, nullptr}, ctx->n_tiles);
-    launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles, xl);
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
   RatioArgs ra;
   ra.packed = packed_all; ra.sscales = server_scales; ra.m = st->m; ra.pm = pm;
   ra.v_fresh = st->v_fresh; ra.v_frozen = st->v_frozen;
   ra.beta1 = ctx->beta1; ra.omb1 = ctx->omb1; ra.beta2 = ctx->beta2; ra.omb2 = ctx->omb2;
-  ApplyArgs aa;
-  aa.packed = packed_all; aa.sscales = server_scales; aa.v_frozen = st->v_frozen; aa.x = st->x;
-  aa.m = st->m; aa.coeff_c = st->coeff_c; aa.lr = lr; aa.eta = ctx->eta;
+  const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const bool hk = st->mom_scale != nullptr;  // (here the momentum is in 1-bit form and st->m is NULL)
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_lb);
   const LayerSel bound{ctx->d_bound_tiles, ctx->d_skip_fused};
@@ -727,7 +816,7 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   if (ctx->n_fused_layers < ctx->L) {
     const LayerSel sel{ctx->d_plain_tiles, ctx->d_skip_plain};
     launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sel, ctx->n_plain_tiles);
-    launch_apply(la, ctx, st, packed_all, server_scales, lr, sel, ctx->n_plain_tiles);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, sel, ctx->n_plain_tiles, xl);
   }
   // 3. the fused kernel over the tiles inside eligible layers
   ctx->epoch_lb += 1;
@@ -737,20 +826,22 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   ls.epoch = ctx->epoch_lb; ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
-  if (hk)
-    OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT, (k_ratios_apply_resident<U_LB, true>), ctx->n_fused_tiles, ra, aa,
-              ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_fused_tiles);
-  else
-    OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT, (k_ratios_apply_resident<U_LB, false>), ctx->n_fused_tiles, ra, aa,
-              ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_fused_tiles);
+  dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
+    OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
+              (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), ctx->n_fused_tiles, ra,
+              aa, ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_fused_tiles);
+  });
   // 4. update of the boundary pieces, with the coefficients the fused kernel committed
-  if (hk)
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, true, false>), ctx->n_bound_tiles, aa, ctx->n_c,
-              ctx->tpc_lb, lt, bound);
-  else
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, false, false>), ctx->n_bound_tiles, aa, ctx->n_c,
-              ctx->tpc_lb, lt, bound);
+  dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
+    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, decltype(k_)::value, false, decltype(lx)::value>),
+              ctx->n_bound_tiles, aa, ctx->n_c, ctx->tpc_lb, lt, bound);
+  });
   return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                               const float* server_scales, float lr, void* hip_stream) {
+  return ob_lamb_ratios_apply_lp(ctx, st, packed_all, server_scales, lr, nullptr, OB_F32, hip_stream);
 }
 
 ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* m_out, void* hip_stream) {

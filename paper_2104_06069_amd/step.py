@@ -27,7 +27,7 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
-                 packed_momentum=False, fused_apply=False, **hyper):
+                 packed_momentum=False, fused_apply=False, x_lp_dtype=None, grad_scale=1.0, **hyper):
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.W = int(num_workers)
@@ -58,6 +58,10 @@ class DeviceStep:
         self._ss = [torch.zeros(self.W, **f32) for _ in range(npairs)]
         self._cur = 0
         self.m_is_packed = False   # True once a step has committed the momentum in 1-bit form
+        # mixed-precision variant: a float16/bfloat16 gradient tensor is taken as it is (times
+        # grad_scale, the inverse loss scale); x_lp_dtype asks for a 16-bit copy of x after each update
+        self.grad_scale = float(grad_scale)
+        self.x_lp = None if x_lp_dtype is None else torch.zeros(self.n_pad, device=self.device, dtype=x_lp_dtype)
 
     # the buffer pair of the current step
     @property
@@ -117,8 +121,22 @@ class DeviceStep:
         return torch.cuda.current_stream(self.device).cuda_stream
 
     # ---- the calls ---------------------------------------------------------------------------
+    @staticmethod
+    def _ob_dtype(t):
+        return {torch.float32: ob.OB_F32, torch.float16: ob.OB_F16, torch.bfloat16: ob.OB_BF16}[t.dtype]
+
+    def _x_lp_args(self):
+        return (None, ob.OB_F32) if self.x_lp is None else (self.x_lp, self._ob_dtype(self.x_lp))
+
+    def _is_plain(self, grad=None):
+        return self.x_lp is None and (grad is None or (grad.dtype == torch.float32 and self.grad_scale == 1.0))
+
     def warmup_step(self, grad, lr):
-        ob.ob_lamb_warmup_step(self.ctx, self._state("read"), grad, lr, self.stream)
+        if self._is_plain(grad):
+            ob.ob_lamb_warmup_step(self.ctx, self._state("read"), grad, lr, self.stream)
+        else:
+            ob.ob_lamb_warmup_step_lp(self.ctx, self._state("read"), grad, self._ob_dtype(grad),
+                                      self.grad_scale, lr, *self._x_lp_args(), self.stream)
 
     def freeze(self):
         ob.ob_lamb_freeze(self.ctx, self._state("read"), self.stream)
@@ -152,8 +170,12 @@ class DeviceStep:
             self._cur = 1 - self._cur
 
     def compress_local(self, grad):
-        ob.ob_lamb_compress_local(self.ctx, self._state("read"), grad, self.packed_local,
-                                  self.scales_local, self.stream)
+        if self._is_plain(grad):
+            ob.ob_lamb_compress_local(self.ctx, self._state("read"), grad, self.packed_local,
+                                      self.scales_local, self.stream)
+        else:
+            ob.ob_lamb_compress_local_lp(self.ctx, self._state("read"), grad, self._ob_dtype(grad),
+                                         self.grad_scale, self.packed_local, self.scales_local, self.stream)
 
     def gather(self):
         """Own chunk c of the worker output -> slot c of the server's input (device copies)."""
@@ -174,14 +196,22 @@ class DeviceStep:
                                 self.stream)
 
     def decompress_apply(self, lr):
-        ob.ob_lamb_decompress_apply(self.ctx, self._state("commit"), self.packed_all,
-                                    self.server_scales, lr, self.stream)
+        if self._is_plain():
+            ob.ob_lamb_decompress_apply(self.ctx, self._state("commit"), self.packed_all,
+                                        self.server_scales, lr, self.stream)
+        else:
+            ob.ob_lamb_decompress_apply_lp(self.ctx, self._state("commit"), self.packed_all,
+                                           self.server_scales, lr, *self._x_lp_args(), self.stream)
         if self.packed_momentum:
             self.m_is_packed = True
 
     def ratios_apply(self, lr):
-        ob.ob_lamb_ratios_apply(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
-                                self.stream)
+        if self._is_plain():
+            ob.ob_lamb_ratios_apply(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
+                                    self.stream)
+        else:
+            ob.ob_lamb_ratios_apply_lp(self.ctx, self._state("read"), self.packed_all, self.server_scales,
+                                       lr, *self._x_lp_args(), self.stream)
         if self.packed_momentum:
             self.m_is_packed = True
 

@@ -1,7 +1,7 @@
 """Host-side mirror of the device step, driving the CPU oracle on numpy arrays (tests only)."""
 import numpy as np
 
-from oracle.obref import Ref
+from oracle.obref import Ref, lp_decode, lp_round
 
 F32 = Ref(np.float32)
 
@@ -46,7 +46,21 @@ class RefStep:
         self.bits_all[...] = np.ascontiguousarray(words).view(np.uint8)
         self.server_scales[...] = scales
 
+    # mixed-precision variant: a gradient given as (fmt, uint16 patterns) is decoded and multiplied
+    # by grad_scale; x_lp(fmt) is the 16-bit copy of the parameters (padding excluded by the caller)
+    grad_scale = 1.0
+
+    def _g32(self, g):
+        if isinstance(g, tuple):
+            fmt, bits = g
+            return lp_decode(fmt, np.ascontiguousarray(bits), self.grad_scale)
+        return g
+
+    def x_lp(self, fmt):
+        return lp_round(fmt, self.t["x"])
+
     def warmup_step(self, g, lr):
+        g = self._g32(g)
         h, t = self.h, self.t
         t["coeff_c"][...] = F32.warmup_step(self.off, h["beta1"], h["beta2"], h["beta3"], h["eta"],
                                             h["c_min"], h["c_max"], h["weight_decay"], lr, g, t["m"],
@@ -72,6 +86,7 @@ class RefStep:
         self.step(g, lr)
 
     def compress_local(self, g):
+        g = self._g32(g)
         self.bits_local, self.scales_local = F32.compress_local(
             self.off, self.W, self.mom_scale, self.h["beta1"], g, self.t["m"], self.t["err_worker"])
 

@@ -75,6 +75,9 @@ def test_null_context_is_rejected(ob):
     assert lib.ob_lamb_layer_ratios(None, C.byref(st), None, None, None) == -1
     assert ob.ob_lamb_num_params(None) == 0
     lib.ob_lamb_destroy(None)
+    assert lib.ob_lamb_compress_local_lp(None, C.byref(st), None, 1, 1.0, None, None, None) == -1
+    assert lib.ob_lamb_ratios_apply_lp(None, C.byref(st), None, None, 1e-3, None, 0, None) == -1
+    assert lib.ob_lamb_warmup_step_lp(None, C.byref(st), None, 2, 1.0, 1e-3, None, 0, None) == -1
 
 
 def test_product_package_does_not_import_the_oracle():

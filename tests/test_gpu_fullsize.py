@@ -19,15 +19,17 @@ from workloads.gen import layer_kappa  # noqa: E402
 pytestmark = pytest.mark.gpu
 
 
-def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False):
+def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False, fused=False, x_lp_dtype=None):
     st = Streams(seed, device="cuda:0")
     pl = cfg["plist"]
     import paper_2104_06069_amd as ob
     if two_pass:
-        dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, two_pass=True, packed_momentum=packed, **HYPER)
+        dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, two_pass=True, packed_momentum=packed,
+                         fused_apply=fused, x_lp_dtype=x_lp_dtype, **HYPER)
     else:  # whatever the library selects for this size on this device
         from paper_2104_06069_amd.step import DeviceStep as D
-        dev = D(pl.offsets, cfg["W"], server_chunk, packed_momentum=packed, **HYPER)
+        dev = D(pl.offsets, cfg["W"], server_chunk, packed_momentum=packed, fused_apply=fused,
+                x_lp_dtype=x_lp_dtype, **HYPER)
     print(f"{cfg['name']}: single-pass worker compression = {ob.ob_lamb_uses_single_pass(dev.ctx)}", flush=True)
     s = init_state(st, cfg)
     # non-trivial momentum and errors, as after many steps
@@ -44,18 +46,32 @@ def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False):
     return st, dev, g
 
 
-@pytest.mark.parametrize("name,two_pass,packed", [("bert_large", False, False), ("bert_large_w256", False, False),
-                                                  ("bert_large", True, False), ("bert_large", False, True)])
-def test_bert_large_whole_step(name, two_pass, packed):
+@pytest.mark.parametrize("name,two_pass,packed,fused,lp", [
+    ("bert_large", False, False, False, None), ("bert_large_w256", False, False, False, None),
+    ("bert_large", True, False, False, None), ("bert_large", False, True, False, None),
+    # the configuration the benchmark times: 1-bit momentum, ratio pass and update in one call
+    ("bert_large", False, True, True, None),
+    # ... and its mixed-precision variant: binary16 gradient (inverse loss scale 1/512), bfloat16 copy of x
+    ("bert_large", False, True, True, ("f16", "bf16", 1.0 / 512))])
+def test_bert_large_whole_step(name, two_pass, packed, fused, lp):
     """Whole steps against the whole oracle; with the 1-bit momentum two steps, so that the second
     one reads the momentum from the first one's packed output."""
     _need_gpu()
     cfg = make_config(name)
     c = cfg["W"] // 2
-    st, dev, g = device_setup(cfg, c, two_pass=two_pass, packed=packed)
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}
+    st, dev, g = device_setup(cfg, c, two_pass=two_pass, packed=packed, fused=fused,
+                              x_lp_dtype=tdt[lp[1]] if lp else None)
+    if fused:
+        import paper_2104_06069_amd as ob
+        print(f"{name}: layers in the single-kernel ratio+update path: {ob.ob_lamb_fused_layers(dev.ctx)}", flush=True)
+        assert ob.ob_lamb_fused_layers(dev.ctx) > 100
     ref = RefStep(cfg["plist"].offsets, cfg["W"], c)
     ref.load_state({k: dev.get(k) for k in ref.t})
+    if lp:
+        dev.grad_scale = ref.grad_scale = lp[2]
     lr = 2e-3
+    N = ref.N
     for t in range(2 if packed else 1):
         if t > 0:
             dev.begin_step()
@@ -65,7 +81,11 @@ def test_bert_large_whole_step(name, two_pass, packed):
             torch.cuda.synchronize()
         ref.set_foreign_in(dev.packed_in.cpu().numpy(), dev.scales_in.cpu().numpy())
         ref.set_foreign_all(dev.packed_all.cpu().numpy(), dev.server_scales.cpu().numpy())
-        gh = g.cpu().numpy()
+        if lp:   # the gradient as the backward pass of a loss-scaled fp16 run would hand it over
+            g = (g / lp[2]).to(tdt[lp[0]])
+            gh = (1 if lp[0] == "f16" else 2, g.view(torch.int16).cpu().numpy().view(np.uint16))
+        else:
+            gh = g.cpu().numpy()
         t0 = time.time()
         ref.step(gh, lr)
         print(f"{name}: oracle step {time.time() - t0:.1f} s", flush=True)
@@ -79,6 +99,13 @@ def test_bert_large_whole_step(name, two_pass, packed):
         for k in ("err_worker", "err_server", "v_fresh", "r_prev", "coeff_c", "x", "m"):
             nd[k] = assert_close(dev.get(k), ref.t[k], k)
         print(f"{name}: step {t}: elements not bit-equal (within 1e-6): {nd}", flush=True)
+        if lp:
+            got = dev.x_lp.view(torch.int16).cpu().numpy().view(np.uint16)
+            want = ref.x_lp(1 if lp[1] == "f16" else 2)
+            same = dev.get("x")[:N].view(np.uint32) == ref.t["x"][:N].view(np.uint32)
+            assert same.mean() > 0.99
+            assert np.array_equal(got[:N][same], want[:N][same]), "16-bit parameter copy"
+            assert np.all(got[N:] == 0)
     finish(dev)
 
 

@@ -89,9 +89,11 @@ def make_case(name):
         sizes = [3000, 1, 9000, 777]
     elif name == "small":  # N below one 256-element span
         sizes = [7, 90, 3]
+    elif name == "one_layer":  # the whole model as one tensor (1-bit Adam's view of it)
+        sizes = [50000]
     else:
         raise KeyError(name)
-    W = {"odd": 3, "w1": 1, "small": 2}[name]
+    W = {"odd": 3, "w1": 1, "small": 2, "one_layer": 4}[name]
     pl = ParamList(name, [(f"t{i}", s) for i, s in enumerate(sizes)])
     n_pad = padded_len(pl.N, W)
     return dict(name=name, plist=pl, W=W, n_pad=n_pad, n_c=n_pad // W, grad="student_t3",
@@ -99,16 +101,18 @@ def make_case(name):
 
 
 def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused=False,
-               fused_max_tiles=None):
+               fused_max_tiles=None, hyper=None):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
     k = None
     if cfg.get("use_k"):
         k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0)
-    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k)
+    h = dict(HYPER)
+    h.update(hyper or {})
+    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **h)
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, fused_apply=fused,
-                     fused_max_tiles=fused_max_tiles, **HYPER)
+                     fused_max_tiles=fused_max_tiles, **h)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -193,9 +197,12 @@ def test_phasewise_single_step(case, two_pass):
 
 
 def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False, fused=False,
-                   fused_max_tiles=None):
+                   fused_max_tiles=None, hyper=None, c_avg=None):
     st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed,
-                              fused=fused, fused_max_tiles=fused_max_tiles)
+                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper)
+    if c_avg is not None:
+        ref.t["c_avg"][...] = c_avg
+        dev.load_state(ref.t)
     stats = dict(word_mismatch_steps=0, scale_ulp_steps=0)
     for t in range(steps):
         g = gradient(st, cfg, t)
@@ -479,4 +486,136 @@ def test_trajectory_fused_ratios_apply(case, steps, packed, max_tiles):
     assert stats["scale_ulp_steps"] == 0 and stats["word_mismatch_steps"] == 0
     for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
         assert np.array_equal(dev.get(k), ref.t[k]), k
+    finish(dev)
+
+
+@pytest.mark.parametrize("case,fused,packed,one_adam", [
+    ("bert_mini", False, False, False), ("bert_mini", True, True, False), ("odd", True, True, False),
+    ("one_layer", False, False, True), ("one_layer", True, True, True)])
+def test_degenerate_variants(case, fused, packed, one_adam):
+    """The method's relatives as settings of the same step (Section 3.4 / Appendix A.4): r pinned
+    to 1 freezes c at its warmup average ("LAMB + basic 1-bit"); one layer with c_avg = 1 is the
+    compression stage of 1-bit Adam."""
+    _need_gpu()
+    cfg = make_case(case)
+    ref, dev, stats = run_trajectory(cfg, 20, packed=packed, fused=fused, warm_state=True,
+                                     hyper=dict(r_min=1.0, r_max=1.0),
+                                     c_avg=(1.0 if one_adam else None))
+    assert stats["scale_ulp_steps"] == 0
+    assert np.all(dev.get("r_prev") == 1.0)
+    assert np.array_equal(dev.get("coeff_c"), ref.t["c_avg"])
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server"):
+        assert np.array_equal(dev.get(k), ref.t[k]), k
+    finish(dev)
+
+
+def _to_lp(g32, fmt):
+    """Input generation for the mixed-precision variant: a 16-bit gradient tensor (torch's
+    conversion) and its raw patterns for the oracle."""
+    t = torch.from_numpy(g32).to({"f16": torch.float16, "bf16": torch.bfloat16}[fmt])
+    return t, (1 if fmt == "f16" else 2, t.view(torch.int16).numpy().view(np.uint16).copy())
+
+
+@pytest.mark.parametrize("case,gfmt,xfmt,fused,packed,scale", [
+    ("bert_mini", "f16", "f16", True, True, 1.0 / 1024),
+    ("bert_mini", "bf16", "bf16", True, True, 1.0),
+    ("bert_mini", "f16", "bf16", False, False, 1.0 / 1000),   # scale not a power of two; separate calls
+    ("odd", "bf16", "f16", True, True, 1.0 / 64),
+    ("odd", "f16", "f16", True, False, 1.0),                 # fp32 momentum behind the fused entry point
+    ("tiny", "f32", "f16", True, True, 1.0),                 # only the 16-bit parameter copy
+    ("small", "f16", None, False, True, 0.5),                # only the 16-bit gradient
+    ("w1", "bf16", "bf16", True, True, 1.0 / 8)])
+def test_mixed_precision_variant(case, gfmt, xfmt, fused, packed, scale):
+    """16-bit gradient in (times the inverse loss scale), 16-bit copy of the parameters out, through
+    3 LAMB steps, the snapshot and 12 compression steps; state and arithmetic stay fp32, so every
+    comparison is as strict as for the fp32 entry points and the 16-bit copy is bit-exact."""
+    _need_gpu()
+    cfg = make_case(case)
+    st = Streams(11)
+    pl = cfg["plist"]
+    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **HYPER)
+    ref.grad_scale = scale
+    tdt = {None: None, "f16": torch.float16, "bf16": torch.bfloat16}[xfmt]
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], packed_momentum=packed, fused_apply=fused,
+                     x_lp_dtype=tdt, grad_scale=scale, **HYPER)
+    s = init_state(st, cfg)
+    s["v_fresh"][...] = 0
+    s["c_avg"][...] = 0
+    ref.load_state(s)
+    dev.load_state(ref.t)
+    N = ref.N
+    T_w, T = 3, 15
+
+    def check_x_lp(t):
+        """Where the fp32 parameters agree bit for bit (everywhere, but for a last-bit difference of
+        a layer's coefficient after an fp64 reduction), the 16-bit copy must agree bit for bit."""
+        if xfmt is None:
+            return
+        got = dev.x_lp.view(torch.int16).cpu().numpy().view(np.uint16)
+        want = ref.x_lp(1 if xfmt == "f16" else 2)
+        same = dev.get("x")[:N].view(np.uint32) == ref.t["x"][:N].view(np.uint32)
+        assert same.mean() >= 0.9, f"step {t}: fp32 parameters differ in {(~same).sum()} places"
+        assert np.array_equal(got[:N][same], want[:N][same]), f"step {t}: 16-bit parameter copy"
+        assert np.all(got[N:] == 0), "padding of the 16-bit copy was written"
+
+    for t in range(T):
+        g32 = (gradient(st, cfg, t) / np.float32(scale)).astype(np.float32)
+        if gfmt == "f32":
+            assert scale == 1.0
+            gd, gr = torch.from_numpy(g32), g32
+        else:
+            gd, gr = _to_lp(g32, gfmt)
+        gd = gd.to(dev.device)
+        lr = 1e-3 * (1 + t % 3)
+        if t < T_w:
+            ref.warmup_step(gr, lr)
+            dev.warmup_step(gd, lr)
+            for k in ("x", "m", "v_fresh", "c_avg"):
+                assert_close(dev.get(k), ref.t[k], f"warmup step {t} {k}")
+            check_x_lp(t)
+            if t == T_w - 1:
+                ref.freeze(); dev.freeze()
+                assert np.array_equal(dev.get("v_frozen"), dev.get("v_fresh"))
+                dev.load_state(ref.t)   # the compression stage starts from identical bits
+            continue
+        fw, fs = foreign_worker_chunks(st, cfg, t)
+        fa, fss = foreign_server_chunks(st, cfg, t)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        dev.begin_step()
+        dev.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+        dev.scales_in.copy_(torch.from_numpy(fs))
+        dev.packed_all.copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
+        dev.server_scales.copy_(torch.from_numpy(fss))
+        ref.step(gr, lr)
+        dev.step(gd, lr)
+        assert np.array_equal(words_of(dev.packed_local), ref.bits_local), f"step {t}: worker sign words"
+        assert np.array_equal(words_of(dev.packed_all), ref.bits_all), f"step {t}: server sign words"
+        for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev"):
+            assert_close(dev.get(k), ref.t[k], f"step {t} {k}")
+        check_x_lp(t)
+    finish(dev)
+
+
+def test_mixed_precision_argument_errors():
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    cfg = make_case("small")
+    pl = cfg["plist"]
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], **HYPER)
+    g = torch.zeros(dev.n_pad, device=dev.device)
+    g16 = g.to(torch.float16)
+    stt = dev._state("read")
+    def status(fn, *a):
+        with pytest.raises(ob.ObLambError) as e:
+            fn(dev.ctx, stt, *a)
+        return e.value.status
+    # fp32 gradient with a scale, unknown dtype, non-finite scale, misaligned pointer
+    assert status(ob.ob_lamb_compress_local_lp, g, ob.OB_F32, 0.5, dev.packed_local, dev.scales_local) == -2
+    assert status(ob.ob_lamb_compress_local_lp, g16, 7, 1.0, dev.packed_local, dev.scales_local) == -2
+    assert status(ob.ob_lamb_compress_local_lp, g16, ob.OB_F16, float("inf"), dev.packed_local, dev.scales_local) == -2
+    assert status(ob.ob_lamb_compress_local_lp, g16.data_ptr() + 2, ob.OB_F16, 1.0, dev.packed_local, dev.scales_local) == -3
+    # 16-bit parameter copy declared as fp32, misaligned
+    assert status(ob.ob_lamb_ratios_apply_lp, dev.packed_all, dev.server_scales, 1e-3, g16, ob.OB_F32) == -2
+    assert status(ob.ob_lamb_decompress_apply_lp, dev.packed_all, dev.server_scales, 1e-3, g16.data_ptr() + 2, ob.OB_BF16) == -3
+    assert status(ob.ob_lamb_warmup_step_lp, g16, ob.OB_F16, 1.0, 1e-3, g16, 5) == -2
     finish(dev)

@@ -587,3 +587,120 @@ def test_momentum_scale_reading():
     k = F32.momentum_scale(off, m)
     # non-empty layers: sigma = (2, 0, 6) -> mean = 8/3
     assert k.tolist() == [pytest.approx(4 / 3, rel=1e-6), 1.0, 1.0, pytest.approx(4 / 9, rel=1e-6)]
+
+
+# --------------------------------------------------------------------------------------------
+# Degenerate settings: the method's two relatives fall out of the same step.
+#  * r_min = r_max = 1 freezes the scaling coefficient at its warmup average -- the
+#    "LAMB + basic 1-bit" ablation of Section 3.4 / Appendix A.4;
+#  * one layer with c_avg = 1 on top of that is the compression stage of 1-bit Adam
+#    (Section 2: x -= lr * m / sqrt(v_frozen), no layerwise coefficient).
+# The expected update is written out in numpy from the wire contents (numpy.unpackbits).
+# --------------------------------------------------------------------------------------------
+def _degenerate_steps(off, W, c_avg, steps=4, seed=41):
+    from tests.refstep import RefStep
+    r = rng(seed)
+    ref = RefStep(off, W, server_chunk=W - 1, r_min=1.0, r_max=1.0)
+    N, n_pad, n_c = ref.N, ref.n_pad, ref.n_c
+    x0 = r.standard_normal(n_pad).astype(np.float32)
+    v = (np.abs(r.standard_normal(n_pad)) * 1e-4 + 1e-8).astype(np.float32)
+    ref.load_state(dict(x=x0, v_fresh=v, v_frozen=v, c_avg=np.asarray(c_avg, np.float32)))
+    lens = np.diff(np.asarray(off))
+    c_elem = np.zeros(n_pad); c_elem[:N] = np.repeat(np.asarray(c_avg, np.float64), lens)
+    for t in range(steps):
+        g = (r.standard_normal(n_pad) * 1e-3).astype(np.float32); g[N:] = 0
+        ref.set_foreign_in(r.integers(0, 2**32, W * n_c // 32, dtype=np.uint32), r.uniform(5e-5, 2e-4, W).astype(np.float32))
+        ref.set_foreign_all(r.integers(0, 2**32, n_pad // 32, dtype=np.uint32), r.uniform(5e-5, 2e-4, W).astype(np.float32))
+        x_before = ref.t["x"].astype(np.float64)
+        lr = 1e-3 * (t + 1)
+        ref.step(g, lr)
+        sign = np.unpackbits(ref.bits_all, bitorder="little").astype(np.float64) * 2 - 1
+        m_bar = sign * np.repeat(ref.server_scales.astype(np.float64), n_c)
+        want = x_before - lr * c_elem * m_bar / (np.sqrt(v.astype(np.float64)) + ref.h["eta"])
+        assert np.all(ref.t["r_prev"] == 1.0)
+        assert np.array_equal(ref.t["coeff_c"], np.asarray(c_avg, np.float32))
+        assert np.allclose(ref.t["x"][:N], want[:N], rtol=2e-6, atol=0)
+        assert np.array_equal(ref.t["x"][N:], x0[N:])            # padding is no layer's
+        assert np.array_equal(ref.t["m"][:N], m_bar[:N].astype(np.float32))
+    return ref
+
+
+def test_degenerate_frozen_coefficient():
+    # r pinned to 1: c_t = c_avg for ever, whatever v_fresh does (it still tracks the gradient)
+    ref = _degenerate_steps([0, 700, 701, 2000, 3000], 4, [0.3, 1.7, 0.9, 1.2])
+    assert not np.array_equal(ref.t["v_fresh"], ref.t["v_frozen"])
+
+
+def test_degenerate_single_layer_is_1bit_adam():
+    _degenerate_steps([0, 3000], 4, [1.0])
+    _degenerate_steps([0, 256], 1, [1.0])
+
+
+# --------------------------------------------------------------------------------------------
+# 16-bit storage formats (mixed-precision variant): pinned to numpy's binary16 and torch's
+# bfloat16 conversions (library routines), to hand-worked ties and to exhaustive round trips
+# --------------------------------------------------------------------------------------------
+def _same_bits_or_nan(a, b, fmt):
+    exp_all = 0x7c00 if fmt == 1 else 0x7f80
+    nan_a = ((a & exp_all) == exp_all) & ((a & ~np.uint16(exp_all | 0x8000)) != 0)
+    nan_b = ((b & exp_all) == exp_all) & ((b & ~np.uint16(exp_all | 0x8000)) != 0)
+    return np.all((a == b) | (nan_a & nan_b))
+
+
+def test_lp_decode_all_patterns():
+    from oracle.obref import lp_decode
+    bits = np.arange(65536, dtype=np.uint16)
+    want16 = bits.view(np.float16).astype(np.float32)
+    got16 = lp_decode(1, bits)
+    assert np.array_equal(got16.view(np.uint32)[~np.isnan(want16)], want16.view(np.uint32)[~np.isnan(want16)])
+    assert np.array_equal(np.isnan(got16), np.isnan(want16))
+    # bfloat16 is the upper half of a binary32 pattern
+    wantb = (bits.astype(np.uint32) << 16).view(np.float32)
+    gotb = lp_decode(2, bits)
+    ok = ~np.isnan(wantb)
+    assert np.array_equal(gotb.view(np.uint32)[ok], wantb.view(np.uint32)[ok])
+    assert np.array_equal(np.isnan(gotb), np.isnan(wantb))
+    # the scale is one binary32 multiply
+    assert lp_decode(1, np.array([0x3c00, 0xc000, 0x0001], np.uint16), 0.25).tolist() == [0.25, -0.5, 2.0 ** -26]
+
+
+def test_lp_round_trip_is_identity():
+    from oracle.obref import lp_decode, lp_round
+    bits = np.arange(65536, dtype=np.uint16)
+    for fmt in (1, 2):
+        back = lp_round(fmt, lp_decode(fmt, bits))
+        assert _same_bits_or_nan(back, bits, fmt)
+
+
+def test_lp_round_hand_cases():
+    from oracle.obref import lp_round
+    f = lambda *v: np.array(v, np.float32)
+    # binary16: 1 + 2^-11 is a tie between 1 (even) and 1 + 2^-10 -> 1; 1 + 3*2^-11 ties up to even
+    assert lp_round(1, f(1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -20)).tolist() == [0x3c00, 0x3c02, 0x3c01]
+    # largest finite 65504; 65519.99 rounds down to it, 65520 (the tie) goes to infinity
+    assert lp_round(1, f(65504, 65519.996, 65520, -1e30)).tolist() == [0x7bff, 0x7bff, 0x7c00, 0xfc00]
+    # subnormals: 2^-24 is the smallest; 2^-25 ties to zero (even), 3*2^-25 ties to 2*2^-24
+    assert lp_round(1, f(2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25, 2.0 ** -25 * 1.0001, -0.0)).tolist() == [1, 0, 2, 1, 0x8000]
+    # rounding up across a binade and from the largest subnormal into the smallest normal
+    assert lp_round(1, f(2047.5, 2.0 ** -14 - 2.0 ** -26)).tolist() == [0x6800, 0x0400]
+    # bfloat16: 1 + 2^-8 ties to 1; 1 + 2^-8 + 2^-23 goes up; 3.3895314e38 -> Inf
+    assert lp_round(2, f(1 + 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -23, 1 + 3 * 2.0 ** -8)).tolist() == [0x3f80, 0x3f81, 0x3f82]
+    assert lp_round(2, np.array([0x7f7fffff, 0x7f7f7fff, 0x00000001, 0x00008000, 0x00018000], np.uint32).view(np.float32)).tolist() == \
+        [0x7f80, 0x7f7f, 0, 0, 2]
+    assert lp_round(1, f(np.nan)).tolist() == [0x7e00] and lp_round(2, f(np.nan, np.inf, -np.inf)).tolist() == [0x7fc0, 0x7f80, 0xff80]
+
+
+def test_lp_round_matches_library_conversions():
+    import torch
+    from oracle.obref import lp_round
+    r = rng(77)
+    x = np.concatenate([
+        (r.standard_normal(200000) * np.exp(r.uniform(-30, 12, 200000))).astype(np.float32),
+        r.integers(0, 2 ** 32, 200000, dtype=np.uint32).view(np.float32),      # every exponent, NaNs, Infs
+        (np.arange(65536, dtype=np.uint32) << 13 | 0x1000).view(np.float32),   # exact binary16 ties
+        ((np.arange(65536, dtype=np.uint32) << 16) | 0x8000).view(np.float32)])  # exact bfloat16 ties
+    with np.errstate(over="ignore", invalid="ignore"):
+        want16 = x.astype(np.float16).view(np.uint16)
+    assert _same_bits_or_nan(lp_round(1, x), want16, 1)
+    wantb = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert _same_bits_or_nan(lp_round(2, x), wantb, 2)
