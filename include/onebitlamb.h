@@ -232,7 +232,9 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * step's outputs are undefined and a device-side flag is raised.  ob_lamb_check_device_status
  * synchronises `hip_stream`, reads that flag and returns OB_OK, or OB_ERR_STATE after re-arming
  * the context to use the two-pass kernels from then on.  Call it whenever you synchronise anyway
- * (e.g. once per logging interval).  ob_lamb_uses_single_pass reports the current choice (1/0). */
+ * (e.g. once per logging interval).  ob_lamb_uses_single_pass reports the current choice (1/0).
+ * OB_LAMB_SPIN_LIMIT=n at ob_lamb_create lowers the bound of the waits (0: give up after one poll);
+ * it exists so that this path can be tested without ever hanging a kernel. */
 ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream);
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx);
 

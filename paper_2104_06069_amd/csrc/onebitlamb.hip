@@ -513,6 +513,12 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     // every instantiation is built for at least 4 workgroups per CU (its launch bounds); count no more
     // than that, whatever this one reaches
     const int64_t slots = (int64_t)std::min(per_cu, 4) * cus;
+    // OB_LAMB_SPIN_LIMIT=n lowers the bound of the device-side waits (tests of the expiry path: with
+    // 0 every wait gives up after one poll, all kernels still run to their end)
+    if (const char* sl = getenv("OB_LAMB_SPIN_LIMIT")) {
+      const long v = atol(sl);
+      if (v >= 0 && v < ctx->spin_limit) ctx->spin_limit = (int)v;
+    }
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }

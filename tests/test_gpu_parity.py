@@ -21,7 +21,7 @@ def _need_gpu():
         pytest.skip("no GPU visible")
 
 
-def DeviceStep(*a, two_pass=False, fused_max_tiles=None, **k):
+def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, **k):
     """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
     kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
     import os
@@ -29,6 +29,9 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, **k):
     import paper_2104_06069_amd as ob
     old = os.environ.pop("OB_LAMB_TWO_PASS", None)
     old2 = os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
+    os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
+    if spin_limit is not None:
+        os.environ["OB_LAMB_SPIN_LIMIT"] = str(spin_limit)
     if two_pass:
         os.environ["OB_LAMB_TWO_PASS"] = "1"
     if fused_max_tiles is not None:
@@ -38,6 +41,7 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, **k):
     finally:
         os.environ.pop("OB_LAMB_TWO_PASS", None)
         os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
+        os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
         if old is not None:
             os.environ["OB_LAMB_TWO_PASS"] = old
         if old2 is not None:
@@ -618,4 +622,58 @@ def test_mixed_precision_argument_errors():
     assert status(ob.ob_lamb_ratios_apply_lp, dev.packed_all, dev.server_scales, 1e-3, g16, ob.OB_F32) == -2
     assert status(ob.ob_lamb_decompress_apply_lp, dev.packed_all, dev.server_scales, 1e-3, g16.data_ptr() + 2, ob.OB_BF16) == -3
     assert status(ob.ob_lamb_warmup_step_lp, g16, ob.OB_F16, 1.0, 1e-3, g16, 5) == -2
+    finish(dev)
+
+
+@pytest.mark.parametrize("which", ["compress", "ratios_apply"])
+def test_expired_wait_is_reported_and_recovered(which):
+    """The in-kernel barriers wait a bounded number of polls.  With the bound forced to 0 from the
+    host every waiting workgroup gives up after its first poll, raises the device flag and runs to
+    its end (nothing hangs, all accesses stay in bounds).  ob_lamb_check_device_status must report
+    that once, switch the context to the barrier-free kernels, and the next steps -- from a restored
+    state -- must again agree with the oracle."""
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    cfg = make_case("tiny")       # 16 tiles of 16384 per chunk, 32 tiles of 8192 per layer
+    st = Streams(5)
+    pl = cfg["plist"]
+    ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **HYPER)
+    # "ratios_apply": the worker compression runs as two passes, so only the per-layer barrier trips
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], two_pass=(which == "ratios_apply"),
+                     packed_momentum=True, fused_apply=True, spin_limit=0, **HYPER)
+    assert ob.ob_lamb_fused_layers(dev.ctx) == pl.L
+    ref.load_state(init_state(st, cfg))
+    dev.load_state(ref.t)
+
+    def one_step(t, check):
+        g = gradient(st, cfg, t)
+        fw, fs = foreign_worker_chunks(st, cfg, t)
+        fa, fss = foreign_server_chunks(st, cfg, t)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        dev.begin_step()
+        dev.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+        dev.scales_in.copy_(torch.from_numpy(fs))
+        dev.packed_all.copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
+        dev.server_scales.copy_(torch.from_numpy(fss))
+        ref.step(g, 1e-3)
+        dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+        if check:
+            assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
+            for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+                assert_close(dev.get(k), ref.t[k], f"step {t} {k}")
+
+    # the first step reads the fp32 momentum (two plain kernels behind ratios_apply), the second one
+    # runs the kernel with the per-layer barrier
+    for t in range(1 if which == "compress" else 2):
+        one_step(t, check=False)
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_check_device_status(dev.ctx, dev.stream)
+    assert e.value.status == -4
+    assert ob.ob_lamb_uses_single_pass(dev.ctx) == 0 and ob.ob_lamb_fused_layers(dev.ctx) == 0
+    ob.ob_lamb_check_device_status(dev.ctx, dev.stream)      # reported once; the context is usable again
+    # restore the state the failed step(s) clobbered, then go on
+    dev.load_state(ref.t)
+    dev.m_is_packed = False
+    for t in range(2, 6):
+        one_step(t, check=True)
     finish(dev)
