@@ -181,3 +181,62 @@ def test_gpt_1p3b_windows():
         print(f"gpt window chunks [{c0},{c1}): {idx.size} whole layers checked", flush=True)
     assert whole >= 12
     finish(dev)
+
+
+def test_bert_base_two_stage_with_generated_momentum_scale():
+    """BERT-Base-shaped list (L = 158, W = 16) with per-tensor gradient scales spread over a factor
+    of 100 -- the case momentum scaling (Appendix A.5.2) is for: two LAMB steps, the end-of-warmup
+    snapshot with the coefficients GENERATED on the device, then compression-stage steps in the
+    benchmarked configuration (1-bit momentum, ratio pass and update in one call)."""
+    _need_gpu()
+    from paper_2104_06069_amd.step import DeviceStep as D
+    cfg = make_config("bert_base")
+    pl, W, c = cfg["plist"], cfg["W"], 5
+    hyper = dict(HYPER, c_min=1e-3)
+    st = Streams(4, device="cuda:0")
+    dev = D(pl.offsets, W, c, packed_momentum=True, fused_apply=True, **hyper)
+    s = init_state(st, cfg)
+    for k in ("v_fresh", "v_frozen", "c_avg"):
+        s[k].zero_() if hasattr(s[k], "zero_") else s[k].fill(0)
+    dev.load_state(s)
+    ref = RefStep(pl.offsets, W, c, **hyper)
+    ref.load_state({k: dev.get(k) for k in ref.t})
+    kappa = layer_kappa(st, cfg)
+    assert kappa.max() / kappa.min() > 20
+    T_w, T = 2, 5
+    for t in range(T):
+        g = gradient(st, cfg, t, kappa=kappa)
+        gh = g.cpu().numpy()
+        fw, fs = foreign_worker_chunks(st, cfg, t)
+        fa, fss = foreign_server_chunks(st, cfg, t)
+        fwh, fah = fw.cpu().numpy(), fa.cpu().numpy()
+
+        def fill_ref(r):
+            r.set_foreign_in(fwh, fs); r.set_foreign_all(fah, fss)
+
+        def fill_dev(d):
+            d.packed_in.copy_(fw); d.scales_in.copy_(torch.from_numpy(fs))
+            d.packed_all.copy_(fa); d.server_scales.copy_(torch.from_numpy(fss))
+
+        t0 = time.time()
+        ref.train_step(t, T_w, gh, 1e-3, fill_ref)
+        print(f"bert_base: oracle step {t}: {time.time() - t0:.1f} s", flush=True)
+        dev.train_step(t, T_w, g, 1e-3, fill_dev)
+        torch.cuda.synchronize()
+        if t == T_w - 1:
+            k_dev = dev.t["mom_scale"].cpu().numpy()
+            assert_close(k_dev, ref.mom_scale, "generated momentum-scale coefficients")
+            print(f"bert_base: k_l spans {k_dev.min():.3g} .. {k_dev.max():.3g}", flush=True)
+            assert k_dev.max() / k_dev.min() > 20
+            assert np.array_equal(dev.get("v_frozen"), dev.get("v_fresh"))
+            dev.load_state(ref.t)                      # identical bits at the hand-off ...
+            dev.t["mom_scale"].copy_(torch.from_numpy(ref.mom_scale))   # ... coefficients included
+        if t >= T_w:
+            assert np.array_equal(words_of(dev.packed_local), ref.bits_local), f"step {t}: worker sign words"
+            assert np.array_equal(words_of(dev.packed_all), ref.bits_all), f"step {t}: server sign words"
+        nd = {k: assert_close(dev.get(k), ref.t[k], f"step {t} {k}")
+              for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c", "c_avg")}
+        print(f"bert_base: step {t}: elements not bit-equal (within 1e-6): {nd}", flush=True)
+    import paper_2104_06069_amd as ob
+    assert ob.ob_lamb_fused_layers(dev.ctx) > 50
+    finish(dev)

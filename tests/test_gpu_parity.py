@@ -677,3 +677,73 @@ def test_expired_wait_is_reported_and_recovered(which):
     for t in range(2, 6):
         one_step(t, check=True)
     finish(dev)
+
+
+@pytest.mark.parametrize("packed,fused,use_k", [(False, False, False), (True, True, True)])
+def test_gpu_rank_inside_a_simulated_job(packed, fused, use_k):
+    """The device plays ONE rank (worker r and server of chunk r) of a W-rank data-parallel job whose
+    other ranks are oracle instances with their own gradients and error buffers (Section 5: every
+    rank compresses its own momentum, chunk c of all ranks meets at server c, every rank applies the
+    same recompressed momentum).  What the device sends must equal what the oracle rank r would send,
+    and its parameters must stay identical to those of the other ranks."""
+    _need_gpu()
+    W, r = 4, 2
+    pl = ParamList("job", [(f"t{i}", s) for i, s in enumerate([5000, 3, 20000, 777, 9000])])
+    n_pad = padded_len(pl.N, W)
+    n_c = n_pad // W
+    cfg = dict(name="job", plist=pl, W=W, n_pad=n_pad, n_c=n_c, grad="student_t3")
+    st = Streams(21)
+    k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if use_k else None
+    s0 = init_state(st, cfg)
+    # one oracle rank per worker; rank w also holds the server error of chunk w
+    ranks = [RefStep(pl.offsets, W, w, mom_scale=k, **HYPER) for w in range(W)]
+    for w, rk in enumerate(ranks):
+        rk.load_state(s0)
+    dev = DeviceStep(pl.offsets, W, r, mom_scale=k, packed_momentum=packed, fused_apply=fused, **HYPER)
+    dev.load_state(ranks[r].t)
+    wb = n_c // 8
+    for t in range(12):
+        lr = 1e-3 * (1 + t % 3)
+        grads = [gradient(st, cfg, t, stream=f"grad_rank{w}") for w in range(W)]
+        # --- oracle job: every worker compresses, every server reduces its chunk
+        for w, rk in enumerate(ranks):
+            rk.compress_local(grads[w])
+        for c, rk in enumerate(ranks):
+            for w in range(W):
+                rk.bits_in[w * wb:(w + 1) * wb] = ranks[w].bits_local[c * wb:(c + 1) * wb]
+                rk.scales_in[w] = ranks[w].scales_local[c]
+            rk.server_reduce()
+        bits_all = np.concatenate([ranks[c].bits_all[c * wb:(c + 1) * wb] for c in range(W)])
+        sscales = np.array([ranks[c].server_scales[c] for c in range(W)], np.float32)
+        for rk in ranks:
+            rk.bits_all[...] = bits_all
+            rk.server_scales[...] = sscales
+            rk.layer_ratios()
+            rk.decompress_apply(lr)
+        # --- the device as rank r: its own gradient, the peers' chunks r, the peers' server outputs
+        dev.begin_step()
+        dev.compress_local(torch.from_numpy(grads[r]).to(dev.device))
+        assert np.array_equal(words_of(dev.packed_local), ranks[r].bits_local), f"step {t}: what rank r sends"
+        assert_close(dev.scales_local.cpu().numpy(), ranks[r].scales_local, "worker scales")
+        dev.packed_in.copy_(torch.from_numpy(ranks[r].bits_in.view(np.int32)))   # the all-to-all's result ...
+        dev.scales_in.copy_(torch.from_numpy(ranks[r].scales_in))
+        dev.packed_in[r * (n_c // 32):(r + 1) * (n_c // 32)].zero_()             # ... own slot comes from gather()
+        dev.gather()
+        dev.packed_all.copy_(torch.from_numpy(bits_all.view(np.int32)))          # the all-gather's result ...
+        dev.server_scales.copy_(torch.from_numpy(sscales))
+        dev.packed_all[r * (n_c // 32):(r + 1) * (n_c // 32)].zero_()            # ... own slot from server_reduce()
+        dev.server_scales[r] = 0.0
+        dev.server_reduce()
+        assert np.array_equal(words_of(dev.packed_all), bits_all), f"step {t}: recompressed momentum"
+        assert_close(dev.server_scales.cpu().numpy(), sscales, "server scales")
+        if fused:
+            dev.ratios_apply(lr)
+        else:
+            dev.layer_ratios()
+            dev.decompress_apply(lr)
+        for key in ("x", "m", "v_fresh", "r_prev", "coeff_c", "err_worker", "err_server"):
+            assert_close(dev.get(key), ranks[r].t[key], f"step {t} {key}")
+        # every rank of the job holds the same parameters and momentum
+        for rk in ranks:
+            assert np.array_equal(rk.t["x"], ranks[0].t["x"]) and np.array_equal(rk.t["m"], ranks[0].t["m"])
+    finish(dev)
