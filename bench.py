@@ -42,6 +42,7 @@ KERNEL_BYTES = {
         "server_sign_pack": (8.125, "n_c"),
         "warmup_moments": (24.0, "n_pad"),       # R g, m, v, x (16) + W m, v (8)
         "warmup_apply": (16.0, "n_pad"),         # R m, v, x (12) + W x (4)
+        "warmup_resident": (28.0, "wfused"),     # R g, m, v, x (16) + W m, v, x (12)
     },
 }
 
@@ -195,12 +196,17 @@ def main():
     KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
     g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
-    for k in ("compress_resident", "momentum_z_sumsq", "warmup_moments"):
+    for k in ("compress_resident", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):
         KB[k] = (KB[k][0] - g_less, KB[k][1])
-    for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply"):
+    for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply", "warmup_resident"):
         KB[k] = (KB[k][0] + x_more, KB[k][1])
     fused_params = ob.ob_lamb_fused_params(ds.ctx) if ds.fused_apply else 0
-    units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params}
+    wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
+    units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params, "wfused": wfused}
+    if wfused:   # the two-pass warmup kernels then cover only the remaining layers (two launches each)
+        for k in ("warmup_moments", "warmup_apply"):
+            KB[k] = (KB[k][0], "rest_w")
+        units["rest_w"] = ds.n_pad - wfused
     if ds.fused_apply:   # the plain ratio/update kernels then cover only the remaining layers
         for k in ("ratios_pass", "decompress_apply"):
             KB[k] = (KB[k][0], "rest")
@@ -210,7 +216,7 @@ def main():
             bpe, unit = KB[k]
             # "rest" is covered by two launches per call (tiles on the boundaries of the fused
             # layers, then the remaining layers): per-launch mean
-            per_call = max(1, round(v["launches"] / args.profile_steps)) if unit == "rest" else 1
+            per_call = max(1, round(v["launches"] / args.profile_steps)) if unit in ("rest", "rest_w") else 1
             v["algo_bytes"] = bpe * units[unit] / per_call
             v["GBps"] = round(v["algo_bytes"] / (v["avg_ms"] * 1e-3) / 1e9, 1)
     dom = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
@@ -273,7 +279,10 @@ def main():
     ms_ms = timed(lambda: ds.momentum_scale())
     out["reference_calls"] = {
         "warmup_step_ms": round(wu_ms, 4),
-        "warmup_step_GBps": round((40.0 - g_less + x_more) * ds.n_pad / (wu_ms * 1e-3) / 1e9, 1),   # 24 + 16 B/elem, two passes
+        # 28 B/elem where g, m, v, x are read once, 24 + 16 in the two-pass form
+        "warmup_step_GBps": round(((28.0 - g_less + x_more) * wfused + (40.0 - g_less + x_more) * (ds.n_pad - wfused))
+                                  / (wu_ms * 1e-3) / 1e9, 1),
+        "warmup_single_pass_params": wfused,
         "warmup_step_params_per_s": round(pl.N / (wu_ms * 1e-3), 1),
         "momentum_scale_ms": round(ms_ms, 4),
         "momentum_scale_GBps": round(4.0 * ds.n_pad / (ms_ms * 1e-3) / 1e9, 1)}

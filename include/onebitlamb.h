@@ -187,6 +187,12 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx);
 /* ... and the number of parameters in those layers. */
 int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx);
+/* The same two counts for ob_lamb_warmup_step, which reads g, m, v and x once (one kernel with a
+ * per-layer barrier that keeps eq. (1)'s update direction and x in registers while the layer's
+ * norms complete) for every layer whose tiles fit on the device, and takes two passes for the
+ * rest.  OB_LAMB_TWO_PASS_WARMUP=1 at ob_lamb_create forces two passes for every layer. */
+int64_t ob_lamb_warmup_fused_layers(const ob_lamb_ctx* ctx);
+int64_t ob_lamb_warmup_fused_params(const ob_lamb_ctx* ctx);
 
 /* Appendix A.5.2, end of warmup: forms the momentum-scale coefficients from the dense momentum
  * st->m and writes them to st->mom_scale [L] (must be non-NULL here).  The paper gives no formula;

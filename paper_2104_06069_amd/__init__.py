@@ -13,4 +13,5 @@ from .binding import (  # noqa: F401
     ob_lamb_uses_single_pass, ob_lamb_momentum_dense, ob_lamb_momentum_scale, ob_lamb_ratios_apply, ob_lamb_fused_layers, ob_lamb_fused_params,
     OB_F32, OB_F16, OB_BF16, ob_lamb_warmup_step_lp, ob_lamb_compress_local_lp,
     ob_lamb_decompress_apply_lp, ob_lamb_ratios_apply_lp,
+    ob_lamb_warmup_fused_layers, ob_lamb_warmup_fused_params,
 )

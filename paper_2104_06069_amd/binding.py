@@ -72,6 +72,8 @@ def lib():
             "ob_lamb_ratios_apply_lp": (C.c_int, [vp, sp, vp, vp, f, vp, C.c_int, vp]),
             "ob_lamb_fused_layers": (i64, [vp]),
             "ob_lamb_fused_params": (i64, [vp]),
+            "ob_lamb_warmup_fused_layers": (i64, [vp]),
+            "ob_lamb_warmup_fused_params": (i64, [vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
@@ -220,6 +222,14 @@ def ob_lamb_fused_layers(ctx):
 
 def ob_lamb_fused_params(ctx):
     return int(lib().ob_lamb_fused_params(ctx))
+
+
+def ob_lamb_warmup_fused_layers(ctx):
+    return int(lib().ob_lamb_warmup_fused_layers(ctx))
+
+
+def ob_lamb_warmup_fused_params(ctx):
+    return int(lib().ob_lamb_warmup_fused_params(ctx))
 
 
 def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):

@@ -1111,15 +1111,17 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     GradSrc g, float* __restrict__ m, float* __restrict__ v,
     const float* __restrict__ x, double* __restrict__ seg_sums /* [2*n_segs] */, int64_t n_c,
     int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd, LayerTab lt,
-    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer) {
+    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer, LayerSel sel) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
+  const TilePos p =
+      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
   const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
   const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  if (uniform && sel.skip && sel.skip[l0]) return;
   v4f G[U], M[U], V[U], X[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -1170,10 +1172,15 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     for (int u = 0; u < U; ++u) {
       const int o = u * SPAN + o0;
       if (o < p.len) {
+        int l = l0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int64_t i = p.tile0 + o + k;
           if (i < N) {
+            if (sel.skip) {
+              l = walk_layer(l, i, lt.off);
+              if (sel.skip[l]) continue;
+            }
             m[i] = M[u][k];
             v[i] = V[u][k];
           }
@@ -1183,6 +1190,7 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     const int s1 = tile_seg0[p.t + 1];
     for (int s = s0; s < s1; ++s) {
       const int l = seg_layer[s];
+      if (sel.skip && sel.skip[l]) continue;
       const int64_t a = lt.off[l], b = lt.off[l + 1];
       double sx = 0.0, su = 0.0;
 #pragma unroll
@@ -1210,13 +1218,30 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
   }
 }
 
+// eq. (1)'s coefficient of one layer from its sums of x^2 and u^2, and Algorithm 1 line 2
+// (thread 0 of a workgroup).
+__device__ __forceinline__ float warmup_coeff_commit(double sx, double su, int l,
+                                                     float* __restrict__ coeff_c,
+                                                     float* __restrict__ c_avg, float c_min,
+                                                     float c_max, float beta3, float omb3) {
+  const float nx = (float)sqrt(sx), nu = (float)sqrt(su);
+  float c = nx / nu;
+  c = (c > c_min) ? c : c_min;
+  c = (c < c_max) ? c : c_max;
+  coeff_c[l] = c;
+  c_avg[l] = beta3 * c_avg[l] + omb3 * c;
+  return c;
+}
+
 __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restrict__ seg_sums,
                                                          const int* __restrict__ layer_seg0,
                                                          float* __restrict__ coeff_c,
                                                          float* __restrict__ c_avg, float c_min,
-                                                         float c_max, float beta3, float omb3) {
+                                                         float c_max, float beta3, float omb3,
+                                                         const unsigned char* __restrict__ skip) {
   __shared__ double lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
+  if (skip && skip[l]) return;
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   double sx = 0.0, su = 0.0;
   for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
@@ -1225,28 +1250,23 @@ __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restric
   }
   sx = block_sum<FBLOCK>(sx, lds);
   su = block_sum<FBLOCK>(su, lds);
-  if (threadIdx.x == 0) {
-    const float nx = (float)sqrt(sx), nu = (float)sqrt(su);
-    float c = nx / nu;
-    c = (c > c_min) ? c : c_min;
-    c = (c < c_max) ? c : c_max;
-    coeff_c[l] = c;
-    c_avg[l] = beta3 * c_avg[l] + omb3 * c;
-  }
+  if (threadIdx.x == 0) (void)warmup_coeff_commit(sx, su, l, coeff_c, c_avg, c_min, c_max, beta3, omb3);
 }
 
 template <int U, bool LPX = false>
 __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
     const float* __restrict__ m, const float* __restrict__ v, float* __restrict__ x,
     const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, float wd,
-    LayerTab lt, void* __restrict__ x_lp, int x_lp_bf16) {
+    LayerTab lt, void* __restrict__ x_lp, int x_lp_bf16, LayerSel sel) {
   constexpr int TILE = SPAN * U;
-  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
+  const TilePos p =
+      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
   const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
   const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
+  if (uniform && sel.skip && sel.skip[l0]) return;
   v4f M[U], V[U], X[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -1283,6 +1303,7 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
           const int64_t i = p.tile0 + o + k;
           if (i < N) {
             l = walk_layer(l, i, lt.off);
+            if (sel.skip && sel.skip[l]) continue;
             const float a = lr * coeff_c[l];
             const float xn = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
             x[i] = xn;
@@ -1290,6 +1311,145 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
           }
         }
       }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K8 a+b+c in one pass for the layers that fit on the device: eq. (1) with g, m, v and x read once.
+// A workgroup updates the moments of its tile, writes them, keeps u and x in registers, publishes
+// the tile's fp64 sums of x^2 and u^2 and arrives at its layer's barrier; the last of the layer's
+// listed tiles to arrive sums ALL of the layer's segment sums in a fixed order, forms c, commits
+// coeff_c and c_avg (Algorithm 1 line 2) and publishes c; the others wait for it and then update x
+// from registers.  Same split of the work as for k_ratios_apply_resident: only tiles inside one
+// eligible layer; the pieces at layer boundaries go through k_warmup_moments before (their sums
+// wait in seg_sums) and k_warmup_apply after.  Same synchronisation and bounded waits.
+// ---------------------------------------------------------------------------------------------
+struct WarmSync {
+  double* seg_sums;             // [2 * segments of this kernel's tiling]
+  const int* layer_seg0;        // [L+1]
+  const int* n_listed;          // [L] tiles of the layer that this kernel covers
+  unsigned long long* counter;  // [L]
+  unsigned long long* flag;     // [L] (epoch << 32) | bits of c
+  unsigned int* errflag;
+  unsigned int epoch;
+  int spin_limit;
+  float* coeff_c;
+  float* c_avg;
+  float c_min, c_max, beta3, omb3;
+};
+
+#ifndef OB_WU_MINW
+#define OB_WU_MINW 4
+#endif
+template <int U, int G, int GT, bool LPX>
+__global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
+    GradSrc g, float* __restrict__ m, float* __restrict__ v, float* __restrict__ x, WarmSync ws,
+    int64_t n_c, int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd,
+    float lr, LayerTab lt, const int* __restrict__ tile_seg0, const int* __restrict__ tile_list,
+    void* __restrict__ x_lp, int x_lp_bf16) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  __shared__ unsigned long long bc;
+  const TilePos p = tile_pos<TILE>(n_c, tpc, tile_list[blockIdx.x]);
+  const int l0 = lt.first_layer[p.t];  // the (eligible) layer the tile lies in
+  const int s0 = tile_seg0[p.t];       // the tile's only segment
+  const int o0 = threadIdx.x * 4;
+  v4f UU[U], X[U];
+  double sx = 0.0, su = 0.0;
+#pragma unroll
+  for (int u0 = 0; u0 < U; u0 += G) {
+    v4f Gr[G], M[G], V[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int o = (u0 + j) * SPAN + o0;
+      X[u0 + j] = 0.0f; UU[u0 + j] = 0.0f;
+      if (o < p.len) {
+        Gr[j] = load_grad<GT>(g, p.tile0 + o);
+        M[j] = ld4(m + p.tile0 + o);
+        V[j] = ld4(v + p.tile0 + o);
+        X[u0 + j] = ld4(x + p.tile0 + o);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int o = (u0 + j) * SPAN + o0;
+      if (o < p.len) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          M[j][k] = beta1 * M[j][k] + omb1 * Gr[j][k];
+          V[j][k] = beta2 * V[j][k] + omb2 * (Gr[j][k] * Gr[j][k]);
+        }
+        st4(m + p.tile0 + o, M[j]);
+        st4(v + p.tile0 + o, V[j]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float uu = lamb_u(M[j][k], V[j][k], X[u0 + j][k], eta, wd);
+          UU[u0 + j][k] = uu;
+          sx += (double)X[u0 + j][k] * (double)X[u0 + j][k];
+          su += (double)uu * (double)uu;
+        }
+      }
+    }
+  }
+  sx = block_sum(sx, lds);
+  su = block_sum(su, lds);
+  // arrive: publish the segment's sums, then count; the last arriver finishes the layer
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&ws.seg_sums[2 * (int64_t)s0], sx, __ATOMIC_RELAXED, OB_AGENT);
+    __hip_atomic_store(&ws.seg_sums[2 * (int64_t)s0 + 1], su, __ATOMIC_RELAXED, OB_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // stores complete before the add
+    const unsigned long long prev =
+        __hip_atomic_fetch_add(&ws.counter[l0], 1ull, __ATOMIC_RELAXED, OB_AGENT);
+    bc = (prev + 1ull == (unsigned long long)ws.epoch * (unsigned long long)ws.n_listed[l0]) ? 1ull : 0ull;
+  }
+  __syncthreads();
+  const bool last = (bc != 0ull);
+  __syncthreads();
+  float c;
+  if (last) {
+    const int a = ws.layer_seg0[l0], b = ws.layer_seg0[l0 + 1];
+    double tx = 0.0, tu = 0.0;
+    for (int j = a + threadIdx.x; j < b; j += BLOCK) {
+      tx += __hip_atomic_load(&ws.seg_sums[2 * (int64_t)j], __ATOMIC_RELAXED, OB_AGENT);
+      tu += __hip_atomic_load(&ws.seg_sums[2 * (int64_t)j + 1], __ATOMIC_RELAXED, OB_AGENT);
+    }
+    tx = block_sum(tx, lds);
+    tu = block_sum(tu, lds);
+    if (threadIdx.x == 0) {
+      const float cc = warmup_coeff_commit(tx, tu, l0, ws.coeff_c, ws.c_avg, ws.c_min, ws.c_max,
+                                           ws.beta3, ws.omb3);
+      const unsigned long long f =
+          ((unsigned long long)ws.epoch << 32) | (unsigned long long)__float_as_uint(cc);
+      __hip_atomic_store(&ws.flag[l0], f, __ATOMIC_RELAXED, OB_AGENT);
+      bc = f;
+    }
+  } else if (threadIdx.x == 0) {
+    unsigned long long f = 0ull;
+    for (int it = 0;; ++it) {
+      f = __hip_atomic_load(&ws.flag[l0], __ATOMIC_RELAXED, OB_AGENT);
+      if ((unsigned int)(f >> 32) == ws.epoch) break;
+      if (it >= ws.spin_limit) {
+        atomicOr(ws.errflag, 1u);
+        break;
+      }
+      if ((it & 63) == 63 && __hip_atomic_load(ws.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
+      __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
+    }
+    bc = f;
+  }
+  __syncthreads();
+  c = __uint_as_float((unsigned int)(bc & 0xffffffffull));
+  const float a = lr * c;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      v4f xn;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) xn[k] = X[u][k] - a * UU[u][k];
+      st4(x + p.tile0 + o, xn);
+      if (LPX) st4_lp(x_lp, p.tile0 + o, xn, x_lp_bf16);
     }
   }
 }

@@ -39,6 +39,7 @@ constexpr int TILE_RES = SPAN * U_RES;
 #endif
 constexpr int U_LB = OB_U_LB;  // ... in the fused ratio+update kernel (v_frozen and signs stay in registers)
 constexpr int TILE_LB = SPAN * U_LB;
+constexpr int G_WU = 2;        // the single-pass warmup kernel issues its loads G_WU accesses at a time
 
 enum KernelId {
   KID_MOMENTUM_Z = 0,
@@ -57,6 +58,7 @@ enum KernelId {
   KID_WARMUP_MOMENTS,
   KID_WARMUP_COEFF,
   KID_WARMUP_APPLY,
+  KID_WARMUP_RESIDENT,
   KID_FILL,
   KID_COPY,
   KID_COUNT
@@ -65,11 +67,34 @@ const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "ratios_pass",     "ratios_finalize",
     "decompress_apply", "ratios_apply_resident", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
-    "fill",             "copy"};
+    "warmup_resident",  "fill",            "copy"};
 
 struct ProfRec {
   int kid;
   hipEvent_t e0, e1;
+};
+
+// Split of the layers between a kernel with a per-layer barrier and the plain kernels.  A layer is
+// "eligible" for the barrier kernel when it has TILE_LB tiles that lie wholly inside it and they
+// all fit on the device at once (at most 80 % of that kernel's workgroup slots); the plain kernels
+// take the other layers (too large, smaller than a tile, or empty) and, on the barrier kernel's
+// tiling, the pieces of eligible layers in tiles that meet a layer boundary.
+struct LayerSplit {
+  bool on = false;          // at least one layer is eligible
+  int n_fused_tiles = 0;    // TILE_LB tiles inside one eligible layer (the barrier kernel's)
+  int n_bound_tiles = 0;    // TILE_LB tiles where an eligible layer meets a boundary
+  int n_plain_tiles = 0;    // TILE_MAIN tiles that hold a segment of a non-eligible layer
+  int64_t n_layers = 0;     // eligible layers
+  int64_t n_params = 0;     // parameters in them
+  int* d_fused_tiles = nullptr;
+  int* d_bound_tiles = nullptr;
+  int* d_n_listed = nullptr;               // [L] barrier-kernel tiles of each layer
+  int* d_plain_tiles = nullptr;
+  unsigned char* d_skip_plain = nullptr;   // [L] 1 for eligible layers (the plain kernels skip them)
+  unsigned char* d_skip_fused = nullptr;   // [L] 1 for the other layers
+  unsigned long long* d_counter = nullptr; // [L] arrivals, monotone
+  unsigned long long* d_flag = nullptr;    // [L] (epoch << 32) | payload
+  unsigned int epoch = 0;
 };
 
 }  // namespace
@@ -107,29 +132,17 @@ struct ob_lamb_ctx {
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
   unsigned int epoch = 0;
   int spin_limit = 1 << 20;
-  // fused ratio+update (k_ratios_apply_resident): its own tiling and the split of the layers into
-  // those it handles ("eligible": the layer's tiles fit on the device) and the rest
-  bool fused = false;             // at least one layer is eligible
+  // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
+  // tiling (TILE_LB) and, for each, the split of the layers between it and the plain kernels
   int tpc_lb = 0, n_tiles_lb = 0, n_segs_lb = 0;
-  int n_fused_tiles = 0;          // TILE_LB tiles inside one eligible layer (the fused kernel's)
-  int n_bound_tiles = 0;          // TILE_LB tiles where an eligible layer meets a boundary
-  int n_plain_tiles = 0;          // TILE_MAIN tiles that hold a segment of a non-eligible layer
-  int64_t n_fused_layers = 0;
-  int64_t n_fused_params = 0;     // parameters in the eligible layers
   int* d_first_layer_lb = nullptr;
   int* d_tile_seg0_lb = nullptr;
   int* d_seg_layer_lb = nullptr;
   int* d_layer_seg0_lb = nullptr;
-  int* d_fused_tiles = nullptr;
-  int* d_bound_tiles = nullptr;
-  int* d_n_listed = nullptr;      // [L] fused-kernel tiles of each layer
-  int* d_plain_tiles = nullptr;
-  unsigned char* d_skip_plain = nullptr;   // [L] 1 for eligible layers (the plain kernels skip them)
-  unsigned char* d_skip_fused = nullptr;   // [L] 1 for the other layers
   float* d_seg_max_lb = nullptr;           // [n_segs_lb]
-  unsigned long long* d_counter_lb = nullptr;  // [L]
-  unsigned long long* d_flag_lb = nullptr;     // [L]
-  unsigned int epoch_lb = 0;
+  double* d_seg_sums_lb = nullptr;         // [2*n_segs_lb]
+  LayerSplit sp_apply;                     // ob_lamb_ratios_apply
+  LayerSplit sp_warm;                      // ob_lamb_warmup_step
   // diagnostics
   bool profile = false;
   std::vector<ProfRec> prof;
@@ -321,6 +334,75 @@ bool build_tiling(int64_t tile, int64_t n_c, int64_t W, int64_t L, const std::ve
   for (int64_t l = 0; l < L; ++l)
     out->layer_seg0[(size_t)l + 1] = out->layer_seg0[(size_t)l] + count[(size_t)l];
   return true;
+}
+
+// Builds and uploads one LayerSplit.  tl / tm: the TILE_LB and TILE_MAIN tilings; max_tiles: the
+// largest number of whole tiles an eligible layer may have (0: no layer is eligible).
+bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off,
+                 int64_t max_tiles, LayerSplit* sp) {
+  const int64_t L = ctx->L;
+  std::vector<unsigned char> skip_plain((size_t)L, 0), skip_fused((size_t)L, 1);
+  std::vector<int> fused_tiles, bound_tiles, plain_tiles, n_listed((size_t)L, 0);
+  auto inside_one_layer = [&](int64_t t) {
+    const int64_t c = t / tl.tpc, b = t % tl.tpc;
+    const int64_t tile0 = c * ctx->n_c + b * TILE_LB;
+    const int64_t tile1 = std::min(tile0 + (int64_t)TILE_LB, (c + 1) * ctx->n_c);
+    const int l = tl.first[(size_t)t];
+    return l < L && tile1 <= h_off[(size_t)l + 1];
+  };
+  for (int64_t t = 0; t < tl.n_tiles; ++t)
+    if (inside_one_layer(t)) ++n_listed[(size_t)tl.first[(size_t)t]];
+  for (int64_t l = 0; l < L; ++l) {
+    const bool elig = n_listed[(size_t)l] >= 1 && n_listed[(size_t)l] <= max_tiles;
+    if (!elig) n_listed[(size_t)l] = 0;
+    skip_plain[(size_t)l] = elig ? 1 : 0;
+    skip_fused[(size_t)l] = elig ? 0 : 1;
+    sp->n_layers += elig ? 1 : 0;
+    sp->n_params += elig ? (h_off[(size_t)l + 1] - h_off[(size_t)l]) : 0;
+  }
+  sp->on = sp->n_layers > 0;
+  for (int64_t t = 0; t < tl.n_tiles; ++t) {
+    if (inside_one_layer(t)) {
+      if (skip_plain[(size_t)tl.first[(size_t)t]]) fused_tiles.push_back((int)t);
+      continue;
+    }
+    bool has = false;
+    for (int sgi = tl.tile_seg0[(size_t)t]; sgi < tl.tile_seg0[(size_t)t + 1]; ++sgi)
+      has = has || skip_plain[(size_t)tl.seg_layer[(size_t)sgi]];
+    if (has) bound_tiles.push_back((int)t);
+  }
+  for (int64_t t = 0; t < tm.n_tiles; ++t) {
+    bool has = false;
+    for (int sgi = tm.tile_seg0[(size_t)t]; sgi < tm.tile_seg0[(size_t)t + 1]; ++sgi)
+      has = has || !skip_plain[(size_t)tm.seg_layer[(size_t)sgi]];
+    if (has) plain_tiles.push_back((int)t);
+  }
+  sp->n_fused_tiles = (int)fused_tiles.size();
+  sp->n_bound_tiles = (int)bound_tiles.size();
+  sp->n_plain_tiles = (int)plain_tiles.size();
+  return upload(ctx, &sp->d_fused_tiles, fused_tiles) && upload(ctx, &sp->d_bound_tiles, bound_tiles) &&
+         upload(ctx, &sp->d_n_listed, n_listed) && upload(ctx, &sp->d_plain_tiles, plain_tiles) &&
+         upload(ctx, &sp->d_skip_plain, skip_plain) && upload(ctx, &sp->d_skip_fused, skip_fused) &&
+         alloc_zero(ctx, &sp->d_counter, (size_t)L) && alloc_zero(ctx, &sp->d_flag, (size_t)L);
+}
+
+void free_split(LayerSplit* sp) {
+  void* ptrs[] = {sp->d_fused_tiles, sp->d_bound_tiles, sp->d_n_listed, sp->d_plain_tiles,
+                  sp->d_skip_plain,  sp->d_skip_fused,  sp->d_counter,  sp->d_flag};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+}
+
+// Largest layer (in whole TILE_LB tiles) that a barrier kernel with `per_cu` resident workgroups
+// per CU may take: 80 % of the device's slots.  OB_LAMB_FUSED_MAX_TILES=n lowers it (tests of the
+// split between the two paths).
+int64_t split_max_tiles(int per_cu, int cus) {
+  int64_t max_tiles = (4 * (int64_t)per_cu * cus) / 5 - 8;
+  if (const char* mt = getenv("OB_LAMB_FUSED_MAX_TILES")) {
+    const long v = atol(mt);
+    if (v >= 0 && v < max_tiles) max_tiles = v;
+  }
+  return max_tiles < 0 ? 0 : max_tiles;
 }
 
 // launches of the ratio pass / finalize / update kernels over the layers selected by `sel`
@@ -522,73 +604,29 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }
-  // fused ratio+update: a layer is handled there when it has tiles that lie inside it and they all
-  // fit on the device at once (at most 80 % of the workgroup slots of that kernel); the plain
-  // kernels take the other layers (too large, smaller than a tile, or empty)
-  std::vector<unsigned char> skip_plain((size_t)L, 0), skip_fused((size_t)L, 1);
-  std::vector<int> fused_tiles, bound_tiles, plain_tiles, n_listed((size_t)L, 0);
+  // the two kernels with a per-layer barrier: which layers each of them takes.  The slot count is
+  // the kernel's launch bound (every instantiation reaches it), whatever the one queried reaches.
   if (ok) {
-    int per_cu = 0, cus = 0;
+    int per_cu_a = 0, per_cu_w = 0, cus = 0;
     ok = hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                         &per_cu, k_ratios_apply_resident<U_LB, true>, BLOCK, 0),
+                         &per_cu_a, k_ratios_apply_resident<U_LB, true>, BLOCK, 0),
+                "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
+         hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                         &per_cu_w, k_warmup_resident<U_LB, G_WU, 0, false>, BLOCK, 0),
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
-    const int64_t slots = (int64_t)std::min(per_cu, OB_LB_MINW) * cus;  // as above: the launch bound
-    const char* env = getenv("OB_LAMB_NO_FUSED_APPLY");
-    const bool allow = ok && !(env && env[0] == '1');
-    // OB_LAMB_FUSED_MAX_TILES=n lowers the limit (tests of the split between the two paths)
-    int64_t max_tiles = (4 * slots) / 5 - 8;
-    if (const char* mt = getenv("OB_LAMB_FUSED_MAX_TILES")) {
-      const long v = atol(mt);
-      if (v >= 0 && v < max_tiles) max_tiles = v;
-    }
-    // tiles of the fused kernel's tiling that lie inside one layer, per layer
-    auto inside_one_layer = [&](int64_t t) {
-      const int64_t c = t / tl.tpc, b = t % tl.tpc;
-      const int64_t tile0 = c * ctx->n_c + b * TILE_LB;
-      const int64_t tile1 = std::min(tile0 + (int64_t)TILE_LB, (c + 1) * ctx->n_c);
-      const int l = tl.first[(size_t)t];
-      return l < L && tile1 <= h_off[(size_t)l + 1];
-    };
-    for (int64_t t = 0; t < tl.n_tiles; ++t)
-      if (inside_one_layer(t)) ++n_listed[(size_t)tl.first[(size_t)t]];
-    for (int64_t l = 0; l < L; ++l) {
-      const bool elig = allow && n_listed[(size_t)l] >= 1 && n_listed[(size_t)l] <= max_tiles;
-      if (!elig) n_listed[(size_t)l] = 0;
-      skip_plain[(size_t)l] = elig ? 1 : 0;
-      skip_fused[(size_t)l] = elig ? 0 : 1;
-      ctx->n_fused_layers += elig ? 1 : 0;
-      ctx->n_fused_params += elig ? (h_off[(size_t)l + 1] - h_off[(size_t)l]) : 0;
-    }
-    ctx->fused = ctx->n_fused_layers > 0;
-    for (int64_t t = 0; t < tl.n_tiles; ++t) {
-      if (inside_one_layer(t)) {
-        if (skip_plain[(size_t)tl.first[(size_t)t]]) fused_tiles.push_back((int)t);
-        continue;
-      }
-      bool has = false;
-      for (int sgi = tl.tile_seg0[(size_t)t]; sgi < tl.tile_seg0[(size_t)t + 1]; ++sgi)
-        has = has || skip_plain[(size_t)tl.seg_layer[(size_t)sgi]];
-      if (has) bound_tiles.push_back((int)t);
-    }
-    for (int64_t t = 0; t < tm.n_tiles; ++t) {
-      bool has = false;
-      for (int sgi = tm.tile_seg0[(size_t)t]; sgi < tm.tile_seg0[(size_t)t + 1]; ++sgi)
-        has = has || !skip_plain[(size_t)tm.seg_layer[(size_t)sgi]];
-      if (has) plain_tiles.push_back((int)t);
-    }
-    ctx->n_fused_tiles = (int)fused_tiles.size();
-    ctx->n_bound_tiles = (int)bound_tiles.size();
-    ctx->n_plain_tiles = (int)plain_tiles.size();
+    const char* ea = getenv("OB_LAMB_NO_FUSED_APPLY");
+    const char* ew = getenv("OB_LAMB_TWO_PASS_WARMUP");
+    const int64_t max_a = (ea && ea[0] == '1') ? 0 : split_max_tiles(std::min(per_cu_a, OB_LB_MINW), cus);
+    const int64_t max_w = (ew && ew[0] == '1') ? 0 : split_max_tiles(std::min(per_cu_w, OB_WU_MINW), cus);
+    ok = ok && build_split(ctx, tl, tm, h_off, max_a, &ctx->sp_apply) &&
+         build_split(ctx, tl, tm, h_off, max_w, &ctx->sp_warm);
   }
   ok = ok && upload(ctx, &ctx->d_first_layer_lb, tl.first) && upload(ctx, &ctx->d_tile_seg0_lb, tl.tile_seg0) &&
        upload(ctx, &ctx->d_seg_layer_lb, tl.seg_layer) && upload(ctx, &ctx->d_layer_seg0_lb, tl.layer_seg0) &&
-       upload(ctx, &ctx->d_fused_tiles, fused_tiles) && upload(ctx, &ctx->d_bound_tiles, bound_tiles) &&
-       upload(ctx, &ctx->d_n_listed, n_listed) && upload(ctx, &ctx->d_plain_tiles, plain_tiles) &&
-       upload(ctx, &ctx->d_skip_plain, skip_plain) && upload(ctx, &ctx->d_skip_fused, skip_fused) &&
        alloc_zero(ctx, &ctx->d_seg_max_lb, (size_t)ctx->n_segs_lb) &&
-       alloc_zero(ctx, &ctx->d_counter_lb, (size_t)L) && alloc_zero(ctx, &ctx->d_flag_lb, (size_t)L);
+       alloc_zero(ctx, &ctx->d_seg_sums_lb, 2 * (size_t)ctx->n_segs_lb);
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
        alloc_zero(ctx, &ctx->d_counter, (size_t)ctx->W) && alloc_zero(ctx, &ctx->d_flag, (size_t)ctx->W) &&
@@ -620,10 +658,11 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
                   ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max, ctx->d_sigma,
                   ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag,
                   ctx->d_first_layer_lb, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, ctx->d_layer_seg0_lb,
-                  ctx->d_fused_tiles, ctx->d_bound_tiles, ctx->d_n_listed, ctx->d_plain_tiles, ctx->d_skip_plain, ctx->d_skip_fused, ctx->d_seg_max_lb,
-                  ctx->d_counter_lb, ctx->d_flag_lb};
+                  ctx->d_seg_max_lb, ctx->d_seg_sums_lb};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
+  free_split(&ctx->sp_apply);
+  free_split(&ctx->sp_warm);
   delete ctx;
 }
 
@@ -645,16 +684,56 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   if (!std::isfinite(lr)) return OB_ERR_ARG;
   Launch la(ctx, hip_stream);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  // the three kernels of the two-pass form over the layers selected by `sel` (all without a list)
+  auto two_pass = [&](LayerSel sel, int n_launch_tiles) {
+    dispatch1(lpg, [&](auto lg) {
+      OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN, decltype(lg)::value ? 1 : 0>), n_launch_tiles,
+                gs, st->m, st->v_fresh, st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
+                ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer, sel);
+    });
+    OB_LAUNCH_B(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
+                st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3, sel.skip);
+    dispatch1(xl.p != nullptr, [&](auto lx) {
+      OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN, decltype(lx)::value>), n_launch_tiles, st->m,
+                st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt, xl.p, xl.bf16,
+                sel);
+    });
+  };
+  LayerSplit& sp = ctx->sp_warm;
+  if (!sp.on) {
+    two_pass(LayerSel{nullptr, nullptr}, ctx->n_tiles);
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
+  const LayerTab ltb = layer_tab(ctx, st, ctx->d_first_layer_lb);
+  const LayerSel bound{sp.d_bound_tiles, sp.d_skip_fused};
+  // 1. the pieces of eligible layers in tiles that meet a layer boundary: moments and partial sums
+  //    with the plain kernel on the barrier kernel's tiling; the sums wait in seg_sums
   dispatch1(lpg, [&](auto lg) {
-    OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN, decltype(lg)::value ? 1 : 0>), ctx->n_tiles, gs,
-              st->m, st->v_fresh, st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-              ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
+    OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_LB, decltype(lg)::value ? 1 : 0>), sp.n_bound_tiles, gs,
+              st->m, st->v_fresh, st->x, ctx->d_seg_sums_lb, ctx->n_c, ctx->tpc_lb, ctx->beta1, ctx->omb1,
+              ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, ltb, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
   });
-  OB_LAUNCH_B(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
-            st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3);
+  // 2. the layers that do not go through the barrier kernel (an empty layer still gets its c)
+  if (sp.n_layers < ctx->L) two_pass(LayerSel{sp.d_plain_tiles, sp.d_skip_plain}, sp.n_plain_tiles);
+  // 3. the barrier kernel over the tiles inside eligible layers
+  sp.epoch += 1;
+  WarmSync ws;
+  ws.seg_sums = ctx->d_seg_sums_lb; ws.layer_seg0 = ctx->d_layer_seg0_lb; ws.n_listed = sp.d_n_listed;
+  ws.counter = sp.d_counter; ws.flag = sp.d_flag; ws.errflag = ctx->d_errflag;
+  ws.epoch = sp.epoch; ws.spin_limit = ctx->spin_limit;
+  ws.coeff_c = st->coeff_c; ws.c_avg = st->c_avg;
+  ws.c_min = ctx->c_min; ws.c_max = ctx->c_max; ws.beta3 = ctx->beta3; ws.omb3 = ctx->omb3;
+  dispatch2(lpg, xl.p != nullptr, [&](auto lg, auto lx) {
+    OB_LAUNCH(la, KID_WARMUP_RESIDENT,
+              (k_warmup_resident<U_LB, G_WU, decltype(lg)::value ? 1 : 0, decltype(lx)::value>), sp.n_fused_tiles,
+              gs, st->m, st->v_fresh, st->x, ws, ctx->n_c, ctx->tpc_lb, ctx->beta1, ctx->omb1, ctx->beta2,
+              ctx->omb2, ctx->eta, ctx->wd, lr, ltb, ctx->d_tile_seg0_lb, sp.d_fused_tiles, xl.p, xl.bf16);
+  });
+  // 4. update of the boundary pieces, with the coefficients the barrier kernel committed
   dispatch1(xl.p != nullptr, [&](auto lx) {
-    OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN, decltype(lx)::value>), ctx->n_tiles, st->m,
-              st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt, xl.p, xl.bf16);
+    OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_LB, decltype(lx)::value>), sp.n_bound_tiles, st->m,
+              st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc_lb, lr, ctx->eta, ctx->wd, ltb, xl.p, xl.bf16,
+              bound);
   });
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
@@ -794,7 +873,8 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
   if (packed_m && st->m_packed == packed_all) return OB_ERR_ARG;
   Launch la(ctx, hip_stream);
-  if (!ctx->fused || !packed_m) {
+  LayerSplit& sp = ctx->sp_apply;
+  if (!sp.on || !packed_m) {
     // no layer fits on the device, or the momentum is a dense array (the fused kernel would have
     // to hold it too, which costs more than the second read of v_frozen saves): two-kernel path
     launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, LayerSel{nullptr, nullptr}, ctx->n_tiles);
@@ -808,39 +888,39 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const bool hk = st->mom_scale != nullptr;  // (here the momentum is in 1-bit form and st->m is NULL)
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_lb);
-  const LayerSel bound{ctx->d_bound_tiles, ctx->d_skip_fused};
+  const LayerSel bound{sp.d_bound_tiles, sp.d_skip_fused};
   // 1. the pieces of eligible layers in tiles that meet a layer boundary: ratio pass with the plain
   //    kernel on the fused kernel's tiling; their maxima wait in seg_max for the layer barrier
   if (hk)
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, true, true>), ctx->n_bound_tiles, ra, ctx->d_seg_max_lb,
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, true, true>), sp.n_bound_tiles, ra, ctx->d_seg_max_lb,
               ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
   else
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, false, true>), ctx->n_bound_tiles, ra, ctx->d_seg_max_lb,
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, false, true>), sp.n_bound_tiles, ra, ctx->d_seg_max_lb,
               ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
   // 2. layers that do not go through the fused kernel (too large for the device, smaller than a
   //    tile, or empty -- the ratio of an empty layer, 0, still goes through the clips)
-  if (ctx->n_fused_layers < ctx->L) {
-    const LayerSel sel{ctx->d_plain_tiles, ctx->d_skip_plain};
-    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sel, ctx->n_plain_tiles);
-    launch_apply(la, ctx, st, packed_all, server_scales, lr, sel, ctx->n_plain_tiles, xl);
+  if (sp.n_layers < ctx->L) {
+    const LayerSel sel{sp.d_plain_tiles, sp.d_skip_plain};
+    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sel, sp.n_plain_tiles);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, sel, sp.n_plain_tiles, xl);
   }
   // 3. the fused kernel over the tiles inside eligible layers
-  ctx->epoch_lb += 1;
+  sp.epoch += 1;
   LayerSync ls;
-  ls.seg_max = ctx->d_seg_max_lb; ls.layer_seg0 = ctx->d_layer_seg0_lb; ls.n_listed = ctx->d_n_listed;
-  ls.counter = ctx->d_counter_lb; ls.flag = ctx->d_flag_lb; ls.errflag = ctx->d_errflag;
-  ls.epoch = ctx->epoch_lb; ls.spin_limit = ctx->spin_limit;
+  ls.seg_max = ctx->d_seg_max_lb; ls.layer_seg0 = ctx->d_layer_seg0_lb; ls.n_listed = sp.d_n_listed;
+  ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
+  ls.epoch = sp.epoch; ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
     OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
-              (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), ctx->n_fused_tiles, ra,
-              aa, ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_fused_tiles);
+              (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), sp.n_fused_tiles, ra,
+              aa, ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, sp.d_fused_tiles);
   });
   // 4. update of the boundary pieces, with the coefficients the fused kernel committed
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
     OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, decltype(k_)::value, false, decltype(lx)::value>),
-              ctx->n_bound_tiles, aa, ctx->n_c, ctx->tpc_lb, lt, bound);
+              sp.n_bound_tiles, aa, ctx->n_c, ctx->tpc_lb, lt, bound);
   });
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
@@ -894,11 +974,13 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   // a bounded wait expired: the step that raised it produced undefined outputs.  Re-arm the
   // synchronisation state and fall back to the two-pass kernels for the rest of this context.
   ctx->resident = false;
-  ctx->fused = false;
   ctx->epoch = 0;
-  ctx->epoch_lb = 0;
-  (void)hipMemset(ctx->d_counter_lb, 0, sizeof(unsigned long long) * (size_t)ctx->L);
-  (void)hipMemset(ctx->d_flag_lb, 0, sizeof(unsigned long long) * (size_t)ctx->L);
+  for (LayerSplit* sp : {&ctx->sp_apply, &ctx->sp_warm}) {
+    sp->on = false;
+    sp->epoch = 0;
+    (void)hipMemset(sp->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->L);
+    (void)hipMemset(sp->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->L);
+  }
   (void)hipMemset(ctx->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->W);
   (void)hipMemset(ctx->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->W);
   (void)hipMemset(ctx->d_errflag, 0, sizeof(unsigned int));
@@ -906,8 +988,10 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   return OB_ERR_STATE;
 }
 
-int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->fused) ? ctx->n_fused_layers : 0; }
-int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->fused) ? ctx->n_fused_params : 0; }
+int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_layers : 0; }
+int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_params : 0; }
+int64_t ob_lamb_warmup_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_layers : 0; }
+int64_t ob_lamb_warmup_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_params : 0; }
 
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx) { return (ctx && ctx->resident) ? 1 : 0; }
 

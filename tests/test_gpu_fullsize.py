@@ -240,3 +240,34 @@ def test_bert_base_two_stage_with_generated_momentum_scale():
     import paper_2104_06069_amd as ob
     assert ob.ob_lamb_fused_layers(dev.ctx) > 50
     finish(dev)
+
+
+@pytest.mark.parametrize("two_pass_warmup", [False, True], ids=["single_pass", "two_pass"])
+def test_bert_large_warmup_step(two_pass_warmup):
+    """One uncompressed LAMB step (eq. (1)) at the full BERT-Large size against the whole oracle, in
+    the form the library selects by default (g, m, v, x read once for the 148 layers that fit on the
+    device) and in the two-pass form."""
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    cfg = make_config("bert_large")
+    pl, W = cfg["plist"], cfg["W"]
+    st = Streams(7, device="cuda:0")
+    dev = DeviceStep(pl.offsets, W, 0, two_pass_warmup=two_pass_warmup, **HYPER)
+    nf = ob.ob_lamb_warmup_fused_layers(dev.ctx)
+    print(f"bert_large: layers in the single-pass warmup kernel: {nf}", flush=True)
+    assert (nf == 0) if two_pass_warmup else (nf > 100)
+    s = init_state(st, cfg)
+    s["m"] = st.normal("m0", 0, cfg["n_pad"], 1e-4); s["m"][pl.N:] = 0
+    dev.load_state(s)
+    ref = RefStep(pl.offsets, W, 0)
+    ref.load_state({k: dev.get(k) for k in ref.t})
+    for t in range(2):
+        g = gradient(st, cfg, t)
+        t0 = time.time()
+        ref.warmup_step(g.cpu().numpy(), 2e-3)
+        print(f"bert_large: oracle warmup step {time.time() - t0:.1f} s", flush=True)
+        dev.warmup_step(g, 2e-3)
+        torch.cuda.synchronize()
+        nd = {k: assert_close(dev.get(k), ref.t[k], k) for k in ("m", "v_fresh", "x", "coeff_c", "c_avg")}
+        print(f"bert_large: warmup step {t}: elements not bit-equal (within 1e-6): {nd}", flush=True)
+    finish(dev)

@@ -21,7 +21,7 @@ def _need_gpu():
         pytest.skip("no GPU visible")
 
 
-def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, **k):
+def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pass_warmup=False, **k):
     """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
     kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
     import os
@@ -30,6 +30,9 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, **k):
     old = os.environ.pop("OB_LAMB_TWO_PASS", None)
     old2 = os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
     os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
+    os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
+    if two_pass_warmup:
+        os.environ["OB_LAMB_TWO_PASS_WARMUP"] = "1"
     if spin_limit is not None:
         os.environ["OB_LAMB_SPIN_LIMIT"] = str(spin_limit)
     if two_pass:
@@ -42,6 +45,7 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, **k):
         os.environ.pop("OB_LAMB_TWO_PASS", None)
         os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
         os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
+        os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
         if old is not None:
             os.environ["OB_LAMB_TWO_PASS"] = old
         if old2 is not None:
@@ -263,17 +267,31 @@ def test_trajectory(case, steps, two_pass, packed):
     finish(dev)
 
 
-@pytest.mark.parametrize("case", ["odd", "bert_mini", "small"])
+@pytest.mark.parametrize("case,path", [
+    ("odd", "single"), ("bert_mini", "single"), ("small", "single"), ("tiny", "single"), ("w1", "single"),
+    ("bert_mini", "two_pass"), ("tiny", "two_pass"),
+    ("bert_mini", 1), ("tiny", 7)])      # layers over that many tiles of 8192 take two passes
 @pytest.mark.parametrize("wd", [0.0, 0.01])
-def test_warmup_and_freeze(case, wd):
-    """eq. (1) with the moving average of c, then the end-of-warmup snapshot."""
+def test_warmup_and_freeze(case, path, wd):
+    """eq. (1) with the moving average of c, then the end-of-warmup snapshot.  path: the single-pass
+    kernel with a per-layer barrier for every layer that qualifies (the default), two passes for
+    every layer, or a lowered size limit so that both run side by side."""
     _need_gpu()
+    import paper_2104_06069_amd as ob
     cfg = make_case(case)
     st = Streams(3)
     pl = cfg["plist"]
     hyper = dict(HYPER); hyper["weight_decay"] = wd
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **hyper)
-    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], **hyper)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], two_pass_warmup=(path == "two_pass"),
+                     fused_max_tiles=(path if isinstance(path, int) else None), **hyper)
+    nf = ob.ob_lamb_warmup_fused_layers(dev.ctx)
+    assert nf == {("tiny", "single"): 4, ("tiny", 7): 0, ("bert_mini", "two_pass"): 0,
+                  ("tiny", "two_pass"): 0, ("small", "single"): 0}.get((case, path), nf)
+    if (case, path) == ("bert_mini", "single"):
+        assert nf >= 2
+    if (case, path) == ("bert_mini", 1):       # the 64000-element tensor is over the limit now
+        assert 1 <= nf
     s = init_state(st, cfg)
     s["v_fresh"][...] = 0
     s["c_avg"][...] = 0
@@ -625,7 +643,7 @@ def test_mixed_precision_argument_errors():
     finish(dev)
 
 
-@pytest.mark.parametrize("which", ["compress", "ratios_apply"])
+@pytest.mark.parametrize("which", ["compress", "ratios_apply", "warmup"])
 def test_expired_wait_is_reported_and_recovered(which):
     """The in-kernel barriers wait a bounded number of polls.  With the bound forced to 0 from the
     host every waiting workgroup gives up after its first poll, raises the device flag and runs to
@@ -662,15 +680,28 @@ def test_expired_wait_is_reported_and_recovered(which):
             for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
                 assert_close(dev.get(k), ref.t[k], f"step {t} {k}")
 
+    if which == "warmup":
+        assert ob.ob_lamb_warmup_fused_layers(dev.ctx) == pl.L
+        dev.warmup_step(torch.from_numpy(gradient(st, cfg, 0)).to(dev.device), 1e-3)
     # the first step reads the fp32 momentum (two plain kernels behind ratios_apply), the second one
     # runs the kernel with the per-layer barrier
-    for t in range(1 if which == "compress" else 2):
+    for t in range({"compress": 1, "ratios_apply": 2, "warmup": 0}[which]):
         one_step(t, check=False)
     with pytest.raises(ob.ObLambError) as e:
         ob.ob_lamb_check_device_status(dev.ctx, dev.stream)
     assert e.value.status == -4
     assert ob.ob_lamb_uses_single_pass(dev.ctx) == 0 and ob.ob_lamb_fused_layers(dev.ctx) == 0
+    assert ob.ob_lamb_warmup_fused_layers(dev.ctx) == 0
     ob.ob_lamb_check_device_status(dev.ctx, dev.stream)      # reported once; the context is usable again
+    if which == "warmup":   # the two-pass form now: two LAMB steps against the oracle, then the snapshot
+        dev.load_state(ref.t)
+        for t in range(2):
+            g = gradient(st, cfg, 50 + t)
+            ref.warmup_step(g, 1e-3)
+            dev.warmup_step(torch.from_numpy(g).to(dev.device), 1e-3)
+            for k in ("m", "v_fresh", "x", "coeff_c", "c_avg"):
+                assert_close(dev.get(k), ref.t[k], f"warmup after recovery, step {t}: {k}")
+        ref.freeze(); dev.freeze()
     # restore the state the failed step(s) clobbered, then go on
     dev.load_state(ref.t)
     dev.m_is_packed = False
