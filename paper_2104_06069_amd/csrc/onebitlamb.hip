@@ -39,7 +39,10 @@ constexpr int TILE_RES = SPAN * U_RES;
 #endif
 constexpr int U_LB = OB_U_LB;  // ... in the fused ratio+update kernel (v_frozen and signs stay in registers)
 constexpr int TILE_LB = SPAN * U_LB;
-constexpr int G_WU = 2;        // the single-pass warmup kernel issues its loads G_WU accesses at a time
+#ifndef OB_G_WU
+#define OB_G_WU 2
+#endif
+constexpr int G_WU = OB_G_WU;        // the single-pass warmup kernel issues its loads G_WU accesses at a time
 
 enum KernelId {
   KID_MOMENTUM_Z = 0,
