@@ -271,3 +271,70 @@ def test_bert_large_warmup_step(two_pass_warmup):
         nd = {k: assert_close(dev.get(k), ref.t[k], k) for k in ("m", "v_fresh", "x", "coeff_c", "c_avg")}
         print(f"bert_large: warmup step {t}: elements not bit-equal (within 1e-6): {nd}", flush=True)
     finish(dev)
+
+
+def test_bert_large_100_step_trajectory_on_a_window(capsys):
+    """100 compression-stage steps at the full BERT-Large size in the benchmarked configuration
+    (single-pass compression, 1-bit momentum, ratio pass and update in one call), checked against
+    the oracle on a window of two chunks.  The compressor, the error feedback, the decompressed
+    momentum and the fresh variance are chunk-local, so the oracle can follow them exactly on the
+    window alone; the ratio and the parameters are compared for the layers that lie wholly inside
+    it.  (The served chunk is outside the window: its 64-way fan-in alone would cost the oracle a
+    second per step; whole steps with it are compared at this size in test_bert_large_whole_step.)"""
+    _need_gpu()
+    cfg = make_config("bert_large")
+    pl, W, n_c = cfg["plist"], cfg["W"], cfg["n_c"]
+    c_srv, c0, c1 = 32, 33, 35
+    A, B, off, inside = window_cfg(cfg, c0, c1)
+    idx = np.nonzero(inside)[0]
+    assert idx.size >= 4
+    st, dev, _ = device_setup(cfg, c_srv, seed=9, packed=True, fused=True)
+    ref = RefStep(off, c1 - c0, 0, n_pad=B - A)
+    for k in ("x", "m", "v_fresh", "v_frozen", "err_worker"):
+        ref.t[k][...] = dev.t[k][A:B].cpu().numpy()
+    ref.t["c_avg"][...] = dev.get("c_avg"); ref.t["r_prev"][...] = dev.get("r_prev")
+    x0 = ref.t["x"].copy()
+    steps = 100
+    t_or = 0.0
+    for t in range(steps):
+        lr = 1e-3 * (1 + t % 5)
+        g = gradient(st, cfg, t)
+        fw, fs = foreign_worker_chunks(st, cfg, t)
+        fa, fss = foreign_server_chunks(st, cfg, t)
+        dev.begin_step()
+        dev.packed_in.copy_(fw); dev.scales_in.copy_(torch.from_numpy(fs))
+        dev.packed_all.copy_(fa); dev.server_scales.copy_(torch.from_numpy(fss))
+        dev.step(g, lr)
+        # --- oracle on the window
+        t0 = time.time()
+        ref.compress_local(g[A:B].cpu().numpy())
+        ref.set_foreign_all(fa[A // 32:B // 32].cpu().numpy(), fss[c0:c1])
+        ref.layer_ratios(); ref.decompress_apply(lr)
+        t_or += time.time() - t0
+        if t % 10 == 0 or t == steps - 1:
+            assert np.array_equal(words_of(dev.packed_local[A // 32:B // 32]), ref.bits_local), f"step {t}: worker words"
+            assert_close(dev.scales_local[c0:c1].cpu().numpy(), ref.scales_local, f"step {t}: worker scales")
+            with capsys.disabled():   # a sign of life for whoever watches the run
+                print(f" [bert_large trajectory: step {t} ok, oracle {t_or:.0f} s so far]", end="", flush=True)
+    torch.cuda.synchronize()
+    assert_close(dev.t["err_worker"][A:B].cpu().numpy(), ref.t["err_worker"], "worker error")
+    assert_close(dev.t["v_fresh"][A:B].cpu().numpy(), ref.t["v_fresh"], "v_fresh")
+    assert_close(dev.get("r_prev")[idx], ref.t["r_prev"][idx], "r")
+    m_dev = dev.get("m")[A:B]
+    offs = pl.offsets
+    num = den = 0.0
+    for l in idx:
+        a, b_ = int(offs[l]) - A, int(offs[l + 1]) - A
+        xd = dev.t["x"][A + a:A + b_].cpu().numpy()
+        assert_close(xd, ref.t["x"][a:b_], f"x layer {l}")
+        assert np.array_equal(m_dev[a:b_], ref.t["m"][a:b_]), f"m layer {l}"
+        num += float(np.sum((xd.astype(np.float64) - ref.t["x"][a:b_]) ** 2))
+        den += float(np.sum(ref.t["x"][a:b_].astype(np.float64) ** 2))
+        assert not np.array_equal(xd, x0[a:b_])
+    rel = (num / den) ** 0.5
+    print(f"bert_large trajectory: {steps} steps, {idx.size} whole layers in the window, "
+          f"relative L2 error of x = {rel:.3e}", flush=True)
+    assert rel <= 1e-4
+    r = dev.get("r_prev")
+    assert np.all(r >= HYPER["r_min"]) and np.all(r <= HYPER["r_max"])
+    finish(dev)
