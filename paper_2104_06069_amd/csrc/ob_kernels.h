@@ -781,18 +781,18 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __re
 }
 
 // Algorithm 1 lines 18-20 for one layer given the raw ratio (thread 0 of a workgroup).
-__device__ __forceinline__ float ratio_clip_commit(float r, int l, const float* __restrict__ c_avg,
+// rp, ca: r_prev[l] and c_avg[l], read by the caller (early, where their latency hides).
+__device__ __forceinline__ float ratio_clip_commit(float r, int l, float rp, float ca,
                                                    float* __restrict__ r_prev,
                                                    float* __restrict__ coeff_c, float one_m_thr,
                                                    float one_p_thr, float r_min, float r_max) {
-  const float rp = r_prev[l];
   const float lo = one_m_thr * rp, hi = one_p_thr * rp;
   r = (r > lo) ? r : lo;
   r = (r < hi) ? r : hi;
   r = (r > r_min) ? r : r_min;
   r = (r < r_max) ? r : r_max;
   r_prev[l] = r;
-  const float c = r * c_avg[l];
+  const float c = r * ca;
   coeff_c[l] = c;
   return c;
 }
@@ -810,6 +810,7 @@ __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restr
   const int l = blockIdx.x;
   if (skip && skip[l]) return;
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
+  const float rp = r_prev[l], ca = c_avg[l];
   float r = 0.0f;
   for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
     const float q = seg_max[s];
@@ -817,7 +818,7 @@ __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restr
   }
   r = block_max<FBLOCK>(r, lds);
   if (threadIdx.x == 0)
-    (void)ratio_clip_commit(r, l, c_avg, r_prev, coeff_c, one_m_thr, one_p_thr, r_min, r_max);
+    (void)ratio_clip_commit(r, l, rp, ca, r_prev, coeff_c, one_m_thr, one_p_thr, r_min, r_max);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -932,15 +933,16 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
 }
 
 // ---------------------------------------------------------------------------------------------
-// K5+K6+K7 in one pass for the layers that fit on the device: Algorithm 1 lines 13-21 with
-// v_frozen and the sign words read once.  A workgroup runs the ratio pass on its tile, keeps
-// v_frozen and the signs in registers, arrives at its layer's barrier, fetches x while the layer
-// completes, and applies the update from registers once the layer's coefficient c_t is published.
+// K5+K6+K7 in one pass: Algorithm 1 lines 13-21 with v_frozen and the sign words read once.
+// A workgroup runs the ratio pass on its tile of U 1024-element spans, keeps v_frozen and the signs
+// in registers, arrives at its layer's barrier, fetches x while the layer completes, and applies
+// the update from registers once the layer's coefficient c_t is published.
 //
-// The kernel covers the tiles that lie inside ONE "eligible" layer (a layer that has such tiles and
-// whose tiles fill at most 80 % of the device's workgroup slots), listed in position order.  The
-// few tiles where an eligible layer meets its neighbours are handled by the plain kernels launched
-// before (ratio pass, which leaves the maxima of those segments in seg_max) and after (update).
+// The kernel covers "listed" tiles: tiles that lie inside ONE layer, at most as many per layer as
+// fit on the device at once (80 % of its workgroup slots; of a larger layer, the last that many).
+// Everything else -- the rest of such a layer, the spans where layers meet, small tensors -- goes
+// through the plain kernels on 1024-element tiles: the ratio pass before this kernel (the maxima
+// of those segments wait in seg_max) and the update after it.
 //
 // Per-layer barrier: like the per-chunk one above, but the payload of a segment is its fp32
 // maximum of v_frozen/v_fresh (order-independent); the last of the layer's listed tiles to arrive
@@ -948,10 +950,48 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
 // and coeff_c and publishes c_t in flag[l].  counter[l] grows by n_listed[l] per launch.  The
 // dispatch-order argument of the chunk barrier applies per layer; all waits are bounded (errflag).
 // ---------------------------------------------------------------------------------------------
-struct LayerSync {
-  float* seg_max;               // [segments of this kernel's tiling]
+// What the last arriver of a layer needs to find the layer's partial results: the listed tiles
+// publish into an array of their own, indexed like the launch (tile_list position = blockIdx), and
+// the plain kernels' segments of the layer lie before the first and after the last listed tile
+// (the listed tiles of a layer are contiguous in position): [layer_seg0[l], seg_first[l]) and
+// [seg_end[l], layer_seg0[l+1]) of the 1024-element tiling's segment array.
+struct ListedTiles {
+  const int* tile_list;         // listed tiles, by position (the launch's blockIdx -> tile)
+  const int* list_begin;        // [L] index in tile_list of the layer's first listed tile
+  const int* n_listed;          // [L] listed tiles of the layer
+  const int* seg_first;         // [L] first segment owned by the layer's listed tiles
+  const int* seg_end;           // [L] one past the last segment owned by them
   const int* layer_seg0;        // [L+1] segments of each layer
-  const int* n_listed;          // [L] tiles of the layer that this kernel covers
+  int64_t n_c;
+  int tpc, tpc_span;            // tiles of this kernel / spans per chunk
+};
+
+// The ranges of one layer, read by every workgroup at its start (uniform, next to its other
+// scalars) so that the one that turns out to arrive last has them at hand.
+struct LayerParts {
+  int nl, lb;                 // listed tiles: tile_list[lb .. lb+nl)
+  int a, s_first, s_end, b;   // plain segments: [a, s_first) and [s_end, b)
+};
+__device__ __forceinline__ LayerParts layer_parts(const ListedTiles& lt, int l) {
+  LayerParts q;
+  q.nl = lt.n_listed[l]; q.lb = lt.list_begin[l];
+  q.a = lt.layer_seg0[l]; q.s_first = lt.seg_first[l]; q.s_end = lt.seg_end[l]; q.b = lt.layer_seg0[l + 1];
+  return q;
+}
+
+// Calls listed(i) for every listed tile of the layer (i = its position in tile_list) and plain(j)
+// for every plain-kernel segment j of it, strided over the workgroup's threads.
+template <class FL, class FP>
+__device__ __forceinline__ void for_layer_parts(const LayerParts& q, FL listed, FP plain) {
+  for (int j = threadIdx.x; j < q.nl; j += BLOCK) listed(q.lb + j);
+  for (int j = q.a + threadIdx.x; j < q.s_first; j += BLOCK) plain(j);
+  for (int j = q.s_end + threadIdx.x; j < q.b; j += BLOCK) plain(j);
+}
+
+struct LayerSync {
+  const float* seg_max;         // [segments of the 1024-element tiling] maxima left by the plain ratio pass
+  float* listed_max;            // [listed tiles] maxima of this launch's tiles
+  ListedTiles lt;
   unsigned long long* counter;  // [L]
   unsigned long long* flag;     // [L] (epoch << 32) | bits of c_t
   unsigned int* errflag;
@@ -963,30 +1003,36 @@ struct LayerSync {
   float one_m_thr, one_p_thr, r_min, r_max;
 };
 
-// Publishes segment s (of layer l) with maximum r and arrives; if this was the layer's last
-// listed tile, finishes the layer.  All threads call; r is valid in thread 0.
-__device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, int s, float r, float* lds,
-                                             unsigned long long* bc) {
+// Publishes the maximum r of the workgroup's listed tile (of layer l) and arrives; if this was the
+// layer's last listed tile, finishes the layer.  All threads call; r is valid in thread 0.
+// lp, rp, ca: the layer's ranges, r_prev[l] and c_avg[l], read at the start of the kernel.
+__device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const LayerParts& lp, float rp,
+                                             float ca, float r, float* lds, unsigned long long* bc) {
   if (threadIdx.x == 0) {
-    __hip_atomic_store(&ls.seg_max[s], r, __ATOMIC_RELAXED, OB_AGENT);
+    __hip_atomic_store(&ls.listed_max[blockIdx.x], r, __ATOMIC_RELAXED, OB_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
     const unsigned long long prev =
         __hip_atomic_fetch_add(&ls.counter[l], 1ull, __ATOMIC_RELAXED, OB_AGENT);
-    *bc = (prev + 1ull == (unsigned long long)ls.epoch * (unsigned long long)ls.n_listed[l]) ? 1ull : 0ull;
+    *bc = (prev + 1ull == (unsigned long long)ls.epoch * (unsigned long long)lp.nl) ? 1ull : 0ull;
   }
   __syncthreads();
   const bool last = (*bc != 0ull);
   __syncthreads();
   if (last) {
-    const int s0 = ls.layer_seg0[l], s1 = ls.layer_seg0[l + 1];
     float q = 0.0f;
-    for (int j = s0 + threadIdx.x; j < s1; j += BLOCK) {
-      const float v = __hip_atomic_load(&ls.seg_max[j], __ATOMIC_RELAXED, OB_AGENT);
-      if (v > q) q = v;
-    }
+    for_layer_parts(
+        lp,
+        [&](int i) {
+          const float v = __hip_atomic_load(&ls.listed_max[i], __ATOMIC_RELAXED, OB_AGENT);
+          if (v > q) q = v;
+        },
+        [&](int j) {
+          const float v = ls.seg_max[j];   // written by an earlier kernel
+          if (v > q) q = v;
+        });
     q = block_max(q, lds);
     if (threadIdx.x == 0) {
-      const float c = ratio_clip_commit(q, l, ls.c_avg, ls.r_prev, ls.coeff_c, ls.one_m_thr,
+      const float c = ratio_clip_commit(q, l, rp, ca, ls.r_prev, ls.coeff_c, ls.one_m_thr,
                                         ls.one_p_thr, ls.r_min, ls.r_max);
       const unsigned long long f =
           ((unsigned long long)ls.epoch << 32) | (unsigned long long)__float_as_uint(c);
@@ -1025,23 +1071,27 @@ __device__ __forceinline__ float layer_wait(const LayerSync& ls, int l, unsigned
 #endif
 template <int U, bool HAS_K, bool LPX = false>
 __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
-    RatioArgs ra, ApplyArgs aa, LayerSync ls, int64_t n_c, int tpc, LayerTab lt,
-    const int* __restrict__ tile_seg0, const int* __restrict__ tile_list) {
+    RatioArgs ra, ApplyArgs aa, LayerSync ls, LayerTab lt) {
+  // lt.first_layer: of the 1024-element tiling
   constexpr int TILE = SPAN * U;
   __shared__ float lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
-  const TilePos p = tile_pos<TILE>(n_c, tpc, tile_list[blockIdx.x]);
-  const int l0 = lt.first_layer[p.t];  // the (eligible) layer the tile lies in
+  const int64_t n_c = ls.lt.n_c;
+  const int tpc = ls.lt.tpc;
+  const TilePos p = tile_pos<TILE>(n_c, tpc, ls.lt.tile_list[blockIdx.x]);
+  const int sp0 = p.c * ls.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span
+  const int l0 = lt.first_layer[sp0];  // the layer the tile lies in
   const float ss = ra.sscales[p.c];
   const float s_prev = ra.pm.scales[p.c];
   const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
-  const int s0 = tile_seg0[p.t];       // the tile's only segment
+  const LayerParts lp = layer_parts(ls.lt, l0);
+  const float rp = ls.r_prev[l0], ca = ls.c_avg[l0];
   const int o0 = threadIdx.x * 4;
   RatioTile<U, HAS_K, true> rt;
   rt.load(ra, p);
   float r = rt.uniform_pass(ra, p, ss, s_prev, kt);
   r = block_max(r, lds);
-  layer_arrive(ls, l0, s0, r, lds, &bc);
+  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);
   v4f X[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {  // x is fetched while the layer completes
@@ -1220,7 +1270,8 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
 
 // eq. (1)'s coefficient of one layer from its sums of x^2 and u^2, and Algorithm 1 line 2
 // (thread 0 of a workgroup).
-__device__ __forceinline__ float warmup_coeff_commit(double sx, double su, int l,
+// ca: c_avg[l], read by the caller (early, where its latency hides).
+__device__ __forceinline__ float warmup_coeff_commit(double sx, double su, int l, float ca,
                                                      float* __restrict__ coeff_c,
                                                      float* __restrict__ c_avg, float c_min,
                                                      float c_max, float beta3, float omb3) {
@@ -1229,7 +1280,7 @@ __device__ __forceinline__ float warmup_coeff_commit(double sx, double su, int l
   c = (c > c_min) ? c : c_min;
   c = (c < c_max) ? c : c_max;
   coeff_c[l] = c;
-  c_avg[l] = beta3 * c_avg[l] + omb3 * c;
+  c_avg[l] = beta3 * ca + omb3 * c;
   return c;
 }
 
@@ -1243,6 +1294,7 @@ __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restric
   const int l = blockIdx.x;
   if (skip && skip[l]) return;
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
+  const float ca = c_avg[l];
   double sx = 0.0, su = 0.0;
   for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
     sx += seg_sums[2 * (int64_t)s];
@@ -1250,7 +1302,7 @@ __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restric
   }
   sx = block_sum<FBLOCK>(sx, lds);
   su = block_sum<FBLOCK>(su, lds);
-  if (threadIdx.x == 0) (void)warmup_coeff_commit(sx, su, l, coeff_c, c_avg, c_min, c_max, beta3, omb3);
+  if (threadIdx.x == 0) (void)warmup_coeff_commit(sx, su, l, ca, coeff_c, c_avg, c_min, c_max, beta3, omb3);
 }
 
 template <int U, bool LPX = false>
@@ -1316,19 +1368,19 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
 }
 
 // ---------------------------------------------------------------------------------------------
-// K8 a+b+c in one pass for the layers that fit on the device: eq. (1) with g, m, v and x read once.
-// A workgroup updates the moments of its tile, writes them, keeps u and x in registers, publishes
-// the tile's fp64 sums of x^2 and u^2 and arrives at its layer's barrier; the last of the layer's
-// listed tiles to arrive sums ALL of the layer's segment sums in a fixed order, forms c, commits
-// coeff_c and c_avg (Algorithm 1 line 2) and publishes c; the others wait for it and then update x
-// from registers.  Same split of the work as for k_ratios_apply_resident: only tiles inside one
-// eligible layer; the pieces at layer boundaries go through k_warmup_moments before (their sums
-// wait in seg_sums) and k_warmup_apply after.  Same synchronisation and bounded waits.
+// K8 a+b+c in one pass: eq. (1) with g, m, v and x read once.  A workgroup updates the moments of
+// its tile, writes them, keeps u and x in registers, publishes the tile's fp64 sums of x^2 and u^2
+// and arrives at its layer's barrier; the last of the layer's listed tiles to arrive sums ALL of
+// the layer's segment sums in a fixed order, forms c, commits coeff_c and c_avg (Algorithm 1 line
+// 2) and publishes c; the others wait for it and then update x from registers.  Same split of the
+// work as for k_ratios_apply_resident (listed tiles here; everything else through
+// k_warmup_moments before, whose sums wait in seg_sums, and k_warmup_apply after), same
+// synchronisation and bounded waits.
 // ---------------------------------------------------------------------------------------------
 struct WarmSync {
-  double* seg_sums;             // [2 * segments of this kernel's tiling]
-  const int* layer_seg0;        // [L+1]
-  const int* n_listed;          // [L] tiles of the layer that this kernel covers
+  const double* seg_sums;       // [2 * segments of the 1024-element tiling] sums left by k_warmup_moments
+  double* listed_sums;          // [2 * listed tiles] sums of this launch's tiles
+  ListedTiles lt;
   unsigned long long* counter;  // [L]
   unsigned long long* flag;     // [L] (epoch << 32) | bits of c
   unsigned int* errflag;
@@ -1345,15 +1397,17 @@ struct WarmSync {
 template <int U, int G, int GT, bool LPX>
 __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
     GradSrc g, float* __restrict__ m, float* __restrict__ v, float* __restrict__ x, WarmSync ws,
-    int64_t n_c, int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd,
-    float lr, LayerTab lt, const int* __restrict__ tile_seg0, const int* __restrict__ tile_list,
+    float beta1, float omb1, float beta2, float omb2, float eta, float wd, float lr, LayerTab lt,
     void* __restrict__ x_lp, int x_lp_bf16) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
-  const TilePos p = tile_pos<TILE>(n_c, tpc, tile_list[blockIdx.x]);
-  const int l0 = lt.first_layer[p.t];  // the (eligible) layer the tile lies in
-  const int s0 = tile_seg0[p.t];       // the tile's only segment
+  const int tpc = ws.lt.tpc;
+  const TilePos p = tile_pos<TILE>(ws.lt.n_c, tpc, ws.lt.tile_list[blockIdx.x]);
+  const int sp0 = p.c * ws.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span (1024-element tiling)
+  const int l0 = lt.first_layer[sp0];   // the layer the tile lies in
+  const LayerParts lp = layer_parts(ws.lt, l0);
+  const float ca = ws.c_avg[l0];
   const int o0 = threadIdx.x * 4;
   v4f UU[U], X[U];
   double sx = 0.0, su = 0.0;
@@ -1396,28 +1450,34 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
   su = block_sum(su, lds);
   // arrive: publish the segment's sums, then count; the last arriver finishes the layer
   if (threadIdx.x == 0) {
-    __hip_atomic_store(&ws.seg_sums[2 * (int64_t)s0], sx, __ATOMIC_RELAXED, OB_AGENT);
-    __hip_atomic_store(&ws.seg_sums[2 * (int64_t)s0 + 1], su, __ATOMIC_RELAXED, OB_AGENT);
+    __hip_atomic_store(&ws.listed_sums[2 * (int64_t)blockIdx.x], sx, __ATOMIC_RELAXED, OB_AGENT);
+    __hip_atomic_store(&ws.listed_sums[2 * (int64_t)blockIdx.x + 1], su, __ATOMIC_RELAXED, OB_AGENT);
+
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // stores complete before the add
     const unsigned long long prev =
         __hip_atomic_fetch_add(&ws.counter[l0], 1ull, __ATOMIC_RELAXED, OB_AGENT);
-    bc = (prev + 1ull == (unsigned long long)ws.epoch * (unsigned long long)ws.n_listed[l0]) ? 1ull : 0ull;
+    bc = (prev + 1ull == (unsigned long long)ws.epoch * (unsigned long long)lp.nl) ? 1ull : 0ull;
   }
   __syncthreads();
   const bool last = (bc != 0ull);
   __syncthreads();
   float c;
   if (last) {
-    const int a = ws.layer_seg0[l0], b = ws.layer_seg0[l0 + 1];
     double tx = 0.0, tu = 0.0;
-    for (int j = a + threadIdx.x; j < b; j += BLOCK) {
-      tx += __hip_atomic_load(&ws.seg_sums[2 * (int64_t)j], __ATOMIC_RELAXED, OB_AGENT);
-      tu += __hip_atomic_load(&ws.seg_sums[2 * (int64_t)j + 1], __ATOMIC_RELAXED, OB_AGENT);
-    }
+    for_layer_parts(
+        lp,
+        [&](int i) {
+          tx += __hip_atomic_load(&ws.listed_sums[2 * (int64_t)i], __ATOMIC_RELAXED, OB_AGENT);
+          tu += __hip_atomic_load(&ws.listed_sums[2 * (int64_t)i + 1], __ATOMIC_RELAXED, OB_AGENT);
+        },
+        [&](int j) {   // written by an earlier kernel
+          tx += ws.seg_sums[2 * (int64_t)j];
+          tu += ws.seg_sums[2 * (int64_t)j + 1];
+        });
     tx = block_sum(tx, lds);
     tu = block_sum(tu, lds);
     if (threadIdx.x == 0) {
-      const float cc = warmup_coeff_commit(tx, tu, l0, ws.coeff_c, ws.c_avg, ws.c_min, ws.c_max,
+      const float cc = warmup_coeff_commit(tx, tu, l0, ca, ws.coeff_c, ws.c_avg, ws.c_min, ws.c_max,
                                            ws.beta3, ws.omb3);
       const unsigned long long f =
           ((unsigned long long)ws.epoch << 32) | (unsigned long long)__float_as_uint(cc);

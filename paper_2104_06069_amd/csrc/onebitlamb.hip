@@ -22,12 +22,10 @@ using namespace obk;
 
 namespace {
 
-#ifndef OB_U_MAIN
-#define OB_U_MAIN 1
-#endif
-// 128-bit accesses per thread per array in the N-sized kernels: tiles of 1024 elements measured
-// ~7 % faster than 4096 on MI355X (ratio and update kernels at 6.4-6.5 TB/s instead of 6.0).
-constexpr int U_MAIN = OB_U_MAIN;
+// 128-bit accesses per thread per array in the plain N-sized kernels: tiles of 1024 elements measured
+// ~7 % faster than 4096 on MI355X (ratio and update kernels at 6.4-6.5 TB/s instead of 6.0).  The
+// kernels with a per-layer barrier share the segment arrays of this tiling, so it is fixed at 1.
+constexpr int U_MAIN = 1;
 constexpr int U_SRV = 1;    // ... in the kernels over the single server chunk
 constexpr int U_RES = 16;   // ... in the single-pass worker compression (z stays in registers)
 constexpr int G_RES = 2;    // the single-pass kernel issues its loads G_RES accesses at a time
@@ -77,24 +75,29 @@ struct ProfRec {
   hipEvent_t e0, e1;
 };
 
-// Split of the layers between a kernel with a per-layer barrier and the plain kernels.  A layer is
-// "eligible" for the barrier kernel when it has TILE_LB tiles that lie wholly inside it and they
-// all fit on the device at once (at most 80 % of that kernel's workgroup slots); the plain kernels
-// take the other layers (too large, smaller than a tile, or empty) and, on the barrier kernel's
-// tiling, the pieces of eligible layers in tiles that meet a layer boundary.
+// Split of the work between a kernel with a per-layer barrier and the plain kernels.  The barrier
+// kernel takes "listed" tiles: the TILE_LB tiles that lie wholly inside one layer, for every layer
+// whose such tiles all fit on the device at once (80 % of that kernel's workgroup slots).  The
+// plain kernels take every other 1024-element tile that holds parameters ("rest" tiles: layers
+// that are too large, the spans where layers meet, small tensors), and finish the layers that
+// have no listed tile.  (Listing only the last tiles of a layer that is too large was measured:
+// a run of layers that each fill the device to the limit stalls at every barrier, and the kernel
+// fell from 5.8 to 3.5 TB/s on a GPT-1.3B-shaped list.)
 struct LayerSplit {
-  bool on = false;          // at least one layer is eligible
-  int n_fused_tiles = 0;    // TILE_LB tiles inside one eligible layer (the barrier kernel's)
-  int n_bound_tiles = 0;    // TILE_LB tiles where an eligible layer meets a boundary
-  int n_plain_tiles = 0;    // TILE_MAIN tiles that hold a segment of a non-eligible layer
-  int64_t n_layers = 0;     // eligible layers
-  int64_t n_params = 0;     // parameters in them
+  bool on = false;          // at least one tile is listed
+  int n_fused_tiles = 0;    // listed TILE_LB tiles
+  int n_rest_tiles = 0;     // TILE_MAIN tiles outside them that hold parameters
+  int64_t n_layers = 0;     // layers with listed tiles
+  int64_t n_params = 0;     // parameters in listed tiles
   int* d_fused_tiles = nullptr;
-  int* d_bound_tiles = nullptr;
-  int* d_n_listed = nullptr;               // [L] barrier-kernel tiles of each layer
-  int* d_plain_tiles = nullptr;
-  unsigned char* d_skip_plain = nullptr;   // [L] 1 for eligible layers (the plain kernels skip them)
-  unsigned char* d_skip_fused = nullptr;   // [L] 1 for the other layers
+  int* d_n_listed = nullptr;               // [L] listed tiles of each layer
+  int* d_list_begin = nullptr;             // [L] index in d_fused_tiles of the layer's first listed tile
+  int* d_seg_first = nullptr;              // [L] first / one past the last segment (TILE_MAIN tiling) that the
+  int* d_seg_end = nullptr;                //     layer's listed tiles cover
+  float* d_listed_max = nullptr;           // [n_fused_tiles] partial results of the listed tiles
+  double* d_listed_sums = nullptr;         // [2*n_fused_tiles]
+  int* d_rest_tiles = nullptr;
+  unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
   unsigned long long* d_counter = nullptr; // [L] arrivals, monotone
   unsigned long long* d_flag = nullptr;    // [L] (epoch << 32) | payload
   unsigned int epoch = 0;
@@ -136,14 +139,9 @@ struct ob_lamb_ctx {
   unsigned int epoch = 0;
   int spin_limit = 1 << 20;
   // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
-  // tiling (TILE_LB) and, for each, the split of the layers between it and the plain kernels
-  int tpc_lb = 0, n_tiles_lb = 0, n_segs_lb = 0;
-  int* d_first_layer_lb = nullptr;
-  int* d_tile_seg0_lb = nullptr;
-  int* d_seg_layer_lb = nullptr;
-  int* d_layer_seg0_lb = nullptr;
-  float* d_seg_max_lb = nullptr;           // [n_segs_lb]
-  double* d_seg_sums_lb = nullptr;         // [2*n_segs_lb]
+  // tiling (TILE_LB; the segment arrays are those of the TILE_MAIN tiling) and, for each, the split
+  // of the work between it and the plain kernels
+  int tpc_lb = 0;
   LayerSplit sp_apply;                     // ob_lamb_ratios_apply
   LayerSplit sp_warm;                      // ob_lamb_warmup_step
   // diagnostics
@@ -340,64 +338,81 @@ bool build_tiling(int64_t tile, int64_t n_c, int64_t W, int64_t L, const std::ve
 }
 
 // Builds and uploads one LayerSplit.  tl / tm: the TILE_LB and TILE_MAIN tilings; max_tiles: the
-// largest number of whole tiles an eligible layer may have (0: no layer is eligible).
+// largest number of tiles of one layer the barrier kernel may hold (0: it is not used).
 bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off,
                  int64_t max_tiles, LayerSplit* sp) {
   const int64_t L = ctx->L;
-  std::vector<unsigned char> skip_plain((size_t)L, 0), skip_fused((size_t)L, 1);
-  std::vector<int> fused_tiles, bound_tiles, plain_tiles, n_listed((size_t)L, 0);
-  auto inside_one_layer = [&](int64_t t) {
+  std::vector<unsigned char> has_listed((size_t)L, 0);
+  std::vector<int> fused_tiles, rest_tiles, n_listed((size_t)L, 0), list_begin((size_t)L, 0);
+  std::vector<int> seg_first((size_t)L, 0), seg_end((size_t)L, 0);
+  std::vector<unsigned char> covered((size_t)tm.n_tiles, 0);   // TILE_MAIN tiles inside listed tiles
+  auto tile_range = [&](int64_t t, int64_t* tile0, int64_t* tile1) {
     const int64_t c = t / tl.tpc, b = t % tl.tpc;
-    const int64_t tile0 = c * ctx->n_c + b * TILE_LB;
-    const int64_t tile1 = std::min(tile0 + (int64_t)TILE_LB, (c + 1) * ctx->n_c);
-    const int l = tl.first[(size_t)t];
-    return l < L && tile1 <= h_off[(size_t)l + 1];
+    *tile0 = c * ctx->n_c + b * TILE_LB;
+    *tile1 = std::min(*tile0 + (int64_t)TILE_LB, (c + 1) * ctx->n_c);
   };
-  for (int64_t t = 0; t < tl.n_tiles; ++t)
-    if (inside_one_layer(t)) ++n_listed[(size_t)tl.first[(size_t)t]];
+  // tiles inside one layer, per layer in position order
+  std::vector<std::vector<int>> inside((size_t)L);
+  for (int64_t t = 0; t < tl.n_tiles && max_tiles > 0; ++t) {
+    int64_t tile0, tile1;
+    tile_range(t, &tile0, &tile1);
+    const int l = tl.first[(size_t)t];
+    if (l < L && tile1 <= h_off[(size_t)l + 1]) inside[(size_t)l].push_back((int)t);
+  }
   for (int64_t l = 0; l < L; ++l) {
-    const bool elig = n_listed[(size_t)l] >= 1 && n_listed[(size_t)l] <= max_tiles;
-    if (!elig) n_listed[(size_t)l] = 0;
-    skip_plain[(size_t)l] = elig ? 1 : 0;
-    skip_fused[(size_t)l] = elig ? 0 : 1;
-    sp->n_layers += elig ? 1 : 0;
-    sp->n_params += elig ? (h_off[(size_t)l + 1] - h_off[(size_t)l]) : 0;
-  }
-  sp->on = sp->n_layers > 0;
-  for (int64_t t = 0; t < tl.n_tiles; ++t) {
-    if (inside_one_layer(t)) {
-      if (skip_plain[(size_t)tl.first[(size_t)t]]) fused_tiles.push_back((int)t);
-      continue;
+    const std::vector<int>& in = inside[(size_t)l];
+    const size_t n = in.size();
+    if (n == 0 || n > (size_t)max_tiles) continue;
+    has_listed[(size_t)l] = 1;
+    n_listed[(size_t)l] = (int)n;
+    list_begin[(size_t)l] = (int)fused_tiles.size();
+    sp->n_layers += 1;
+    for (size_t j = 0; j < n; ++j) {
+      const int64_t t = in[j];
+      int64_t tile0, tile1;
+      tile_range(t, &tile0, &tile1);
+      fused_tiles.push_back((int)t);
+      sp->n_params += tile1 - tile0;
+      const int64_t c = t / tl.tpc, b = t % tl.tpc;
+      const int64_t span0 = c * tm.tpc + b * (TILE_LB / TILE_MAIN);
+      const int64_t nspan = (tile1 - tile0 + TILE_MAIN - 1) / TILE_MAIN;
+      for (int64_t j2 = 0; j2 < nspan; ++j2) covered[(size_t)(span0 + j2)] = 1;
+      // each of these spans lies inside the layer: one segment each, consecutive
+      if (j == 0) seg_first[(size_t)l] = tm.tile_seg0[(size_t)span0];
+      seg_end[(size_t)l] = tm.tile_seg0[(size_t)(span0 + nspan)];
     }
-    bool has = false;
-    for (int sgi = tl.tile_seg0[(size_t)t]; sgi < tl.tile_seg0[(size_t)t + 1]; ++sgi)
-      has = has || skip_plain[(size_t)tl.seg_layer[(size_t)sgi]];
-    if (has) bound_tiles.push_back((int)t);
   }
-  for (int64_t t = 0; t < tm.n_tiles; ++t) {
-    bool has = false;
-    for (int sgi = tm.tile_seg0[(size_t)t]; sgi < tm.tile_seg0[(size_t)t + 1]; ++sgi)
-      has = has || !skip_plain[(size_t)tm.seg_layer[(size_t)sgi]];
-    if (has) plain_tiles.push_back((int)t);
-  }
+  sp->on = !fused_tiles.empty();
+  for (int64_t t = 0; t < tm.n_tiles; ++t)
+    if (!covered[(size_t)t] && tm.tile_seg0[(size_t)t + 1] > tm.tile_seg0[(size_t)t]) rest_tiles.push_back((int)t);
   sp->n_fused_tiles = (int)fused_tiles.size();
-  sp->n_bound_tiles = (int)bound_tiles.size();
-  sp->n_plain_tiles = (int)plain_tiles.size();
-  return upload(ctx, &sp->d_fused_tiles, fused_tiles) && upload(ctx, &sp->d_bound_tiles, bound_tiles) &&
-         upload(ctx, &sp->d_n_listed, n_listed) && upload(ctx, &sp->d_plain_tiles, plain_tiles) &&
-         upload(ctx, &sp->d_skip_plain, skip_plain) && upload(ctx, &sp->d_skip_fused, skip_fused) &&
+  sp->n_rest_tiles = (int)rest_tiles.size();
+  return upload(ctx, &sp->d_fused_tiles, fused_tiles) && upload(ctx, &sp->d_n_listed, n_listed) &&
+         upload(ctx, &sp->d_list_begin, list_begin) && upload(ctx, &sp->d_seg_first, seg_first) &&
+         upload(ctx, &sp->d_seg_end, seg_end) && alloc_zero(ctx, &sp->d_listed_max, fused_tiles.size()) &&
+         alloc_zero(ctx, &sp->d_listed_sums, 2 * fused_tiles.size()) &&
+         upload(ctx, &sp->d_rest_tiles, rest_tiles) && upload(ctx, &sp->d_has_listed, has_listed) &&
          alloc_zero(ctx, &sp->d_counter, (size_t)L) && alloc_zero(ctx, &sp->d_flag, (size_t)L);
 }
 
 void free_split(LayerSplit* sp) {
-  void* ptrs[] = {sp->d_fused_tiles, sp->d_bound_tiles, sp->d_n_listed, sp->d_plain_tiles,
-                  sp->d_skip_plain,  sp->d_skip_fused,  sp->d_counter,  sp->d_flag};
+  void* ptrs[] = {sp->d_fused_tiles, sp->d_n_listed, sp->d_list_begin, sp->d_seg_first, sp->d_seg_end,
+                  sp->d_listed_max,  sp->d_listed_sums, sp->d_rest_tiles,
+                  sp->d_has_listed,  sp->d_counter,  sp->d_flag};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
 }
 
-// Largest layer (in whole TILE_LB tiles) that a barrier kernel with `per_cu` resident workgroups
-// per CU may take: 80 % of the device's slots.  OB_LAMB_FUSED_MAX_TILES=n lowers it (tests of the
+ListedTiles listed_tiles(const ob_lamb_ctx* ctx, const LayerSplit& sp) {
+  ListedTiles lt;
+  lt.tile_list = sp.d_fused_tiles; lt.list_begin = sp.d_list_begin; lt.n_listed = sp.d_n_listed;
+  lt.seg_first = sp.d_seg_first; lt.seg_end = sp.d_seg_end; lt.layer_seg0 = ctx->d_layer_seg0;
+  lt.n_c = ctx->n_c; lt.tpc = ctx->tpc_lb; lt.tpc_span = ctx->tpc;
+  return lt;
+}
+
+// Largest number of one layer's tiles that a barrier kernel with `per_cu` resident workgroups per
+// CU may hold: 80 % of the device's slots.  OB_LAMB_FUSED_MAX_TILES=n lowers it (tests of the
 // split between the two paths).
 int64_t split_max_tiles(int per_cu, int cus) {
   int64_t max_tiles = (4 * (int64_t)per_cu * cus) / 5 - 8;
@@ -408,11 +423,12 @@ int64_t split_max_tiles(int per_cu, int cus) {
   return max_tiles < 0 ? 0 : max_tiles;
 }
 
-// launches of the ratio pass / finalize / update kernels over the layers selected by `sel`
-// (all layers when sel has no list): shared by the separate calls and by ob_lamb_ratios_apply.
+// Launches of the plain ratio pass and finalize kernels.  tiles: the 1024-element tiles to cover
+// (NULL: all, in order), n_launch_tiles of them; layers with done_elsewhere[l] != 0 (NULL: none) are
+// left to be finished by the kernel with the per-layer barrier.
 void launch_ratios(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
-                          const float* server_scales, bool packed_m, const PackedMom& pm, LayerSel sel,
-                          int n_launch_tiles) {
+                   const float* server_scales, bool packed_m, const PackedMom& pm, const int* tiles,
+                   int n_launch_tiles, const unsigned char* done_elsewhere, bool finalize) {
   RatioArgs ra;
   ra.packed = packed_all; ra.sscales = server_scales; ra.m = st->m; ra.pm = pm;
   ra.v_fresh = st->v_fresh; ra.v_frozen = st->v_frozen;
@@ -421,11 +437,12 @@ void launch_ratios(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
     OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
               n_launch_tiles, ra, ctx->d_seg_max, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
-              sel);
+              LayerSel{tiles, nullptr});
   });
-  OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
-              ctx->d_layer_seg0, st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr,
-              ctx->r_min, ctx->r_max, sel.skip);
+  if (finalize)
+    OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
+                ctx->d_layer_seg0, st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr,
+                ctx->r_min, ctx->r_max, done_elsewhere);
 }
 
 ApplyArgs apply_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
@@ -438,8 +455,8 @@ ApplyArgs apply_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint
 }
 
 void launch_apply(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
-                         const float* server_scales, float lr, LayerSel sel, int n_launch_tiles,
-                         const XLp& xl) {
+                  const float* server_scales, float lr, const int* tiles, int n_launch_tiles, const XLp& xl) {
+  const LayerSel sel{tiles, nullptr};
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
   dispatch2(st->mom_scale != nullptr, st->m != nullptr, [&](auto hk, auto wm) {
@@ -564,8 +581,6 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   ctx->n_tiles = (int)tm.n_tiles;
   ctx->n_segs = (int)tm.seg_layer.size();
   ctx->tpc_lb = (int)tl.tpc;
-  ctx->n_tiles_lb = (int)tl.n_tiles;
-  ctx->n_segs_lb = (int)tl.seg_layer.size();
   const std::vector<int>&first = tm.first, &tile_seg0 = tm.tile_seg0, &seg_layer = tm.seg_layer,
                         &layer_seg0 = tm.layer_seg0;
 
@@ -626,10 +641,6 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     ok = ok && build_split(ctx, tl, tm, h_off, max_a, &ctx->sp_apply) &&
          build_split(ctx, tl, tm, h_off, max_w, &ctx->sp_warm);
   }
-  ok = ok && upload(ctx, &ctx->d_first_layer_lb, tl.first) && upload(ctx, &ctx->d_tile_seg0_lb, tl.tile_seg0) &&
-       upload(ctx, &ctx->d_seg_layer_lb, tl.seg_layer) && upload(ctx, &ctx->d_layer_seg0_lb, tl.layer_seg0) &&
-       alloc_zero(ctx, &ctx->d_seg_max_lb, (size_t)ctx->n_segs_lb) &&
-       alloc_zero(ctx, &ctx->d_seg_sums_lb, 2 * (size_t)ctx->n_segs_lb);
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
        alloc_zero(ctx, &ctx->d_counter, (size_t)ctx->W) && alloc_zero(ctx, &ctx->d_flag, (size_t)ctx->W) &&
@@ -659,9 +670,7 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
   }
   void* ptrs[] = {ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer, ctx->d_layer_seg0,
                   ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max, ctx->d_sigma,
-                  ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag,
-                  ctx->d_first_layer_lb, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, ctx->d_layer_seg0_lb,
-                  ctx->d_seg_max_lb, ctx->d_seg_sums_lb};
+                  ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   free_split(&ctx->sp_apply);
@@ -687,41 +696,40 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   if (!std::isfinite(lr)) return OB_ERR_ARG;
   Launch la(ctx, hip_stream);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  // the three kernels of the two-pass form over the layers selected by `sel` (all without a list)
-  auto two_pass = [&](LayerSel sel, int n_launch_tiles) {
+  auto moments = [&](const int* tiles, int n_launch_tiles) {
     dispatch1(lpg, [&](auto lg) {
       OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN, decltype(lg)::value ? 1 : 0>), n_launch_tiles,
                 gs, st->m, st->v_fresh, st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-                ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer, sel);
+                ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
+                LayerSel{tiles, nullptr});
     });
+  };
+  auto coeff = [&](const unsigned char* done_elsewhere) {
     OB_LAUNCH_B(la, KID_WARMUP_COEFF, k_warmup_coeff, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
-                st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3, sel.skip);
+                st->coeff_c, st->c_avg, ctx->c_min, ctx->c_max, ctx->beta3, ctx->omb3, done_elsewhere);
+  };
+  auto apply = [&](const int* tiles, int n_launch_tiles) {
     dispatch1(xl.p != nullptr, [&](auto lx) {
       OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN, decltype(lx)::value>), n_launch_tiles, st->m,
                 st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt, xl.p, xl.bf16,
-                sel);
+                LayerSel{tiles, nullptr});
     });
   };
   LayerSplit& sp = ctx->sp_warm;
-  if (!sp.on) {
-    two_pass(LayerSel{nullptr, nullptr}, ctx->n_tiles);
+  if (!sp.on) {   // two passes over everything
+    moments(nullptr, ctx->n_tiles);
+    coeff(nullptr);
+    apply(nullptr, ctx->n_tiles);
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
-  const LayerTab ltb = layer_tab(ctx, st, ctx->d_first_layer_lb);
-  const LayerSel bound{sp.d_bound_tiles, sp.d_skip_fused};
-  // 1. the pieces of eligible layers in tiles that meet a layer boundary: moments and partial sums
-  //    with the plain kernel on the barrier kernel's tiling; the sums wait in seg_sums
-  dispatch1(lpg, [&](auto lg) {
-    OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_LB, decltype(lg)::value ? 1 : 0>), sp.n_bound_tiles, gs,
-              st->m, st->v_fresh, st->x, ctx->d_seg_sums_lb, ctx->n_c, ctx->tpc_lb, ctx->beta1, ctx->omb1,
-              ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, ltb, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
-  });
-  // 2. the layers that do not go through the barrier kernel (an empty layer still gets its c)
-  if (sp.n_layers < ctx->L) two_pass(LayerSel{sp.d_plain_tiles, sp.d_skip_plain}, sp.n_plain_tiles);
-  // 3. the barrier kernel over the tiles inside eligible layers
+  // 1. moments and partial sums of everything outside the listed tiles; the layers without listed
+  //    tiles get their c here (an empty layer too), the sums of the others wait in seg_sums
+  moments(sp.d_rest_tiles, sp.n_rest_tiles);
+  if (sp.n_layers < ctx->L) coeff(sp.d_has_listed);
+  // 2. the listed tiles: moments, layer barrier, update
   sp.epoch += 1;
   WarmSync ws;
-  ws.seg_sums = ctx->d_seg_sums_lb; ws.layer_seg0 = ctx->d_layer_seg0_lb; ws.n_listed = sp.d_n_listed;
+  ws.seg_sums = ctx->d_seg_sums; ws.listed_sums = sp.d_listed_sums; ws.lt = listed_tiles(ctx, sp);
   ws.counter = sp.d_counter; ws.flag = sp.d_flag; ws.errflag = ctx->d_errflag;
   ws.epoch = sp.epoch; ws.spin_limit = ctx->spin_limit;
   ws.coeff_c = st->coeff_c; ws.c_avg = st->c_avg;
@@ -729,15 +737,11 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   dispatch2(lpg, xl.p != nullptr, [&](auto lg, auto lx) {
     OB_LAUNCH(la, KID_WARMUP_RESIDENT,
               (k_warmup_resident<U_LB, G_WU, decltype(lg)::value ? 1 : 0, decltype(lx)::value>), sp.n_fused_tiles,
-              gs, st->m, st->v_fresh, st->x, ws, ctx->n_c, ctx->tpc_lb, ctx->beta1, ctx->omb1, ctx->beta2,
-              ctx->omb2, ctx->eta, ctx->wd, lr, ltb, ctx->d_tile_seg0_lb, sp.d_fused_tiles, xl.p, xl.bf16);
+              gs, st->m, st->v_fresh, st->x, ws, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2, ctx->eta, ctx->wd,
+              lr, lt, xl.p, xl.bf16);
   });
-  // 4. update of the boundary pieces, with the coefficients the barrier kernel committed
-  dispatch1(xl.p != nullptr, [&](auto lx) {
-    OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_LB, decltype(lx)::value>), sp.n_bound_tiles, st->m,
-              st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc_lb, lr, ctx->eta, ctx->wd, ltb, xl.p, xl.bf16,
-              bound);
-  });
+  // 3. update of everything outside the listed tiles, with the coefficients of steps 1 and 2
+  apply(sp.d_rest_tiles, sp.n_rest_tiles);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -837,7 +841,7 @@ ob_status ob_lamb_layer_ratios(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   PackedMom pm;
   if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
   Launch la(ctx, hip_stream);
-  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, LayerSel{nullptr, nullptr}, ctx->n_tiles);
+  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, nullptr, ctx->n_tiles, nullptr, true);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -848,7 +852,7 @@ ob_status ob_lamb_decompress_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
   XLp xl;
   if (ob_status s = x_lp_target(x_lp, x_dtype, &xl)) return s;
   Launch la(ctx, hip_stream);
-  launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles, xl);
+  launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
   commit_packed_momentum(la, ctx, st, packed_all, server_scales);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
@@ -878,10 +882,10 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   Launch la(ctx, hip_stream);
   LayerSplit& sp = ctx->sp_apply;
   if (!sp.on || !packed_m) {
-    // no layer fits on the device, or the momentum is a dense array (the fused kernel would have
-    // to hold it too, which costs more than the second read of v_frozen saves): two-kernel path
-    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, LayerSel{nullptr, nullptr}, ctx->n_tiles);
-    launch_apply(la, ctx, st, packed_all, server_scales, lr, LayerSel{nullptr, nullptr}, ctx->n_tiles, xl);
+    // no tile qualifies, or the momentum is a dense array (the barrier kernel would have to hold it
+    // too, which costs more than the second read of v_frozen saves): the two plain kernels
+    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, nullptr, ctx->n_tiles, nullptr, true);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
   RatioArgs ra;
@@ -890,27 +894,16 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   ra.beta1 = ctx->beta1; ra.omb1 = ctx->omb1; ra.beta2 = ctx->beta2; ra.omb2 = ctx->omb2;
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const bool hk = st->mom_scale != nullptr;  // (here the momentum is in 1-bit form and st->m is NULL)
-  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_lb);
-  const LayerSel bound{sp.d_bound_tiles, sp.d_skip_fused};
-  // 1. the pieces of eligible layers in tiles that meet a layer boundary: ratio pass with the plain
-  //    kernel on the fused kernel's tiling; their maxima wait in seg_max for the layer barrier
-  if (hk)
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, true, true>), sp.n_bound_tiles, ra, ctx->d_seg_max_lb,
-              ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
-  else
-    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_LB, false, true>), sp.n_bound_tiles, ra, ctx->d_seg_max_lb,
-              ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, ctx->d_seg_layer_lb, bound);
-  // 2. layers that do not go through the fused kernel (too large for the device, smaller than a
-  //    tile, or empty -- the ratio of an empty layer, 0, still goes through the clips)
-  if (sp.n_layers < ctx->L) {
-    const LayerSel sel{sp.d_plain_tiles, sp.d_skip_plain};
-    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sel, sp.n_plain_tiles);
-    launch_apply(la, ctx, st, packed_all, server_scales, lr, sel, sp.n_plain_tiles, xl);
-  }
-  // 3. the fused kernel over the tiles inside eligible layers
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  // 1. ratio pass over everything outside the listed tiles; the layers without listed tiles are
+  //    finished here (the ratio of an empty layer, 0, still goes through the clips), the maxima of
+  //    the others wait in seg_max for the layer barrier
+  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_tiles, sp.n_rest_tiles,
+                sp.d_has_listed, sp.n_layers < ctx->L);
+  // 2. the listed tiles: ratio pass, layer barrier, update
   sp.epoch += 1;
   LayerSync ls;
-  ls.seg_max = ctx->d_seg_max_lb; ls.layer_seg0 = ctx->d_layer_seg0_lb; ls.n_listed = sp.d_n_listed;
+  ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
   ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
   ls.epoch = sp.epoch; ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
@@ -918,13 +911,10 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
     OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
               (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), sp.n_fused_tiles, ra,
-              aa, ls, ctx->n_c, ctx->tpc_lb, lt, ctx->d_tile_seg0_lb, sp.d_fused_tiles);
+              aa, ls, lt);
   });
-  // 4. update of the boundary pieces, with the coefficients the fused kernel committed
-  dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
-    OB_LAUNCH(la, KID_APPLY, (k_decompress_apply<U_LB, decltype(k_)::value, false, decltype(lx)::value>),
-              sp.n_bound_tiles, aa, ctx->n_c, ctx->tpc_lb, lt, bound);
-  });
+  // 3. update of everything outside the listed tiles, with the coefficients of steps 1 and 2
+  launch_apply(la, ctx, st, packed_all, server_scales, lr, sp.d_rest_tiles, sp.n_rest_tiles, xl);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 

@@ -290,7 +290,9 @@ def test_warmup_and_freeze(case, path, wd):
                   ("tiny", "two_pass"): 0, ("small", "single"): 0}.get((case, path), nf)
     if (case, path) == ("bert_mini", "single"):
         assert nf >= 2
-    if (case, path) == ("bert_mini", 1):       # the 64000-element tensor is over the limit now
+    if (case, path) == ("tiny", "single"):
+        assert ob.ob_lamb_warmup_fused_params(dev.ctx) == 4 * 262144
+    if (case, path) == ("bert_mini", 1):
         assert 1 <= nf
     s = init_state(st, cfg)
     s["v_fresh"][...] = 0
