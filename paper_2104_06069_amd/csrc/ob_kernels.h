@@ -637,9 +637,11 @@ struct RatioTile {
     }
   }
 
-  // Tile inside layer l0: updates and stores v_fresh, returns the thread's max of v_frozen/v_fresh.
-  // VZ keeps v_frozen.
+  // Tile inside layer l0: updates v_fresh, returns the thread's max of v_frozen/v_fresh.
+  // VZ keeps v_frozen.  DEFER: the new v_fresh stays in VF for store_v_fresh() instead of being
+  // stored at once (a barrier arrival that follows then does not wait for these stores).
   // ss, s_prev: new and previous server scale of the chunk; kt: k of the layer (1 without HAS_K).
+  template <bool DEFER = false>
   __device__ __forceinline__ float uniform_pass(const RatioArgs& ra, const TilePos& p, float ss,
                                                 float s_prev, float kt) {
     const int o0 = threadIdx.x * 4;
@@ -672,10 +674,20 @@ struct RatioTile {
           const float q = VZ[u][k] / vf[k];
           if (q > r) r = q;
         }
-        st4(ra.v_fresh + p.tile0 + o, vf);
+        if (DEFER) VF[u] = vf;
+        else st4(ra.v_fresh + p.tile0 + o, vf);
       }
     }
     return r;
+  }
+
+  __device__ __forceinline__ void store_v_fresh(const RatioArgs& ra, const TilePos& p) const {
+    const int o0 = threadIdx.x * 4;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) st4(ra.v_fresh + p.tile0 + o, VF[u]);
+    }
   }
 
   // Tile that meets a layer boundary or the end of the parameters: element by element, leaving
@@ -1089,9 +1101,10 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
   const int o0 = threadIdx.x * 4;
   RatioTile<U, HAS_K, true> rt;
   rt.load(ra, p);
-  float r = rt.uniform_pass(ra, p, ss, s_prev, kt);
+  float r = rt.template uniform_pass<true>(ra, p, ss, s_prev, kt);
   r = block_max(r, lds);
-  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);
+  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);   // before the stores of v_fresh: nothing to wait for
+  rt.store_v_fresh(ra, p);
   v4f X[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {  // x is fetched while the layer completes
