@@ -219,7 +219,7 @@ def main():
             per_call = max(1, round(v["launches"] / args.profile_steps)) if unit in ("rest", "rest_w") else 1
             v["algo_bytes"] = bpe * units[unit] / per_call
             v["GBps"] = round(v["algo_bytes"] / (v["avg_ms"] * 1e-3) / 1e9, 1)
-    dom = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
+    dom = max((k for k in kern if "GBps" in kern[k]), key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
