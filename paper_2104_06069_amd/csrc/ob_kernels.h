@@ -188,13 +188,12 @@ struct LayerTab {
   int L;
 };
 
-// Restriction of a layer-wise kernel to a subset of the layers: the launch covers the tiles listed
-// in tile_list (NULL: all tiles, in order) and leaves the elements of layers with skip[l] != 0
-// alone (NULL: no layer is skipped).
-struct LayerSel {
-  const int* tile_list;
-  const unsigned char* skip;
-};
+// The layer-wise N-sized kernels take an optional tile list: the launch then covers tile
+// tile_list[blockIdx.x] instead of tile blockIdx.x (the tiles outside the ones a kernel with a
+// per-layer barrier handles).
+__device__ __forceinline__ int listed_tile(const int* __restrict__ tile_list) {
+  return tile_list ? tile_list[blockIdx.x] : (int)blockIdx.x;
+}
 
 // Momentum source in 1-bit form (only read when PACKED_M).
 struct PackedMom {
@@ -691,11 +690,9 @@ struct RatioTile {
   }
 
   // Tile that meets a layer boundary or the end of the parameters: element by element, leaving
-  // the padding and the layers with skip[l] != 0 alone.  VZ is overwritten by the quotients
-  // (0 where nothing was computed).
+  // the padding alone.  VZ is overwritten by the quotients (0 in the padding).
   __device__ __forceinline__ void element_pass(const RatioArgs& ra, const LayerTab& lt,
-                                               const TilePos& p, int l0, float ss, float s_prev,
-                                               const unsigned char* __restrict__ skip) {
+                                               const TilePos& p, int l0, float ss, float s_prev) {
     const int o0 = threadIdx.x * 4;
     const int64_t N = lt.off[lt.L];
 #pragma unroll
@@ -709,22 +706,20 @@ struct RatioTile {
           float q = 0.0f;
           if (i < N) {
             l = walk_layer(l, i, lt.off);
-            if (!(skip && skip[l])) {
-              const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
-              const float sp = HAS_K ? ss / kk : ss;
-              const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-              float bmk;
-              if (PACKED_M) {
-                const float b = ra.beta1 * (HAS_K ? s_prev / kk : s_prev);
-                bmk = ((OB[u] >> k) & 1u) ? b : -b;
-              } else {
-                bmk = ra.beta1 * M[u][k];
-              }
-              const float gr = (mt - bmk) / ra.omb1;
-              const float vf = ra.beta2 * VF[u][k] + ra.omb2 * (gr * gr);
-              ra.v_fresh[i] = vf;
-              q = VZ[u][k] / vf;
+            const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
+            const float sp = HAS_K ? ss / kk : ss;
+            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+            float bmk;
+            if (PACKED_M) {
+              const float b = ra.beta1 * (HAS_K ? s_prev / kk : s_prev);
+              bmk = ((OB[u] >> k) & 1u) ? b : -b;
+            } else {
+              bmk = ra.beta1 * M[u][k];
             }
+            const float gr = (mt - bmk) / ra.omb1;
+            const float vf = ra.beta2 * VF[u][k] + ra.omb2 * (gr * gr);
+            ra.v_fresh[i] = vf;
+            q = VZ[u][k] / vf;
           }
           VZ[u][k] = q;
         }
@@ -756,11 +751,10 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __re
                                                        int64_t n_c, int tpc, LayerTab lt,
                                                        const int* __restrict__ tile_seg0,
                                                        const int* __restrict__ seg_layer,
-                                                       LayerSel sel) {
+                                                       const int* __restrict__ tile_list) {
   constexpr int TILE = SPAN * U;
   __shared__ float lds[BLOCK / WAVE];
-  const TilePos p =
-      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, listed_tile(tile_list));
   const int l0 = lt.first_layer[p.t];
   if (l0 >= lt.L) return;  // tile lies in the padding (it has no segment)
   // every scalar the tile needs is requested before the streaming loads, so that nothing is
@@ -769,22 +763,19 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __re
   const float s_prev = PACKED_M ? ra.pm.scales[p.c] : 0.0f;
   const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
   const int64_t l0_end = lt.off[l0 + 1];
-  const bool skip0 = sel.skip && sel.skip[l0];
   const int s0 = tile_seg0[p.t];
   RatioTile<U, HAS_K, PACKED_M> rt;
   rt.load(ra, p);
   const bool uniform = (p.tile0 + p.len <= l0_end);
-  if (uniform && skip0) return;
   if (uniform) {
     float r = rt.uniform_pass(ra, p, ss, s_prev, kt);
     r = block_max(r, lds);
     if (threadIdx.x == 0) seg_max[s0] = r;
   } else {
-    rt.element_pass(ra, lt, p, l0, ss, s_prev, sel.skip);
+    rt.element_pass(ra, lt, p, l0, ss, s_prev);
     const int s1 = tile_seg0[p.t + 1];
     for (int s = s0; s < s1; ++s) {
       const int l = seg_layer[s];
-      if (sel.skip && sel.skip[l]) continue;
       float r = rt.segment_max(p, lt.off[l], lt.off[l + 1]);
       r = block_max(r, lds);
       if (threadIdx.x == 0) seg_max[s] = r;
@@ -817,10 +808,10 @@ __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restr
                                                             float* __restrict__ coeff_c,
                                                             float one_m_thr, float one_p_thr,
                                                             float r_min, float r_max,
-                                                            const unsigned char* __restrict__ skip) {
+                                                            const unsigned char* __restrict__ done_elsewhere) {
   __shared__ float lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
-  if (skip && skip[l]) return;
+  if (done_elsewhere && done_elsewhere[l]) return;  // the kernel with the per-layer barrier finishes it
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   const float rp = r_prev[l], ca = c_avg[l];
   float r = 0.0f;
@@ -880,7 +871,6 @@ __device__ __forceinline__ void apply_uniform(const ApplyArgs& aa, const TilePos
 template <int U, bool HAS_K, bool WRITE_M, bool LPX = false>
 __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerTab& lt,
                                                const TilePos& p, int l0, float ss,
-                                               const unsigned char* __restrict__ skip,
                                                const unsigned int (&NB)[U], const v4f (&VZ)[U],
                                                const v4f (&X)[U]) {
   const int o0 = threadIdx.x * 4;
@@ -895,16 +885,14 @@ __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerT
         const int64_t i = p.tile0 + o + k;
         if (i < N) {
           l = walk_layer(l, i, lt.off);
-          if (!(skip && skip[l])) {
-            const float sp = HAS_K ? ss / lt.mom_scale[l] : ss;
-            const float a = aa.lr * aa.coeff_c[l];
-            const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
-            const float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
-            const float xn = X[u][k] - a * uu;
-            aa.x[i] = xn;
-            if (LPX) reinterpret_cast<unsigned short*>(aa.x_lp)[i] = float_to_lp(xn, aa.x_lp_bf16);
-            if (WRITE_M) aa.m[i] = mt;
-          }
+          const float sp = HAS_K ? ss / lt.mom_scale[l] : ss;
+          const float a = aa.lr * aa.coeff_c[l];
+          const float mt = ((NB[u] >> k) & 1u) ? sp : -sp;
+          const float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
+          const float xn = X[u][k] - a * uu;
+          aa.x[i] = xn;
+          if (LPX) reinterpret_cast<unsigned short*>(aa.x_lp)[i] = float_to_lp(xn, aa.x_lp_bf16);
+          if (WRITE_M) aa.m[i] = mt;
         }
       }
     }
@@ -913,10 +901,10 @@ __device__ __forceinline__ void apply_elements(const ApplyArgs& aa, const LayerT
 
 template <int U, bool HAS_K, bool WRITE_M, bool LPX = false>
 __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_t n_c, int tpc,
-                                                            LayerTab lt, LayerSel sel) {
+                                                            LayerTab lt,
+                                                            const int* __restrict__ tile_list) {
   constexpr int TILE = SPAN * U;
-  const TilePos p =
-      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, listed_tile(tile_list));
   const int l0 = lt.first_layer[p.t];
   if (l0 >= lt.L) return;
   // scalars first (see k_ratios_pass), then the streaming loads
@@ -924,7 +912,6 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
   const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
   const float c0 = aa.coeff_c[l0];
   const int64_t l0_end = lt.off[l0 + 1];
-  const bool skip0 = sel.skip && sel.skip[l0];
   const int o0 = threadIdx.x * 4;
   unsigned int NB[U];
   v4f X[U], VZ[U];
@@ -939,9 +926,8 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
     }
   }
   const bool uniform = (p.tile0 + p.len <= l0_end);
-  if (uniform && skip0) return;
   if (uniform) apply_uniform<U, HAS_K, WRITE_M, LPX>(aa, p, ss, kt, c0, NB, VZ, X);
-  else apply_elements<U, HAS_K, WRITE_M, LPX>(aa, lt, p, l0, ss, sel.skip, NB, VZ, X);
+  else apply_elements<U, HAS_K, WRITE_M, LPX>(aa, lt, p, l0, ss, NB, VZ, X);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1174,17 +1160,16 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     GradSrc g, float* __restrict__ m, float* __restrict__ v,
     const float* __restrict__ x, double* __restrict__ seg_sums /* [2*n_segs] */, int64_t n_c,
     int tpc, float beta1, float omb1, float beta2, float omb2, float eta, float wd, LayerTab lt,
-    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer, LayerSel sel) {
+    const int* __restrict__ tile_seg0, const int* __restrict__ seg_layer,
+    const int* __restrict__ tile_list) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p =
-      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, listed_tile(tile_list));
   const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
   const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
-  if (uniform && sel.skip && sel.skip[l0]) return;
   v4f G[U], M[U], V[U], X[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -1235,15 +1220,10 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     for (int u = 0; u < U; ++u) {
       const int o = u * SPAN + o0;
       if (o < p.len) {
-        int l = l0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int64_t i = p.tile0 + o + k;
           if (i < N) {
-            if (sel.skip) {
-              l = walk_layer(l, i, lt.off);
-              if (sel.skip[l]) continue;
-            }
             m[i] = M[u][k];
             v[i] = V[u][k];
           }
@@ -1253,7 +1233,6 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_moments(
     const int s1 = tile_seg0[p.t + 1];
     for (int s = s0; s < s1; ++s) {
       const int l = seg_layer[s];
-      if (sel.skip && sel.skip[l]) continue;
       const int64_t a = lt.off[l], b = lt.off[l + 1];
       double sx = 0.0, su = 0.0;
 #pragma unroll
@@ -1302,10 +1281,10 @@ __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restric
                                                          float* __restrict__ coeff_c,
                                                          float* __restrict__ c_avg, float c_min,
                                                          float c_max, float beta3, float omb3,
-                                                         const unsigned char* __restrict__ skip) {
+                                                         const unsigned char* __restrict__ done_elsewhere) {
   __shared__ double lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
-  if (skip && skip[l]) return;
+  if (done_elsewhere && done_elsewhere[l]) return;  // the kernel with the per-layer barrier finishes it
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   const float ca = c_avg[l];
   double sx = 0.0, su = 0.0;
@@ -1322,16 +1301,14 @@ template <int U, bool LPX = false>
 __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
     const float* __restrict__ m, const float* __restrict__ v, float* __restrict__ x,
     const float* __restrict__ coeff_c, int64_t n_c, int tpc, float lr, float eta, float wd,
-    LayerTab lt, void* __restrict__ x_lp, int x_lp_bf16, LayerSel sel) {
+    LayerTab lt, void* __restrict__ x_lp, int x_lp_bf16, const int* __restrict__ tile_list) {
   constexpr int TILE = SPAN * U;
-  const TilePos p =
-      tile_pos<TILE>(n_c, tpc, sel.tile_list ? sel.tile_list[blockIdx.x] : (int)blockIdx.x);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, listed_tile(tile_list));
   const int l0 = lt.first_layer[p.t];
   const int L = lt.L;
   if (l0 >= L) return;
   const int o0 = threadIdx.x * 4;
   const bool uniform = (p.tile0 + p.len <= lt.off[l0 + 1]);
-  if (uniform && sel.skip && sel.skip[l0]) return;
   v4f M[U], V[U], X[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -1368,7 +1345,6 @@ __global__ __launch_bounds__(BLOCK) void k_warmup_apply(
           const int64_t i = p.tile0 + o + k;
           if (i < N) {
             l = walk_layer(l, i, lt.off);
-            if (sel.skip && sel.skip[l]) continue;
             const float a = lr * coeff_c[l];
             const float xn = X[u][k] - a * lamb_u(M[u][k], V[u][k], X[u][k], eta, wd);
             x[i] = xn;

@@ -437,7 +437,7 @@ void launch_ratios(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
   dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
     OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass<U_MAIN, decltype(hk)::value, decltype(pk)::value>),
               n_launch_tiles, ra, ctx->d_seg_max, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
-              LayerSel{tiles, nullptr});
+              tiles);
   });
   if (finalize)
     OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
@@ -456,14 +456,13 @@ ApplyArgs apply_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint
 
 void launch_apply(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                   const float* server_scales, float lr, const int* tiles, int n_launch_tiles, const XLp& xl) {
-  const LayerSel sel{tiles, nullptr};
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
   dispatch2(st->mom_scale != nullptr, st->m != nullptr, [&](auto hk, auto wm) {
     dispatch1(xl.p != nullptr, [&](auto lx) {
       OB_LAUNCH(la, KID_APPLY,
                 (k_decompress_apply<U_MAIN, decltype(hk)::value, decltype(wm)::value, decltype(lx)::value>),
-                n_launch_tiles, aa, ctx->n_c, ctx->tpc, lt, sel);
+                n_launch_tiles, aa, ctx->n_c, ctx->tpc, lt, tiles);
     });
   });
 }
@@ -700,8 +699,7 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
     dispatch1(lpg, [&](auto lg) {
       OB_LAUNCH(la, KID_WARMUP_MOMENTS, (k_warmup_moments<U_MAIN, decltype(lg)::value ? 1 : 0>), n_launch_tiles,
                 gs, st->m, st->v_fresh, st->x, ctx->d_seg_sums, ctx->n_c, ctx->tpc, ctx->beta1, ctx->omb1,
-                ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
-                LayerSel{tiles, nullptr});
+                ctx->beta2, ctx->omb2, ctx->eta, ctx->wd, lt, ctx->d_tile_seg0, ctx->d_seg_layer, tiles);
     });
   };
   auto coeff = [&](const unsigned char* done_elsewhere) {
@@ -712,7 +710,7 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
     dispatch1(xl.p != nullptr, [&](auto lx) {
       OB_LAUNCH(la, KID_WARMUP_APPLY, (k_warmup_apply<U_MAIN, decltype(lx)::value>), n_launch_tiles, st->m,
                 st->v_fresh, st->x, st->coeff_c, ctx->n_c, ctx->tpc, lr, ctx->eta, ctx->wd, lt, xl.p, xl.bf16,
-                LayerSel{tiles, nullptr});
+                tiles);
     });
   };
   LayerSplit& sp = ctx->sp_warm;
