@@ -38,6 +38,10 @@ constexpr int WAVE = 64;
 constexpr int SPAN = BLOCK * 4;  // elements one workgroup-wide 128-bit access covers
 constexpr int FBLOCK = 1024;     // threads per workgroup of the small per-layer / per-chunk finalize kernels
 #define OB_AGENT __HIP_MEMORY_SCOPE_AGENT
+// Arrival counters of different chunks / layers sit 128 bytes apart: read-modify-write atomics on one
+// cache line are served one at a time (12 ns each, measured), whichever word of it they address,
+// and several chunks or layers are always in flight together.
+constexpr int CTR_STRIDE = 16;   // in 8-byte words
 #ifndef OB_POLL_SLEEP
 #define OB_POLL_SLEEP 16  // s_sleep argument (units of 64 clocks) between two polls of a barrier flag
 #endif
@@ -415,7 +419,7 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
 // ---------------------------------------------------------------------------------------------
 struct ChunkSync {
   double* partials;             // [tiles of the launching kernel]
-  unsigned long long* counter;  // [chunks]
+  unsigned long long* counter;  // [chunks * CTR_STRIDE]
   unsigned long long* flag;     // [chunks]
   unsigned int* errflag;        // [1]
   unsigned int epoch;           // launch number, starts at 1
@@ -430,7 +434,7 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int ti
     __hip_atomic_store(&cs.partials[tile], part, __ATOMIC_RELAXED, OB_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
     const unsigned long long prev =
-        __hip_atomic_fetch_add(&cs.counter[c], 1ull, __ATOMIC_RELAXED, OB_AGENT);
+        __hip_atomic_fetch_add(&cs.counter[(int64_t)c * CTR_STRIDE], 1ull, __ATOMIC_RELAXED, OB_AGENT);
     *bc = (prev + 1ull == (unsigned long long)cs.epoch * (unsigned long long)tpc) ? 1ull : 0ull;
   }
   __syncthreads();
@@ -990,7 +994,7 @@ struct LayerSync {
   const float* seg_max;         // [segments of the 1024-element tiling] maxima left by the plain ratio pass
   float* listed_max;            // [listed tiles] maxima of this launch's tiles
   ListedTiles lt;
-  unsigned long long* counter;  // [L]
+  unsigned long long* counter;  // [L * CTR_STRIDE]
   unsigned long long* flag;     // [L] (epoch << 32) | bits of c_t
   unsigned int* errflag;
   unsigned int epoch;
@@ -1010,7 +1014,7 @@ __device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const L
     __hip_atomic_store(&ls.listed_max[blockIdx.x], r, __ATOMIC_RELAXED, OB_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
     const unsigned long long prev =
-        __hip_atomic_fetch_add(&ls.counter[l], 1ull, __ATOMIC_RELAXED, OB_AGENT);
+        __hip_atomic_fetch_add(&ls.counter[(int64_t)l * CTR_STRIDE], 1ull, __ATOMIC_RELAXED, OB_AGENT);
     *bc = (prev + 1ull == (unsigned long long)ls.epoch * (unsigned long long)lp.nl) ? 1ull : 0ull;
   }
   __syncthreads();
@@ -1370,7 +1374,7 @@ struct WarmSync {
   const double* seg_sums;       // [2 * segments of the 1024-element tiling] sums left by k_warmup_moments
   double* listed_sums;          // [2 * listed tiles] sums of this launch's tiles
   ListedTiles lt;
-  unsigned long long* counter;  // [L]
+  unsigned long long* counter;  // [L * CTR_STRIDE]
   unsigned long long* flag;     // [L] (epoch << 32) | bits of c
   unsigned int* errflag;
   unsigned int epoch;
@@ -1444,7 +1448,7 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // stores complete before the add
     const unsigned long long prev =
-        __hip_atomic_fetch_add(&ws.counter[l0], 1ull, __ATOMIC_RELAXED, OB_AGENT);
+        __hip_atomic_fetch_add(&ws.counter[(int64_t)l0 * CTR_STRIDE], 1ull, __ATOMIC_RELAXED, OB_AGENT);
     bc = (prev + 1ull == (unsigned long long)ws.epoch * (unsigned long long)lp.nl) ? 1ull : 0ull;
   }
   __syncthreads();

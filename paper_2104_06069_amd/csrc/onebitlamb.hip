@@ -104,7 +104,7 @@ struct LayerSplit {
   double* d_listed_sums = nullptr;         // [2*n_fused_tiles]
   int* d_rest_tiles = nullptr;
   unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
-  unsigned long long* d_counter = nullptr; // [L] arrivals, monotone
+  unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] arrivals, monotone
   unsigned long long* d_flag = nullptr;    // [L] (epoch << 32) | payload
   unsigned int epoch = 0;
 };
@@ -139,7 +139,7 @@ struct ob_lamb_ctx {
   int tpc_res = 0, n_tiles_res = 0;
   int* d_first_layer_res = nullptr;        // [n_tiles_res]
   double* d_partials_res = nullptr;        // [n_tiles_res]
-  unsigned long long* d_counter = nullptr; // [W] arrivals, monotone
+  unsigned long long* d_counter = nullptr; // [W * CTR_STRIDE] arrivals, monotone
   unsigned long long* d_flag = nullptr;    // [W] (epoch << 32) | scale bits
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
   unsigned int epoch = 0;
@@ -398,7 +398,7 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std
          upload(ctx, &sp->d_seg_end, seg_end) && alloc_zero(ctx, &sp->d_listed_max, fused_tiles.size()) &&
          alloc_zero(ctx, &sp->d_listed_sums, 2 * fused_tiles.size()) &&
          upload(ctx, &sp->d_rest_tiles, rest_tiles) && upload(ctx, &sp->d_has_listed, has_listed) &&
-         alloc_zero(ctx, &sp->d_counter, (size_t)L) && alloc_zero(ctx, &sp->d_flag, (size_t)L);
+         alloc_zero(ctx, &sp->d_counter, (size_t)L * CTR_STRIDE) && alloc_zero(ctx, &sp->d_flag, (size_t)L);
 }
 
 void free_split(LayerSplit* sp) {
@@ -648,7 +648,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   }
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
-       alloc_zero(ctx, &ctx->d_counter, (size_t)ctx->W) && alloc_zero(ctx, &ctx->d_flag, (size_t)ctx->W) &&
+       alloc_zero(ctx, &ctx->d_counter, (size_t)ctx->W * CTR_STRIDE) && alloc_zero(ctx, &ctx->d_flag, (size_t)ctx->W) &&
        alloc_zero(ctx, &ctx->d_errflag, 1);
   ok = ok && upload(ctx, &ctx->d_off, h_off) && upload(ctx, &ctx->d_first_layer, first) &&
        upload(ctx, &ctx->d_tile_seg0, tile_seg0) && upload(ctx, &ctx->d_seg_layer, seg_layer) &&
@@ -975,10 +975,10 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   for (LayerSplit* sp : {&ctx->sp_apply, &ctx->sp_warm}) {
     sp->on = false;
     sp->epoch = 0;
-    (void)hipMemset(sp->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->L);
+    (void)hipMemset(sp->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->L * CTR_STRIDE);
     (void)hipMemset(sp->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->L);
   }
-  (void)hipMemset(ctx->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->W);
+  (void)hipMemset(ctx->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->W * CTR_STRIDE);
   (void)hipMemset(ctx->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->W);
   (void)hipMemset(ctx->d_errflag, 0, sizeof(unsigned int));
   (void)hipDeviceSynchronize();
