@@ -27,14 +27,20 @@ namespace {
 // kernels with a per-layer barrier share the segment arrays of this tiling, so it is fixed at 1.
 constexpr int U_MAIN = 1;
 constexpr int U_SRV = 1;    // ... in the kernels over the single server chunk
-constexpr int U_RES = 16;   // ... in the single-pass worker compression (z stays in registers)
+#ifndef OB_U_RES
+#define OB_U_RES 16
+#endif
+constexpr int U_RES = OB_U_RES;   // ... in the single-pass worker compression (z stays in registers)
 // workgroups per CU the single-pass compression kernel is built for: 5 lets the instantiation with
 // momentum scaling spill its layer cursor (touched only in tiles that meet a layer boundary) instead
 // of dropping to 4 (measured 3 % faster; without momentum scaling the kernel fits 5 anyway)
 #ifndef OB_RES_MINW
 #define OB_RES_MINW 5
 #endif
-constexpr int G_RES = 2;    // the single-pass kernel issues its loads G_RES accesses at a time
+#ifndef OB_G_RES
+#define OB_G_RES 2
+#endif
+constexpr int G_RES = OB_G_RES;    // the single-pass kernel issues its loads G_RES accesses at a time
 constexpr int TILE_MAIN = SPAN * U_MAIN;
 constexpr int TILE_SRV = SPAN * U_SRV;
 constexpr int TILE_RES = SPAN * U_RES;
