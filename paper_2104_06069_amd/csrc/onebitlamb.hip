@@ -150,6 +150,7 @@ struct ob_lamb_ctx {
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
   unsigned int epoch = 0;
   int spin_limit = 1 << 20;
+  unsigned int epoch_wrap = 0xffffffffu;   // launch number after which the barrier state is re-armed
   // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
   // tiling (TILE_LB; the segment arrays are those of the TILE_MAIN tiling) and, for each, the split
   // of the work between it and the plain kernels
@@ -423,6 +424,20 @@ ListedTiles listed_tiles(const ob_lamb_ctx* ctx, const LayerSplit& sp) {
   return lt;
 }
 
+// Next launch number of a barrier kernel.  The number travels in the high half of the 64-bit flag
+// words and multiplies the arrival counts, so when it would wrap (after 2^32 - 1 launches) the
+// counters and flags are zeroed on the stream first and numbering restarts at 1.
+unsigned int next_epoch(Launch& la, unsigned int* epoch, unsigned long long* counter, int64_t n_counter,
+                        unsigned long long* flag, int64_t n_flag) {
+  if (*epoch >= la.ctx->epoch_wrap) {
+    OB_LAUNCH(la, KID_FILL, k_zero64, (int)((n_counter + BLOCK - 1) / BLOCK), counter, n_counter);
+    OB_LAUNCH(la, KID_FILL, k_zero64, (int)((n_flag + BLOCK - 1) / BLOCK), flag, n_flag);
+    *epoch = 0;
+  }
+  *epoch += 1;
+  return *epoch;
+}
+
 // Largest number of one layer's tiles that a barrier kernel with `per_cu` resident workgroups per
 // CU may hold: 80 % of the device's slots.  OB_LAMB_FUSED_MAX_TILES=n lowers it (tests of the
 // split between the two paths).
@@ -630,6 +645,12 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
       const long v = atol(sl);
       if (v >= 0 && v < ctx->spin_limit) ctx->spin_limit = (int)v;
     }
+    // OB_LAMB_EPOCH_WRAP=n re-arms the barrier state every n launches instead of every 2^32 - 1
+    // (tests of that path)
+    if (const char* ew = getenv("OB_LAMB_EPOCH_WRAP")) {
+      const long v = atol(ew);
+      if (v >= 1) ctx->epoch_wrap = (unsigned int)v;
+    }
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }
@@ -737,7 +758,7 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   moments(sp.d_rest_tiles, sp.n_rest_tiles);
   if (sp.n_layers < ctx->L) coeff(sp.d_has_listed);
   // 2. the listed tiles: moments, layer barrier, update
-  sp.epoch += 1;
+  next_epoch(la, &sp.epoch, sp.d_counter, ctx->L * CTR_STRIDE, sp.d_flag, ctx->L);
   WarmSync ws;
   ws.seg_sums = ctx->d_seg_sums; ws.listed_sums = sp.d_listed_sums; ws.lt = listed_tiles(ctx, sp);
   ws.counter = sp.d_counter; ws.flag = sp.d_flag; ws.errflag = ctx->d_errflag;
@@ -789,7 +810,7 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   if (packed_m && st->m_packed == packed_out) return OB_ERR_ARG;  // would be overwritten while read
   Launch la(ctx, hip_stream);
   if (ctx->resident) {
-    ctx->epoch += 1;
+    next_epoch(la, &ctx->epoch, ctx->d_counter, (int64_t)ctx->W * CTR_STRIDE, ctx->d_flag, ctx->W);
     ChunkSync cs;
     cs.partials = ctx->d_partials_res;
     cs.counter = ctx->d_counter;
@@ -911,7 +932,7 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_tiles, sp.n_rest_tiles,
                 sp.d_has_listed, sp.n_layers < ctx->L);
   // 2. the listed tiles: ratio pass, layer barrier, update
-  sp.epoch += 1;
+  next_epoch(la, &sp.epoch, sp.d_counter, ctx->L * CTR_STRIDE, sp.d_flag, ctx->L);
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
   ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;

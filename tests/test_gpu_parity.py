@@ -21,7 +21,8 @@ def _need_gpu():
         pytest.skip("no GPU visible")
 
 
-def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pass_warmup=False, **k):
+def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pass_warmup=False,
+               epoch_wrap=None, **k):
     """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
     kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
     import os
@@ -31,6 +32,9 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pa
     old2 = os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
     os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
     os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
+    os.environ.pop("OB_LAMB_EPOCH_WRAP", None)
+    if epoch_wrap is not None:
+        os.environ["OB_LAMB_EPOCH_WRAP"] = str(epoch_wrap)
     if two_pass_warmup:
         os.environ["OB_LAMB_TWO_PASS_WARMUP"] = "1"
     if spin_limit is not None:
@@ -46,6 +50,7 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pa
         os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
         os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
         os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
+        os.environ.pop("OB_LAMB_EPOCH_WRAP", None)
         if old is not None:
             os.environ["OB_LAMB_TWO_PASS"] = old
         if old2 is not None:
@@ -109,7 +114,7 @@ def make_case(name):
 
 
 def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused=False,
-               fused_max_tiles=None, hyper=None):
+               fused_max_tiles=None, hyper=None, epoch_wrap=None):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -120,7 +125,7 @@ def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused
     h.update(hyper or {})
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **h)
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, fused_apply=fused,
-                     fused_max_tiles=fused_max_tiles, **h)
+                     fused_max_tiles=fused_max_tiles, epoch_wrap=epoch_wrap, **h)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -205,9 +210,9 @@ def test_phasewise_single_step(case, two_pass):
 
 
 def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False, fused=False,
-                   fused_max_tiles=None, hyper=None, c_avg=None):
+                   fused_max_tiles=None, hyper=None, c_avg=None, epoch_wrap=None):
     st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed,
-                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper)
+                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper, epoch_wrap=epoch_wrap)
     if c_avg is not None:
         ref.t["c_avg"][...] = c_avg
         dev.load_state(ref.t)
@@ -779,4 +784,26 @@ def test_gpu_rank_inside_a_simulated_job(packed, fused, use_k):
         # every rank of the job holds the same parameters and momentum
         for rk in ranks:
             assert np.array_equal(rk.t["x"], ranks[0].t["x"]) and np.array_equal(rk.t["m"], ranks[0].t["m"])
+    finish(dev)
+
+
+@pytest.mark.parametrize("wrap", [1, 3])
+def test_barrier_launch_number_wrap(wrap):
+    """The barrier kernels number their launches (the number rides in the flag words and scales the
+    arrival counts); when it would wrap, counters and flags are re-armed on the stream.  Forced to
+    happen every `wrap` launches here, over a trajectory and a few LAMB steps."""
+    _need_gpu()
+    cfg = make_case("tiny")
+    ref, dev, stats = run_trajectory(cfg, 12, packed=True, fused=True, epoch_wrap=wrap)
+    assert stats["scale_ulp_steps"] == 0 and stats["word_mismatch_steps"] == 0
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+        assert np.array_equal(dev.get(k), ref.t[k]), k
+    st = Streams(77)
+    dev.load_state(ref.t)
+    for t in range(5):
+        g = gradient(st, cfg, t)
+        ref.warmup_step(g, 1e-3)
+        dev.warmup_step(torch.from_numpy(g).to(dev.device), 1e-3)
+    for k in ("m", "v_fresh", "x", "coeff_c", "c_avg"):
+        assert_close(dev.get(k), ref.t[k], k)
     finish(dev)
