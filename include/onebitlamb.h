@@ -174,18 +174,19 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * the separate calls run).  If it is NULL the source is (st->m_packed, st->m_scales), which must
  * not be packed_all (OB_ERR_ARG), and nothing is written -- the new momentum is
  * packed_all/server_scales themselves, to be passed as m_packed/m_scales of the next step; then,
- * for every layer that holds whole tiles of 8192 elements and whose tiles fit on the device at once
- * (at most 80 % of its workgroup slots), a single kernel keeps v_frozen and the sign words in
- * registers across a per-layer barrier, so they are read once instead of twice (4.125 bytes per
- * parameter less); larger, smaller and empty layers take the two kernels.  Waits are bounded as for
+ * for every layer that holds whole tiles of 8192 elements and whose such tiles fit on the device at
+ * once (at most 80 % of its workgroup slots), a single kernel keeps v_frozen and the sign words of
+ * those tiles in registers across a per-layer barrier, so they are read once instead of twice
+ * (4.125 bytes per parameter less); everything outside those tiles (larger layers, small tensors,
+ * the spans where layers meet) takes the two kernels, restricted to it.  Waits are bounded as for
  * ob_lamb_compress_local (ob_lamb_check_device_status).  OB_LAMB_NO_FUSED_APPLY=1 at
- * ob_lamb_create forces the two-kernel path for every layer, OB_LAMB_FUSED_MAX_TILES=n for every
+ * ob_lamb_create forces the two-kernel path for everything, OB_LAMB_FUSED_MAX_TILES=n for every
  * layer with more than n such tiles. */
 ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, float lr, void* hip_stream);
-/* Number of layers the fused kernel of ob_lamb_ratios_apply handles on this device (0..L). */
+/* Number of layers the single kernel of ob_lamb_ratios_apply takes part in on this device (0..L). */
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx);
-/* ... and the number of parameters in those layers. */
+/* ... and the number of parameters in its tiles. */
 int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx);
 /* The same two counts for ob_lamb_warmup_step, which reads g, m, v and x once (one kernel with a
  * per-layer barrier that keeps eq. (1)'s update direction and x in registers while the layer's
