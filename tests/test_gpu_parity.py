@@ -325,12 +325,14 @@ def test_warmup_and_freeze(case, path, wd):
     finish(dev)
 
 
-def test_degenerate_values():
+@pytest.mark.parametrize("case,packed,fused", [("odd", False, False), ("tiny", True, True),
+                                               ("bert_mini", True, True), ("bert_mini", False, True)])
+def test_degenerate_values(case, packed, fused):
     """Zero chunks, NaN/Inf gradients, zero fresh variance, near-zero layers: IEEE behaviour of the
-    device matches the oracle's."""
+    device matches the oracle's -- in the plain kernels and in the ones with in-kernel barriers."""
     _need_gpu()
-    cfg = make_case("odd")
-    st, ref, dev = start_pair(cfg, warm_state=False)
+    cfg = make_case(case)
+    st, ref, dev = start_pair(cfg, warm_state=False, packed=packed, fused=fused)
     N = ref.N
     # step 0: all-zero gradient and momentum -> every scale is 0, every bit is 1
     g = np.zeros(cfg["n_pad"], np.float32)
@@ -358,6 +360,20 @@ def test_degenerate_values():
     assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
     assert np.array_equal(words_of(dev.packed_all), ref.bits_all)
     assert_close(dev.scales_local.cpu().numpy(), ref.scales_local, "scales with NaN/Inf")
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+        assert_close(dev.get(k), ref.t[k], k)
+    assert np.all(np.isfinite(dev.get("r_prev")))
+    # step 2 (with the 1-bit momentum this is the step that runs the kernel with the per-layer
+    # barrier): the variances now hold NaN, Inf and 0 from step 1; one more Inf in the gradient
+    g = gradient(st, cfg, 2)
+    g[77] = np.inf
+    fw, fs = foreign_worker_chunks(st, cfg, 2); fa, fss = foreign_server_chunks(st, cfg, 2)
+    ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+    dev.begin_step()
+    push_wire(ref, dev)
+    ref.step(g, 1e-3); dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
+    assert np.array_equal(words_of(dev.packed_all), ref.bits_all)
     for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
         assert_close(dev.get(k), ref.t[k], k)
     assert np.all(np.isfinite(dev.get("r_prev")))
