@@ -273,28 +273,29 @@ def test_bert_large_warmup_step(two_pass_warmup):
     finish(dev)
 
 
-def test_bert_large_100_step_trajectory_on_a_window(capsys):
-    """100 compression-stage steps at the full BERT-Large size in the benchmarked configuration
-    (single-pass compression, 1-bit momentum, ratio pass and update in one call), checked against
-    the oracle on a window of two chunks.  The compressor, the error feedback, the decompressed
-    momentum and the fresh variance are chunk-local, so the oracle can follow them exactly on the
-    window alone; the ratio and the parameters are compared for the layers that lie wholly inside
-    it.  (The served chunk is outside the window: its 64-way fan-in alone would cost the oracle a
-    second per step; whole steps with it are compared at this size in test_bert_large_whole_step.)"""
-    _need_gpu()
-    cfg = make_config("bert_large")
+def trajectory_on_a_window(capsys, name, c_srv, c0, c1, steps, min_layers, seed=9):
+    """`steps` compression-stage steps at full size in the benchmarked configuration (single-pass
+    compression, 1-bit momentum, ratio pass and update in one call), checked against the oracle on
+    the window of chunks [c0, c1).  The compressor, the error feedback, the decompressed momentum
+    and the fresh variance are chunk-local, so the oracle can follow them exactly on the window
+    alone; the ratio and the parameters are compared for the layers that lie wholly inside it.
+    (The served chunk is outside the window: its W-way fan-in alone would cost the oracle a second
+    per step; whole steps with it are compared in test_bert_large_whole_step and, for the
+    GPT-shaped list, in test_gpt_1p3b_windows.)"""
+    import paper_2104_06069_amd as ob
+    cfg = make_config(name)
     pl, W, n_c = cfg["plist"], cfg["W"], cfg["n_c"]
-    c_srv, c0, c1 = 32, 33, 35
+    assert not (c0 <= c_srv < c1)
     A, B, off, inside = window_cfg(cfg, c0, c1)
     idx = np.nonzero(inside)[0]
-    assert idx.size >= 4
-    st, dev, _ = device_setup(cfg, c_srv, seed=9, packed=True, fused=True)
+    assert idx.size >= min_layers
+    st, dev, _ = device_setup(cfg, c_srv, seed=seed, packed=True, fused=True)
+    assert ob.ob_lamb_fused_layers(dev.ctx) > 0
     ref = RefStep(off, c1 - c0, 0, n_pad=B - A)
     for k in ("x", "m", "v_fresh", "v_frozen", "err_worker"):
         ref.t[k][...] = dev.t[k][A:B].cpu().numpy()
     ref.t["c_avg"][...] = dev.get("c_avg"); ref.t["r_prev"][...] = dev.get("r_prev")
     x0 = ref.t["x"].copy()
-    steps = 100
     t_or = 0.0
     for t in range(steps):
         lr = 1e-3 * (1 + t % 5)
@@ -315,7 +316,7 @@ def test_bert_large_100_step_trajectory_on_a_window(capsys):
             assert np.array_equal(words_of(dev.packed_local[A // 32:B // 32]), ref.bits_local), f"step {t}: worker words"
             assert_close(dev.scales_local[c0:c1].cpu().numpy(), ref.scales_local, f"step {t}: worker scales")
             with capsys.disabled():   # a sign of life for whoever watches the run
-                print(f" [bert_large trajectory: step {t} ok, oracle {t_or:.0f} s so far]", end="", flush=True)
+                print(f" [{name} trajectory: step {t} ok, oracle {t_or:.0f} s so far]", end="", flush=True)
     torch.cuda.synchronize()
     assert_close(dev.t["err_worker"][A:B].cpu().numpy(), ref.t["err_worker"], "worker error")
     assert_close(dev.t["v_fresh"][A:B].cpu().numpy(), ref.t["v_fresh"], "v_fresh")
@@ -332,9 +333,20 @@ def test_bert_large_100_step_trajectory_on_a_window(capsys):
         den += float(np.sum(ref.t["x"][a:b_].astype(np.float64) ** 2))
         assert not np.array_equal(xd, x0[a:b_])
     rel = (num / den) ** 0.5
-    print(f"bert_large trajectory: {steps} steps, {idx.size} whole layers in the window, "
+    print(f"{name} trajectory: {steps} steps, {idx.size} whole layers in the window, "
           f"relative L2 error of x = {rel:.3e}", flush=True)
     assert rel <= 1e-4
     r = dev.get("r_prev")
     assert np.all(r >= HYPER["r_min"]) and np.all(r <= HYPER["r_max"])
     finish(dev)
+
+
+def test_bert_large_100_step_trajectory_on_a_window(capsys):
+    trajectory_on_a_window(capsys, "bert_large", c_srv=32, c0=33, c1=35, steps=100, min_layers=4)
+
+
+def test_gpt_1p3b_trajectory_on_a_window(capsys):
+    """The GPT-1.3B-shaped list in the benchmarked configuration: most of its tensors are too large for
+    the single-kernel paths, so the plain kernels on tile lists and the barrier kernels run side by
+    side; 1 % of the tensors have gradients of 1e-9."""
+    trajectory_on_a_window(capsys, "gpt_1p3b", c_srv=77, c0=10, c1=13, steps=6, min_layers=5)
