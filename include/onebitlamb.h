@@ -240,6 +240,10 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * synchronises `hip_stream`, reads that flag and returns OB_OK, or OB_ERR_STATE after re-arming
  * the context to use the two-pass kernels from then on.  Call it whenever you synchronise anyway
  * (e.g. once per logging interval).  ob_lamb_uses_single_pass reports the current choice (1/0).
+ * The single-pass kernels (this one and those of ob_lamb_ratios_apply and ob_lamb_warmup_step) count
+ * on having the device to themselves while they run: kernels of other streams or processes that
+ * keep more than a fifth of the compute units busy for seconds on end can make a wait expire,
+ * which is reported as above; shorter interference only slows them down.
  * OB_LAMB_SPIN_LIMIT=n at ob_lamb_create lowers the bound of the waits (0: give up after one poll);
  * it exists so that this path can be tested without ever hanging a kernel. */
 ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream);
