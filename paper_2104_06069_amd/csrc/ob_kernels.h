@@ -413,32 +413,76 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
 // *errflag, uses whatever it last read and goes on to exit, and all later waits end at once.
 //
 // Synchronisation uses relaxed agent-scope atomics whose payload travels in the atomic itself
-// (partials: one double each; flag[c]: launch epoch in the high word, scale bits in the low word),
+// (partials: one double each; flag[c]: generation in the high word, scale bits in the low word),
 // so no cache write-back/invalidate is needed; the store of the partial is complete (s_waitcnt)
-// before the arrival counter is incremented.  counter[c] grows by tpc per launch.
+// before the arrival counter is incremented.
+//
+// The barrier carries its own launch numbering, so a launch needs nothing from the host that
+// changes from call to call (a captured launch can be replayed): counter[c] holds the generation
+// in its high word and the arrivals of the running launch in its low word.  An arriving workgroup
+// learns both from its fetch-add; the last one publishes the result under generation + 1 and then
+// adds 2^32 - tpc to the counter (arrivals back to 0, generation + 1); the others wait for a flag
+// of generation + 1.  All of it wraps harmlessly.
 // ---------------------------------------------------------------------------------------------
 struct ChunkSync {
   double* partials;             // [tiles of the launching kernel]
-  unsigned long long* counter;  // [chunks * CTR_STRIDE]
-  unsigned long long* flag;     // [chunks]
+  unsigned long long* counter;  // [chunks * CTR_STRIDE] (generation << 32) | arrivals
+  unsigned long long* flag;     // [chunks] (generation << 32) | bits of the scale
   unsigned int* errflag;        // [1]
-  unsigned int epoch;           // launch number, starts at 1
   int spin_limit;
 };
+
+// One arrival at `counter` of a barrier with n participants: returns ((generation + 1) << 32) |
+// (1 if this was the last arrival).
+__device__ __forceinline__ unsigned long long barrier_arrive(unsigned long long* counter, int n) {
+  const unsigned long long prev = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, OB_AGENT);
+  const unsigned int want = (unsigned int)(prev >> 32) + 1u;
+  const bool last = ((unsigned int)prev + 1u == (unsigned int)n);
+  return ((unsigned long long)want << 32) | (last ? 1ull : 0ull);
+}
+
+// The last arrival's publication: flag <- (want << 32) | payload, then the counter is re-armed.
+__device__ __forceinline__ unsigned long long barrier_publish(unsigned long long* flag,
+                                                              unsigned long long* counter, int n,
+                                                              unsigned int want, unsigned int payload) {
+  const unsigned long long f = ((unsigned long long)want << 32) | (unsigned long long)payload;
+  __hip_atomic_store(flag, f, __ATOMIC_RELAXED, OB_AGENT);
+  (void)__hip_atomic_fetch_add(counter, (1ull << 32) - (unsigned long long)n, __ATOMIC_RELAXED, OB_AGENT);
+  return f;
+}
+
+// Bounded wait (thread 0 of a workgroup) for a flag of generation `want`; returns the flag word last
+// read.  On expiry *errflag is raised; once it is raised every wait ends within 64 polls.
+__device__ __forceinline__ unsigned long long barrier_wait(const unsigned long long* flag,
+                                                           unsigned int want, unsigned int* errflag,
+                                                           int spin_limit) {
+  unsigned long long f = 0ull;
+  for (int it = 0;; ++it) {
+    f = __hip_atomic_load(flag, __ATOMIC_RELAXED, OB_AGENT);
+    if ((unsigned int)(f >> 32) == want) break;
+    if (it >= spin_limit) {
+      atomicOr(errflag, 1u);
+      break;
+    }
+    if ((it & 63) == 63 && __hip_atomic_load(errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
+    __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
+  }
+  return f;
+}
 
 __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int tile, int c, int tpc,
                                                      int64_t n_c, double part, double* lds,
                                                      unsigned long long* bc,
                                                      float* __restrict__ scale_out) {
+  unsigned long long* counter = &cs.counter[(int64_t)c * CTR_STRIDE];
   if (threadIdx.x == 0) {
     __hip_atomic_store(&cs.partials[tile], part, __ATOMIC_RELAXED, OB_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
-    const unsigned long long prev =
-        __hip_atomic_fetch_add(&cs.counter[(int64_t)c * CTR_STRIDE], 1ull, __ATOMIC_RELAXED, OB_AGENT);
-    *bc = (prev + 1ull == (unsigned long long)cs.epoch * (unsigned long long)tpc) ? 1ull : 0ull;
+    *bc = barrier_arrive(counter, tpc);
   }
   __syncthreads();
-  const bool last = (*bc != 0ull);
+  const bool last = ((*bc & 1ull) != 0ull);
+  const unsigned int want = (unsigned int)(*bc >> 32);
   __syncthreads();
   if (last) {
     double a = 0.0;
@@ -448,24 +492,10 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int ti
     if (threadIdx.x == 0) {
       const float sc = (float)sqrt(S / (double)n_c);
       scale_out[c] = sc;
-      const unsigned long long f =
-          ((unsigned long long)cs.epoch << 32) | (unsigned long long)__float_as_uint(sc);
-      __hip_atomic_store(&cs.flag[c], f, __ATOMIC_RELAXED, OB_AGENT);
-      *bc = f;
+      *bc = barrier_publish(&cs.flag[c], counter, tpc, want, __float_as_uint(sc));
     }
   } else if (threadIdx.x == 0) {
-    unsigned long long f = 0ull;
-    for (int it = 0;; ++it) {
-      f = __hip_atomic_load(&cs.flag[c], __ATOMIC_RELAXED, OB_AGENT);
-      if ((unsigned int)(f >> 32) == cs.epoch) break;
-      if (it >= cs.spin_limit) {
-        atomicOr(cs.errflag, 1u);
-        break;
-      }
-      if ((it & 63) == 63 && __hip_atomic_load(cs.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
-      __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
-    }
-    *bc = f;
+    *bc = barrier_wait(&cs.flag[c], want, cs.errflag, cs.spin_limit);
   }
   __syncthreads();
   return __uint_as_float((unsigned int)(*bc & 0xffffffffull));
@@ -994,10 +1024,9 @@ struct LayerSync {
   const float* seg_max;         // [segments of the 1024-element tiling] maxima left by the plain ratio pass
   float* listed_max;            // [listed tiles] maxima of this launch's tiles
   ListedTiles lt;
-  unsigned long long* counter;  // [L * CTR_STRIDE]
-  unsigned long long* flag;     // [L] (epoch << 32) | bits of c_t
+  unsigned long long* counter;  // [L * CTR_STRIDE] (generation << 32) | arrivals
+  unsigned long long* flag;     // [L] (generation << 32) | bits of c_t
   unsigned int* errflag;
-  unsigned int epoch;
   int spin_limit;
   const float* c_avg;
   float* r_prev;
@@ -1010,15 +1039,15 @@ struct LayerSync {
 // lp, rp, ca: the layer's ranges, r_prev[l] and c_avg[l], read at the start of the kernel.
 __device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const LayerParts& lp, float rp,
                                              float ca, float r, float* lds, unsigned long long* bc) {
+  unsigned long long* counter = &ls.counter[(int64_t)l * CTR_STRIDE];
   if (threadIdx.x == 0) {
     __hip_atomic_store(&ls.listed_max[blockIdx.x], r, __ATOMIC_RELAXED, OB_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
-    const unsigned long long prev =
-        __hip_atomic_fetch_add(&ls.counter[(int64_t)l * CTR_STRIDE], 1ull, __ATOMIC_RELAXED, OB_AGENT);
-    *bc = (prev + 1ull == (unsigned long long)ls.epoch * (unsigned long long)lp.nl) ? 1ull : 0ull;
+    *bc = barrier_arrive(counter, lp.nl);
   }
   __syncthreads();
-  const bool last = (*bc != 0ull);
+  const bool last = ((*bc & 1ull) != 0ull);
+  const unsigned int want = (unsigned int)(*bc >> 32);
   __syncthreads();
   if (last) {
     float q = 0.0f;
@@ -1036,30 +1065,17 @@ __device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const L
     if (threadIdx.x == 0) {
       const float c = ratio_clip_commit(q, l, rp, ca, ls.r_prev, ls.coeff_c, ls.one_m_thr,
                                         ls.one_p_thr, ls.r_min, ls.r_max);
-      const unsigned long long f =
-          ((unsigned long long)ls.epoch << 32) | (unsigned long long)__float_as_uint(c);
-      __hip_atomic_store(&ls.flag[l], f, __ATOMIC_RELAXED, OB_AGENT);
+      (void)barrier_publish(&ls.flag[l], counter, lp.nl, want, __float_as_uint(c));
     }
   }
+  // every thread leaves with the generation to wait for in *bc's high word (the last arriver too)
 }
 
-// Waits (bounded) until layer l's coefficient of this launch is published; returns it to all threads.
+// Waits (bounded) until layer l's coefficient of this launch is published; returns it to all
+// threads.  *bc still holds what layer_arrive left there.
 __device__ __forceinline__ float layer_wait(const LayerSync& ls, int l, unsigned long long* bc) {
   __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long f = 0ull;
-    for (int it = 0;; ++it) {
-      f = __hip_atomic_load(&ls.flag[l], __ATOMIC_RELAXED, OB_AGENT);
-      if ((unsigned int)(f >> 32) == ls.epoch) break;
-      if (it >= ls.spin_limit) {
-        atomicOr(ls.errflag, 1u);
-        break;
-      }
-      if ((it & 63) == 63 && __hip_atomic_load(ls.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
-      __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
-    }
-    *bc = f;
-  }
+  if (threadIdx.x == 0) *bc = barrier_wait(&ls.flag[l], (unsigned int)(*bc >> 32), ls.errflag, ls.spin_limit);
   __syncthreads();
   return __uint_as_float((unsigned int)(*bc & 0xffffffffull));
 }
@@ -1374,10 +1390,9 @@ struct WarmSync {
   const double* seg_sums;       // [2 * segments of the 1024-element tiling] sums left by k_warmup_moments
   double* listed_sums;          // [2 * listed tiles] sums of this launch's tiles
   ListedTiles lt;
-  unsigned long long* counter;  // [L * CTR_STRIDE]
-  unsigned long long* flag;     // [L] (epoch << 32) | bits of c
+  unsigned long long* counter;  // [L * CTR_STRIDE] (generation << 32) | arrivals
+  unsigned long long* flag;     // [L] (generation << 32) | bits of c
   unsigned int* errflag;
-  unsigned int epoch;
   int spin_limit;
   float* coeff_c;
   float* c_avg;
@@ -1441,18 +1456,17 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
   }
   sx = block_sum(sx, lds);
   su = block_sum(su, lds);
-  // arrive: publish the segment's sums, then count; the last arriver finishes the layer
+  // arrive: publish the tile's sums, then count; the last arriver finishes the layer
+  unsigned long long* counter = &ws.counter[(int64_t)l0 * CTR_STRIDE];
   if (threadIdx.x == 0) {
     __hip_atomic_store(&ws.listed_sums[2 * (int64_t)blockIdx.x], sx, __ATOMIC_RELAXED, OB_AGENT);
     __hip_atomic_store(&ws.listed_sums[2 * (int64_t)blockIdx.x + 1], su, __ATOMIC_RELAXED, OB_AGENT);
-
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // stores complete before the add
-    const unsigned long long prev =
-        __hip_atomic_fetch_add(&ws.counter[(int64_t)l0 * CTR_STRIDE], 1ull, __ATOMIC_RELAXED, OB_AGENT);
-    bc = (prev + 1ull == (unsigned long long)ws.epoch * (unsigned long long)lp.nl) ? 1ull : 0ull;
+    bc = barrier_arrive(counter, lp.nl);
   }
   __syncthreads();
-  const bool last = (bc != 0ull);
+  const bool last = ((bc & 1ull) != 0ull);
+  const unsigned int want = (unsigned int)(bc >> 32);
   __syncthreads();
   float c;
   if (last) {
@@ -1472,24 +1486,10 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
     if (threadIdx.x == 0) {
       const float cc = warmup_coeff_commit(tx, tu, l0, ca, ws.coeff_c, ws.c_avg, ws.c_min, ws.c_max,
                                            ws.beta3, ws.omb3);
-      const unsigned long long f =
-          ((unsigned long long)ws.epoch << 32) | (unsigned long long)__float_as_uint(cc);
-      __hip_atomic_store(&ws.flag[l0], f, __ATOMIC_RELAXED, OB_AGENT);
-      bc = f;
+      bc = barrier_publish(&ws.flag[l0], counter, lp.nl, want, __float_as_uint(cc));
     }
   } else if (threadIdx.x == 0) {
-    unsigned long long f = 0ull;
-    for (int it = 0;; ++it) {
-      f = __hip_atomic_load(&ws.flag[l0], __ATOMIC_RELAXED, OB_AGENT);
-      if ((unsigned int)(f >> 32) == ws.epoch) break;
-      if (it >= ws.spin_limit) {
-        atomicOr(ws.errflag, 1u);
-        break;
-      }
-      if ((it & 63) == 63 && __hip_atomic_load(ws.errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
-      __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
-    }
-    bc = f;
+    bc = barrier_wait(&ws.flag[l0], want, ws.errflag, ws.spin_limit);
   }
   __syncthreads();
   c = __uint_as_float((unsigned int)(bc & 0xffffffffull));

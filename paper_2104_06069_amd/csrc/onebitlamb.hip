@@ -111,8 +111,7 @@ struct LayerSplit {
   int* d_rest_tiles = nullptr;
   unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
   unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] arrivals, monotone
-  unsigned long long* d_flag = nullptr;    // [L] (epoch << 32) | payload
-  unsigned int epoch = 0;
+  unsigned long long* d_flag = nullptr;    // [L] (generation << 32) | payload
 };
 
 }  // namespace
@@ -146,11 +145,9 @@ struct ob_lamb_ctx {
   int* d_first_layer_res = nullptr;        // [n_tiles_res]
   double* d_partials_res = nullptr;        // [n_tiles_res]
   unsigned long long* d_counter = nullptr; // [W * CTR_STRIDE] arrivals, monotone
-  unsigned long long* d_flag = nullptr;    // [W] (epoch << 32) | scale bits
+  unsigned long long* d_flag = nullptr;    // [W] (generation << 32) | scale bits
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
-  unsigned int epoch = 0;
   int spin_limit = 1 << 20;
-  unsigned int epoch_wrap = 0xffffffffu;   // launch number after which the barrier state is re-armed
   // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
   // tiling (TILE_LB; the segment arrays are those of the TILE_MAIN tiling) and, for each, the split
   // of the work between it and the plain kernels
@@ -424,20 +421,6 @@ ListedTiles listed_tiles(const ob_lamb_ctx* ctx, const LayerSplit& sp) {
   return lt;
 }
 
-// Next launch number of a barrier kernel.  The number travels in the high half of the 64-bit flag
-// words and multiplies the arrival counts, so when it would wrap (after 2^32 - 1 launches) the
-// counters and flags are zeroed on the stream first and numbering restarts at 1.
-unsigned int next_epoch(Launch& la, unsigned int* epoch, unsigned long long* counter, int64_t n_counter,
-                        unsigned long long* flag, int64_t n_flag) {
-  if (*epoch >= la.ctx->epoch_wrap) {
-    OB_LAUNCH(la, KID_FILL, k_zero64, (int)((n_counter + BLOCK - 1) / BLOCK), counter, n_counter);
-    OB_LAUNCH(la, KID_FILL, k_zero64, (int)((n_flag + BLOCK - 1) / BLOCK), flag, n_flag);
-    *epoch = 0;
-  }
-  *epoch += 1;
-  return *epoch;
-}
-
 // Largest number of one layer's tiles that a barrier kernel with `per_cu` resident workgroups per
 // CU may hold: 80 % of the device's slots.  OB_LAMB_FUSED_MAX_TILES=n lowers it (tests of the
 // split between the two paths).
@@ -645,12 +628,6 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
       const long v = atol(sl);
       if (v >= 0 && v < ctx->spin_limit) ctx->spin_limit = (int)v;
     }
-    // OB_LAMB_EPOCH_WRAP=n re-arms the barrier state every n launches instead of every 2^32 - 1
-    // (tests of that path)
-    if (const char* ew = getenv("OB_LAMB_EPOCH_WRAP")) {
-      const long v = atol(ew);
-      if (v >= 1) ctx->epoch_wrap = (unsigned int)v;
-    }
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
   }
@@ -758,11 +735,10 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   moments(sp.d_rest_tiles, sp.n_rest_tiles);
   if (sp.n_layers < ctx->L) coeff(sp.d_has_listed);
   // 2. the listed tiles: moments, layer barrier, update
-  next_epoch(la, &sp.epoch, sp.d_counter, ctx->L * CTR_STRIDE, sp.d_flag, ctx->L);
   WarmSync ws;
   ws.seg_sums = ctx->d_seg_sums; ws.listed_sums = sp.d_listed_sums; ws.lt = listed_tiles(ctx, sp);
   ws.counter = sp.d_counter; ws.flag = sp.d_flag; ws.errflag = ctx->d_errflag;
-  ws.epoch = sp.epoch; ws.spin_limit = ctx->spin_limit;
+  ws.spin_limit = ctx->spin_limit;
   ws.coeff_c = st->coeff_c; ws.c_avg = st->c_avg;
   ws.c_min = ctx->c_min; ws.c_max = ctx->c_max; ws.beta3 = ctx->beta3; ws.omb3 = ctx->omb3;
   dispatch2(lpg, xl.p != nullptr, [&](auto lg, auto lx) {
@@ -810,13 +786,11 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   if (packed_m && st->m_packed == packed_out) return OB_ERR_ARG;  // would be overwritten while read
   Launch la(ctx, hip_stream);
   if (ctx->resident) {
-    next_epoch(la, &ctx->epoch, ctx->d_counter, (int64_t)ctx->W * CTR_STRIDE, ctx->d_flag, ctx->W);
     ChunkSync cs;
     cs.partials = ctx->d_partials_res;
     cs.counter = ctx->d_counter;
     cs.flag = ctx->d_flag;
     cs.errflag = ctx->d_errflag;
-    cs.epoch = ctx->epoch;
     cs.spin_limit = ctx->spin_limit;
     const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer_res);
     dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
@@ -932,11 +906,10 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_tiles, sp.n_rest_tiles,
                 sp.d_has_listed, sp.n_layers < ctx->L);
   // 2. the listed tiles: ratio pass, layer barrier, update
-  next_epoch(la, &sp.epoch, sp.d_counter, ctx->L * CTR_STRIDE, sp.d_flag, ctx->L);
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
   ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
-  ls.epoch = sp.epoch; ls.spin_limit = ctx->spin_limit;
+  ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
@@ -998,10 +971,8 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   // a bounded wait expired: the step that raised it produced undefined outputs.  Re-arm the
   // synchronisation state and fall back to the two-pass kernels for the rest of this context.
   ctx->resident = false;
-  ctx->epoch = 0;
   for (LayerSplit* sp : {&ctx->sp_apply, &ctx->sp_warm}) {
     sp->on = false;
-    sp->epoch = 0;
     (void)hipMemset(sp->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->L * CTR_STRIDE);
     (void)hipMemset(sp->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->L);
   }

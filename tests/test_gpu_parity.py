@@ -21,8 +21,7 @@ def _need_gpu():
         pytest.skip("no GPU visible")
 
 
-def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pass_warmup=False,
-               epoch_wrap=None, **k):
+def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pass_warmup=False, **k):
     """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
     kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
     import os
@@ -32,9 +31,6 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pa
     old2 = os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
     os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
     os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
-    os.environ.pop("OB_LAMB_EPOCH_WRAP", None)
-    if epoch_wrap is not None:
-        os.environ["OB_LAMB_EPOCH_WRAP"] = str(epoch_wrap)
     if two_pass_warmup:
         os.environ["OB_LAMB_TWO_PASS_WARMUP"] = "1"
     if spin_limit is not None:
@@ -50,7 +46,6 @@ def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pa
         os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
         os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
         os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
-        os.environ.pop("OB_LAMB_EPOCH_WRAP", None)
         if old is not None:
             os.environ["OB_LAMB_TWO_PASS"] = old
         if old2 is not None:
@@ -114,7 +109,7 @@ def make_case(name):
 
 
 def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused=False,
-               fused_max_tiles=None, hyper=None, epoch_wrap=None):
+               fused_max_tiles=None, hyper=None):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -125,7 +120,7 @@ def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused
     h.update(hyper or {})
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **h)
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, fused_apply=fused,
-                     fused_max_tiles=fused_max_tiles, epoch_wrap=epoch_wrap, **h)
+                     fused_max_tiles=fused_max_tiles, **h)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -210,9 +205,9 @@ def test_phasewise_single_step(case, two_pass):
 
 
 def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False, fused=False,
-                   fused_max_tiles=None, hyper=None, c_avg=None, epoch_wrap=None):
+                   fused_max_tiles=None, hyper=None, c_avg=None):
     st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed,
-                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper, epoch_wrap=epoch_wrap)
+                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper)
     if c_avg is not None:
         ref.t["c_avg"][...] = c_avg
         dev.load_state(ref.t)
@@ -803,23 +798,74 @@ def test_gpu_rank_inside_a_simulated_job(packed, fused, use_k):
     finish(dev)
 
 
-@pytest.mark.parametrize("wrap", [1, 3])
-def test_barrier_launch_number_wrap(wrap):
-    """The barrier kernels number their launches (the number rides in the flag words and scales the
-    arrival counts); when it would wrap, counters and flags are re-armed on the stream.  Forced to
-    happen every `wrap` launches here, over a trajectory and a few LAMB steps."""
+@pytest.mark.parametrize("case", ["tiny", "bert_mini"])
+def test_step_replayed_from_a_captured_graph(case):
+    """The barriers of the single-pass kernels number their launches themselves, so a step needs
+    nothing from the host that changes from call to call: two consecutive steps (with the 1-bit
+    momentum the buffer pairs alternate, so two steps return to the starting arrangement) are
+    captured into one graph and replayed, with eager work and synchronisation between the replays;
+    every replay is checked against the oracle."""
     _need_gpu()
-    cfg = make_case("tiny")
-    ref, dev, stats = run_trajectory(cfg, 12, packed=True, fused=True, epoch_wrap=wrap)
-    assert stats["scale_ulp_steps"] == 0 and stats["word_mismatch_steps"] == 0
-    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
-        assert np.array_equal(dev.get(k), ref.t[k]), k
-    st = Streams(77)
-    dev.load_state(ref.t)
-    for t in range(5):
+    cfg = make_case(case)
+    st, ref, dev = start_pair(cfg, warm_state=False, packed=True, fused=True)
+    n_pad = cfg["n_pad"]
+    gbuf = [torch.zeros(n_pad, device=dev.device) for _ in range(2)]
+    lr = 1e-3
+
+    def wire(t):   # what the other ranks send at step t, into the pair that step t uses
+        fw, fs = foreign_worker_chunks(st, cfg, t)
+        fa, fss = foreign_server_chunks(st, cfg, t)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        return fw, fs, fa, fss
+
+    # two eager steps first: the momentum is then in 1-bit form and the pairs alternate regularly
+    for t in range(2):
         g = gradient(st, cfg, t)
-        ref.warmup_step(g, 1e-3)
-        dev.warmup_step(torch.from_numpy(g).to(dev.device), 1e-3)
-    for k in ("m", "v_fresh", "x", "coeff_c", "c_avg"):
-        assert_close(dev.get(k), ref.t[k], k)
+        fw, fs, fa, fss = wire(t)
+        dev.begin_step()
+        push_wire(ref, dev)
+        ref.step(g, lr); dev.step(torch.from_numpy(g).to(dev.device), lr)
+    assert dev.m_is_packed
+    torch.cuda.synchronize()
+    # foreign input of the captured steps lives in fixed device buffers, refilled before each replay
+    fin = [dict(pi=torch.zeros_like(dev.packed_in), si=torch.zeros_like(dev.scales_in),
+                pa=torch.zeros_like(dev.packed_all), sa=torch.zeros_like(dev.server_scales)) for _ in range(2)]
+
+    def two_steps():
+        for j in range(2):
+            dev.begin_step()
+            dev.packed_in.copy_(fin[j]["pi"]); dev.scales_in.copy_(fin[j]["si"])
+            dev.packed_all.copy_(fin[j]["pa"]); dev.server_scales.copy_(fin[j]["sa"])
+            dev.step(gbuf[j], lr)
+
+    cur0 = dev._cur
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        # capture only records the launches; the steps themselves first run at the first replay
+        with torch.cuda.graph(graph, stream=side):
+            two_steps()
+    torch.cuda.current_stream().wait_stream(side)
+    assert dev._cur == cur0     # two steps: back to the starting pair
+    for rep in range(4):
+        for j in range(2):
+            t = 2 + 2 * rep + j
+            g = gradient(st, cfg, t)
+            fw, fs, fa, fss = wire(t)
+            gbuf[j].copy_(torch.from_numpy(g))
+            fin[j]["pi"].copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+            fin[j]["si"].copy_(torch.from_numpy(fs))
+            fin[j]["pa"].copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
+            fin[j]["sa"].copy_(torch.from_numpy(fss))
+            ref.step(g, lr)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        # eager work of the same library between the replays (its own context: nothing shared)
+        assert np.array_equal(words_of(dev.packed_local), ref.bits_local), f"replay {rep}: worker words"
+        assert np.array_equal(words_of(dev.packed_all), ref.bits_all), f"replay {rep}: server words"
+        for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+            assert_close(dev.get(k), ref.t[k], f"replay {rep}: {k}")
     finish(dev)
+
