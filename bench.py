@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--x-lp", choices=["none", "f16", "bf16"], default="none",
                     help="mixed-precision variant: also write a 16-bit copy of the parameters "
                          "(2 bytes/param more)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph that holds two consecutive steps (for launch-bound "
+                         "sizes; --steps must be even)")
     ap.add_argument("--dense-momentum", action="store_true",
                     help="keep the momentum as an fp32 array (default: the 1-bit form it has after "
                          "Algorithm 1 line 13; same results, 12 bytes/param less traffic)")
@@ -157,14 +160,31 @@ def main():
                      fw=ds.packed_in.cpu().numpy(), fs=fs.copy(), fa=ds._pa[0].cpu().numpy(),
                      fss=ds._ss[0].cpu().numpy())
 
-    for t in range(args.warmup):
+    for t in range(args.warmup + (args.warmup % 2 if args.graph else 0)):
         one_step(t)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(args.steps):
-        one_step(t)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    if args.graph:
+        # two steps return the alternating buffer pairs to where they started: one graph, replayed
+        assert args.steps % 2 == 0, "--graph replays pairs of steps"
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                one_step(0); one_step(1)
+        torch.cuda.current_stream().wait_stream(side)
+        graph.replay(); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps // 2):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for t in range(args.steps):
+            one_step(t)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
 
     # per-call times (events on the launch stream) and per-kernel durations (library's own events)
@@ -247,7 +267,7 @@ def main():
         "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
                    "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
                    "mom_scale": bool(args.mom_scale), "momentum": mode,
-                   "grad_dtype": args.grad_dtype, "x_lp": args.x_lp,
+                   "grad_dtype": args.grad_dtype, "x_lp": args.x_lp, "graph_replay": bool(args.graph),
                    "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
                    "fused_params": fused_params,
                    "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx)},
