@@ -375,17 +375,24 @@ def test_degenerate_values(case, packed, fused):
     finish(dev)
 
 
-def test_bitwise_reproducible():
-    """Same inputs twice -> identical bits everywhere (fixed-order reductions, no float atomics)."""
+@pytest.mark.parametrize("case,packed,fused", [("bert_mini", False, False), ("bert_mini", True, True),
+                                               ("tiny", True, True)])
+def test_bitwise_reproducible(case, packed, fused):
+    """Same inputs twice -> identical bits everywhere (fixed-order reductions, no float atomics; in
+    the kernels with barriers the order of arrival does not enter the result).  Two steps, so that
+    the second one runs the single-pass ratio+update kernel when the momentum is in 1-bit form."""
     _need_gpu()
-    cfg = make_case("bert_mini")
+    cfg = make_case(case)
     outs = []
     for _ in range(2):
-        st, ref, dev = start_pair(cfg)
-        g = torch.from_numpy(gradient(st, cfg, 0)).to(dev.device)
-        fw, fs = foreign_worker_chunks(st, cfg, 0); fa, fss = foreign_server_chunks(st, cfg, 0)
-        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss); push_wire(ref, dev)
-        dev.step(g, 1e-3)
+        st, ref, dev = start_pair(cfg, packed=packed, fused=fused)
+        for t in range(2):
+            g = torch.from_numpy(gradient(st, cfg, t)).to(dev.device)
+            fw, fs = foreign_worker_chunks(st, cfg, t); fa, fss = foreign_server_chunks(st, cfg, t)
+            ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+            dev.begin_step()
+            push_wire(ref, dev)
+            dev.step(g, 1e-3)
         outs.append({k: dev.get(k).copy() for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev")}
                     | {"scales": dev.scales_local.cpu().numpy(), "w": words_of(dev.packed_local).copy()})
         finish(dev)
