@@ -350,3 +350,31 @@ def test_gpt_1p3b_trajectory_on_a_window(capsys):
     the single-kernel paths, so the plain kernels on tile lists and the barrier kernels run side by
     side; 1 % of the tensors have gradients of 1e-9."""
     trajectory_on_a_window(capsys, "gpt_1p3b", c_srv=77, c0=10, c1=13, steps=6, min_layers=5)
+
+
+def test_bert_large_bitwise_reproducible():
+    """Two runs of three steps at the full BERT-Large size in the benchmarked configuration give
+    identical bits everywhere: with thousands of workgroups arriving at the barriers in whatever
+    order the hardware runs them, the order must not enter any result."""
+    _need_gpu()
+    cfg = make_config("bert_large")
+    outs = []
+    for run in range(2):
+        st, dev, g = device_setup(cfg, cfg["W"] // 2, seed=5, packed=True, fused=True)
+        for t in range(3):
+            if t > 0:
+                dev.begin_step()
+                g = gradient(st, cfg, t)
+                fa, fss = foreign_server_chunks(st, cfg, t)
+                dev.packed_all.copy_(fa); dev.server_scales.copy_(torch.from_numpy(fss))
+            dev.step(g, 1e-3)
+        torch.cuda.synchronize()
+        out = {k: dev.t[k].clone() for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c")}
+        out["packed_local"] = dev.packed_local.clone(); out["packed_all"] = dev.packed_all.clone()
+        out["scales_local"] = dev.scales_local.clone(); out["server_scales"] = dev.server_scales.clone()
+        outs.append(out)
+        finish(dev)
+    for k in outs[0]:
+        a, b = outs[0][k], outs[1][k]
+        same = torch.equal(a.view(torch.int32), b.view(torch.int32)) if a.dtype == torch.float32 else torch.equal(a, b)
+        assert same, k
