@@ -1595,12 +1595,6 @@ __global__ __launch_bounds__(FBLOCK) void k_momentum_scale(const double* __restr
   }
 }
 
-// Zeroes n 8-byte words (re-arming of barrier counters and flags when a launch number wraps).
-__global__ __launch_bounds__(BLOCK) void k_zero64(unsigned long long* __restrict__ p, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
-  if (i < n) p[i] = 0ull;
-}
-
 __global__ __launch_bounds__(BLOCK) void k_fill(float* __restrict__ p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
   if (i < n) p[i] = v;

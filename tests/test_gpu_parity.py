@@ -876,3 +876,58 @@ def test_step_replayed_from_a_captured_graph(case):
             assert_close(dev.get(k), ref.t[k], f"replay {rep}: {k}")
     finish(dev)
 
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_random_layer_lists(seed):
+    """Random tensor lists -- empty, tiny, exactly tile-sized, tile-aligned and ragged tensors, random
+    W and served chunk, with or without momentum scaling, random size limit of the barrier kernels
+    -- through LAMB steps, the snapshot and compression steps in the benchmarked configuration.
+    Exercises the host's tiling: which tiles the barrier kernels take, what is left to the plain
+    kernels, chunk ends inside and between layers."""
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    r = np.random.default_rng(1000 + seed)
+    kinds = [0, 1, 2, 3, 7, 255, 256, 1023, 1024, 1025, 4096, 8191, 8192, 8193, 16384, 24576, 40000, 65536, 100000]
+    sizes = [int(r.choice(kinds)) for _ in range(int(r.integers(3, 14)))]
+    if sum(sizes) == 0:
+        sizes.append(5000)
+    W = int(r.choice([1, 2, 3, 4, 5, 8]))
+    pl = ParamList(f"rand{seed}", [(f"t{i}", s) for i, s in enumerate(sizes)])
+    n_pad = padded_len(pl.N, W)
+    cfg = dict(name=f"rand{seed}", plist=pl, W=W, n_pad=n_pad, n_c=n_pad // W, grad="student_t3")
+    c_srv = int(r.integers(0, W))
+    use_k = bool(r.integers(0, 2))
+    max_tiles = [None, None, 1, 2, 3][int(r.integers(0, 5))]
+    st = Streams(seed)
+    k = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if use_k else None
+    hyper = dict(HYPER, c_min=1e-3)
+    ref = RefStep(pl.offsets, W, c_srv, mom_scale=k, **hyper)
+    dev = DeviceStep(pl.offsets, W, c_srv, mom_scale=k, packed_momentum=True, fused_apply=True,
+                     fused_max_tiles=max_tiles, **hyper)
+    assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
+    print(f"sizes {sizes} W {W} served {c_srv} k {use_k} max_tiles {max_tiles}: "
+          f"{ob.ob_lamb_fused_layers(dev.ctx)} / {ob.ob_lamb_warmup_fused_layers(dev.ctx)} layers in the barrier kernels")
+    s = init_state(st, cfg)
+    s["v_fresh"][...] = 0
+    s["c_avg"][...] = 0
+    ref.load_state(s); dev.load_state(ref.t)
+    for t in range(3):
+        g = gradient(st, cfg, t)
+        ref.warmup_step(g, 1e-3); dev.warmup_step(torch.from_numpy(g).to(dev.device), 1e-3)
+        for key in ("m", "v_fresh", "x", "coeff_c", "c_avg"):
+            assert_close(dev.get(key), ref.t[key], f"warmup {t} {key}")
+    ref.freeze(); dev.freeze()
+    dev.load_state(ref.t)     # identical bits at the hand-off
+    for t in range(3, 8):
+        g = gradient(st, cfg, t)
+        fw, fs = foreign_worker_chunks(st, cfg, t); fa, fss = foreign_server_chunks(st, cfg, t)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        dev.begin_step()
+        push_wire(ref, dev)
+        ref.step(g, 1e-3); dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+        assert np.array_equal(words_of(dev.packed_local), ref.bits_local), f"step {t}: worker words"
+        assert np.array_equal(words_of(dev.packed_all), ref.bits_all), f"step {t}: server words"
+        for key in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+            assert_close(dev.get(key), ref.t[key], f"step {t} {key}")
+    finish(dev)
