@@ -331,7 +331,18 @@ def cpu_baseline(cfg, server_chunk, hyper, mom_scale, h, lr, budget_s):
     sec = float(np.median(times))
     return {"value": round(cfg["plist"].N / sec, 1), "unit": "params/s", "cores": 1, "kind": "oracle",
             "sample": f"{len(times)} whole step(s) of the same workload, median {sec:.2f} s/step",
-            "host_cpus": os.cpu_count()}
+            "host_cpus": os.cpu_count(), "cpu_model": _cpu_model()}
+
+
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 if __name__ == "__main__":
