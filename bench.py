@@ -3,7 +3,8 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input already resident in
 HBM: compress_local -> (gather copy) -> server_reduce -> ratios_apply (= layer_ratios + decompress_apply).
-Prints ONE JSON line (see the design doc for the fields).  `--gpus N` with N > 1 is refused: this
+Prints ONE JSON line: the metric, the dominant kernel's roofline from HIP-event timings of its
+launches, per-call and per-kernel times, and the CPU oracle timed beside it.  `--gpus N` with N > 1 is refused: this
 build measures one GPU's share of the data-parallel step and uses no collectives.
 """
 import argparse

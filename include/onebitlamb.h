@@ -34,8 +34,10 @@
  * - All arithmetic is IEEE binary32 with one rounding per operation (no fused multiply-add),
  *   except the two sum-of-squares reductions (chunk scales, LAMB norms), which accumulate in
  *   binary64 in a fixed order: results are bit-reproducible from run to run.
- * - A context owns a small device workspace (partial sums, per-layer maxima, tile tables).
- *   Calls on one context must not overlap in time (use one stream, or order them yourself).
+ * - A context owns a small device workspace (partial sums, per-layer maxima, tile tables) on the
+ *   device that was current at ob_lamb_create; step calls made with another device current return
+ *   OB_ERR_ARG.  Calls on one context must not overlap in time (use one stream, or order them
+ *   yourself).
  * - Call order of one compression step:
  *     ob_lamb_compress_local -> [exchange] -> ob_lamb_server_reduce -> [exchange]
  *     -> ob_lamb_layer_ratios -> ob_lamb_decompress_apply.
@@ -110,7 +112,8 @@ ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, floa
                                  void* hip_stream);
 
 /* Creates a context on the current HIP device: copies the configuration, builds the tile tables
- * and allocates the workspace (blocking; uses hipMalloc/hipMemcpy).  *out is NULL on error. */
+ * and allocates the workspace (blocking; uses hipMalloc/hipMemcpy).  *out is NULL on error
+ * (OB_ERR_ARG also when the host tables cannot be allocated). */
 ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out);
 /* Frees the context and its device memory (blocking).  NULL is ignored. */
 void ob_lamb_destroy(ob_lamb_ctx* ctx);

@@ -110,7 +110,7 @@ struct LayerSplit {
   double* d_listed_sums = nullptr;         // [2*n_fused_tiles]
   int* d_rest_tiles = nullptr;
   unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
-  unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] arrivals, monotone
+  unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] (generation << 32) | arrivals
   unsigned long long* d_flag = nullptr;    // [L] (generation << 32) | payload
 };
 
@@ -144,7 +144,7 @@ struct ob_lamb_ctx {
   int tpc_res = 0, n_tiles_res = 0;
   int* d_first_layer_res = nullptr;        // [n_tiles_res]
   double* d_partials_res = nullptr;        // [n_tiles_res]
-  unsigned long long* d_counter = nullptr; // [W * CTR_STRIDE] arrivals, monotone
+  unsigned long long* d_counter = nullptr; // [W * CTR_STRIDE] (generation << 32) | arrivals
   unsigned long long* d_flag = nullptr;    // [W] (generation << 32) | scale bits
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
   int spin_limit = 1 << 20;
@@ -218,6 +218,9 @@ bool alloc_zero(ob_lamb_ctx* ctx, T** dst, size_t count) {
 
 ob_status check_common(const ob_lamb_ctx* ctx, const ob_lamb_state* st) {
   if (!ctx || !st) return OB_ERR_NULL;
+  // the context's tables live on the device it was created on
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device) return OB_ERR_ARG;
   return OB_OK;
 }
 
@@ -536,7 +539,19 @@ const char* ob_lamb_status_string(ob_status s) {
 
 const char* ob_lamb_last_hip_error(const ob_lamb_ctx* ctx) { return ctx ? ctx->hip_err.c_str() : ""; }
 
+static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out);
+
 ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
+  // the host tables are std::vectors: a failed allocation must not leave the C ABI as an exception
+  try {
+    return create_ctx(cfg, out);
+  } catch (const std::bad_alloc&) {
+    if (out) *out = nullptr;
+    return OB_ERR_ARG;
+  }
+}
+
+static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   if (out) *out = nullptr;
   if (!cfg || !out || !cfg->layer_offsets) return OB_ERR_NULL;
   const int64_t L = cfg->num_layers;
@@ -555,6 +570,10 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
 
   ob_lamb_ctx* ctx = new (std::nothrow) ob_lamb_ctx();
   if (!ctx) return OB_ERR_ARG;
+  struct Guard {   // frees the context and what it holds on every path that does not hand it over
+    ob_lamb_ctx* c;
+    ~Guard() { ob_lamb_destroy(c); }
+  } guard{ctx};
   ctx->L = L;
   ctx->N = N;
   ctx->W = cfg->num_workers;
@@ -573,7 +592,7 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   ctx->invW = 1.0f / (float)ctx->W;
 
   const int64_t tpc_srv = (ctx->n_c + TILE_SRV - 1) / TILE_SRV;
-  if (tpc_srv > 0x7fffffff) { delete ctx; return OB_ERR_ARG; }
+  if (tpc_srv > 0x7fffffff) return OB_ERR_ARG;
   ctx->tpc_srv = (int)tpc_srv;
 
   std::vector<int64_t> h_off((size_t)L + 2);
@@ -581,10 +600,8 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   h_off[(size_t)L + 1] = std::numeric_limits<int64_t>::max();
   Tiling tm, tl;
   if (!build_tiling(TILE_MAIN, ctx->n_c, ctx->W, L, h_off, &tm) ||
-      !build_tiling(TILE_LB, ctx->n_c, ctx->W, L, h_off, &tl)) {
-    delete ctx;
+      !build_tiling(TILE_LB, ctx->n_c, ctx->W, L, h_off, &tl))
     return OB_ERR_ARG;
-  }
   const int64_t n_tiles = tm.n_tiles;
   ctx->tpc = (int)tm.tpc;
   ctx->n_tiles = (int)tm.n_tiles;
@@ -663,10 +680,8 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
        alloc_zero(ctx, &ctx->d_sigma, (size_t)L) &&
        alloc_zero(ctx, &ctx->d_seg_max, (size_t)ctx->n_segs);
   ok = ok && hip_ok(ctx, hipDeviceSynchronize(), "hipDeviceSynchronize");
-  if (!ok) {
-    ob_lamb_destroy(ctx);
-    return OB_ERR_HIP;
-  }
+  if (!ok) return OB_ERR_HIP;
+  guard.c = nullptr;
   *out = ctx;
   return OB_OK;
 }
