@@ -50,7 +50,7 @@ def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False, fused=
     ("bert_large", False, False, False, None), ("bert_large_w256", False, False, False, None),
     ("bert_large", True, False, False, None), ("bert_large", False, True, False, None),
     # the configuration the benchmark times: 1-bit momentum, ratio pass and update in one call
-    ("bert_large", False, True, True, None),
+    ("bert_large", False, True, True, None), ("bert_large_w256", False, True, True, None),
     # ... and its mixed-precision variant: binary16 gradient (inverse loss scale 1/512), bfloat16 copy of x
     ("bert_large", False, True, True, ("f16", "bf16", 1.0 / 512))])
 def test_bert_large_whole_step(name, two_pass, packed, fused, lp):
