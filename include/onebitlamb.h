@@ -247,7 +247,7 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * on having the device to themselves while they run: kernels of other streams or processes that
  * keep more than a fifth of the compute units busy for seconds on end can make a wait expire,
  * which is reported as above; shorter interference only slows them down.
- * OB_LAMB_SPIN_LIMIT=n at ob_lamb_create lowers the bound of the waits (0: give up after one poll);
+ * OB_LAMB_SPIN_LIMIT=n at ob_lamb_create lowers the bound of the waits (0: give up without polling);
  * it exists so that this path can be tested without ever hanging a kernel. */
 ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream);
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx);

@@ -451,19 +451,20 @@ __device__ __forceinline__ unsigned long long barrier_publish(unsigned long long
   return f;
 }
 
-// Bounded wait (thread 0 of a workgroup) for a flag of generation `want`; returns the flag word last
-// read.  On expiry *errflag is raised; once it is raised every wait ends within 64 polls.
+// Bounded wait (thread 0 of a workgroup) for a flag of generation `want`: at most spin_limit polls
+// (0: none, the wait expires at once whatever the flag holds); returns the flag word last read (0
+// if none was).  On expiry *errflag is raised; once it is raised every wait ends within 64 polls.
 __device__ __forceinline__ unsigned long long barrier_wait(const unsigned long long* flag,
                                                            unsigned int want, unsigned int* errflag,
                                                            int spin_limit) {
   unsigned long long f = 0ull;
   for (int it = 0;; ++it) {
-    f = __hip_atomic_load(flag, __ATOMIC_RELAXED, OB_AGENT);
-    if ((unsigned int)(f >> 32) == want) break;
     if (it >= spin_limit) {
       atomicOr(errflag, 1u);
       break;
     }
+    f = __hip_atomic_load(flag, __ATOMIC_RELAXED, OB_AGENT);
+    if ((unsigned int)(f >> 32) == want) break;
     if ((it & 63) == 63 && __hip_atomic_load(errflag, __ATOMIC_RELAXED, OB_AGENT) != 0u) break;
     __builtin_amdgcn_s_sleep(OB_POLL_SLEEP);
   }
@@ -1118,8 +1119,36 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
     X[u] = 0.0f;
     if (o < p.len) X[u] = ld4(aa.x + p.tile0 + o);
   }
+  // m_t/(sqrt(v_frozen)+eta) does not depend on the layer's coefficient: it is formed now, in place
+  // of v_frozen, so that the square root and the division run while the layer completes instead
+  // of after it (the same operations on the same operands as apply_uniform's)
+  const float sp = HAS_K ? ss / kt : ss;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float mt = ((rt.NB[u] >> k) & 1u) ? sp : -sp;
+        float uu = mt / (sqrtf(rt.VZ[u][k]) + aa.eta);
+        asm volatile("" : "+v"(uu));   // evaluated here, not sunk below the wait
+        rt.VZ[u][k] = uu;
+      }
+    }
+  }
   const float c = layer_wait(ls, l0, &bc);
-  apply_uniform<U, HAS_K, false, LPX>(aa, p, ss, kt, c, rt.NB, rt.VZ, X);
+  const float a = aa.lr * c;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      v4f xn;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) xn[k] = X[u][k] - a * rt.VZ[u][k];
+      st4(aa.x + p.tile0 + o, xn);
+      if (LPX) st4_lp(aa.x_lp, p.tile0 + o, xn, aa.x_lp_bf16);
+    }
+  }
 }
 
 // Dense view of a momentum held in 1-bit form: m[i] = (bit ? s_c : -s_c)/k_l for i < N (the

@@ -640,7 +640,7 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     // no more than that, whatever this one reaches
     const int64_t slots = (int64_t)std::min(per_cu, OB_RES_MINW) * cus;
     // OB_LAMB_SPIN_LIMIT=n lowers the bound of the device-side waits (tests of the expiry path: with
-    // 0 every wait gives up after one poll, all kernels still run to their end)
+    // 0 every wait gives up without polling, all kernels still run to their end)
     if (const char* sl = getenv("OB_LAMB_SPIN_LIMIT")) {
       const long v = atol(sl);
       if (v >= 0 && v < ctx->spin_limit) ctx->spin_limit = (int)v;

@@ -671,7 +671,7 @@ def test_mixed_precision_argument_errors():
 @pytest.mark.parametrize("which", ["compress", "ratios_apply", "warmup"])
 def test_expired_wait_is_reported_and_recovered(which):
     """The in-kernel barriers wait a bounded number of polls.  With the bound forced to 0 from the
-    host every waiting workgroup gives up after its first poll, raises the device flag and runs to
+    host every waiting workgroup gives up without polling, raises the device flag and runs to
     its end (nothing hangs, all accesses stay in bounds).  ob_lamb_check_device_status must report
     that once, switch the context to the barrier-free kernels, and the next steps -- from a restored
     state -- must again agree with the oracle."""
