@@ -980,20 +980,21 @@ __global__ __launch_bounds__(BLOCK) void k_decompress_apply(ApplyArgs aa, int64_
 // ---------------------------------------------------------------------------------------------
 // K5+K6+K7 in one pass: Algorithm 1 lines 13-21 with v_frozen and the sign words read once.
 // A workgroup runs the ratio pass on its tile of U 1024-element spans, keeps v_frozen and the signs
-// in registers, arrives at its layer's barrier, fetches x while the layer completes, and applies
-// the update from registers once the layer's coefficient c_t is published.
+// in registers, arrives at its layer's barrier, and while the layer completes writes v_fresh,
+// fetches x and forms m_t/(sqrt(v_frozen)+eta) in place of v_frozen; once the layer's coefficient
+// c_t is published only a multiply and a subtract per element are left before x is stored.
 //
-// The kernel covers "listed" tiles: tiles that lie inside ONE layer, at most as many per layer as
-// fit on the device at once (80 % of its workgroup slots; of a larger layer, the last that many).
-// Everything else -- the rest of such a layer, the spans where layers meet, small tensors -- goes
-// through the plain kernels on 1024-element tiles: the ratio pass before this kernel (the maxima
-// of those segments wait in seg_max) and the update after it.
+// The kernel covers "listed" tiles: the tiles that lie inside ONE layer, for every layer whose such
+// tiles all fit on the device at once (80 % of its workgroup slots).  Everything else -- layers
+// that are too large, the spans where layers meet, small tensors -- goes through the plain kernels
+// on 1024-element tiles: the ratio pass before this kernel (the maxima of those segments wait in
+// seg_max) and the update after it.
 //
-// Per-layer barrier: like the per-chunk one above, but the payload of a segment is its fp32
-// maximum of v_frozen/v_fresh (order-independent); the last of the layer's listed tiles to arrive
-// reduces ALL of the layer's segment maxima, applies the two clips (lines 18-19), commits r_prev
-// and coeff_c and publishes c_t in flag[l].  counter[l] grows by n_listed[l] per launch.  The
-// dispatch-order argument of the chunk barrier applies per layer; all waits are bounded (errflag).
+// Per-layer barrier: like the per-chunk one above (same self-numbering counter and flag words),
+// but the payload of a tile is its fp32 maximum of v_frozen/v_fresh (order-independent); the last
+// of the layer's listed tiles to arrive reduces ALL of the layer's maxima, applies the two clips
+// (lines 18-19), commits r_prev and coeff_c and publishes c_t in flag[l].  The dispatch-order
+// argument of the chunk barrier applies per layer; all waits are bounded (errflag).
 // ---------------------------------------------------------------------------------------------
 // What the last arriver of a layer needs to find the layer's partial results: the listed tiles
 // publish into an array of their own, indexed like the launch (tile_list position = blockIdx), and
