@@ -40,6 +40,7 @@ KERNEL_BYTES = {
     "both": {
         "sign_pack_error": (8.125, "n_pad"),     # R z (4) + W err (4) + W bits (1/8)
         "server_unpack_avg": (None, "n_c"),      # W/8 + 8, filled in below
+        "server_resident": (None, "n_c"),        # W/8 + 8.125, filled in below
         "server_sign_pack": (8.125, "n_c"),
         "warmup_moments": (24.0, "n_pad"),       # R g, m, v, x (16) + W m, v (8)
         "warmup_apply": (16.0, "n_pad"),         # R m, v, x (12) + W x (4)
@@ -215,6 +216,7 @@ def main():
     KB = dict(KERNEL_BYTES["both"])
     KB.update(KERNEL_BYTES[mode])
     KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
+    KB["server_resident"] = (W / 8.0 + 8.125, "n_c")   # R W*bits, err (4) + W err (4), bits (1/8)
     g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
     for k in ("compress_resident", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):

@@ -251,6 +251,11 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * it exists so that this path can be tested without ever hanging a kernel. */
 ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream);
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx);
+/* ob_lamb_server_reduce as one kernel with a chunk barrier (the averaged chunk stays in registers
+ * between Algorithm 1 line 10's sum and its recompression): 0 if the three-kernel form is used (the
+ * served chunk's workgroups do not fit on the device at once, OB_LAMB_TWO_PASS=1, or after an
+ * expired wait), else the kernel's tile size in units of 1024 elements (1, 2 or 4). */
+int32_t ob_lamb_server_single_pass(const ob_lamb_ctx* ctx);
 
 /* ---- per-kernel timing (diagnostics; used by the benchmark) ----
  * While enabled, every kernel launch of this context is bracketed by HIP events on its stream.

@@ -78,6 +78,7 @@ def lib():
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
             "ob_lamb_uses_single_pass": (i32, [vp]),
+            "ob_lamb_server_single_pass": (i32, [vp]),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
             "ob_lamb_profile_read": (i32, [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(i64)]),
@@ -247,6 +248,10 @@ def ob_lamb_check_device_status(ctx, stream=None):
 
 def ob_lamb_uses_single_pass(ctx):
     return bool(lib().ob_lamb_uses_single_pass(ctx))
+
+
+def ob_lamb_server_single_pass(ctx):
+    return int(lib().ob_lamb_server_single_pass(ctx))
 
 
 def ob_lamb_profile_enable(ctx, on):

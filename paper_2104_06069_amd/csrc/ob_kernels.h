@@ -645,6 +645,46 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
   if (threadIdx.x == 0) partials[p.t] = s;
 }
 
+// K3+K4 in one pass: Algorithm 1 line 10 on the served chunk with zb kept in registers across the
+// chunk barrier above (one chunk: c = 0, its own counter, flag and partials), instead of three
+// launches and a round trip of zb through err_server.  The host selects it only when all of its
+// workgroups fit on the device at once.
+template <int U>
+__global__ __launch_bounds__(BLOCK) void k_server_resident(
+    const uint32_t* __restrict__ packed_in, const float* __restrict__ scales_in,
+    float* __restrict__ err_s, uint32_t* __restrict__ packed_out, float* __restrict__ scale_out,
+    ChunkSync cs, int64_t n_c, int W, float invW) {
+  constexpr int TILE = SPAN * U;
+  __shared__ double lds[BLOCK / WAVE];
+  __shared__ unsigned long long bc;
+  const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x, (int)blockIdx.x);  // one chunk: c == 0
+  const int o0 = threadIdx.x * 4;
+  float acc[U][4];
+  server_average<U>(packed_in, scales_in, n_c, W, p, acc);
+  v4f Z[U];
+  double sq = 0.0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    Z[u] = 0.0f;
+    if (o < p.len) {
+      const v4f e = ld4(err_s + p.tile0 + o);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        Z[u][k] = acc[u][k] * invW + e[k];
+        sq += (double)Z[u][k] * (double)Z[u][k];
+      }
+    }
+  }
+  const double part = block_sum(sq, lds);
+  const float s = chunk_barrier_scale(cs, p.t, 0, (int)gridDim.x, n_c, part, lds, &bc, scale_out);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) sign_pack_store(Z[u], s, err_s, packed_out, p.tile0 + u * SPAN);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // K5  per layer: global momentum, reconstructed gradient, fresh variance, max(v_frozen/v_fresh)
 //     (Algorithm 1 lines 13, 15-17).  One maximum per (tile, layer) segment, no atomics.

@@ -27,6 +27,10 @@ namespace {
 // kernels with a per-layer barrier share the segment arrays of this tiling, so it is fixed at 1.
 constexpr int U_MAIN = 1;
 constexpr int U_SRV = 1;    // ... in the kernels over the single server chunk
+// ... in the single-pass server kernel (zb stays in registers): the smallest of these whose tiles of
+// the served chunk all fit on the device at once (more, smaller workgroups hide the W dependent
+// additions per element better)
+constexpr int U_SRV_RES[] = {1, 2, 4};   // (8 would need registers that cost more slots than it saves tiles)
 #ifndef OB_U_RES
 #define OB_U_RES 16
 #endif
@@ -62,6 +66,7 @@ enum KernelId {
   KID_SERVER_AVG,
   KID_SERVER_SCALE,
   KID_SERVER_PACK,
+  KID_SERVER_RESIDENT,
   KID_RATIOS_PASS,
   KID_RATIOS_FINALIZE,
   KID_APPLY,
@@ -78,7 +83,7 @@ enum KernelId {
 };
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "server_unpack_avg",
-    "server_scale",     "server_sign_pack", "ratios_pass",     "ratios_finalize",
+    "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
     "decompress_apply", "ratios_apply_resident", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
 
@@ -147,6 +152,13 @@ struct ob_lamb_ctx {
   unsigned long long* d_counter = nullptr; // [W * CTR_STRIDE] (generation << 32) | arrivals
   unsigned long long* d_flag = nullptr;    // [W] (generation << 32) | scale bits
   unsigned int* d_errflag = nullptr;       // [1] raised when a bounded wait expired
+  // single-pass server kernel (k_server_resident): selected at create when all of its workgroups
+  // fit on the device at once
+  int u_srv_res = 0;                           // its tile size in 1024-element spans; 0: not used
+  int tpc_srv_res = 0;                         // such tiles of the server chunk
+  double* d_partials_srv_res = nullptr;        // [tpc_srv_res]
+  unsigned long long* d_counter_srv = nullptr; // [CTR_STRIDE]
+  unsigned long long* d_flag_srv = nullptr;    // [1]
   int spin_limit = 1 << 20;
   // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
   // tiling (TILE_LB; the segment arrays are those of the TILE_MAIN tiling) and, for each, the split
@@ -647,6 +659,21 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     }
     const char* env = getenv("OB_LAMB_TWO_PASS");
     ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
+    // the single-pass server kernel: same rule for the one chunk it covers
+    int per_cu_s[3] = {0, 0, 0};
+    ok = ok &&
+         hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s[0], k_server_resident<U_SRV_RES[0]>, BLOCK, 0),
+                "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
+         hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s[1], k_server_resident<U_SRV_RES[1]>, BLOCK, 0),
+                "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
+         hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s[2], k_server_resident<U_SRV_RES[2]>, BLOCK, 0),
+                "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+    // the tile table of the chunk's partials is sized for the smallest tile
+    ctx->tpc_srv_res = (int)((ctx->n_c + SPAN - 1) / SPAN);
+    for (int i = 0; ok && i < 3 && ctx->u_srv_res == 0 && !(env && env[0] == '1'); ++i) {
+      const int64_t tiles = (ctx->n_c + (int64_t)SPAN * U_SRV_RES[i] - 1) / ((int64_t)SPAN * U_SRV_RES[i]);
+      if (5 * (tiles + 8) <= 4 * (int64_t)per_cu_s[i] * cus) ctx->u_srv_res = U_SRV_RES[i];
+    }
   }
   // the two kernels with a per-layer barrier: which layers each of them takes.  The slot count is
   // the kernel's launch bound (every instantiation reaches it), whatever the one queried reaches.
@@ -670,7 +697,9 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
        alloc_zero(ctx, &ctx->d_counter, (size_t)ctx->W * CTR_STRIDE) && alloc_zero(ctx, &ctx->d_flag, (size_t)ctx->W) &&
-       alloc_zero(ctx, &ctx->d_errflag, 1);
+       alloc_zero(ctx, &ctx->d_errflag, 1) &&
+       alloc_zero(ctx, &ctx->d_partials_srv_res, (size_t)ctx->tpc_srv_res) &&
+       alloc_zero(ctx, &ctx->d_counter_srv, (size_t)CTR_STRIDE) && alloc_zero(ctx, &ctx->d_flag_srv, 1);
   ok = ok && upload(ctx, &ctx->d_off, h_off) && upload(ctx, &ctx->d_first_layer, first) &&
        upload(ctx, &ctx->d_tile_seg0, tile_seg0) && upload(ctx, &ctx->d_seg_layer, seg_layer) &&
        upload(ctx, &ctx->d_layer_seg0, layer_seg0) &&
@@ -694,7 +723,8 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
   }
   void* ptrs[] = {ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer, ctx->d_layer_seg0,
                   ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max, ctx->d_sigma,
-                  ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag};
+                  ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag,
+                  ctx->d_partials_srv_res, ctx->d_counter_srv, ctx->d_flag_srv};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   free_split(&ctx->sp_apply);
@@ -846,6 +876,26 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
   REQUIRE_PTR(packed_in); REQUIRE_PTR(packed_out); REQUIRE_PTR(st->err_server);
   if (!scales_in || !scale_out) return OB_ERR_NULL;
   Launch la(ctx, hip_stream);
+  if (ctx->u_srv_res) {
+    ChunkSync cs;
+    cs.partials = ctx->d_partials_srv_res;
+    cs.counter = ctx->d_counter_srv;
+    cs.flag = ctx->d_flag_srv;
+    cs.errflag = ctx->d_errflag;
+    cs.spin_limit = ctx->spin_limit;
+    const int64_t tile = (int64_t)SPAN * ctx->u_srv_res;
+    const int tiles = (int)((ctx->n_c + tile - 1) / tile);
+    auto launch = [&](auto u) {
+      OB_LAUNCH(la, KID_SERVER_RESIDENT, (k_server_resident<decltype(u)::value>), tiles, packed_in, scales_in,
+                st->err_server, packed_out, scale_out, cs, ctx->n_c, (int)ctx->W, ctx->invW);
+    };
+    switch (ctx->u_srv_res) {
+      case 1: launch(std::integral_constant<int, 1>{}); break;
+      case 2: launch(std::integral_constant<int, 2>{}); break;
+      default: launch(std::integral_constant<int, 4>{}); break;
+    }
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
   OB_LAUNCH(la, KID_SERVER_AVG, (k_server_unpack_avg<U_SRV>), ctx->tpc_srv, packed_in, scales_in,
             st->err_server, ctx->d_partials_srv, ctx->n_c, (int)ctx->W, ctx->invW);
   OB_LAUNCH_B(la, KID_SERVER_SCALE, k_chunk_scale, 1, FBLOCK, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out);
@@ -986,6 +1036,9 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   // a bounded wait expired: the step that raised it produced undefined outputs.  Re-arm the
   // synchronisation state and fall back to the two-pass kernels for the rest of this context.
   ctx->resident = false;
+  ctx->u_srv_res = 0;
+  (void)hipMemset(ctx->d_counter_srv, 0, sizeof(unsigned long long) * CTR_STRIDE);
+  (void)hipMemset(ctx->d_flag_srv, 0, sizeof(unsigned long long));
   for (LayerSplit* sp : {&ctx->sp_apply, &ctx->sp_warm}) {
     sp->on = false;
     (void)hipMemset(sp->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->L * CTR_STRIDE);
@@ -1004,6 +1057,7 @@ int64_t ob_lamb_warmup_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx
 int64_t ob_lamb_warmup_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_params : 0; }
 
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx) { return (ctx && ctx->resident) ? 1 : 0; }
+int32_t ob_lamb_server_single_pass(const ob_lamb_ctx* ctx) { return ctx ? ctx->u_srv_res : 0; }
 
 ob_status ob_lamb_profile_enable(ob_lamb_ctx* ctx, int on) {
   if (!ctx) return OB_ERR_NULL;

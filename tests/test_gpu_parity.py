@@ -716,6 +716,7 @@ def test_expired_wait_is_reported_and_recovered(which):
         ob.ob_lamb_check_device_status(dev.ctx, dev.stream)
     assert e.value.status == -4
     assert ob.ob_lamb_uses_single_pass(dev.ctx) == 0 and ob.ob_lamb_fused_layers(dev.ctx) == 0
+    assert ob.ob_lamb_server_single_pass(dev.ctx) == 0
     assert ob.ob_lamb_warmup_fused_layers(dev.ctx) == 0
     ob.ob_lamb_check_device_status(dev.ctx, dev.stream)      # reported once; the context is usable again
     if which == "warmup":   # the two-pass form now: two LAMB steps against the oracle, then the snapshot
@@ -930,4 +931,40 @@ def test_random_layer_lists(seed):
         assert np.array_equal(words_of(dev.packed_all), ref.bits_all), f"step {t}: server words"
         for key in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
             assert_close(dev.get(key), ref.t[key], f"step {t} {key}")
+    finish(dev)
+
+
+@pytest.mark.parametrize("n_c_target,W,expect", [
+    (300_000, 3, 1), (2_500_000, 2, 2), (5_000_000, 2, 4), (8_000_000, 1, 0), (300_000, 3, "two_pass")])
+def test_server_reduce_forms(n_c_target, W, expect):
+    """ob_lamb_server_reduce in each of its forms -- one kernel with a chunk barrier on tiles of
+    1024, 2048 or 4096 elements (the smallest whose workgroups all fit on the device), three
+    kernels when the chunk is too large for that or when asked for -- against the oracle, two
+    calls in a row (the second starts from the first one's error buffer), ragged chunk end."""
+    _need_gpu()
+    import paper_2104_06069_amd as ob
+    from tests.refstep import F32
+    N = n_c_target * W - 777
+    pl = ParamList("srv", [("a", N // 3), ("b", N - N // 3)])
+    two_pass = expect == "two_pass"
+    dev = DeviceStep(pl.offsets, W, W - 1, two_pass=two_pass, **HYPER)
+    form = ob.ob_lamb_server_single_pass(dev.ctx)
+    print(f"n_c {dev.n_c} W {W}: single-pass server kernel tile = {form} x 1024", flush=True)
+    assert form == (0 if two_pass else expect)
+    r = np.random.default_rng(n_c_target + W)
+    err = (1e-4 * r.standard_normal(dev.n_c)).astype(np.float32)
+    dev.t["err_server"].copy_(torch.from_numpy(err))
+    for call in range(2):
+        words = r.integers(0, 2 ** 32, size=W * dev.n_c // 32, dtype=np.uint64).astype(np.uint32)
+        scales = (1e-4 * r.uniform(0.5, 1.5, W)).astype(np.float32)
+        dev.packed_in.copy_(torch.from_numpy(words.view(np.int32)))
+        dev.scales_in.copy_(torch.from_numpy(scales))
+        bits_ref, s_ref = F32.server_reduce(W, words.view(np.uint8), scales, err)   # err updated in place
+        dev.server_reduce()
+        torch.cuda.synchronize()
+        wpc = dev.n_c // 32
+        got = words_of(dev.packed_all)[(W - 1) * wpc * 4:W * wpc * 4]
+        assert np.array_equal(got, bits_ref), f"call {call}: recompressed sign words"
+        assert_close(dev.server_scales.cpu().numpy()[W - 1:W], np.array([s_ref], np.float32), f"call {call}: scale")
+        assert_close(dev.get("err_server"), err, f"call {call}: server error")
     finish(dev)
