@@ -1500,6 +1500,7 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
   const float ca = ws.c_avg[l0];
   const int o0 = threadIdx.x * 4;
   v4f UU[U], X[U];
+  v4f Ml[G], Vl[G];   // m and v of the last group: stored after the arrival, which then waits for no store
   double sx = 0.0, su = 0.0;
 #pragma unroll
   for (int u0 = 0; u0 < U; u0 += G) {
@@ -1524,8 +1525,13 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
           M[j][k] = beta1 * M[j][k] + omb1 * Gr[j][k];
           V[j][k] = beta2 * V[j][k] + omb2 * (Gr[j][k] * Gr[j][k]);
         }
-        st4(m + p.tile0 + o, M[j]);
-        st4(v + p.tile0 + o, V[j]);
+        if (u0 + G < U) {
+          st4(m + p.tile0 + o, M[j]);
+          st4(v + p.tile0 + o, V[j]);
+        } else {
+          Ml[j] = M[j];
+          Vl[j] = V[j];
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const float uu = lamb_u(M[j][k], V[j][k], X[u0 + j][k], eta, wd);
@@ -1550,6 +1556,14 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
   const bool last = ((bc & 1ull) != 0ull);
   const unsigned int want = (unsigned int)(bc >> 32);
   __syncthreads();
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    const int o = (U - G + j) * SPAN + o0;
+    if (o < p.len) {
+      st4(m + p.tile0 + o, Ml[j]);
+      st4(v + p.tile0 + o, Vl[j]);
+    }
+  }
   float c;
   if (last) {
     double tx = 0.0, tu = 0.0;
