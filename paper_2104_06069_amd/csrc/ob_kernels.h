@@ -418,7 +418,7 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
 //
 // Synchronisation uses relaxed agent-scope atomics whose payload travels in the atomic itself
 // (partials: one double each; flag[c]: generation in the high word, scale bits in the low word),
-// so no cache write-back/invalidate is needed; the store of the partial is complete (s_waitcnt)
+// so no cache write-back/invalidate is needed; the store of the partial is complete (an explicit s_waitcnt)
 // before the arrival counter is incremented.
 //
 // The barrier carries its own launch numbering, so a launch needs nothing from the host that
@@ -435,6 +435,14 @@ struct ChunkSync {
   unsigned int* errflag;        // [1]
   int spin_limit;
 };
+
+// Between a workgroup's publication of its payload (write-through atomic stores) and its arrival:
+// the stores have been acknowledged before the arrival is issued, so whoever sees the arrival
+// finds the payload.  (A release fence of workgroup scope emits no wait here, and one of agent
+// scope would also write back the L2's dirty lines, i.e. the kernel's own streaming stores.)
+__device__ __forceinline__ void payload_before_arrival() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
 
 // One arrival at `counter` of a barrier with n participants: returns ((generation + 1) << 32) |
 // (1 if this was the last arrival).
@@ -482,7 +490,7 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int ti
   unsigned long long* counter = &cs.counter[(int64_t)c * CTR_STRIDE];
   if (threadIdx.x == 0) {
     __hip_atomic_store(&cs.partials[tile], part, __ATOMIC_RELAXED, OB_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
+    payload_before_arrival();
     *bc = barrier_arrive(counter, tpc);
   }
   __syncthreads();
@@ -1096,7 +1104,7 @@ __device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const L
   unsigned long long* counter = &ls.counter[(int64_t)l * CTR_STRIDE];
   if (threadIdx.x == 0) {
     __hip_atomic_store(&ls.listed_max[blockIdx.x], r, __ATOMIC_RELAXED, OB_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // store complete before the add
+    payload_before_arrival();
     *bc = barrier_arrive(counter, lp.nl);
   }
   __syncthreads();
@@ -1549,7 +1557,7 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
   if (threadIdx.x == 0) {
     __hip_atomic_store(&ws.listed_sums[2 * (int64_t)blockIdx.x], sx, __ATOMIC_RELAXED, OB_AGENT);
     __hip_atomic_store(&ws.listed_sums[2 * (int64_t)blockIdx.x + 1], su, __ATOMIC_RELAXED, OB_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // stores complete before the add
+    payload_before_arrival();
     bc = barrier_arrive(counter, lp.nl);
   }
   __syncthreads();
