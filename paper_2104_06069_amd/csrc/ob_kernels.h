@@ -498,9 +498,18 @@ __device__ __forceinline__ float chunk_barrier_scale(const ChunkSync& cs, int ti
   const unsigned int want = (unsigned int)(*bc >> 32);
   __syncthreads();
   if (last) {
+    // four loads in flight per thread: every waiter of the chunk is waiting for this sum (the
+    // partials are >= +0, so the zeros that stand in for missing ones change nothing)
     double a = 0.0;
-    for (int j = threadIdx.x; j < tpc; j += BLOCK)
-      a += __hip_atomic_load(&cs.partials[(int64_t)c * tpc + j], __ATOMIC_RELAXED, OB_AGENT);
+    const double* part_c = cs.partials + (int64_t)c * tpc;
+    for (int j = threadIdx.x; j < tpc; j += 4 * BLOCK) {
+      double v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        v[q] = (j + q * BLOCK < tpc) ? __hip_atomic_load(&part_c[j + q * BLOCK], __ATOMIC_RELAXED, OB_AGENT) : 0.0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a += v[q];
+    }
     const double S = block_sum(a, lds);
     if (threadIdx.x == 0) {
       const float sc = (float)sqrt(S / (double)n_c);
@@ -1073,11 +1082,19 @@ __device__ __forceinline__ LayerParts layer_parts(const ListedTiles& lt, int l) 
   return q;
 }
 
-// Calls listed(i) for every listed tile of the layer (i = its position in tile_list) and plain(j)
-// for every plain-kernel segment j of it, strided over the workgroup's threads.
-template <class FL, class FP>
-__device__ __forceinline__ void for_layer_parts(const LayerParts& q, FL listed, FP plain) {
-  for (int j = threadIdx.x; j < q.nl; j += BLOCK) listed(q.lb + j);
+// The last arriver's walk over a layer's partial results, strided over the workgroup's threads:
+// comb(load(i)) for every listed tile of the layer (i = its position in tile_list), four loads in
+// flight per thread (every waiter of the layer is waiting for this; `zero` stands in for missing
+// ones and must leave comb's result unchanged), then plain(j) for every plain-kernel segment j.
+template <class T, class FL, class FC, class FP>
+__device__ __forceinline__ void for_layer_parts(const LayerParts& q, T zero, FL load, FC comb, FP plain) {
+  for (int j = threadIdx.x; j < q.nl; j += 4 * BLOCK) {
+    T v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = (j + u * BLOCK < q.nl) ? load(q.lb + j + u * BLOCK) : zero;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) comb(v[u]);
+  }
   for (int j = q.a + threadIdx.x; j < q.s_first; j += BLOCK) plain(j);
   for (int j = q.s_end + threadIdx.x; j < q.b; j += BLOCK) plain(j);
 }
@@ -1114,11 +1131,9 @@ __device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const L
   if (last) {
     float q = 0.0f;
     for_layer_parts(
-        lp,
-        [&](int i) {
-          const float v = __hip_atomic_load(&ls.listed_max[i], __ATOMIC_RELAXED, OB_AGENT);
-          if (v > q) q = v;
-        },
+        lp, 0.0f,
+        [&](int i) { return __hip_atomic_load(&ls.listed_max[i], __ATOMIC_RELAXED, OB_AGENT); },
+        [&](float v) { if (v > q) q = v; },
         [&](int j) {
           const float v = ls.seg_max[j];   // written by an earlier kernel
           if (v > q) q = v;
@@ -1575,12 +1590,16 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
   float c;
   if (last) {
     double tx = 0.0, tu = 0.0;
+    struct Sums { double x, u; };
     for_layer_parts(
-        lp,
+        lp, Sums{0.0, 0.0},   // the sums are >= +0: adding these zeros changes nothing
         [&](int i) {
-          tx += __hip_atomic_load(&ws.listed_sums[2 * (int64_t)i], __ATOMIC_RELAXED, OB_AGENT);
-          tu += __hip_atomic_load(&ws.listed_sums[2 * (int64_t)i + 1], __ATOMIC_RELAXED, OB_AGENT);
+          Sums v;
+          v.x = __hip_atomic_load(&ws.listed_sums[2 * (int64_t)i], __ATOMIC_RELAXED, OB_AGENT);
+          v.u = __hip_atomic_load(&ws.listed_sums[2 * (int64_t)i + 1], __ATOMIC_RELAXED, OB_AGENT);
+          return v;
         },
+        [&](const Sums& v) { tx += v.x; tu += v.u; },
         [&](int j) {   // written by an earlier kernel
           tx += ws.seg_sums[2 * (int64_t)j];
           tu += ws.seg_sums[2 * (int64_t)j + 1];
