@@ -187,6 +187,17 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * layer with more than n such tiles. */
 ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, float lr, void* hip_stream);
+/* Host-only planning query (no HIP call, no device needed): how ob_lamb_create splits a tensor list
+ * between a kernel with a per-layer barrier and the plain kernels when one layer may occupy at most
+ * max_tiles of that kernel's 8192-element tiles (on a device, 80 % of the kernel's workgroup
+ * slots).  span_owner: host, [W * ceil(n_c / 1024)] bytes, one per 1024-element span of the
+ * padded buffer, chunk-major (the last span of a chunk may be shorter): 0 = holds no parameter
+ * (padding only, no kernel visits it), 1 = plain kernels, 2 = barrier kernel.  layer_listed: host,
+ * [L], number of 8192-element tiles of each layer that the barrier kernel takes (0: the layer is
+ * finished by the plain kernels).  Returns OB_ERR_NULL / OB_ERR_ARG like ob_lamb_create. */
+ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8_t* span_owner,
+                             int32_t* layer_listed);
+
 /* Number of layers the single kernel of ob_lamb_ratios_apply takes part in on this device (0..L). */
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx);
 /* ... and the number of parameters in its tiles. */

@@ -79,6 +79,7 @@ def lib():
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_server_single_pass": (i32, [vp]),
+            "ob_lamb_plan_split": (C.c_int, [C.POINTER(ObLambConfig), i64, vp, vp]),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
             "ob_lamb_profile_read": (i32, [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(i64)]),
@@ -133,6 +134,22 @@ def ob_lamb_create(layer_offsets, num_workers, server_chunk=0, beta1=0.9, beta2=
     if st != OB_OK:
         raise ObLambError(st, "ob_lamb_create")
     return out
+
+
+def ob_lamb_plan_split(layer_offsets, num_workers, max_tiles):
+    """Host-only: -> (span_owner uint8[W * ceil(n_c/1024)], layer_listed int32[L]) as numpy arrays."""
+    import numpy as np
+    offs = [int(o) for o in layer_offsets]
+    arr = (C.c_int64 * len(offs))(*offs)
+    cfg = ObLambConfig(len(offs) - 1, arr, int(num_workers), 0, 0.9, 0.999, 0.9, 1e-6, 0.01, 0.3, 0.5, 4.0,
+                       0.1, 0.0)
+    n_c = ob_lamb_padded_len_for(offs[-1], num_workers) // int(num_workers)
+    owner = np.zeros(int(num_workers) * ((n_c + 1023) // 1024), dtype=np.uint8)
+    listed = np.zeros(len(offs) - 1, dtype=np.int32)
+    st = lib().ob_lamb_plan_split(C.byref(cfg), int(max_tiles), owner.ctypes.data, listed.ctypes.data)
+    if st != OB_OK:
+        raise ObLambError(st, "ob_lamb_plan_split")
+    return owner, listed
 
 
 def ob_lamb_destroy(ctx):

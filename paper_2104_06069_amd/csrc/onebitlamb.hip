@@ -362,19 +362,28 @@ bool build_tiling(int64_t tile, int64_t n_c, int64_t W, int64_t L, const std::ve
   return true;
 }
 
-// Builds and uploads one LayerSplit.  tl / tm: the TILE_LB and TILE_MAIN tilings; max_tiles: the
-// largest number of tiles of one layer the barrier kernel may hold (0: it is not used).
-bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off,
-                 int64_t max_tiles, LayerSplit* sp) {
-  const int64_t L = ctx->L;
-  std::vector<unsigned char> has_listed((size_t)L, 0);
-  std::vector<int> fused_tiles, rest_tiles, n_listed((size_t)L, 0), list_begin((size_t)L, 0);
-  std::vector<int> seg_first((size_t)L, 0), seg_end((size_t)L, 0);
-  std::vector<unsigned char> covered((size_t)tm.n_tiles, 0);   // TILE_MAIN tiles inside listed tiles
+// The host side of one LayerSplit: which tiles the barrier kernel takes and what is left.
+struct SplitPlan {
+  std::vector<unsigned char> has_listed;   // [L] 1 for layers that the barrier kernel finishes
+  std::vector<int> fused_tiles, rest_tiles, n_listed, list_begin, seg_first, seg_end;
+  std::vector<unsigned char> covered;      // [TILE_MAIN tiles] 1 inside a listed tile
+  int64_t n_layers = 0, n_params = 0;
+};
+
+// tl / tm: the TILE_LB and TILE_MAIN tilings; max_tiles: the largest number of tiles of one layer
+// the barrier kernel may hold (0: it is not used).  No HIP call.
+void plan_split(const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off, int64_t n_c,
+                int64_t L, int64_t max_tiles, SplitPlan* pl) {
+  pl->has_listed.assign((size_t)L, 0);
+  pl->n_listed.assign((size_t)L, 0);
+  pl->list_begin.assign((size_t)L, 0);
+  pl->seg_first.assign((size_t)L, 0);
+  pl->seg_end.assign((size_t)L, 0);
+  pl->covered.assign((size_t)tm.n_tiles, 0);
   auto tile_range = [&](int64_t t, int64_t* tile0, int64_t* tile1) {
     const int64_t c = t / tl.tpc, b = t % tl.tpc;
-    *tile0 = c * ctx->n_c + b * TILE_LB;
-    *tile1 = std::min(*tile0 + (int64_t)TILE_LB, (c + 1) * ctx->n_c);
+    *tile0 = c * n_c + b * TILE_LB;
+    *tile1 = std::min(*tile0 + (int64_t)TILE_LB, (c + 1) * n_c);
   };
   // tiles inside one layer, per layer in position order
   std::vector<std::vector<int>> inside((size_t)L);
@@ -388,35 +397,46 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std
     const std::vector<int>& in = inside[(size_t)l];
     const size_t n = in.size();
     if (n == 0 || n > (size_t)max_tiles) continue;
-    has_listed[(size_t)l] = 1;
-    n_listed[(size_t)l] = (int)n;
-    list_begin[(size_t)l] = (int)fused_tiles.size();
-    sp->n_layers += 1;
+    pl->has_listed[(size_t)l] = 1;
+    pl->n_listed[(size_t)l] = (int)n;
+    pl->list_begin[(size_t)l] = (int)pl->fused_tiles.size();
+    pl->n_layers += 1;
     for (size_t j = 0; j < n; ++j) {
       const int64_t t = in[j];
       int64_t tile0, tile1;
       tile_range(t, &tile0, &tile1);
-      fused_tiles.push_back((int)t);
-      sp->n_params += tile1 - tile0;
+      pl->fused_tiles.push_back((int)t);
+      pl->n_params += tile1 - tile0;
       const int64_t c = t / tl.tpc, b = t % tl.tpc;
       const int64_t span0 = c * tm.tpc + b * (TILE_LB / TILE_MAIN);
       const int64_t nspan = (tile1 - tile0 + TILE_MAIN - 1) / TILE_MAIN;
-      for (int64_t j2 = 0; j2 < nspan; ++j2) covered[(size_t)(span0 + j2)] = 1;
+      for (int64_t j2 = 0; j2 < nspan; ++j2) pl->covered[(size_t)(span0 + j2)] = 1;
       // each of these spans lies inside the layer: one segment each, consecutive
-      if (j == 0) seg_first[(size_t)l] = tm.tile_seg0[(size_t)span0];
-      seg_end[(size_t)l] = tm.tile_seg0[(size_t)(span0 + nspan)];
+      if (j == 0) pl->seg_first[(size_t)l] = tm.tile_seg0[(size_t)span0];
+      pl->seg_end[(size_t)l] = tm.tile_seg0[(size_t)(span0 + nspan)];
     }
   }
-  sp->on = !fused_tiles.empty();
   for (int64_t t = 0; t < tm.n_tiles; ++t)
-    if (!covered[(size_t)t] && tm.tile_seg0[(size_t)t + 1] > tm.tile_seg0[(size_t)t]) rest_tiles.push_back((int)t);
-  sp->n_fused_tiles = (int)fused_tiles.size();
-  sp->n_rest_tiles = (int)rest_tiles.size();
-  return upload(ctx, &sp->d_fused_tiles, fused_tiles) && upload(ctx, &sp->d_n_listed, n_listed) &&
-         upload(ctx, &sp->d_list_begin, list_begin) && upload(ctx, &sp->d_seg_first, seg_first) &&
-         upload(ctx, &sp->d_seg_end, seg_end) && alloc_zero(ctx, &sp->d_listed_max, fused_tiles.size()) &&
-         alloc_zero(ctx, &sp->d_listed_sums, 2 * fused_tiles.size()) &&
-         upload(ctx, &sp->d_rest_tiles, rest_tiles) && upload(ctx, &sp->d_has_listed, has_listed) &&
+    if (!pl->covered[(size_t)t] && tm.tile_seg0[(size_t)t + 1] > tm.tile_seg0[(size_t)t])
+      pl->rest_tiles.push_back((int)t);
+}
+
+// Plans and uploads one LayerSplit.
+bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off,
+                 int64_t max_tiles, LayerSplit* sp) {
+  const int64_t L = ctx->L;
+  SplitPlan pl;
+  plan_split(tl, tm, h_off, ctx->n_c, L, max_tiles, &pl);
+  sp->n_layers = pl.n_layers;
+  sp->n_params = pl.n_params;
+  sp->on = !pl.fused_tiles.empty();
+  sp->n_fused_tiles = (int)pl.fused_tiles.size();
+  sp->n_rest_tiles = (int)pl.rest_tiles.size();
+  return upload(ctx, &sp->d_fused_tiles, pl.fused_tiles) && upload(ctx, &sp->d_n_listed, pl.n_listed) &&
+         upload(ctx, &sp->d_list_begin, pl.list_begin) && upload(ctx, &sp->d_seg_first, pl.seg_first) &&
+         upload(ctx, &sp->d_seg_end, pl.seg_end) && alloc_zero(ctx, &sp->d_listed_max, pl.fused_tiles.size()) &&
+         alloc_zero(ctx, &sp->d_listed_sums, 2 * pl.fused_tiles.size()) &&
+         upload(ctx, &sp->d_rest_tiles, pl.rest_tiles) && upload(ctx, &sp->d_has_listed, pl.has_listed) &&
          alloc_zero(ctx, &sp->d_counter, (size_t)L * CTR_STRIDE) && alloc_zero(ctx, &sp->d_flag, (size_t)L);
 }
 
@@ -563,9 +583,8 @@ ob_status ob_lamb_create(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   }
 }
 
-static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
-  if (out) *out = nullptr;
-  if (!cfg || !out || !cfg->layer_offsets) return OB_ERR_NULL;
+static ob_status check_config(const ob_lamb_config* cfg) {
+  if (!cfg || !cfg->layer_offsets) return OB_ERR_NULL;
   const int64_t L = cfg->num_layers;
   if (L < 1 || L > (int64_t)1 << 24 || cfg->num_workers < 1 || cfg->num_workers > 65536) return OB_ERR_ARG;
   if (cfg->server_chunk < 0 || cfg->server_chunk >= cfg->num_workers) return OB_ERR_ARG;
@@ -579,6 +598,47 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   for (float f : fl)
     if (!std::isfinite(f)) return OB_ERR_ARG;
   if (cfg->c_min > cfg->c_max || cfg->r_min > cfg->r_max) return OB_ERR_ARG;
+  return OB_OK;
+}
+
+// Offsets with the sentinel the per-element paths rely on.
+static std::vector<int64_t> host_offsets(const ob_lamb_config* cfg) {
+  const int64_t L = cfg->num_layers;
+  std::vector<int64_t> h_off((size_t)L + 2);
+  for (int64_t l = 0; l <= L; ++l) h_off[(size_t)l] = cfg->layer_offsets[l];
+  h_off[(size_t)L + 1] = std::numeric_limits<int64_t>::max();
+  return h_off;
+}
+
+ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8_t* span_owner,
+                             int32_t* layer_listed) {
+  if (ob_status s = check_config(cfg)) return s;
+  if (!span_owner || !layer_listed) return OB_ERR_NULL;
+  if (max_tiles < 0) return OB_ERR_ARG;
+  try {
+    const int64_t L = cfg->num_layers, W = cfg->num_workers;
+    const int64_t n_c = ob_lamb_padded_len_for(cfg->layer_offsets[L], cfg->num_workers) / W;
+    const std::vector<int64_t> h_off = host_offsets(cfg);
+    Tiling tm, tl;
+    if (!build_tiling(TILE_MAIN, n_c, W, L, h_off, &tm) || !build_tiling(TILE_LB, n_c, W, L, h_off, &tl))
+      return OB_ERR_ARG;
+    SplitPlan pl;
+    plan_split(tl, tm, h_off, n_c, L, max_tiles, &pl);
+    for (int64_t t = 0; t < tm.n_tiles; ++t) span_owner[t] = pl.covered[(size_t)t] ? 2 : 0;
+    for (int t : pl.rest_tiles) span_owner[t] = 1;
+    for (int64_t l = 0; l < L; ++l) layer_listed[l] = pl.n_listed[(size_t)l];
+    return OB_OK;
+  } catch (const std::bad_alloc&) {
+    return OB_ERR_ARG;
+  }
+}
+
+static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
+  if (out) *out = nullptr;
+  if (!out) return OB_ERR_NULL;
+  if (ob_status s = check_config(cfg)) return s;
+  const int64_t L = cfg->num_layers;
+  const int64_t N = cfg->layer_offsets[L];
 
   ob_lamb_ctx* ctx = new (std::nothrow) ob_lamb_ctx();
   if (!ctx) return OB_ERR_ARG;
@@ -607,9 +667,7 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   if (tpc_srv > 0x7fffffff) return OB_ERR_ARG;
   ctx->tpc_srv = (int)tpc_srv;
 
-  std::vector<int64_t> h_off((size_t)L + 2);
-  for (int64_t l = 0; l <= L; ++l) h_off[(size_t)l] = cfg->layer_offsets[l];
-  h_off[(size_t)L + 1] = std::numeric_limits<int64_t>::max();
+  const std::vector<int64_t> h_off = host_offsets(cfg);
   Tiling tm, tl;
   if (!build_tiling(TILE_MAIN, ctx->n_c, ctx->W, L, h_off, &tm) ||
       !build_tiling(TILE_LB, ctx->n_c, ctx->W, L, h_off, &tl))

@@ -87,3 +87,78 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 txt = open(os.path.join(d, f)).read()
                 assert "obref" not in txt and "oracle" not in txt.lower().replace("oracle-free", ""), f
+
+
+def _expected_split(offsets, W, max_tiles):
+    """The split written out from its definition, element by element where it matters: an
+    8192-element tile (counted from the start of its chunk, clipped to the chunk) belongs to the
+    barrier kernel iff it lies inside one layer and that layer has between 1 and max_tiles such
+    tiles; a 1024-element span outside those tiles belongs to the plain kernels iff it holds a
+    parameter."""
+    import numpy as np
+    off = np.asarray(offsets, dtype=np.int64)
+    N, L = int(off[-1]), len(off) - 1
+    q = 256 * W
+    n_pad = max(((N + q - 1) // q) * q, q)
+    n_c = n_pad // W
+    layer_of = np.full(n_pad, L, dtype=np.int64)           # L = padding
+    for l in range(L):
+        layer_of[off[l]:off[l + 1]] = l
+    tiles = {}                                             # layer -> [(start, end)]
+    for c in range(W):
+        for a in range(c * n_c, (c + 1) * n_c, 8192):
+            b = min(a + 8192, (c + 1) * n_c)
+            l = int(layer_of[a])
+            if l < L and np.all(layer_of[a:b] == l):
+                tiles.setdefault(l, []).append((a, b))
+    listed = np.zeros(L, dtype=np.int32)
+    in_barrier = np.zeros(n_pad, dtype=bool)
+    for l, ts in tiles.items():
+        if 0 < len(ts) <= max_tiles:
+            listed[l] = len(ts)
+            for a, b in ts:
+                in_barrier[a:b] = True
+    owner = []
+    for c in range(W):
+        for a in range(c * n_c, (c + 1) * n_c, 1024):
+            b = min(a + 1024, (c + 1) * n_c)
+            if in_barrier[a]:
+                assert in_barrier[a:b].all()
+                owner.append(2)
+            else:
+                assert not in_barrier[a:b].any()
+                owner.append(1 if (layer_of[a:b] < L).any() else 0)
+    return np.array(owner, dtype=np.uint8), listed
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_split_between_barrier_and_plain_kernels(ob, seed):
+    """The host's planning of which tiles the kernels with a per-layer barrier take (no device
+    needed) against the definition, on random tensor lists with empty, tiny, tile-sized,
+    tile-aligned and ragged tensors."""
+    import numpy as np
+    r = np.random.default_rng(seed)
+    kinds = [0, 1, 2, 3, 255, 256, 1023, 1024, 1025, 4096, 8191, 8192, 8193, 16384, 24576, 40000, 65536, 100000]
+    sizes = [int(r.choice(kinds)) for _ in range(int(r.integers(2, 16)))] + [int(r.integers(1, 5000))]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    W = int(r.choice([1, 2, 3, 4, 5, 8, 16]))
+    max_tiles = int(r.choice([0, 1, 2, 3, 5, 1000]))
+    owner, listed = ob.ob_lamb_plan_split(offsets, W, max_tiles)
+    want_owner, want_listed = _expected_split(offsets, W, max_tiles)
+    assert np.array_equal(listed, want_listed), (sizes, W, max_tiles)
+    assert np.array_equal(owner, want_owner), (sizes, W, max_tiles)
+    if max_tiles == 0:
+        assert not (owner == 2).any()
+
+
+def test_plan_split_rejects_bad_arguments(ob):
+    import numpy as np
+    lib = ob.lib()
+    offs = (C.c_int64 * 3)(0, 5000, 20000)
+    cfg = ob.ObLambConfig(2, offs, 2, 0, 0.9, 0.999, 0.9, 1e-6, 0.01, 0.3, 0.5, 4.0, 0.1, 0.0)
+    owner = np.zeros(64, dtype=np.uint8)
+    listed = np.zeros(2, dtype=np.int32)
+    assert lib.ob_lamb_plan_split(None, 1, owner.ctypes.data, listed.ctypes.data) == -1
+    assert lib.ob_lamb_plan_split(C.byref(cfg), 1, None, listed.ctypes.data) == -1
+    assert lib.ob_lamb_plan_split(C.byref(cfg), -1, owner.ctypes.data, listed.ctypes.data) == -2
+    assert lib.ob_lamb_plan_split(C.byref(cfg), 1, owner.ctypes.data, listed.ctypes.data) == 0
