@@ -162,3 +162,32 @@ def test_plan_split_rejects_bad_arguments(ob):
     assert lib.ob_lamb_plan_split(C.byref(cfg), 1, None, listed.ctypes.data) == -1
     assert lib.ob_lamb_plan_split(C.byref(cfg), -1, owner.ctypes.data, listed.ctypes.data) == -2
     assert lib.ob_lamb_plan_split(C.byref(cfg), 1, owner.ctypes.data, listed.ctypes.data) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share; asked for more it says so and exits without touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The package and bench.py's timed path never load anything from oracle/ (only the tests, the
+    smoke check and the cpu_baseline leg may)."""
+    import re as _re
+    pkg = os.path.join(ROOT, "paper_2104_06069_amd")
+    for fn in os.listdir(pkg):
+        if fn.endswith(".py"):
+            src = open(os.path.join(pkg, fn)).read()
+            assert not _re.search(r"^\s*(from|import)\s+oracle\b", src, flags=_re.M), fn
+    for d, _, files in os.walk(os.path.join(pkg, "csrc")):
+        for fn in files:
+            assert "obref" not in open(os.path.join(d, fn)).read(), fn
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    # in bench.py the oracle is reachable from cpu_baseline() only
+    head, _, tail = bench.partition("def cpu_baseline(")
+    assert not _re.search(r"^\s*(from|import)\s+(oracle|tests)\b", head, flags=_re.M), "oracle imported outside cpu_baseline"
+    assert _re.search(r"^\s*from\s+tests\.refstep\s+import", "def cpu_baseline(" + tail, flags=_re.M)
