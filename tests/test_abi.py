@@ -191,3 +191,12 @@ def test_product_path_does_not_import_the_oracle():
     head, _, tail = bench.partition("def cpu_baseline(")
     assert not _re.search(r"^\s*(from|import)\s+(oracle|tests)\b", head, flags=_re.M), "oracle imported outside cpu_baseline"
     assert _re.search(r"^\s*from\s+tests\.refstep\s+import", "def cpu_baseline(" + tail, flags=_re.M)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """No fallback: without the built shared library the binding raises instead of computing anything."""
+    import paper_2104_06069_amd.binding as b
+    monkeypatch.setattr(b, "_LIB", None)
+    monkeypatch.setattr(b, "lib_path", lambda: "/nonexistent/libonebitlamb.so")
+    with pytest.raises(ImportError):
+        b.ob_lamb_padded_len_for(10, 2)
