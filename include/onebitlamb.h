@@ -76,7 +76,28 @@ typedef struct ob_lamb_config {
   float r_min, r_max;           /* Algorithm 1 line 19 */
   float r_threshold;            /* Algorithm 1 line 18 */
   float weight_decay;           /* warmup only: u += wd * x; 0 = eq. (1) as printed */
+  /* Kernel selection (all results are the same whatever is selected; 0 everywhere = the library's
+   * own choice for the device).  Per context: two contexts in one process may differ. */
+  uint32_t flags;               /* OB_CFG_* bits */
+  int32_t fused_max_tiles;      /* > 0: the kernels with a per-layer barrier leave every layer with more
+                                   than this many 8192-element tiles to the plain kernels, even if
+                                   the device could hold more; 0 = the device's limit */
+  int32_t spin_limit;           /* bound, in polls, of every device-side wait: 0 = the default
+                                   (OB_SPIN_LIMIT_DEFAULT); > 0 = that many, at most the default;
+                                   OB_SPIN_NONE = give up without polling (exists so that the expiry
+                                   path can be tested without ever hanging a kernel) */
 } ob_lamb_config;
+
+/* ob_lamb_config.flags */
+#define OB_CFG_TWO_PASS_COMPRESS 1u   /* ob_lamb_compress_local as two passes through memory and
+                                         ob_lamb_server_reduce as three kernels: no chunk barrier */
+#define OB_CFG_NO_FUSED_APPLY 2u      /* ob_lamb_ratios_apply runs the two plain kernels for every layer */
+#define OB_CFG_TWO_PASS_WARMUP 4u     /* ob_lamb_warmup_step takes two passes for every layer */
+#define OB_CFG_NO_BARRIERS (OB_CFG_TWO_PASS_COMPRESS | OB_CFG_NO_FUSED_APPLY | OB_CFG_TWO_PASS_WARMUP)
+#define OB_SPIN_NONE (-1)
+/* A poll is one 8-byte load plus a sleep of 1024 clocks; at the 2.4 GHz the device runs at, the
+ * default bounds a wait at 2^20 polls = about 0.5 s (about 1 s at the lowest power state's clock). */
+#define OB_SPIN_LIMIT_DEFAULT (1 << 20)
 
 /* Device pointers, caller-owned, fp32.  N-sized arrays have N_pad elements. */
 typedef struct ob_lamb_state {
@@ -182,9 +203,9 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * those tiles in registers across a per-layer barrier, so they are read once instead of twice
  * (4.125 bytes per parameter less); everything outside those tiles (larger layers, small tensors,
  * the spans where layers meet) takes the two kernels, restricted to it.  Waits are bounded as for
- * ob_lamb_compress_local (ob_lamb_check_device_status).  OB_LAMB_NO_FUSED_APPLY=1 at
- * ob_lamb_create forces the two-kernel path for everything, OB_LAMB_FUSED_MAX_TILES=n for every
- * layer with more than n such tiles. */
+ * ob_lamb_compress_local (ob_lamb_check_device_status).  OB_CFG_NO_FUSED_APPLY in
+ * ob_lamb_config.flags forces the two-kernel path for everything, ob_lamb_config.fused_max_tiles = n
+ * for every layer with more than n such tiles. */
 ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, float lr, void* hip_stream);
 /* Host-only planning query (no HIP call, no device needed): how ob_lamb_create splits a tensor list
@@ -205,7 +226,7 @@ int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx);
 /* The same two counts for ob_lamb_warmup_step, which reads g, m, v and x once (one kernel with a
  * per-layer barrier that keeps eq. (1)'s update direction and x in registers while the layer's
  * norms complete) for every layer whose tiles fit on the device, and takes two passes for the
- * rest.  OB_LAMB_TWO_PASS_WARMUP=1 at ob_lamb_create forces two passes for every layer. */
+ * rest.  OB_CFG_TWO_PASS_WARMUP in ob_lamb_config.flags forces two passes for every layer. */
 int64_t ob_lamb_warmup_fused_layers(const ob_lamb_ctx* ctx);
 int64_t ob_lamb_warmup_fused_params(const ob_lamb_ctx* ctx);
 
@@ -246,26 +267,52 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                   const uint32_t* packed_all, const float* server_scales, float lr,
                                   void* x_lp, ob_dtype x_dtype, void* hip_stream);
 
-/* ob_lamb_compress_local runs as ONE kernel that keeps z in registers across a per-chunk arrival
- * barrier whenever one chunk's workgroups fill at most 80 % of the device (otherwise, or when the
- * environment variable OB_LAMB_TWO_PASS=1 is set at ob_lamb_create, as two passes through memory;
- * the results are bit-identical).  The barrier's waits are bounded; should one ever expire, the
- * step's outputs are undefined and a device-side flag is raised.  ob_lamb_check_device_status
- * synchronises `hip_stream`, reads that flag and returns OB_OK, or OB_ERR_STATE after re-arming
- * the context to use the two-pass kernels from then on.  Call it whenever you synchronise anyway
- * (e.g. once per logging interval).  ob_lamb_uses_single_pass reports the current choice (1/0).
- * The single-pass kernels (this one and those of ob_lamb_ratios_apply and ob_lamb_warmup_step) count
- * on having the device to themselves while they run: kernels of other streams or processes that
- * keep more than a fifth of the compute units busy for seconds on end can make a wait expire,
- * which is reported as above; shorter interference only slows them down.
- * OB_LAMB_SPIN_LIMIT=n at ob_lamb_create lowers the bound of the waits (0: give up without polling);
- * it exists so that this path can be tested without ever hanging a kernel. */
+/* Kernels with an in-kernel barrier, and what happens if one of their waits expires
+ * -----------------------------------------------------------------------------------
+ * ob_lamb_compress_local runs as ONE kernel that keeps z in registers across a per-chunk arrival
+ * barrier whenever one chunk's workgroups fill at most 80 % of the device (otherwise, or with
+ * OB_CFG_TWO_PASS_COMPRESS, as two passes through memory).  ob_lamb_server_reduce,
+ * ob_lamb_ratios_apply and ob_lamb_warmup_step have such a form too (per chunk / per layer).  All
+ * forms compute the same operations in the same order per element; the two sum-of-squares
+ * reductions add the same fp64 terms grouped by different tile sizes, so a scale or norm can differ
+ * in its last binary32 bit between forms (about once in 10^8 reductions) -- within the 1e-6 bar,
+ * and the sign words that depend on such a scale can then differ for elements within one unit in
+ * the last place of zero.
+ *
+ * Progress of a barrier rests on two things the HIP programming model does not promise but the
+ * hardware's dispatcher provides: workgroups start in index order, and a chunk's (layer's)
+ * workgroups are all resident at once -- the host checks the second against the kernel's occupancy
+ * on the device and keeps a 20 % margin.  The barrier kernels count on having the device to
+ * themselves while they run: kernels of other streams or processes that keep more than a fifth of
+ * the compute units busy for seconds on end can make a wait expire; shorter interference only slows
+ * them down.  Every wait is bounded by ob_lamb_config.spin_limit polls (one 8-byte atomic load,
+ * whose round trip to the memory side is of the order of a microsecond, plus a sleep of 1024
+ * clocks = 0.43 us at 2.4 GHz): with the default of 2^20 polls a wait lasts 1.5 s at most (3 s at
+ * half the clock), and once one wait has expired every other wait of the context ends within 64
+ * polls, so a kernel in which a wait expires still ends about 2 s after its last workgroup started.
+ *
+ * An expired wait does NOT stop the kernel: the workgroup goes on with whatever the flag word last
+ * held (a stale scale or coefficient), raises a device-side flag, and the step's outputs are
+ * undefined.  The buffers updated in place are then corrupt and must be restored from a copy that
+ * the CALLER holds -- the library keeps none:
+ *   ob_lamb_compress_local   err_worker (and packed_out, scales_out)
+ *   ob_lamb_server_reduce    err_server (and packed_out, scale_out)
+ *   ob_lamb_ratios_apply     x, v_fresh, r_prev, coeff_c
+ *   ob_lamb_warmup_step      x, m, v_fresh, c_avg, coeff_c
+ * No step call returns OB_ERR_STATE by itself (none of them synchronises).  The caller learns of an
+ * expiry from ob_lamb_check_device_status, which synchronises `hip_stream`, reads the flag and
+ * returns OB_OK, or OB_ERR_STATE after re-arming the context to use the barrier-free kernels from
+ * then on.  Call it at every point where the state is about to become irreplaceable -- before a
+ * checkpoint is written, before the previous checkpoint is dropped, and at a fixed interval of steps
+ * (it costs one stream synchronisation); on OB_ERR_STATE restore x, m, v_fresh, err_worker,
+ * err_server, c_avg, r_prev from the last checkpoint taken after an OB_OK and redo the steps.
+ * ob_lamb_uses_single_pass reports the current choice for ob_lamb_compress_local (1/0). */
 ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream);
 int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx);
 /* ob_lamb_server_reduce as one kernel with a chunk barrier (the averaged chunk stays in registers
  * between Algorithm 1 line 10's sum and its recompression): 0 if the three-kernel form is used (the
- * served chunk's workgroups do not fit on the device at once, OB_LAMB_TWO_PASS=1, or after an
- * expired wait), else the kernel's tile size in units of 1024 elements (1, 2 or 4). */
+ * served chunk's workgroups do not fit on the device at once, OB_CFG_TWO_PASS_COMPRESS, or after
+ * an expired wait), else the kernel's tile size in units of 1024 elements (1, 2 or 4). */
 int32_t ob_lamb_server_single_pass(const ob_lamb_ctx* ctx);
 
 /* ---- per-kernel timing (diagnostics; used by the benchmark) ----

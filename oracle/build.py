@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "obref.cpp")
 LIB = os.path.join(HERE, "libobref.so")
 FLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-         "-Wall", "-Wextra"]
+         "-pthread", "-Wall", "-Wextra"]
 
 
 def build(force=True):

@@ -1,12 +1,15 @@
 // obref -- CPU oracle for the 1-bit LAMB compression-stage step.  Test infrastructure only:
 // see obref.h for what may load it and for the list of readings it fixes.
 //
-// Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC obref.cpp -o libobref.so
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC -pthread obref.cpp -o libobref.so
 // Every loop below is scalar and in the order the paper states the step; T is float for the
 // oracle proper and double for the shadow the algebraic pins use.
 #include "obref.h"
 
+#include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <thread>
 #include <vector>
 
 namespace {
@@ -68,12 +71,13 @@ void compress_local(int64_t n_pad, int64_t L, const int64_t* off, int32_t W, con
     compress_chunk<T>(err + c * n_c, n_c, bits + c * (n_c / 8), scales + c, err + c * n_c);
 }
 
-// Algorithm 1 line 10 on one chunk.
+// Algorithm 1 line 10 on one chunk, first half: the average of the W decompressed chunks plus the
+// carried server error, for elements [j0, j1) (each element is independent of the others).
 template <class T>
-void server_reduce(int64_t n_c, int32_t W, const uint8_t* bits_in, const T* scales_in,
-                   T* err_server, uint8_t* bits_out, T* scale_out) {
+void server_average(int64_t n_c, int32_t W, const uint8_t* bits_in, const T* scales_in,
+                    T* err_server, int64_t j0, int64_t j1) {
   const T invW = (T)1 / (T)W;
-  for (int64_t j = 0; j < n_c; ++j) {
+  for (int64_t j = j0; j < j1; ++j) {
     T acc = (T)0;
     for (int32_t w = 0; w < W; ++w) {
       const T s = scales_in[w];
@@ -81,21 +85,35 @@ void server_reduce(int64_t n_c, int32_t W, const uint8_t* bits_in, const T* scal
     }
     err_server[j] = acc * invW + err_server[j];
   }
+}
+
+// Algorithm 1 line 10 on one chunk.
+template <class T>
+void server_reduce(int64_t n_c, int32_t W, const uint8_t* bits_in, const T* scales_in,
+                   T* err_server, uint8_t* bits_out, T* scale_out) {
+  server_average<T>(n_c, W, bits_in, scales_in, err_server, 0, n_c);
   compress_chunk<T>(err_server, n_c, bits_out, scale_out, err_server);
 }
 
-// Algorithm 1 line 13 (+ A.5.2: divide the global momentum by the layer's coefficient).
+// Algorithm 1 line 13 (+ A.5.2: divide the global momentum by the layer's coefficient), layers
+// [l0, l1) (each element is independent of the others).
 template <class T>
-void global_momentum(int64_t n_pad, int64_t L, const int64_t* off, int32_t W, const T* mom_scale,
-                     const uint8_t* bits_all, const T* server_scales, T* mt) {
-  const int64_t n_c = n_pad / W;
-  for (int64_t l = 0; l < L; ++l) {
+void global_momentum_layers(int64_t n_c, const int64_t* off, int64_t l0, int64_t l1,
+                            const T* mom_scale, const uint8_t* bits_all, const T* server_scales,
+                            T* mt) {
+  for (int64_t l = l0; l < l1; ++l) {
     for (int64_t i = off[l]; i < off[l + 1]; ++i) {
       const T s = server_scales[i / n_c];
       const T d = get_bit(bits_all, i) ? s : -s;
       mt[i] = mom_scale ? d / mom_scale[l] : d;
     }
   }
+}
+
+template <class T>
+void global_momentum(int64_t n_pad, int64_t L, const int64_t* off, int32_t W, const T* mom_scale,
+                     const uint8_t* bits_all, const T* server_scales, T* mt) {
+  global_momentum_layers<T>(n_pad / W, off, 0, L, mom_scale, bits_all, server_scales, mt);
   for (int64_t i = off[L]; i < n_pad; ++i) mt[i] = (T)0;
 }
 
@@ -277,24 +295,37 @@ void obref64_warmup_step(int64_t L, const int64_t* off, double beta1, double bet
                       c_out, c_avg);
 }
 
-void obref_momentum_scale(int64_t L, const int64_t* off, const float* m, float* mom_scale) {
-  std::vector<double> sigma((size_t)L, 0.0);
+namespace {
+// A.5.2 (reading): sigma_l = ||m_l||_2 / sqrt(n_l), 0 for an empty layer.
+double layer_sigma(const int64_t* off, int64_t l, const float* m) {
+  const int64_t n = off[l + 1] - off[l];
+  if (n <= 0) return 0.0;
+  double S = 0.0;
+  for (int64_t i = off[l]; i < off[l + 1]; ++i) S += (double)m[i] * (double)m[i];
+  return std::sqrt(S / (double)n);
+}
+
+// k_l = mean(sigma over the non-empty layers, in layer order) / sigma_l; 1 where sigma_l == 0.
+void momentum_scale_from_sigma(int64_t L, const int64_t* off, const double* sigma, float* mom_scale) {
   double sum = 0.0;
   int64_t cnt = 0;
   for (int64_t l = 0; l < L; ++l) {
-    const int64_t n = off[l + 1] - off[l];
-    if (n <= 0) continue;
-    double S = 0.0;
-    for (int64_t i = off[l]; i < off[l + 1]; ++i) S += (double)m[i] * (double)m[i];
-    sigma[(size_t)l] = std::sqrt(S / (double)n);
-    sum += sigma[(size_t)l];
+    if (off[l + 1] - off[l] <= 0) continue;
+    sum += sigma[l];
     ++cnt;
   }
   const double mean = cnt ? sum / (double)cnt : 0.0;
   for (int64_t l = 0; l < L; ++l) {
-    const double s = sigma[(size_t)l];
+    const double s = sigma[l];
     mom_scale[l] = (s > 0.0) ? (float)(mean / s) : 1.0f;
   }
+}
+}  // namespace
+
+void obref_momentum_scale(int64_t L, const int64_t* off, const float* m, float* mom_scale) {
+  std::vector<double> sigma((size_t)L, 0.0);
+  for (int64_t l = 0; l < L; ++l) sigma[(size_t)l] = layer_sigma(off, l, m);
+  momentum_scale_from_sigma(L, off, sigma.data(), mom_scale);
 }
 
 namespace {
@@ -346,6 +377,130 @@ void obref_lp_decode(int32_t fmt, int64_t n, const uint16_t* bits, float scale, 
 
 void obref_lp_round(int32_t fmt, int64_t n, const float* x, uint16_t* bits) {
   for (int64_t i = 0; i < n; ++i) bits[i] = lp_nearest(fmt, x[i]);
+}
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// Multi-threaded drivers.  They hold no arithmetic: each cuts the problem into independent pieces
+// (chunks, layers, element ranges of an elementwise loop), runs the scalar routines above on the
+// pieces from a pool of std::threads and leaves every output element to exactly one piece, so the
+// results equal the serial entry points' bit for bit (tests pin that).  The pieces:
+//   compress_local   one call of compress_local<float> per chunk, on the sub-problem "this chunk
+//                    alone" (offsets clipped to the chunk; A.7.1: chunks are independent)
+//   server_reduce    server_average<float> on element ranges, then compress_chunk<float> once
+//   layer_ratios, decompress_apply, warmup_step   one layer at a time (lines 15-21 and eq. (1)
+//                    are per layer), largest layers first
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+template <class F>
+void run_pieces(int64_t n, int threads, F f) {
+  if (threads > n) threads = (int)n;
+  if (threads <= 1) {
+    for (int64_t i = 0; i < n; ++i) f(i);
+    return;
+  }
+  std::atomic<int64_t> next{0};
+  auto work = [&] {
+    for (;;) {
+      const int64_t i = next.fetch_add(1);
+      if (i >= n) break;
+      f(i);
+    }
+  };
+  std::vector<std::thread> pool;
+  for (int t = 1; t < threads; ++t) pool.emplace_back(work);
+  work();
+  for (auto& th : pool) th.join();
+}
+
+// layer indices, largest layer first (ties: lower index first)
+std::vector<int64_t> layers_by_size(int64_t L, const int64_t* off) {
+  std::vector<int64_t> idx((size_t)L);
+  for (int64_t l = 0; l < L; ++l) idx[(size_t)l] = l;
+  std::stable_sort(idx.begin(), idx.end(), [&](int64_t a, int64_t b) {
+    return off[a + 1] - off[a] > off[b + 1] - off[b];
+  });
+  return idx;
+}
+
+}  // namespace
+
+extern "C" {
+
+void obref_compress_local_mt(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                             const float* mom_scale, float beta1, const float* g, const float* m,
+                             float* err, uint8_t* bits, float* scales, int32_t threads) {
+  const int64_t n_c = n_pad / W;
+  run_pieces(W, threads, [&](int64_t c) {
+    const int64_t a = c * n_c, b = a + n_c;
+    std::vector<int64_t> oc((size_t)L + 1);   // the layers as seen from inside chunk c
+    for (int64_t l = 0; l <= L; ++l) oc[(size_t)l] = std::min(std::max(off[l], a), b) - a;
+    compress_local<float>(n_c, L, oc.data(), 1, mom_scale, beta1, g + a, m + a, err + a,
+                          bits + a / 8, scales + c);
+  });
+}
+
+void obref_server_reduce_mt(int64_t n_c, int32_t W, const uint8_t* bits_in, const float* scales_in,
+                            float* err_server, uint8_t* bits_out, float* scale_out, int32_t threads) {
+  const int64_t piece = 1 << 16;
+  const int64_t n = (n_c + piece - 1) / piece;
+  run_pieces(n, threads, [&](int64_t p) {
+    server_average<float>(n_c, W, bits_in, scales_in, err_server, p * piece,
+                          std::min((p + 1) * piece, n_c));
+  });
+  compress_chunk<float>(err_server, n_c, bits_out, scale_out, err_server);
+}
+
+void obref_layer_ratios_mt(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                           const float* mom_scale, float beta1, float beta2, float r_min, float r_max,
+                           float r_thr, const uint8_t* bits_all, const float* server_scales,
+                           const float* m, float* v_fresh, const float* v_frozen, const float* c_avg,
+                           float* r_prev, float* coeff_c, int32_t threads) {
+  std::vector<float> mt((size_t)n_pad);
+  const std::vector<int64_t> order = layers_by_size(L, off);
+  run_pieces(L, threads, [&](int64_t k) {
+    const int64_t l = order[(size_t)k];
+    global_momentum_layers<float>(n_pad / W, off, l, l + 1, mom_scale, bits_all, server_scales, mt.data());
+    ratios_dense<float>(1, off + l, beta1, beta2, r_min, r_max, r_thr, mt.data(), m, v_fresh, v_frozen,
+                        c_avg + l, r_prev + l, coeff_c + l);
+  });
+}
+
+void obref_decompress_apply_mt(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                               const float* mom_scale, float eta, float lr, const uint8_t* bits_all,
+                               const float* server_scales, const float* coeff_c, const float* v_frozen,
+                               float* x, float* m, int32_t threads) {
+  std::vector<float> mt((size_t)n_pad);
+  const std::vector<int64_t> order = layers_by_size(L, off);
+  run_pieces(L, threads, [&](int64_t k) {
+    const int64_t l = order[(size_t)k];
+    global_momentum_layers<float>(n_pad / W, off, l, l + 1, mom_scale, bits_all, server_scales, mt.data());
+    apply_dense<float>(1, off + l, eta, lr, mt.data(), coeff_c + l, v_frozen, x, m);
+  });
+}
+
+void obref_warmup_step_mt(int64_t L, const int64_t* off, float beta1, float beta2, float beta3,
+                          float eta, float c_min, float c_max, float weight_decay, float lr,
+                          const float* g, float* m, float* v, float* x, float* c_out, float* c_avg,
+                          int32_t threads) {
+  const std::vector<int64_t> order = layers_by_size(L, off);
+  run_pieces(L, threads, [&](int64_t k) {
+    const int64_t l = order[(size_t)k];
+    warmup_step<float>(1, off + l, beta1, beta2, beta3, eta, c_min, c_max, weight_decay, lr, g, m, v,
+                       x, c_out + l, c_avg + l);
+  });
+}
+
+void obref_momentum_scale_mt(int64_t L, const int64_t* off, const float* m, float* mom_scale,
+                             int32_t threads) {
+  std::vector<double> sigma((size_t)L, 0.0);
+  const std::vector<int64_t> order = layers_by_size(L, off);
+  run_pieces(L, threads, [&](int64_t k) {
+    const int64_t l = order[(size_t)k];
+    sigma[(size_t)l] = layer_sigma(off, l, m);
+  });
+  momentum_scale_from_sigma(L, off, sigma.data(), mom_scale);
 }
 
 }  // extern "C"

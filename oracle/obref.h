@@ -147,6 +147,37 @@ void obref_momentum_scale(int64_t L, const int64_t* off, const float* m, float* 
 void obref_lp_decode(int32_t fmt, int64_t n, const uint16_t* bits, float scale, float* out);
 void obref_lp_round(int32_t fmt, int64_t n, const float* x, uint16_t* bits);
 
+/* ---- multi-threaded drivers of the float routines above (`threads` >= 1 worker threads) ----
+ * No arithmetic of their own: the problem is cut into independent pieces -- chunks for
+ * obref_compress_local (A.7.1: each chunk is its own parameter-server instance), element ranges of
+ * the averaging loop for obref_server_reduce, layers for the per-layer routines -- and the scalar
+ * routines run on the pieces in parallel.  Every output element is produced by the same operations
+ * in the same order as in the serial entry point: results are bit-identical (pinned by a test).
+ * They exist so that whole trajectories at the benchmark sizes finish in seconds; the serial
+ * entry points remain the definition. */
+void obref_compress_local_mt(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                             const float* mom_scale, float beta1, const float* g, const float* m,
+                             float* err, uint8_t* bits, float* scales, int32_t threads);
+void obref_server_reduce_mt(int64_t n_c, int32_t W, const uint8_t* bits_in, const float* scales_in,
+                            float* err_server, uint8_t* bits_out, float* scale_out, int32_t threads);
+void obref_layer_ratios_mt(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                           const float* mom_scale, float beta1, float beta2,
+                           float r_min, float r_max, float r_thr,
+                           const uint8_t* bits_all, const float* server_scales,
+                           const float* m, float* v_fresh, const float* v_frozen,
+                           const float* c_avg, float* r_prev, float* coeff_c, int32_t threads);
+void obref_decompress_apply_mt(int64_t n_pad, int64_t L, const int64_t* off, int32_t W,
+                               const float* mom_scale, float eta, float lr,
+                               const uint8_t* bits_all, const float* server_scales,
+                               const float* coeff_c, const float* v_frozen, float* x, float* m,
+                               int32_t threads);
+void obref_warmup_step_mt(int64_t L, const int64_t* off, float beta1, float beta2, float beta3,
+                          float eta, float c_min, float c_max, float weight_decay, float lr,
+                          const float* g, float* m, float* v, float* x, float* c_out, float* c_avg,
+                          int32_t threads);
+void obref_momentum_scale_mt(int64_t L, const int64_t* off, const float* m, float* mom_scale,
+                             int32_t threads);
+
 #ifdef __cplusplus
 }
 #endif

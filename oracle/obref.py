@@ -64,11 +64,27 @@ def lp_round(fmt, x):
     return out
 
 
-class Ref:
-    """The oracle in one precision.  All methods update their array arguments in place."""
+def default_threads():
+    """Worker threads for the multi-threaded drivers: the host's cores, capped by OMP_NUM_THREADS
+    (set to the job's CPU share on shared machines) and by 16."""
+    n = os.cpu_count() or 1
+    try:
+        n = min(n, int(os.environ.get("OMP_NUM_THREADS", n)))
+    except ValueError:
+        pass
+    return max(1, min(n, 16))
 
-    def __init__(self, dtype=np.float32):
+
+class Ref:
+    """The oracle in one precision.  All methods update their array arguments in place.
+    threads > 1 (binary32 only) routes the N-sized calls through the multi-threaded drivers, whose
+    results are bit-identical to the serial routines'."""
+
+    def __init__(self, dtype=np.float32, threads=1):
         self.dt = np.dtype(dtype)
+        self.threads = int(threads)
+        if self.threads > 1 and self.dt != np.float32:
+            raise TypeError("the multi-threaded drivers are binary32 only")
         if self.dt == np.float32:
             self.pre, self.ct = "obref_", C.c_float
         elif self.dt == np.float64:
@@ -113,9 +129,12 @@ class Ref:
         _chk(mom_scale, self.dt, L, "mom_scale")
         bits = np.empty(n_pad // 8, dtype=np.uint8)
         scales = np.empty(W, dtype=self.dt)
-        self._f("compress_local")(C.c_int64(n_pad), C.c_int64(L), _p(off), C.c_int32(W),
-                                  _p(mom_scale), self.ct(float(beta1)), _p(g), _p(m), _p(err),
-                                  _p(bits), _p(scales))
+        args = (C.c_int64(n_pad), C.c_int64(L), _p(off), C.c_int32(W), _p(mom_scale),
+                self.ct(float(beta1)), _p(g), _p(m), _p(err), _p(bits), _p(scales))
+        if self.threads > 1:
+            self.l.obref_compress_local_mt(*args, C.c_int32(self.threads))
+        else:
+            self._f("compress_local")(*args)
         return bits, scales
 
     def server_reduce(self, W, bits_in, scales_in, err_server):
@@ -127,8 +146,12 @@ class Ref:
         _chk(err_server, self.dt)
         bits_out = np.empty(n_c // 8, dtype=np.uint8)
         s = self.ct(0)
-        self._f("server_reduce")(C.c_int64(n_c), C.c_int32(W), _p(bits_in), _p(scales_in),
-                                 _p(err_server), _p(bits_out), C.byref(s))
+        args = (C.c_int64(n_c), C.c_int32(W), _p(bits_in), _p(scales_in), _p(err_server),
+                _p(bits_out), C.byref(s))
+        if self.threads > 1:
+            self.l.obref_server_reduce_mt(*args, C.c_int32(self.threads))
+        else:
+            self._f("server_reduce")(*args)
         return bits_out, self.dt.type(s.value)
 
     def global_momentum(self, off, W, mom_scale, bits_all, server_scales, n_pad):
@@ -183,11 +206,13 @@ class Ref:
         _chk(r_prev, self.dt, L)
         coeff = np.empty(L, dtype=self.dt)
         t = self.ct
-        self.l.obref_layer_ratios(C.c_int64(n_pad), C.c_int64(L), _p(off), C.c_int32(W),
-                                  _p(mom_scale), t(float(beta1)), t(float(beta2)), t(float(r_min)),
-                                  t(float(r_max)), t(float(r_thr)), _p(bits_all),
-                                  _p(server_scales), _p(m), _p(v_fresh), _p(v_frozen), _p(c_avg),
-                                  _p(r_prev), _p(coeff))
+        args = (C.c_int64(n_pad), C.c_int64(L), _p(off), C.c_int32(W), _p(mom_scale), t(float(beta1)),
+                t(float(beta2)), t(float(r_min)), t(float(r_max)), t(float(r_thr)), _p(bits_all),
+                _p(server_scales), _p(m), _p(v_fresh), _p(v_frozen), _p(c_avg), _p(r_prev), _p(coeff))
+        if self.threads > 1:
+            self.l.obref_layer_ratios_mt(*args, C.c_int32(self.threads))
+        else:
+            self.l.obref_layer_ratios(*args)
         return coeff
 
     def decompress_apply(self, off, W, mom_scale, eta, lr, bits_all, server_scales, coeff_c,
@@ -202,9 +227,12 @@ class Ref:
         _chk(mom_scale, self.dt, L)
         _chk(coeff_c, self.dt, L)
         t = self.ct
-        self.l.obref_decompress_apply(C.c_int64(n_pad), C.c_int64(L), _p(off), C.c_int32(W),
-                                      _p(mom_scale), t(float(eta)), t(float(lr)), _p(bits_all),
-                                      _p(server_scales), _p(coeff_c), _p(v_frozen), _p(x), _p(m))
+        args = (C.c_int64(n_pad), C.c_int64(L), _p(off), C.c_int32(W), _p(mom_scale), t(float(eta)),
+                t(float(lr)), _p(bits_all), _p(server_scales), _p(coeff_c), _p(v_frozen), _p(x), _p(m))
+        if self.threads > 1:
+            self.l.obref_decompress_apply_mt(*args, C.c_int32(self.threads))
+        else:
+            self.l.obref_decompress_apply(*args)
 
     def warmup_step(self, off, beta1, beta2, beta3, eta, c_min, c_max, wd, lr, g, m, v, x, c_avg):
         """m, v, x, c_avg updated in place. -> c[L]"""
@@ -216,10 +244,13 @@ class Ref:
         _chk(c_avg, self.dt, L)
         c = np.empty(L, dtype=self.dt)
         t = self.ct
-        self._f("warmup_step")(C.c_int64(L), _p(off), t(float(beta1)), t(float(beta2)),
-                               t(float(beta3)), t(float(eta)), t(float(c_min)), t(float(c_max)),
-                               t(float(wd)), t(float(lr)), _p(g), _p(m), _p(v), _p(x), _p(c),
-                               _p(c_avg))
+        args = (C.c_int64(L), _p(off), t(float(beta1)), t(float(beta2)), t(float(beta3)), t(float(eta)),
+                t(float(c_min)), t(float(c_max)), t(float(wd)), t(float(lr)), _p(g), _p(m), _p(v), _p(x),
+                _p(c), _p(c_avg))
+        if self.threads > 1:
+            self.l.obref_warmup_step_mt(*args, C.c_int32(self.threads))
+        else:
+            self._f("warmup_step")(*args)
         return c
 
     def momentum_scale(self, off, m):
@@ -227,5 +258,8 @@ class Ref:
         off, L = self._off(off)
         _chk(m, self.dt)
         k = np.empty(L, dtype=np.float32)
-        self.l.obref_momentum_scale(C.c_int64(L), _p(off), _p(m), _p(k))
+        if self.threads > 1:
+            self.l.obref_momentum_scale_mt(C.c_int64(L), _p(off), _p(m), _p(k), C.c_int32(self.threads))
+        else:
+            self.l.obref_momentum_scale(C.c_int64(L), _p(off), _p(m), _p(k))
         return k

@@ -27,7 +27,14 @@ class ObLambConfig(C.Structure):
                 ("beta1", C.c_float), ("beta2", C.c_float), ("beta3", C.c_float),
                 ("eta", C.c_float), ("c_min", C.c_float), ("c_max", C.c_float),
                 ("r_min", C.c_float), ("r_max", C.c_float), ("r_threshold", C.c_float),
-                ("weight_decay", C.c_float)]
+                ("weight_decay", C.c_float),
+                ("flags", C.c_uint32), ("fused_max_tiles", C.c_int32), ("spin_limit", C.c_int32)]
+
+
+# ob_lamb_config.flags / spin_limit
+OB_CFG_TWO_PASS_COMPRESS, OB_CFG_NO_FUSED_APPLY, OB_CFG_TWO_PASS_WARMUP = 1, 2, 4
+OB_CFG_NO_BARRIERS = 7
+OB_SPIN_NONE = -1
 
 
 class ObLambState(C.Structure):
@@ -123,12 +130,13 @@ def ob_lamb_padded_len_for(n, num_workers):
 
 def ob_lamb_create(layer_offsets, num_workers, server_chunk=0, beta1=0.9, beta2=0.999, beta3=0.9,
                    eta=1e-6, c_min=0.01, c_max=0.3, r_min=0.5, r_max=4.0, r_threshold=0.1,
-                   weight_decay=0.0):
+                   weight_decay=0.0, flags=0, fused_max_tiles=0, spin_limit=0):
     """-> opaque context handle (on the current HIP device)."""
     offs = [int(o) for o in layer_offsets]
     arr = (C.c_int64 * len(offs))(*offs)
     cfg = ObLambConfig(len(offs) - 1, arr, int(num_workers), int(server_chunk), beta1, beta2, beta3,
-                       eta, c_min, c_max, r_min, r_max, r_threshold, weight_decay)
+                       eta, c_min, c_max, r_min, r_max, r_threshold, weight_decay, int(flags),
+                       int(fused_max_tiles), int(spin_limit))
     out = C.c_void_p()
     st = lib().ob_lamb_create(C.byref(cfg), C.byref(out))
     if st != OB_OK:
@@ -142,7 +150,7 @@ def ob_lamb_plan_split(layer_offsets, num_workers, max_tiles):
     offs = [int(o) for o in layer_offsets]
     arr = (C.c_int64 * len(offs))(*offs)
     cfg = ObLambConfig(len(offs) - 1, arr, int(num_workers), 0, 0.9, 0.999, 0.9, 1e-6, 0.01, 0.3, 0.5, 4.0,
-                       0.1, 0.0)
+                       0.1, 0.0, 0, 0, 0)
     n_c = ob_lamb_padded_len_for(offs[-1], num_workers) // int(num_workers)
     owner = np.zeros(int(num_workers) * ((n_c + 1023) // 1024), dtype=np.uint8)
     listed = np.zeros(len(offs) - 1, dtype=np.int32)

@@ -159,7 +159,7 @@ struct ob_lamb_ctx {
   double* d_partials_srv_res = nullptr;        // [tpc_srv_res]
   unsigned long long* d_counter_srv = nullptr; // [CTR_STRIDE]
   unsigned long long* d_flag_srv = nullptr;    // [1]
-  int spin_limit = 1 << 20;
+  int spin_limit = OB_SPIN_LIMIT_DEFAULT;
   // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
   // tiling (TILE_LB; the segment arrays are those of the TILE_MAIN tiling) and, for each, the split
   // of the work between it and the plain kernels
@@ -457,14 +457,11 @@ ListedTiles listed_tiles(const ob_lamb_ctx* ctx, const LayerSplit& sp) {
 }
 
 // Largest number of one layer's tiles that a barrier kernel with `per_cu` resident workgroups per
-// CU may hold: 80 % of the device's slots.  OB_LAMB_FUSED_MAX_TILES=n lowers it (tests of the
-// split between the two paths).
-int64_t split_max_tiles(int per_cu, int cus) {
+// CU may hold: 80 % of the device's slots, or the configuration's fused_max_tiles if that is lower
+// (cap; 0 = none).
+int64_t split_max_tiles(int per_cu, int cus, int32_t cap) {
   int64_t max_tiles = (4 * (int64_t)per_cu * cus) / 5 - 8;
-  if (const char* mt = getenv("OB_LAMB_FUSED_MAX_TILES")) {
-    const long v = atol(mt);
-    if (v >= 0 && v < max_tiles) max_tiles = v;
-  }
+  if (cap > 0 && cap < max_tiles) max_tiles = cap;
   return max_tiles < 0 ? 0 : max_tiles;
 }
 
@@ -598,6 +595,8 @@ static ob_status check_config(const ob_lamb_config* cfg) {
   for (float f : fl)
     if (!std::isfinite(f)) return OB_ERR_ARG;
   if (cfg->c_min > cfg->c_max || cfg->r_min > cfg->r_max) return OB_ERR_ARG;
+  if ((cfg->flags & ~OB_CFG_NO_BARRIERS) != 0u || cfg->fused_max_tiles < 0 || cfg->spin_limit < OB_SPIN_NONE)
+    return OB_ERR_ARG;
   return OB_OK;
 }
 
@@ -709,14 +708,12 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
     // every instantiation is built for at least OB_RES_MINW workgroups per CU (its launch bounds); count
     // no more than that, whatever this one reaches
     const int64_t slots = (int64_t)std::min(per_cu, OB_RES_MINW) * cus;
-    // OB_LAMB_SPIN_LIMIT=n lowers the bound of the device-side waits (tests of the expiry path: with
-    // 0 every wait gives up without polling, all kernels still run to their end)
-    if (const char* sl = getenv("OB_LAMB_SPIN_LIMIT")) {
-      const long v = atol(sl);
-      if (v >= 0 && v < ctx->spin_limit) ctx->spin_limit = (int)v;
-    }
-    const char* env = getenv("OB_LAMB_TWO_PASS");
-    ctx->resident = ok && !(env && env[0] == '1') && 5 * (tpc_res + 8) <= 4 * slots;
+    // a lower bound of the device-side waits (tests of the expiry path: with OB_SPIN_NONE every wait
+    // gives up without polling, all kernels still run to their end)
+    if (cfg->spin_limit == OB_SPIN_NONE) ctx->spin_limit = 0;
+    else if (cfg->spin_limit > 0 && cfg->spin_limit < ctx->spin_limit) ctx->spin_limit = cfg->spin_limit;
+    const bool two_pass = (cfg->flags & OB_CFG_TWO_PASS_COMPRESS) != 0;
+    ctx->resident = ok && !two_pass && 5 * (tpc_res + 8) <= 4 * slots;
     // the single-pass server kernel: same rule for the one chunk it covers
     int per_cu_s[3] = {0, 0, 0};
     ok = ok &&
@@ -728,7 +725,7 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor");
     // the tile table of the chunk's partials is sized for the smallest tile
     ctx->tpc_srv_res = (int)((ctx->n_c + SPAN - 1) / SPAN);
-    for (int i = 0; ok && i < 3 && ctx->u_srv_res == 0 && !(env && env[0] == '1'); ++i) {
+    for (int i = 0; ok && i < 3 && ctx->u_srv_res == 0 && !two_pass; ++i) {
       const int64_t tiles = (ctx->n_c + (int64_t)SPAN * U_SRV_RES[i] - 1) / ((int64_t)SPAN * U_SRV_RES[i]);
       if (5 * (tiles + 8) <= 4 * (int64_t)per_cu_s[i] * cus) ctx->u_srv_res = U_SRV_RES[i];
     }
@@ -745,10 +742,10 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
-    const char* ea = getenv("OB_LAMB_NO_FUSED_APPLY");
-    const char* ew = getenv("OB_LAMB_TWO_PASS_WARMUP");
-    const int64_t max_a = (ea && ea[0] == '1') ? 0 : split_max_tiles(std::min(per_cu_a, OB_LB_MINW), cus);
-    const int64_t max_w = (ew && ew[0] == '1') ? 0 : split_max_tiles(std::min(per_cu_w, OB_WU_MINW), cus);
+    const int64_t max_a = (cfg->flags & OB_CFG_NO_FUSED_APPLY)
+                              ? 0 : split_max_tiles(std::min(per_cu_a, OB_LB_MINW), cus, cfg->fused_max_tiles);
+    const int64_t max_w = (cfg->flags & OB_CFG_TWO_PASS_WARMUP)
+                              ? 0 : split_max_tiles(std::min(per_cu_w, OB_WU_MINW), cus, cfg->fused_max_tiles);
     ok = ok && build_split(ctx, tl, tm, h_off, max_a, &ctx->sp_apply) &&
          build_split(ctx, tl, tm, h_off, max_w, &ctx->sp_warm);
   }

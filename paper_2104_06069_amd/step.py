@@ -27,7 +27,15 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
-                 packed_momentum=False, fused_apply=False, x_lp_dtype=None, grad_scale=1.0, **hyper):
+                 packed_momentum=False, fused_apply=False, x_lp_dtype=None, grad_scale=1.0,
+                 status_interval=64, **hyper):
+        """hyper: the fields of ob_lamb_config (hyper-parameters, flags, fused_max_tiles, spin_limit).
+        status_interval: every that many optimizer steps step()/warmup_step() ask the library whether a
+        bounded device-side wait has expired (one stream synchronisation; raises ObLambError with
+        OB_ERR_STATE if so, after which the state must be restored from a checkpoint); 0 = never,
+        the caller calls check_status() itself."""
+        self.status_interval = int(status_interval)
+        self._steps_since_check = 0
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.W = int(num_workers)
@@ -131,7 +139,23 @@ class DeviceStep:
     def _is_plain(self, grad=None):
         return self.x_lp is None and (grad is None or (grad.dtype == torch.float32 and self.grad_scale == 1.0))
 
+    def check_status(self):
+        """Synchronises the stream; raises ObLambError(OB_ERR_STATE) if a device-side wait expired
+        since the last check (the outputs of the steps since then are undefined)."""
+        self._steps_since_check = 0
+        ob.ob_lamb_check_device_status(self.ctx, self.stream)
+
+    def _count_step(self):
+        self._steps_since_check += 1
+        if (self.status_interval and self._steps_since_check >= self.status_interval
+                and not torch.cuda.is_current_stream_capturing()):   # (a capture cannot synchronise)
+            self.check_status()
+
     def warmup_step(self, grad, lr):
+        self._warmup_step(grad, lr)
+        self._count_step()
+
+    def _warmup_step(self, grad, lr):
         if self._is_plain(grad):
             ob.ob_lamb_warmup_step(self.ctx, self._state("read"), grad, lr, self.stream)
         else:
@@ -226,3 +250,4 @@ class DeviceStep:
         else:
             self.layer_ratios()
             self.decompress_apply(lr)
+        self._count_step()

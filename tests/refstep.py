@@ -1,7 +1,7 @@
 """Host-side mirror of the device step, driving the CPU oracle on numpy arrays (tests only)."""
 import numpy as np
 
-from oracle.obref import Ref, lp_decode, lp_round
+from oracle.obref import Ref, default_threads, lp_decode, lp_round  # noqa: F401
 
 F32 = Ref(np.float32)
 
@@ -10,7 +10,10 @@ HYPER = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3,
 
 
 class RefStep:
-    def __init__(self, layer_offsets, num_workers, server_chunk=0, mom_scale=None, n_pad=None, **hyper):
+    def __init__(self, layer_offsets, num_workers, server_chunk=0, mom_scale=None, n_pad=None, threads=1,
+                 **hyper):
+        # threads > 1: the oracle's multi-threaded drivers (bit-identical to the serial routines)
+        self.F = F32 if threads <= 1 else Ref(np.float32, threads)
         self.off = np.asarray(layer_offsets, dtype=np.int64)
         self.L = self.off.size - 1
         self.N = int(self.off[-1])
@@ -62,7 +65,7 @@ class RefStep:
     def warmup_step(self, g, lr):
         g = self._g32(g)
         h, t = self.h, self.t
-        t["coeff_c"][...] = F32.warmup_step(self.off, h["beta1"], h["beta2"], h["beta3"], h["eta"],
+        t["coeff_c"][...] = self.F.warmup_step(self.off, h["beta1"], h["beta2"], h["beta3"], h["eta"],
                                             h["c_min"], h["c_max"], h["weight_decay"], lr, g, t["m"],
                                             t["v_fresh"], t["x"], t["c_avg"])
 
@@ -71,7 +74,7 @@ class RefStep:
         self.t["r_prev"][...] = 1.0
 
     def momentum_scale(self):
-        self.mom_scale = F32.momentum_scale(self.off, self.t["m"])
+        self.mom_scale = self.F.momentum_scale(self.off, self.t["m"])
 
     def train_step(self, t, warmup_steps, g, lr, fill_wire=None, momentum_scaling=True):
         if t < warmup_steps:
@@ -87,7 +90,7 @@ class RefStep:
 
     def compress_local(self, g):
         g = self._g32(g)
-        self.bits_local, self.scales_local = F32.compress_local(
+        self.bits_local, self.scales_local = self.F.compress_local(
             self.off, self.W, self.mom_scale, self.h["beta1"], g, self.t["m"], self.t["err_worker"])
 
     def gather(self):
@@ -97,20 +100,20 @@ class RefStep:
 
     def server_reduce(self):
         b = self.n_c // 8
-        bo, so = F32.server_reduce(self.W, self.bits_in, self.scales_in, self.t["err_server"])
+        bo, so = self.F.server_reduce(self.W, self.bits_in, self.scales_in, self.t["err_server"])
         self.bits_all[self.c * b:(self.c + 1) * b] = bo
         self.server_scales[self.c] = so
 
     def layer_ratios(self):
         h, t = self.h, self.t
-        t["coeff_c"][...] = F32.layer_ratios(self.off, self.W, self.mom_scale, h["beta1"], h["beta2"],
+        t["coeff_c"][...] = self.F.layer_ratios(self.off, self.W, self.mom_scale, h["beta1"], h["beta2"],
                                              h["r_min"], h["r_max"], h["r_threshold"], self.bits_all,
                                              self.server_scales, t["m"], t["v_fresh"], t["v_frozen"],
                                              t["c_avg"], t["r_prev"])
 
     def decompress_apply(self, lr):
         t = self.t
-        F32.decompress_apply(self.off, self.W, self.mom_scale, self.h["eta"], lr, self.bits_all,
+        self.F.decompress_apply(self.off, self.W, self.mom_scale, self.h["eta"], lr, self.bits_all,
                              self.server_scales, t["coeff_c"], t["v_frozen"], t["x"], t["m"])
 
     def step(self, g, lr):

@@ -23,33 +23,17 @@ def _need_gpu():
 
 def DeviceStep(*a, two_pass=False, fused_max_tiles=None, spin_limit=None, two_pass_warmup=False, **k):
     """two_pass=True forces the two-kernel worker compression (the default picks the single-pass
-    kernel whenever the chunk's workgroups fit on the device, which is the case for every size here)."""
-    import os
+    kernel whenever the chunk's workgroups fit on the device, which is the case for every size here).
+    The selection travels in the context's configuration (flags, fused_max_tiles, spin_limit)."""
     from paper_2104_06069_amd.step import DeviceStep as D
     import paper_2104_06069_amd as ob
-    old = os.environ.pop("OB_LAMB_TWO_PASS", None)
-    old2 = os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
-    os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
-    os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
-    if two_pass_warmup:
-        os.environ["OB_LAMB_TWO_PASS_WARMUP"] = "1"
-    if spin_limit is not None:
-        os.environ["OB_LAMB_SPIN_LIMIT"] = str(spin_limit)
-    if two_pass:
-        os.environ["OB_LAMB_TWO_PASS"] = "1"
-    if fused_max_tiles is not None:
-        os.environ["OB_LAMB_FUSED_MAX_TILES"] = str(fused_max_tiles)
-    try:
-        d = D(*a, **k)
-    finally:
-        os.environ.pop("OB_LAMB_TWO_PASS", None)
-        os.environ.pop("OB_LAMB_FUSED_MAX_TILES", None)
-        os.environ.pop("OB_LAMB_SPIN_LIMIT", None)
-        os.environ.pop("OB_LAMB_TWO_PASS_WARMUP", None)
-        if old is not None:
-            os.environ["OB_LAMB_TWO_PASS"] = old
-        if old2 is not None:
-            os.environ["OB_LAMB_FUSED_MAX_TILES"] = old2
+    flags = (ob.OB_CFG_TWO_PASS_COMPRESS if two_pass else 0) | (ob.OB_CFG_TWO_PASS_WARMUP if two_pass_warmup else 0)
+    if fused_max_tiles == 0:    # no layer at all in the kernels with a per-layer barrier
+        flags |= ob.OB_CFG_NO_FUSED_APPLY | ob.OB_CFG_TWO_PASS_WARMUP
+        fused_max_tiles = None
+    if spin_limit == 0:
+        spin_limit = ob.OB_SPIN_NONE
+    d = D(*a, flags=flags, fused_max_tiles=fused_max_tiles or 0, spin_limit=spin_limit or 0, **k)
     assert ob.ob_lamb_uses_single_pass(d.ctx) == (not two_pass)
     return d
 
