@@ -122,3 +122,111 @@ class RefStep:
         self.server_reduce()
         self.layer_ratios()
         self.decompress_apply(lr)
+
+
+class WindowRef:
+    """The oracle on chunks [c0, c1) of a W-chunk problem with chunk length n_c.
+
+    Worker compression, error feedback, the decompressed momentum and the fresh variance are
+    chunk-local (Appendix A.7.1: each chunk is its own parameter-server instance), so the oracle
+    follows them exactly on the window alone; the ratio, the coefficient and the parameters are
+    per layer and are valid for the layers that lie wholly inside the window (`inside`, `layers`).
+    If the served chunk c_srv lies in the window, Algorithm 1 line 10 runs on it with the full
+    fan-in of W packed chunks."""
+
+    def __init__(self, offsets, W, n_c, c0, c1, c_srv, mom_scale=None, threads=1, **hyper):
+        offsets = np.asarray(offsets, dtype=np.int64)
+        self.W, self.n_c, self.c0, self.c1, self.c_srv = int(W), int(n_c), int(c0), int(c1), int(c_srv)
+        self.A, self.B = self.c0 * self.n_c, self.c1 * self.n_c
+        off = (np.clip(offsets, self.A, self.B) - self.A).astype(np.int64)
+        self.inside = (offsets[:-1] >= self.A) & (offsets[1:] <= self.B) & (offsets[1:] > offsets[:-1])
+        self.layers = np.nonzero(self.inside)[0]
+        self.lo = offsets[:-1] - self.A      # window-relative [lo[l], hi[l]) of layer l (valid if inside)
+        self.hi = offsets[1:] - self.A
+        self.served = self.c0 <= self.c_srv < self.c1
+        self.ref = RefStep(off, self.c1 - self.c0, (self.c_srv - self.c0) if self.served else 0,
+                           mom_scale=mom_scale, n_pad=self.B - self.A, threads=threads, **hyper)
+        assert self.ref.n_c == self.n_c
+        self.t = self.ref.t
+        self.server_bits = self.server_scale = None
+
+    def load(self, get):
+        """get(key) -> the full-size array (numpy) of that key, or a callable slicing the device."""
+        for k in ("x", "m", "v_fresh", "v_frozen", "err_worker"):
+            self.t[k][...] = get(k, self.A, self.B)
+        for k in ("c_avg", "r_prev"):
+            self.t[k][...] = get(k, None, None)
+        if self.served:
+            self.t["err_server"][...] = get("err_server", None, None)
+
+    def step(self, g_win, lr, all_words_win, all_scales_win, in_words=None, in_scales=None):
+        """g_win: the gradient on the window.  all_words_win / all_scales_win: what the W servers
+        broadcast, restricted to the window (uint32 words / float32; the served chunk's slot is
+        overwritten here with the oracle's own server output).  in_words / in_scales: what the W
+        workers sent for the served chunk (needed when it lies in the window; the own slot is
+        overwritten with the oracle's own worker output)."""
+        r = self.ref
+        r.compress_local(g_win)
+        words = np.array(all_words_win, dtype=np.uint32, copy=True)
+        scales = np.array(all_scales_win, dtype=np.float32, copy=True)
+        if self.served:
+            b = self.n_c // 8
+            bits_in = np.array(in_words, copy=True).view(np.uint8)
+            sc_in = np.array(in_scales, dtype=np.float32, copy=True)
+            j = self.c_srv - self.c0
+            bits_in[self.c_srv * b:(self.c_srv + 1) * b] = r.bits_local[j * b:(j + 1) * b]
+            sc_in[self.c_srv] = r.scales_local[j]
+            bo, so = r.F.server_reduce(self.W, bits_in, sc_in, r.t["err_server"])
+            self.server_bits, self.server_scale = bo, so
+            words.view(np.uint8)[j * b:(j + 1) * b] = bo
+            scales[j] = so
+        r.set_foreign_all(words, scales)
+        r.layer_ratios()
+        r.decompress_apply(lr)
+
+
+def _for_each(items, fn, threads):
+    """fn(item) for every item, on a pool of host threads (the oracle's C routines release the GIL)."""
+    if threads <= 1:
+        for it in items:
+            fn(it)
+        return
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(fn, items))
+
+
+def simulated_worker_chunks(F, offsets, W, n_c, c_srv, mom_scale, beta1, m_chunk, grads, errs, threads=1):
+    """What W-1 other workers would send for chunk c_srv: each compresses, with the oracle's own
+    routine and its own error buffer errs[w] (updated in place), the local momentum
+    k*(beta1*m + (1-beta1)*g_w) + err_w of that chunk, g_w = grads[w] being its own gradient draw
+    (Algorithm 1 lines 6-7 on the sub-problem "this chunk alone").  -> (words uint32 [W * n_c/32],
+    scales [W]); slot c_srv is left zero for the caller's own output."""
+    offsets = np.asarray(offsets, dtype=np.int64)
+    A = c_srv * n_c
+    off = (np.clip(offsets, A, A + n_c) - A).astype(np.int64)
+    words = np.zeros(W * (n_c // 32), np.uint32)
+    scales = np.zeros(W, np.float32)
+    def one(w):
+        bits, s = F.compress_local(off, 1, mom_scale, beta1, grads[w], m_chunk, errs[w])
+        words[w * (n_c // 32):(w + 1) * (n_c // 32)] = bits.view(np.uint32)
+        scales[w] = s[0]
+    _for_each([w for w in range(W) if w != c_srv], one, threads)
+    return words, scales
+
+
+def simulated_server_chunks(F, W, n_c, c_srv, own_bits, own_scales, server_errs, threads=1):
+    """What the W-1 other servers would broadcast if every worker had sent what this one sent
+    ("all workers identical" on the chunks this rank does not serve): chunk c's server takes this
+    worker's decompressed chunk c as the average (a fan-in of 1), adds its own error buffer
+    server_errs[c] (updated in place) and recompresses (Algorithm 1 line 10).  -> (words uint32 [W * n_c/32], scales [W]); slot c_srv left zero."""
+    b = n_c // 8
+    words = np.zeros(W * (n_c // 32), np.uint32)
+    scales = np.zeros(W, np.float32)
+    def one(c):
+        bo, so = F.server_reduce(1, np.ascontiguousarray(own_bits[c * b:(c + 1) * b]),
+                                 np.ascontiguousarray(own_scales[c:c + 1]), server_errs[c])
+        words[c * (n_c // 32):(c + 1) * (n_c // 32)] = bo.view(np.uint32)
+        scales[c] = so
+    _for_each([c for c in range(W) if c != c_srv], one, threads)
+    return words, scales

@@ -108,3 +108,90 @@ def test_default_threads_is_bounded():
     with pytest.raises(TypeError):
         Ref(np.float64, threads=2)
     assert padded_len(5, 2) == 512
+
+
+@pytest.mark.parametrize("c0,c1,c_srv,with_k", [(2, 5, 3, True), (0, 4, 6, False), (5, 8, 7, True)])
+def test_window_oracle_equals_the_whole_oracle(c0, c1, c_srv, with_k):
+    """The oracle restricted to a window of whole chunks (what the full-size GPU tests follow)
+    against the oracle on the whole buffer: every chunk-local quantity on every element of the
+    window, every per-layer quantity on the layers that lie wholly inside it, the server step when
+    the served chunk lies inside -- bit for bit, over several steps."""
+    from tests.refstep import WindowRef
+    from workloads import make_config
+    cfg = make_config("bert_mini")
+    pl, W, n_c = cfg["plist"], cfg["W"], cfg["n_c"]
+    rng = np.random.default_rng(c0 * 10 + c1)
+    k = rng.uniform(0.25, 4, pl.L).astype(np.float32) if with_k else None
+    whole = RefStep(pl.offsets, W, c_srv, mom_scale=k)
+    whole.load_state(random_state(rng, whole))
+    win = WindowRef(pl.offsets, W, n_c, c0, c1, c_srv, mom_scale=k, threads=3, **HYPER)
+    assert win.layers.size >= 2 and win.served == (c0 <= c_srv < c1)
+    win.load(lambda key, A, B: whole.t[key] if A is None else whole.t[key][A:B])
+    A, B = win.A, win.B
+    for t in range(5):
+        g = (rng.standard_normal(whole.n_pad) * 1e-3).astype(np.float32); g[whole.N:] = 0
+        fw = rng.integers(0, 2 ** 32, W * (n_c // 32), dtype=np.uint32)
+        fs = rng.uniform(5e-5, 1.5e-4, W).astype(np.float32)
+        fa = rng.integers(0, 2 ** 32, whole.n_pad // 32, dtype=np.uint32)
+        fss = rng.uniform(5e-5, 1.5e-4, W).astype(np.float32)
+        whole.set_foreign_in(fw, fs); whole.set_foreign_all(fa, fss)
+        whole.step(g, 2e-3)
+        win.step(g[A:B], 2e-3, fa[A // 32:B // 32], fss[c0:c1], fw if win.served else None,
+                 fs if win.served else None)
+        assert np.array_equal(whole.bits_local[A // 8:B // 8], win.ref.bits_local)
+        assert np.array_equal(whole.scales_local[c0:c1], win.ref.scales_local)
+        for key in ("err_worker", "v_fresh", "m"):
+            assert np.array_equal(whole.t[key][A:B], win.t[key]), (t, key)
+        if win.served:
+            b = n_c // 8
+            assert np.array_equal(whole.bits_all[c_srv * b:(c_srv + 1) * b], win.server_bits)
+            assert whole.server_scales[c_srv] == win.server_scale
+            assert np.array_equal(whole.t["err_server"], win.t["err_server"])
+        ls = win.layers
+        assert np.array_equal(whole.t["r_prev"][ls], win.t["r_prev"][ls])
+        assert np.array_equal(whole.t["coeff_c"][ls], win.t["coeff_c"][ls])
+        for l in ls:
+            a, b_ = int(win.lo[l]), int(win.hi[l])
+            assert np.array_equal(whole.t["x"][A + a:A + b_], win.t["x"][a:b_]), (t, l)
+
+
+def test_simulated_ranks_are_what_the_oracle_itself_would_send():
+    """The generators of the other ranks' traffic (tests/refstep.py) against a full simulation: W
+    oracle workers compress the same momentum with their own gradients and error buffers; what
+    worker w sends for chunk c is slot w of simulated_worker_chunks."""
+    from tests.refstep import simulated_server_chunks, simulated_worker_chunks
+    rng = np.random.default_rng(5)
+    W, c_srv = 4, 2
+    off = np.array([0, 700, 700, 1900, 4000], np.int64)
+    n_pad = padded_len(4000, W); n_c = n_pad // W
+    F = Ref(np.float32)
+    k = rng.uniform(0.5, 2, 4).astype(np.float32)
+    m = (rng.standard_normal(n_pad) * 1e-4).astype(np.float32); m[4000:] = 0
+    grads = [(rng.standard_normal(n_pad) * 1e-3).astype(np.float32) for _ in range(W)]
+    errs = [(rng.standard_normal(n_pad) * 5e-5).astype(np.float32) for _ in range(W)]
+    sl = slice(c_srv * n_c, (c_srv + 1) * n_c)
+    g_c = {w: np.ascontiguousarray(grads[w][sl]) for w in range(W)}
+    e_c = {w: errs[w][sl].copy() for w in range(W)}
+    words, scales = simulated_worker_chunks(F, off, W, n_c, c_srv, k, 0.9, np.ascontiguousarray(m[sl]),
+                                            g_c, e_c, threads=2)
+    for w in range(W):
+        bits, sc = F.compress_local(off, W, k, 0.9, grads[w], m, errs[w])   # the full worker
+        if w == c_srv:
+            assert not words[w * (n_c // 32):(w + 1) * (n_c // 32)].any() and scales[w] == 0
+            continue
+        assert np.array_equal(words[w * (n_c // 32):(w + 1) * (n_c // 32)].view(np.uint8),
+                              bits[c_srv * (n_c // 8):(c_srv + 1) * (n_c // 8)])
+        assert scales[w] == sc[c_srv]
+        assert np.array_equal(e_c[w], errs[w][sl])
+    # servers: chunk c's output decodes, with its error, to what it received plus its old error
+    bits0, sc0 = F.compress_local(off, W, k, 0.9, grads[0], m, errs[0].copy())
+    se = {c: (rng.standard_normal(n_c) * 5e-5).astype(np.float32) for c in range(W)}
+    se0 = {c: v.copy() for c, v in se.items()}
+    sw, ssc = simulated_server_chunks(F, W, n_c, c_srv, bits0, sc0, se, threads=2)
+    for c in range(W):
+        if c == c_srv:
+            assert ssc[c] == 0
+            continue
+        recv = F.decompress_chunk(np.ascontiguousarray(bits0[c * (n_c // 8):(c + 1) * (n_c // 8)]), sc0[c], n_c)
+        sent = F.decompress_chunk(sw[c * (n_c // 32):(c + 1) * (n_c // 32)].view(np.uint8).copy(), ssc[c], n_c)
+        assert np.allclose(sent.astype(np.float64) + se[c], recv.astype(np.float64) + se0[c], rtol=0, atol=1e-10)
