@@ -62,7 +62,8 @@ typedef enum ob_status {
   OB_ERR_ARG = -2,   /* a size, offset table or hyper-parameter is invalid */
   OB_ERR_ALIGN = -3, /* a device pointer is not 16-byte aligned */
   OB_ERR_STATE = -4, /* a bounded device-side wait expired (see ob_lamb_check_device_status) */
-  OB_ERR_HIP = -5    /* a HIP runtime call failed (see ob_lamb_last_hip_error) */
+  OB_ERR_HIP = -5,   /* a HIP runtime call failed (see ob_lamb_last_hip_error) */
+  OB_ERR_SIZE = -6   /* a size exceeds a fixed capacity (ob_lamb_server_reduce_static) */
 } ob_status;
 
 typedef struct ob_lamb_config {
@@ -314,6 +315,23 @@ int32_t ob_lamb_uses_single_pass(const ob_lamb_ctx* ctx);
  * served chunk's workgroups do not fit on the device at once, OB_CFG_TWO_PASS_COMPRESS, or after
  * an expired wait), else the kernel's tile size in units of 1024 elements (1, 2 or 4). */
 int32_t ob_lamb_server_single_pass(const ob_lamb_ctx* ctx);
+
+/* ob_lamb_server_reduce for callers that cannot allocate device memory -- code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
+ * arguments' meaning (all device pointers, 16-byte aligned; num_workers = W, chunk_len = n_c, a
+ * multiple of 256), but no context: the partial sums between its kernels live in a fixed array
+ * inside the library's device image (256 KiB per GPU, held until the process ends), looked up on
+ * the first call on each device.  It calls no hipMalloc/hipFree or any allocating routine, enqueues
+ * three kernels on `hip_stream` and returns without synchronising.
+ *   chunk_len > ob_lamb_static_max_chunk_len() (2^25 elements) -> OB_ERR_SIZE, nothing enqueued;
+ *   other invalid sizes -> OB_ERR_ARG; NULL / misaligned pointers -> OB_ERR_NULL / OB_ERR_ALIGN.
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ * streams, two threads) race; order them yourself.  Results equal ob_lamb_server_reduce's in its
+ * three-kernel form bit for bit. */
+ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, const uint32_t* packed_in,
+                                       const float* scales_in, float* err_server, uint32_t* packed_out,
+                                       float* scale_out, void* hip_stream);
+int64_t ob_lamb_static_max_chunk_len(void);
 
 /* ---- per-kernel timing (diagnostics; used by the benchmark) ----
  * While enabled, every kernel launch of this context is bracketed by HIP events on its stream.

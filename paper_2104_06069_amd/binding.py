@@ -87,6 +87,8 @@ def lib():
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_server_single_pass": (i32, [vp]),
             "ob_lamb_plan_split": (C.c_int, [C.POINTER(ObLambConfig), i64, vp, vp]),
+            "ob_lamb_server_reduce_static": (C.c_int, [i32, i64, vp, vp, vp, vp, vp, vp]),
+            "ob_lamb_static_max_chunk_len": (i64, []),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
             "ob_lamb_profile_read": (i32, [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(i64)]),
@@ -195,6 +197,18 @@ def ob_lamb_server_reduce(ctx, state, packed_in, scales_in, packed_out, scale_ou
     _check(lib().ob_lamb_server_reduce(ctx, C.byref(state), _addr(packed_in), _addr(scales_in),
                                        _addr(packed_out), _addr(scale_out), _addr(stream)), ctx,
            "ob_lamb_server_reduce")
+
+
+def ob_lamb_server_reduce_static(num_workers, chunk_len, packed_in, scales_in, err_server, packed_out,
+                                 scale_out, stream=None):
+    _check(lib().ob_lamb_server_reduce_static(int(num_workers), int(chunk_len), _addr(packed_in),
+                                              _addr(scales_in), _addr(err_server), _addr(packed_out),
+                                              _addr(scale_out), _addr(stream)), None,
+           "ob_lamb_server_reduce_static")
+
+
+def ob_lamb_static_max_chunk_len():
+    return int(lib().ob_lamb_static_max_chunk_len())
 
 
 def ob_lamb_layer_ratios(ctx, state, packed_all, server_scales, stream=None):

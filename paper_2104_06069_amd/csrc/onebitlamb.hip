@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <string>
 #include <type_traits>
@@ -562,6 +563,7 @@ const char* ob_lamb_status_string(ob_status s) {
     case OB_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case OB_ERR_STATE: return "invalid state";
     case OB_ERR_HIP: return "HIP runtime error";
+    case OB_ERR_SIZE: return "size exceeds the capacity of the static scratch";
   }
   return "unknown status";
 }
@@ -1146,6 +1148,67 @@ int32_t ob_lamb_profile_read(ob_lamb_ctx* ctx, int32_t cap, const char** names, 
     ++n;
   }
   return n;
+}
+
+}  // extern "C"
+
+// ---- Algorithm 1 line 10 for callers that cannot allocate -------------------------------------
+// ob_lamb_server_reduce needs a context, whose creation allocates the partial sums that its
+// kernels pass from the averaging pass to the scale.  This variant keeps them in a fixed array in
+// the library's own device image instead: no context, no allocation of any kind.
+namespace {
+constexpr int64_t STATIC_MAX_CHUNK = (int64_t)1 << 25;                 // elements of the served chunk
+constexpr int64_t STATIC_MAX_TILES = STATIC_MAX_CHUNK / TILE_SRV;      // 32768 partial sums = 256 KiB
+}
+// One copy per GPU the library runs on, alive until the process ends.  In host code this name is
+// only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) double scratch[STATIC_MAX_TILES];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+double* g_scratch_ptr[STATIC_MAX_DEVICES] = {};   // per device: the address of ITS copy of `scratch`
+
+// Device address of the current device's scratch array (looked up once per device).
+ob_status static_scratch(double** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return OB_ERR_HIP;
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return OB_ERR_ARG;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return OB_ERR_HIP;
+    g_scratch_ptr[dev] = static_cast<double*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return OB_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int64_t ob_lamb_static_max_chunk_len(void) { return STATIC_MAX_CHUNK; }
+
+ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, const uint32_t* packed_in,
+                                       const float* scales_in, float* err_server, uint32_t* packed_out,
+                                       float* scale_out, void* hip_stream) {
+  if (num_workers < 1 || num_workers > 65536 || chunk_len < 256 || chunk_len % 256 != 0) return OB_ERR_ARG;
+  if (chunk_len > STATIC_MAX_CHUNK) return OB_ERR_SIZE;
+  REQUIRE_PTR(packed_in); REQUIRE_PTR(packed_out); REQUIRE_PTR(err_server);
+  if (!scales_in || !scale_out) return OB_ERR_NULL;
+  double* partials = nullptr;
+  if (ob_status s = static_scratch(&partials)) return s;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const int tiles = (int)((chunk_len + TILE_SRV - 1) / TILE_SRV);   // <= STATIC_MAX_TILES
+  const float invW = 1.0f / (float)num_workers;
+  // the three kernels of ob_lamb_server_reduce's barrier-free form; every partial that the second
+  // reads has been written by the first, so the array's previous contents do not matter
+  hipLaunchKernelGGL((k_server_unpack_avg<U_SRV>), dim3((unsigned)tiles), dim3(BLOCK), 0, stream, packed_in,
+                     scales_in, err_server, partials, chunk_len, (int)num_workers, invW);
+  hipLaunchKernelGGL(k_chunk_scale, dim3(1), dim3(FBLOCK), 0, stream, partials, tiles, chunk_len, scale_out);
+  hipLaunchKernelGGL((k_sign_pack_error<U_SRV>), dim3((unsigned)tiles), dim3(BLOCK), 0, stream, err_server,
+                     packed_out, scale_out, chunk_len, tiles);
+  return hipGetLastError() == hipSuccess ? OB_OK : OB_ERR_HIP;
 }
 
 }  // extern "C"
