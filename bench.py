@@ -3,9 +3,12 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input already resident in
 HBM: compress_local -> (gather copy) -> server_reduce -> ratios_apply (= layer_ratios + decompress_apply).
-Prints ONE JSON line: the metric, the dominant kernel's roofline from HIP-event timings of its
-launches, per-call and per-kernel times, and the CPU oracle timed beside it.  `--gpus N` with N > 1 is refused: this
-build measures one GPU's share of the data-parallel step and uses no collectives.
+Prints ONE JSON line: the metric on the BERT-Large-shaped list at W = 64, the dominant kernel's
+roofline from HIP-event timings of its launches, per-call and per-kernel times (each kernel also
+against a plain copy kernel's rate measured in the same run), the other benchmark configurations in
+brief (`workloads`), and the CPU oracle timed beside it (serial, and through its multi-threaded
+drivers).  `--gpus N` with N > 1 is refused: this build measures one GPU's share of the
+data-parallel step and uses no collectives.
 """
 import argparse
 import json
@@ -18,6 +21,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+HYPER = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3, r_min=0.5,
+             r_max=4.0, r_threshold=0.1, weight_decay=0.0)
 
 # Algorithmic HBM bytes per element of one launch of each kernel (every input read once, every
 # output written once), by momentum representation.  Units per launch: n_pad for the N-sized
@@ -49,36 +54,206 @@ KERNEL_BYTES = {
 }
 
 
-def compulsory_step_bytes_per_param(W):
-    """The step's compulsory bytes with an fp32 momentum array (the accounting this build was
-    specified against): compress_local 16.125 + server_reduce (0.125 + 8.125/W) + layer_ratios
-    16.125 + decompress_apply 12.0."""
+def fp32_momentum_equivalent_bytes_per_param(W):
+    """The accounting this build was specified against: an fp32 momentum array and two N-sized
+    update calls -- compress_local 16.125 + server_reduce (0.125 + 8.125/W) + layer_ratios 16.125 +
+    decompress_apply 12.0 bytes per parameter.  The implemented step moves fewer bytes (see
+    algorithmic_step_bytes_per_param), so a rate formed from these bytes is an equivalent, not an
+    achieved bandwidth."""
     return 16.125 + 0.125 + 8.125 / W + 16.125 + 12.0
 
 
-def algorithmic_step_bytes_per_param(W, mode, fused_frac=0.0):
-    """What the N-sized calls as implemented must move (each call's inputs once, outputs once),
-    plus the server call.  fused_frac: share of the parameters whose ratio pass and update run as
-    one kernel (ob_lamb_ratios_apply), reading v_frozen and the sign words once."""
+def algorithmic_step_bytes_per_param(W, mode, fused_frac, single_pass_compress, server_single_pass):
+    """What the calls as implemented must move (each kernel's inputs once, outputs once).
+    fused_frac: share of the parameters whose ratio pass and update run as one kernel
+    (ob_lamb_ratios_apply), reading v_frozen and the sign words once."""
     k = KERNEL_BYTES[mode]
     separate = k["ratios_pass"][0] + k["decompress_apply"][0]
-    return (k["compress_resident"][0] + fused_frac * k["ratios_apply_resident"][0]
-            + (1.0 - fused_frac) * separate + 0.125 + 8.125 / W)
+    compress = k["compress_resident"][0] if single_pass_compress else k["momentum_z_sumsq"][0] + 8.125
+    server = (0.125 + 8.125 / W) if server_single_pass else (0.125 + 16.125 / W)
+    return (compress + fused_frac * k["ratios_apply_resident"][0] + (1.0 - fused_frac) * separate + server)
+
+
+class Workload:
+    """One benchmark configuration resident in HBM: state, a few gradients, what the other ranks send."""
+
+    def __init__(self, name, args, torch):
+        import paper_2104_06069_amd as ob
+        from paper_2104_06069_amd.step import DeviceStep
+        from workloads import (Streams, foreign_server_chunks, foreign_worker_chunks, gradient,
+                               init_state, make_config)
+        self.ob, self.torch, self.name = ob, torch, name
+        self.cfg = cfg = make_config(name)
+        self.pl, self.W = cfg["plist"], cfg["W"]
+        self.server_chunk = self.W // 2
+        st = Streams(0, device="cuda:0")
+        self.mode = "dense" if args.dense_momentum else "packed"
+        tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "none": None}
+        # momentum scaling (Appendix A.5.2) off, or with the coefficients GENERATED by the library from
+        # a momentum that a LAMB step has formed (below)
+        self.ds = DeviceStep(self.pl.offsets, self.W, self.server_chunk, device="cuda:0", mom_scale=None,
+                             packed_momentum=(self.mode == "packed"), fused_apply=not args.separate_calls,
+                             x_lp_dtype=tdt[args.x_lp], status_interval=0, **HYPER)
+        ds = self.ds
+        ds.load_state(init_state(st, cfg))
+        self.grads = [gradient(st, cfg, t).to(tdt[args.grad_dtype]) for t in range(3)]
+        if args.mom_scale:
+            # one LAMB step on a scratch copy of the state gives every layer a momentum of its own
+            # scale; the coefficients are formed from it, then the state is put back
+            keep = {k: ds.t[k].clone() for k in ("x", "m", "v_fresh", "c_avg")}
+            ds.warmup_step(self.grads[0], 1e-3)
+            ds.momentum_scale()
+            for k, v in keep.items():
+                ds.t[k].copy_(v)
+            del keep
+        self.fw, self.fs = foreign_worker_chunks(st, cfg, 0)
+        ds.packed_in.copy_(self.fw); ds.scales_in.copy_(torch.from_numpy(self.fs))
+        for i in range(len(ds._pa)):   # what the other ranks' servers send, for both buffer pairs
+            fa, fss = foreign_server_chunks(st, cfg, i)
+            ds._pa[i].copy_(fa); ds._ss[i].copy_(torch.from_numpy(fss))
+        self.lr = 1e-3
+        torch.cuda.synchronize()
+        self.fused_params = ob.ob_lamb_fused_params(ds.ctx) if ds.fused_apply else 0
+        self.wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
+
+    def one_step(self, t):
+        self.ds.begin_step()
+        self.ds.step(self.grads[t % len(self.grads)], self.lr)
+
+    def timed(self, steps, warmup, graph=False):
+        """-> (mean ms per step over exactly `steps` steps bracketed by synchronisations,
+               median ms per step from events recorded between the steps of a second pass)."""
+        torch = self.torch
+        for t in range(warmup + (warmup % 2 if graph else 0)):
+            self.one_step(t)
+        torch.cuda.synchronize()
+        if graph:
+            # two steps return the alternating buffer pairs to where they started: one graph, replayed
+            assert steps % 2 == 0, "--graph replays pairs of steps"
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    self.one_step(0); self.one_step(1)
+            torch.cuda.current_stream().wait_stream(side)
+            g.replay(); torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps // 2):
+                g.replay()
+            torch.cuda.synchronize()
+            mean = 1e3 * (time.perf_counter() - t0) / steps
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps // 2 + 1)]
+            for i in range(steps // 2):
+                ev[i].record(); g.replay()
+            ev[-1].record(); torch.cuda.synchronize()
+            per = [ev[i].elapsed_time(ev[i + 1]) / 2 for i in range(steps // 2)]
+        else:
+            t0 = time.perf_counter()
+            for t in range(steps):
+                self.one_step(t)
+            torch.cuda.synchronize()
+            mean = 1e3 * (time.perf_counter() - t0) / steps
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            for t in range(steps):
+                ev[t].record(); self.one_step(t)
+            ev[-1].record(); torch.cuda.synchronize()
+            per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+        per.sort()
+        return mean, per[len(per) // 2]
+
+    def step_bytes(self, g_less, x_more):
+        ob, ds = self.ob, self.ds
+        return (algorithmic_step_bytes_per_param(self.W, self.mode, self.fused_params / float(ds.n_pad),
+                                                 ob.ob_lamb_uses_single_pass(ds.ctx),
+                                                 ob.ob_lamb_server_single_pass(ds.ctx) > 0)
+                - g_less + x_more) * ds.n_pad
+
+    def warmup_reference(self, reps=5):
+        """One uncompressed LAMB step (eq. (1)) on the same buffers, timed alone."""
+        torch, ds = self.torch, self.ds
+        ds.m_is_packed = False
+        fn = lambda: ds.warmup_step(self.grads[0], self.lr)
+        fn(); torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def close(self):
+        self.ob.ob_lamb_check_device_status(self.ds.ctx, self.ds.stream)  # raises if a device wait expired
+        self.ds.close()
+        self.grads = self.fw = None
+        self.torch.cuda.empty_cache()
+
+
+def copy_ceiling(torch, ob, src, dst, reps=20):
+    """Rate of the library's plain nontemporal copy kernel (1024-element tiles) between two existing
+    N_pad-long arrays, timed with events on the launch stream: the device's practical streaming
+    ceiling.  (No allocation here: releasing a 2 GiB buffer before a measurement left every later
+    step about 1 % slower.)"""
+    n = src.numel()
+    s = torch.cuda.current_stream().cuda_stream
+    for _ in range(5):
+        ob.ob_lamb_diag_copy(src, dst, n, s)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        ob.ob_lamb_diag_copy(src, dst, n, s)
+    e1.record(); torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    assert torch.equal(src[-5:], dst[-5:]) and torch.equal(src[:5], dst[:5])
+    gbps = 8.0 * n / (ms * 1e-3) / 1e9
+    return {"kernel": "plain nontemporal copy, 1024-element tiles (ob_lamb_diag_copy)",
+            "bytes_per_launch": 8 * n, "avg_launch_ms": round(ms, 4), "GBps": round(gbps, 1),
+            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
+
+
+def brief(name, args, torch, steps, graph_too=False):
+    """A benchmark configuration other than the headline one: step time, rate, the step's own
+    algorithmic bytes against the peak, share of the parameters in the single-kernel paths, and one
+    uncompressed LAMB step as reference."""
+    w = Workload(name, args, torch)
+    mean, med = w.timed(steps, args.warmup)
+    b = w.step_bytes(0.0, 0.0)
+    out = {"N": w.pl.N, "W": w.W, "L": w.pl.L, "steps": steps, "ms_per_step": round(mean, 4),
+           "ms_per_step_median": round(med, 4), "params_per_s": round(w.pl.N / (mean * 1e-3), 1),
+           "step_algorithmic_bytes": b,
+           "step_algorithmic_pct_of_hbm_peak": round(100 * b / (mean * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+           "fused_share": round(w.fused_params / float(w.ds.n_pad), 4),
+           "single_pass_compress": bool(w.ob.ob_lamb_uses_single_pass(w.ds.ctx)),
+           "server_single_pass": int(w.ob.ob_lamb_server_single_pass(w.ds.ctx))}
+    if graph_too:
+        gm, gmed = w.timed(steps + steps % 2, args.warmup, graph=True)
+        out["graph_replay_ms_per_step"] = round(gm, 4)
+        out["graph_replay_pct_of_hbm_peak"] = round(100 * b / (gm * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)
+    wu = w.warmup_reference()
+    out["warmup_step_ms"] = round(wu, 4)
+    out["warmup_step_params_per_s"] = round(w.pl.N / (wu * 1e-3), 1)
+    out["warmup_single_pass_share"] = round(w.wfused / float(w.ds.n_pad), 4)
+    w.close()
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # (after a pause of even 50 ms the device takes about ten 2 ms steps to return to its full rate)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bert_large")
     ap.add_argument("--profile-steps", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the brief runs of the other benchmark configurations")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="only run a plain 1 GiB device copy 10 times (for scaling rocprofv3 "
-                         "FETCH_SIZE/WRITE_SIZE readings) and exit")
-    ap.add_argument("--mom-scale", action="store_true", help="with Appendix A.5.2 momentum scaling")
+                    help="only run the library's plain copy kernel on 2 x 1 GiB 10 times (for scaling "
+                         "rocprofv3 FETCH_SIZE/WRITE_SIZE readings) and exit")
+    ap.add_argument("--mom-scale", action="store_true",
+                    help="with Appendix A.5.2 momentum scaling, coefficients generated by the library")
     ap.add_argument("--separate-calls", action="store_true",
                     help="ob_lamb_layer_ratios + ob_lamb_decompress_apply instead of the fused "
                          "ob_lamb_ratios_apply")
@@ -104,92 +279,50 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    import paper_2104_06069_amd as ob
 
     if args.calibrate_copy:
-        n = 1 << 28  # 2^28 fp32 = 1 GiB read + 1 GiB written per copy
+        n = 1 << 28  # 2^28 fp32 = 1 GiB read + 1 GiB written per launch
         a = torch.ones(n, device=dev); b = torch.empty_like(a)
         torch.cuda.synchronize()
         for _ in range(10):
-            b.copy_(a)
+            ob.ob_lamb_diag_copy(a, b, n, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy": True, "bytes_read": 4 * n, "bytes_written": 4 * n,
                           "launches": 10}))
         return
 
-    import paper_2104_06069_amd as ob
-    from paper_2104_06069_amd.step import DeviceStep
-    from workloads import (Streams, foreign_server_chunks, foreign_worker_chunks, gradient,
-                           init_state, make_config)
-
-    cfg = make_config(args.workload)
-    pl, W = cfg["plist"], cfg["W"]
-    hyper = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3, r_min=0.5,
-                 r_max=4.0, r_threshold=0.1, weight_decay=0.0)
-    server_chunk = W // 2
-    st = Streams(0, device="cuda:0")
-    mom_scale = st.uniform_host("mom_scale", 0, pl.L, 0.25, 4.0) if args.mom_scale else None
-    mode = "dense" if args.dense_momentum else "packed"
-    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "none": None}
-    ds = DeviceStep(pl.offsets, W, server_chunk, device="cuda:0", mom_scale=mom_scale,
-                    packed_momentum=(mode == "packed"), fused_apply=not args.separate_calls,
-                    x_lp_dtype=tdt[args.x_lp], **hyper)
-    ds.load_state(init_state(st, cfg))
-    n_grads = 3
-    grads = [gradient(st, cfg, t).to(tdt[args.grad_dtype]) for t in range(n_grads)]
     lp_variant = args.grad_dtype != "f32" or args.x_lp != "none"
     if lp_variant and not args.no_cpu_baseline:
         print("bench.py: the CPU-baseline leg covers the fp32 entry points; add --no-cpu-baseline "
               "to time the mixed-precision variant", file=sys.stderr)
         sys.exit(2)
-    fw, fs = foreign_worker_chunks(st, cfg, 0)
-    ds.packed_in.copy_(fw); ds.scales_in.copy_(torch.from_numpy(fs))
-    for i in range(len(ds._pa)):   # what the other ranks' servers send, for both buffer pairs
-        fa, fss = foreign_server_chunks(st, cfg, i)
-        ds._pa[i].copy_(fa); ds._ss[i].copy_(torch.from_numpy(fss))
-    lr = 1e-3
-    torch.cuda.synchronize()
 
-    def one_step(t):
-        ds.begin_step()
-        ds.step(grads[t % n_grads], lr)
-
+    wl = Workload(args.workload, args, torch)
+    ds, cfg, pl, W, mode, lr = wl.ds, wl.cfg, wl.pl, wl.W, wl.mode, wl.lr
+    grads, n_grads = wl.grads, len(wl.grads)
     host0 = None
     if not args.no_cpu_baseline:
         # host copy of the initial state and inputs for the CPU-baseline leg, taken before any step
         host0 = dict(state={k: ds.get(k).copy() for k in
                             ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev")},
                      grads=[g.cpu().numpy() for g in grads[:2]],
-                     fw=ds.packed_in.cpu().numpy(), fs=fs.copy(), fa=ds._pa[0].cpu().numpy(),
-                     fss=ds._ss[0].cpu().numpy())
+                     fw=ds.packed_in.cpu().numpy(), fs=wl.fs.copy(), fa=ds._pa[0].cpu().numpy(),
+                     fss=ds._ss[0].cpu().numpy(),
+                     mom_scale=None if ds.t["mom_scale"] is None else ds.t["mom_scale"].cpu().numpy())
 
-    for t in range(args.warmup + (args.warmup % 2 if args.graph else 0)):
-        one_step(t)
-    torch.cuda.synchronize()
-    if args.graph:
-        # two steps return the alternating buffer pairs to where they started: one graph, replayed
-        assert args.steps % 2 == 0, "--graph replays pairs of steps"
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                one_step(0); one_step(1)
-        torch.cuda.current_stream().wait_stream(side)
-        graph.replay(); torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps // 2):
-            graph.replay()
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-    else:
-        t0 = time.perf_counter()
-        for t in range(args.steps):
-            one_step(t)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+    ms_per_step, ms_median = wl.timed(args.steps, args.warmup, graph=args.graph)
 
-    # per-call times (events on the launch stream) and per-kernel durations (library's own events)
+    # per-kernel durations (the library's own events: each kernel's start and end on the device) and
+    # per-call times (events on the launch stream), both straight after the timed steps so that the
+    # device never pauses in between
+    ob.ob_lamb_profile_enable(ds.ctx, True)
+    for t in range(args.profile_steps):
+        wl.one_step(t)
+    prof = ob.ob_lamb_profile_read(ds.ctx)
+    ob.ob_lamb_profile_enable(ds.ctx, False)
+    for t in range(5):
+        wl.one_step(t)
     calls = {}
     tail = ([("ratios_apply", lambda: ds.ratios_apply(lr))] if ds.fused_apply else
             [("layer_ratios", ds.layer_ratios), ("decompress_apply", lambda: ds.decompress_apply(lr))])
@@ -205,13 +338,16 @@ def main():
         evs.append(e)
     torch.cuda.synchronize()
     for i, (nm, _) in enumerate(seq):
-        calls[nm] = round(float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])), 4)
+        calls[nm] = round(float(np.median([e[i].elapsed_time(e[i + 1]) for e in evs])), 4)
 
-    ob.ob_lamb_profile_enable(ds.ctx, True)
-    for t in range(args.profile_steps):
-        one_step(t)
-    prof = ob.ob_lamb_profile_read(ds.ctx)
-    ob.ob_lamb_profile_enable(ds.ctx, False)
+    # the streaming ceiling, on two of the workload's own arrays (the dense momentum array is not
+    # part of the state while the momentum is kept in its 1-bit form; v_frozen is only read)
+    for t in range(5):
+        wl.one_step(t)
+    scratch_dst = ds.t["m"] if mode == "packed" else torch.empty_like(ds.t["v_frozen"])
+    ceiling = copy_ceiling(torch, ob, ds.t["v_frozen"], scratch_dst)
+    if mode == "packed":
+        scratch_dst.zero_()
     kern = {k: {"avg_ms": round(v[0] / v[1], 4), "launches": v[1]} for k, v in prof.items()}
     KB = dict(KERNEL_BYTES["both"])
     KB.update(KERNEL_BYTES[mode])
@@ -223,25 +359,25 @@ def main():
         KB[k] = (KB[k][0] - g_less, KB[k][1])
     for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply", "warmup_resident"):
         KB[k] = (KB[k][0] + x_more, KB[k][1])
-    fused_params = ob.ob_lamb_fused_params(ds.ctx) if ds.fused_apply else 0
-    wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
+    fused_params, wfused = wl.fused_params, wl.wfused
     units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params, "wfused": wfused}
     if wfused:   # the two-pass warmup kernels then cover only the remaining layers (two launches each)
         for k in ("warmup_moments", "warmup_apply"):
             KB[k] = (KB[k][0], "rest_w")
         units["rest_w"] = ds.n_pad - wfused
-    if ds.fused_apply:   # the plain ratio/update kernels then cover only the remaining layers
+    if ds.fused_apply and fused_params:   # the plain ratio/update kernels then cover only the remaining layers
         for k in ("ratios_pass", "decompress_apply"):
             KB[k] = (KB[k][0], "rest")
         units["rest"] = ds.n_pad - fused_params
     for k, v in kern.items():
         if k in KB:
             bpe, unit = KB[k]
-            # "rest" is covered by two launches per call (tiles on the boundaries of the fused
-            # layers, then the remaining layers): per-launch mean
+            # (should a call cover its elements with several launches of one kernel: per-launch mean)
             per_call = max(1, round(v["launches"] / args.profile_steps)) if unit in ("rest", "rest_w") else 1
             v["algo_bytes"] = bpe * units[unit] / per_call
             v["GBps"] = round(v["algo_bytes"] / (v["avg_ms"] * 1e-3) / 1e9, 1)
+            v["frac_of_hbm_peak"] = round(v["GBps"] / HBM_PEAK_GBS, 4)
+            v["frac_of_copy_ceiling"] = round(v["GBps"] / ceiling["GBps"], 4)
     dom = max((k for k in kern if "GBps" in kern[k]), key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -255,51 +391,55 @@ def main():
             traffic = None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(kern[dom]["GBps"] / HBM_PEAK_GBS, 4),
+                "frac_of_copy_ceiling": kern[dom]["frac_of_copy_ceiling"],
                 "avg_launch_ms": kern[dom]["avg_ms"], "algo_bytes_per_launch": kern[dom]["algo_bytes"],
                 "traffic": traffic}
 
-    step_bytes = compulsory_step_bytes_per_param(W) * ds.n_pad
-    algo_bytes = (algorithmic_step_bytes_per_param(W, mode, fused_params / float(ds.n_pad))
-                  - g_less + x_more) * ds.n_pad
+    equiv_bytes = fp32_momentum_equivalent_bytes_per_param(W) * ds.n_pad
+    algo_bytes = wl.step_bytes(g_less, x_more)
     out = {
         "metric": "1-bit LAMB compressed step: params/sec and % of HBM peak GB/s, 1 GPU",
         "value": round(pl.N / (ms_per_step * 1e-3), 1), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
+        "value_at_median": round(pl.N / (ms_median * 1e-3), 1),
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}_shaped_W{W}", "N": pl.N, "N_pad": ds.n_pad, "L": pl.L,
-                   "W": W, "n_c": ds.n_c, "server_chunk": server_chunk,
+                   "W": W, "n_c": ds.n_c, "server_chunk": wl.server_chunk,
                    "mom_scale": bool(args.mom_scale), "momentum": mode,
                    "grad_dtype": args.grad_dtype, "x_lp": args.x_lp, "graph_replay": bool(args.graph),
                    "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
                    "fused_params": fused_params,
-                   "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx)},
+                   "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx),
+                   "server_single_pass": ob.ob_lamb_server_single_pass(ds.ctx)},
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_algorithmic_pct_of_hbm_peak": round(100 * algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
-        "step_compulsory_bytes": step_bytes,
-        "step_compulsory_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "step_pct_of_hbm_peak": round(100 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "step_algorithmic_pct_of_copy_ceiling": round(100 * algo_bytes / (ms_per_step * 1e-3) / 1e9 / ceiling["GBps"], 2),
+        # NOT an achieved bandwidth: the bytes of the fp32-momentum, two-update-call accounting divided
+        # by the measured step time (the implemented step moves step_algorithmic_bytes)
+        "fp32_momentum_equivalent": {
+            "bytes": equiv_bytes,
+            "equivalent_GBps": round(equiv_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+            "equivalent_pct_of_hbm_peak": round(100 * equiv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)},
+        "ceiling": ceiling,
         "roofline": roofline,
         "calls_ms": calls,
         "kernels": kern,
     }
 
-    ob.ob_lamb_check_device_status(ds.ctx, ds.stream)  # raises if a bounded device wait expired
-
     # reference timings outside the headline metric: one uncompressed LAMB warmup step (eq. (1)) and
     # the end-of-warmup momentum-scale generation (Appendix A.5.2), on the same buffers
-    def timed(fn, reps=5):
-        fn(); torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record(); torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+    wu_ms = wl.warmup_reference()
     ds.m_is_packed = False
-    wu_ms = timed(lambda: ds.warmup_step(grads[0], lr))
-    ms_ms = timed(lambda: ds.momentum_scale())
+    ds.momentum_scale(); torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        ds.momentum_scale()
+    e1.record(); torch.cuda.synchronize()
+    ms_ms = e0.elapsed_time(e1) / 5
     out["reference_calls"] = {
         "warmup_step_ms": round(wu_ms, 4),
         # 28 B/elem where g, m, v, x are read once, 24 + 16 in the two-pass form
@@ -309,19 +449,37 @@ def main():
         "warmup_step_params_per_s": round(pl.N / (wu_ms * 1e-3), 1),
         "momentum_scale_ms": round(ms_ms, 4),
         "momentum_scale_GBps": round(4.0 * ds.n_pad / (ms_ms * 1e-3) / 1e9, 1)}
+    wl.close()
+    del wl, ds, grads
+
+    if not args.no_workloads and not lp_variant:
+        # the other benchmark configurations (parity-test cases), same defaults
+        others = {}
+        for name, steps, graph_too in (("tiny", 200, True), ("bert_base", 50, True),
+                                       ("bert_large", 50, False), ("bert_large_w256", 50, False),
+                                       ("gpt_1p3b", 20, False)):
+            if name == args.workload:
+                continue
+            others[name] = brief(name, args, torch, steps, graph_too)
+        out["workloads"] = others
     if host0 is not None:
-        out["cpu_baseline"] = cpu_baseline(cfg, server_chunk, hyper, mom_scale, host0, lr,
-                                           args.cpu_seconds)
-    ds.close()
+        out["cpu_baseline"] = cpu_baseline(cfg, cfg["W"] // 2, host0, lr, args.cpu_seconds, False)
+        mt = cpu_baseline(cfg, cfg["W"] // 2, host0, lr, args.cpu_seconds, True)
+        if mt["cores"] > 1:
+            out["cpu_baseline_mt"] = mt
     print(json.dumps(out))
 
 
-def cpu_baseline(cfg, server_chunk, hyper, mom_scale, h, lr, budget_s):
-    """The oracle as it stands, single thread, on the same workload: whole steps until `budget_s`
-    seconds of CPU work have been spent (at least one step, at most three)."""
+def cpu_baseline(cfg, server_chunk, h, lr, budget_s, multi_threaded):
+    """The oracle as it stands on the same workload: whole steps until `budget_s` seconds of CPU work
+    have been spent (at least one step, at most three).  Serial routines, or its multi-threaded
+    drivers, which run the same scalar routines on chunks and layers in parallel on the host's share
+    of cores."""
     import numpy as np
-    from tests.refstep import RefStep
-    ref = RefStep(cfg["plist"].offsets, cfg["W"], server_chunk, mom_scale=mom_scale, **hyper)
+    from tests.refstep import RefStep, default_threads
+    threads = default_threads() if multi_threaded else 1
+    ref = RefStep(cfg["plist"].offsets, cfg["W"], server_chunk, mom_scale=h["mom_scale"], threads=threads,
+                  **HYPER)
     ref.load_state(h["state"])
     ref.set_foreign_in(h["fw"], h["fs"])
     ref.set_foreign_all(h["fa"], h["fss"])
@@ -332,20 +490,30 @@ def cpu_baseline(cfg, server_chunk, hyper, mom_scale, h, lr, budget_s):
         ref.step(g, lr)
         times.append(time.perf_counter() - t0)
     sec = float(np.median(times))
-    return {"value": round(cfg["plist"].N / sec, 1), "unit": "params/s", "cores": 1, "kind": "oracle",
+    return {"value": round(cfg["plist"].N / sec, 1), "unit": "params/s", "cores": threads, "kind": "oracle",
             "sample": f"{len(times)} whole step(s) of the same workload, median {sec:.2f} s/step",
             "host_cpus": os.cpu_count(), "cpu_model": _cpu_model()}
 
 
 def _cpu_model():
+    """Model name as the host reports it, with family/model numbers (virtual machines often shorten
+    the name)."""
+    f = {}
     try:
-        with open("/proc/cpuinfo") as f:
-            for line in f:
-                if line.startswith("model name"):
-                    return line.split(":", 1)[1].strip()
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if ":" in line:
+                    k, v = line.split(":", 1)
+                    k = k.strip()
+                    if k in ("model name", "cpu family", "model") and k not in f:
+                        f[k] = v.strip()
+                if len(f) == 3:
+                    break
     except OSError:
         pass
-    return "unknown"
+    if not f:
+        return "unknown"
+    return f"{f.get('model name', 'unknown')} (family {f.get('cpu family', '?')}, model {f.get('model', '?')})"
 
 
 if __name__ == "__main__":

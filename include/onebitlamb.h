@@ -333,8 +333,15 @@ ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, c
                                        float* scale_out, void* hip_stream);
 int64_t ob_lamb_static_max_chunk_len(void);
 
+/* Diagnostics: dst[0..n) <- src[0..n) (device pointers, 16-byte aligned, not overlapping) by a plain
+ * streaming kernel in the shape of the library's N-sized kernels (1024-element tiles, 128-bit
+ * nontemporal accesses).  Its rate (8n bytes per launch) is the device's practical streaming
+ * ceiling; the benchmark reports every kernel against it next to the published peak. */
+ob_status ob_lamb_diag_copy(const float* src, float* dst, int64_t n, void* hip_stream);
+
 /* ---- per-kernel timing (diagnostics; used by the benchmark) ----
- * While enabled, every kernel launch of this context is bracketed by HIP events on its stream.
+ * While enabled, every kernel launch of this context carries a pair of HIP events that the device
+ * stamps with the kernel's own start and end (hipExtLaunchKernel).
  * ob_lamb_profile_read synchronises, aggregates by kernel and clears the record.
  * Returns the number of distinct kernels; fills up to `cap` entries of each array.
  * names[i] points to a static string. */

@@ -89,6 +89,7 @@ def lib():
             "ob_lamb_plan_split": (C.c_int, [C.POINTER(ObLambConfig), i64, vp, vp]),
             "ob_lamb_server_reduce_static": (C.c_int, [i32, i64, vp, vp, vp, vp, vp, vp]),
             "ob_lamb_static_max_chunk_len": (i64, []),
+            "ob_lamb_diag_copy": (C.c_int, [vp, vp, i64, vp]),
             "ob_lamb_profile_enable": (C.c_int, [vp, C.c_int]),
             "ob_lamb_profile_read": (i32, [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                            C.POINTER(i64)]),
@@ -205,6 +206,10 @@ def ob_lamb_server_reduce_static(num_workers, chunk_len, packed_in, scales_in, e
                                               _addr(scales_in), _addr(err_server), _addr(packed_out),
                                               _addr(scale_out), _addr(stream)), None,
            "ob_lamb_server_reduce_static")
+
+
+def ob_lamb_diag_copy(src, dst, n, stream=None):
+    _check(lib().ob_lamb_diag_copy(_addr(src), _addr(dst), int(n), _addr(stream)), None, "ob_lamb_diag_copy")
 
 
 def ob_lamb_static_max_chunk_len():

@@ -1718,6 +1718,20 @@ __global__ __launch_bounds__(FBLOCK) void k_momentum_scale(const double* __restr
   }
 }
 
+// Diagnostics: a plain streaming copy in the shape of the N-sized kernels above (1024-element
+// tiles, one 128-bit nontemporal load and store per thread).  What it reaches is the device's
+// practical streaming ceiling, against which the benchmark reports every kernel next to the
+// published peak.
+__global__ __launch_bounds__(BLOCK) void k_diag_copy(const float* __restrict__ src, float* __restrict__ dst,
+                                                     int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * SPAN + threadIdx.x * 4;
+  if (i + 4 <= n) {
+    st4(dst + i, ld4(src + i));
+  } else {
+    for (int64_t j = i; j < n; ++j) dst[j] = src[j];
+  }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_fill(float* __restrict__ p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
   if (i < n) p[i] = v;

@@ -4,6 +4,7 @@
 // Build flags that the arithmetic depends on: -ffp-contract=off (one rounding per operation) and
 // hipcc's default correctly rounded fp32 divide/sqrt; never -ffast-math.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdint>
@@ -188,28 +189,36 @@ struct Launch {
   hipStream_t stream;
   bool ok = true;
   Launch(ob_lamb_ctx* c, void* s) : ctx(c), stream(reinterpret_cast<hipStream_t>(s)) {}
-  void begin(int kid) {
-    if (!ctx->profile || !ok) return;
+  // A timing record for the coming launch (profile mode).  record_start: also record its first
+  // event on the stream now (device copies); kernels hand both events to the launch instead, which
+  // stamps them with the kernel's own start and end on the device.
+  bool begin(int kid, bool record_start) {
+    if (!ctx->profile || !ok) return false;
     ProfRec r;
     r.kid = kid;
     ok = hip_ok(ctx, hipEventCreate(&r.e0), "hipEventCreate") &&
          hip_ok(ctx, hipEventCreate(&r.e1), "hipEventCreate") &&
-         hip_ok(ctx, hipEventRecord(r.e0, stream), "hipEventRecord");
+         (!record_start || hip_ok(ctx, hipEventRecord(r.e0, stream), "hipEventRecord"));
     if (ok) ctx->prof.push_back(r);
+    return ok;
   }
-  void end(const char* name) {
+  void end(const char* name, bool record_stop) {
     if (!ok) return;
     ok = hip_ok(ctx, hipGetLastError(), name);
-    if (ok && ctx->profile) ok = hip_ok(ctx, hipEventRecord(ctx->prof.back().e1, stream), "hipEventRecord");
+    if (ok && ctx->profile && record_stop)
+      ok = hip_ok(ctx, hipEventRecord(ctx->prof.back().e1, stream), "hipEventRecord");
   }
 };
 
 #define OB_LAUNCH_B(la, kid, kernel, grid, block, ...)                            \
   do {                                                                            \
     if ((la).ok && (grid) > 0) {                                                  \
-      (la).begin(kid);                                                            \
-      hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(block), 0, (la).stream, __VA_ARGS__); \
-      (la).end(kKernelNames[kid]);                                                \
+      if ((la).begin(kid, false))                                                 \
+        hipExtLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(block), 0, (la).stream, \
+                              (la).ctx->prof.back().e0, (la).ctx->prof.back().e1, 0, __VA_ARGS__); \
+      else if ((la).ok)                                                           \
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(block), 0, (la).stream, __VA_ARGS__); \
+      (la).end(kKernelNames[kid], false);                                         \
     }                                                                             \
   } while (0)
 #define OB_LAUNCH(la, kid, kernel, grid, ...) OB_LAUNCH_B(la, kid, kernel, grid, BLOCK, __VA_ARGS__)
@@ -514,13 +523,13 @@ void launch_apply(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const u
 void commit_packed_momentum(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                    const uint32_t* packed_all, const float* server_scales) {
   if (!(st->m_packed && st->m_packed != packed_all)) return;
-  la.begin(KID_COPY);
+  la.begin(KID_COPY, true);
   if (la.ok)
     la.ok = hip_ok(ctx, hipMemcpyAsync(st->m_packed, packed_all, (size_t)ctx->n_pad / 8,
                                        hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync") &&
             hip_ok(ctx, hipMemcpyAsync(st->m_scales, server_scales, (size_t)ctx->W * sizeof(float),
                                        hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
-  la.end("copy");
+  la.end("copy", true);
 }
 
 ob_status check_ratios_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
@@ -864,11 +873,11 @@ ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_st
   REQUIRE_PTR(st->v_fresh); REQUIRE_PTR(st->v_frozen);
   if (!st->r_prev) return OB_ERR_NULL;
   Launch la(ctx, hip_stream);
-  la.begin(KID_COPY);
+  la.begin(KID_COPY, true);
   if (la.ok)
     la.ok = hip_ok(ctx, hipMemcpyAsync(st->v_frozen, st->v_fresh, (size_t)ctx->n_pad * sizeof(float),
                                        hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
-  la.end("copy");
+  la.end("copy", true);
   OB_LAUNCH(la, KID_FILL, k_fill, (int)((ctx->L + BLOCK - 1) / BLOCK), st->r_prev, ctx->L, 1.0f);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
@@ -1188,6 +1197,17 @@ ob_status static_scratch(double** out) {
 extern "C" {
 
 int64_t ob_lamb_static_max_chunk_len(void) { return STATIC_MAX_CHUNK; }
+
+ob_status ob_lamb_diag_copy(const float* src, float* dst, int64_t n, void* hip_stream) {
+  if (n < 0 || n > ((int64_t)1 << 40)) return OB_ERR_ARG;
+  REQUIRE_PTR(src); REQUIRE_PTR(dst);
+  if (n == 0) return OB_OK;
+  const int64_t tiles = (n + SPAN - 1) / SPAN;
+  if (tiles > 0x7fffffff) return OB_ERR_ARG;
+  hipLaunchKernelGGL(k_diag_copy, dim3((unsigned)tiles), dim3(BLOCK), 0, reinterpret_cast<hipStream_t>(hip_stream),
+                     src, dst, n);
+  return hipGetLastError() == hipSuccess ? OB_OK : OB_ERR_HIP;
+}
 
 ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, const uint32_t* packed_in,
                                        const float* scales_in, float* err_server, uint32_t* packed_out,
