@@ -143,6 +143,12 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx);
 int64_t ob_lamb_num_params(const ob_lamb_ctx* ctx); /* N     */
 int64_t ob_lamb_padded_len(const ob_lamb_ctx* ctx); /* N_pad */
 int64_t ob_lamb_chunk_len(const ob_lamb_ctx* ctx);  /* n_c   */
+/* Device memory the context itself holds (tile tables, partial sums, barrier words), in bytes: a few
+ * bytes per 1024 parameters.  The library allocates it in ob_lamb_create and frees it in
+ * ob_lamb_destroy; it is tied to the tables built from this configuration on this device, which is
+ * why it is not a caller-supplied buffer (a caller that must not allocate after start-up creates
+ * its contexts at start-up; ob_lamb_server_reduce_static needs none). */
+size_t ob_lamb_workspace_bytes(const ob_lamb_ctx* ctx);
 /* Static helper: N_pad for given N and W without a context (0 if an argument is invalid). */
 int64_t ob_lamb_padded_len_for(int64_t n, int32_t num_workers);
 const char* ob_lamb_status_string(ob_status s);

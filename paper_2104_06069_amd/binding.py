@@ -63,6 +63,7 @@ def lib():
             "ob_lamb_num_params": (i64, [vp]),
             "ob_lamb_padded_len": (i64, [vp]),
             "ob_lamb_chunk_len": (i64, [vp]),
+            "ob_lamb_workspace_bytes": (C.c_size_t, [vp]),
             "ob_lamb_padded_len_for": (i64, [i64, i32]),
             "ob_lamb_status_string": (C.c_char_p, [C.c_int]),
             "ob_lamb_last_hip_error": (C.c_char_p, [vp]),
@@ -177,6 +178,10 @@ def ob_lamb_padded_len(ctx):
 
 def ob_lamb_chunk_len(ctx):
     return int(lib().ob_lamb_chunk_len(ctx))
+
+
+def ob_lamb_workspace_bytes(ctx):
+    return int(lib().ob_lamb_workspace_bytes(ctx))
 
 
 def ob_lamb_warmup_step(ctx, state, grad, lr, stream=None):

@@ -168,6 +168,7 @@ struct ob_lamb_ctx {
   int tpc_lb = 0;
   LayerSplit sp_apply;                     // ob_lamb_ratios_apply
   LayerSplit sp_warm;                      // ob_lamb_warmup_step
+  size_t device_bytes = 0;                 // device memory this context holds (tables + workspace)
   // diagnostics
   bool profile = false;
   std::vector<ProfRec> prof;
@@ -227,6 +228,7 @@ template <class T>
 bool upload(ob_lamb_ctx* ctx, T** dst, const std::vector<T>& src) {
   const size_t bytes = src.size() * sizeof(T);
   if (!hip_ok(ctx, hipMalloc(reinterpret_cast<void**>(dst), bytes ? bytes : sizeof(T)), "hipMalloc")) return false;
+  ctx->device_bytes += bytes ? bytes : sizeof(T);
   if (bytes && !hip_ok(ctx, hipMemcpy(*dst, src.data(), bytes, hipMemcpyHostToDevice), "hipMemcpy")) return false;
   return true;
 }
@@ -235,6 +237,7 @@ template <class T>
 bool alloc_zero(ob_lamb_ctx* ctx, T** dst, size_t count) {
   const size_t bytes = (count ? count : 1) * sizeof(T);
   if (!hip_ok(ctx, hipMalloc(reinterpret_cast<void**>(dst), bytes), "hipMalloc")) return false;
+  ctx->device_bytes += bytes;
   return hip_ok(ctx, hipMemset(*dst, 0, bytes), "hipMemset");
 }
 
@@ -801,6 +804,7 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
 int64_t ob_lamb_num_params(const ob_lamb_ctx* ctx) { return ctx ? ctx->N : 0; }
 int64_t ob_lamb_padded_len(const ob_lamb_ctx* ctx) { return ctx ? ctx->n_pad : 0; }
 int64_t ob_lamb_chunk_len(const ob_lamb_ctx* ctx) { return ctx ? ctx->n_c : 0; }
+size_t ob_lamb_workspace_bytes(const ob_lamb_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
 
 ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const void* grad,
                                  ob_dtype grad_dtype, float grad_scale, float lr, void* x_lp,

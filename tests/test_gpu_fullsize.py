@@ -12,7 +12,8 @@ import pytest
 torch = pytest.importorskip("torch")
 
 from tests.refstep import HYPER, RefStep  # noqa: E402
-from tests.test_gpu_parity import assert_close, words_of, _need_gpu, DeviceStep, finish  # noqa: E402
+from tests.test_gpu_parity import (assert_close, assert_mostly_close, sign_bit_mismatch, words_of, _need_gpu,  # noqa: E402
+                                   DeviceStep, finish)
 from workloads import Streams, make_config, gradient, init_state, foreign_worker_chunks, foreign_server_chunks  # noqa: E402
 from workloads.gen import layer_kappa  # noqa: E402
 
@@ -336,22 +337,6 @@ def test_bert_large_warmup_step(two_pass_warmup):
         nd = {k: assert_close(dev.get(k), ref.t[k], k) for k in ("m", "v_fresh", "x", "coeff_c", "c_avg")}
         print(f"bert_large: warmup step {t}: elements not bit-equal (within 1e-6): {nd}", flush=True)
     finish(dev)
-
-
-def sign_bit_mismatch(a, b):
-    """Fraction of differing bits between two packed streams (uint8 views)."""
-    x = np.bitwise_xor(np.asarray(a).view(np.uint8), np.asarray(b).view(np.uint8))
-    return float(np.unpackbits(x).sum()) / (8.0 * x.size)
-
-
-def assert_mostly_close(gpu, ref, what, rel=1e-4, max_frac=1e-4):
-    """After a scale has differed in its last bit, elements within one unit in the last place of zero
-    may take the other sign, and their error and momentum then differ by 2*scale on BOTH sides
-    legitimately: all but a fraction max_frac of the elements must agree within rel."""
-    g = np.asarray(gpu, np.float64); r = np.asarray(ref, np.float64)
-    rms = np.sqrt(np.mean(r * r))
-    bad = np.abs(g - r) > rel * np.maximum(np.abs(r), rms)
-    assert bad.mean() <= max_frac, f"{what}: {bad.sum()} of {r.size} elements beyond {rel}"
 
 
 def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmup_steps=0, seed=9,
