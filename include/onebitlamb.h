@@ -63,7 +63,7 @@ typedef enum ob_status {
   OB_ERR_ALIGN = -3, /* a device pointer is not 16-byte aligned */
   OB_ERR_STATE = -4, /* a bounded device-side wait expired (see ob_lamb_check_device_status) */
   OB_ERR_HIP = -5,   /* a HIP runtime call failed (see ob_lamb_last_hip_error) */
-  OB_ERR_SIZE = -6   /* a size exceeds a fixed capacity (ob_lamb_server_reduce_static) */
+  OB_ERR_SIZE = -6   /* a size exceeds a fixed capacity (ob_lamb_server_reduce, ob_lamb_server_reduce_static) */
 } ob_status;
 
 typedef struct ob_lamb_config {
@@ -178,7 +178,8 @@ ob_status ob_lamb_compress_local(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
  *   packed_out, *scale_out = C[zb];  err_server <- zb - C[zb].
  * packed_in: W consecutive blocks of n_c/32 words, block w = what worker w sent for this chunk.
  * scales_in: [W].  packed_out: [n_c/32].  scale_out: [1].  (All device pointers; packed_out may
- * point into the packed_all buffer of the next two calls.) */
+ * point into the packed_all buffer of the next two calls.)  packed_in must be smaller than 2 GiB
+ * (W * n_c / 8 < 2^31 bytes; OB_ERR_SIZE otherwise): its kernels use 32-bit offsets into it. */
 ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                 const uint32_t* packed_in, const float* scales_in,
                                 uint32_t* packed_out, float* scale_out, void* hip_stream);
@@ -329,7 +330,8 @@ int32_t ob_lamb_server_single_pass(const ob_lamb_ctx* ctx);
  * inside the library's device image (256 KiB per GPU, held until the process ends), looked up on
  * the first call on each device.  It calls no hipMalloc/hipFree or any allocating routine, enqueues
  * three kernels on `hip_stream` and returns without synchronising.
- *   chunk_len > ob_lamb_static_max_chunk_len() (2^25 elements) -> OB_ERR_SIZE, nothing enqueued;
+ *   chunk_len > ob_lamb_static_max_chunk_len() (2^25 elements), or a packed_in of 2 GiB or more
+ *   -> OB_ERR_SIZE, nothing enqueued;
  *   other invalid sizes -> OB_ERR_ARG; NULL / misaligned pointers -> OB_ERR_NULL / OB_ERR_ALIGN.
  * Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU (two
  * streams, two threads) race; order them yourself.  Results equal ob_lamb_server_reduce's in its

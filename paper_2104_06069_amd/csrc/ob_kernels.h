@@ -590,44 +590,90 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
 
 // ---------------------------------------------------------------------------------------------
 // K3  server: zb = (sum_w +-s_w, sequentially) * (1/W) + err_server   (Algorithm 1 line 10)
-// Workers strictly in order 0..W-1 (the fp32 sum is order dependent); the loads of GROUP workers
-// are issued together so that their latencies overlap.
+// Workers strictly in order 0..W-1 (the fp32 sum is order dependent).  The W additions per element
+// are the whole cost (the inputs are one bit per element and worker), so the loop is written for
+// the vector ALU: three instructions per element and worker -- shift the worker's word so that the
+// element's bit is bit 0, add that bit, moved to bit 31, to the bit pattern of -s (the carry out of
+// bit 31 is dropped: bit 1 gives +s, bit 0 leaves -s; one v_lshl_add_u32), add to the accumulator --
+// with no compare/select through a lane mask.  The scales come from LDS (staged SRV_STAGE at a
+// time), the sign words of the next G workers are requested before those of the current G are
+// consumed, and nothing inside the loop branches on the tile's shape: a wavefront whose elements lie
+// beyond the tile's end skips the loop.
 // ---------------------------------------------------------------------------------------------
+constexpr int SRV_STAGE = 1024;   // scales held in LDS at a time
+// The sign words are fetched with buffer loads: the wavefront-uniform part of the address (worker
+// block) travels in a scalar register, the thread's part in one 32-bit register, so no vector
+// instruction is spent on addresses, and a read outside [packed_in, packed_in + W*n_c/32) would
+// return 0 instead of faulting.  Offsets are 32-bit: the host admits W*n_c/8 < 2^31 bytes.
+constexpr int OB_BUFFER_RSRC_WORD3 = 0x00020000;   // raw 32-bit data format word of gfx9-family descriptors
+
 template <int U>
 __device__ __forceinline__ void server_average(const uint32_t* __restrict__ packed_in,
                                                const float* __restrict__ scales_in, int64_t n_c,
-                                               int W, const TilePos& p, float (&acc)[U][4]) {
-  constexpr int GROUP = 8;
+                                               int W, const TilePos& p, float (&acc)[U][4],
+                                               unsigned int* lds_negs /* [SRV_STAGE] */) {
+  constexpr int G = (U >= 8) ? 1 : 8 / U;   // workers whose sign words are in flight together
   const int o0 = threadIdx.x * 4;
-  const int sh = 4 * (threadIdx.x & 7);
-  const int64_t wpc = n_c >> 5;  // words per worker block
+  const bool active = (o0 < p.len);   // uniform over a wavefront: len is a multiple of 256
+  const int wpc_bytes = (int)(n_c >> 3);   // bytes per worker block
+  // descriptor of the tile's column of packed_in: from the tile's first word to the end of the array
+  const int64_t col0 = p.tile0 >> 5;
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(packed_in + col0), 0, (int)(((int64_t)W * (n_c >> 5) - col0) * 4), OB_BUFFER_RSRC_WORD3);
+  // byte offset of the thread's word of span 0 in a worker's block; span u lies 128 bytes further.
+  // (A partial tile's missing spans read the words that follow the tile -- inside the array, or 0
+  // beyond its end -- and their sums are never used.)
+  const int voff0 = 4 * (int)(threadIdx.x >> 3);
+  unsigned int shk[4];                // position of the thread's k-th bit in its word
+#pragma unroll
+  for (int k = 0; k < 4; ++k) shk[k] = 4u * (threadIdx.x & 7) + (unsigned)k;
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
     for (int k = 0; k < 4; ++k) acc[u][k] = 0.0f;
-  for (int w0 = 0; w0 < W; w0 += GROUP) {
-    unsigned int word[GROUP][U];
+  auto add_worker = [&](const unsigned int (&word)[U], unsigned int negs) {
 #pragma unroll
-    for (int j = 0; j < GROUP; ++j) {
-      const int w = (w0 + j < W) ? w0 + j : W - 1;
-      const uint32_t* row = packed_in + (int64_t)w * wpc;
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int o = u * SPAN + o0;
-        word[j][u] = (o < p.len) ? row[(p.tile0 + o) >> 5] : 0u;
+      for (int k = 0; k < 4; ++k) {
+        const unsigned int t = ((word[u] >> shk[k]) << 31) + negs;   // bit ? +s : -s
+        acc[u][k] = acc[u][k] + __uint_as_float(t);
       }
+  };
+  auto load_worker = [&](unsigned int (&word)[U], int w) {
+    const int soff = w * wpc_bytes;   // uniform
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      word[u] = (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, voff0 + 128 * u, soff, 0);
+  };
+  for (int wb = 0; wb < W; wb += SRV_STAGE) {
+    const int nb = (W - wb < SRV_STAGE) ? W - wb : SRV_STAGE;
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb; i += BLOCK) lds_negs[i] = __float_as_uint(scales_in[wb + i]) ^ 0x80000000u;
+    __syncthreads();
+    if (!active) continue;
+    const int full = nb - nb % G;
+    unsigned int cur[G][U], nxt[G][U];
+    if (full > 0) {
+#pragma unroll
+      for (int j = 0; j < G; ++j) load_worker(cur[j], wb + j);
     }
+    for (int j0 = 0; j0 < full; j0 += G) {
+      if (j0 + G < full) {
 #pragma unroll
-    for (int j = 0; j < GROUP; ++j) {
-      if (w0 + j < W) {
-        const float s = scales_in[w0 + j];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const unsigned int nib = word[j][u] >> sh;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) acc[u][k] = acc[u][k] + (((nib >> k) & 1u) ? s : -s);
-        }
+        for (int j = 0; j < G; ++j) load_worker(nxt[j], wb + j0 + G + j);
       }
+#pragma unroll
+      for (int j = 0; j < G; ++j) add_worker(cur[j], lds_negs[j0 + j]);
+#pragma unroll
+      for (int j = 0; j < G; ++j)
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[j][u] = nxt[j][u];
+    }
+    for (int j = full; j < nb; ++j) {   // the last nb % G workers
+      unsigned int word[U];
+      load_worker(word, wb + j);
+      add_worker(word, lds_negs[j]);
     }
   }
 }
@@ -639,10 +685,11 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
     float* __restrict__ err_s, double* __restrict__ partials, int64_t n_c, int W, float invW) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
+  __shared__ unsigned int lds_negs[SRV_STAGE];
   const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x, (int)blockIdx.x);  // one chunk: c == 0
   const int o0 = threadIdx.x * 4;
   float acc[U][4];
-  server_average<U>(packed_in, scales_in, n_c, W, p, acc);
+  server_average<U>(packed_in, scales_in, n_c, W, p, acc, lds_negs);
   double sq = 0.0;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -666,18 +713,21 @@ __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
 // chunk barrier above (one chunk: c = 0, its own counter, flag and partials), instead of three
 // launches and a round trip of zb through err_server.  The host selects it only when all of its
 // workgroups fit on the device at once.
+// Workgroups per CU the kernel is built for: 8 (at most 64 registers) for the smaller tiles; the
+// 4096-element tile needs a few more registers than that and takes 7 rather than spill in its loop.
 template <int U>
-__global__ __launch_bounds__(BLOCK) void k_server_resident(
+__global__ __launch_bounds__(BLOCK, (U >= 4 ? 7 : 8)) void k_server_resident(
     const uint32_t* __restrict__ packed_in, const float* __restrict__ scales_in,
     float* __restrict__ err_s, uint32_t* __restrict__ packed_out, float* __restrict__ scale_out,
     ChunkSync cs, int64_t n_c, int W, float invW) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
+  __shared__ unsigned int lds_negs[SRV_STAGE];
   const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x, (int)blockIdx.x);  // one chunk: c == 0
   const int o0 = threadIdx.x * 4;
   float acc[U][4];
-  server_average<U>(packed_in, scales_in, n_c, W, p, acc);
+  server_average<U>(packed_in, scales_in, n_c, W, p, acc, lds_negs);
   v4f Z[U];
   double sq = 0.0;
 #pragma unroll

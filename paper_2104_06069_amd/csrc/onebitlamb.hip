@@ -945,6 +945,8 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
   if (ob_status s = check_common(ctx, st)) return s;
   REQUIRE_PTR(packed_in); REQUIRE_PTR(packed_out); REQUIRE_PTR(st->err_server);
   if (!scales_in || !scale_out) return OB_ERR_NULL;
+  // the kernels address packed_in with 32-bit byte offsets
+  if ((int64_t)ctx->W * (ctx->n_c / 8) >= ((int64_t)1 << 31)) return OB_ERR_SIZE;
   Launch la(ctx, hip_stream);
   if (ctx->u_srv_res) {
     ChunkSync cs;
@@ -1218,6 +1220,7 @@ ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, c
                                        float* scale_out, void* hip_stream) {
   if (num_workers < 1 || num_workers > 65536 || chunk_len < 256 || chunk_len % 256 != 0) return OB_ERR_ARG;
   if (chunk_len > STATIC_MAX_CHUNK) return OB_ERR_SIZE;
+  if ((int64_t)num_workers * (chunk_len / 8) >= ((int64_t)1 << 31)) return OB_ERR_SIZE;   // 32-bit offsets into packed_in
   REQUIRE_PTR(packed_in); REQUIRE_PTR(packed_out); REQUIRE_PTR(err_server);
   if (!scales_in || !scale_out) return OB_ERR_NULL;
   double* partials = nullptr;
