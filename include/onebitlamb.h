@@ -70,7 +70,7 @@ typedef struct ob_lamb_config {
   int64_t num_layers;           /* L >= 1 */
   const int64_t* layer_offsets; /* host, L+1 entries, [0] = 0, non-decreasing (empty layers allowed) */
   int32_t num_workers;          /* W >= 1 */
-  int32_t server_chunk;         /* chunk this rank serves, 0..W-1 (informational; see server_reduce) */
+  int32_t server_chunk;         /* chunk this rank serves, 0..W-1 (which chunk ob_lamb_state.own_packed_in receives) */
   float beta1, beta2, beta3;    /* momentum, variance, coefficient moving average (Algorithm 1 line 1) */
   float eta;                    /* added to sqrt(v) in eq. (1) and in line 21; 0 = line 21 as printed */
   float c_min, c_max;           /* clip of LAMB's coefficient in eq. (1) (warmup only) */
@@ -115,6 +115,12 @@ typedef struct ob_lamb_state {
   /* The momentum in the 1-bit form it has after Algorithm 1 line 13 (optional, see below). */
   uint32_t* m_packed; /* [N_pad/32] sign words, or NULL */
   float* m_scales;    /* [W] server scales they decode with, or NULL */
+  /* Optional second destination of ob_lamb_compress_local for chunk `server_chunk` of its output:
+   * the slot of this rank's own server input (block server_chunk of packed_in, entry server_chunk
+   * of scales_in) that the exchange would otherwise fill with a device-to-device copy of the rank's
+   * own data.  Both or neither; NULL = not written. */
+  uint32_t* own_packed_in; /* [n_c/32] or NULL */
+  float* own_scale_in;     /* [1] or NULL */
 } ob_lamb_state;
 
 /* Momentum representation.  After line 13 of any compression step the global momentum is exactly

@@ -40,7 +40,7 @@ OB_SPIN_NONE = -1
 class ObLambState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev",
-                 "coeff_c", "mom_scale", "m_packed", "m_scales")]
+                 "coeff_c", "mom_scale", "m_packed", "m_scales", "own_packed_in", "own_scale_in")]
 
 
 def lib_path():

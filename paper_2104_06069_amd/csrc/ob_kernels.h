@@ -361,8 +361,11 @@ __global__ __launch_bounds__(FBLOCK) void k_chunk_scale(const double* __restrict
 // Sign, pack and error update of one 128-bit access held in registers (Algorithm 1 line 7/10).
 // span0: flat index of the first element of the workgroup-wide access (uniform, multiple of 1024);
 // the thread's elements are span0 + 4*threadIdx.x + k.
+// own: if not NULL, the words are also written there at word index own_word0 + (thread's word) (the
+// copy of this rank's own chunk in its server's input).
 __device__ __forceinline__ void sign_pack_store(v4f z, float s, float* __restrict__ err,
-                                                uint32_t* __restrict__ packed, int64_t span0) {
+                                                uint32_t* __restrict__ packed, int64_t span0,
+                                                uint32_t* __restrict__ own = nullptr, int64_t own_word0 = 0) {
   unsigned int nib = 0;
   v4f e;
 #pragma unroll
@@ -373,7 +376,10 @@ __device__ __forceinline__ void sign_pack_store(v4f z, float s, float* __restric
   }
   st4(err + span0 + threadIdx.x * 4, e);
   const unsigned int word = gather_word(nib);
-  if ((threadIdx.x & 7) == 0) (packed + (span0 >> 5))[threadIdx.x >> 3] = word;
+  if ((threadIdx.x & 7) == 0) {
+    (packed + (span0 >> 5))[threadIdx.x >> 3] = word;
+    if (own) (own + own_word0)[threadIdx.x >> 3] = word;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -428,6 +434,13 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
 // adds 2^32 - tpc to the counter (arrivals back to 0, generation + 1); the others wait for a flag
 // of generation + 1.  All of it wraps harmlessly.
 // ---------------------------------------------------------------------------------------------
+// Second destination of the worker's chunk `chunk` (see ob_lamb_state.own_packed_in); packed == NULL: none.
+struct OwnCopy {
+  uint32_t* packed;   // [n_c/32]
+  float* scale;       // [1]
+  int chunk;
+};
+
 struct ChunkSync {
   double* partials;             // [tiles of the launching kernel]
   unsigned long long* counter;  // [chunks * CTR_STRIDE] (generation << 32) | arrivals
@@ -533,7 +546,7 @@ template <int U, int G, bool HAS_K, bool PACKED_M, int MINW = 4, int GT = 0>
 __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
     GradSrc g, const float* __restrict__ m, PackedMom pm,
     float* __restrict__ err, uint32_t* __restrict__ packed, float* __restrict__ scales,
-    ChunkSync cs, int64_t n_c, int tpc, float beta1, float omb1, LayerTab lt) {
+    ChunkSync cs, int64_t n_c, int tpc, float beta1, float omb1, LayerTab lt, OwnCopy oc) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
@@ -581,10 +594,13 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
   else stream(std::false_type{});
   const double part = block_sum(acc, lds);
   const float s = chunk_barrier_scale(cs, p.t, p.c, tpc, n_c, part, lds, &bc, scales);
+  uint32_t* own = (oc.packed && p.c == oc.chunk) ? oc.packed : nullptr;   // uniform
+  const int64_t own_tile0 = (p.tile0 - (int64_t)p.c * n_c) >> 5;           // the tile's first word within its chunk
+  if (own && p.t == p.c * tpc && threadIdx.x == 0) *oc.scale = s;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
-    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + u * SPAN);
+    if (o < p.len) sign_pack_store(Z[u], s, err, packed, p.tile0 + u * SPAN, own, own_tile0 + u * (SPAN / 32));
   }
 }
 
@@ -1273,6 +1289,123 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
       for (int k = 0; k < 4; ++k) xn[k] = X[u][k] - a * rt.VZ[u][k];
       st4(aa.x + p.tile0 + o, xn);
       if (LPX) st4_lp(aa.x_lp, p.tile0 + o, xn, aa.x_lp_bf16);
+    }
+  }
+}
+
+// The same step for tiles of U spans with U too large to hold v_fresh, v_frozen and x of the whole
+// tile at once: the ratio pass streams the tile G spans at a time (v_fresh is written back as it
+// goes, the last group after the arrival) and keeps only v_frozen -- turned into
+// m_t/(sqrt(v_frozen)+eta) while the layer completes -- and one sign nibble per span; x is fetched
+// only after the layer's coefficient is known, G spans at a time.  Per element 4 bytes live across
+// the barrier instead of 8, so a layer of twice the size fits on the device.
+template <int U, int G, bool HAS_K, bool LPX = false>
+__global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_stream(
+    RatioArgs ra, ApplyArgs aa, LayerSync ls, LayerTab lt) {
+  static_assert(U % G == 0 && U % 8 == 0, "tile shape");
+  constexpr int TILE = SPAN * U;
+  __shared__ float lds[BLOCK / WAVE];
+  __shared__ unsigned long long bc;
+  const int64_t n_c = ls.lt.n_c;
+  const int tpc = ls.lt.tpc;
+  const TilePos p = tile_pos<TILE>(n_c, tpc, ls.lt.tile_list[blockIdx.x]);
+  const int sp0 = p.c * ls.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span
+  const int l0 = lt.first_layer[sp0];  // the layer the tile lies in
+  const float ss = ra.sscales[p.c];
+  const float s_prev = ra.pm.scales[p.c];
+  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const LayerParts lp = layer_parts(ls.lt, l0);
+  const float rp = ls.r_prev[l0], ca = ls.c_avg[l0];
+  const int o0 = threadIdx.x * 4;
+  // the two magnitudes the reconstructed gradient can take (see RatioTile::uniform_pass)
+  const float sp = HAS_K ? ss / kt : ss;
+  const float bm = ra.beta1 * (HAS_K ? s_prev / kt : s_prev);
+  const float g_same = (sp - bm) / ra.omb1;
+  const float g_diff = (sp - (-bm)) / ra.omb1;
+  const float t_same = ra.omb2 * (g_same * g_same);
+  const float t_diff = ra.omb2 * (g_diff * g_diff);
+  v4f VZ[U];
+  unsigned int NBP[U / 8];   // the new momentum's sign nibbles, 8 spans to a register
+  v4f VFl[G];                // fresh variance of the last group: stored after the arrival
+#pragma unroll
+  for (int i = 0; i < U / 8; ++i) NBP[i] = 0u;
+  float r = 0.0f;
+#pragma unroll
+  for (int u0 = 0; u0 < U; u0 += G) {
+    unsigned int NB[G], OBt[G];
+    v4f VF[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int u = u0 + j, o = u * SPAN + o0;
+      NB[j] = 0u; OBt[j] = 0u; VF[j] = 0.0f; VZ[u] = 0.0f;
+      if (o < p.len) {
+        NB[j] = load_nibble(ra.packed, p.tile0 + u * SPAN);
+        OBt[j] = load_nibble(ra.pm.bits, p.tile0 + u * SPAN);
+        VF[j] = ld4(ra.v_fresh + p.tile0 + o);
+        VZ[u] = ld4(ra.v_frozen + p.tile0 + o);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int u = u0 + j, o = u * SPAN + o0;
+      if (o < p.len) {
+        v4f vf;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float t = (((NB[j] ^ OBt[j]) >> k) & 1u) ? t_diff : t_same;
+          vf[k] = ra.beta2 * VF[j][k] + t;
+          const float q = VZ[u][k] / vf[k];
+          if (q > r) r = q;
+        }
+        if (u0 + G < U) st4(ra.v_fresh + p.tile0 + o, vf);
+        else VFl[j] = vf;
+        NBP[u / 8] |= (NB[j] & 15u) << (4 * (u % 8));
+      }
+    }
+  }
+  r = block_max(r, lds);
+  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    const int o = (U - G + j) * SPAN + o0;
+    if (o < p.len) st4(ra.v_fresh + p.tile0 + o, VFl[j]);
+  }
+  // m_t/(sqrt(v_frozen)+eta) in place of v_frozen while the layer completes (the same operations on
+  // the same operands as apply_uniform's)
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float mt = ((NBP[u / 8] >> (4 * (u % 8) + k)) & 1u) ? sp : -sp;
+        float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
+        asm volatile("" : "+v"(uu));   // evaluated here, not sunk below the wait
+        VZ[u][k] = uu;
+      }
+    }
+  }
+  const float c = layer_wait(ls, l0, &bc);
+  const float a = aa.lr * c;
+#pragma unroll
+  for (int u0 = 0; u0 < U; u0 += G) {
+    v4f X[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int o = (u0 + j) * SPAN + o0;
+      X[j] = 0.0f;
+      if (o < p.len) X[j] = ld4(aa.x + p.tile0 + o);
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int o = (u0 + j) * SPAN + o0;
+      if (o < p.len) {
+        v4f xn;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xn[k] = X[j][k] - a * VZ[u0 + j][k];
+        st4(aa.x + p.tile0 + o, xn);
+        if (LPX) st4_lp(aa.x_lp, p.tile0 + o, xn, aa.x_lp_bf16);
+      }
     }
   }
 }

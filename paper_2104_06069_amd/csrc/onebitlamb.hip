@@ -55,6 +55,24 @@ constexpr int TILE_RES = SPAN * U_RES;
 #endif
 constexpr int U_LB = OB_U_LB;  // ... in the fused ratio+update kernel (v_frozen and signs stay in registers)
 constexpr int TILE_LB = SPAN * U_LB;
+#ifndef OB_U_WU
+#define OB_U_WU 8
+#endif
+// 1: the ratio+update kernel streams its tile and fetches x after the layer's coefficient is known
+// (k_ratios_apply_stream; half the registers per element across the barrier), OB_G_LB spans at a time
+#ifndef OB_LB_STREAM
+#define OB_LB_STREAM 0
+#endif
+#ifndef OB_G_LB
+#define OB_G_LB 2
+#endif
+// safety margin, in tiles, under 80 % of the device's workgroup slots for the largest layer a
+// barrier kernel takes
+#ifndef OB_SPLIT_MARGIN
+#define OB_SPLIT_MARGIN 8
+#endif
+constexpr int U_WU = OB_U_WU;  // ... in the single-pass warmup kernel (u and x stay in registers)
+constexpr int TILE_WU = SPAN * U_WU;
 #ifndef OB_G_WU
 #define OB_G_WU 2
 #endif
@@ -115,6 +133,8 @@ struct LayerSplit {
   int* d_seg_end = nullptr;                //     layer's listed tiles cover
   float* d_listed_max = nullptr;           // [n_fused_tiles] partial results of the listed tiles
   double* d_listed_sums = nullptr;         // [2*n_fused_tiles]
+  int tile = 0;             // elements per listed tile
+  int tpc = 0;              // such tiles per chunk
   int* d_rest_tiles = nullptr;
   unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
   unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] (generation << 32) | arrivals
@@ -165,7 +185,6 @@ struct ob_lamb_ctx {
   // kernels with a per-layer barrier (k_ratios_apply_resident, k_warmup_resident): their common
   // tiling (TILE_LB; the segment arrays are those of the TILE_MAIN tiling) and, for each, the split
   // of the work between it and the plain kernels
-  int tpc_lb = 0;
   LayerSplit sp_apply;                     // ob_lamb_ratios_apply
   LayerSplit sp_warm;                      // ob_lamb_warmup_step
   size_t device_bytes = 0;                 // device memory this context holds (tables + workspace)
@@ -383,10 +402,11 @@ struct SplitPlan {
   int64_t n_layers = 0, n_params = 0;
 };
 
-// tl / tm: the TILE_LB and TILE_MAIN tilings; max_tiles: the largest number of tiles of one layer
-// the barrier kernel may hold (0: it is not used).  No HIP call.
-void plan_split(const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off, int64_t n_c,
-                int64_t L, int64_t max_tiles, SplitPlan* pl) {
+// tl / tm: the barrier kernel's tiling (tiles of tile_lb elements) and the TILE_MAIN tiling;
+// max_tiles: the largest number of tiles of one layer the barrier kernel may hold (0: it is not
+// used).  No HIP call.
+void plan_split(const Tiling& tl, int64_t tile_lb, const Tiling& tm, const std::vector<int64_t>& h_off,
+                int64_t n_c, int64_t L, int64_t max_tiles, SplitPlan* pl) {
   pl->has_listed.assign((size_t)L, 0);
   pl->n_listed.assign((size_t)L, 0);
   pl->list_begin.assign((size_t)L, 0);
@@ -395,8 +415,8 @@ void plan_split(const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& 
   pl->covered.assign((size_t)tm.n_tiles, 0);
   auto tile_range = [&](int64_t t, int64_t* tile0, int64_t* tile1) {
     const int64_t c = t / tl.tpc, b = t % tl.tpc;
-    *tile0 = c * n_c + b * TILE_LB;
-    *tile1 = std::min(*tile0 + (int64_t)TILE_LB, (c + 1) * n_c);
+    *tile0 = c * n_c + b * tile_lb;
+    *tile1 = std::min(*tile0 + tile_lb, (c + 1) * n_c);
   };
   // tiles inside one layer, per layer in position order
   std::vector<std::vector<int>> inside((size_t)L);
@@ -421,7 +441,7 @@ void plan_split(const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& 
       pl->fused_tiles.push_back((int)t);
       pl->n_params += tile1 - tile0;
       const int64_t c = t / tl.tpc, b = t % tl.tpc;
-      const int64_t span0 = c * tm.tpc + b * (TILE_LB / TILE_MAIN);
+      const int64_t span0 = c * tm.tpc + b * (tile_lb / TILE_MAIN);
       const int64_t nspan = (tile1 - tile0 + TILE_MAIN - 1) / TILE_MAIN;
       for (int64_t j2 = 0; j2 < nspan; ++j2) pl->covered[(size_t)(span0 + j2)] = 1;
       // each of these spans lies inside the layer: one segment each, consecutive
@@ -435,11 +455,13 @@ void plan_split(const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& 
 }
 
 // Plans and uploads one LayerSplit.
-bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, const Tiling& tm, const std::vector<int64_t>& h_off,
-                 int64_t max_tiles, LayerSplit* sp) {
+bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, int tile_lb, const Tiling& tm,
+                 const std::vector<int64_t>& h_off, int64_t max_tiles, LayerSplit* sp) {
   const int64_t L = ctx->L;
   SplitPlan pl;
-  plan_split(tl, tm, h_off, ctx->n_c, L, max_tiles, &pl);
+  plan_split(tl, tile_lb, tm, h_off, ctx->n_c, L, max_tiles, &pl);
+  sp->tile = tile_lb;
+  sp->tpc = (int)tl.tpc;
   sp->n_layers = pl.n_layers;
   sp->n_params = pl.n_params;
   sp->on = !pl.fused_tiles.empty();
@@ -465,7 +487,7 @@ ListedTiles listed_tiles(const ob_lamb_ctx* ctx, const LayerSplit& sp) {
   ListedTiles lt;
   lt.tile_list = sp.d_fused_tiles; lt.list_begin = sp.d_list_begin; lt.n_listed = sp.d_n_listed;
   lt.seg_first = sp.d_seg_first; lt.seg_end = sp.d_seg_end; lt.layer_seg0 = ctx->d_layer_seg0;
-  lt.n_c = ctx->n_c; lt.tpc = ctx->tpc_lb; lt.tpc_span = ctx->tpc;
+  lt.n_c = ctx->n_c; lt.tpc = sp.tpc; lt.tpc_span = ctx->tpc;
   return lt;
 }
 
@@ -473,7 +495,7 @@ ListedTiles listed_tiles(const ob_lamb_ctx* ctx, const LayerSplit& sp) {
 // CU may hold: 80 % of the device's slots, or the configuration's fused_max_tiles if that is lower
 // (cap; 0 = none).
 int64_t split_max_tiles(int per_cu, int cus, int32_t cap) {
-  int64_t max_tiles = (4 * (int64_t)per_cu * cus) / 5 - 8;
+  int64_t max_tiles = (4 * (int64_t)per_cu * cus) / 5 - OB_SPLIT_MARGIN;
   if (cap > 0 && cap < max_tiles) max_tiles = cap;
   return max_tiles < 0 ? 0 : max_tiles;
 }
@@ -636,7 +658,7 @@ ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8
     if (!build_tiling(TILE_MAIN, n_c, W, L, h_off, &tm) || !build_tiling(TILE_LB, n_c, W, L, h_off, &tl))
       return OB_ERR_ARG;
     SplitPlan pl;
-    plan_split(tl, tm, h_off, n_c, L, max_tiles, &pl);
+    plan_split(tl, TILE_LB, tm, h_off, n_c, L, max_tiles, &pl);
     for (int64_t t = 0; t < tm.n_tiles; ++t) span_owner[t] = pl.covered[(size_t)t] ? 2 : 0;
     for (int t : pl.rest_tiles) span_owner[t] = 1;
     for (int64_t l = 0; l < L; ++l) layer_listed[l] = pl.n_listed[(size_t)l];
@@ -681,15 +703,15 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   ctx->tpc_srv = (int)tpc_srv;
 
   const std::vector<int64_t> h_off = host_offsets(cfg);
-  Tiling tm, tl;
+  Tiling tm, tl, tw;
   if (!build_tiling(TILE_MAIN, ctx->n_c, ctx->W, L, h_off, &tm) ||
-      !build_tiling(TILE_LB, ctx->n_c, ctx->W, L, h_off, &tl))
+      !build_tiling(TILE_LB, ctx->n_c, ctx->W, L, h_off, &tl) ||
+      !build_tiling(TILE_WU, ctx->n_c, ctx->W, L, h_off, &tw))
     return OB_ERR_ARG;
   const int64_t n_tiles = tm.n_tiles;
   ctx->tpc = (int)tm.tpc;
   ctx->n_tiles = (int)tm.n_tiles;
   ctx->n_segs = (int)tm.seg_layer.size();
-  ctx->tpc_lb = (int)tl.tpc;
   const std::vector<int>&first = tm.first, &tile_seg0 = tm.tile_seg0, &seg_layer = tm.seg_layer,
                         &layer_seg0 = tm.layer_seg0;
 
@@ -749,10 +771,14 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   if (ok) {
     int per_cu_a = 0, per_cu_w = 0, cus = 0;
     ok = hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
+#if OB_LB_STREAM
+                         &per_cu_a, k_ratios_apply_stream<U_LB, OB_G_LB, true>, BLOCK, 0),
+#else
                          &per_cu_a, k_ratios_apply_resident<U_LB, true>, BLOCK, 0),
+#endif
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                         &per_cu_w, k_warmup_resident<U_LB, G_WU, 0, false>, BLOCK, 0),
+                         &per_cu_w, k_warmup_resident<U_WU, G_WU, 0, false>, BLOCK, 0),
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
@@ -760,8 +786,8 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                               ? 0 : split_max_tiles(std::min(per_cu_a, OB_LB_MINW), cus, cfg->fused_max_tiles);
     const int64_t max_w = (cfg->flags & OB_CFG_TWO_PASS_WARMUP)
                               ? 0 : split_max_tiles(std::min(per_cu_w, OB_WU_MINW), cus, cfg->fused_max_tiles);
-    ok = ok && build_split(ctx, tl, tm, h_off, max_a, &ctx->sp_apply) &&
-         build_split(ctx, tl, tm, h_off, max_w, &ctx->sp_warm);
+    ok = ok && build_split(ctx, tl, TILE_LB, tm, h_off, max_a, &ctx->sp_apply) &&
+         build_split(ctx, tw, TILE_WU, tm, h_off, max_w, &ctx->sp_warm);
   }
   ok = ok && upload(ctx, &ctx->d_first_layer_res, first_res) &&
        alloc_zero(ctx, &ctx->d_partials_res, (size_t)ctx->n_tiles_res) &&
@@ -858,7 +884,7 @@ ob_status ob_lamb_warmup_step_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   ws.c_min = ctx->c_min; ws.c_max = ctx->c_max; ws.beta3 = ctx->beta3; ws.omb3 = ctx->omb3;
   dispatch2(lpg, xl.p != nullptr, [&](auto lg, auto lx) {
     OB_LAUNCH(la, KID_WARMUP_RESIDENT,
-              (k_warmup_resident<U_LB, G_WU, decltype(lg)::value ? 1 : 0, decltype(lx)::value>), sp.n_fused_tiles,
+              (k_warmup_resident<U_WU, G_WU, decltype(lg)::value ? 1 : 0, decltype(lx)::value>), sp.n_fused_tiles,
               gs, st->m, st->v_fresh, st->x, ws, ctx->beta1, ctx->omb1, ctx->beta2, ctx->omb2, ctx->eta, ctx->wd,
               lr, lt, xl.p, xl.bf16);
   });
@@ -899,6 +925,10 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   PackedMom pm;
   if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
   if (packed_m && st->m_packed == packed_out) return OB_ERR_ARG;  // would be overwritten while read
+  if ((st->own_packed_in == nullptr) != (st->own_scale_in == nullptr)) return OB_ERR_NULL;
+  if (st->own_packed_in && misaligned(st->own_packed_in)) return OB_ERR_ALIGN;
+  OwnCopy oc;
+  oc.packed = st->own_packed_in; oc.scale = st->own_scale_in; oc.chunk = ctx->server_chunk;
   Launch la(ctx, hip_stream);
   if (ctx->resident) {
     ChunkSync cs;
@@ -914,7 +944,7 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
                   (k_compress_resident<U_RES, G_RES, decltype(hk)::value, decltype(pk)::value, OB_RES_MINW,
                                        decltype(lg)::value ? 1 : 0>),
                   ctx->n_tiles_res, gs, st->m, pm, st->err_worker, packed_out, scales_out, cs, ctx->n_c,
-                  ctx->tpc_res, ctx->beta1, ctx->omb1, lt);
+                  ctx->tpc_res, ctx->beta1, ctx->omb1, lt, oc);
       });
     });
     return la.ok ? OB_OK : OB_ERR_HIP;
@@ -931,6 +961,16 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   OB_LAUNCH_B(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, FBLOCK, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out);
   OB_LAUNCH(la, KID_SIGN_PACK, (k_sign_pack_error<U_MAIN>), ctx->n_tiles, st->err_worker, packed_out,
             scales_out, ctx->n_c, ctx->tpc);
+  if (oc.packed) {   // the two-pass form copies the rank's own chunk afterwards
+    const int64_t wpc = ctx->n_c / 32;
+    la.begin(KID_COPY, true);
+    if (la.ok)
+      la.ok = hip_ok(ctx, hipMemcpyAsync(oc.packed, packed_out + (int64_t)oc.chunk * wpc, (size_t)wpc * 4,
+                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync") &&
+              hip_ok(ctx, hipMemcpyAsync(oc.scale, scales_out + oc.chunk, sizeof(float),
+                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
+    la.end("copy", true);
+  }
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -1050,9 +1090,15 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
+#if OB_LB_STREAM
+    OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
+              (k_ratios_apply_stream<U_LB, OB_G_LB, decltype(k_)::value, decltype(lx)::value>), sp.n_fused_tiles,
+              ra, aa, ls, lt);
+#else
     OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
               (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), sp.n_fused_tiles, ra,
               aa, ls, lt);
+#endif
   });
   // 3. update of everything outside the listed tiles, with the coefficients of steps 1 and 2
   launch_apply(la, ctx, st, packed_all, server_scales, lr, sp.d_rest_tiles, sp.n_rest_tiles, xl);

@@ -28,12 +28,15 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
                  packed_momentum=False, fused_apply=False, x_lp_dtype=None, grad_scale=1.0,
-                 status_interval=64, **hyper):
+                 status_interval=64, fold_gather=True, **hyper):
         """hyper: the fields of ob_lamb_config (hyper-parameters, flags, fused_max_tiles, spin_limit).
         status_interval: every that many optimizer steps step()/warmup_step() ask the library whether a
         bounded device-side wait has expired (one stream synchronisation; raises ObLambError with
         OB_ERR_STATE if so, after which the state must be restored from a checkpoint); 0 = never,
         the caller calls check_status() itself."""
+        # fold_gather: compress_local also writes this rank's own chunk straight into its server's
+        # input slot, so gather() has nothing left to copy
+        self.fold_gather = bool(fold_gather)
         self.status_interval = int(status_interval)
         self._steps_since_check = 0
         self.device = torch.device(device)
@@ -88,6 +91,10 @@ class DeviceStep:
     def _state(self, momentum):
         """ob_lamb_state for one call.  momentum: 'read' (source of m_{t-1}) or 'commit'."""
         b = dict(self.t)
+        if self.fold_gather:
+            wpc = self.n_c // 32
+            b["own_packed_in"] = self.packed_in[self.c * wpc:]
+            b["own_scale_in"] = self.scales_in[self.c:]
         if self.packed_momentum and momentum == "commit":
             b["m"] = None                       # committed in place: packed_all is the momentum
             b["m_packed"], b["m_scales"] = self.packed_all, self.server_scales
@@ -202,7 +209,10 @@ class DeviceStep:
                                          self.grad_scale, self.packed_local, self.scales_local, self.stream)
 
     def gather(self):
-        """Own chunk c of the worker output -> slot c of the server's input (device copies)."""
+        """Own chunk c of the worker output -> slot c of the server's input (device copies; already
+        done by compress_local when fold_gather is on)."""
+        if self.fold_gather:
+            return
         wpc = self.n_c // 32
         self.packed_in[self.c * wpc:(self.c + 1) * wpc].copy_(
             self.packed_local[self.c * wpc:(self.c + 1) * wpc], non_blocking=True)

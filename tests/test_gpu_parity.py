@@ -475,8 +475,36 @@ def test_argument_errors():
     with pytest.raises(ob.ObLambError) as e:
         ob.ob_lamb_compress_local(dev.ctx, alias, g, dev.packed_local, dev.scales_local)
     assert e.value.status == -2
+    # the second destination of the rank's own chunk: both pointers or neither
+    half = ob.make_state(**dict(dev.t, own_packed_in=dev.packed_in))
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_compress_local(dev.ctx, half, g, dev.packed_local, dev.scales_local)
+    assert e.value.status == -1
     torch.cuda.synchronize()
     assert np.array_equal(dev.get("x"), x0)
+    finish(dev)
+
+
+@pytest.mark.parametrize("two_pass", [False, True], ids=["single_pass", "two_pass"])
+@pytest.mark.parametrize("case", ["odd", "bert_mini"])
+def test_own_chunk_written_into_the_server_input(case, two_pass):
+    """ob_lamb_compress_local with ob_lamb_state.own_packed_in / own_scale_in: the served chunk of the
+    worker output lands in its slot of the server's input as well (what the exchange's copy of the
+    rank's own data would do), and nothing else of that buffer is touched."""
+    _need_gpu()
+    cfg = make_case(case)
+    st, ref, dev = start_pair(cfg, two_pass=two_pass)
+    assert dev.fold_gather
+    g = gradient(st, cfg, 0)
+    fw, fs = foreign_worker_chunks(st, cfg, 0)
+    dev.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+    dev.scales_in.copy_(torch.from_numpy(fs))
+    ref.set_foreign_in(fw, fs)
+    ref.compress_local(g); ref.gather()
+    dev.compress_local(torch.from_numpy(g).to(dev.device)); dev.gather()
+    assert np.array_equal(words_of(dev.packed_in), ref.bits_in)
+    assert np.array_equal(dev.scales_in.cpu().numpy(), ref.scales_in)
+    assert np.array_equal(words_of(dev.packed_local), ref.bits_local)
     finish(dev)
 
 
@@ -823,12 +851,13 @@ def test_gpu_rank_inside_a_simulated_job(packed, fused, use_k):
             rk.decompress_apply(lr)
         # --- the device as rank r: its own gradient, the peers' chunks r, the peers' server outputs
         dev.begin_step()
+        dev.packed_in.copy_(torch.from_numpy(ranks[r].bits_in.view(np.int32)))   # the all-to-all's result ...
+        dev.scales_in.copy_(torch.from_numpy(ranks[r].scales_in))
+        dev.packed_in[r * (n_c // 32):(r + 1) * (n_c // 32)].zero_()             # ... own slot comes from the device
+        dev.scales_in[r] = 0.0                                                   #     (compress_local / gather())
         dev.compress_local(torch.from_numpy(grads[r]).to(dev.device))
         assert np.array_equal(words_of(dev.packed_local), ranks[r].bits_local), f"step {t}: what rank r sends"
         assert_close(dev.scales_local.cpu().numpy(), ranks[r].scales_local, "worker scales")
-        dev.packed_in.copy_(torch.from_numpy(ranks[r].bits_in.view(np.int32)))   # the all-to-all's result ...
-        dev.scales_in.copy_(torch.from_numpy(ranks[r].scales_in))
-        dev.packed_in[r * (n_c // 32):(r + 1) * (n_c // 32)].zero_()             # ... own slot comes from gather()
         dev.gather()
         dev.packed_all.copy_(torch.from_numpy(bits_all.view(np.int32)))          # the all-gather's result ...
         dev.server_scales.copy_(torch.from_numpy(sscales))
