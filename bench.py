@@ -30,6 +30,7 @@ HYPER = dict(beta1=0.9, beta2=0.999, beta3=0.9, eta=1e-6, c_min=0.01, c_max=0.3,
 KERNEL_BYTES = {
     "dense": {   # momentum read and written as an fp32 array
         "compress_resident": (16.125, "n_pad"),  # R g, m, err (12) + W err (4) + W bits (1/8)
+        "compress_deferred": (16.25, "n_pad"),   # R g, m, z (12), own previous bits (1/8) + W z (4), bits (1/8)
         "momentum_z_sumsq": (16.0, "n_pad"),     # R g, m, err (12) + W z (4)
         "ratios_pass": (16.125, "n_pad"),        # R bits, m, v_fresh, v_frozen (12.125) + W v_fresh (4)
         "decompress_apply": (16.125, "n_pad"),   # R bits, v_frozen, x (8.125) + W x, m (8)
@@ -37,6 +38,7 @@ KERNEL_BYTES = {
     },
     "packed": {  # momentum read from last step's sign words, never written as fp32
         "compress_resident": (12.25, "n_pad"),   # R g, err (8) + m bits (1/8) + W err (4) + bits (1/8)
+        "compress_deferred": (12.375, "n_pad"),  # R g, z (8), m bits, own previous bits (1/4) + W z (4), bits (1/8)
         "momentum_z_sumsq": (12.125, "n_pad"),
         "ratios_pass": (12.25, "n_pad"),         # R bits, m bits (1/4), v_fresh, v_frozen (8) + W v_fresh (4)
         "decompress_apply": (12.125, "n_pad"),   # R bits, v_frozen, x (8.125) + W x (4)
@@ -63,13 +65,14 @@ def fp32_momentum_equivalent_bytes_per_param(W):
     return 16.125 + 0.125 + 8.125 / W + 16.125 + 12.0
 
 
-def algorithmic_step_bytes_per_param(W, mode, fused_frac, single_pass_compress, server_single_pass):
+def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_single_pass):
     """What the calls as implemented must move (each kernel's inputs once, outputs once).
     fused_frac: share of the parameters whose ratio pass and update run as one kernel
     (ob_lamb_ratios_apply), reading v_frozen and the sign words once."""
     k = KERNEL_BYTES[mode]
     separate = k["ratios_pass"][0] + k["decompress_apply"][0]
-    compress = k["compress_resident"][0] if single_pass_compress else k["momentum_z_sumsq"][0] + 8.125
+    compress = {"deferred": k["compress_deferred"][0], "barrier": k["compress_resident"][0],
+                "two_pass": k["momentum_z_sumsq"][0] + 8.125}[compress_form]
     server = (0.125 + 8.125 / W) if server_single_pass else (0.125 + 16.125 / W)
     return (compress + fused_frac * k["ratios_apply_resident"][0] + (1.0 - fused_frac) * separate + server)
 
@@ -93,7 +96,8 @@ class Workload:
         # a momentum that a LAMB step has formed (below)
         self.ds = DeviceStep(self.pl.offsets, self.W, self.server_chunk, device="cuda:0", mom_scale=None,
                              packed_momentum=(self.mode == "packed"), fused_apply=not args.separate_calls,
-                             x_lp_dtype=tdt[args.x_lp], status_interval=0, **HYPER)
+                             x_lp_dtype=tdt[args.x_lp], status_interval=0,
+                             deferred_error=not args.barrier_compress, **HYPER)
         ds = self.ds
         ds.load_state(init_state(st, cfg))
         self.grads = [gradient(st, cfg, t).to(tdt[args.grad_dtype]) for t in range(3)]
@@ -165,9 +169,14 @@ class Workload:
     def step_bytes(self, g_less, x_more):
         ob, ds = self.ob, self.ds
         return (algorithmic_step_bytes_per_param(self.W, self.mode, self.fused_params / float(ds.n_pad),
-                                                 ob.ob_lamb_uses_single_pass(ds.ctx),
+                                                 self.compress_form(),
                                                  ob.ob_lamb_server_single_pass(ds.ctx) > 0)
                 - g_less + x_more) * ds.n_pad
+
+    def compress_form(self):
+        if self.ds.deferred_error:
+            return "deferred"
+        return "barrier" if self.ob.ob_lamb_uses_single_pass(self.ds.ctx) else "two_pass"
 
     def warmup_reference(self, reps=5):
         """One uncompressed LAMB step (eq. (1)) on the same buffers, timed alone."""
@@ -223,7 +232,7 @@ def brief(name, args, torch, steps, graph_too=False):
            "step_algorithmic_bytes": b,
            "step_algorithmic_pct_of_hbm_peak": round(100 * b / (mean * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
            "fused_share": round(w.fused_params / float(w.ds.n_pad), 4),
-           "single_pass_compress": bool(w.ob.ob_lamb_uses_single_pass(w.ds.ctx)),
+           "compress_form": w.compress_form(),
            "server_single_pass": int(w.ob.ob_lamb_server_single_pass(w.ds.ctx))}
     if graph_too:
         gm, gmed = w.timed(steps + steps % 2, args.warmup, graph=True)
@@ -265,6 +274,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds two consecutive steps (for launch-bound "
                          "sizes; --steps must be even)")
+    ap.add_argument("--barrier-compress", action="store_true",
+                    help="ob_lamb_compress_local as one kernel with a chunk barrier that writes the error itself "
+                         "(default: the deferred error form, one barrier-free pass)")
     ap.add_argument("--dense-momentum", action="store_true",
                     help="keep the momentum as an fp32 array (default: the 1-bit form it has after "
                          "Algorithm 1 line 13; same results, 12 bytes/param less traffic)")
@@ -355,7 +367,7 @@ def main():
     KB["server_resident"] = (W / 8.0 + 8.125, "n_c")   # R W*bits, err (4) + W err (4), bits (1/8)
     g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
-    for k in ("compress_resident", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):
+    for k in ("compress_resident", "compress_deferred", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):
         KB[k] = (KB[k][0] - g_less, KB[k][1])
     for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply", "warmup_resident"):
         KB[k] = (KB[k][0] + x_more, KB[k][1])
@@ -411,7 +423,7 @@ def main():
                    "grad_dtype": args.grad_dtype, "x_lp": args.x_lp, "graph_replay": bool(args.graph),
                    "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
                    "fused_params": fused_params,
-                   "single_pass_compress": ob.ob_lamb_uses_single_pass(ds.ctx),
+                   "compress_form": wl.compress_form(),
                    "server_single_pass": ob.ob_lamb_server_single_pass(ds.ctx)},
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),

@@ -121,7 +121,29 @@ typedef struct ob_lamb_state {
    * own data.  Both or neither; NULL = not written. */
   uint32_t* own_packed_in; /* [n_c/32] or NULL */
   float* own_scale_in;     /* [1] or NULL */
+  /* The worker error in deferred form (optional, see below): this worker's own previous packed
+   * output and its scales.  Both or neither. */
+  const uint32_t* err_packed; /* [N_pad/32] or NULL */
+  const float* err_scales;    /* [W] or NULL */
 } ob_lamb_state;
+
+/* Worker error representation.  Algorithm 1 line 7 leaves delta = z - C[z] in the error buffer, and
+ * C[z] needs the chunk's scale, i.e. a reduction over the whole chunk, before any delta can be
+ * written: that is what forces ob_lamb_compress_local into two passes or an in-kernel barrier.  The
+ * subtraction can wait until the next step instead.  With err_packed / err_scales non-NULL,
+ *   - err_worker holds z of the previous call, and ob_lamb_compress_local reads the carried error as
+ *     err_worker[i] - (bit_i ? +s_c : -s_c) with the bits and scales of err_packed / err_scales --
+ *     the same binary32 subtraction, on the same operands, as line 7's;
+ *   - it writes the new z to err_worker, its sign words to packed_out and the scales to scales_out,
+ *     which are the err_packed / err_scales of the next call.  They may be the very same buffers
+ *     (err_packed == packed_out, err_scales == scales_out): pass the worker's output buffers and
+ *     leave them untouched between the steps.
+ * The call is then ONE streaming kernel plus a W-workgroup kernel for the scales: no in-kernel
+ * barrier, nothing read twice.  Results are bit-identical to the other forms.  An err_scales of all
+ * zeros makes err_worker an ordinary error buffer (x - (+-0) = x): that is how a run starts, or
+ * resumes from a dense error.  ob_lamb_error_dense writes the error itself, delta, to err_out
+ * [N_pad] (err_out may be st->err_worker if the caller then zeroes err_scales). */
+ob_status ob_lamb_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* err_out, void* hip_stream);
 
 /* Momentum representation.  After line 13 of any compression step the global momentum is exactly
  * m[i] = (bit_i ? +s_c : -s_c) / k_l (0 in the padding), i.e. the step's packed_all/server_scales.
@@ -172,7 +194,7 @@ ob_status ob_lamb_freeze(ob_lamb_ctx* ctx, const ob_lamb_state* st, void* hip_st
 
 /* Algorithm 1 lines 6-7 over the whole flat buffer, with Appendix A.5.2's momentum scaling:
  *   z = k_l * (beta1*m + (1-beta1)*grad) + err_worker;   per chunk c: scales_out[c], bits;
- *   err_worker <- z - C[z].
+ *   err_worker <- z - C[z]   (or, in the deferred form described at ob_lamb_state, err_worker <- z).
  * grad: [N_pad] this worker's local gradient.  packed_out: [N_pad/32] words.  scales_out: [W].
  * Reads the momentum (dense or 1-bit form), does not modify it.  In the 1-bit form m_packed must
  * not be the buffer packed_out (OB_ERR_ARG). */

@@ -40,7 +40,8 @@ OB_SPIN_NONE = -1
 class ObLambState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev",
-                 "coeff_c", "mom_scale", "m_packed", "m_scales", "own_packed_in", "own_scale_in")]
+                 "coeff_c", "mom_scale", "m_packed", "m_scales", "own_packed_in", "own_scale_in",
+                 "err_packed", "err_scales")]
 
 
 def lib_path():
@@ -84,6 +85,7 @@ def lib():
             "ob_lamb_warmup_fused_params": (i64, [vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
+            "ob_lamb_error_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_server_single_pass": (i32, [vp]),
@@ -285,6 +287,11 @@ def ob_lamb_warmup_fused_params(ctx):
 def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):
     _check(lib().ob_lamb_momentum_dense(ctx, C.byref(state), _addr(m_out), _addr(stream)), ctx,
            "ob_lamb_momentum_dense")
+
+
+def ob_lamb_error_dense(ctx, state, err_out, stream=None):
+    _check(lib().ob_lamb_error_dense(ctx, C.byref(state), _addr(err_out), _addr(stream)), ctx,
+           "ob_lamb_error_dense")
 
 
 def ob_lamb_momentum_scale(ctx, state, stream=None):

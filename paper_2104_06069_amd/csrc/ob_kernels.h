@@ -206,6 +206,29 @@ struct PackedMom {
   const float* __restrict__ scales;      // [W]
 };
 
+// Second destination of the worker's chunk `chunk` (see ob_lamb_state.own_packed_in); packed == NULL: none.
+struct OwnCopy {
+  uint32_t* packed;   // [n_c/32]
+  float* scale;       // [1]
+  int chunk;
+};
+
+// The worker error in deferred form (only read when DEFER): err holds z of the previous step, and
+// delta = z - C[z] is formed on the fly from the previous step's own sign words and chunk scales,
+// delta[i] = err[i] - (bit_i ? s_c : -s_c) -- the very subtraction of Algorithm 1 line 7, one step
+// late.  With all scales 0 the array is the error itself (x - (+-0) = x).
+struct PackedErr {
+  const uint32_t* bits;     // [N_pad/32] this worker's own previous output (may be packed_out itself)
+  const float* scales;      // [W]        ... and its scales (may be scales_out itself)
+};
+
+__device__ __forceinline__ v4f deferred_error(v4f e, unsigned int nib, float s) {
+  v4f r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = e[k] - (((nib >> k) & 1u) ? s : -s);
+  return r;
+}
+
 // ---------------------------------------------------------------------------------------------
 // z = k_l * (beta1*m + (1-beta1)*g) + err       (Algorithm 1 lines 6-7, Appendix A.5.2)
 // Per-tile constants and the per-access evaluation, shared by the two-pass and single-pass kernels.
@@ -308,39 +331,61 @@ struct ZTile {
 // ---------------------------------------------------------------------------------------------
 // K1 (two-pass path)  z written over err, and the tile's sum of z^2 in fp64.
 // ---------------------------------------------------------------------------------------------
-template <int U, bool HAS_K, bool PACKED_M, int GT = 0>
+// DEFER: the whole of lines 6-7 in this one pass, with no wait for the chunk's scale: the carried
+// error arrives in deferred form (PackedErr), z is written over it AS the next deferred error, and
+// the sign words of z are packed and written here as well (they do not depend on the scale); the
+// scale itself follows from the tile partials in k_chunk_scale.  packed_out / pe.bits may be the
+// same buffer: a word is read and rewritten by the same 8 lanes, in program order.
+template <int U, bool HAS_K, bool PACKED_M, int GT = 0, bool DEFER = false>
 __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
     GradSrc g, const float* __restrict__ m, PackedMom pm,
     float* __restrict__ err, double* __restrict__ partials, int64_t n_c, int tpc, float beta1,
-    float omb1, LayerTab lt) {
+    float omb1, LayerTab lt, PackedErr pe, uint32_t* packed_out, OwnCopy oc) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
   const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
   const int o0 = threadIdx.x * 4;
+  const float se = DEFER ? pe.scales[p.c] : 0.0f;
   v4f G[U], M[U], E[U];
-  unsigned int NB[U];
+  unsigned int NB[U], EB[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
-    M[u] = 0.0f; NB[u] = 0u;
+    M[u] = 0.0f; NB[u] = 0u; EB[u] = 0u;
     if (o < p.len) {
       G[u] = load_grad<GT>(g, p.tile0 + o);
       if (PACKED_M) NB[u] = load_nibble(pm.bits, p.tile0 + u * SPAN);
       else M[u] = ld4(m + p.tile0 + o);
+      if (DEFER) EB[u] = load_nibble(pe.bits, p.tile0 + u * SPAN);
       E[u] = ld4(err + p.tile0 + o);
     }
   }
   ZTile<HAS_K, PACKED_M> zt;
   zt.init(lt, pm, p, beta1);
+  uint32_t* own = (DEFER && oc.packed && p.c == oc.chunk) ? oc.packed : nullptr;   // uniform
+  const int64_t own_tile0 = (p.tile0 - (int64_t)p.c * n_c) >> 5;
   double acc = 0.0;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
-    if (o < p.len) {
+    if (o < p.len) {   // uniform over the wavefront (len is a multiple of 256), as the shuffles below require
+      if (DEFER) E[u] = deferred_error(E[u], EB[u], se);
       const v4f z = zt.z(lt, beta1, omb1, G[u], M[u], NB[u], E[u], p.tile0 + o);
       st4(err + p.tile0 + o, z);
+      unsigned int nib = 0;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) acc += (double)z[k] * (double)z[k];
+      for (int k = 0; k < 4; ++k) {
+        acc += (double)z[k] * (double)z[k];
+        if (DEFER) nib |= ((z[k] >= 0.0f) ? 1u : 0u) << k;
+      }
+      if (DEFER) {
+        const unsigned int word = gather_word(nib);
+        if ((threadIdx.x & 7) == 0) {
+          const int64_t span0 = p.tile0 + u * SPAN;
+          (packed_out + (span0 >> 5))[threadIdx.x >> 3] = word;
+          if (own) (own + own_tile0 + u * (SPAN / 32))[threadIdx.x >> 3] = word;
+        }
+      }
     }
   }
   const double s = block_sum(acc, lds);
@@ -348,14 +393,32 @@ __global__ __launch_bounds__(BLOCK) void k_momentum_z_sumsq(
 }
 
 // scale[c] = sqrt(sum of the chunk's tile partials / n_c), summed in a fixed order.
+// own_scale (may be NULL): also receives the scale of chunk own_chunk.
 __global__ __launch_bounds__(FBLOCK) void k_chunk_scale(const double* __restrict__ partials, int tpc,
-                                                        int64_t n_c, float* __restrict__ scales) {
+                                                        int64_t n_c, float* __restrict__ scales,
+                                                        float* __restrict__ own_scale, int own_chunk) {
   __shared__ double lds[FBLOCK / WAVE];
   const int c = blockIdx.x;
   double a = 0.0;
   for (int j = threadIdx.x; j < tpc; j += FBLOCK) a += partials[(int64_t)c * tpc + j];
   const double S = block_sum<FBLOCK>(a, lds);
-  if (threadIdx.x == 0) scales[c] = (float)sqrt(S / (double)n_c);
+  if (threadIdx.x == 0) {
+    const float sc = (float)sqrt(S / (double)n_c);
+    scales[c] = sc;
+    if (own_scale && c == own_chunk) *own_scale = sc;
+  }
+}
+
+// Dense view of a worker error held in deferred form: out[i] = err[i] - (bit_i ? s_c : -s_c) over the
+// whole padded buffer (out may be err itself).
+__global__ __launch_bounds__(BLOCK) void k_error_dense(const float* __restrict__ err, PackedErr pe,
+                                                       float* __restrict__ out, int64_t n_c, int tpc) {
+  const TilePos p = tile_pos<SPAN>(n_c, tpc, (int)blockIdx.x);
+  const int o = threadIdx.x * 4;
+  if (o >= p.len) return;
+  const float se = pe.scales[p.c];
+  const unsigned int nb = load_nibble(pe.bits, p.tile0);
+  st4(out + p.tile0 + o, deferred_error(ld4(err + p.tile0 + o), nb, se));
 }
 
 // Sign, pack and error update of one 128-bit access held in registers (Algorithm 1 line 7/10).
@@ -434,13 +497,6 @@ __global__ __launch_bounds__(BLOCK) void k_sign_pack_error(float* __restrict__ e
 // adds 2^32 - tpc to the counter (arrivals back to 0, generation + 1); the others wait for a flag
 // of generation + 1.  All of it wraps harmlessly.
 // ---------------------------------------------------------------------------------------------
-// Second destination of the worker's chunk `chunk` (see ob_lamb_state.own_packed_in); packed == NULL: none.
-struct OwnCopy {
-  uint32_t* packed;   // [n_c/32]
-  float* scale;       // [1]
-  int chunk;
-};
-
 struct ChunkSync {
   double* partials;             // [tiles of the launching kernel]
   unsigned long long* counter;  // [chunks * CTR_STRIDE] (generation << 32) | arrivals

@@ -83,6 +83,7 @@ enum KernelId {
   KID_COMPRESS_RESIDENT,
   KID_CHUNK_SCALE,
   KID_SIGN_PACK,
+  KID_COMPRESS_DEFERRED,
   KID_SERVER_AVG,
   KID_SERVER_SCALE,
   KID_SERVER_PACK,
@@ -102,7 +103,7 @@ enum KernelId {
   KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
-    "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "server_unpack_avg",
+    "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "compress_deferred", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
     "decompress_apply", "ratios_apply_resident", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
@@ -930,6 +931,27 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   OwnCopy oc;
   oc.packed = st->own_packed_in; oc.scale = st->own_scale_in; oc.chunk = ctx->server_chunk;
   Launch la(ctx, hip_stream);
+  PackedErr pe;
+  pe.bits = st->err_packed; pe.scales = st->err_scales;
+  if ((st->err_packed == nullptr) != (st->err_scales == nullptr)) return OB_ERR_NULL;
+  if (st->err_packed) {
+    // deferred error: the whole call is one streaming pass plus the scales -- no barrier, no second pass
+    if (misaligned(st->err_packed)) return OB_ERR_ALIGN;
+    if (packed_m && st->m_packed == st->err_packed) return OB_ERR_ARG;
+    const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+    dispatch2(st->mom_scale != nullptr, packed_m, [&](auto hk, auto pk) {
+      dispatch1(lpg, [&](auto lg) {
+        OB_LAUNCH(la, KID_COMPRESS_DEFERRED,
+                  (k_momentum_z_sumsq<U_MAIN, decltype(hk)::value, decltype(pk)::value,
+                                      decltype(lg)::value ? 1 : 0, true>),
+                  ctx->n_tiles, gs, st->m, pm, st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc,
+                  ctx->beta1, ctx->omb1, lt, pe, packed_out, oc);
+      });
+    });
+    OB_LAUNCH_B(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, FBLOCK, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out,
+                oc.scale, oc.chunk);
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
   if (ctx->resident) {
     ChunkSync cs;
     cs.partials = ctx->d_partials_res;
@@ -955,10 +977,11 @@ ob_status ob_lamb_compress_local_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
       OB_LAUNCH(la, KID_MOMENTUM_Z,
                 (k_momentum_z_sumsq<U_MAIN, decltype(hk)::value, decltype(pk)::value, decltype(lg)::value ? 1 : 0>),
                 ctx->n_tiles, gs, st->m, pm, st->err_worker, ctx->d_partials, ctx->n_c, ctx->tpc,
-                ctx->beta1, ctx->omb1, lt);
+                ctx->beta1, ctx->omb1, lt, pe, packed_out, oc);
     });
   });
-  OB_LAUNCH_B(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, FBLOCK, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out);
+  OB_LAUNCH_B(la, KID_CHUNK_SCALE, k_chunk_scale, ctx->W, FBLOCK, ctx->d_partials, ctx->tpc, ctx->n_c, scales_out,
+              (float*)nullptr, 0);
   OB_LAUNCH(la, KID_SIGN_PACK, (k_sign_pack_error<U_MAIN>), ctx->n_tiles, st->err_worker, packed_out,
             scales_out, ctx->n_c, ctx->tpc);
   if (oc.packed) {   // the two-pass form copies the rank's own chunk afterwards
@@ -1010,7 +1033,8 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
   }
   OB_LAUNCH(la, KID_SERVER_AVG, (k_server_unpack_avg<U_SRV>), ctx->tpc_srv, packed_in, scales_in,
             st->err_server, ctx->d_partials_srv, ctx->n_c, (int)ctx->W, ctx->invW);
-  OB_LAUNCH_B(la, KID_SERVER_SCALE, k_chunk_scale, 1, FBLOCK, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out);
+  OB_LAUNCH_B(la, KID_SERVER_SCALE, k_chunk_scale, 1, FBLOCK, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out,
+              (float*)nullptr, 0);
   OB_LAUNCH(la, KID_SERVER_PACK, (k_sign_pack_error<U_SRV>), ctx->tpc_srv, st->err_server, packed_out,
             scale_out, ctx->n_c, ctx->tpc_srv);
   return la.ok ? OB_OK : OB_ERR_HIP;
@@ -1125,6 +1149,17 @@ ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, floa
   else
     OB_LAUNCH(la, KID_MOMENTUM_DENSE, (k_momentum_dense<U_MAIN, false>), ctx->n_tiles, pm, m_out, ctx->n_c,
               ctx->tpc, lt);
+  return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* err_out, void* hip_stream) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(err_out); REQUIRE_PTR(st->err_worker); REQUIRE_PTR(st->err_packed);
+  if (!st->err_scales) return OB_ERR_NULL;
+  PackedErr pe;
+  pe.bits = st->err_packed; pe.scales = st->err_scales;
+  Launch la(ctx, hip_stream);
+  OB_LAUNCH(la, KID_MOMENTUM_DENSE, k_error_dense, ctx->n_tiles, st->err_worker, pe, err_out, ctx->n_c, ctx->tpc);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -1278,7 +1313,8 @@ ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, c
   // reads has been written by the first, so the array's previous contents do not matter
   hipLaunchKernelGGL((k_server_unpack_avg<U_SRV>), dim3((unsigned)tiles), dim3(BLOCK), 0, stream, packed_in,
                      scales_in, err_server, partials, chunk_len, (int)num_workers, invW);
-  hipLaunchKernelGGL(k_chunk_scale, dim3(1), dim3(FBLOCK), 0, stream, partials, tiles, chunk_len, scale_out);
+  hipLaunchKernelGGL(k_chunk_scale, dim3(1), dim3(FBLOCK), 0, stream, partials, tiles, chunk_len, scale_out,
+                     (float*)nullptr, 0);
   hipLaunchKernelGGL((k_sign_pack_error<U_SRV>), dim3((unsigned)tiles), dim3(BLOCK), 0, stream, err_server,
                      packed_out, scale_out, chunk_len, tiles);
   return hipGetLastError() == hipSuccess ? OB_OK : OB_ERR_HIP;

@@ -28,7 +28,7 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
                  packed_momentum=False, fused_apply=False, x_lp_dtype=None, grad_scale=1.0,
-                 status_interval=64, fold_gather=True, **hyper):
+                 status_interval=64, fold_gather=True, deferred_error=False, **hyper):
         """hyper: the fields of ob_lamb_config (hyper-parameters, flags, fused_max_tiles, spin_limit).
         status_interval: every that many optimizer steps step()/warmup_step() ask the library whether a
         bounded device-side wait has expired (one stream synchronisation; raises ObLambError with
@@ -37,6 +37,9 @@ class DeviceStep:
         # fold_gather: compress_local also writes this rank's own chunk straight into its server's
         # input slot, so gather() has nothing left to copy
         self.fold_gather = bool(fold_gather)
+        # deferred_error: err_worker holds z; the error itself is z - C[z] with this worker's own
+        # previous output (packed_local / scales_local, which then must survive between the steps)
+        self.deferred_error = bool(deferred_error)
         self.status_interval = int(status_interval)
         self._steps_since_check = 0
         self.device = torch.device(device)
@@ -95,6 +98,8 @@ class DeviceStep:
             wpc = self.n_c // 32
             b["own_packed_in"] = self.packed_in[self.c * wpc:]
             b["own_scale_in"] = self.scales_in[self.c:]
+        if self.deferred_error:
+            b["err_packed"], b["err_scales"] = self.packed_local, self.scales_local
         if self.packed_momentum and momentum == "commit":
             b["m"] = None                       # committed in place: packed_all is the momentum
             b["m_packed"], b["m_scales"] = self.packed_all, self.server_scales
@@ -123,8 +128,20 @@ class DeviceStep:
                 self.t[k].copy_(self._dev(st[k]))
         if "m" in st and st["m"] is not None:
             self.m_is_packed = False
+        if "err_worker" in st and st["err_worker"] is not None:
+            self.scales_local.zero_()      # (deferred form: zero scales make err_worker the error itself)
+
+    def err_dense(self):
+        """The worker error delta as a device tensor (materialised from the deferred form if that is in use)."""
+        if not self.deferred_error:
+            return self.t["err_worker"]
+        out = torch.empty_like(self.t["err_worker"])
+        ob.ob_lamb_error_dense(self.ctx, self._state("read"), out, self.stream)
+        return out
 
     def get(self, k):
+        if k == "err_worker" and self.deferred_error:
+            return self.err_dense().cpu().numpy()
         if k == "m" and self.m_is_packed:
             # dense view of the 1-bit momentum (held by the pair of the step that committed it)
             s = ob.make_state(**dict(self.t, m_packed=self.packed_all, m_scales=self.server_scales))

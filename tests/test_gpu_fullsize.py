@@ -20,17 +20,18 @@ from workloads.gen import layer_kappa  # noqa: E402
 pytestmark = pytest.mark.gpu
 
 
-def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False, fused=False, x_lp_dtype=None):
+def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False, fused=False, x_lp_dtype=None,
+                 deferred=False):
     st = Streams(seed, device="cuda:0")
     pl = cfg["plist"]
     import paper_2104_06069_amd as ob
     if two_pass:
         dev = DeviceStep(pl.offsets, cfg["W"], server_chunk, two_pass=True, packed_momentum=packed,
-                         fused_apply=fused, x_lp_dtype=x_lp_dtype, **HYPER)
+                         fused_apply=fused, x_lp_dtype=x_lp_dtype, deferred_error=deferred, **HYPER)
     else:  # whatever the library selects for this size on this device
         from paper_2104_06069_amd.step import DeviceStep as D
         dev = D(pl.offsets, cfg["W"], server_chunk, packed_momentum=packed, fused_apply=fused,
-                x_lp_dtype=x_lp_dtype, **HYPER)
+                x_lp_dtype=x_lp_dtype, deferred_error=deferred, **HYPER)
     print(f"{cfg['name']}: single-pass worker compression = {ob.ob_lamb_uses_single_pass(dev.ctx)}", flush=True)
     s = init_state(st, cfg)
     # non-trivial momentum and errors, as after many steps
@@ -66,7 +67,7 @@ def test_bert_large_whole_step(name, two_pass, packed, fused, lp, serial):
     c = cfg["W"] // 2
     tdt = {"f16": torch.float16, "bf16": torch.bfloat16}
     st, dev, g = device_setup(cfg, c, two_pass=two_pass, packed=packed, fused=fused,
-                              x_lp_dtype=tdt[lp[1]] if lp else None)
+                              x_lp_dtype=tdt[lp[1]] if lp else None, deferred=(packed and fused))
     if fused:
         import paper_2104_06069_amd as ob
         print(f"{name}: layers in the single-kernel ratio+update path: {ob.ob_lamb_fused_layers(dev.ctx)}", flush=True)
@@ -131,7 +132,7 @@ def test_bert_large_whole_steps_among_simulated_ranks():
     c = 21
     MT = default_threads()
     st = Streams(12, device="cuda:0")
-    dev = D(pl.offsets, W, c, packed_momentum=True, fused_apply=True, **HYPER)
+    dev = D(pl.offsets, W, c, packed_momentum=True, fused_apply=True, deferred_error=True, **HYPER)
     assert ob.ob_lamb_fused_layers(dev.ctx) > 100 and ob.ob_lamb_uses_single_pass(dev.ctx)
     s = init_state(st, cfg)
     s["m"] = st.normal("m0", 0, cfg["n_pad"], 1e-4); s["m"][pl.N:] = 0
@@ -212,7 +213,7 @@ def test_gpt_1p3b_windows():
         ref.compress_local(gw)
         assert np.array_equal(words_of(dev.packed_local[A // 32:B // 32]), ref.bits_local), (c0, "worker words")
         assert_close(dev.scales_local[c0:c1].cpu().numpy(), ref.scales_local, "worker scales")
-        assert_close(dev.t["err_worker"][A:B].cpu().numpy(), ref.t["err_worker"], "worker error")
+        assert_close(dev.err_dense()[A:B].cpu().numpy(), ref.t["err_worker"], "worker error")
         if srv_in:
             ref.t["err_server"][...] = before["err_server"].cpu().numpy()
             refs = RefStep(np.array([0, n_c]), W, c_srv, n_pad=W * n_c)   # served chunk, full fan-in
@@ -361,7 +362,7 @@ def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmu
     MT = default_threads()
     hyper = dict(HYPER, c_min=1e-3) if warmup_steps else dict(HYPER)
     st = Streams(seed, device="cuda:0")
-    dev = D(pl.offsets, W, c_srv, packed_momentum=True, fused_apply=True, **hyper)
+    dev = D(pl.offsets, W, c_srv, packed_momentum=True, fused_apply=True, deferred_error=True, **hyper)
     s = init_state(st, cfg)
     if warmup_steps:
         for k in ("v_fresh", "v_frozen"):
@@ -456,12 +457,13 @@ def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmu
                       f"oracle {t_or:.0f} s so far]", end="", flush=True)
     torch.cuda.synchronize()
     m_dev = dev.get("m")
+    err_dev = dev.err_dense()
     r_dev, c_dev = dev.get("r_prev"), dev.get("coeff_c")
     num = den = 0.0
     n_layers = 0
     for i, w in enumerate(wins):
         close = assert_close if exact else assert_mostly_close
-        close(dev.t["err_worker"][w.A:w.B].cpu().numpy(), w.t["err_worker"], "worker error")
+        close(err_dev[w.A:w.B].cpu().numpy(), w.t["err_worker"], "worker error")
         close(dev.t["v_fresh"][w.A:w.B].cpu().numpy(), w.t["v_fresh"], "v_fresh")
         if w.served:
             close(dev.get("err_server"), w.t["err_server"], "server error")
@@ -542,7 +544,7 @@ def test_bert_large_bitwise_reproducible():
     cfg = make_config("bert_large")
     outs = []
     for run in range(2):
-        st, dev, g = device_setup(cfg, cfg["W"] // 2, seed=5, packed=True, fused=True)
+        st, dev, g = device_setup(cfg, cfg["W"] // 2, seed=5, packed=True, fused=True, deferred=True)
         for t in range(3):
             if t > 0:
                 dev.begin_step()
@@ -552,6 +554,7 @@ def test_bert_large_bitwise_reproducible():
             dev.step(g, 1e-3)
         torch.cuda.synchronize()
         out = {k: dev.t[k].clone() for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c")}
+        out["err_dense"] = dev.err_dense().clone()
         out["packed_local"] = dev.packed_local.clone(); out["packed_all"] = dev.packed_all.clone()
         out["scales_local"] = dev.scales_local.clone(); out["server_scales"] = dev.server_scales.clone()
         outs.append(out)

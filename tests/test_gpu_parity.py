@@ -109,7 +109,7 @@ def make_case(name):
 
 
 def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused=False,
-               fused_max_tiles=None, hyper=None):
+               fused_max_tiles=None, hyper=None, deferred=False):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -120,7 +120,7 @@ def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused
     h.update(hyper or {})
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **h)
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, fused_apply=fused,
-                     fused_max_tiles=fused_max_tiles, **h)
+                     fused_max_tiles=fused_max_tiles, deferred_error=deferred, **h)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -147,13 +147,15 @@ def push_wire(ref, dev):
 CASES = ["small", "odd", "w1", "tiny", "bert_mini"]
 
 
-@pytest.mark.parametrize("two_pass", [False, True], ids=["single_pass", "two_pass"])
+@pytest.mark.parametrize("two_pass", [False, True, "deferred"], ids=["single_pass", "two_pass", "deferred"])
 @pytest.mark.parametrize("case", CASES)
 def test_phasewise_single_step(case, two_pass):
-    """Each call is fed the oracle's outputs of the previous phase; signs must be bit-exact."""
+    """Each call is fed the oracle's outputs of the previous phase; signs must be bit-exact.
+    The worker side in its three forms: one kernel with a chunk barrier, two passes, and the deferred
+    error (one pass, the subtraction of C[z] postponed to the next call)."""
     _need_gpu()
     cfg = make_case(case)
-    st, ref, dev = start_pair(cfg, two_pass=two_pass)
+    st, ref, dev = start_pair(cfg, two_pass=(two_pass is True), deferred=(two_pass == "deferred"))
     g = gradient(st, cfg, 0)
     gd = torch.from_numpy(g).to(dev.device)
     lr = 2e-3
@@ -205,7 +207,7 @@ def test_phasewise_single_step(case, two_pass):
 
 
 def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False, fused=False,
-                   fused_max_tiles=None, hyper=None, c_avg=None, nudge_step=None):
+                   fused_max_tiles=None, hyper=None, c_avg=None, nudge_step=None, deferred=False):
     """The device feeds itself for `steps` steps; the oracle does the same on the host.
     While every scale has been bit-equal on both sides, everything must be bit-equal.  Once a scale
     has differed in its last bit (the two sides add the same fp64 terms in different groupings; about
@@ -217,7 +219,7 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=
     chunk it does not serve would have left there (scale one ulp up, the chunk's errors moved by that
     ulp), so that the second regime is exercised."""
     st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed,
-                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper)
+                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper, deferred=deferred)
     if c_avg is not None:
         ref.t["c_avg"][...] = c_avg
         dev.load_state(ref.t)
@@ -275,7 +277,7 @@ def test_trajectory_after_a_last_bit_difference_of_a_scale():
     CPU): the two sides stay within the stated bounds for the rest of a 60-step run."""
     _need_gpu()
     cfg = make_case("bert_mini")
-    ref, dev, stats = run_trajectory(cfg, 60, packed=True, fused=True, nudge_step=4)
+    ref, dev, stats = run_trajectory(cfg, 60, packed=True, fused=True, nudge_step=4, deferred=True)
     x_ref = ref.t["x"][:ref.N].astype(np.float64)
     x_gpu = dev.get("x")[:ref.N].astype(np.float64)
     rel = np.linalg.norm(x_gpu - x_ref) / np.linalg.norm(x_ref)
@@ -290,13 +292,16 @@ def test_trajectory_after_a_last_bit_difference_of_a_scale():
     ("bert_mini", 30, True, False),
     # momentum kept in its 1-bit form from the first step on
     ("tiny", 10, False, True), ("bert_mini", 100, False, True), ("odd", 30, False, True),
-    ("bert_mini", 30, True, True), ("w1", 10, True, True), ("small", 10, False, True)])
+    ("bert_mini", 30, True, True), ("w1", 10, True, True), ("small", 10, False, True),
+    # the worker error in deferred form (z kept, C[z] subtracted by the next step)
+    ("tiny", 10, "deferred", False), ("bert_mini", 100, "deferred", True), ("odd", 30, "deferred", True),
+    ("w1", 10, "deferred", False), ("small", 10, "deferred", True)])
 def test_trajectory(case, steps, two_pass, packed):
     """The device feeds itself for `steps` steps; the oracle does the same on the host."""
     _need_gpu()
     cfg = make_case(case)
-    ref, dev, stats = run_trajectory(cfg, steps, two_pass=two_pass, packed=packed,
-                                     warm_state=(case in ("odd", "w1")))
+    ref, dev, stats = run_trajectory(cfg, steps, two_pass=(two_pass is True), packed=packed,
+                                     warm_state=(case in ("odd", "w1")), deferred=(two_pass == "deferred"))
     x_ref = ref.t["x"][:ref.N].astype(np.float64)
     x_gpu = dev.get("x")[:ref.N].astype(np.float64)
     rel = np.linalg.norm(x_gpu - x_ref) / np.linalg.norm(x_ref)
@@ -888,7 +893,7 @@ def test_step_replayed_from_a_captured_graph(case):
     every replay is checked against the oracle."""
     _need_gpu()
     cfg = make_case(case)
-    st, ref, dev = start_pair(cfg, warm_state=False, packed=True, fused=True)
+    st, ref, dev = start_pair(cfg, warm_state=False, packed=True, fused=True, deferred=True)
     n_pad = cfg["n_pad"]
     gbuf = [torch.zeros(n_pad, device=dev.device) for _ in range(2)]
     lr = 1e-3
@@ -978,7 +983,7 @@ def test_random_layer_lists(seed):
     hyper = dict(HYPER, c_min=1e-3)
     ref = RefStep(pl.offsets, W, c_srv, mom_scale=k, **hyper)
     dev = DeviceStep(pl.offsets, W, c_srv, mom_scale=k, packed_momentum=True, fused_apply=True,
-                     fused_max_tiles=max_tiles, **hyper)
+                     fused_max_tiles=max_tiles, deferred_error=bool(seed % 2), **hyper)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     print(f"sizes {sizes} W {W} served {c_srv} k {use_k} max_tiles {max_tiles}: "
           f"{ob.ob_lamb_fused_layers(dev.ctx)} / {ob.ob_lamb_warmup_fused_layers(dev.ctx)} layers in the barrier kernels")
