@@ -73,7 +73,10 @@ def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_
     separate = k["ratios_pass"][0] + k["decompress_apply"][0]
     compress = {"deferred": k["compress_deferred"][0], "barrier": k["compress_resident"][0],
                 "two_pass": k["momentum_z_sumsq"][0] + 8.125}[compress_form]
-    server = (0.125 + 8.125 / W) if server_single_pass else (0.125 + 16.125 / W)
+    if compress_form == "deferred":    # the server error is deferred too: one pass over the chunk
+        server = 0.125 + 8.375 / W     # R W packed chunks, zb, own previous bits; W zb, bits twice
+    else:
+        server = (0.125 + 8.125 / W) if server_single_pass else (0.125 + 16.125 / W)
     return (compress + fused_frac * k["ratios_apply_resident"][0] + (1.0 - fused_frac) * separate + server)
 
 
@@ -363,7 +366,7 @@ def main():
     kern = {k: {"avg_ms": round(v[0] / v[1], 4), "launches": v[1]} for k, v in prof.items()}
     KB = dict(KERNEL_BYTES["both"])
     KB.update(KERNEL_BYTES[mode])
-    KB["server_unpack_avg"] = (W / 8.0 + 8.0, "n_c")
+    KB["server_unpack_avg"] = (W / 8.0 + (8.375 if ds.deferred_error else 8.0), "n_c")
     KB["server_resident"] = (W / 8.0 + 8.125, "n_c")   # R W*bits, err (4) + W err (4), bits (1/8)
     g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written

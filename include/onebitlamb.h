@@ -125,6 +125,11 @@ typedef struct ob_lamb_state {
    * output and its scales.  Both or neither. */
   const uint32_t* err_packed; /* [N_pad/32] or NULL */
   const float* err_scales;    /* [W] or NULL */
+  /* ... and the server error in the same deferred form: the server's own previous output for the
+   * chunk it serves, kept by the library's kernels in these two buffers (read AND rewritten by
+   * ob_lamb_server_reduce; not the packed_out of that call).  Both or neither. */
+  uint32_t* srv_err_packed;   /* [n_c/32] or NULL */
+  float* srv_err_scale;       /* [1] or NULL */
 } ob_lamb_state;
 
 /* Worker error representation.  Algorithm 1 line 7 leaves delta = z - C[z] in the error buffer, and
@@ -144,6 +149,14 @@ typedef struct ob_lamb_state {
  * resumes from a dense error.  ob_lamb_error_dense writes the error itself, delta, to err_out
  * [N_pad] (err_out may be st->err_worker if the caller then zeroes err_scales). */
 ob_status ob_lamb_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* err_out, void* hip_stream);
+/* The same for Algorithm 1 line 10's server error: with srv_err_packed / srv_err_scale non-NULL,
+ * err_server holds zb of the previous ob_lamb_server_reduce, the carried error is err_server -
+ * C[zb] decoded from those two buffers, and the call writes the new zb to err_server and its sign
+ * words to packed_out and to srv_err_packed (the new scale to scale_out and srv_err_scale): one pass
+ * over the chunk plus one workgroup for the scale, no barrier.  A zero srv_err_scale makes err_server
+ * an ordinary error.  ob_lamb_server_error_dense writes the error itself to err_out [n_c]. */
+ob_status ob_lamb_server_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* err_out,
+                                     void* hip_stream);
 
 /* Momentum representation.  After line 13 of any compression step the global momentum is exactly
  * m[i] = (bit_i ? +s_c : -s_c) / k_l (0 in the padding), i.e. the step's packed_all/server_scales.

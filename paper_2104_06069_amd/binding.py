@@ -41,7 +41,7 @@ class ObLambState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev",
                  "coeff_c", "mom_scale", "m_packed", "m_scales", "own_packed_in", "own_scale_in",
-                 "err_packed", "err_scales")]
+                 "err_packed", "err_scales", "srv_err_packed", "srv_err_scale")]
 
 
 def lib_path():
@@ -86,6 +86,7 @@ def lib():
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_error_dense": (C.c_int, [vp, sp, vp, vp]),
+            "ob_lamb_server_error_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_server_single_pass": (i32, [vp]),
@@ -292,6 +293,11 @@ def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):
 def ob_lamb_error_dense(ctx, state, err_out, stream=None):
     _check(lib().ob_lamb_error_dense(ctx, C.byref(state), _addr(err_out), _addr(stream)), ctx,
            "ob_lamb_error_dense")
+
+
+def ob_lamb_server_error_dense(ctx, state, err_out, stream=None):
+    _check(lib().ob_lamb_server_error_dense(ctx, C.byref(state), _addr(err_out), _addr(stream)), ctx,
+           "ob_lamb_server_error_dense")
 
 
 def ob_lamb_momentum_scale(ctx, state, stream=None):

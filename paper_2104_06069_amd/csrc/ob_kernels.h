@@ -750,31 +750,48 @@ __device__ __forceinline__ void server_average(const uint32_t* __restrict__ pack
   }
 }
 
-// two-pass form: zb written over err_server, tile partial of sum zb^2
-template <int U>
+// two-pass form: zb written over err_server, tile partial of sum zb^2.
+// DEFER: the server error in deferred form (as for the worker, see PackedErr; here one chunk, one
+// scale): err_s holds zb of the previous call, the carried error is err_s - C[zb] with the server's
+// own previous output `keep` (read and rewritten in place), and the sign words of the new zb are
+// written here, to packed_out and to `keep`; no second pass over the chunk is needed.
+template <int U, bool DEFER = false>
 __global__ __launch_bounds__(BLOCK) void k_server_unpack_avg(
     const uint32_t* __restrict__ packed_in, const float* __restrict__ scales_in,
-    float* __restrict__ err_s, double* __restrict__ partials, int64_t n_c, int W, float invW) {
+    float* __restrict__ err_s, double* __restrict__ partials, int64_t n_c, int W, float invW,
+    uint32_t* keep, const float* keep_scale, uint32_t* packed_out) {
   constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
   __shared__ unsigned int lds_negs[SRV_STAGE];
   const TilePos p = tile_pos<TILE>(n_c, (int)gridDim.x, (int)blockIdx.x);  // one chunk: c == 0
   const int o0 = threadIdx.x * 4;
+  const float se = DEFER ? keep_scale[0] : 0.0f;
   float acc[U][4];
   server_average<U>(packed_in, scales_in, n_c, W, p, acc, lds_negs);
   double sq = 0.0;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int o = u * SPAN + o0;
-    if (o < p.len) {
-      const v4f e = ld4(err_s + p.tile0 + o);
+    if (o < p.len) {   // uniform over the wavefront, as the shuffles below require
+      v4f e = ld4(err_s + p.tile0 + o);
+      if (DEFER) e = deferred_error(e, load_nibble(keep, p.tile0 + u * SPAN), se);
       v4f z;
+      unsigned int nib = 0;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         z[k] = acc[u][k] * invW + e[k];
         sq += (double)z[k] * (double)z[k];
+        if (DEFER) nib |= ((z[k] >= 0.0f) ? 1u : 0u) << k;
       }
       st4(err_s + p.tile0 + o, z);
+      if (DEFER) {
+        const unsigned int word = gather_word(nib);
+        if ((threadIdx.x & 7) == 0) {
+          const int64_t w0 = (p.tile0 + u * SPAN) >> 5;
+          (packed_out + w0)[threadIdx.x >> 3] = word;
+          (keep + w0)[threadIdx.x >> 3] = word;
+        }
+      }
     }
   }
   const double s = block_sum(sq, lds);

@@ -1011,6 +1011,18 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
   // the kernels address packed_in with 32-bit byte offsets
   if ((int64_t)ctx->W * (ctx->n_c / 8) >= ((int64_t)1 << 31)) return OB_ERR_SIZE;
   Launch la(ctx, hip_stream);
+  if ((st->srv_err_packed == nullptr) != (st->srv_err_scale == nullptr)) return OB_ERR_NULL;
+  if (st->srv_err_packed) {
+    // deferred server error: one pass over the chunk plus its scale -- no barrier, no second pass
+    if (misaligned(st->srv_err_packed)) return OB_ERR_ALIGN;
+    if (st->srv_err_packed == packed_out) return OB_ERR_ARG;
+    OB_LAUNCH(la, KID_SERVER_AVG, (k_server_unpack_avg<U_SRV, true>), ctx->tpc_srv, packed_in, scales_in,
+              st->err_server, ctx->d_partials_srv, ctx->n_c, (int)ctx->W, ctx->invW, st->srv_err_packed,
+              st->srv_err_scale, packed_out);
+    OB_LAUNCH_B(la, KID_SERVER_SCALE, k_chunk_scale, 1, FBLOCK, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out,
+                st->srv_err_scale, 0);
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
   if (ctx->u_srv_res) {
     ChunkSync cs;
     cs.partials = ctx->d_partials_srv_res;
@@ -1032,7 +1044,8 @@ ob_status ob_lamb_server_reduce(ob_lamb_ctx* ctx, const ob_lamb_state* st, const
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
   OB_LAUNCH(la, KID_SERVER_AVG, (k_server_unpack_avg<U_SRV>), ctx->tpc_srv, packed_in, scales_in,
-            st->err_server, ctx->d_partials_srv, ctx->n_c, (int)ctx->W, ctx->invW);
+            st->err_server, ctx->d_partials_srv, ctx->n_c, (int)ctx->W, ctx->invW, (uint32_t*)nullptr,
+            (const float*)nullptr, (uint32_t*)nullptr);
   OB_LAUNCH_B(la, KID_SERVER_SCALE, k_chunk_scale, 1, FBLOCK, ctx->d_partials_srv, ctx->tpc_srv, ctx->n_c, scale_out,
               (float*)nullptr, 0);
   OB_LAUNCH(la, KID_SERVER_PACK, (k_sign_pack_error<U_SRV>), ctx->tpc_srv, st->err_server, packed_out,
@@ -1160,6 +1173,20 @@ ob_status ob_lamb_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* 
   pe.bits = st->err_packed; pe.scales = st->err_scales;
   Launch la(ctx, hip_stream);
   OB_LAUNCH(la, KID_MOMENTUM_DENSE, k_error_dense, ctx->n_tiles, st->err_worker, pe, err_out, ctx->n_c, ctx->tpc);
+  return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_server_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* err_out,
+                                     void* hip_stream) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(err_out); REQUIRE_PTR(st->err_server); REQUIRE_PTR(st->srv_err_packed);
+  if (!st->srv_err_scale) return OB_ERR_NULL;
+  PackedErr pe;
+  pe.bits = st->srv_err_packed; pe.scales = st->srv_err_scale;
+  Launch la(ctx, hip_stream);
+  // the served chunk as a one-chunk buffer
+  OB_LAUNCH(la, KID_MOMENTUM_DENSE, k_error_dense, ctx->tpc_srv, st->err_server, pe, err_out, ctx->n_c,
+            ctx->tpc_srv);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -1312,7 +1339,8 @@ ob_status ob_lamb_server_reduce_static(int32_t num_workers, int64_t chunk_len, c
   // the three kernels of ob_lamb_server_reduce's barrier-free form; every partial that the second
   // reads has been written by the first, so the array's previous contents do not matter
   hipLaunchKernelGGL((k_server_unpack_avg<U_SRV>), dim3((unsigned)tiles), dim3(BLOCK), 0, stream, packed_in,
-                     scales_in, err_server, partials, chunk_len, (int)num_workers, invW);
+                     scales_in, err_server, partials, chunk_len, (int)num_workers, invW, (uint32_t*)nullptr,
+                     (const float*)nullptr, (uint32_t*)nullptr);
   hipLaunchKernelGGL(k_chunk_scale, dim3(1), dim3(FBLOCK), 0, stream, partials, tiles, chunk_len, scale_out,
                      (float*)nullptr, 0);
   hipLaunchKernelGGL((k_sign_pack_error<U_SRV>), dim3((unsigned)tiles), dim3(BLOCK), 0, stream, err_server,

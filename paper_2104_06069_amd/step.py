@@ -39,6 +39,7 @@ class DeviceStep:
         self.fold_gather = bool(fold_gather)
         # deferred_error: err_worker holds z; the error itself is z - C[z] with this worker's own
         # previous output (packed_local / scales_local, which then must survive between the steps)
+        # (and err_server holds zb, with the server's own previous output kept in srv_words / srv_scale)
         self.deferred_error = bool(deferred_error)
         self.status_interval = int(status_interval)
         self._steps_since_check = 0
@@ -64,6 +65,8 @@ class DeviceStep:
         self.scales_local = torch.zeros(self.W, **f32)
         self.packed_in = torch.zeros(self.W * (self.n_c // 32), **i32)  # what the served chunk receives
         self.scales_in = torch.zeros(self.W, **f32)
+        self.srv_words = torch.zeros(self.n_c // 32, **i32)             # deferred server error: own previous output
+        self.srv_scale = torch.zeros(1, **f32)
         # the W recompressed chunks (two pairs when they double as the momentum)
         self.packed_momentum = bool(packed_momentum)
         self.fused_apply = bool(fused_apply)   # layer_ratios + decompress_apply as one call
@@ -100,6 +103,7 @@ class DeviceStep:
             b["own_scale_in"] = self.scales_in[self.c:]
         if self.deferred_error:
             b["err_packed"], b["err_scales"] = self.packed_local, self.scales_local
+            b["srv_err_packed"], b["srv_err_scale"] = self.srv_words, self.srv_scale
         if self.packed_momentum and momentum == "commit":
             b["m"] = None                       # committed in place: packed_all is the momentum
             b["m_packed"], b["m_scales"] = self.packed_all, self.server_scales
@@ -130,6 +134,8 @@ class DeviceStep:
             self.m_is_packed = False
         if "err_worker" in st and st["err_worker"] is not None:
             self.scales_local.zero_()      # (deferred form: zero scales make err_worker the error itself)
+        if "err_server" in st and st["err_server"] is not None:
+            self.srv_scale.zero_()
 
     def err_dense(self):
         """The worker error delta as a device tensor (materialised from the deferred form if that is in use)."""
@@ -142,6 +148,10 @@ class DeviceStep:
     def get(self, k):
         if k == "err_worker" and self.deferred_error:
             return self.err_dense().cpu().numpy()
+        if k == "err_server" and self.deferred_error:
+            out = torch.empty_like(self.t["err_server"])
+            ob.ob_lamb_server_error_dense(self.ctx, self._state("read"), out, self.stream)
+            return out.cpu().numpy()
         if k == "m" and self.m_is_packed:
             # dense view of the 1-bit momentum (held by the pair of the step that committed it)
             s = ob.make_state(**dict(self.t, m_packed=self.packed_all, m_scales=self.server_scales))
