@@ -120,7 +120,8 @@ class Workload:
             ds._pa[i].copy_(fa); ds._ss[i].copy_(torch.from_numpy(fss))
         self.lr = 1e-3
         torch.cuda.synchronize()
-        self.fused_params = ob.ob_lamb_fused_params(ds.ctx) if ds.fused_apply else 0
+        # (with a dense momentum ob_lamb_ratios_apply runs the two plain kernels for every layer)
+        self.fused_params = ob.ob_lamb_fused_params(ds.ctx) if (ds.fused_apply and self.mode == "packed") else 0
         self.wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
 
     def one_step(self, t):
