@@ -329,7 +329,8 @@ struct ZTile {
 };
 
 // ---------------------------------------------------------------------------------------------
-// K1 (two-pass path)  z written over err, and the tile's sum of z^2 in fp64.
+// K1  z written over err, and the tile's sum of z^2 in fp64: the first of the two passes of the
+// worker compression (k_sign_pack_error is the second), or, with DEFER, all of it.
 // ---------------------------------------------------------------------------------------------
 // DEFER: the whole of lines 6-7 in this one pass, with no wait for the chunk's scale: the carried
 // error arrives in deferred form (PackedErr), z is written over it AS the next deferred error, and

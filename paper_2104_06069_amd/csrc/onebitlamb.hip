@@ -93,6 +93,7 @@ enum KernelId {
   KID_APPLY,
   KID_RATIOS_APPLY_RESIDENT,
   KID_MOMENTUM_DENSE,
+  KID_ERROR_DENSE,
   KID_MOMENTUM_SCALE,
   KID_WARMUP_MOMENTS,
   KID_WARMUP_COEFF,
@@ -105,7 +106,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "compress_deferred", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "ratios_apply_resident", "momentum_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "ratios_apply_resident", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
 
 struct ProfRec {
@@ -1172,7 +1173,7 @@ ob_status ob_lamb_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* 
   PackedErr pe;
   pe.bits = st->err_packed; pe.scales = st->err_scales;
   Launch la(ctx, hip_stream);
-  OB_LAUNCH(la, KID_MOMENTUM_DENSE, k_error_dense, ctx->n_tiles, st->err_worker, pe, err_out, ctx->n_c, ctx->tpc);
+  OB_LAUNCH(la, KID_ERROR_DENSE, k_error_dense, ctx->n_tiles, st->err_worker, pe, err_out, ctx->n_c, ctx->tpc);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
@@ -1185,7 +1186,7 @@ ob_status ob_lamb_server_error_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, 
   pe.bits = st->srv_err_packed; pe.scales = st->srv_err_scale;
   Launch la(ctx, hip_stream);
   // the served chunk as a one-chunk buffer
-  OB_LAUNCH(la, KID_MOMENTUM_DENSE, k_error_dense, ctx->tpc_srv, st->err_server, pe, err_out, ctx->n_c,
+  OB_LAUNCH(la, KID_ERROR_DENSE, k_error_dense, ctx->tpc_srv, st->err_server, pe, err_out, ctx->n_c,
             ctx->tpc_srv);
   return la.ok ? OB_OK : OB_ERR_HIP;
 }

@@ -67,7 +67,7 @@ def test_bert_large_whole_step(name, two_pass, packed, fused, lp, serial):
     c = cfg["W"] // 2
     tdt = {"f16": torch.float16, "bf16": torch.bfloat16}
     st, dev, g = device_setup(cfg, c, two_pass=two_pass, packed=packed, fused=fused,
-                              x_lp_dtype=tdt[lp[1]] if lp else None, deferred=(packed and fused))
+                              x_lp_dtype=tdt[lp[1]] if lp else None, deferred=packed)
     if fused:
         import paper_2104_06069_amd as ob
         print(f"{name}: layers in the single-kernel ratio+update path: {ob.ob_lamb_fused_layers(dev.ctx)}", flush=True)
