@@ -482,6 +482,13 @@ def main():
                 continue
             others[name] = brief(name, args, torch, steps, graph_too)
         out["workloads"] = others
+        # the same workload with no in-kernel wait anywhere: deferred errors + ratio pass and update as
+        # two plain kernels (what a caller who cannot accept the per-layer barrier's assumptions runs)
+        import copy
+        a2 = copy.copy(args)
+        a2.separate_calls = True
+        if not args.separate_calls and not args.barrier_compress:
+            out["wait_free_configuration"] = brief(args.workload, a2, torch, args.steps)
     if host0 is not None:
         out["cpu_baseline"] = cpu_baseline(cfg, cfg["W"] // 2, host0, lr, args.cpu_seconds, False)
         mt = cpu_baseline(cfg, cfg["W"] // 2, host0, lr, args.cpu_seconds, True)
