@@ -1059,9 +1059,16 @@ __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restr
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   const float rp = r_prev[l], ca = c_avg[l];
   float r = 0.0f;
-  for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
-    const float q = seg_max[s];
-    if (q > r) r = q;
+  // four loads in flight per thread: a tensor too large for the kernel with the per-layer barrier
+  // has tens of thousands of segments, and this one workgroup walks them alone (the maxima are
+  // >= +0 or NaN, so the zeros that stand in for missing ones change nothing)
+  for (int s = s0 + threadIdx.x; s < s1; s += 4 * FBLOCK) {
+    float q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) q[u] = (s + u * FBLOCK < s1) ? seg_max[s + u * FBLOCK] : 0.0f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (q[u] > r) r = q[u];
   }
   r = block_max<FBLOCK>(r, lds);
   if (threadIdx.x == 0)
