@@ -15,6 +15,7 @@ from tests.refstep import HYPER, RefStep  # noqa: E402
 from tests.test_gpu_parity import (assert_close, assert_mostly_close, sign_bit_mismatch, words_of, _need_gpu,  # noqa: E402
                                    DeviceStep, finish)
 from workloads import Streams, make_config, gradient, init_state, foreign_worker_chunks, foreign_server_chunks  # noqa: E402
+from workloads.gen import init_state_items  # noqa: E402
 from workloads.gen import layer_kappa  # noqa: E402
 
 pytestmark = pytest.mark.gpu
@@ -363,17 +364,22 @@ def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmu
     hyper = dict(HYPER, c_min=1e-3) if warmup_steps else dict(HYPER)
     st = Streams(seed, device="cuda:0")
     dev = D(pl.offsets, W, c_srv, packed_momentum=True, fused_apply=True, deferred_error=True, **hyper)
-    s = init_state(st, cfg)
-    if warmup_steps:
-        for k in ("v_fresh", "v_frozen"):
-            s[k].zero_()
-        s["c_avg"][...] = 0
-    else:   # as after many steps: non-trivial momentum and errors
-        s["m"] = st.normal("m0", 0, cfg["n_pad"], 1e-4); s["m"][pl.N:] = 0
-        s["err_worker"] = st.normal("ew0", 0, cfg["n_pad"], 5e-5)
-        s["err_server"] = st.normal("es0", 0, cfg["n_c"], 5e-5)
-    dev.load_state(s)
-    del s
+    # one array at a time: at the largest sizes two sets of N-sized arrays would not fit beside the
+    # gradient and the dense views taken at the end
+    for k, a in init_state_items(st, cfg):
+        if warmup_steps:
+            if k in ("v_fresh", "v_frozen"):
+                a.zero_()
+            elif k == "c_avg":
+                a[...] = 0
+        elif k == "m":          # as after many steps: non-trivial momentum and errors
+            a = st.normal("m0", 0, cfg["n_pad"], 1e-4); a[pl.N:] = 0
+        elif k == "err_worker":
+            a = st.normal("ew0", 0, cfg["n_pad"], 5e-5)
+        elif k == "err_server":
+            a = st.normal("es0", 0, cfg["n_c"], 5e-5)
+        dev.load_state({k: a})
+        del a
     wins = [WindowRef(pl.offsets, W, n_c, c0, c1, c_srv, threads=MT, **hyper) for (c0, c1) in windows]
     assert sum(w.served for w in wins) == 1, "the served chunk must lie in exactly one window"
     covered = set()
@@ -534,6 +540,41 @@ def test_gpt_1p3b_50_steps_two_stage_on_windows(capsys):
                           warmup_steps=2, check_every=10, seed=seed,
                           must_cover=["emb.word", "emb.pos", "l11.qkv.w", "l11.out.w", "l11.ffn1.w",
                                       "l11.ffn2.w"])
+
+
+def test_flat_buffer_longer_than_2_to_32_on_windows(capsys):
+    """Maximum sizes: a flat buffer of 4.54e9 elements (the GPT-1.3B block repeated 88 times; 18 GB per
+    fp32 array, W = 256), so that element indices pass 2^31 and 2^32 and byte offsets 2^34.  Four
+    compression steps in the benchmarked configuration, compared with the oracle on three windows:
+    the transformer block in which index 2^31 falls plus the first tensors of the next one, the
+    same around index 2^32 (with the served chunk), and the last block with the end of the
+    parameters and the padding.  Each window holds tensors of both paths: 12.6 M / 16.8 M-element
+    ones (plain kernels) and 4.2 M-element and small ones (kernel with the per-layer barrier)."""
+    _need_gpu()
+    if torch.cuda.get_device_properties(0).total_memory < 200 * 2 ** 30:
+        pytest.skip("needs about 170 GB of device memory")
+    cfg = make_config("gpt_beyond_2p32")
+    pl, n_c = cfg["plist"], cfg["n_c"]
+    assert pl.N > 2 ** 32
+    names = [n for n, _ in pl.tensors]
+    off = pl.offsets
+
+    def block_of(i):
+        l = int(np.searchsorted(off, i, side="right")) - 1
+        return int(names[l].split(".")[0][1:])
+    b31, b32 = block_of(2 ** 31), block_of(2 ** 32)
+    w31 = chunks_of(cfg, f"l{b31}.qkv.w", f"l{b31 + 1}.out.w")
+    w32 = chunks_of(cfg, f"l{b32}.qkv.w", f"l{b32 + 1}.out.w")
+    wend = (chunks_of(cfg, "l87.qkv.w", "lnf.b")[0], cfg["W"])
+    assert w31[0] * n_c < 2 ** 31 < w31[1] * n_c and w32[0] * n_c < 2 ** 32 < w32[1] * n_c
+    assert w31[1] <= w32[0] and w32[1] <= wend[0]
+    c_srv = -(-2 ** 32 // n_c)          # the first chunk that lies wholly beyond 2^32
+    assert w32[0] <= c_srv < w32[1]
+    trajectory_on_windows(capsys, "gpt_beyond_2p32", c_srv=c_srv, windows=[w31, w32, wend], steps=4,
+                          check_every=1, seed=4,
+                          must_cover=[f"l{b31}.ffn2.w", f"l{b31 + 1}.qkv.w", f"l{b31 + 1}.out.w",
+                                      f"l{b32}.out.w", f"l{b32}.ffn1.w", f"l{b32 + 1}.out.w",
+                                      "l87.ffn2.w", "lnf.w", "lnf.b"])
 
 
 def test_bert_large_bitwise_reproducible():

@@ -102,22 +102,34 @@ def _zero_pad(a, n):
     return a
 
 
-def init_state(st: Streams, cfg):
-    """Optimizer state at the start of the compression stage; n_pad-long arrays, pad zeroed."""
+def init_state_items(st: Streams, cfg):
+    """The arrays of init_state, one (key, array) pair at a time, so that a consumer that copies each
+    one into place never holds two sets of N-sized arrays.  v_frozen and v_fresh are yielded as the
+    SAME array (the snapshot and its source are equal at the start of the compression stage)."""
     pl, n_pad, W = cfg["plist"], cfg["n_pad"], cfg["W"]
     N, L = pl.N, pl.L
-    x = _zero_pad(st.normal("x", 0, n_pad, 0.02), N)
+    yield "x", _zero_pad(st.normal("x", 0, n_pad, 0.02), N)
+    yield "m", st.zeros(n_pad)
     v = st.normal("v", 0, n_pad, 1e-4)
     v = abs(v) if st.device is None else v.abs_()
     v += 1e-8
     v = _zero_pad(v, N)
-    state = dict(
-        x=x, m=st.zeros(n_pad), v_frozen=v,
-        v_fresh=(v.copy() if st.device is None else v.clone()),
-        err_worker=st.zeros(n_pad), err_server=st.zeros(n_pad // W),
-        c_avg=st.uniform_host("c_avg", 0, L, 0.5, 2.0),
-        r_prev=np.ones(L, dtype=np.float32),
-    )
+    yield "v_frozen", v
+    yield "v_fresh", v
+    del v
+    yield "err_worker", st.zeros(n_pad)
+    yield "err_server", st.zeros(n_pad // W)
+    yield "c_avg", st.uniform_host("c_avg", 0, L, 0.5, 2.0)
+    yield "r_prev", np.ones(L, dtype=np.float32)
+
+
+def init_state(st: Streams, cfg):
+    """Optimizer state at the start of the compression stage; n_pad-long arrays, pad zeroed."""
+    state = {}
+    for k, a in init_state_items(st, cfg):
+        if k == "v_fresh":
+            a = a.copy() if st.device is None else a.clone()
+        state[k] = a
     return state
 
 

@@ -88,6 +88,10 @@ CONFIGS = {
                             W=256, grad="student_t3", steps=100),
     "gpt_1p3b": dict(plist=lambda: gpt_shaped(2048, 8192, 24, 50304, 2048, name="gpt_1p3b"),
                      W=128, grad="normal_sparse_layers", steps=50),
+    # not a benchmark configuration: the GPT-1.3B block repeated until the flat buffer is longer than
+    # 2^32 elements (4.54e9; 18 GB per fp32 array), for the tests of 64-bit indexing
+    "gpt_beyond_2p32": dict(plist=lambda: gpt_shaped(2048, 8192, 88, 50304, 2048, name="gpt_beyond_2p32"),
+                            W=256, grad="normal", steps=4),
     # not a benchmark configuration: a BERT-patterned list small enough for the CPU oracle to run
     # 100-step trajectories in seconds, with the same odd tensor sizes (2-element bias, etc.)
     "bert_mini": dict(plist=lambda: bert_shaped(64, 256, 2, 1000, max_pos=32, fused_qkv=False,
