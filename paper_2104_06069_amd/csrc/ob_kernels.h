@@ -675,9 +675,10 @@ __global__ __launch_bounds__(BLOCK, MINW) void k_compress_resident(
 // ---------------------------------------------------------------------------------------------
 constexpr int SRV_STAGE = 1024;   // scales held in LDS at a time
 // The sign words are fetched with buffer loads: the wavefront-uniform part of the address (worker
-// block) travels in a scalar register, the thread's part in one 32-bit register, so no vector
-// instruction is spent on addresses, and a read outside [packed_in, packed_in + W*n_c/32) would
-// return 0 instead of faulting.  Offsets are 32-bit: the host admits W*n_c/8 < 2^31 bytes.
+// block, span of the tile) travels in a scalar register, the thread's part in one 32-bit register,
+// so no vector instruction is spent on addresses.  Every address is inside [packed_in, packed_in +
+// W*n_c/32) by construction (the descriptor's range check does not see the scalar part, so it is
+// not relied on).  Offsets are 32-bit: the host admits W*n_c/8 < 2^31 bytes.
 constexpr int OB_BUFFER_RSRC_WORD3 = 0x00020000;   // raw 32-bit data format word of gfx9-family descriptors
 
 template <int U>
@@ -694,9 +695,13 @@ __device__ __forceinline__ void server_average(const uint32_t* __restrict__ pack
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint32_t*>(packed_in + col0), 0, (int)(((int64_t)W * (n_c >> 5) - col0) * 4), OB_BUFFER_RSRC_WORD3);
   // byte offset of the thread's word of span 0 in a worker's block; span u lies 128 bytes further.
-  // (A partial tile's missing spans read the words that follow the tile -- inside the array, or 0
-  // beyond its end -- and their sums are never used.)
+  // The spans a partial tile lacks (only the chunk's last tile has any; uniform over the workgroup)
+  // read span 0 again and their sums are never used: the words that follow the tile would lie in
+  // the next worker's block and, for the last worker, beyond the end of the array.
   const int voff0 = 4 * (int)(threadIdx.x >> 3);
+  int uoff[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) uoff[u] = (u * SPAN < p.len) ? 128 * u : 0;
   unsigned int shk[4];                // position of the thread's k-th bit in its word
 #pragma unroll
   for (int k = 0; k < 4; ++k) shk[k] = 4u * (threadIdx.x & 7) + (unsigned)k;
@@ -717,7 +722,7 @@ __device__ __forceinline__ void server_average(const uint32_t* __restrict__ pack
     const int soff = w * wpc_bytes;   // uniform
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      word[u] = (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, voff0 + 128 * u, soff, 0);
+      word[u] = (unsigned int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, voff0, soff + uoff[u], 0);
   };
   for (int wb = 0; wb < W; wb += SRV_STAGE) {
     const int nb = (W - wb < SRV_STAGE) ? W - wb : SRV_STAGE;

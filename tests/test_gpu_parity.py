@@ -1013,7 +1013,10 @@ def test_random_layer_lists(seed):
 
 
 @pytest.mark.parametrize("n_c_target,W,expect", [
-    (300_000, 3, 1), (2_500_000, 2, 2), (5_000_000, 2, 4), (8_000_000, 1, 0), (300_000, 3, "two_pass")])
+    (300_000, 3, 1), (2_500_000, 2, 2), (5_000_000, 2, 4), (8_000_000, 1, 0), (300_000, 3, "two_pass"),
+    # fan-ins that are not multiples of the number of workers whose words are in flight together,
+    # and one above the number of scales staged at a time
+    (40_000, 203, 1), (2_500_000, 13, 2), (2_000, 1100, 1), (2_000, 1100, "two_pass")])
 def test_server_reduce_forms(n_c_target, W, expect):
     """ob_lamb_server_reduce in each of its forms -- one kernel with a chunk barrier on tiles of
     1024, 2048 or 4096 elements (the smallest whose workgroups all fit on the device), three
