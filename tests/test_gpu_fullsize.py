@@ -553,6 +553,8 @@ def test_flat_buffer_longer_than_2_to_32_on_windows(capsys):
     _need_gpu()
     if torch.cuda.get_device_properties(0).total_memory < 200 * 2 ** 30:
         pytest.skip("needs about 170 GB of device memory")
+    import gc
+    gc.collect(); torch.cuda.empty_cache()    # what earlier tests left in torch's cache
     cfg = make_config("gpt_beyond_2p32")
     pl, n_c = cfg["plist"], cfg["n_c"]
     assert pl.N > 2 ** 32
@@ -575,6 +577,7 @@ def test_flat_buffer_longer_than_2_to_32_on_windows(capsys):
                           must_cover=[f"l{b31}.ffn2.w", f"l{b31 + 1}.qkv.w", f"l{b31 + 1}.out.w",
                                       f"l{b32}.out.w", f"l{b32}.ffn1.w", f"l{b32 + 1}.out.w",
                                       "l87.ffn2.w", "lnf.w", "lnf.b"])
+    gc.collect(); torch.cuda.empty_cache()
 
 
 def test_bert_large_bitwise_reproducible():
