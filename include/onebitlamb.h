@@ -368,9 +368,11 @@ int32_t ob_lamb_server_single_pass(const ob_lamb_ctx* ctx);
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
  * arguments' meaning (all device pointers, 16-byte aligned; num_workers = W, chunk_len = n_c, a
  * multiple of 256), but no context: the partial sums between its kernels live in a fixed array
- * inside the library's device image (256 KiB per GPU, held until the process ends), looked up on
- * the first call on each device.  It calls no hipMalloc/hipFree or any allocating routine, enqueues
- * three kernels on `hip_stream` and returns without synchronising.
+ * inside the library's device image (256 KiB per GPU, held until the process ends), whose address
+ * on a device is looked up once, by the first ob_lamb_create or the first call of this function with
+ * that device current (a caller under graph capture makes one of the two before the capture
+ * begins).  It calls no hipMalloc/hipFree or any allocating routine, enqueues three kernels on
+ * `hip_stream` and returns without synchronising.
  *   chunk_len > ob_lamb_static_max_chunk_len() (2^25 elements), or a packed_in of 2 GiB or more
  *   -> OB_ERR_SIZE, nothing enqueued;
  *   other invalid sizes -> OB_ERR_ARG; NULL / misaligned pointers -> OB_ERR_NULL / OB_ERR_ALIGN.

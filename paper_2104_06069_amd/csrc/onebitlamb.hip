@@ -670,10 +670,18 @@ ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8
   }
 }
 
+namespace { ob_status static_scratch(double** out); }
+
 static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
   if (out) *out = nullptr;
   if (!out) return OB_ERR_NULL;
   if (ob_status s = check_config(cfg)) return s;
+  {
+    // set-up time is also when this device's copy of the static scratch array (used by
+    // ob_lamb_server_reduce_static, which must not do anything but launch) is looked up
+    double* unused = nullptr;
+    if (ob_status s = static_scratch(&unused)) return s;
+  }
   const int64_t L = cfg->num_layers;
   const int64_t N = cfg->layer_offsets[L];
 
