@@ -22,7 +22,9 @@ def lib():
         spec = importlib.util.spec_from_file_location("_obref_build", os.path.join(_HERE, "build.py"))
         mod = importlib.util.module_from_spec(spec)
         spec.loader.exec_module(mod)
-        _LIB = C.CDLL(mod.build(force=False))
+        # OBREF_LIB: a library built elsewhere from a DELIBERATELY WRONG copy of obref.cpp -- only
+        # tests/test_oracle_mutants.py sets it, to show that the pins fail on such a copy
+        _LIB = C.CDLL(os.environ.get("OBREF_LIB") or mod.build(force=False))
         _LIB.obref_padded_len.restype = C.c_int64
         _LIB.obref_padded_len.argtypes = [C.c_int64, C.c_int32]
     return _LIB

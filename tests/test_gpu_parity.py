@@ -369,6 +369,33 @@ def test_warmup_and_freeze(case, path, wd):
     finish(dev)
 
 
+@pytest.mark.parametrize("packed,fused", [(False, False), (True, True)])
+def test_previous_ratio_outside_its_bounds(packed, fused):
+    """Algorithm 1 applies line 18 (the window around the previous ratio) before line 19 (r_min,
+    r_max); the order shows when a loaded r_prev lies outside [r_min, r_max], and when it is not 1
+    the window is a factor, not a distance.  Two steps from previous ratios between 0.05 and 20."""
+    _need_gpu()
+    cfg = make_case("bert_mini")
+    st, ref, dev = start_pair(cfg, warm_state=True, packed=packed, fused=fused)
+    r0 = np.exp(np.random.default_rng(3).uniform(np.log(0.05), np.log(20.0), ref.L)).astype(np.float32)
+    assert (r0 < HYPER["r_min"]).sum() >= 3 and (r0 > HYPER["r_max"]).sum() >= 3
+    ref.t["r_prev"][...] = r0
+    sync_dev_from_ref(ref, dev)
+    for t in range(2):
+        g = gradient(st, cfg, t)
+        fw, fs = foreign_worker_chunks(st, cfg, t); fa, fss = foreign_server_chunks(st, cfg, t)
+        ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
+        if t:
+            dev.begin_step()
+        push_wire(ref, dev)
+        ref.step(g, 1e-3); dev.step(torch.from_numpy(g).to(dev.device), 1e-3)
+        for k in ("r_prev", "coeff_c", "x", "v_fresh"):
+            assert_close(dev.get(k), ref.t[k], f"step {t}: {k}")
+        r = dev.get("r_prev")
+        assert np.all(r >= HYPER["r_min"]) and np.all(r <= HYPER["r_max"])
+    finish(dev)
+
+
 @pytest.mark.parametrize("case,packed,fused", [("odd", False, False), ("tiny", True, True),
                                                ("bert_mini", True, True), ("bert_mini", False, True)])
 def test_degenerate_values(case, packed, fused):

@@ -199,6 +199,19 @@ def test_server_sum_is_sequential_binary32():
     assert so2 == np.float32(4194305.0)
 
 
+def test_server_divides_once_after_the_sum():
+    # W = 3 (1/W not exact), scales (1, 2^-24, 2^-24), all bits set.  Sum first: 1 + 2^-24 is a tie
+    # and rounds to 1 (even), twice; one multiply by fl(1/3) = 0x3EAAAAAB gives 0x3EAAAAAB.
+    # Dividing every term instead gives fl(1/3) + 1.99e-8 twice; each addend is more than half an
+    # ulp (1.49e-8) of the sum and rounds it up: 0x3EAAAAAD.
+    n_c, W = 8, 3
+    bits_in = np.full(W * n_c // 8, 0xFF, np.uint8)
+    sc = np.array([1.0, 2.0 ** -24, 2.0 ** -24], dtype=np.float32)
+    es = np.zeros(n_c, dtype=np.float32)
+    _, so = F32.server_reduce(W, bits_in, sc, es)     # all elements equal: the scale is that value
+    assert np.float32(so).view(np.uint32) == 0x3EAAAAAB
+
+
 @pytest.mark.parametrize("ref,tol", [(F32, 1e-6), (F64, 1e-13)])
 def test_server_average_vs_dense_mean(ref, tol):
     # decompress every worker with the (pinned) chunk decompressor, average with numpy
@@ -332,6 +345,18 @@ def test_ratios_hand():
     vf = np.array([4.0, 8, 4]); r_prev = np.array([4.0, 0.5])
     F64.ratios_dense(off, 0.5, 0.75, 0.5, 4.0, 0.1, mt, m, vf, vz, c_avg, r_prev)
     assert r_prev.tolist() == [pytest.approx(3.6), 0.5]   # raw 2 -> window [3.6, 4.4] -> 3.6
+    # the window is a FACTOR around the previous ratio, above as well as below: r_prev = 1.5 -> window
+    # [1.35, 1.65]; raw 2 -> 1.65 (a window of +-0.1 would give 1.6)
+    vf = np.array([4.0, 8, 4]); r_prev = np.array([1.5, 1.5])
+    F64.ratios_dense(off, 0.5, 0.75, 0.5, 4.0, 0.1, mt, m, vf, vz, c_avg, r_prev)
+    assert r_prev.tolist() == [pytest.approx(1.65), pytest.approx(1.35)]
+    # line 18 before line 19, visible when the previous ratio lies outside [r_min, r_max] (a state
+    # loaded from elsewhere, or bounds changed between runs): r_prev = 0.2 -> window [0.18, 0.22];
+    # raw 2 -> 0.22 -> r_min = 0.5 (the other order ends at 0.22);  r_prev = 8 -> window [7.2, 8.8];
+    # raw 0.25 -> 7.2 -> r_max = 4 (the other order ends at 7.2)
+    vf = np.array([4.0, 8, 4]); r_prev = np.array([0.2, 8.0])
+    F64.ratios_dense(off, 0.5, 0.75, 0.5, 4.0, 0.1, mt, m, vf, vz, c_avg, r_prev)
+    assert r_prev.tolist() == [0.5, 4.0]
 
 
 def test_ratio_special_values():
