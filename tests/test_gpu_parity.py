@@ -331,6 +331,11 @@ def test_warmup_and_freeze(case, path, wd):
     st = Streams(3)
     pl = cfg["plist"]
     hyper = dict(HYPER); hyper["weight_decay"] = wd
+    if wd == 0.0:
+        # with these inputs ||x||/||u|| is about 0.006, below the paper's c_min: lower the bound so that
+        # the coefficient is the ratio of the two norms itself and not the clip's bound (checked below);
+        # the wd = 0.01 cases keep the paper's bounds and run clipped
+        hyper["c_min"] = 1e-4
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **hyper)
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], two_pass_warmup=(path == "two_pass"),
                      fused_max_tiles=(path if isinstance(path, int) else None), **hyper)
@@ -353,6 +358,9 @@ def test_warmup_and_freeze(case, path, wd):
         dev.warmup_step(torch.from_numpy(g).to(dev.device), 1e-3 * (t + 1))
         for k in ("m", "v_fresh", "x", "coeff_c", "c_avg"):
             assert_close(dev.get(k), ref.t[k], f"step {t}: {k}")
+        if wd == 0.0:
+            c = ref.t["coeff_c"][np.diff(pl.offsets) > 0]
+            assert ((c > hyper["c_min"]) & (c < hyper["c_max"])).mean() > 0.5, "most coefficients should be unclipped"
     ref.freeze(); dev.freeze()
     assert np.array_equal(dev.get("v_frozen"), dev.get("v_fresh"))
     assert np.all(dev.get("r_prev") == 1.0)
@@ -692,6 +700,11 @@ def test_mixed_precision_variant(case, gfmt, xfmt, fused, packed, scale):
     s = init_state(st, cfg)
     s["v_fresh"][...] = 0
     s["c_avg"][...] = 0
+    # parameters whose 16-bit copy overflows, lands on the largest finite value or is subnormal
+    # (binary16: max 65504, ties at 65520, subnormals below 6.1e-5; bfloat16: max 3.39e38)
+    special = [7e4, 65519.0, 65520.0, -65536.0, -1e-7, 3e-8, 3.39e38, -3.4e38, 1e-40]
+    i0 = int(np.argmax(np.diff(pl.offsets) >= len(special)))      # the first tensor that can hold them
+    s["x"][pl.offsets[i0]:pl.offsets[i0] + len(special)] = np.array(special, np.float32)
     ref.load_state(s)
     dev.load_state(ref.t)
     N = ref.N
@@ -1037,6 +1050,35 @@ def test_random_layer_lists(seed):
         for key in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
             assert_close(dev.get(key), ref.t[key], f"step {t} {key}")
     finish(dev)
+
+
+@pytest.mark.parametrize("form", ["single_pass", "two_pass", "deferred"])
+def test_server_sum_order_and_single_division(form):
+    """Inputs on which the binary32 server average depends on HOW it is formed: scales (2^24, 1, 1, 1)
+    give 2^24 when the workers are added in the order 0..W-1 and 2^24 + 1 otherwise; scales
+    (1, 2^-24, 2^-24) at W = 3 give fl(1/3) when the sum is divided once and two ulps more when every
+    term is divided.  All sign bits are set and the carried error is 0, so every element of the
+    average has that value and the recompressed scale equals it: compared bit for bit."""
+    _need_gpu()
+    from tests.refstep import F32
+    for scales in ([2.0 ** 24, 1, 1, 1], [1, 1, 1, 2.0 ** 24], [1, 2.0 ** -24, 2.0 ** -24], [2.0 ** -24, 2.0 ** -24, 1]):
+        W = len(scales)
+        n_c = 2048
+        pl = ParamList("srv", [("a", n_c * W)])
+        dev = DeviceStep(pl.offsets, W, 0, two_pass=(form == "two_pass"), deferred_error=(form == "deferred"), **HYPER)
+        assert dev.n_c == n_c
+        sc = np.array(scales, np.float32)
+        words = np.full(W * n_c // 8, 0xFF, np.uint8)
+        err = np.zeros(n_c, np.float32)
+        _, s_ref = F32.server_reduce(W, words, sc, err)
+        dev.packed_in.copy_(torch.from_numpy(words.view(np.int32)))
+        dev.scales_in.copy_(torch.from_numpy(sc))
+        dev.server_reduce()
+        torch.cuda.synchronize()
+        s_dev = dev.server_scales.cpu().numpy()[0]
+        assert np.float32(s_dev).view(np.uint32) == np.float32(s_ref).view(np.uint32), (scales, s_dev, s_ref)
+        assert np.array_equal(dev.get("err_server").view(np.uint32), err.view(np.uint32)), scales
+        finish(dev)
 
 
 @pytest.mark.parametrize("n_c_target,W,expect", [

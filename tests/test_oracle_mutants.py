@@ -102,29 +102,33 @@ MUTANTS = [
 ]
 
 
+def build_mutant(m, base):
+    """Compile the copy of obref.cpp with mistake m = (name, old, new, count, which) planted, under
+    the directory `base`; -> (name, path of the library)."""
+    from oracle.build import FLAGS
+    name, old, new, count, which = m
+    text = open(SRC).read()
+    assert text.count(old) == count, f"{name}: the text to replace occurs {text.count(old)} times, not {count}"
+    parts = text.split(old)
+    mutated = old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
+    d = os.path.join(str(base), name)
+    os.makedirs(d)
+    shutil.copy(os.path.join(ROOT, "oracle", "obref.h"), os.path.join(d, "obref.h"))
+    with open(os.path.join(d, "obref.cpp"), "w") as f:
+        f.write(mutated)
+    lib = os.path.join(d, "libobref_mutant.so")
+    flags = [f for f in FLAGS if f != "-O2"] + ["-O1", "-w"]
+    r = subprocess.run(["g++"] + flags + [os.path.join(d, "obref.cpp"), "-o", lib], capture_output=True, text=True)
+    assert r.returncode == 0, f"{name}: the mutated copy does not compile:\n{r.stderr[-2000:]}"
+    return name, lib
+
+
 @pytest.fixture(scope="module")
 def mutant_libs(tmp_path_factory):
     """name -> path of the library built from the mutated copy (all built up front, in parallel)."""
-    from oracle.build import FLAGS
     base = tmp_path_factory.mktemp("mutants")
-    text = open(SRC).read()
-
-    def make(m):
-        name, old, new, count, which = m
-        assert text.count(old) == count, f"{name}: the text to replace occurs {text.count(old)} times, not {count}"
-        parts = text.split(old)
-        mutated = old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
-        d = base / name
-        d.mkdir()
-        shutil.copy(os.path.join(ROOT, "oracle", "obref.h"), d / "obref.h")
-        (d / "obref.cpp").write_text(mutated)
-        lib = str(d / "libobref_mutant.so")
-        flags = [f for f in FLAGS if f != "-O2"] + ["-O1", "-w"]
-        r = subprocess.run(["g++"] + flags + [str(d / "obref.cpp"), "-o", lib], capture_output=True, text=True)
-        assert r.returncode == 0, f"{name}: the mutated copy does not compile:\n{r.stderr[-2000:]}"
-        return name, lib
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
-        return dict(ex.map(make, MUTANTS))
+        return dict(ex.map(lambda m: build_mutant(m, base), MUTANTS))
 
 
 def run_pins(lib=None):
