@@ -1682,9 +1682,16 @@ __global__ __launch_bounds__(FBLOCK) void k_warmup_coeff(const double* __restric
   const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
   const float ca = c_avg[l];
   double sx = 0.0, su = 0.0;
-  for (int s = s0 + threadIdx.x; s < s1; s += FBLOCK) {
-    sx += seg_sums[2 * (int64_t)s];
-    su += seg_sums[2 * (int64_t)s + 1];
+  for (int s = s0 + threadIdx.x; s < s1; s += 4 * FBLOCK) {   // four pairs in flight per thread
+    double vx[4], vu[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool in = (s + u * FBLOCK < s1);
+      vx[u] = in ? seg_sums[2 * (int64_t)(s + u * FBLOCK)] : 0.0;
+      vu[u] = in ? seg_sums[2 * (int64_t)(s + u * FBLOCK) + 1] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { sx += vx[u]; su += vu[u]; }
   }
   sx = block_sum<FBLOCK>(sx, lds);
   su = block_sum<FBLOCK>(su, lds);
@@ -1907,43 +1914,88 @@ __global__ __launch_bounds__(BLOCK, OB_WU_MINW) void k_warmup_resident(
 //   a: per (tile, layer) segment the fp64 sum of m^2
 //   b: one workgroup: per-layer sigma, their mean (fixed order), k_l
 // ---------------------------------------------------------------------------------------------
-template <int U>
+// A workgroup takes R consecutive tiles of the 1024-element tiling (the segment tables are the
+// plain kernels'), looks up what it needs to know about all of them, then requests all of them,
+// then reduces them one by one: with one 128-bit load per thread in flight, and the table look-ups
+// of a tile that meets a layer boundary (three dependent loads) made for every tile after its data
+// had arrived, the kernel ran at half the streaming rate.
+template <int R>
 __global__ __launch_bounds__(BLOCK) void k_momentum_sumsq(const float* __restrict__ m,
                                                           double* __restrict__ seg_sums,
-                                                          int64_t n_c, int tpc, LayerTab lt,
+                                                          int64_t n_c, int tpc, int n_tiles, LayerTab lt,
                                                           const int* __restrict__ tile_seg0,
                                                           const int* __restrict__ seg_layer) {
-  constexpr int TILE = SPAN * U;
   __shared__ double lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc, (int)blockIdx.x);
-  const int l0 = lt.first_layer[p.t];
-  if (l0 >= lt.L) return;
-  const int o0 = threadIdx.x * 4;
-  v4f M[U];
+  const int o = threadIdx.x * 4;
+  const int t0 = (int)blockIdx.x * R;
+  TilePos P[R];
+  int l0[R], s0[R];
+  int64_t end0[R];       // end of the layer the tile starts in
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int o = u * SPAN + o0;
-    M[u] = 0.0f;
-    if (o < p.len) M[u] = ld4(m + p.tile0 + o);
+  for (int r = 0; r < R; ++r) {
+    const int t = (t0 + r < n_tiles) ? t0 + r : n_tiles - 1;   // (a repeated last tile is skipped below)
+    P[r] = tile_pos<SPAN>(n_c, tpc, t);
+    l0[r] = lt.first_layer[t];
+    s0[r] = tile_seg0[t];
   }
-  const int s0 = tile_seg0[p.t], s1 = tile_seg0[p.t + 1];
-  for (int s = s0; s < s1; ++s) {
-    const int l = seg_layer[s];
-    const int64_t a = lt.off[l], b = lt.off[l + 1];
+#pragma unroll
+  for (int r = 0; r < R; ++r) end0[r] = lt.off[l0[r] + 1];   // off has L+2 entries
+  v4f M[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    M[r] = 0.0f;
+    if (t0 + r < n_tiles && l0[r] < lt.L && o < P[r].len) M[r] = ld4(m + P[r].tile0 + o);
+  }
+  // the usual case: all R tiles lie inside one and the same layer -- one reduction for all of them;
+  // the sum goes to the first tile's segment and the other segments contribute 0 to the layer
+  bool together = (t0 + R <= n_tiles) && (l0[0] < lt.L);
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+    together = together && (l0[r] == l0[0]) && (P[r].len == SPAN) && (P[r].tile0 + SPAN <= end0[r]);
+  if (together) {   // uniform
     double acc = 0.0;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int o = u * SPAN + o0;
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc += (double)M[r][k] * (double)M[r][k];
+    acc = block_sum(acc, lds);
+    if (threadIdx.x == 0) {
+      seg_sums[s0[0]] = acc;
+#pragma unroll
+      for (int r = 1; r < R; ++r) seg_sums[s0[r]] = 0.0;
+    }
+    return;
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    if (t0 + r >= n_tiles) break;          // uniform
+    if (l0[r] >= lt.L) continue;           // uniform: the tile lies in the padding (it has no segment)
+    const TilePos& p = P[r];
+    if (p.tile0 + p.len <= end0[r]) {      // uniform: the tile lies inside one layer, its one segment
+      double acc = 0.0;
+      if (o < p.len) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc += (double)M[r][k] * (double)M[r][k];
+      }
+      acc = block_sum(acc, lds);
+      if (threadIdx.x == 0) seg_sums[s0[r]] = acc;
+      continue;
+    }
+    const int s1 = tile_seg0[p.t + 1];
+    for (int s = s0[r]; s < s1; ++s) {
+      const int l = seg_layer[s];
+      const int64_t a = lt.off[l], b = lt.off[l + 1];
+      double acc = 0.0;
       if (o < p.len) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int64_t i = p.tile0 + o + k;
-          if (i >= a && i < b) acc += (double)M[u][k] * (double)M[u][k];
+          if (i >= a && i < b) acc += (double)M[r][k] * (double)M[r][k];
         }
       }
+      acc = block_sum(acc, lds);
+      if (threadIdx.x == 0) seg_sums[s] = acc;
     }
-    acc = block_sum(acc, lds);
-    if (threadIdx.x == 0) seg_sums[s] = acc;
   }
 }
 
@@ -1955,7 +2007,14 @@ __global__ __launch_bounds__(FBLOCK) void k_layer_rms(const double* __restrict__
   __shared__ double lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
   double a = 0.0;
-  for (int s = layer_seg0[l] + threadIdx.x; s < layer_seg0[l + 1]; s += FBLOCK) a += seg_sums[s];
+  const int s1 = layer_seg0[l + 1];
+  for (int s = layer_seg0[l] + threadIdx.x; s < s1; s += 4 * FBLOCK) {   // four loads in flight per thread
+    double v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = (s + u * FBLOCK < s1) ? seg_sums[s + u * FBLOCK] : 0.0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a += v[u];
+  }
   a = block_sum<FBLOCK>(a, lds);
   if (threadIdx.x == 0) {
     const int64_t n = off[l + 1] - off[l];

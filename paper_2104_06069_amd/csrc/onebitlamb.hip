@@ -1205,8 +1205,10 @@ ob_status ob_lamb_momentum_scale(ob_lamb_ctx* ctx, const ob_lamb_state* st, void
   if (!st->mom_scale) return OB_ERR_NULL;
   Launch la(ctx, hip_stream);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  OB_LAUNCH(la, KID_MOMENTUM_SCALE, (k_momentum_sumsq<U_MAIN>), ctx->n_tiles, st->m, ctx->d_seg_sums,
-            ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
+  constexpr int R = 8;   // tiles per workgroup
+  static_assert(U_MAIN == 1, "the segment tables are those of the 1024-element tiling");
+  OB_LAUNCH(la, KID_MOMENTUM_SCALE, (k_momentum_sumsq<R>), (ctx->n_tiles + R - 1) / R, st->m, ctx->d_seg_sums,
+            ctx->n_c, ctx->tpc, ctx->n_tiles, lt, ctx->d_tile_seg0, ctx->d_seg_layer);
   OB_LAUNCH_B(la, KID_MOMENTUM_SCALE, k_layer_rms, (int)ctx->L, FBLOCK, ctx->d_seg_sums, ctx->d_layer_seg0,
               ctx->d_off, ctx->d_sigma);
   OB_LAUNCH_B(la, KID_MOMENTUM_SCALE, k_momentum_scale, 1, FBLOCK, ctx->d_sigma, ctx->d_off, (int)ctx->L,
