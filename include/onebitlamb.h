@@ -257,6 +257,47 @@ ob_status ob_lamb_decompress_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st,
  * for every layer with more than n such tiles. */
 ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, float lr, void* hip_stream);
+/* The fresh variance in deferred form: ob_lamb_ratios_apply for callers that keep the sign words and
+ * scales of the last few global momenta (they are the steps' own packed_all / server_scales buffers).
+ *
+ * With the momentum in 1-bit form the reconstructed gradient of Algorithm 1 line 15 takes one of two
+ * magnitudes per chunk, layer and step, chosen per element by whether the momentum's sign bit
+ * flipped.  The variance after several steps therefore follows from st->v_fresh as last written and
+ * the momenta since then, by the very operations line 16 performs step by step (the results are
+ * bit-identical); line 17 needs the up-to-date variance of every element, but the array need not be
+ * rewritten at every step.  A call with write_v = 0 reads st->v_fresh and writes nothing to it
+ * (4 bytes per parameter less than ob_lamb_ratios_apply, plus one bit per parameter and older
+ * momentum read); a call with write_v = 1 brings the array up to date, after which the history
+ * starts anew (the next call passes n_old = 0).
+ *
+ * n_old: number of momenta older than the previous one (st->m_packed / st->m_scales) that have been
+ * committed since st->v_fresh was last written, 0..OB_VF_MAX_OLD; bits[i] / scales[i], i < n_old:
+ * their sign words [N_pad/32] and scales [W], NEWEST FIRST (bits[0] is the momentum before the
+ * previous one), device pointers, 16-byte aligned, read only.  st->v_fresh must be the variance as
+ * of the momentum bits[n_old-1] (as of the previous momentum if n_old = 0).  h = NULL means
+ * n_old = 0, write_v = 1: ob_lamb_ratios_apply itself.
+ * Requires the momentum in 1-bit form (st->m == NULL, else OB_ERR_ARG).  Everything else -- layers,
+ * barrier, bounded waits, what an expired wait leaves behind -- as for ob_lamb_ratios_apply. */
+#define OB_VF_MAX_OLD 7
+typedef struct ob_lamb_vf_history {
+  int32_t n_old;
+  int32_t write_v;
+  const uint32_t* bits[OB_VF_MAX_OLD];
+  const float* scales[OB_VF_MAX_OLD];
+} ob_lamb_vf_history;
+ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                    const float* server_scales, float lr, const ob_lamb_vf_history* h,
+                                    void* hip_stream);
+/* Dense view of a variance held in that form: v_out [N_pad] receives the variance as of the momentum
+ * (packed_all, server_scales), given st->v_fresh, st->m_packed / st->m_scales and h exactly as they
+ * were passed to the ob_lamb_ratios_apply_hist call that committed that momentum (h->write_v is
+ * ignored).  The padding of v_out is left untouched.  v_out may be st->v_fresh itself (the array is
+ * then up to date: the next call passes n_old = 0).  For checkpoints, inspection and a return to
+ * the LAMB step. */
+ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                 const float* server_scales, const ob_lamb_vf_history* h, float* v_out,
+                                 void* hip_stream);
+
 /* Host-only planning query (no HIP call, no device needed): how ob_lamb_create splits a tensor list
  * between a kernel with a per-layer barrier and the plain kernels when one layer may occupy at most
  * max_tiles of that kernel's 8192-element tiles (on a device, 80 % of the kernel's workgroup

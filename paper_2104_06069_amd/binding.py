@@ -35,6 +35,7 @@ class ObLambConfig(C.Structure):
 OB_CFG_TWO_PASS_COMPRESS, OB_CFG_NO_FUSED_APPLY, OB_CFG_TWO_PASS_WARMUP = 1, 2, 4
 OB_CFG_NO_BARRIERS = 7
 OB_SPIN_NONE = -1
+OB_VF_MAX_OLD = 7
 
 
 class ObLambState(C.Structure):
@@ -42,6 +43,11 @@ class ObLambState(C.Structure):
                 ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev",
                  "coeff_c", "mom_scale", "m_packed", "m_scales", "own_packed_in", "own_scale_in",
                  "err_packed", "err_scales", "srv_err_packed", "srv_err_scale")]
+
+
+class ObLambVfHistory(C.Structure):
+    _fields_ = [("n_old", C.c_int32), ("write_v", C.c_int32),
+                ("bits", C.c_void_p * OB_VF_MAX_OLD), ("scales", C.c_void_p * OB_VF_MAX_OLD)]
 
 
 def lib_path():
@@ -85,6 +91,8 @@ def lib():
             "ob_lamb_warmup_fused_params": (i64, [vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
+            "ob_lamb_ratios_apply_hist": (C.c_int, [vp, sp, vp, vp, f, C.POINTER(ObLambVfHistory), vp]),
+            "ob_lamb_variance_dense": (C.c_int, [vp, sp, vp, vp, C.POINTER(ObLambVfHistory), vp, vp]),
             "ob_lamb_error_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_server_error_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_check_device_status": (C.c_int, [vp, vp]),
@@ -288,6 +296,31 @@ def ob_lamb_warmup_fused_params(ctx):
 def ob_lamb_momentum_dense(ctx, state, m_out, stream=None):
     _check(lib().ob_lamb_momentum_dense(ctx, C.byref(state), _addr(m_out), _addr(stream)), ctx,
            "ob_lamb_momentum_dense")
+
+
+def make_vf_history(bits, scales, write_v):
+    """ob_lamb_vf_history from the older momenta's sign-word and scale tensors, NEWEST FIRST."""
+    assert len(bits) == len(scales) <= OB_VF_MAX_OLD
+    h = ObLambVfHistory()
+    h.n_old = len(bits)
+    h.write_v = 1 if write_v else 0
+    for i, (b, s) in enumerate(zip(bits, scales)):
+        h.bits[i] = _addr(b)
+        h.scales[i] = _addr(s)
+    h._keep = (list(bits), list(scales))   # the tensors must outlive the call
+    return h
+
+
+def ob_lamb_ratios_apply_hist(ctx, state, packed_all, server_scales, lr, hist, stream=None):
+    _check(lib().ob_lamb_ratios_apply_hist(ctx, C.byref(state), _addr(packed_all), _addr(server_scales), lr,
+                                           None if hist is None else C.byref(hist), _addr(stream)),
+           ctx, "ob_lamb_ratios_apply_hist")
+
+
+def ob_lamb_variance_dense(ctx, state, packed_all, server_scales, hist, v_out, stream=None):
+    _check(lib().ob_lamb_variance_dense(ctx, C.byref(state), _addr(packed_all), _addr(server_scales),
+                                        None if hist is None else C.byref(hist), _addr(v_out), _addr(stream)),
+           ctx, "ob_lamb_variance_dense")
 
 
 def ob_lamb_error_dense(ctx, state, err_out, stream=None):

@@ -1496,6 +1496,302 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_stream(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The fresh variance in deferred form (Algorithm 1 line 16 evaluated every step, stored every few).
+//
+// With the momentum in 1-bit form the reconstructed gradient of line 15 takes two magnitudes per
+// (chunk, layer) and step, chosen per element by whether the momentum's sign bit flipped.  So the
+// variance after a more steps follows from the variance array as last written ("base") and the
+// sign words and scales of the a+1 momenta since then, by the very operations line 16 would have
+// performed step by step (v <- beta2*v + t, t one of the two values of that step): the ratio of
+// line 17 needs the up-to-date variance of every element in registers, but the array need not be
+// rewritten each time.  A step then reads the base (4 bytes per element, as before) plus one bit
+// per element and older step, and writes nothing; every few steps the caller asks for the array to
+// be brought up to date (write_v) and the history starts anew.
+//
+// Planes, newest first: 0 = the new momentum (RatioArgs.packed / sscales), 1 = the previous one
+// (RatioArgs.pm), 2 + i = VfHist.bits[i] / scales[i] for i < n_old (so bits[0] is the momentum
+// before the previous one).  The base is the variance as of plane n_old + 1.
+// ---------------------------------------------------------------------------------------------
+constexpr int VF_MAX_OLD = 7;
+struct VfHist {
+  int n_old;                            // 0..VF_MAX_OLD
+  int write_v;                          // store the up-to-date variance
+  const uint32_t* bits[VF_MAX_OLD];     // [N_pad/32] each
+  const float* scales[VF_MAX_OLD];      // [W] each
+};
+
+// The two values omb2*g^2 of one step (the operations of RatioTile::uniform_pass, in its order).
+// s_new, s_old: the chunk's scale of the step's momentum and of the one before.
+template <bool HAS_K>
+__device__ __forceinline__ void variance_terms(const RatioArgs& ra, float s_new, float s_old, float kt,
+                                               float* t_same, float* t_diff) {
+  const float sp = HAS_K ? s_new / kt : s_new;
+  const float bm = ra.beta1 * (HAS_K ? s_old / kt : s_old);
+  const float g_same = (sp - bm) / ra.omb1;     // new and old momentum of equal sign
+  const float g_diff = (sp - (-bm)) / ra.omb1;  // of opposite sign
+  *t_same = ra.omb2 * (g_same * g_same);
+  *t_diff = ra.omb2 * (g_diff * g_diff);
+}
+
+// bit ? a : b on the bit patterns, with the bit taken from position `pos` of `word` (two vector
+// instructions: a signed one-bit field extract gives the all-ones / all-zeros mask)
+__device__ __forceinline__ float select_by_bit(unsigned int word, int pos, float a, float b) {
+  const unsigned int m = (unsigned int)(((int)(word << (31 - pos))) >> 31);
+  return __uint_as_float((m & __float_as_uint(a)) | (~m & __float_as_uint(b)));
+}
+
+// scale of plane q (newest first) for chunk c; q is a compile-time constant where it is called
+__device__ __forceinline__ float plane_scale(const RatioArgs& ra, const VfHist& h, int q, int c) {
+  return q == 0 ? ra.sscales[c] : (q == 1 ? ra.pm.scales[c] : h.scales[q - 2][c]);
+}
+__device__ __forceinline__ const uint32_t* plane_bits(const RatioArgs& ra, const VfHist& h, int q) {
+  return q == 0 ? ra.packed : (q == 1 ? ra.pm.bits : h.bits[q - 2]);
+}
+
+// K5 over plain 1024-element tiles with the variance in deferred form.  seg_max may be NULL (no
+// ratio wanted: the dense view of the variance).  The up-to-date variance goes to the base array
+// itself if h.write_v, else to vf_dense if that is not NULL (a dense view in another array, which
+// leaves the base as it is), else nowhere.
+template <bool HAS_K>
+__global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist h, float* __restrict__ seg_max,
+                                                            float* __restrict__ vf_dense, int64_t n_c, int tpc, LayerTab lt,
+                                                            const int* __restrict__ tile_seg0,
+                                                            const int* __restrict__ seg_layer,
+                                                            const int* __restrict__ tile_list) {
+  __shared__ float lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<SPAN>(n_c, tpc, listed_tile(tile_list));
+  const int l0 = lt.first_layer[p.t];
+  if (l0 >= lt.L) return;  // tile lies in the padding (it has no segment)
+  const int a = h.n_old + 1;   // steps to apply
+  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const int64_t l0_end = lt.off[l0 + 1];
+  const int s0 = tile_seg0[p.t];
+  const int o = threadIdx.x * 4;
+  const bool in = (o < p.len);
+  float* vf_out = h.write_v ? ra.v_fresh : vf_dense;   // uniform
+  unsigned int NBq[VF_MAX_OLD + 2];   // the lane's nibble of every plane, newest first
+  float SC[VF_MAX_OLD + 2];           // the chunk's scale of every plane
+#pragma unroll
+  for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
+    NBq[q] = 0u; SC[q] = 0.0f;
+    if (q <= a) {   // uniform
+      SC[q] = plane_scale(ra, h, q, p.c);
+      if (in) NBq[q] = load_nibble(plane_bits(ra, h, q), p.tile0);
+    }
+  }
+  v4f V = 0.0f, VZ = 0.0f;
+  if (in) {
+    V = ld4(ra.v_fresh + p.tile0 + o);
+    VZ = ld4(ra.v_frozen + p.tile0 + o);
+  }
+  const bool uniform = (p.tile0 + p.len <= l0_end);
+  const int64_t N = lt.off[lt.L];
+  if (uniform) {
+#pragma unroll
+    for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
+      if (s <= a) {   // uniform: the step from plane s to plane s-1
+        float t_same, t_diff;
+        variance_terms<HAS_K>(ra, SC[s - 1], SC[s], kt, &t_same, &t_diff);
+        const unsigned int flip = NBq[s] ^ NBq[s - 1];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) V[k] = ra.beta2 * V[k] + select_by_bit(flip, k, t_diff, t_same);
+      }
+    }
+    float r = 0.0f;
+    if (in) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float q = VZ[k] / V[k];
+        if (q > r) r = q;
+      }
+      if (vf_out) st4(vf_out + p.tile0 + o, V);
+    }
+    if (seg_max) {
+      r = block_max(r, lds);
+      if (threadIdx.x == 0) seg_max[s0] = r;
+    }
+  } else {
+    // the tile meets a layer boundary or the end of the parameters: element by element, leaving the
+    // padding alone (the operations of RatioTile::element_pass, once per step)
+    float Q[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (in) {
+      int l = l0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int64_t i = p.tile0 + o + k;
+        if (i < N) {
+          l = walk_layer(l, i, lt.off);
+          const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
+          float v = V[k];
+#pragma unroll
+          for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
+            if (s <= a) {
+              const float sp = HAS_K ? SC[s - 1] / kk : SC[s - 1];
+              const float mt = ((NBq[s - 1] >> k) & 1u) ? sp : -sp;
+              const float b = ra.beta1 * (HAS_K ? SC[s] / kk : SC[s]);
+              const float bmk = ((NBq[s] >> k) & 1u) ? b : -b;
+              const float gr = (mt - bmk) / ra.omb1;
+              v = ra.beta2 * v + ra.omb2 * (gr * gr);
+            }
+          }
+          if (vf_out) vf_out[i] = v;
+          Q[k] = VZ[k] / v;
+        }
+      }
+    }
+    if (seg_max) {
+      const int s1 = tile_seg0[p.t + 1];
+      for (int sg = s0; sg < s1; ++sg) {
+        const int l = seg_layer[sg];
+        const int64_t lo = lt.off[l], hi = lt.off[l + 1];
+        float r = 0.0f;
+        if (in) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int64_t i = p.tile0 + o + k;
+            if (i >= lo && i < hi && Q[k] > r) r = Q[k];
+          }
+        }
+        r = block_max(r, lds);
+        if (threadIdx.x == 0) seg_max[sg] = r;
+      }
+    }
+  }
+}
+
+// k_ratios_apply_resident with the variance in deferred form.  A wavefront's part of a tile is 64
+// words of every plane (8 spans x 8 words): each lane fetches ONE word of each plane and the lanes
+// then pass each other the words they need; what a lane keeps of a plane is its 8 nibbles packed
+// into one register.
+template <bool HAS_K, bool LPX>
+__global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
+    RatioArgs ra, VfHist h, ApplyArgs aa, LayerSync ls, LayerTab lt) {
+  constexpr int U = 8;
+  constexpr int TILE = SPAN * U;
+  __shared__ float lds[BLOCK / WAVE];
+  __shared__ unsigned long long bc;
+  const int tpc = ls.lt.tpc;
+  const TilePos p = tile_pos<TILE>(ls.lt.n_c, tpc, ls.lt.tile_list[blockIdx.x]);
+  const int sp0 = p.c * ls.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span
+  const int l0 = lt.first_layer[sp0];  // the layer the tile lies in (lt.first_layer: of the 1024-element tiling)
+  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const LayerParts lp = layer_parts(ls.lt, l0);
+  const float rp = ls.r_prev[l0], ca = ls.c_avg[l0];
+  const int a = h.n_old + 1;   // steps to apply
+  const int o0 = threadIdx.x * 4;
+  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+  // the lane's word of each plane: span lane/8, word lane%8 of the wavefront's 8 words (256 elements) of that span
+  const int e0 = (lane >> 3) * SPAN + wv * (WAVE * 4) + (lane & 7) * 32;
+  const bool have_word = (e0 < p.len);   // len is a multiple of 256: a wavefront's part of a span is all there or all missing
+  const int64_t wi = (p.tile0 + e0) >> 5;
+  unsigned int Wq[VF_MAX_OLD + 2];
+  float SC[VF_MAX_OLD + 2];
+#pragma unroll
+  for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
+    Wq[q] = 0u; SC[q] = 0.0f;
+    if (q <= a) {   // uniform
+      SC[q] = plane_scale(ra, h, q, p.c);
+      if (have_word) Wq[q] = plane_bits(ra, h, q)[wi];
+    }
+  }
+  v4f V[U], VZ[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    V[u] = 0.0f; VZ[u] = 0.0f;
+    if (o < p.len) {
+      V[u] = ld4(ra.v_fresh + p.tile0 + o);
+      VZ[u] = ld4(ra.v_frozen + p.tile0 + o);
+    }
+  }
+  // flips between consecutive planes, formed on the words as loaded; plane 0 stays (line 21 needs it)
+#pragma unroll
+  for (int s = VF_MAX_OLD + 1; s >= 1; --s)
+    if (s <= a) Wq[s] ^= Wq[s - 1];
+  // the lanes' own nibbles of every span, 8 to a register
+  const int src = lane >> 3;               // + 8*u: the lane that holds this lane's word of span u
+  const unsigned int sh = 4u * (lane & 7);
+#pragma unroll
+  for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
+    if (q <= a) {   // uniform
+      unsigned int packed = 0u;
+#pragma unroll
+      for (int u = 0; u < U; ++u) packed |= ((__shfl(Wq[q], 8 * u + src, WAVE) >> sh) & 15u) << (4 * u);
+      Wq[q] = packed;
+    }
+  }
+#pragma unroll
+  for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
+    if (s <= a) {   // uniform: the step from plane s to plane s-1
+      float t_same, t_diff;
+      variance_terms<HAS_K>(ra, SC[s - 1], SC[s], kt, &t_same, &t_diff);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) V[u][k] = ra.beta2 * V[u][k] + select_by_bit(Wq[s], 4 * u + k, t_diff, t_same);
+    }
+  }
+  float r = 0.0f;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float q = VZ[u][k] / V[u][k];
+        if (q > r) r = q;
+      }
+    }
+  }
+  r = block_max(r, lds);
+  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);   // before any store: nothing to wait for
+  if (h.write_v) {   // uniform
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int o = u * SPAN + o0;
+      if (o < p.len) st4(ra.v_fresh + p.tile0 + o, V[u]);
+    }
+  }
+  v4f X[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {  // x is fetched while the layer completes
+    const int o = u * SPAN + o0;
+    X[u] = 0.0f;
+    if (o < p.len) X[u] = ld4(aa.x + p.tile0 + o);
+  }
+  // m_t/(sqrt(v_frozen)+eta), formed in place of v_frozen while the layer completes (the same
+  // operations on the same operands as apply_uniform's)
+  const float ss = SC[0];
+  const float sp = HAS_K ? ss / kt : ss;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float mt = ((Wq[0] >> (4 * u + k)) & 1u) ? sp : -sp;
+        float uu = mt / (sqrtf(VZ[u][k]) + aa.eta);
+        asm volatile("" : "+v"(uu));   // evaluated here, not sunk below the wait
+        VZ[u][k] = uu;
+      }
+    }
+  }
+  const float c = layer_wait(ls, l0, &bc);
+  const float al = aa.lr * c;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+      v4f xn;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) xn[k] = X[u][k] - al * VZ[u][k];
+      st4(aa.x + p.tile0 + o, xn);
+      if (LPX) st4_lp(aa.x_lp, p.tile0 + o, xn, aa.x_lp_bf16);
+    }
+  }
+}
+
 // Dense view of a momentum held in 1-bit form: m[i] = (bit ? s_c : -s_c)/k_l for i < N (the
 // padding of m is left untouched).
 template <int U, bool HAS_K>

@@ -92,6 +92,9 @@ enum KernelId {
   KID_RATIOS_FINALIZE,
   KID_APPLY,
   KID_RATIOS_APPLY_RESIDENT,
+  KID_RATIOS_PASS_HIST,
+  KID_RATIOS_APPLY_HIST,
+  KID_VARIANCE_DENSE,
   KID_MOMENTUM_DENSE,
   KID_ERROR_DENSE,
   KID_MOMENTUM_SCALE,
@@ -106,7 +109,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "compress_deferred", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "ratios_apply_resident", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "ratios_apply_resident", "ratios_pass_hist", "ratios_apply_hist", "variance_dense", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
 
 struct ProfRec {
@@ -792,6 +795,10 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
                 "hipOccupancyMaxActiveBlocksPerMultiprocessor") &&
          hip_ok(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device),
                 "hipDeviceGetAttribute");
+    int per_cu_h = 0;   // the same tiles go through the kernel with the variance in deferred form
+    ok = ok && hip_ok(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_h, k_ratios_apply_hist<true, false>, BLOCK, 0),
+                      "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+    per_cu_a = std::min(per_cu_a, per_cu_h);
     const int64_t max_a = (cfg->flags & OB_CFG_NO_FUSED_APPLY)
                               ? 0 : split_max_tiles(std::min(per_cu_a, OB_LB_MINW), cus, cfg->fused_max_tiles);
     const int64_t max_w = (cfg->flags & OB_CFG_TWO_PASS_WARMUP)
@@ -1154,6 +1161,122 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
 ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                const float* server_scales, float lr, void* hip_stream) {
   return ob_lamb_ratios_apply_lp(ctx, st, packed_all, server_scales, lr, nullptr, OB_F32, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+// The caller's history -> the kernels' (validated; h == NULL: none, write).
+ob_status vf_history(const ob_lamb_vf_history* h, VfHist* out) {
+  static_assert(OB_VF_MAX_OLD == VF_MAX_OLD, "header and kernels disagree");
+  out->n_old = 0;
+  out->write_v = 1;
+  for (int i = 0; i < VF_MAX_OLD; ++i) {
+    out->bits[i] = nullptr;
+    out->scales[i] = nullptr;
+  }
+  if (!h) return OB_OK;
+  if (h->n_old < 0 || h->n_old > OB_VF_MAX_OLD) return OB_ERR_ARG;
+  for (int i = 0; i < h->n_old; ++i) {
+    if (!h->bits[i] || !h->scales[i]) return OB_ERR_NULL;
+    if (misaligned(h->bits[i])) return OB_ERR_ALIGN;
+    out->bits[i] = h->bits[i];
+    out->scales[i] = h->scales[i];
+  }
+  out->n_old = h->n_old;
+  out->write_v = h->write_v ? 1 : 0;
+  return OB_OK;
+}
+
+RatioArgs ratio_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                     const float* server_scales, const PackedMom& pm) {
+  RatioArgs ra;
+  ra.packed = packed_all; ra.sscales = server_scales; ra.m = st->m; ra.pm = pm;
+  ra.v_fresh = st->v_fresh; ra.v_frozen = st->v_frozen;
+  ra.beta1 = ctx->beta1; ra.omb1 = ctx->omb1; ra.beta2 = ctx->beta2; ra.omb2 = ctx->omb2;
+  return ra;
+}
+
+// ratio pass with the variance in deferred form over `tiles` (NULL: all), then the layers' clips
+void launch_ratios_hist(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const RatioArgs& ra,
+                        const VfHist& vh, const int* tiles, int n_launch_tiles,
+                        const unsigned char* done_elsewhere, bool finalize) {
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch1(st->mom_scale != nullptr, [&](auto hk) {
+    OB_LAUNCH(la, KID_RATIOS_PASS_HIST, (k_ratios_pass_hist<decltype(hk)::value>), n_launch_tiles, ra, vh,
+              ctx->d_seg_max, (float*)nullptr, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer, tiles);
+  });
+  if (finalize)
+    OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
+                ctx->d_layer_seg0, st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr,
+                ctx->r_min, ctx->r_max, done_elsewhere);
+}
+}  // namespace
+
+extern "C" {
+
+ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                    const float* server_scales, float lr, const ob_lamb_vf_history* h,
+                                    void* hip_stream) {
+  if (ob_status s = check_ratios_args(ctx, st, packed_all, server_scales)) return s;
+  REQUIRE_PTR(st->x);
+  if (!std::isfinite(lr)) return OB_ERR_ARG;
+  bool packed_m = false;
+  PackedMom pm;
+  if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
+  if (!packed_m || st->m_packed == packed_all) return OB_ERR_ARG;   // the history is one of 1-bit momenta
+  VfHist vh;
+  if (ob_status s = vf_history(h, &vh)) return s;
+  XLp xl;
+  if (ob_status s = x_lp_target(nullptr, OB_F32, &xl)) return s;
+  Launch la(ctx, hip_stream);
+  const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
+  LayerSplit& sp = ctx->sp_apply;
+  if (!sp.on) {
+    launch_ratios_hist(la, ctx, st, ra, vh, nullptr, ctx->n_tiles, nullptr, true);
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
+  const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  // the three stages of ob_lamb_ratios_apply
+  launch_ratios_hist(la, ctx, st, ra, vh, sp.d_rest_tiles, sp.n_rest_tiles, sp.d_has_listed, sp.n_layers < ctx->L);
+  LayerSync ls;
+  ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
+  ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
+  ls.spin_limit = ctx->spin_limit;
+  ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
+  ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
+  dispatch1(st->mom_scale != nullptr, [&](auto k_) {
+    OB_LAUNCH(la, KID_RATIOS_APPLY_HIST, (k_ratios_apply_hist<decltype(k_)::value, false>), sp.n_fused_tiles, ra,
+              vh, aa, ls, lt);
+  });
+  launch_apply(la, ctx, st, packed_all, server_scales, lr, sp.d_rest_tiles, sp.n_rest_tiles, xl);
+  return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                 const float* server_scales, const ob_lamb_vf_history* h, float* v_out,
+                                 void* hip_stream) {
+  if (ob_status s = check_common(ctx, st)) return s;
+  REQUIRE_PTR(packed_all); REQUIRE_PTR(st->v_fresh); REQUIRE_PTR(st->v_frozen); REQUIRE_PTR(v_out);
+  if (!server_scales) return OB_ERR_NULL;
+  bool packed_m = false;
+  PackedMom pm;
+  if (ob_status s = momentum_source(st, &packed_m, &pm)) return s;
+  if (!packed_m || st->m_packed == packed_all) return OB_ERR_ARG;
+  VfHist vh;
+  if (ob_status s = vf_history(h, &vh)) return s;
+  vh.write_v = (v_out == st->v_fresh) ? 1 : 0;   // in place: through the array's own pointer
+  Launch la(ctx, hip_stream);
+  const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
+  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+  dispatch1(st->mom_scale != nullptr, [&](auto hk) {
+    OB_LAUNCH(la, KID_VARIANCE_DENSE, (k_ratios_pass_hist<decltype(hk)::value>), ctx->n_tiles, ra, vh,
+              (float*)nullptr, vh.write_v ? (float*)nullptr : v_out, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0,
+              ctx->d_seg_layer, (const int*)nullptr);
+  });
+  return la.ok ? OB_OK : OB_ERR_HIP;
 }
 
 ob_status ob_lamb_momentum_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, float* m_out, void* hip_stream) {

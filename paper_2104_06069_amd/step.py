@@ -28,7 +28,7 @@ _STATE_KEYS = ("x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_a
 class DeviceStep:
     def __init__(self, layer_offsets, num_workers, server_chunk=0, device="cuda:0", mom_scale=None,
                  packed_momentum=False, fused_apply=False, x_lp_dtype=None, grad_scale=1.0,
-                 status_interval=64, fold_gather=True, deferred_error=False, **hyper):
+                 status_interval=64, fold_gather=True, deferred_error=False, deferred_variance=0, **hyper):
         """hyper: the fields of ob_lamb_config (hyper-parameters, flags, fused_max_tiles, spin_limit).
         status_interval: every that many optimizer steps step()/warmup_step() ask the library whether a
         bounded device-side wait has expired (one stream synchronisation; raises ObLambError with
@@ -41,6 +41,17 @@ class DeviceStep:
         # previous output (packed_local / scales_local, which then must survive between the steps)
         # (and err_server holds zb, with the server's own previous output kept in srv_words / srv_scale)
         self.deferred_error = bool(deferred_error)
+        # deferred_variance = K >= 2: v_fresh is brought up to date only every K-th compression step;
+        # in between, the steps form the up-to-date variance in registers from the array and the sign
+        # words and scales of the momenta since it was written (ob_lamb_ratios_apply_hist), which are
+        # the steps' own packed_all / server_scales buffers: K + 1 of them are kept in a ring
+        self.vf_period = int(deferred_variance)
+        if self.vf_period:
+            assert 2 <= self.vf_period <= ob.OB_VF_MAX_OLD + 1 and packed_momentum and fused_apply and x_lp_dtype is None, \
+                "deferred_variance needs the 1-bit momentum, ob_lamb_ratios_apply and fp32 parameters"
+        self.vf_ages = {}         # steps taken so far by the number of momentum steps each had to apply
+        self._vf_n_old = 0        # momenta older than the previous one since v_fresh was written
+        self._vf_pending = None   # arguments of the last step that left v_fresh behind (for the dense view)
         self.status_interval = int(status_interval)
         self._steps_since_check = 0
         self.device = torch.device(device)
@@ -70,7 +81,7 @@ class DeviceStep:
         # the W recompressed chunks (two pairs when they double as the momentum)
         self.packed_momentum = bool(packed_momentum)
         self.fused_apply = bool(fused_apply)   # layer_ratios + decompress_apply as one call
-        npairs = 2 if self.packed_momentum else 1
+        npairs = (self.vf_period + 1 if self.vf_period else 2) if self.packed_momentum else 1
         self._pa = [torch.zeros(self.n_pad // 32, **i32) for _ in range(npairs)]
         self._ss = [torch.zeros(self.W, **f32) for _ in range(npairs)]
         self._cur = 0
@@ -88,6 +99,11 @@ class DeviceStep:
     @property
     def server_scales(self):
         return self._ss[self._cur]
+
+    @property
+    def _prev(self):
+        """Ring index of the pair that holds the previous momentum."""
+        return (self._cur - 1) % len(self._pa)
 
     def _dev(self, a):
         if isinstance(a, np.ndarray):
@@ -109,7 +125,7 @@ class DeviceStep:
             b["m_packed"], b["m_scales"] = self.packed_all, self.server_scales
         elif self.packed_momentum and self.m_is_packed:
             b["m"] = None
-            b["m_packed"], b["m_scales"] = self._pa[1 - self._cur], self._ss[1 - self._cur]
+            b["m_packed"], b["m_scales"] = self._pa[self._prev], self._ss[self._prev]
         return ob.make_state(**b)
 
     def close(self):
@@ -130,12 +146,42 @@ class DeviceStep:
         for k in _STATE_KEYS:
             if k in st and st[k] is not None:
                 self.t[k].copy_(self._dev(st[k]))
+        if "v_fresh" in st and st["v_fresh"] is not None:
+            self._vf_n_old, self._vf_pending = 0, None    # the array is the variance again
         if "m" in st and st["m"] is not None:
+            self._vf_fold()            # (a dense momentum ends the history of 1-bit momenta)
             self.m_is_packed = False
         if "err_worker" in st and st["err_worker"] is not None:
             self.scales_local.zero_()      # (deferred form: zero scales make err_worker the error itself)
         if "err_server" in st and st["err_server"] is not None:
             self.srv_scale.zero_()
+
+    def _vf_hist(self, n_old, write_v):
+        """ob_lamb_vf_history of the step whose pairs are (_cur, _prev): the n_old pairs before them."""
+        R = len(self._pa)
+        idx = [(self._cur - 2 - i) % R for i in range(n_old)]
+        return ob.make_vf_history([self._pa[i] for i in idx], [self._ss[i] for i in idx], write_v)
+
+    def v_fresh_dense(self):
+        """The fresh variance as a device tensor (materialised if the array was left behind)."""
+        if self._vf_pending is None:
+            return self.t["v_fresh"]
+        cur, n_old = self._vf_pending
+        assert cur == self._cur, "the dense view belongs to the step that was taken last"
+        out = self.t["v_fresh"].clone()     # (the padding of the view is the array's)
+        ob.ob_lamb_variance_dense(self.ctx, self._state("read"), self.packed_all, self.server_scales,
+                                  self._vf_hist(n_old, 0), out, self.stream)
+        return out
+
+    def _vf_fold(self):
+        """Bring the v_fresh array up to date (before anything that uses it as the variance itself)."""
+        if self._vf_pending is None:
+            return
+        cur, n_old = self._vf_pending
+        assert cur == self._cur
+        ob.ob_lamb_variance_dense(self.ctx, self._state("read"), self.packed_all, self.server_scales,
+                                  self._vf_hist(n_old, 1), self.t["v_fresh"], self.stream)
+        self._vf_n_old, self._vf_pending = 0, None
 
     def err_dense(self):
         """The worker error delta as a device tensor (materialised from the deferred form if that is in use)."""
@@ -152,6 +198,8 @@ class DeviceStep:
             out = torch.empty_like(self.t["err_server"])
             ob.ob_lamb_server_error_dense(self.ctx, self._state("read"), out, self.stream)
             return out.cpu().numpy()
+        if k == "v_fresh":
+            return self.v_fresh_dense().cpu().numpy()
         if k == "m" and self.m_is_packed:
             # dense view of the 1-bit momentum (held by the pair of the step that committed it)
             s = ob.make_state(**dict(self.t, m_packed=self.packed_all, m_scales=self.server_scales))
@@ -190,6 +238,7 @@ class DeviceStep:
         self._count_step()
 
     def _warmup_step(self, grad, lr):
+        self._vf_fold()
         if self._is_plain(grad):
             ob.ob_lamb_warmup_step(self.ctx, self._state("read"), grad, lr, self.stream)
         else:
@@ -197,6 +246,7 @@ class DeviceStep:
                                       self.grad_scale, lr, *self._x_lp_args(), self.stream)
 
     def freeze(self):
+        self._vf_fold()
         ob.ob_lamb_freeze(self.ctx, self._state("read"), self.stream)
 
     def momentum_scale(self):
@@ -225,7 +275,7 @@ class DeviceStep:
     def begin_step(self):
         """Select the wire buffers of the coming step: the pair that does not hold the momentum."""
         if self.packed_momentum and self.m_is_packed:
-            self._cur = 1 - self._cur
+            self._cur = (self._cur + 1) % len(self._pa)
 
     def compress_local(self, grad):
         if self._is_plain(grad):
@@ -253,6 +303,7 @@ class DeviceStep:
                                  self.stream)
 
     def layer_ratios(self):
+        self._vf_fold()
         ob.ob_lamb_layer_ratios(self.ctx, self._state("read"), self.packed_all, self.server_scales,
                                 self.stream)
 
@@ -267,7 +318,18 @@ class DeviceStep:
             self.m_is_packed = True
 
     def ratios_apply(self, lr):
-        if self._is_plain():
+        if self.vf_period and self.m_is_packed:
+            # the variance in deferred form: the array is brought up to date every vf_period-th step
+            n_old = self._vf_n_old
+            write_v = (n_old + 1 >= self.vf_period)
+            ob.ob_lamb_ratios_apply_hist(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
+                                         self._vf_hist(n_old, write_v), self.stream)
+            self.vf_ages[n_old + 1] = self.vf_ages.get(n_old + 1, 0) + 1
+            if write_v:
+                self._vf_n_old, self._vf_pending = 0, None
+            else:
+                self._vf_n_old, self._vf_pending = n_old + 1, (self._cur, n_old)
+        elif self._is_plain():
             ob.ob_lamb_ratios_apply(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
                                     self.stream)
         else:

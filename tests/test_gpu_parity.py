@@ -109,7 +109,7 @@ def make_case(name):
 
 
 def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused=False,
-               fused_max_tiles=None, hyper=None, deferred=False):
+               fused_max_tiles=None, hyper=None, deferred=False, deferred_variance=0):
     """Oracle-side and device-side steps with identical, non-trivial state."""
     st = Streams(seed)
     pl = cfg["plist"]
@@ -120,7 +120,7 @@ def start_pair(cfg, seed=0, warm_state=True, two_pass=False, packed=False, fused
     h.update(hyper or {})
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, **h)
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], mom_scale=k, two_pass=two_pass, packed_momentum=packed, fused_apply=fused,
-                     fused_max_tiles=fused_max_tiles, deferred_error=deferred, **h)
+                     fused_max_tiles=fused_max_tiles, deferred_error=deferred, deferred_variance=deferred_variance, **h)
     assert (dev.N, dev.n_pad, dev.n_c) == (ref.N, ref.n_pad, ref.n_c)
     s = init_state(st, cfg)
     if warm_state:  # non-zero momentum and errors so that every term is exercised
@@ -207,7 +207,8 @@ def test_phasewise_single_step(case, two_pass):
 
 
 def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=False, fused=False,
-                   fused_max_tiles=None, hyper=None, c_avg=None, nudge_step=None, deferred=False):
+                   fused_max_tiles=None, hyper=None, c_avg=None, nudge_step=None, deferred=False,
+                   deferred_variance=0, check_every=10):
     """The device feeds itself for `steps` steps; the oracle does the same on the host.
     While every scale has been bit-equal on both sides, everything must be bit-equal.  Once a scale
     has differed in its last bit (the two sides add the same fp64 terms in different groupings; about
@@ -219,7 +220,8 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=
     chunk it does not serve would have left there (scale one ulp up, the chunk's errors moved by that
     ulp), so that the second regime is exercised."""
     st, ref, dev = start_pair(cfg, seed=seed, warm_state=warm_state, two_pass=two_pass, packed=packed,
-                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper, deferred=deferred)
+                              fused=fused, fused_max_tiles=fused_max_tiles, hyper=hyper, deferred=deferred,
+                              deferred_variance=deferred_variance)
     if c_avg is not None:
         ref.t["c_avg"][...] = c_avg
         dev.load_state(ref.t)
@@ -247,7 +249,7 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=
         if stats["scale_ulp_steps"] == 0 and not nudged:
             # a sign may differ only after a scale differed in its last bit at an earlier step
             assert same_words, f"step {t}: sign words differ although all scales were bit-equal"
-            if t % 10 == 0 or t == steps - 1:
+            if t % check_every == 0 or t == steps - 1:
                 for k in ("x", "v_fresh", "err_worker", "r_prev"):
                     assert np.array_equal(dev.get(k), ref.t[k]), (t, k)
         else:
@@ -270,6 +272,29 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=
             nudged = True
     assert dev.m_is_packed == packed
     return ref, dev, stats
+
+
+@pytest.mark.parametrize("case,steps,period,fused_max_tiles", [
+    ("tiny", 12, 4, None), ("tiny", 20, 8, None), ("bert_mini", 30, 4, None), ("bert_mini", 21, 8, None),
+    ("bert_mini", 13, 2, 1), ("odd", 14, 3, None), ("odd", 12, 5, 0), ("w1", 10, 4, None), ("small", 10, 4, None)])
+def test_trajectory_with_the_variance_in_deferred_form(case, steps, period, fused_max_tiles):
+    """ob_lamb_ratios_apply_hist: the v_fresh array is brought up to date only every `period`-th
+    step; in between every step forms the up-to-date variance from the array and the sign words and
+    scales of the momenta since then.  After EVERY step the dense view of the variance
+    (ob_lamb_variance_dense), the parameters, the errors and the ratios equal the oracle's bit for
+    bit, in the kernel with the per-layer barrier and in the plain kernels (tiles at layer
+    boundaries, empty and tiny tensors, momentum scaling on bert_mini)."""
+    _need_gpu()
+    cfg = make_case(case)
+    ref, dev, stats = run_trajectory(cfg, steps, packed=True, fused=True, warm_state=True, deferred=True,
+                                     deferred_variance=period, fused_max_tiles=fused_max_tiles, check_every=1)
+    assert stats["scale_ulp_steps"] == 0, "bit-equality was not tested all the way"
+    ages = dev.vf_ages
+    assert set(ages) == set(range(1, period + 1)), ages     # every history length was exercised
+    # what the array itself holds is the variance of the last step that wrote it
+    for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
+        assert np.array_equal(dev.get(k), ref.t[k]), k
+    finish(dev)
 
 
 def test_trajectory_after_a_last_bit_difference_of_a_scale():
