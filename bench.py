@@ -66,10 +66,20 @@ def fp32_momentum_equivalent_bytes_per_param(W):
     return 16.125 + 0.125 + 8.125 / W + 16.125 + 12.0
 
 
-def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_single_pass):
+def hist_kernel_bytes_per_param(ages, period):
+    """ob_lamb_ratios_apply_hist's kernel with the per-layer barrier, per element, averaged over
+    steps that applied `ages` = {momentum steps applied: count}: R v_fresh as last written, v_frozen,
+    x (12) + the sign words of a + 1 momenta ((a + 1)/8) + W x (4), and W v_fresh (4) on the steps
+    that bring the array up to date (a == period)."""
+    n = sum(ages.values())
+    return sum(c * (16.0 + 0.125 * (a + 1) + (4.0 if a >= period else 0.0)) for a, c in ages.items()) / n
+
+
+def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_single_pass, fused_bytes=None):
     """What the calls as implemented must move (each kernel's inputs once, outputs once).
     fused_frac: share of the parameters whose ratio pass and update run as one kernel
-    (ob_lamb_ratios_apply), reading v_frozen and the sign words once."""
+    (ob_lamb_ratios_apply), reading v_frozen and the sign words once.
+    fused_bytes: that kernel's bytes per element if not KERNEL_BYTES' (hist_kernel_bytes_per_param)."""
     k = KERNEL_BYTES[mode]
     separate = k["ratios_pass"][0] + k["decompress_apply"][0]
     compress = {"deferred": k["compress_deferred"][0], "barrier": k["compress_resident"][0],
@@ -78,7 +88,8 @@ def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_
         server = 0.125 + 8.375 / W     # R W packed chunks, zb, own previous bits; W zb, bits twice
     else:
         server = (0.125 + 8.125 / W) if server_single_pass else (0.125 + 16.125 / W)
-    return (compress + fused_frac * k["ratios_apply_resident"][0] + (1.0 - fused_frac) * separate + server)
+    fb = k["ratios_apply_resident"][0] if fused_bytes is None else fused_bytes
+    return (compress + fused_frac * fb + (1.0 - fused_frac) * separate + server)
 
 
 class Workload:
@@ -101,7 +112,8 @@ class Workload:
         self.ds = DeviceStep(self.pl.offsets, self.W, self.server_chunk, device="cuda:0", mom_scale=None,
                              packed_momentum=(self.mode == "packed"), fused_apply=not args.separate_calls,
                              x_lp_dtype=tdt[args.x_lp], status_interval=0,
-                             deferred_error=not args.barrier_compress, **HYPER)
+                             deferred_error=not args.barrier_compress,
+                             deferred_variance=self.variance_period(args), **HYPER)
         ds = self.ds
         ds.load_state(init_state(st, cfg))
         self.grads = [gradient(st, cfg, t).to(tdt[args.grad_dtype]) for t in range(3)]
@@ -125,6 +137,22 @@ class Workload:
         self.fused_params = ob.ob_lamb_fused_params(ds.ctx) if (ds.fused_apply and self.mode == "packed") else 0
         self.wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
 
+    @staticmethod
+    def variance_period(args):
+        """The fresh variance in deferred form needs the 1-bit momentum, the one-call ratio+update and
+        fp32 parameters; a captured graph cannot carry it (the history's buffers change from step to
+        step with a period of K(K+1) steps)."""
+        k = int(getattr(args, "variance_period", 0))
+        if args.dense_momentum or args.separate_calls or args.x_lp != "none" or getattr(args, "graph", False):
+            return 0
+        return k
+
+    def ages_since(self, before):
+        """{momentum steps applied: steps} of the ratio+update calls since the snapshot `before`."""
+        now = self.ds.vf_ages
+        d = {a: now[a] - before.get(a, 0) for a in now if now[a] - before.get(a, 0) > 0}
+        return d
+
     def one_step(self, t):
         self.ds.begin_step()
         self.ds.step(self.grads[t % len(self.grads)], self.lr)
@@ -141,6 +169,7 @@ class Workload:
             self.one_step(t)
         torch.cuda.synchronize()
         if graph:
+            assert not self.ds.vf_period, "a captured graph cannot carry the variance's history"
             # two steps return the alternating buffer pairs to where they started: one graph, replayed
             assert steps % 2 == 0, "--graph replays pairs of steps"
             side = torch.cuda.Stream()
@@ -162,11 +191,13 @@ class Workload:
             ev[-1].record(); torch.cuda.synchronize()
             per = [ev[i].elapsed_time(ev[i + 1]) / 2 for i in range(steps // 2)]
         else:
+            ages0 = dict(self.ds.vf_ages)
             t0 = time.perf_counter()
             for t in range(steps):
                 self.one_step(t)
             torch.cuda.synchronize()
             mean = 1e3 * (time.perf_counter() - t0) / steps
+            self.ages_timed = self.ages_since(ages0)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
             for t in range(steps):
                 ev[t].record(); self.one_step(t)
@@ -176,10 +207,14 @@ class Workload:
         return mean, per[len(per) // 2]
 
     def step_bytes(self, g_less, x_more):
+        """Algorithmic bytes of one step, averaged over the steps of the last timed() loop."""
         ob, ds = self.ob, self.ds
+        fb = None
+        if ds.vf_period and getattr(self, "ages_timed", None):
+            fb = hist_kernel_bytes_per_param(self.ages_timed, ds.vf_period)
         return (algorithmic_step_bytes_per_param(self.W, self.mode, self.fused_params / float(ds.n_pad),
                                                  self.compress_form(),
-                                                 ob.ob_lamb_server_single_pass(ds.ctx) > 0)
+                                                 ob.ob_lamb_server_single_pass(ds.ctx) > 0, fused_bytes=fb)
                 - g_less + x_more) * ds.n_pad
 
     def compress_form(self):
@@ -243,10 +278,17 @@ def brief(name, args, torch, steps, graph_too=False):
            "fused_share": round(w.fused_params / float(w.ds.n_pad), 4),
            "compress_form": w.compress_form(),
            "server_single_pass": int(w.ob.ob_lamb_server_single_pass(w.ds.ctx))}
+    out["variance_period"] = w.ds.vf_period
     if graph_too:
-        gm, gmed = w.timed(steps + steps % 2, args.warmup, graph=True)
+        import copy
+        ag = copy.copy(args)
+        ag.graph = True     # (the variance array rewritten at every step: see Workload.variance_period)
+        wg = Workload(name, ag, torch)
+        gm, gmed = wg.timed(steps + steps % 2, args.warmup, graph=True)
+        bg = wg.step_bytes(0.0, 0.0)
+        wg.close()
         out["graph_replay_ms_per_step"] = round(gm, 4)
-        out["graph_replay_pct_of_hbm_peak"] = round(100 * b / (gm * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)
+        out["graph_replay_pct_of_hbm_peak"] = round(100 * bg / (gm * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)
     wu = w.warmup_reference()
     out["warmup_step_ms"] = round(wu, 4)
     out["warmup_step_params_per_s"] = round(w.pl.N / (wu * 1e-3), 1)
@@ -261,7 +303,11 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_large")
-    ap.add_argument("--profile-steps", type=int, default=5)
+    ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--variance-period", type=int, default=4,
+                    help="bring the v_fresh array up to date every that many steps and let the steps in between form "
+                         "the variance from it and the momenta's sign words (ob_lamb_ratios_apply_hist); 0: rewrite "
+                         "the array at every step (ob_lamb_ratios_apply)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-workloads", action="store_true",
                     help="skip the brief runs of the other benchmark configurations")
@@ -337,8 +383,10 @@ def main():
     # per-call times (events on the launch stream), both straight after the timed steps so that the
     # device never pauses in between
     ob.ob_lamb_profile_enable(ds.ctx, True)
+    ages0 = dict(ds.vf_ages)
     for t in range(args.profile_steps):
         wl.one_step(t)
+    ages_prof = wl.ages_since(ages0)
     prof = ob.ob_lamb_profile_read(ds.ctx)
     ob.ob_lamb_profile_enable(ds.ctx, False)
     for t in range(5):
@@ -373,12 +421,14 @@ def main():
     KB.update(KERNEL_BYTES[mode])
     KB["server_unpack_avg"] = (W / 8.0 + (8.375 if ds.deferred_error else 8.0), "n_c")
     KB["server_resident"] = (W / 8.0 + 8.125, "n_c")   # R W*bits, err (4) + W err (4), bits (1/8)
+    if ages_prof:   # mean over the profiled launches, which differ in how many momentum steps they applied
+        KB["ratios_apply_hist"] = (hist_kernel_bytes_per_param(ages_prof, ds.vf_period), "fused")
     g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
     for k in ("compress_resident", "compress_deferred", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):
         KB[k] = (KB[k][0] - g_less, KB[k][1])
     for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply", "warmup_resident"):
-        KB[k] = (KB[k][0] + x_more, KB[k][1])
+        KB[k] = (KB[k][0] + x_more, KB[k][1])   # (ratios_apply_hist: fp32 parameters only)
     fused_params, wfused = wl.fused_params, wl.wfused
     units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params, "wfused": wfused}
     if wfused:   # the two-pass warmup kernels then cover only the remaining layers (two launches each)
@@ -432,7 +482,9 @@ def main():
                    "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
                    "fused_params": fused_params,
                    "compress_form": wl.compress_form(),
-                   "server_single_pass": ob.ob_lamb_server_single_pass(ds.ctx)},
+                   "server_single_pass": ob.ob_lamb_server_single_pass(ds.ctx),
+                   "variance_period": ds.vf_period,
+                   "timed_steps_by_momentum_steps_applied": {str(a): c for a, c in sorted(getattr(wl, "ages_timed", {}).items())}},
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_algorithmic_pct_of_hbm_peak": round(100 * algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),

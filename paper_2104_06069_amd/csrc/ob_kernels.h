@@ -1549,14 +1549,50 @@ __device__ __forceinline__ const uint32_t* plane_bits(const RatioArgs& ra, const
   return q == 0 ? ra.packed : (q == 1 ? ra.pm.bits : h.bits[q - 2]);
 }
 
+// The two values of every step are the same for all elements of a (chunk, layer) pair.  A small
+// kernel forms them once per call for every pair and step; the N-sized kernels then fetch two
+// scalars per step instead of each thread redoing four divisions per step.
+// Pairs: the layers that meet chunk c, in layer order, are pairs pair_base[c] .. pair_base[c+1]-1;
+// the pair of (c, l) is pair_base[c] + l - pair_lfirst[c].
+struct VTerms {
+  const float* __restrict__ t;   // [VF_MAX_OLD + 1 steps][n_pairs][2]: t_same, t_diff; step s (1 = newest) at s - 1
+  const int* pair_base;       // [W + 1]
+  const int* pair_lfirst;     // [W]
+  const int* pair_c;          // [n_pairs]
+  const int* pair_l;          // [n_pairs]
+  int n_pairs;
+};
+__device__ __forceinline__ int pair_of(const VTerms& vt, int c, int l) { return vt.pair_base[c] + l - vt.pair_lfirst[c]; }
+
+template <bool HAS_K>
+__global__ __launch_bounds__(BLOCK) void k_variance_terms(RatioArgs ra, VfHist h, VTerms vt,
+                                                          const float* __restrict__ mom_scale,
+                                                          float* __restrict__ out /* = vt.t */) {
+  const int pr = blockIdx.x * BLOCK + threadIdx.x;
+  if (pr >= vt.n_pairs) return;
+  const int c = vt.pair_c[pr], l = vt.pair_l[pr];
+  const float kt = HAS_K ? mom_scale[l] : 1.0f;
+  const int a = h.n_old + 1;
+#pragma unroll
+  for (int s = 1; s <= VF_MAX_OLD + 1; ++s) {
+    if (s <= a) {
+      float t_same, t_diff;
+      variance_terms<HAS_K>(ra, plane_scale(ra, h, s - 1, c), plane_scale(ra, h, s, c), kt, &t_same, &t_diff);
+      float* o = out + ((int64_t)(s - 1) * vt.n_pairs + pr) * 2;
+      o[0] = t_same;
+      o[1] = t_diff;
+    }
+  }
+}
+
 // K5 over plain 1024-element tiles with the variance in deferred form.  seg_max may be NULL (no
 // ratio wanted: the dense view of the variance).  The up-to-date variance goes to the base array
 // itself if h.write_v, else to vf_dense if that is not NULL (a dense view in another array, which
 // leaves the base as it is), else nowhere.
-template <bool HAS_K>
-__global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist h, float* __restrict__ seg_max,
-                                                            float* __restrict__ vf_dense, int64_t n_c, int tpc, LayerTab lt,
-                                                            const int* __restrict__ tile_seg0,
+__global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist h, VTerms vt,
+                                                            float* __restrict__ seg_max,
+                                                            float* __restrict__ vf_dense, int64_t n_c, int tpc,
+                                                            LayerTab lt, const int* __restrict__ tile_seg0,
                                                             const int* __restrict__ seg_layer,
                                                             const int* __restrict__ tile_list) {
   __shared__ float lds[BLOCK / WAVE];
@@ -1564,21 +1600,17 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist
   const int l0 = lt.first_layer[p.t];
   if (l0 >= lt.L) return;  // tile lies in the padding (it has no segment)
   const int a = h.n_old + 1;   // steps to apply
-  const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
   const int64_t l0_end = lt.off[l0 + 1];
   const int s0 = tile_seg0[p.t];
+  const int pbase = vt.pair_base[p.c] - vt.pair_lfirst[p.c];   // pair of (c, l): pbase + l
   const int o = threadIdx.x * 4;
   const bool in = (o < p.len);
   float* vf_out = h.write_v ? ra.v_fresh : vf_dense;   // uniform
   unsigned int NBq[VF_MAX_OLD + 2];   // the lane's nibble of every plane, newest first
-  float SC[VF_MAX_OLD + 2];           // the chunk's scale of every plane
 #pragma unroll
   for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
-    NBq[q] = 0u; SC[q] = 0.0f;
-    if (q <= a) {   // uniform
-      SC[q] = plane_scale(ra, h, q, p.c);
-      if (in) NBq[q] = load_nibble(plane_bits(ra, h, q), p.tile0);
-    }
+    NBq[q] = 0u;
+    if (q <= a && in) NBq[q] = load_nibble(plane_bits(ra, h, q), p.tile0);
   }
   v4f V = 0.0f, VZ = 0.0f;
   if (in) {
@@ -1588,11 +1620,11 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist
   const bool uniform = (p.tile0 + p.len <= l0_end);
   const int64_t N = lt.off[lt.L];
   if (uniform) {
+    const float* tt = vt.t + (int64_t)(pbase + l0) * 2;
 #pragma unroll
     for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
       if (s <= a) {   // uniform: the step from plane s to plane s-1
-        float t_same, t_diff;
-        variance_terms<HAS_K>(ra, SC[s - 1], SC[s], kt, &t_same, &t_diff);
+        const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
         const unsigned int flip = NBq[s] ^ NBq[s - 1];
 #pragma unroll
         for (int k = 0; k < 4; ++k) V[k] = ra.beta2 * V[k] + select_by_bit(flip, k, t_diff, t_same);
@@ -1613,7 +1645,7 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist
     }
   } else {
     // the tile meets a layer boundary or the end of the parameters: element by element, leaving the
-    // padding alone (the operations of RatioTile::element_pass, once per step)
+    // padding alone
     float Q[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (in) {
       int l = l0;
@@ -1622,17 +1654,13 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist
         const int64_t i = p.tile0 + o + k;
         if (i < N) {
           l = walk_layer(l, i, lt.off);
-          const float kk = HAS_K ? lt.mom_scale[l] : 1.0f;
+          const float* tt = vt.t + (int64_t)(pbase + l) * 2;
           float v = V[k];
 #pragma unroll
           for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
             if (s <= a) {
-              const float sp = HAS_K ? SC[s - 1] / kk : SC[s - 1];
-              const float mt = ((NBq[s - 1] >> k) & 1u) ? sp : -sp;
-              const float b = ra.beta1 * (HAS_K ? SC[s] / kk : SC[s]);
-              const float bmk = ((NBq[s] >> k) & 1u) ? b : -b;
-              const float gr = (mt - bmk) / ra.omb1;
-              v = ra.beta2 * v + ra.omb2 * (gr * gr);
+              const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
+              v = ra.beta2 * v + select_by_bit(NBq[s] ^ NBq[s - 1], k, t_diff, t_same);
             }
           }
           if (vf_out) vf_out[i] = v;
@@ -1666,7 +1694,7 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist
 // into one register.
 template <bool HAS_K, bool LPX>
 __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
-    RatioArgs ra, VfHist h, ApplyArgs aa, LayerSync ls, LayerTab lt) {
+    RatioArgs ra, VfHist h, VTerms vt, ApplyArgs aa, LayerSync ls, LayerTab lt) {
   constexpr int U = 8;
   constexpr int TILE = SPAN * U;
   __shared__ float lds[BLOCK / WAVE];
@@ -1676,8 +1704,10 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
   const int sp0 = p.c * ls.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span
   const int l0 = lt.first_layer[sp0];  // the layer the tile lies in (lt.first_layer: of the 1024-element tiling)
   const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
+  const float ss = ra.sscales[p.c];
   const LayerParts lp = layer_parts(ls.lt, l0);
   const float rp = ls.r_prev[l0], ca = ls.c_avg[l0];
+  const float* tt = vt.t + (int64_t)pair_of(vt, p.c, l0) * 2;
   const int a = h.n_old + 1;   // steps to apply
   const int o0 = threadIdx.x * 4;
   const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
@@ -1686,14 +1716,10 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
   const bool have_word = (e0 < p.len);   // len is a multiple of 256: a wavefront's part of a span is all there or all missing
   const int64_t wi = (p.tile0 + e0) >> 5;
   unsigned int Wq[VF_MAX_OLD + 2];
-  float SC[VF_MAX_OLD + 2];
 #pragma unroll
   for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
-    Wq[q] = 0u; SC[q] = 0.0f;
-    if (q <= a) {   // uniform
-      SC[q] = plane_scale(ra, h, q, p.c);
-      if (have_word) Wq[q] = plane_bits(ra, h, q)[wi];
-    }
+    Wq[q] = 0u;
+    if (q <= a && have_word) Wq[q] = plane_bits(ra, h, q)[wi];
   }
   v4f V[U], VZ[U];
 #pragma unroll
@@ -1724,8 +1750,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
 #pragma unroll
   for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
     if (s <= a) {   // uniform: the step from plane s to plane s-1
-      float t_same, t_diff;
-      variance_terms<HAS_K>(ra, SC[s - 1], SC[s], kt, &t_same, &t_diff);
+      const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -1762,7 +1787,6 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
   }
   // m_t/(sqrt(v_frozen)+eta), formed in place of v_frozen while the layer completes (the same
   // operations on the same operands as apply_uniform's)
-  const float ss = SC[0];
   const float sp = HAS_K ? ss / kt : ss;
 #pragma unroll
   for (int u = 0; u < U; ++u) {

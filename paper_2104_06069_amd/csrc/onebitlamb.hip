@@ -95,6 +95,7 @@ enum KernelId {
   KID_RATIOS_PASS_HIST,
   KID_RATIOS_APPLY_HIST,
   KID_VARIANCE_DENSE,
+  KID_VARIANCE_TERMS,
   KID_MOMENTUM_DENSE,
   KID_ERROR_DENSE,
   KID_MOMENTUM_SCALE,
@@ -109,7 +110,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "compress_deferred", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "ratios_apply_resident", "ratios_pass_hist", "ratios_apply_hist", "variance_dense", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "ratios_apply_resident", "ratios_pass_hist", "ratios_apply_hist", "variance_dense", "variance_terms", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
 
 struct ProfRec {
@@ -141,6 +142,8 @@ struct LayerSplit {
   int tile = 0;             // elements per listed tile
   int tpc = 0;              // such tiles per chunk
   int* d_rest_tiles = nullptr;
+  int n_cov_tiles = 0;                     // TILE_MAIN tiles inside the listed tiles
+  int* d_cov_tiles = nullptr;
   unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
   unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] (generation << 32) | arrivals
   unsigned long long* d_flag = nullptr;    // [L] (generation << 32) | payload
@@ -171,6 +174,13 @@ struct ob_lamb_ctx {
   double* d_seg_sums = nullptr;   // [2*n_segs]
   double* d_sigma = nullptr;      // [L] per-layer RMS (momentum-scale generation)
   float* d_seg_max = nullptr;     // [n_segs] per-segment max(v_frozen/v_fresh)
+  // (chunk, layer) pairs and the per-step values of the variance in deferred form (VTerms)
+  int n_pairs = 0;
+  int* d_pair_base = nullptr;     // [W+1]
+  int* d_pair_lfirst = nullptr;   // [W]
+  int* d_pair_c = nullptr;        // [n_pairs]
+  int* d_pair_l = nullptr;        // [n_pairs]
+  float* d_vterms = nullptr;      // [(VF_MAX_OLD+1) * n_pairs * 2]
   // single-pass worker compression (k_compress_resident)
   bool resident = false;          // selected at create when the device can hold 2 chunks of tiles
   int tpc_res = 0, n_tiles_res = 0;
@@ -472,7 +482,11 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, int tile_lb, const Tiling& 
   sp->on = !pl.fused_tiles.empty();
   sp->n_fused_tiles = (int)pl.fused_tiles.size();
   sp->n_rest_tiles = (int)pl.rest_tiles.size();
-  return upload(ctx, &sp->d_fused_tiles, pl.fused_tiles) && upload(ctx, &sp->d_n_listed, pl.n_listed) &&
+  std::vector<int> cov;
+  for (int64_t t = 0; t < tm.n_tiles; ++t)
+    if (pl.covered[(size_t)t]) cov.push_back((int)t);
+  sp->n_cov_tiles = (int)cov.size();
+  return upload(ctx, &sp->d_cov_tiles, cov) && upload(ctx, &sp->d_fused_tiles, pl.fused_tiles) && upload(ctx, &sp->d_n_listed, pl.n_listed) &&
          upload(ctx, &sp->d_list_begin, pl.list_begin) && upload(ctx, &sp->d_seg_first, pl.seg_first) &&
          upload(ctx, &sp->d_seg_end, pl.seg_end) && alloc_zero(ctx, &sp->d_listed_max, pl.fused_tiles.size()) &&
          alloc_zero(ctx, &sp->d_listed_sums, 2 * pl.fused_tiles.size()) &&
@@ -482,7 +496,7 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, int tile_lb, const Tiling& 
 
 void free_split(LayerSplit* sp) {
   void* ptrs[] = {sp->d_fused_tiles, sp->d_n_listed, sp->d_list_begin, sp->d_seg_first, sp->d_seg_end,
-                  sp->d_listed_max,  sp->d_listed_sums, sp->d_rest_tiles,
+                  sp->d_listed_max,  sp->d_listed_sums, sp->d_rest_tiles, sp->d_cov_tiles,
                   sp->d_has_listed,  sp->d_counter,  sp->d_flag};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -820,6 +834,29 @@ static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {
        alloc_zero(ctx, &ctx->d_seg_sums, 2 * (size_t)ctx->n_segs) &&
        alloc_zero(ctx, &ctx->d_sigma, (size_t)L) &&
        alloc_zero(ctx, &ctx->d_seg_max, (size_t)ctx->n_segs);
+  if (ok) {
+    // the layers that meet each chunk (empty layers in between included; a chunk that lies in the
+    // padding has none)
+    std::vector<int> pair_base((size_t)ctx->W + 1, 0), pair_lfirst((size_t)ctx->W, 0), pair_c, pair_l;
+    int64_t l = 0;
+    for (int64_t c = 0; c < ctx->W; ++c) {
+      const int64_t c0 = c * ctx->n_c, c1 = std::min((c + 1) * ctx->n_c, N);
+      pair_base[(size_t)c] = (int)pair_c.size();
+      if (c0 < N) {
+        while (h_off[(size_t)l + 1] <= c0) ++l;      // the layer that holds element c0
+        pair_lfirst[(size_t)c] = (int)l;
+        for (int64_t q = l; q < L && h_off[(size_t)q] < c1; ++q) {
+          pair_c.push_back((int)c);
+          pair_l.push_back((int)q);
+        }
+      }
+    }
+    pair_base[(size_t)ctx->W] = (int)pair_c.size();
+    ctx->n_pairs = (int)pair_c.size();
+    ok = upload(ctx, &ctx->d_pair_base, pair_base) && upload(ctx, &ctx->d_pair_lfirst, pair_lfirst) &&
+         upload(ctx, &ctx->d_pair_c, pair_c) && upload(ctx, &ctx->d_pair_l, pair_l) &&
+         alloc_zero(ctx, &ctx->d_vterms, (size_t)(VF_MAX_OLD + 1) * (size_t)ctx->n_pairs * 2);
+  }
   ok = ok && hip_ok(ctx, hipDeviceSynchronize(), "hipDeviceSynchronize");
   if (!ok) return OB_ERR_HIP;
   guard.c = nullptr;
@@ -836,7 +873,8 @@ void ob_lamb_destroy(ob_lamb_ctx* ctx) {
   void* ptrs[] = {ctx->d_off, ctx->d_first_layer, ctx->d_tile_seg0, ctx->d_seg_layer, ctx->d_layer_seg0,
                   ctx->d_partials, ctx->d_partials_srv, ctx->d_seg_sums, ctx->d_seg_max, ctx->d_sigma,
                   ctx->d_first_layer_res, ctx->d_partials_res, ctx->d_counter, ctx->d_flag, ctx->d_errflag,
-                  ctx->d_partials_srv_res, ctx->d_counter_srv, ctx->d_flag_srv};
+                  ctx->d_partials_srv_res, ctx->d_counter_srv, ctx->d_flag_srv, ctx->d_pair_base,
+                  ctx->d_pair_lfirst, ctx->d_pair_c, ctx->d_pair_l, ctx->d_vterms};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   free_split(&ctx->sp_apply);
@@ -1197,20 +1235,23 @@ RatioArgs ratio_args(const ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint
   return ra;
 }
 
-// ratio pass with the variance in deferred form over `tiles` (NULL: all), then the layers' clips
-void launch_ratios_hist(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const RatioArgs& ra,
-                        const VfHist& vh, const int* tiles, int n_launch_tiles,
-                        const unsigned char* done_elsewhere, bool finalize) {
-  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  dispatch1(st->mom_scale != nullptr, [&](auto hk) {
-    OB_LAUNCH(la, KID_RATIOS_PASS_HIST, (k_ratios_pass_hist<decltype(hk)::value>), n_launch_tiles, ra, vh,
-              ctx->d_seg_max, (float*)nullptr, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer, tiles);
-  });
-  if (finalize)
-    OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
-                ctx->d_layer_seg0, st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr,
-                ctx->r_min, ctx->r_max, done_elsewhere);
+VTerms vterms(const ob_lamb_ctx* ctx) {
+  VTerms vt;
+  vt.t = ctx->d_vterms; vt.pair_base = ctx->d_pair_base; vt.pair_lfirst = ctx->d_pair_lfirst;
+  vt.pair_c = ctx->d_pair_c; vt.pair_l = ctx->d_pair_l; vt.n_pairs = ctx->n_pairs;
+  return vt;
 }
+
+// the two values of every (chunk, layer) pair and step of the history, for the kernels below
+void launch_variance_terms(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st, const RatioArgs& ra,
+                           const VfHist& vh) {
+  const VTerms vt = vterms(ctx);
+  dispatch1(st->mom_scale != nullptr, [&](auto hk) {
+    OB_LAUNCH(la, KID_VARIANCE_TERMS, (k_variance_terms<decltype(hk)::value>), (ctx->n_pairs + BLOCK - 1) / BLOCK,
+              ra, vh, vt, st->mom_scale, ctx->d_vterms);
+  });
+}
+
 }  // namespace
 
 extern "C" {
@@ -1230,17 +1271,22 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   XLp xl;
   if (ob_status s = x_lp_target(nullptr, OB_F32, &xl)) return s;
   Launch la(ctx, hip_stream);
-  const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
   LayerSplit& sp = ctx->sp_apply;
   if (!sp.on) {
-    launch_ratios_hist(la, ctx, st, ra, vh, nullptr, ctx->n_tiles, nullptr, true);
+    // no tile goes through the kernel with the per-layer barrier: the whole array is kept up to date
+    launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, nullptr, ctx->n_tiles, nullptr, true);
     launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
+  const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  // the three stages of ob_lamb_ratios_apply
-  launch_ratios_hist(la, ctx, st, ra, vh, sp.d_rest_tiles, sp.n_rest_tiles, sp.d_has_listed, sp.n_layers < ctx->L);
+  // the three stages of ob_lamb_ratios_apply; only the kernel with the per-layer barrier works from
+  // the history (outside its tiles the plain ratio pass keeps the array up to date at every step:
+  // on 1024-element tiles that pass is bound by its launch shape, not by the bytes it moves)
+  launch_variance_terms(la, ctx, st, ra, vh);
+  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_tiles, sp.n_rest_tiles,
+                sp.d_has_listed, sp.n_layers < ctx->L);
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
   ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
@@ -1249,7 +1295,7 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
   dispatch1(st->mom_scale != nullptr, [&](auto k_) {
     OB_LAUNCH(la, KID_RATIOS_APPLY_HIST, (k_ratios_apply_hist<decltype(k_)::value, false>), sp.n_fused_tiles, ra,
-              vh, aa, ls, lt);
+              vh, vterms(ctx), aa, ls, lt);
   });
   launch_apply(la, ctx, st, packed_all, server_scales, lr, sp.d_rest_tiles, sp.n_rest_tiles, xl);
   return la.ok ? OB_OK : OB_ERR_HIP;
@@ -1269,13 +1315,22 @@ ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
   if (ob_status s = vf_history(h, &vh)) return s;
   vh.write_v = (v_out == st->v_fresh) ? 1 : 0;   // in place: through the array's own pointer
   Launch la(ctx, hip_stream);
-  const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
-  const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  dispatch1(st->mom_scale != nullptr, [&](auto hk) {
-    OB_LAUNCH(la, KID_VARIANCE_DENSE, (k_ratios_pass_hist<decltype(hk)::value>), ctx->n_tiles, ra, vh,
-              (float*)nullptr, vh.write_v ? (float*)nullptr : v_out, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0,
-              ctx->d_seg_layer, (const int*)nullptr);
-  });
+  if (!vh.write_v) {   // everything outside the listed tiles is up to date in the array itself
+    la.begin(KID_COPY, true);
+    if (la.ok)
+      la.ok = hip_ok(ctx, hipMemcpyAsync(v_out, st->v_fresh, (size_t)ctx->n_pad * sizeof(float),
+                                         hipMemcpyDeviceToDevice, la.stream), "hipMemcpyAsync");
+    la.end("copy", true);
+  }
+  LayerSplit& sp = ctx->sp_apply;
+  if (sp.on && sp.n_cov_tiles > 0) {
+    const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
+    const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
+    launch_variance_terms(la, ctx, st, ra, vh);
+    OB_LAUNCH(la, KID_VARIANCE_DENSE, k_ratios_pass_hist, sp.n_cov_tiles, ra, vh, vterms(ctx), (float*)nullptr,
+              vh.write_v ? (float*)nullptr : v_out, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
+              sp.d_cov_tiles);
+  }
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
 

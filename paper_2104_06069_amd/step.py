@@ -162,6 +162,11 @@ class DeviceStep:
         idx = [(self._cur - 2 - i) % R for i in range(n_old)]
         return ob.make_vf_history([self._pa[i] for i in idx], [self._ss[i] for i in idx], write_v)
 
+    def _vf_state(self):
+        """ob_lamb_state of the dense-view calls: the previous momentum in its 1-bit form, whatever
+        form the next step will read it in."""
+        return ob.make_state(**dict(self.t, m=None, m_packed=self._pa[self._prev], m_scales=self._ss[self._prev]))
+
     def v_fresh_dense(self):
         """The fresh variance as a device tensor (materialised if the array was left behind)."""
         if self._vf_pending is None:
@@ -169,7 +174,7 @@ class DeviceStep:
         cur, n_old = self._vf_pending
         assert cur == self._cur, "the dense view belongs to the step that was taken last"
         out = self.t["v_fresh"].clone()     # (the padding of the view is the array's)
-        ob.ob_lamb_variance_dense(self.ctx, self._state("read"), self.packed_all, self.server_scales,
+        ob.ob_lamb_variance_dense(self.ctx, self._vf_state(), self.packed_all, self.server_scales,
                                   self._vf_hist(n_old, 0), out, self.stream)
         return out
 
@@ -179,7 +184,7 @@ class DeviceStep:
             return
         cur, n_old = self._vf_pending
         assert cur == self._cur
-        ob.ob_lamb_variance_dense(self.ctx, self._state("read"), self.packed_all, self.server_scales,
+        ob.ob_lamb_variance_dense(self.ctx, self._vf_state(), self.packed_all, self.server_scales,
                                   self._vf_hist(n_old, 1), self.t["v_fresh"], self.stream)
         self._vf_n_old, self._vf_pending = 0, None
 

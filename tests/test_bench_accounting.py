@@ -43,3 +43,19 @@ def test_step_bytes():
     # the accounting with an fp32 momentum and two update calls that the step is NOT measured against
     assert abs(b.fp32_momentum_equivalent_bytes_per_param(W) - (16.125 + bit + 8.125 / W + 16.125 + 12.0)) < 1e-12
     assert b.HBM_PEAK_GBS == 8000.0
+
+
+def test_bytes_with_the_variance_in_deferred_form():
+    b = _bench()
+    bit = 1.0 / 8
+    # one momentum step applied and the array written: the same accesses as the kernel that rewrites
+    # the array at every step
+    assert b.hist_kernel_bytes_per_param({1: 3}, 1) == b.KERNEL_BYTES["packed"]["ratios_apply_resident"][0]
+    # period 4: three steps that write nothing (2, 3, 4 momenta's sign words) and one that reads 5 and writes
+    per_step = [4 + 4 + 4 + 4 + 2 * bit, 16 + 3 * bit, 16 + 4 * bit, 16 + 5 * bit + 4]
+    assert abs(b.hist_kernel_bytes_per_param({1: 1, 2: 1, 3: 1, 4: 1}, 4) - sum(per_step) / 4) < 1e-12
+    # ... weighted by how often each length occurred
+    assert abs(b.hist_kernel_bytes_per_param({1: 2, 4: 1}, 4) - (2 * per_step[0] + per_step[3]) / 3) < 1e-12
+    W = 64
+    step = b.algorithmic_step_bytes_per_param(W, "packed", 0.9, "deferred", False, fused_bytes=17.0)
+    assert abs(step - (12.375 + 0.9 * 17.0 + 0.1 * (12.25 + 12.125) + bit + 8.375 / W)) < 1e-12

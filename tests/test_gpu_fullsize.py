@@ -31,8 +31,10 @@ def device_setup(cfg, server_chunk, seed=0, two_pass=False, packed=False, fused=
                          fused_apply=fused, x_lp_dtype=x_lp_dtype, deferred_error=deferred, **HYPER)
     else:  # whatever the library selects for this size on this device
         from paper_2104_06069_amd.step import DeviceStep as D
+        # (with the deferred errors also the variance in deferred form: the benchmarked configuration)
         dev = D(pl.offsets, cfg["W"], server_chunk, packed_momentum=packed, fused_apply=fused,
-                x_lp_dtype=x_lp_dtype, deferred_error=deferred, **HYPER)
+                x_lp_dtype=x_lp_dtype, deferred_error=deferred,
+                deferred_variance=(4 if deferred and packed and fused and x_lp_dtype is None else 0), **HYPER)
     print(f"{cfg['name']}: single-pass worker compression = {ob.ob_lamb_uses_single_pass(dev.ctx)}", flush=True)
     s = init_state(st, cfg)
     # non-trivial momentum and errors, as after many steps
@@ -234,7 +236,7 @@ def test_gpt_1p3b_windows():
                             dev.server_scales[c0:c1].cpu().numpy())
         ref.layer_ratios()
         ref.decompress_apply(lr)
-        assert_close(dev.t["v_fresh"][A:B].cpu().numpy(), ref.t["v_fresh"], "v_fresh")
+        assert_close(dev.v_fresh_dense()[A:B].cpu().numpy(), ref.t["v_fresh"], "v_fresh")
         idx = np.nonzero(inside)[0]
         whole += idx.size
         assert_close(dev.get("r_prev")[idx], ref.t["r_prev"][idx], "r")
@@ -344,7 +346,8 @@ def test_bert_large_warmup_step(two_pass_warmup):
 def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmup_steps=0, seed=9,
                           check_every=10):
     """`steps` compression-stage steps at full size in the benchmarked configuration (single-pass
-    compression, 1-bit momentum, ratio pass and update in one call), followed by the oracle on
+    compression, 1-bit momentum, ratio pass and update in one call, errors and fresh variance in
+    deferred form), followed by the oracle on
     windows of whole chunks (tests/refstep.py::WindowRef): the compressor, the error feedback, the
     decompressed momentum and the fresh variance are compared for every element of every window,
     the ratio, the coefficient and the parameters for every layer that lies wholly inside one, and
@@ -363,7 +366,8 @@ def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmu
     MT = default_threads()
     hyper = dict(HYPER, c_min=1e-3) if warmup_steps else dict(HYPER)
     st = Streams(seed, device="cuda:0")
-    dev = D(pl.offsets, W, c_srv, packed_momentum=True, fused_apply=True, deferred_error=True, **hyper)
+    dev = D(pl.offsets, W, c_srv, packed_momentum=True, fused_apply=True, deferred_error=True,
+            deferred_variance=4, **hyper)
     # one array at a time: at the largest sizes two sets of N-sized arrays would not fit beside the
     # gradient and the dense views taken at the end
     for k, a in init_state_items(st, cfg):
@@ -464,13 +468,14 @@ def trajectory_on_windows(capsys, name, c_srv, windows, steps, must_cover, warmu
     torch.cuda.synchronize()
     m_dev = dev.get("m")
     err_dev = dev.err_dense()
+    vf_dev = dev.v_fresh_dense()
     r_dev, c_dev = dev.get("r_prev"), dev.get("coeff_c")
     num = den = 0.0
     n_layers = 0
     for i, w in enumerate(wins):
         close = assert_close if exact else assert_mostly_close
         close(err_dev[w.A:w.B].cpu().numpy(), w.t["err_worker"], "worker error")
-        close(dev.t["v_fresh"][w.A:w.B].cpu().numpy(), w.t["v_fresh"], "v_fresh")
+        close(vf_dev[w.A:w.B].cpu().numpy(), w.t["v_fresh"], "v_fresh")
         if w.served:
             close(dev.get("err_server"), w.t["err_server"], "server error")
         assert_close(r_dev[w.layers], w.t["r_prev"][w.layers], "r")
@@ -599,6 +604,7 @@ def test_bert_large_bitwise_reproducible():
         torch.cuda.synchronize()
         out = {k: dev.t[k].clone() for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c")}
         out["err_dense"] = dev.err_dense().clone()
+        out["v_fresh_dense"] = dev.v_fresh_dense().clone()
         out["packed_local"] = dev.packed_local.clone(); out["packed_all"] = dev.packed_all.clone()
         out["scales_local"] = dev.scales_local.clone(); out["server_scales"] = dev.server_scales.clone()
         outs.append(out)
