@@ -265,19 +265,24 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
  * flipped.  The variance after several steps therefore follows from st->v_fresh as last written and
  * the momenta since then, by the very operations line 16 performs step by step (the results are
  * bit-identical); line 17 needs the up-to-date variance of every element, but the array need not be
- * rewritten at every step.  A call with write_v = 0 reads st->v_fresh and writes nothing to it
- * (4 bytes per parameter less than ob_lamb_ratios_apply, plus one bit per parameter and older
- * momentum read); a call with write_v = 1 brings the array up to date, after which the history
- * starts anew (the next call passes n_old = 0).
+ * rewritten at every step.  This applies to the tiles of the single kernel with the per-layer
+ * barrier (see ob_lamb_ratios_apply; ob_lamb_fused_params of them): with write_v = 0 the call reads
+ * st->v_fresh there and writes nothing to it (4 bytes per parameter less than ob_lamb_ratios_apply,
+ * plus one bit per parameter and older momentum read); with write_v = 1 it brings the array up to
+ * date there, after which the history starts anew (the next call passes n_old = 0).  Everywhere
+ * else -- the plain kernels' elements -- st->v_fresh is rewritten at every call as by
+ * ob_lamb_ratios_apply and the history is not read (on their 1024-element tiles the ratio pass is
+ * bound by its launch shape, not by the bytes it moves).
  *
  * n_old: number of momenta older than the previous one (st->m_packed / st->m_scales) that have been
- * committed since st->v_fresh was last written, 0..OB_VF_MAX_OLD; bits[i] / scales[i], i < n_old:
- * their sign words [N_pad/32] and scales [W], NEWEST FIRST (bits[0] is the momentum before the
- * previous one), device pointers, 16-byte aligned, read only.  st->v_fresh must be the variance as
- * of the momentum bits[n_old-1] (as of the previous momentum if n_old = 0).  h = NULL means
- * n_old = 0, write_v = 1: ob_lamb_ratios_apply itself.
- * Requires the momentum in 1-bit form (st->m == NULL, else OB_ERR_ARG).  Everything else -- layers,
- * barrier, bounded waits, what an expired wait leaves behind -- as for ob_lamb_ratios_apply. */
+ * committed since write_v was last 1 (or since ob_lamb_ratios_apply / the LAMB step last wrote
+ * st->v_fresh), 0..OB_VF_MAX_OLD; bits[i] / scales[i], i < n_old: their sign words [N_pad/32] and
+ * scales [W], NEWEST FIRST (bits[0] is the momentum before the previous one), device pointers,
+ * 16-byte aligned, read only.  h = NULL means n_old = 0, write_v = 1: ob_lamb_ratios_apply itself.
+ * Requires the momentum in 1-bit form (st->m == NULL, else OB_ERR_ARG) and fp32 parameters.
+ * Everything else -- layers, barrier, bounded waits, what an expired wait leaves behind -- as for
+ * ob_lamb_ratios_apply.  A caller's duty: between a call with write_v = 0 and the next one with
+ * write_v = 1, st->v_fresh is NOT the variance; ob_lamb_variance_dense gives it. */
 #define OB_VF_MAX_OLD 7
 typedef struct ob_lamb_vf_history {
   int32_t n_old;
@@ -291,9 +296,9 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
 /* Dense view of a variance held in that form: v_out [N_pad] receives the variance as of the momentum
  * (packed_all, server_scales), given st->v_fresh, st->m_packed / st->m_scales and h exactly as they
  * were passed to the ob_lamb_ratios_apply_hist call that committed that momentum (h->write_v is
- * ignored).  The padding of v_out is left untouched.  v_out may be st->v_fresh itself (the array is
- * then up to date: the next call passes n_old = 0).  For checkpoints, inspection and a return to
- * the LAMB step. */
+ * ignored): a device copy of st->v_fresh, then the elements that lag are brought up to date.
+ * v_out may be st->v_fresh itself (no copy; the array is then up to date and the next call passes
+ * n_old = 0).  For checkpoints, inspection and a return to the LAMB step. */
 ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
                                  const float* server_scales, const ob_lamb_vf_history* h, float* v_out,
                                  void* hip_stream);

@@ -173,7 +173,7 @@ class DeviceStep:
             return self.t["v_fresh"]
         cur, n_old = self._vf_pending
         assert cur == self._cur, "the dense view belongs to the step that was taken last"
-        out = self.t["v_fresh"].clone()     # (the padding of the view is the array's)
+        out = torch.empty_like(self.t["v_fresh"])     # (the call copies the array, then updates what lags)
         ob.ob_lamb_variance_dense(self.ctx, self._vf_state(), self.packed_all, self.server_scales,
                                   self._vf_hist(n_old, 0), out, self.stream)
         return out

@@ -545,6 +545,29 @@ def test_argument_errors():
     with pytest.raises(ob.ObLambError) as e:
         ob.ob_lamb_compress_local(dev.ctx, half, g, dev.packed_local, dev.scales_local)
     assert e.value.status == -1
+    # the variance in deferred form: needs the 1-bit momentum; history within its limit, complete, aligned
+    with pytest.raises(ob.ObLambError) as e:   # dense momentum
+        ob.ob_lamb_ratios_apply_hist(dev.ctx, state, dev.packed_all, dev.server_scales, 1e-3, None)
+    assert e.value.status == -2
+    other = torch.zeros_like(dev.packed_all); other_s = torch.ones_like(dev.server_scales)
+    bits1 = ob.make_state(**dict(dev.t, m=None, m_packed=other, m_scales=other_s))
+    too_long = ob.make_vf_history([], [], False); too_long.n_old = ob.OB_VF_MAX_OLD + 1
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_ratios_apply_hist(dev.ctx, bits1, dev.packed_all, dev.server_scales, 1e-3, too_long)
+    assert e.value.status == -2
+    missing = ob.make_vf_history([other], [other_s], False); missing.scales[0] = None
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_ratios_apply_hist(dev.ctx, bits1, dev.packed_all, dev.server_scales, 1e-3, missing)
+    assert e.value.status == -1
+    odd = ob.make_vf_history([other[1:]], [other_s], False)
+    with pytest.raises(ob.ObLambError) as e:
+        ob.ob_lamb_variance_dense(dev.ctx, bits1, dev.packed_all, dev.server_scales, odd, torch.empty_like(dev.t["x"]))
+    assert e.value.status == -3
+    with pytest.raises(ob.ObLambError) as e:   # the previous momentum aliased with the new one
+        ob.ob_lamb_ratios_apply_hist(dev.ctx, ob.make_state(**dict(dev.t, m=None, m_packed=dev.packed_all,
+                                                                   m_scales=dev.server_scales)),
+                                     dev.packed_all, dev.server_scales, 1e-3, None)
+    assert e.value.status == -2
     torch.cuda.synchronize()
     assert np.array_equal(dev.get("x"), x0)
     finish(dev)
