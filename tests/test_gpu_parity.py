@@ -833,7 +833,7 @@ def test_mixed_precision_argument_errors():
     finish(dev)
 
 
-@pytest.mark.parametrize("which", ["compress", "ratios_apply", "warmup"])
+@pytest.mark.parametrize("which", ["compress", "ratios_apply", "ratios_apply_hist", "warmup"])
 def test_expired_wait_is_reported_and_recovered(which):
     """The in-kernel barriers wait a bounded number of polls.  With the bound forced to 0 from the
     host every waiting workgroup gives up without polling, raises the device flag and runs to
@@ -847,8 +847,10 @@ def test_expired_wait_is_reported_and_recovered(which):
     pl = cfg["plist"]
     ref = RefStep(pl.offsets, cfg["W"], cfg["server_chunk"], **HYPER)
     # "ratios_apply": the worker compression runs as two passes, so only the per-layer barrier trips
-    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], two_pass=(which == "ratios_apply"),
-                     packed_momentum=True, fused_apply=True, spin_limit=0, **HYPER)
+    # "ratios_apply_hist": the same with the variance in deferred form (its own kernel)
+    dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], two_pass=which.startswith("ratios_apply"),
+                     packed_momentum=True, fused_apply=True, spin_limit=0,
+                     deferred_variance=(3 if which == "ratios_apply_hist" else 0), **HYPER)
     assert ob.ob_lamb_fused_layers(dev.ctx) == pl.L
     ref.load_state(init_state(st, cfg))
     dev.load_state(ref.t)
@@ -875,7 +877,7 @@ def test_expired_wait_is_reported_and_recovered(which):
         dev.warmup_step(torch.from_numpy(gradient(st, cfg, 0)).to(dev.device), 1e-3)
     # the first step reads the fp32 momentum (two plain kernels behind ratios_apply), the second one
     # runs the kernel with the per-layer barrier
-    for t in range({"compress": 1, "ratios_apply": 2, "warmup": 0}[which]):
+    for t in range({"compress": 1, "ratios_apply": 2, "ratios_apply_hist": 2, "warmup": 0}[which]):
         one_step(t, check=False)
     with pytest.raises(ob.ObLambError) as e:
         ob.ob_lamb_check_device_status(dev.ctx, dev.stream)
