@@ -75,11 +75,22 @@ def hist_kernel_bytes_per_param(ages, period):
     return sum(c * (16.0 + 0.125 * (a + 1) + (4.0 if a >= period else 0.0)) for a, c in ages.items()) / n
 
 
-def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_single_pass, fused_bytes=None):
+def hist_big_ratio_bytes_per_param(ages, period):
+    """The ratio pass from the history on the 8192-element tiles of the layers that are too large for
+    the kernel with the per-layer barrier: R v_fresh as last written, v_frozen (8) + the sign words of
+    a + 1 momenta, and W v_fresh (4) on the steps that bring the array up to date."""
+    n = sum(ages.values())
+    return sum(c * (8.0 + 0.125 * (a + 1) + (4.0 if a >= period else 0.0)) for a, c in ages.items()) / n
+
+
+def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_single_pass, fused_bytes=None,
+                                     big_frac=0.0, big_ratio_bytes=None):
     """What the calls as implemented must move (each kernel's inputs once, outputs once).
     fused_frac: share of the parameters whose ratio pass and update run as one kernel
     (ob_lamb_ratios_apply), reading v_frozen and the sign words once.
-    fused_bytes: that kernel's bytes per element if not KERNEL_BYTES' (hist_kernel_bytes_per_param)."""
+    fused_bytes: that kernel's bytes per element if not KERNEL_BYTES' (hist_kernel_bytes_per_param).
+    big_frac, big_ratio_bytes: share of the parameters whose ratio pass runs from the history on
+    8192-element tiles (hist_big_ratio_bytes_per_param); their update is the plain kernel's."""
     k = KERNEL_BYTES[mode]
     separate = k["ratios_pass"][0] + k["decompress_apply"][0]
     compress = {"deferred": k["compress_deferred"][0], "barrier": k["compress_resident"][0],
@@ -89,7 +100,8 @@ def algorithmic_step_bytes_per_param(W, mode, fused_frac, compress_form, server_
     else:
         server = (0.125 + 8.125 / W) if server_single_pass else (0.125 + 16.125 / W)
     fb = k["ratios_apply_resident"][0] if fused_bytes is None else fused_bytes
-    return (compress + fused_frac * fb + (1.0 - fused_frac) * separate + server)
+    big = big_frac * ((big_ratio_bytes if big_ratio_bytes is not None else k["ratios_pass"][0]) + k["decompress_apply"][0])
+    return (compress + fused_frac * fb + big + (1.0 - fused_frac - big_frac) * separate + server)
 
 
 class Workload:
@@ -136,6 +148,8 @@ class Workload:
         # (with a dense momentum ob_lamb_ratios_apply runs the two plain kernels for every layer)
         self.fused_params = ob.ob_lamb_fused_params(ds.ctx) if (ds.fused_apply and self.mode == "packed") else 0
         self.wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
+        # (only ob_lamb_ratios_apply_hist treats the large layers' whole tiles differently from the rest)
+        self.big_params = ob.ob_lamb_big_tile_params(ds.ctx) if (ds.vf_period and self.fused_params) else 0
 
     @staticmethod
     def variance_period(args):
@@ -209,12 +223,16 @@ class Workload:
     def step_bytes(self, g_less, x_more):
         """Algorithmic bytes of one step, averaged over the steps of the last timed() loop."""
         ob, ds = self.ob, self.ds
-        fb = None
+        fb = bb = None
+        big = 0.0
         if ds.vf_period and getattr(self, "ages_timed", None):
             fb = hist_kernel_bytes_per_param(self.ages_timed, ds.vf_period)
+            bb = hist_big_ratio_bytes_per_param(self.ages_timed, ds.vf_period)
+            big = self.big_params / float(ds.n_pad)
         return (algorithmic_step_bytes_per_param(self.W, self.mode, self.fused_params / float(ds.n_pad),
                                                  self.compress_form(),
-                                                 ob.ob_lamb_server_single_pass(ds.ctx) > 0, fused_bytes=fb)
+                                                 ob.ob_lamb_server_single_pass(ds.ctx) > 0, fused_bytes=fb,
+                                                 big_frac=big, big_ratio_bytes=bb)
                 - g_less + x_more) * ds.n_pad
 
     def compress_form(self):
@@ -280,6 +298,7 @@ def brief(name, args, torch, steps, graph_too=False):
            "step_algorithmic_bytes": b,
            "step_algorithmic_pct_of_hbm_peak": round(100 * b / (mean * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
            "fused_share": round(w.fused_params / float(w.ds.n_pad), 4),
+           "big_tile_share": round(w.big_params / float(w.ds.n_pad), 4),
            "compress_form": w.compress_form(),
            "server_single_pass": int(w.ob.ob_lamb_server_single_pass(w.ds.ctx))}
     out["variance_period"] = w.ds.vf_period
@@ -427,6 +446,7 @@ def main():
     KB["server_resident"] = (W / 8.0 + 8.125, "n_c")   # R W*bits, err (4) + W err (4), bits (1/8)
     if ages_prof:   # mean over the profiled launches, which differ in how many momentum steps they applied
         KB["ratios_apply_hist"] = (hist_kernel_bytes_per_param(ages_prof, ds.vf_period), "fused")
+        KB["ratios_big_hist"] = (hist_big_ratio_bytes_per_param(ages_prof, ds.vf_period), "big")
     g_less = 2.0 if args.grad_dtype != "f32" else 0.0     # 16-bit gradient read
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
     for k in ("compress_resident", "compress_deferred", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):
@@ -434,20 +454,21 @@ def main():
     for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply", "warmup_resident"):
         KB[k] = (KB[k][0] + x_more, KB[k][1])   # (ratios_apply_hist: fp32 parameters only)
     fused_params, wfused = wl.fused_params, wl.wfused
-    units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params, "wfused": wfused}
+    units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params, "wfused": wfused, "big": wl.big_params}
     if wfused:   # the two-pass warmup kernels then cover only the remaining layers (two launches each)
         for k in ("warmup_moments", "warmup_apply"):
             KB[k] = (KB[k][0], "rest_w")
         units["rest_w"] = ds.n_pad - wfused
     if ds.fused_apply and fused_params:   # the plain ratio/update kernels then cover only the remaining layers
-        for k in ("ratios_pass", "decompress_apply"):
-            KB[k] = (KB[k][0], "rest")
+        KB["ratios_pass"] = (KB["ratios_pass"][0], "rest_ratio")
+        KB["decompress_apply"] = (KB["decompress_apply"][0], "rest")
         units["rest"] = ds.n_pad - fused_params
+        units["rest_ratio"] = ds.n_pad - fused_params - wl.big_params
     for k, v in kern.items():
         if k in KB:
             bpe, unit = KB[k]
             # (should a call cover its elements with several launches of one kernel: per-launch mean)
-            per_call = max(1, round(v["launches"] / args.profile_steps)) if unit in ("rest", "rest_w") else 1
+            per_call = max(1, round(v["launches"] / args.profile_steps)) if unit in ("rest", "rest_w", "rest_ratio") else 1
             v["algo_bytes"] = bpe * units[unit] / per_call
             v["GBps"] = round(v["algo_bytes"] / (v["avg_ms"] * 1e-3) / 1e9, 1)
             v["frac_of_hbm_peak"] = round(v["GBps"] / HBM_PEAK_GBS, 4)
@@ -484,7 +505,7 @@ def main():
                    "mom_scale": bool(args.mom_scale), "momentum": mode,
                    "grad_dtype": args.grad_dtype, "x_lp": args.x_lp, "graph_replay": bool(args.graph),
                    "fused_ratios_apply": ds.fused_apply, "fused_layers": ob.ob_lamb_fused_layers(ds.ctx),
-                   "fused_params": fused_params,
+                   "fused_params": fused_params, "big_tile_params": wl.big_params,
                    "compress_form": wl.compress_form(),
                    "server_single_pass": ob.ob_lamb_server_single_pass(ds.ctx),
                    "variance_period": ds.vf_period,

@@ -266,7 +266,8 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
  * the momenta since then, by the very operations line 16 performs step by step (the results are
  * bit-identical); line 17 needs the up-to-date variance of every element, but the array need not be
  * rewritten at every step.  This applies to the tiles of the single kernel with the per-layer
- * barrier (see ob_lamb_ratios_apply; ob_lamb_fused_params of them): with write_v = 0 the call reads
+ * barrier (see ob_lamb_ratios_apply; ob_lamb_fused_params of them) and to the whole 8192-element
+ * tiles of the layers that are too large for it (ob_lamb_big_tile_params): with write_v = 0 the call reads
  * st->v_fresh there and writes nothing to it (4 bytes per parameter less than ob_lamb_ratios_apply,
  * plus one bit per parameter and older momentum read); with write_v = 1 it brings the array up to
  * date there, after which the history starts anew (the next call passes n_old = 0).  Everywhere
@@ -318,6 +319,9 @@ ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx);
 /* ... and the number of parameters in its tiles. */
 int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx);
+/* Number of parameters in the 8192-element tiles of the layers that are too large for that kernel,
+ * where ob_lamb_ratios_apply_hist also works from the history (ratio pass only). */
+int64_t ob_lamb_big_tile_params(const ob_lamb_ctx* ctx);
 /* The same two counts for ob_lamb_warmup_step, which reads g, m, v and x once (one kernel with a
  * per-layer barrier that keeps eq. (1)'s update direction and x in registers while the layer's
  * norms complete) for every layer whose tiles fit on the device, and takes two passes for the

@@ -89,6 +89,7 @@ def lib():
             "ob_lamb_fused_params": (i64, [vp]),
             "ob_lamb_warmup_fused_layers": (i64, [vp]),
             "ob_lamb_warmup_fused_params": (i64, [vp]),
+            "ob_lamb_big_tile_params": (i64, [vp]),
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_ratios_apply_hist": (C.c_int, [vp, sp, vp, vp, f, C.POINTER(ObLambVfHistory), vp]),
@@ -287,6 +288,10 @@ def ob_lamb_fused_params(ctx):
 
 def ob_lamb_warmup_fused_layers(ctx):
     return int(lib().ob_lamb_warmup_fused_layers(ctx))
+
+
+def ob_lamb_big_tile_params(ctx):
+    return int(lib().ob_lamb_big_tile_params(ctx))
 
 
 def ob_lamb_warmup_fused_params(ctx):

@@ -1688,6 +1688,89 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist
   }
 }
 
+// The ratio pass with the variance in deferred form on 8192-element tiles that lie inside one layer,
+// for the layers that are too large for the kernel with the per-layer barrier (their update still
+// runs as the plain kernel).  On such tiles the pass moves bytes at the streaming rate, so reading
+// the stale array and the momenta's sign words instead of rewriting the array pays; on 1024-element
+// tiles it does not (k_ratios_pass_hist is only used for the dense view).  Same loads, exchange and
+// walk through the steps as k_ratios_apply_hist.  The tile's maximum goes to the segment of its
+// first 1024-element span, 0 to the segments of its other spans (k_ratios_finalize takes the
+// maximum over all of a layer's segments).
+__global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_big_hist(RatioArgs ra, VfHist h, VTerms vt, float* __restrict__ seg_max,
+                                                           const int* __restrict__ big_tiles, int64_t n_c,
+                                                           int tpc_big, int tpc_span, LayerTab lt,
+                                                           const int* __restrict__ tile_seg0) {
+  constexpr int U = 8;
+  constexpr int TILE = SPAN * U;
+  __shared__ float lds[BLOCK / WAVE];
+  const TilePos p = tile_pos<TILE>(n_c, tpc_big, big_tiles[blockIdx.x]);
+  const int sp0 = p.c * tpc_span + (p.t - p.c * tpc_big) * U;  // the tile's first span
+  const int l0 = lt.first_layer[sp0];  // the layer the tile lies in (lt.first_layer: of the 1024-element tiling)
+  const float* tt = vt.t + (int64_t)pair_of(vt, p.c, l0) * 2;
+  const int a = h.n_old + 1;   // steps to apply
+  const int o0 = threadIdx.x * 4;
+  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+  const int e0 = (lane >> 3) * SPAN + wv * (WAVE * 4) + (lane & 7) * 32;
+  const bool have_word = (e0 < p.len);
+  const int64_t wi = (p.tile0 + e0) >> 5;
+  unsigned int Wq[VF_MAX_OLD + 2];
+#pragma unroll
+  for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
+    Wq[q] = 0u;
+    if (q <= a && have_word) Wq[q] = plane_bits(ra, h, q)[wi];
+  }
+  v4f V[U], VZ[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    V[u] = 0.0f; VZ[u] = 0.0f;
+    if (o < p.len) {
+      V[u] = ld4(ra.v_fresh + p.tile0 + o);
+      VZ[u] = ld4(ra.v_frozen + p.tile0 + o);
+    }
+  }
+#pragma unroll
+  for (int s = VF_MAX_OLD + 1; s >= 1; --s)
+    if (s <= a) Wq[s] ^= Wq[s - 1];
+  const int src = lane >> 3;
+  const unsigned int sh = 4u * (lane & 7);
+#pragma unroll
+  for (int q = 1; q < VF_MAX_OLD + 2; ++q) {   // (plane 0 itself is not needed here: only the flips)
+    if (q <= a) {   // uniform
+      unsigned int packed = 0u;
+#pragma unroll
+      for (int u = 0; u < U; ++u) packed |= ((__shfl(Wq[q], 8 * u + src, WAVE) >> sh) & 15u) << (4 * u);
+      Wq[q] = packed;
+    }
+  }
+#pragma unroll
+  for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
+    if (s <= a) {   // uniform: the step from plane s to plane s-1
+      const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) V[u][k] = ra.beta2 * V[u][k] + select_by_bit(Wq[s], 4 * u + k, t_diff, t_same);
+    }
+  }
+  float r = 0.0f;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int o = u * SPAN + o0;
+    if (o < p.len) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float q = VZ[u][k] / V[u][k];
+        if (q > r) r = q;
+      }
+      if (h.write_v) st4(ra.v_fresh + p.tile0 + o, V[u]);
+    }
+  }
+  r = block_max(r, lds);
+  const int nspan = (p.len + SPAN - 1) / SPAN;
+  if (threadIdx.x < nspan) seg_max[tile_seg0[sp0 + threadIdx.x]] = (threadIdx.x == 0) ? r : 0.0f;
+}
+
 // k_ratios_apply_resident with the variance in deferred form.  A wavefront's part of a tile is 64
 // words of every plane (8 spans x 8 words): each lane fetches ONE word of each plane and the lanes
 // then pass each other the words they need; what a lane keeps of a plane is its 8 nibbles packed

@@ -73,6 +73,9 @@ constexpr int TILE_LB = SPAN * U_LB;
 #endif
 constexpr int U_WU = OB_U_WU;  // ... in the single-pass warmup kernel (u and x stay in registers)
 constexpr int TILE_WU = SPAN * U_WU;
+#ifndef OB_BIG_MIN_TILES
+#define OB_BIG_MIN_TILES 64   // a layer outside the barrier kernel with at least that many whole 8192-element tiles
+#endif
 #ifndef OB_G_WU
 #define OB_G_WU 2
 #endif
@@ -96,6 +99,7 @@ enum KernelId {
   KID_RATIOS_APPLY_HIST,
   KID_VARIANCE_DENSE,
   KID_VARIANCE_TERMS,
+  KID_RATIOS_BIG_HIST,
   KID_MOMENTUM_DENSE,
   KID_ERROR_DENSE,
   KID_MOMENTUM_SCALE,
@@ -110,7 +114,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "compress_deferred", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "ratios_apply_resident", "ratios_pass_hist", "ratios_apply_hist", "variance_dense", "variance_terms", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "ratios_apply_resident", "ratios_pass_hist", "ratios_apply_hist", "variance_dense", "variance_terms", "ratios_big_hist", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
 
 struct ProfRec {
@@ -142,7 +146,14 @@ struct LayerSplit {
   int tile = 0;             // elements per listed tile
   int tpc = 0;              // such tiles per chunk
   int* d_rest_tiles = nullptr;
-  int n_cov_tiles = 0;                     // TILE_MAIN tiles inside the listed tiles
+  // The layers that are too large for the barrier kernel: their TILE_LB tiles ("big" tiles) take the
+  // ratio pass with the variance in deferred form (ob_lamb_ratios_apply_hist only)
+  int n_big_tiles = 0;
+  int64_t n_big_params = 0;
+  int* d_big_tiles = nullptr;
+  int n_rest_ratio_tiles = 0;              // TILE_MAIN tiles outside the listed and the big tiles
+  int* d_rest_ratio_tiles = nullptr;
+  int n_cov_tiles = 0;                     // TILE_MAIN tiles inside the listed or the big tiles
   int* d_cov_tiles = nullptr;
   unsigned char* d_has_listed = nullptr;   // [L] 1 for layers that the barrier kernel finishes
   unsigned long long* d_counter = nullptr; // [L * CTR_STRIDE] (generation << 32) | arrivals
@@ -414,7 +425,9 @@ struct SplitPlan {
   std::vector<unsigned char> has_listed;   // [L] 1 for layers that the barrier kernel finishes
   std::vector<int> fused_tiles, rest_tiles, n_listed, list_begin, seg_first, seg_end;
   std::vector<unsigned char> covered;      // [TILE_MAIN tiles] 1 inside a listed tile
-  int64_t n_layers = 0, n_params = 0;
+  std::vector<int> big_tiles, rest_ratio_tiles;
+  std::vector<unsigned char> covered_big;  // [TILE_MAIN tiles] 1 inside a big tile
+  int64_t n_layers = 0, n_params = 0, n_big_params = 0;
 };
 
 // tl / tm: the barrier kernel's tiling (tiles of tile_lb elements) and the TILE_MAIN tiling;
@@ -464,9 +477,27 @@ void plan_split(const Tiling& tl, int64_t tile_lb, const Tiling& tm, const std::
       pl->seg_end[(size_t)l] = tm.tile_seg0[(size_t)(span0 + nspan)];
     }
   }
+  // big tiles: the whole tiles of the layers that hold many of them but are not listed
+  pl->covered_big.assign((size_t)tm.n_tiles, 0);
+  for (int64_t l = 0; l < L && max_tiles > 0; ++l) {
+    const std::vector<int>& in = inside[(size_t)l];
+    if (pl->has_listed[(size_t)l] || in.size() < (size_t)OB_BIG_MIN_TILES) continue;
+    for (int t : in) {
+      int64_t tile0, tile1;
+      tile_range(t, &tile0, &tile1);
+      pl->big_tiles.push_back(t);
+      pl->n_big_params += tile1 - tile0;
+      const int64_t c = t / tl.tpc, b = t % tl.tpc;
+      const int64_t span0 = c * tm.tpc + b * (tile_lb / TILE_MAIN);
+      const int64_t nspan = (tile1 - tile0 + TILE_MAIN - 1) / TILE_MAIN;
+      for (int64_t j2 = 0; j2 < nspan; ++j2) pl->covered_big[(size_t)(span0 + j2)] = 1;
+    }
+  }
   for (int64_t t = 0; t < tm.n_tiles; ++t)
-    if (!pl->covered[(size_t)t] && tm.tile_seg0[(size_t)t + 1] > tm.tile_seg0[(size_t)t])
+    if (!pl->covered[(size_t)t] && tm.tile_seg0[(size_t)t + 1] > tm.tile_seg0[(size_t)t]) {
       pl->rest_tiles.push_back((int)t);
+      if (!pl->covered_big[(size_t)t]) pl->rest_ratio_tiles.push_back((int)t);
+    }
 }
 
 // Plans and uploads one LayerSplit.
@@ -484,9 +515,13 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, int tile_lb, const Tiling& 
   sp->n_rest_tiles = (int)pl.rest_tiles.size();
   std::vector<int> cov;
   for (int64_t t = 0; t < tm.n_tiles; ++t)
-    if (pl.covered[(size_t)t]) cov.push_back((int)t);
+    if (pl.covered[(size_t)t] || pl.covered_big[(size_t)t]) cov.push_back((int)t);
   sp->n_cov_tiles = (int)cov.size();
-  return upload(ctx, &sp->d_cov_tiles, cov) && upload(ctx, &sp->d_fused_tiles, pl.fused_tiles) && upload(ctx, &sp->d_n_listed, pl.n_listed) &&
+  sp->n_big_tiles = (int)pl.big_tiles.size();
+  sp->n_big_params = pl.n_big_params;
+  sp->n_rest_ratio_tiles = (int)pl.rest_ratio_tiles.size();
+  return upload(ctx, &sp->d_cov_tiles, cov) && upload(ctx, &sp->d_big_tiles, pl.big_tiles) &&
+         upload(ctx, &sp->d_rest_ratio_tiles, pl.rest_ratio_tiles) && upload(ctx, &sp->d_fused_tiles, pl.fused_tiles) && upload(ctx, &sp->d_n_listed, pl.n_listed) &&
          upload(ctx, &sp->d_list_begin, pl.list_begin) && upload(ctx, &sp->d_seg_first, pl.seg_first) &&
          upload(ctx, &sp->d_seg_end, pl.seg_end) && alloc_zero(ctx, &sp->d_listed_max, pl.fused_tiles.size()) &&
          alloc_zero(ctx, &sp->d_listed_sums, 2 * pl.fused_tiles.size()) &&
@@ -496,7 +531,8 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, int tile_lb, const Tiling& 
 
 void free_split(LayerSplit* sp) {
   void* ptrs[] = {sp->d_fused_tiles, sp->d_n_listed, sp->d_list_begin, sp->d_seg_first, sp->d_seg_end,
-                  sp->d_listed_max,  sp->d_listed_sums, sp->d_rest_tiles, sp->d_cov_tiles,
+                  sp->d_listed_max,  sp->d_listed_sums, sp->d_rest_tiles, sp->d_cov_tiles, sp->d_big_tiles,
+                  sp->d_rest_ratio_tiles,
                   sp->d_has_listed,  sp->d_counter,  sp->d_flag};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -1285,7 +1321,10 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   // the history (outside its tiles the plain ratio pass keeps the array up to date at every step:
   // on 1024-element tiles that pass is bound by its launch shape, not by the bytes it moves)
   launch_variance_terms(la, ctx, st, ra, vh);
-  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_tiles, sp.n_rest_tiles,
+  if (sp.n_big_tiles > 0)   // the layers too large for the barrier kernel: ratio pass from the history on 8192-element tiles
+    OB_LAUNCH(la, KID_RATIOS_BIG_HIST, k_ratios_big_hist, sp.n_big_tiles, ra, vh, vterms(ctx), ctx->d_seg_max,
+              sp.d_big_tiles, ctx->n_c, sp.tpc, ctx->tpc, lt, ctx->d_tile_seg0);
+  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_ratio_tiles, sp.n_rest_ratio_tiles,
                 sp.d_has_listed, sp.n_layers < ctx->L);
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
@@ -1422,6 +1461,7 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
 
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_layers : 0; }
 int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_params : 0; }
+int64_t ob_lamb_big_tile_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_big_params : 0; }
 int64_t ob_lamb_warmup_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_layers : 0; }
 int64_t ob_lamb_warmup_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_params : 0; }
 

@@ -59,3 +59,8 @@ def test_bytes_with_the_variance_in_deferred_form():
     W = 64
     step = b.algorithmic_step_bytes_per_param(W, "packed", 0.9, "deferred", False, fused_bytes=17.0)
     assert abs(step - (12.375 + 0.9 * 17.0 + 0.1 * (12.25 + 12.125) + bit + 8.375 / W)) < 1e-12
+    # part of the parameters in layers too large for that kernel: ratio pass from the history on big tiles
+    assert b.hist_big_ratio_bytes_per_param({1: 1, 2: 1, 3: 1, 4: 1}, 4) == (8 + 2 * bit + 8 + 3 * bit + 8 + 4 * bit + 8 + 5 * bit + 4) / 4
+    step = b.algorithmic_step_bytes_per_param(W, "packed", 0.5, "deferred", False, fused_bytes=17.0, big_frac=0.3,
+                                              big_ratio_bytes=9.5)
+    assert abs(step - (12.375 + 0.5 * 17.0 + 0.3 * (9.5 + 12.125) + 0.2 * (12.25 + 12.125) + bit + 8.375 / W)) < 1e-12

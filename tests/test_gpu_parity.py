@@ -99,9 +99,14 @@ def make_case(name):
         sizes = [7, 90, 3]
     elif name == "one_layer":  # the whole model as one tensor (1-bit Adam's view of it)
         sizes = [50000]
+    elif name == "big_and_small":
+        # one tensor of 70+ tiles of 8192 elements, unaligned at both ends, between tensors of a few
+        # tiles: with a low limit on the tiles per layer the large one is "too large" for the kernel
+        # with the per-layer barrier while the others are not
+        sizes = [3 * 8192 + 5, 75 * 8192 + 1234, 100, 4 * 8192, 2 * 8192 + 77]
     else:
         raise KeyError(name)
-    W = {"odd": 3, "w1": 1, "small": 2, "one_layer": 4}[name]
+    W = {"odd": 3, "w1": 1, "small": 2, "one_layer": 4, "big_and_small": 2}[name]
     pl = ParamList(name, [(f"t{i}", s) for i, s in enumerate(sizes)])
     n_pad = padded_len(pl.N, W)
     return dict(name=name, plist=pl, W=W, n_pad=n_pad, n_c=n_pad // W, grad="student_t3",
@@ -276,7 +281,8 @@ def run_trajectory(cfg, steps, seed=0, two_pass=False, packed=False, warm_state=
 
 @pytest.mark.parametrize("case,steps,period,fused_max_tiles", [
     ("tiny", 12, 4, None), ("tiny", 20, 8, None), ("bert_mini", 30, 4, None), ("bert_mini", 21, 8, None),
-    ("bert_mini", 13, 2, 1), ("odd", 14, 3, None), ("odd", 12, 5, 0), ("w1", 10, 4, None), ("small", 10, 4, None)])
+    ("bert_mini", 13, 2, 1), ("odd", 14, 3, None), ("odd", 12, 5, 0), ("w1", 10, 4, None), ("small", 10, 4, None),
+    ("big_and_small", 11, 4, 8), ("big_and_small", 7, 3, 5)])
 def test_trajectory_with_the_variance_in_deferred_form(case, steps, period, fused_max_tiles):
     """ob_lamb_ratios_apply_hist: the v_fresh array is brought up to date only every `period`-th
     step; in between every step forms the up-to-date variance from the array and the sign words and
@@ -291,6 +297,9 @@ def test_trajectory_with_the_variance_in_deferred_form(case, steps, period, fuse
     assert stats["scale_ulp_steps"] == 0, "bit-equality was not tested all the way"
     ages = dev.vf_ages
     assert set(ages) == set(range(1, period + 1)), ages     # every history length was exercised
+    if case == "big_and_small":   # the large tensor's whole tiles take the ratio pass from the history too
+        import paper_2104_06069_amd as ob
+        assert ob.ob_lamb_big_tile_params(dev.ctx) >= 70 * 8192 and ob.ob_lamb_fused_layers(dev.ctx) >= 2
     # what the array itself holds is the variance of the last step that wrote it
     for k in ("x", "m", "v_fresh", "err_worker", "err_server", "r_prev", "coeff_c"):
         assert np.array_equal(dev.get(k), ref.t[k]), k
