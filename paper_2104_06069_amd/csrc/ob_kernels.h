@@ -1585,114 +1585,44 @@ __global__ __launch_bounds__(BLOCK) void k_variance_terms(RatioArgs ra, VfHist h
   }
 }
 
-// K5 over plain 1024-element tiles with the variance in deferred form.  seg_max may be NULL (no
-// ratio wanted: the dense view of the variance).  The up-to-date variance goes to the base array
-// itself if h.write_v, else to vf_dense if that is not NULL (a dense view in another array, which
-// leaves the base as it is), else nowhere.
-__global__ __launch_bounds__(BLOCK) void k_ratios_pass_hist(RatioArgs ra, VfHist h, VTerms vt,
-                                                            float* __restrict__ seg_max,
-                                                            float* __restrict__ vf_dense, int64_t n_c, int tpc,
-                                                            LayerTab lt, const int* __restrict__ tile_seg0,
-                                                            const int* __restrict__ seg_layer,
-                                                            const int* __restrict__ tile_list) {
-  __shared__ float lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<SPAN>(n_c, tpc, listed_tile(tile_list));
+// Dense view of a variance held in deferred form, over the 1024-element tiles inside the tiles of
+// the two kernels below (each lies inside one layer): the up-to-date variance goes to the base
+// array itself if h.write_v, else to vf_dense (another array, which leaves the base as it is).
+__global__ __launch_bounds__(BLOCK) void k_variance_dense(RatioArgs ra, VfHist h, VTerms vt,
+                                                          float* __restrict__ vf_dense, int64_t n_c, int tpc,
+                                                          LayerTab lt, const int* __restrict__ tile_list) {
+  const TilePos p = tile_pos<SPAN>(n_c, tpc, tile_list[blockIdx.x]);
   const int l0 = lt.first_layer[p.t];
-  if (l0 >= lt.L) return;  // tile lies in the padding (it has no segment)
+  if (l0 >= lt.L || p.tile0 + p.len > lt.off[l0 + 1]) return;   // (not a tile of those kernels: nothing lags there)
   const int a = h.n_old + 1;   // steps to apply
-  const int64_t l0_end = lt.off[l0 + 1];
-  const int s0 = tile_seg0[p.t];
-  const int pbase = vt.pair_base[p.c] - vt.pair_lfirst[p.c];   // pair of (c, l): pbase + l
+  const float* tt = vt.t + (int64_t)pair_of(vt, p.c, l0) * 2;
   const int o = threadIdx.x * 4;
-  const bool in = (o < p.len);
+  if (o >= p.len) return;
   float* vf_out = h.write_v ? ra.v_fresh : vf_dense;   // uniform
   unsigned int NBq[VF_MAX_OLD + 2];   // the lane's nibble of every plane, newest first
 #pragma unroll
   for (int q = 0; q < VF_MAX_OLD + 2; ++q) {
     NBq[q] = 0u;
-    if (q <= a && in) NBq[q] = load_nibble(plane_bits(ra, h, q), p.tile0);
+    if (q <= a) NBq[q] = load_nibble(plane_bits(ra, h, q), p.tile0);
   }
-  v4f V = 0.0f, VZ = 0.0f;
-  if (in) {
-    V = ld4(ra.v_fresh + p.tile0 + o);
-    VZ = ld4(ra.v_frozen + p.tile0 + o);
-  }
-  const bool uniform = (p.tile0 + p.len <= l0_end);
-  const int64_t N = lt.off[lt.L];
-  if (uniform) {
-    const float* tt = vt.t + (int64_t)(pbase + l0) * 2;
+  v4f V = ld4(ra.v_fresh + p.tile0 + o);
 #pragma unroll
-    for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
-      if (s <= a) {   // uniform: the step from plane s to plane s-1
-        const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
-        const unsigned int flip = NBq[s] ^ NBq[s - 1];
+  for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
+    if (s <= a) {   // uniform: the step from plane s to plane s-1
+      const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
+      const unsigned int flip = NBq[s] ^ NBq[s - 1];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) V[k] = ra.beta2 * V[k] + select_by_bit(flip, k, t_diff, t_same);
-      }
-    }
-    float r = 0.0f;
-    if (in) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float q = VZ[k] / V[k];
-        if (q > r) r = q;
-      }
-      if (vf_out) st4(vf_out + p.tile0 + o, V);
-    }
-    if (seg_max) {
-      r = block_max(r, lds);
-      if (threadIdx.x == 0) seg_max[s0] = r;
-    }
-  } else {
-    // the tile meets a layer boundary or the end of the parameters: element by element, leaving the
-    // padding alone
-    float Q[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (in) {
-      int l = l0;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int64_t i = p.tile0 + o + k;
-        if (i < N) {
-          l = walk_layer(l, i, lt.off);
-          const float* tt = vt.t + (int64_t)(pbase + l) * 2;
-          float v = V[k];
-#pragma unroll
-          for (int s = VF_MAX_OLD + 1; s >= 1; --s) {
-            if (s <= a) {
-              const float t_same = tt[(int64_t)(s - 1) * vt.n_pairs * 2], t_diff = tt[(int64_t)(s - 1) * vt.n_pairs * 2 + 1];
-              v = ra.beta2 * v + select_by_bit(NBq[s] ^ NBq[s - 1], k, t_diff, t_same);
-            }
-          }
-          if (vf_out) vf_out[i] = v;
-          Q[k] = VZ[k] / v;
-        }
-      }
-    }
-    if (seg_max) {
-      const int s1 = tile_seg0[p.t + 1];
-      for (int sg = s0; sg < s1; ++sg) {
-        const int l = seg_layer[sg];
-        const int64_t lo = lt.off[l], hi = lt.off[l + 1];
-        float r = 0.0f;
-        if (in) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int64_t i = p.tile0 + o + k;
-            if (i >= lo && i < hi && Q[k] > r) r = Q[k];
-          }
-        }
-        r = block_max(r, lds);
-        if (threadIdx.x == 0) seg_max[sg] = r;
-      }
+      for (int k = 0; k < 4; ++k) V[k] = ra.beta2 * V[k] + select_by_bit(flip, k, t_diff, t_same);
     }
   }
+  st4(vf_out + p.tile0 + o, V);
 }
 
 // The ratio pass with the variance in deferred form on 8192-element tiles that lie inside one layer,
 // for the layers that are too large for the kernel with the per-layer barrier (their update still
 // runs as the plain kernel).  On such tiles the pass moves bytes at the streaming rate, so reading
 // the stale array and the momenta's sign words instead of rewriting the array pays; on 1024-element
-// tiles it does not (k_ratios_pass_hist is only used for the dense view).  Same loads, exchange and
+// tiles it does not.  Same loads, exchange and
 // walk through the steps as k_ratios_apply_hist.  The tile's maximum goes to the segment of its
 // first 1024-element span, 0 to the segments of its other spans (k_ratios_finalize takes the
 // maximum over all of a layer's segments).

@@ -95,7 +95,6 @@ enum KernelId {
   KID_RATIOS_FINALIZE,
   KID_APPLY,
   KID_RATIOS_APPLY_RESIDENT,
-  KID_RATIOS_PASS_HIST,
   KID_RATIOS_APPLY_HIST,
   KID_VARIANCE_DENSE,
   KID_VARIANCE_TERMS,
@@ -114,7 +113,7 @@ enum KernelId {
 const char* const kKernelNames[KID_COUNT] = {
     "momentum_z_sumsq", "compress_resident", "chunk_scale",     "sign_pack_error", "compress_deferred", "server_unpack_avg",
     "server_scale",     "server_sign_pack", "server_resident", "ratios_pass",     "ratios_finalize",
-    "decompress_apply", "ratios_apply_resident", "ratios_pass_hist", "ratios_apply_hist", "variance_dense", "variance_terms", "ratios_big_hist", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
+    "decompress_apply", "ratios_apply_resident", "ratios_apply_hist", "variance_dense", "variance_terms", "ratios_big_hist", "momentum_dense", "error_dense", "momentum_scale", "warmup_moments",   "warmup_coeff",    "warmup_apply",
     "warmup_resident",  "fill",            "copy"};
 
 struct ProfRec {
@@ -1366,9 +1365,8 @@ ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
     const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
     const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
     launch_variance_terms(la, ctx, st, ra, vh);
-    OB_LAUNCH(la, KID_VARIANCE_DENSE, k_ratios_pass_hist, sp.n_cov_tiles, ra, vh, vterms(ctx), (float*)nullptr,
-              vh.write_v ? (float*)nullptr : v_out, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0, ctx->d_seg_layer,
-              sp.d_cov_tiles);
+    OB_LAUNCH(la, KID_VARIANCE_DENSE, k_variance_dense, sp.n_cov_tiles, ra, vh, vterms(ctx),
+              vh.write_v ? (float*)nullptr : v_out, ctx->n_c, ctx->tpc, lt, sp.d_cov_tiles);
   }
   return la.ok ? OB_OK : OB_ERR_HIP;
 }
