@@ -125,7 +125,8 @@ class Workload:
                              packed_momentum=(self.mode == "packed"), fused_apply=not args.separate_calls,
                              x_lp_dtype=tdt[args.x_lp], status_interval=0,
                              deferred_error=not args.barrier_compress,
-                             deferred_variance=self.variance_period(args), **HYPER)
+                             deferred_variance=self.variance_period(args),
+                             flags=(ob.OB_CFG_NO_BARRIERS if getattr(args, "no_barriers", False) else 0), **HYPER)
         ds = self.ds
         ds.load_state(init_state(st, cfg))
         self.grads = [gradient(st, cfg, t).to(tdt[args.grad_dtype]) for t in range(3)]
@@ -149,7 +150,7 @@ class Workload:
         self.fused_params = ob.ob_lamb_fused_params(ds.ctx) if (ds.fused_apply and self.mode == "packed") else 0
         self.wfused = ob.ob_lamb_warmup_fused_params(ds.ctx)
         # (only ob_lamb_ratios_apply_hist treats the large layers' whole tiles differently from the rest)
-        self.big_params = ob.ob_lamb_big_tile_params(ds.ctx) if (ds.vf_period and self.fused_params) else 0
+        self.big_params = ob.ob_lamb_big_tile_params(ds.ctx) if ds.vf_period else 0
 
     @staticmethod
     def variance_period(args):
@@ -351,6 +352,8 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds two consecutive steps (for launch-bound "
                          "sizes; --steps must be even)")
+    ap.add_argument("--no-barriers", action="store_true",
+                    help="OB_CFG_NO_BARRIERS: none of the kernels with an in-kernel barrier")
     ap.add_argument("--barrier-compress", action="store_true",
                     help="ob_lamb_compress_local as one kernel with a chunk barrier that writes the error itself "
                          "(default: the deferred error form, one barrier-free pass)")
@@ -559,12 +562,13 @@ def main():
                 continue
             others[name] = brief(name, args, torch, steps, graph_too)
         out["workloads"] = others
-        # the same workload with no in-kernel wait anywhere: deferred errors + ratio pass and update as
-        # two plain kernels (what a caller who cannot accept the per-layer barrier's assumptions runs)
+        # the same workload with no in-kernel wait anywhere (OB_CFG_NO_BARRIERS; what a caller who cannot
+        # accept the per-layer barrier's assumptions runs): deferred errors, the ratio pass of every layer
+        # with enough whole tiles from the variance's history, the update as the plain kernel
         import copy
         a2 = copy.copy(args)
-        a2.separate_calls = True
-        if not args.separate_calls and not args.barrier_compress:
+        a2.no_barriers = True
+        if not args.separate_calls and not args.barrier_compress and not args.no_barriers:
             out["wait_free_configuration"] = brief(args.workload, a2, torch, args.steps)
     if host0 is not None:
         out["cpu_baseline"] = cpu_baseline(cfg, cfg["W"] // 2, host0, lr, args.cpu_seconds, False)

@@ -147,6 +147,7 @@ struct LayerSplit {
   int* d_rest_tiles = nullptr;
   // The layers that are too large for the barrier kernel: their TILE_LB tiles ("big" tiles) take the
   // ratio pass with the variance in deferred form (ob_lamb_ratios_apply_hist only)
+  bool big_on = false;                     // there are such tiles (and no wait has expired)
   int n_big_tiles = 0;
   int64_t n_big_params = 0;
   int* d_big_tiles = nullptr;
@@ -447,7 +448,7 @@ void plan_split(const Tiling& tl, int64_t tile_lb, const Tiling& tm, const std::
   };
   // tiles inside one layer, per layer in position order
   std::vector<std::vector<int>> inside((size_t)L);
-  for (int64_t t = 0; t < tl.n_tiles && max_tiles > 0; ++t) {
+  for (int64_t t = 0; t < tl.n_tiles; ++t) {
     int64_t tile0, tile1;
     tile_range(t, &tile0, &tile1);
     const int l = tl.first[(size_t)t];
@@ -456,7 +457,7 @@ void plan_split(const Tiling& tl, int64_t tile_lb, const Tiling& tm, const std::
   for (int64_t l = 0; l < L; ++l) {
     const std::vector<int>& in = inside[(size_t)l];
     const size_t n = in.size();
-    if (n == 0 || n > (size_t)max_tiles) continue;
+    if (n == 0 || n > (size_t)max_tiles) continue;   // (max_tiles = 0: no layer is listed)
     pl->has_listed[(size_t)l] = 1;
     pl->n_listed[(size_t)l] = (int)n;
     pl->list_begin[(size_t)l] = (int)pl->fused_tiles.size();
@@ -478,7 +479,7 @@ void plan_split(const Tiling& tl, int64_t tile_lb, const Tiling& tm, const std::
   }
   // big tiles: the whole tiles of the layers that hold many of them but are not listed
   pl->covered_big.assign((size_t)tm.n_tiles, 0);
-  for (int64_t l = 0; l < L && max_tiles > 0; ++l) {
+  for (int64_t l = 0; l < L; ++l) {   // (also when no layer is listed: the pass needs no barrier)
     const std::vector<int>& in = inside[(size_t)l];
     if (pl->has_listed[(size_t)l] || in.size() < (size_t)OB_BIG_MIN_TILES) continue;
     for (int t : in) {
@@ -517,6 +518,7 @@ bool build_split(ob_lamb_ctx* ctx, const Tiling& tl, int tile_lb, const Tiling& 
     if (pl.covered[(size_t)t] || pl.covered_big[(size_t)t]) cov.push_back((int)t);
   sp->n_cov_tiles = (int)cov.size();
   sp->n_big_tiles = (int)pl.big_tiles.size();
+  sp->big_on = sp->n_big_tiles > 0;
   sp->n_big_params = pl.n_big_params;
   sp->n_rest_ratio_tiles = (int)pl.rest_ratio_tiles.size();
   return upload(ctx, &sp->d_cov_tiles, cov) && upload(ctx, &sp->d_big_tiles, pl.big_tiles) &&
@@ -1307,8 +1309,8 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   if (ob_status s = x_lp_target(nullptr, OB_F32, &xl)) return s;
   Launch la(ctx, hip_stream);
   LayerSplit& sp = ctx->sp_apply;
-  if (!sp.on) {
-    // no tile goes through the kernel with the per-layer barrier: the whole array is kept up to date
+  if (!sp.on && !sp.big_on) {
+    // no tile works from the history: the whole array is kept up to date
     launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, nullptr, ctx->n_tiles, nullptr, true);
     launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
     return la.ok ? OB_OK : OB_ERR_HIP;
@@ -1316,15 +1318,22 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  // the three stages of ob_lamb_ratios_apply; only the kernel with the per-layer barrier works from
-  // the history (outside its tiles the plain ratio pass keeps the array up to date at every step:
-  // on 1024-element tiles that pass is bound by its launch shape, not by the bytes it moves)
+  // the three stages of ob_lamb_ratios_apply; the kernel with the per-layer barrier and the ratio
+  // pass of the layers that are too large for it work from the history (outside their tiles the plain
+  // ratio pass keeps the array up to date at every step: on 1024-element tiles that pass is bound by
+  // its launch shape, not by the bytes it moves).  Without the barrier kernel (OB_CFG_NO_FUSED_APPLY)
+  // every layer with enough whole tiles counts as too large: no wait anywhere, and still no rewrite
+  // of the array at every step.
   launch_variance_terms(la, ctx, st, ra, vh);
-  if (sp.n_big_tiles > 0)   // the layers too large for the barrier kernel: ratio pass from the history on 8192-element tiles
+  if (sp.big_on)
     OB_LAUNCH(la, KID_RATIOS_BIG_HIST, k_ratios_big_hist, sp.n_big_tiles, ra, vh, vterms(ctx), ctx->d_seg_max,
               sp.d_big_tiles, ctx->n_c, sp.tpc, ctx->tpc, lt, ctx->d_tile_seg0);
   launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_ratio_tiles, sp.n_rest_ratio_tiles,
-                sp.d_has_listed, sp.n_layers < ctx->L);
+                sp.on ? sp.d_has_listed : nullptr, sp.on ? sp.n_layers < ctx->L : true);
+  if (!sp.on) {
+    launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
+    return la.ok ? OB_OK : OB_ERR_HIP;
+  }
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
   ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
@@ -1361,7 +1370,7 @@ ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
     la.end("copy", true);
   }
   LayerSplit& sp = ctx->sp_apply;
-  if (sp.on && sp.n_cov_tiles > 0) {
+  if ((sp.on || sp.big_on) && sp.n_cov_tiles > 0) {
     const RatioArgs ra = ratio_args(ctx, st, packed_all, server_scales, pm);
     const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
     launch_variance_terms(la, ctx, st, ra, vh);
@@ -1447,6 +1456,7 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
   (void)hipMemset(ctx->d_flag_srv, 0, sizeof(unsigned long long));
   for (LayerSplit* sp : {&ctx->sp_apply, &ctx->sp_warm}) {
     sp->on = false;
+    sp->big_on = false;   // (no wait in that pass; but after an expiry every call takes the plain kernels)
     (void)hipMemset(sp->d_counter, 0, sizeof(unsigned long long) * (size_t)ctx->L * CTR_STRIDE);
     (void)hipMemset(sp->d_flag, 0, sizeof(unsigned long long) * (size_t)ctx->L);
   }
@@ -1459,7 +1469,7 @@ ob_status ob_lamb_check_device_status(ob_lamb_ctx* ctx, void* hip_stream) {
 
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_layers : 0; }
 int64_t ob_lamb_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_params : 0; }
-int64_t ob_lamb_big_tile_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.on) ? ctx->sp_apply.n_big_params : 0; }
+int64_t ob_lamb_big_tile_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_apply.big_on) ? ctx->sp_apply.n_big_params : 0; }
 int64_t ob_lamb_warmup_fused_layers(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_layers : 0; }
 int64_t ob_lamb_warmup_fused_params(const ob_lamb_ctx* ctx) { return (ctx && ctx->sp_warm.on) ? ctx->sp_warm.n_params : 0; }
 
