@@ -325,6 +325,10 @@ class DeviceStep:
     def ratios_apply(self, lr):
         if self.vf_period and self.m_is_packed:
             # the variance in deferred form: the array is brought up to date every vf_period-th step
+            # (the history's buffers change from step to step with a period of K(K+1) steps, so a
+            # captured pair of steps cannot carry it)
+            if torch.cuda.is_current_stream_capturing():
+                raise RuntimeError("deferred_variance cannot be captured into a graph: construct with deferred_variance=0")
             n_old = self._vf_n_old
             write_v = (n_old + 1 >= self.vf_period)
             ob.ob_lamb_ratios_apply_hist(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
