@@ -156,6 +156,17 @@ class DeviceStep:
         if "err_server" in st and st["err_server"] is not None:
             self.srv_scale.zero_()
 
+    def checkpoint(self):
+        """The optimizer state as host arrays in its plain form, whatever compact forms are in use:
+        the momentum, both compression errors and the fresh variance are materialised (fp32, exactly
+        the values the compact forms stand for), so that load_state() of the result into a new
+        DeviceStep -- of any configuration -- continues the run bit for bit."""
+        keys = ["x", "m", "v_fresh", "v_frozen", "err_worker", "err_server", "c_avg", "r_prev", "coeff_c"]
+        ck = {k: self.get(k).copy() for k in keys}
+        if self.t["mom_scale"] is not None:
+            ck["mom_scale"] = self.t["mom_scale"].cpu().numpy().copy()
+        return ck
+
     def _vf_hist(self, n_old, write_v):
         """ob_lamb_vf_history of the step whose pairs are (_cur, _prev): the n_old pairs before them."""
         R = len(self._pa)

@@ -308,6 +308,47 @@ def test_trajectory_with_the_variance_in_deferred_form(case, steps, period, fuse
     finish(dev)
 
 
+def test_resume_from_a_checkpoint_continues_bit_for_bit():
+    """DeviceStep.checkpoint() materialises every compact form (1-bit momentum, deferred errors, the
+    variance's history -- taken here in the middle of a history, two steps after the array was last
+    written); a new context that loads it continues exactly where the first one would have gone:
+    after four more steps every array equals the uninterrupted run's bit for bit."""
+    _need_gpu()
+    cfg = make_case("bert_mini")
+    opts = dict(packed=True, fused=True, warm_state=True, deferred=True, deferred_variance=4)
+
+    def steps(dev, st, t0, t1):
+        for t in range(t0, t1):
+            g = gradient(st, cfg, t)
+            fw, fs = foreign_worker_chunks(st, cfg, t)
+            fa, fss = foreign_server_chunks(st, cfg, t)
+            dev.begin_step()
+            dev.packed_in.copy_(torch.from_numpy(np.ascontiguousarray(fw).view(np.int32)))
+            dev.scales_in.copy_(torch.from_numpy(fs))
+            dev.packed_all.copy_(torch.from_numpy(np.ascontiguousarray(fa).view(np.int32)))
+            dev.server_scales.copy_(torch.from_numpy(fss))
+            dev.step(torch.from_numpy(g).to(dev.device), 1e-3 * (1 + t % 3))
+
+    st, _, straight = start_pair(cfg, **opts)
+    steps(straight, st, 0, 11)
+    want = straight.checkpoint()
+    finish(straight)
+
+    st, _, first = start_pair(cfg, **opts)
+    steps(first, st, 0, 7)
+    assert first._vf_pending is not None and first._vf_n_old == 2   # in the middle of a history
+    ck = first.checkpoint()
+    finish(first)
+    st2, _, second = start_pair(cfg, **opts)
+    second.load_state(ck)
+    second.t["mom_scale"].copy_(torch.from_numpy(ck["mom_scale"]))
+    steps(second, st2, 7, 11)
+    got = second.checkpoint()
+    for k in want:
+        assert np.array_equal(got[k].view(np.uint32), want[k].view(np.uint32)), k
+    finish(second)
+
+
 def test_trajectory_after_a_last_bit_difference_of_a_scale():
     """The regime that a last-bit difference of a scale opens (planted in the oracle's state, on the
     CPU): the two sides stay within the stated bounds for the rest of a 60-step run."""
