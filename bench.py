@@ -154,11 +154,11 @@ class Workload:
 
     @staticmethod
     def variance_period(args):
-        """The fresh variance in deferred form needs the 1-bit momentum, the one-call ratio+update and
-        fp32 parameters; a captured graph cannot carry it (the history's buffers change from step to
-        step with a period of K(K+1) steps)."""
+        """The fresh variance in deferred form needs the 1-bit momentum and the one-call ratio+update;
+        a captured graph cannot carry it (the history's buffers change from step to step with a
+        period of K(K+1) steps)."""
         k = int(getattr(args, "variance_period", 0))
-        if args.dense_momentum or args.separate_calls or args.x_lp != "none" or getattr(args, "graph", False):
+        if args.dense_momentum or args.separate_calls or getattr(args, "graph", False):
             return 0
         return k
 
@@ -454,8 +454,9 @@ def main():
     x_more = 2.0 if args.x_lp != "none" else 0.0          # 16-bit parameter copy written
     for k in ("compress_resident", "compress_deferred", "momentum_z_sumsq", "warmup_moments", "warmup_resident"):
         KB[k] = (KB[k][0] - g_less, KB[k][1])
-    for k in ("decompress_apply", "ratios_apply_resident", "warmup_apply", "warmup_resident"):
-        KB[k] = (KB[k][0] + x_more, KB[k][1])   # (ratios_apply_hist: fp32 parameters only)
+    for k in ("decompress_apply", "ratios_apply_resident", "ratios_apply_hist", "warmup_apply", "warmup_resident"):
+        if k in KB:
+            KB[k] = (KB[k][0] + x_more, KB[k][1])
     fused_params, wfused = wl.fused_params, wl.wfused
     units = {"n_pad": ds.n_pad, "n_c": ds.n_c, "fused": fused_params, "wfused": wfused, "big": wl.big_params}
     if wfused:   # the two-pass warmup kernels then cover only the remaining layers (two launches each)

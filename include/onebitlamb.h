@@ -280,7 +280,7 @@ ob_status ob_lamb_ratios_apply(ob_lamb_ctx* ctx, const ob_lamb_state* st, const 
  * st->v_fresh), 0..OB_VF_MAX_OLD; bits[i] / scales[i], i < n_old: their sign words [N_pad/32] and
  * scales [W], NEWEST FIRST (bits[0] is the momentum before the previous one), device pointers,
  * 16-byte aligned, read only.  h = NULL means n_old = 0, write_v = 1: ob_lamb_ratios_apply itself.
- * Requires the momentum in 1-bit form (st->m == NULL, else OB_ERR_ARG) and fp32 parameters.
+ * Requires the momentum in 1-bit form (st->m == NULL, else OB_ERR_ARG).
  * Everything else -- layers, barrier, bounded waits, what an expired wait leaves behind -- as for
  * ob_lamb_ratios_apply.  A caller's duty: between a call with write_v = 0 and the next one with
  * write_v = 1, st->v_fresh is NOT the variance; ob_lamb_variance_dense gives it. */
@@ -365,6 +365,11 @@ ob_status ob_lamb_decompress_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
 ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
                                   const uint32_t* packed_all, const float* server_scales, float lr,
                                   void* x_lp, ob_dtype x_dtype, void* hip_stream);
+/* ob_lamb_ratios_apply_hist with the 16-bit copy of the parameters (h as there, x_lp / x_dtype as above). */
+ob_status ob_lamb_ratios_apply_hist_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st,
+                                       const uint32_t* packed_all, const float* server_scales, float lr,
+                                       const ob_lamb_vf_history* h, void* x_lp, ob_dtype x_dtype,
+                                       void* hip_stream);
 
 /* Kernels with an in-kernel barrier, and what happens if one of their waits expires
  * -----------------------------------------------------------------------------------

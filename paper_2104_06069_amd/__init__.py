@@ -16,5 +16,5 @@ from .binding import (  # noqa: F401
     ob_lamb_warmup_fused_layers, ob_lamb_warmup_fused_params,
     OB_CFG_TWO_PASS_COMPRESS, OB_CFG_NO_FUSED_APPLY, OB_CFG_TWO_PASS_WARMUP, OB_CFG_NO_BARRIERS, OB_SPIN_NONE,
     ob_lamb_server_reduce_static, ob_lamb_static_max_chunk_len, ob_lamb_diag_copy, ob_lamb_workspace_bytes, ob_lamb_error_dense, ob_lamb_server_error_dense,
-    OB_VF_MAX_OLD, ObLambVfHistory, make_vf_history, ob_lamb_ratios_apply_hist, ob_lamb_variance_dense, ob_lamb_big_tile_params,
+    OB_VF_MAX_OLD, ObLambVfHistory, make_vf_history, ob_lamb_ratios_apply_hist, ob_lamb_ratios_apply_hist_lp, ob_lamb_variance_dense, ob_lamb_big_tile_params,
 )

@@ -93,6 +93,7 @@ def lib():
             "ob_lamb_momentum_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_momentum_scale": (C.c_int, [vp, sp, vp]),
             "ob_lamb_ratios_apply_hist": (C.c_int, [vp, sp, vp, vp, f, C.POINTER(ObLambVfHistory), vp]),
+            "ob_lamb_ratios_apply_hist_lp": (C.c_int, [vp, sp, vp, vp, f, C.POINTER(ObLambVfHistory), vp, C.c_int, vp]),
             "ob_lamb_variance_dense": (C.c_int, [vp, sp, vp, vp, C.POINTER(ObLambVfHistory), vp, vp]),
             "ob_lamb_error_dense": (C.c_int, [vp, sp, vp, vp]),
             "ob_lamb_server_error_dense": (C.c_int, [vp, sp, vp, vp]),
@@ -320,6 +321,13 @@ def ob_lamb_ratios_apply_hist(ctx, state, packed_all, server_scales, lr, hist, s
     _check(lib().ob_lamb_ratios_apply_hist(ctx, C.byref(state), _addr(packed_all), _addr(server_scales), lr,
                                            None if hist is None else C.byref(hist), _addr(stream)),
            ctx, "ob_lamb_ratios_apply_hist")
+
+
+def ob_lamb_ratios_apply_hist_lp(ctx, state, packed_all, server_scales, lr, hist, x_lp, x_dtype, stream=None):
+    _check(lib().ob_lamb_ratios_apply_hist_lp(ctx, C.byref(state), _addr(packed_all), _addr(server_scales), lr,
+                                              None if hist is None else C.byref(hist), _addr(x_lp), int(x_dtype),
+                                              _addr(stream)),
+           ctx, "ob_lamb_ratios_apply_hist_lp")
 
 
 def ob_lamb_variance_dense(ctx, state, packed_all, server_scales, hist, v_out, stream=None):

@@ -1293,10 +1293,12 @@ void launch_variance_terms(Launch& la, ob_lamb_ctx* ctx, const ob_lamb_state* st
 
 extern "C" {
 
-ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
-                                    const float* server_scales, float lr, const ob_lamb_vf_history* h,
-                                    void* hip_stream) {
+ob_status ob_lamb_ratios_apply_hist_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                       const float* server_scales, float lr, const ob_lamb_vf_history* h,
+                                       void* x_lp, ob_dtype x_dtype, void* hip_stream) {
   if (ob_status s = check_ratios_args(ctx, st, packed_all, server_scales)) return s;
+  XLp xl;
+  if (ob_status s = x_lp_target(x_lp, x_dtype, &xl)) return s;
   REQUIRE_PTR(st->x);
   if (!std::isfinite(lr)) return OB_ERR_ARG;
   bool packed_m = false;
@@ -1305,8 +1307,6 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   if (!packed_m || st->m_packed == packed_all) return OB_ERR_ARG;   // the history is one of 1-bit momenta
   VfHist vh;
   if (ob_status s = vf_history(h, &vh)) return s;
-  XLp xl;
-  if (ob_status s = x_lp_target(nullptr, OB_F32, &xl)) return s;
   Launch la(ctx, hip_stream);
   LayerSplit& sp = ctx->sp_apply;
   if (!sp.on && !sp.big_on) {
@@ -1340,12 +1340,18 @@ ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, c
   ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
-  dispatch1(st->mom_scale != nullptr, [&](auto k_) {
-    OB_LAUNCH(la, KID_RATIOS_APPLY_HIST, (k_ratios_apply_hist<decltype(k_)::value, false>), sp.n_fused_tiles, ra,
-              vh, vterms(ctx), aa, ls, lt);
+  dispatch2(st->mom_scale != nullptr, xl.p != nullptr, [&](auto k_, auto lx) {
+    OB_LAUNCH(la, KID_RATIOS_APPLY_HIST, (k_ratios_apply_hist<decltype(k_)::value, decltype(lx)::value>),
+              sp.n_fused_tiles, ra, vh, vterms(ctx), aa, ls, lt);
   });
   launch_apply(la, ctx, st, packed_all, server_scales, lr, sp.d_rest_tiles, sp.n_rest_tiles, xl);
   return la.ok ? OB_OK : OB_ERR_HIP;
+}
+
+ob_status ob_lamb_ratios_apply_hist(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,
+                                    const float* server_scales, float lr, const ob_lamb_vf_history* h,
+                                    void* hip_stream) {
+  return ob_lamb_ratios_apply_hist_lp(ctx, st, packed_all, server_scales, lr, h, nullptr, OB_F32, hip_stream);
 }
 
 ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, const uint32_t* packed_all,

@@ -47,8 +47,8 @@ class DeviceStep:
         # the steps' own packed_all / server_scales buffers: K + 1 of them are kept in a ring
         self.vf_period = int(deferred_variance)
         if self.vf_period:
-            assert 2 <= self.vf_period <= ob.OB_VF_MAX_OLD + 1 and packed_momentum and fused_apply and x_lp_dtype is None, \
-                "deferred_variance needs the 1-bit momentum, ob_lamb_ratios_apply and fp32 parameters"
+            assert 2 <= self.vf_period <= ob.OB_VF_MAX_OLD + 1 and packed_momentum and fused_apply, \
+                "deferred_variance needs the 1-bit momentum and ob_lamb_ratios_apply"
         self.vf_ages = {}         # steps taken so far by the number of momentum steps each had to apply
         self._vf_n_old = 0        # momenta older than the previous one since v_fresh was written
         self._vf_pending = None   # arguments of the last step that left v_fresh behind (for the dense view)
@@ -342,8 +342,8 @@ class DeviceStep:
                 raise RuntimeError("deferred_variance cannot be captured into a graph: construct with deferred_variance=0")
             n_old = self._vf_n_old
             write_v = (n_old + 1 >= self.vf_period)
-            ob.ob_lamb_ratios_apply_hist(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
-                                         self._vf_hist(n_old, write_v), self.stream)
+            ob.ob_lamb_ratios_apply_hist_lp(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,
+                                            self._vf_hist(n_old, write_v), *self._x_lp_args(), self.stream)
             self.vf_ages[n_old + 1] = self.vf_ages.get(n_old + 1, 0) + 1
             if write_v:
                 self._vf_n_old, self._vf_pending = 0, None

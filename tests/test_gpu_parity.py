@@ -775,16 +775,21 @@ def _to_lp(g32, fmt):
     return t, (1 if fmt == "f16" else 2, t.view(torch.int16).numpy().view(np.uint16).copy())
 
 
-@pytest.mark.parametrize("case,gfmt,xfmt,fused,packed,scale", [
-    ("bert_mini", "f16", "f16", True, True, 1.0 / 1024),
-    ("bert_mini", "bf16", "bf16", True, True, 1.0),
-    ("bert_mini", "f16", "bf16", False, False, 1.0 / 1000),   # scale not a power of two; separate calls
-    ("odd", "bf16", "f16", True, True, 1.0 / 64),
-    ("odd", "f16", "f16", True, False, 1.0),                 # fp32 momentum behind the fused entry point
-    ("tiny", "f32", "f16", True, True, 1.0),                 # only the 16-bit parameter copy
-    ("small", "f16", None, False, True, 0.5),                # only the 16-bit gradient
-    ("w1", "bf16", "bf16", True, True, 1.0 / 8)])
-def test_mixed_precision_variant(case, gfmt, xfmt, fused, packed, scale):
+@pytest.mark.parametrize("case,gfmt,xfmt,fused,packed,scale,vperiod", [
+    ("bert_mini", "f16", "f16", True, True, 1.0 / 1024, 0),
+    ("bert_mini", "bf16", "bf16", True, True, 1.0, 0),
+    ("bert_mini", "f16", "bf16", False, False, 1.0 / 1000, 0),   # scale not a power of two; separate calls
+    ("odd", "bf16", "f16", True, True, 1.0 / 64, 0),
+    ("odd", "f16", "f16", True, False, 1.0, 0),                 # fp32 momentum behind the fused entry point
+    ("tiny", "f32", "f16", True, True, 1.0, 0),                 # only the 16-bit parameter copy
+    ("small", "f16", None, False, True, 0.5, 0),                # only the 16-bit gradient
+    ("w1", "bf16", "bf16", True, True, 1.0 / 8, 0),
+    # with the variance in deferred form (ob_lamb_ratios_apply_hist_lp)
+    ("bert_mini", "f16", "f16", True, True, 1.0 / 1024, 4),
+    ("tiny", "bf16", "bf16", True, True, 1.0, 3),
+    ("odd", "f32", "f16", True, True, 1.0, 2),
+    ("big_and_small", "bf16", "bf16", True, True, 1.0 / 16, 4)])
+def test_mixed_precision_variant(case, gfmt, xfmt, fused, packed, scale, vperiod):
     """16-bit gradient in (times the inverse loss scale), 16-bit copy of the parameters out, through
     3 LAMB steps, the snapshot and 12 compression steps; state and arithmetic stay fp32, so every
     comparison is as strict as for the fp32 entry points and the 16-bit copy is bit-exact."""
@@ -796,7 +801,7 @@ def test_mixed_precision_variant(case, gfmt, xfmt, fused, packed, scale):
     ref.grad_scale = scale
     tdt = {None: None, "f16": torch.float16, "bf16": torch.bfloat16}[xfmt]
     dev = DeviceStep(pl.offsets, cfg["W"], cfg["server_chunk"], packed_momentum=packed, fused_apply=fused,
-                     x_lp_dtype=tdt, grad_scale=scale, **HYPER)
+                     x_lp_dtype=tdt, grad_scale=scale, deferred_variance=vperiod, **HYPER)
     s = init_state(st, cfg)
     s["v_fresh"][...] = 0
     s["c_avg"][...] = 0
@@ -857,6 +862,8 @@ def test_mixed_precision_variant(case, gfmt, xfmt, fused, packed, scale):
         for k in ("x", "v_fresh", "err_worker", "err_server", "r_prev"):
             assert_close(dev.get(k), ref.t[k], f"step {t} {k}")
         check_x_lp(t)
+    if vperiod:
+        assert set(dev.vf_ages) == set(range(1, vperiod + 1)), dev.vf_ages
     finish(dev)
 
 
@@ -882,6 +889,9 @@ def test_mixed_precision_argument_errors():
     assert status(ob.ob_lamb_ratios_apply_lp, dev.packed_all, dev.server_scales, 1e-3, g16, ob.OB_F32) == -2
     assert status(ob.ob_lamb_decompress_apply_lp, dev.packed_all, dev.server_scales, 1e-3, g16.data_ptr() + 2, ob.OB_BF16) == -3
     assert status(ob.ob_lamb_warmup_step_lp, g16, ob.OB_F16, 1.0, 1e-3, g16, 5) == -2
+    assert status(ob.ob_lamb_ratios_apply_hist_lp, dev.packed_all, dev.server_scales, 1e-3, None, g16, ob.OB_F32) == -2
+    assert status(ob.ob_lamb_ratios_apply_hist_lp, dev.packed_all, dev.server_scales, 1e-3, None,
+                  g16.data_ptr() + 2, ob.OB_F16) == -3
     finish(dev)
 
 
