@@ -315,6 +315,12 @@ ob_status ob_lamb_variance_dense(ob_lamb_ctx* ctx, const ob_lamb_state* st, cons
 ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8_t* span_owner,
                              int32_t* layer_listed);
 
+/* Host-only, like ob_lamb_plan_split and for the same max_tiles: span_big [W * ceil(n_c / 1024)] bytes
+ * receives 1 for the 1024-element spans inside the 8192-element tiles where ob_lamb_ratios_apply_hist
+ * takes the ratio pass from the history although the barrier kernel does not hold them -- the whole
+ * tiles of every layer that is not listed and has at least 64 of them -- and 0 elsewhere. */
+ob_status ob_lamb_plan_big_tiles(const ob_lamb_config* cfg, int64_t max_tiles, uint8_t* span_big);
+
 /* Number of layers the single kernel of ob_lamb_ratios_apply takes part in on this device (0..L). */
 int64_t ob_lamb_fused_layers(const ob_lamb_ctx* ctx);
 /* ... and the number of parameters in its tiles. */

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     ob_lamb_destroy, ob_lamb_freeze, ob_lamb_layer_ratios, ob_lamb_num_params, ob_lamb_padded_len,
     ob_lamb_padded_len_for, ob_lamb_profile_enable, ob_lamb_profile_read, ob_lamb_server_reduce,
     ob_lamb_status_string, ob_lamb_warmup_step, make_state, ob_lamb_check_device_status,
-    ob_lamb_uses_single_pass, ob_lamb_server_single_pass, ob_lamb_plan_split, ob_lamb_momentum_dense, ob_lamb_momentum_scale, ob_lamb_ratios_apply, ob_lamb_fused_layers, ob_lamb_fused_params,
+    ob_lamb_uses_single_pass, ob_lamb_server_single_pass, ob_lamb_plan_split, ob_lamb_plan_big_tiles, ob_lamb_momentum_dense, ob_lamb_momentum_scale, ob_lamb_ratios_apply, ob_lamb_fused_layers, ob_lamb_fused_params,
     OB_F32, OB_F16, OB_BF16, ob_lamb_warmup_step_lp, ob_lamb_compress_local_lp,
     ob_lamb_decompress_apply_lp, ob_lamb_ratios_apply_lp,
     ob_lamb_warmup_fused_layers, ob_lamb_warmup_fused_params,

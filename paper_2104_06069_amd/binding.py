@@ -101,6 +101,7 @@ def lib():
             "ob_lamb_uses_single_pass": (i32, [vp]),
             "ob_lamb_server_single_pass": (i32, [vp]),
             "ob_lamb_plan_split": (C.c_int, [C.POINTER(ObLambConfig), i64, vp, vp]),
+            "ob_lamb_plan_big_tiles": (C.c_int, [C.POINTER(ObLambConfig), i64, vp]),
             "ob_lamb_server_reduce_static": (C.c_int, [i32, i64, vp, vp, vp, vp, vp, vp]),
             "ob_lamb_static_max_chunk_len": (i64, []),
             "ob_lamb_diag_copy": (C.c_int, [vp, vp, i64, vp]),
@@ -175,6 +176,21 @@ def ob_lamb_plan_split(layer_offsets, num_workers, max_tiles):
     if st != OB_OK:
         raise ObLambError(st, "ob_lamb_plan_split")
     return owner, listed
+
+
+def ob_lamb_plan_big_tiles(layer_offsets, num_workers, max_tiles):
+    """Host-only: -> span_big uint8[W * ceil(n_c/1024)] as a numpy array."""
+    import numpy as np
+    offs = [int(o) for o in layer_offsets]
+    arr = (C.c_int64 * len(offs))(*offs)
+    cfg = ObLambConfig(len(offs) - 1, arr, int(num_workers), 0, 0.9, 0.999, 0.9, 1e-6, 0.01, 0.3, 0.5, 4.0,
+                       0.1, 0.0, 0, 0, 0)
+    n_c = ob_lamb_padded_len_for(offs[-1], num_workers) // int(num_workers)
+    big = np.zeros(int(num_workers) * ((n_c + 1023) // 1024), dtype=np.uint8)
+    st = lib().ob_lamb_plan_big_tiles(C.byref(cfg), int(max_tiles), big.ctypes.data)
+    if st != OB_OK:
+        raise ObLambError(st, "ob_lamb_plan_big_tiles")
+    return big
 
 
 def ob_lamb_destroy(ctx):

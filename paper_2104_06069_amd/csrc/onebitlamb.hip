@@ -724,6 +724,26 @@ ob_status ob_lamb_plan_split(const ob_lamb_config* cfg, int64_t max_tiles, uint8
   }
 }
 
+ob_status ob_lamb_plan_big_tiles(const ob_lamb_config* cfg, int64_t max_tiles, uint8_t* span_big) {
+  if (ob_status s = check_config(cfg)) return s;
+  if (!span_big) return OB_ERR_NULL;
+  if (max_tiles < 0) return OB_ERR_ARG;
+  try {
+    const int64_t L = cfg->num_layers, W = cfg->num_workers;
+    const int64_t n_c = ob_lamb_padded_len_for(cfg->layer_offsets[L], cfg->num_workers) / W;
+    const std::vector<int64_t> h_off = host_offsets(cfg);
+    Tiling tm, tl;
+    if (!build_tiling(TILE_MAIN, n_c, W, L, h_off, &tm) || !build_tiling(TILE_LB, n_c, W, L, h_off, &tl))
+      return OB_ERR_ARG;
+    SplitPlan pl;
+    plan_split(tl, TILE_LB, tm, h_off, n_c, L, max_tiles, &pl);
+    for (int64_t t = 0; t < tm.n_tiles; ++t) span_big[t] = pl.covered_big[(size_t)t] ? 1 : 0;
+    return OB_OK;
+  } catch (const std::bad_alloc&) {
+    return OB_ERR_ARG;
+  }
+}
+
 namespace { ob_status static_scratch(double** out); }
 
 static ob_status create_ctx(const ob_lamb_config* cfg, ob_lamb_ctx** out) {

@@ -151,6 +151,50 @@ def test_split_between_barrier_and_plain_kernels(ob, seed):
         assert not (owner == 2).any()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_big_tiles_of_the_layers_outside_the_barrier_kernel(ob, seed):
+    """Which 8192-element tiles take the ratio pass from the variance's history without the barrier
+    kernel (host planning, no device): the whole tiles of every layer that has at least 64 of them
+    and is not listed -- against the definition written out span by span."""
+    import numpy as np
+    r = np.random.default_rng(100 + seed)
+    kinds = [0, 3, 1024, 8192, 40000, 63 * 8192, 64 * 8192, 64 * 8192 + 5000, 70 * 8192 + 1, 100 * 8192]
+    sizes = [int(r.choice(kinds)) for _ in range(int(r.integers(2, 8)))] + [int(r.integers(1, 5000))]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    W = int(r.choice([1, 2, 3, 8]))
+    max_tiles = int(r.choice([0, 5, 66, 1000]))
+    big = ob.ob_lamb_plan_big_tiles(offsets, W, max_tiles)
+    owner, listed = ob.ob_lamb_plan_split(offsets, W, max_tiles)
+    off = np.asarray(offsets, dtype=np.int64)
+    N, L = int(off[-1]), len(off) - 1
+    n_pad = ob.ob_lamb_padded_len_for(N, W)
+    n_c = n_pad // W
+    layer_of = np.full(n_pad, L, dtype=np.int64)
+    for l in range(L):
+        layer_of[off[l]:off[l + 1]] = l
+    whole = {}
+    for c in range(W):
+        for a in range(c * n_c, (c + 1) * n_c, 8192):
+            b = min(a + 8192, (c + 1) * n_c)
+            l = int(layer_of[a])
+            if l < L and np.all(layer_of[a:b] == l):
+                whole.setdefault(l, []).append((a, b))
+    in_big = np.zeros(n_pad, dtype=bool)
+    for l, ts in whole.items():
+        if listed[l] == 0 and len(ts) >= 64:
+            for a, b in ts:
+                in_big[a:b] = True
+    want = []
+    for c in range(W):
+        for a in range(c * n_c, (c + 1) * n_c, 1024):
+            want.append(1 if in_big[a] else 0)
+    want = np.array(want, dtype=np.uint8)
+    assert np.array_equal(big, want), (sizes, W, max_tiles)
+    assert not ((big == 1) & (owner != 1)).any()     # their update runs in the plain kernels
+    if max_tiles >= 1000:
+        assert not big.any()                         # every layer with whole tiles is listed
+
+
 def test_plan_split_rejects_bad_arguments(ob):
     import numpy as np
     lib = ob.lib()
@@ -162,6 +206,10 @@ def test_plan_split_rejects_bad_arguments(ob):
     assert lib.ob_lamb_plan_split(C.byref(cfg), 1, None, listed.ctypes.data) == -1
     assert lib.ob_lamb_plan_split(C.byref(cfg), -1, owner.ctypes.data, listed.ctypes.data) == -2
     assert lib.ob_lamb_plan_split(C.byref(cfg), 1, owner.ctypes.data, listed.ctypes.data) == 0
+    assert lib.ob_lamb_plan_big_tiles(None, 1, owner.ctypes.data) == -1
+    assert lib.ob_lamb_plan_big_tiles(C.byref(cfg), 1, None) == -1
+    assert lib.ob_lamb_plan_big_tiles(C.byref(cfg), -1, owner.ctypes.data) == -2
+    assert lib.ob_lamb_plan_big_tiles(C.byref(cfg), 1, owner.ctypes.data) == 0
 
 
 def test_bench_refuses_more_than_one_gpu():
