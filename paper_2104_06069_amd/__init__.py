@@ -5,7 +5,7 @@ of the path runs in the library's kernels.  There is no CPU fallback: loading fa
 the shared library has not been built (`python -m paper_2104_06069_amd.build`).
 """
 from .binding import (  # noqa: F401
-    OB_OK, ObLambConfig, ObLambError, ObLambState, lib, lib_path,
+    OB_OK, OB_ERR_NULL, OB_ERR_ARG, OB_ERR_ALIGN, OB_ERR_STATE, OB_ERR_HIP, ObLambConfig, ObLambError, ObLambState, lib, lib_path,
     ob_lamb_chunk_len, ob_lamb_compress_local, ob_lamb_create, ob_lamb_decompress_apply,
     ob_lamb_destroy, ob_lamb_freeze, ob_lamb_layer_ratios, ob_lamb_num_params, ob_lamb_padded_len,
     ob_lamb_padded_len_for, ob_lamb_profile_enable, ob_lamb_profile_read, ob_lamb_server_reduce,

@@ -8,6 +8,7 @@ import ctypes as C
 import os
 
 OB_OK = 0
+OB_ERR_NULL, OB_ERR_ARG, OB_ERR_ALIGN, OB_ERR_STATE, OB_ERR_HIP = -1, -2, -3, -4, -5
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 

@@ -37,6 +37,57 @@ def test_every_declared_symbol_is_exported(ob):
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c_and_the_binding_mirrors_its_layouts(ob, tmp_path):
+    """include/onebitlamb.h compiles as C99 without warnings, and every structure and constant the
+    Python binding re-declares (argument marshalling happens through them) has the size, the field
+    offsets and the value the header gives it."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    structs = {"ob_lamb_config": ob.ObLambConfig, "ob_lamb_state": ob.ObLambState,
+               "ob_lamb_vf_history": ob.ObLambVfHistory}
+    consts = ["OB_OK", "OB_ERR_NULL", "OB_ERR_ARG", "OB_ERR_ALIGN", "OB_ERR_STATE", "OB_ERR_HIP",
+              "OB_F32", "OB_F16", "OB_BF16", "OB_VF_MAX_OLD", "OB_SPIN_NONE"]
+    flags = ["OB_CFG_TWO_PASS_COMPRESS", "OB_CFG_NO_FUSED_APPLY", "OB_CFG_TWO_PASS_WARMUP", "OB_CFG_NO_BARRIERS"]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "onebitlamb.h"', 'int main(void) {']
+    for cname, ct in structs.items():
+        lines.append(f'  printf("sizeof {cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in ct._fields_:
+            lines.append(f'  printf("offsetof {cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    for c in consts:
+        lines.append(f'  printf("const {c} %d\\n", (int)({c}));')
+    for c in flags:
+        lines.append(f'  printf("const {c} %u\\n", (unsigned)({c}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout
+    got = {}
+    for ln in out.splitlines():
+        kind, name, val = ln.split()
+        got[(kind, name)] = int(val)
+    for cname, ct in structs.items():
+        assert got[("sizeof", cname)] == C.sizeof(ct), cname
+        for fname, _ in ct._fields_:
+            assert got[("offsetof", f"{cname}.{fname}")] == getattr(ct, fname).offset, (cname, fname)
+        n_header = sum(1 for k in got if k[0] == "offsetof" and k[1].startswith(cname + "."))
+        assert n_header == len(ct._fields_)
+    # the header's structures hold nothing the binding does not know of: sizes already agree, and the
+    # last field ends where the structure (up to its alignment) ends
+    for cname, ct in structs.items():
+        last = ct._fields_[-1][0]
+        end = getattr(ct, last).offset + getattr(ct, last).size
+        assert C.sizeof(ct) - end < C.alignment(ct), cname
+    for c in consts + flags:
+        assert got[("const", c)] == getattr(ob, c), c
+
+
 def test_padded_len_helper(ob):
     assert ob.ob_lamb_padded_len_for(1, 1) == 256
     assert ob.ob_lamb_padded_len_for(336232258, 64) == 336232448
