@@ -154,11 +154,9 @@ class Workload:
 
     @staticmethod
     def variance_period(args):
-        """The fresh variance in deferred form needs the 1-bit momentum and the one-call ratio+update;
-        a captured graph cannot carry it (the history's buffers change from step to step with a
-        period of K(K+1) steps)."""
+        """The fresh variance in deferred form needs the 1-bit momentum and the one-call ratio+update."""
         k = int(getattr(args, "variance_period", 0))
-        if args.dense_momentum or args.separate_calls or getattr(args, "graph", False):
+        if args.dense_momentum or args.separate_calls:
             return 0
         return k
 
@@ -180,31 +178,35 @@ class Workload:
         torch = self.torch
         for t in range(PREWARM - PREWARM % 2):
             self.one_step(t)
-        for t in range(warmup + (warmup % 2 if graph else 0)):
+        P = self.ds.graph_period if graph else 1
+        for t in range(warmup + (-warmup % P)):
             self.one_step(t)
         torch.cuda.synchronize()
         if graph:
-            assert not self.ds.vf_period, "a captured graph cannot carry the variance's history"
-            # two steps return the alternating buffer pairs to where they started: one graph, replayed
-            assert steps % 2 == 0, "--graph replays pairs of steps"
+            # P steps return the buffer pairs (and the variance's history) to where they started: one
+            # graph of P steps, replayed
+            assert steps % P == 0, f"--graph replays groups of {P} steps"
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             g = torch.cuda.CUDAGraph()
+            ages0 = dict(self.ds.vf_ages)
             with torch.cuda.stream(side):
                 with torch.cuda.graph(g, stream=side):
-                    self.one_step(0); self.one_step(1)
+                    for t in range(P):
+                        self.one_step(t)
             torch.cuda.current_stream().wait_stream(side)
+            self.ages_timed = self.ages_since(ages0)     # (one group's; every replay repeats it)
             g.replay(); torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(steps // 2):
+            for _ in range(steps // P):
                 g.replay()
             torch.cuda.synchronize()
             mean = 1e3 * (time.perf_counter() - t0) / steps
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps // 2 + 1)]
-            for i in range(steps // 2):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps // P + 1)]
+            for i in range(steps // P):
                 ev[i].record(); g.replay()
             ev[-1].record(); torch.cuda.synchronize()
-            per = [ev[i].elapsed_time(ev[i + 1]) / 2 for i in range(steps // 2)]
+            per = [ev[i].elapsed_time(ev[i + 1]) / P for i in range(steps // P)]
         else:
             ages0 = dict(self.ds.vf_ages)
             t0 = time.perf_counter()
@@ -306,9 +308,9 @@ def brief(name, args, torch, steps, graph_too=False):
     if graph_too:
         import copy
         ag = copy.copy(args)
-        ag.graph = True     # (the variance array rewritten at every step: see Workload.variance_period)
+        ag.graph = True
         wg = Workload(name, ag, torch)
-        gm, gmed = wg.timed(steps + steps % 2, args.warmup, graph=True)
+        gm, gmed = wg.timed(steps + (-steps % wg.ds.graph_period), args.warmup, graph=True)
         bg = wg.step_bytes(0.0, 0.0)
         wg.close()
         out["graph_replay_ms_per_step"] = round(gm, 4)
@@ -350,8 +352,9 @@ def main():
                     help="mixed-precision variant: also write a 16-bit copy of the parameters "
                          "(2 bytes/param more)")
     ap.add_argument("--graph", action="store_true",
-                    help="time replays of a HIP graph that holds two consecutive steps (for launch-bound "
-                         "sizes; --steps must be even)")
+                    help="time replays of a HIP graph that holds as many consecutive steps as it takes for the "
+                         "buffers to be arranged as at the start (2, or twice --variance-period; for launch-bound "
+                         "sizes; --steps is rounded up to a multiple)")
     ap.add_argument("--no-barriers", action="store_true",
                     help="OB_CFG_NO_BARRIERS: none of the kernels with an in-kernel barrier")
     ap.add_argument("--barrier-compress", action="store_true",
@@ -403,6 +406,8 @@ def main():
                      fss=ds._ss[0].cpu().numpy(),
                      mom_scale=None if ds.t["mom_scale"] is None else ds.t["mom_scale"].cpu().numpy())
 
+    if args.graph:
+        args.steps += -args.steps % wl.ds.graph_period
     ms_per_step, ms_median = wl.timed(args.steps, args.warmup, graph=args.graph)
 
     # per-kernel durations (the library's own events: each kernel's start and end on the device) and

@@ -44,7 +44,9 @@ class DeviceStep:
         # deferred_variance = K >= 2: v_fresh is brought up to date only every K-th compression step;
         # in between, the steps form the up-to-date variance in registers from the array and the sign
         # words and scales of the momenta since it was written (ob_lamb_ratios_apply_hist), which are
-        # the steps' own packed_all / server_scales buffers: K + 1 of them are kept in a ring
+        # the steps' own packed_all / server_scales buffers, kept in a ring.  K + 1 buffers would do;
+        # the ring has 2K, so that the arrangement of buffers and history repeats every 2K steps
+        # (graph_period) and a graph that holds that many consecutive steps can be replayed
         self.vf_period = int(deferred_variance)
         if self.vf_period:
             assert 2 <= self.vf_period <= ob.OB_VF_MAX_OLD + 1 and packed_momentum and fused_apply, \
@@ -81,7 +83,7 @@ class DeviceStep:
         # the W recompressed chunks (two pairs when they double as the momentum)
         self.packed_momentum = bool(packed_momentum)
         self.fused_apply = bool(fused_apply)   # layer_ratios + decompress_apply as one call
-        npairs = (self.vf_period + 1 if self.vf_period else 2) if self.packed_momentum else 1
+        npairs = (2 * self.vf_period if self.vf_period else 2) if self.packed_momentum else 1
         self._pa = [torch.zeros(self.n_pad // 32, **i32) for _ in range(npairs)]
         self._ss = [torch.zeros(self.W, **f32) for _ in range(npairs)]
         self._cur = 0
@@ -99,6 +101,12 @@ class DeviceStep:
     @property
     def server_scales(self):
         return self._ss[self._cur]
+
+    @property
+    def graph_period(self):
+        """Number of consecutive steps after which the buffers a step uses (wire pairs, momentum, the
+        variance's history and its age) are the same again: what one captured graph must hold."""
+        return len(self._pa)
 
     @property
     def _prev(self):
@@ -336,10 +344,8 @@ class DeviceStep:
     def ratios_apply(self, lr):
         if self.vf_period and self.m_is_packed:
             # the variance in deferred form: the array is brought up to date every vf_period-th step
-            # (the history's buffers change from step to step with a period of K(K+1) steps, so a
-            # captured pair of steps cannot carry it)
-            if torch.cuda.is_current_stream_capturing():
-                raise RuntimeError("deferred_variance cannot be captured into a graph: construct with deferred_variance=0")
+            # (which buffers hold the history and how old the array is changes from step to step with
+            # a period of graph_period steps: a captured graph must hold a multiple of that many)
             n_old = self._vf_n_old
             write_v = (n_old + 1 >= self.vf_period)
             ob.ob_lamb_ratios_apply_hist_lp(self.ctx, self._state("read"), self.packed_all, self.server_scales, lr,

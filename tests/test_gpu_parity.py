@@ -1036,18 +1036,23 @@ def test_gpu_rank_inside_a_simulated_job(packed, fused, use_k):
     finish(dev)
 
 
-@pytest.mark.parametrize("case", ["tiny", "bert_mini"])
-def test_step_replayed_from_a_captured_graph(case):
+@pytest.mark.parametrize("case,period", [("tiny", 0), ("bert_mini", 0), ("bert_mini", 2), ("tiny", 3), ("big_and_small", 2)])
+def test_step_replayed_from_a_captured_graph(case, period):
     """The barriers of the single-pass kernels number their launches themselves, so a step needs
-    nothing from the host that changes from call to call: two consecutive steps (with the 1-bit
-    momentum the buffer pairs alternate, so two steps return to the starting arrangement) are
-    captured into one graph and replayed, with eager work and synchronisation between the replays;
-    every replay is checked against the oracle."""
+    nothing from the host that changes from call to call: as many consecutive steps as it takes for
+    the buffers to be arranged as at the start (DeviceStep.graph_period: 2 with the 1-bit momentum,
+    whose buffer pairs alternate; twice the variance's period with the variance in deferred form,
+    whose history lives in a ring of that many buffers) are captured into one graph and replayed,
+    with eager work and synchronisation between the replays; every replay is checked against the
+    oracle."""
     _need_gpu()
     cfg = make_case(case)
-    st, ref, dev = start_pair(cfg, warm_state=False, packed=True, fused=True, deferred=True)
+    st, ref, dev = start_pair(cfg, warm_state=False, packed=True, fused=True, deferred=True,
+                              deferred_variance=period, fused_max_tiles=(8 if case == "big_and_small" else None))
+    P = dev.graph_period
+    assert P == (2 * period if period else 2)
     n_pad = cfg["n_pad"]
-    gbuf = [torch.zeros(n_pad, device=dev.device) for _ in range(2)]
+    gbuf = [torch.zeros(n_pad, device=dev.device) for _ in range(P)]
     lr = 1e-3
 
     def wire(t):   # what the other ranks send at step t, into the pair that step t uses
@@ -1056,8 +1061,10 @@ def test_step_replayed_from_a_captured_graph(case):
         ref.set_foreign_in(fw, fs); ref.set_foreign_all(fa, fss)
         return fw, fs, fa, fss
 
-    # two eager steps first: the momentum is then in 1-bit form and the pairs alternate regularly
-    for t in range(2):
+    # eager steps first: the momentum is then in 1-bit form and the pairs rotate regularly (an odd
+    # number with the deferred variance, so that the capture starts in the middle of a history)
+    n_eager = 3 if period else 2
+    for t in range(n_eager):
         g = gradient(st, cfg, t)
         fw, fs, fa, fss = wire(t)
         dev.begin_step()
@@ -1067,28 +1074,28 @@ def test_step_replayed_from_a_captured_graph(case):
     torch.cuda.synchronize()
     # foreign input of the captured steps lives in fixed device buffers, refilled before each replay
     fin = [dict(pi=torch.zeros_like(dev.packed_in), si=torch.zeros_like(dev.scales_in),
-                pa=torch.zeros_like(dev.packed_all), sa=torch.zeros_like(dev.server_scales)) for _ in range(2)]
+                pa=torch.zeros_like(dev.packed_all), sa=torch.zeros_like(dev.server_scales)) for _ in range(P)]
 
-    def two_steps():
-        for j in range(2):
+    def group_of_steps():
+        for j in range(P):
             dev.begin_step()
             dev.packed_in.copy_(fin[j]["pi"]); dev.scales_in.copy_(fin[j]["si"])
             dev.packed_all.copy_(fin[j]["pa"]); dev.server_scales.copy_(fin[j]["sa"])
             dev.step(gbuf[j], lr)
 
-    cur0 = dev._cur
+    cur0, n_old0 = dev._cur, dev._vf_n_old
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         # capture only records the launches; the steps themselves first run at the first replay
         with torch.cuda.graph(graph, stream=side):
-            two_steps()
+            group_of_steps()
     torch.cuda.current_stream().wait_stream(side)
-    assert dev._cur == cur0     # two steps: back to the starting pair
-    for rep in range(4):
-        for j in range(2):
-            t = 2 + 2 * rep + j
+    assert (dev._cur, dev._vf_n_old) == (cur0, n_old0)     # back to the starting arrangement
+    for rep in range(3 if period else 4):
+        for j in range(P):
+            t = n_eager + P * rep + j
             g = gradient(st, cfg, t)
             fw, fs, fa, fss = wire(t)
             gbuf[j].copy_(torch.from_numpy(g))
