@@ -995,15 +995,14 @@ struct RatioTile {
   }
 };
 
+// The ratio pass of one tile (a workgroup; lds: [BLOCK / WAVE]).
 template <int U, bool HAS_K, bool PACKED_M>
-__global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __restrict__ seg_max,
-                                                       int64_t n_c, int tpc, LayerTab lt,
-                                                       const int* __restrict__ tile_seg0,
-                                                       const int* __restrict__ seg_layer,
-                                                       const int* __restrict__ tile_list) {
+__device__ __forceinline__ void ratios_pass_tile(const RatioArgs& ra, float* __restrict__ seg_max,
+                                                 int64_t n_c, int tpc, const LayerTab& lt,
+                                                 const int* __restrict__ tile_seg0,
+                                                 const int* __restrict__ seg_layer, int tile, float* lds) {
   constexpr int TILE = SPAN * U;
-  __shared__ float lds[BLOCK / WAVE];
-  const TilePos p = tile_pos<TILE>(n_c, tpc, listed_tile(tile_list));
+  const TilePos p = tile_pos<TILE>(n_c, tpc, tile);
   const int l0 = lt.first_layer[p.t];
   if (l0 >= lt.L) return;  // tile lies in the padding (it has no segment)
   // every scalar the tile needs is requested before the streaming loads, so that nothing is
@@ -1032,6 +1031,16 @@ __global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __re
   }
 }
 
+template <int U, bool HAS_K, bool PACKED_M>
+__global__ __launch_bounds__(BLOCK) void k_ratios_pass(RatioArgs ra, float* __restrict__ seg_max,
+                                                       int64_t n_c, int tpc, LayerTab lt,
+                                                       const int* __restrict__ tile_seg0,
+                                                       const int* __restrict__ seg_layer,
+                                                       const int* __restrict__ tile_list) {
+  __shared__ float lds[BLOCK / WAVE];
+  ratios_pass_tile<U, HAS_K, PACKED_M>(ra, seg_max, n_c, tpc, lt, tile_seg0, seg_layer, listed_tile(tile_list), lds);
+}
+
 // Algorithm 1 lines 18-20 for one layer given the raw ratio (thread 0 of a workgroup).
 // rp, ca: r_prev[l] and c_avg[l], read by the caller (early, where their latency hides).
 __device__ __forceinline__ float ratio_clip_commit(float r, int l, float rp, float ca,
@@ -1050,6 +1059,33 @@ __device__ __forceinline__ float ratio_clip_commit(float r, int l, float rp, flo
 }
 
 // K6  per layer: max over the layer's segments (0 for an empty layer), then lines 18-20.
+// One workgroup of NT threads per layer; lds: [NT / WAVE].
+template <int NT>
+__device__ __forceinline__ void ratios_finalize_layer(int l, const float* __restrict__ seg_max,
+                                                      const int* __restrict__ layer_seg0,
+                                                      const float* __restrict__ c_avg,
+                                                      float* __restrict__ r_prev, float* __restrict__ coeff_c,
+                                                      float one_m_thr, float one_p_thr, float r_min,
+                                                      float r_max, float* lds) {
+  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
+  const float rp = r_prev[l], ca = c_avg[l];
+  float r = 0.0f;
+  // four loads in flight per thread: a tensor too large for the kernel with the per-layer barrier
+  // has tens of thousands of segments, and this one workgroup walks them alone (the maxima are
+  // >= +0 or NaN, so the zeros that stand in for missing ones change nothing)
+  for (int s = s0 + threadIdx.x; s < s1; s += 4 * NT) {
+    float q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) q[u] = (s + u * NT < s1) ? seg_max[s + u * NT] : 0.0f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (q[u] > r) r = q[u];
+  }
+  r = block_max<NT>(r, lds);
+  if (threadIdx.x == 0)
+    (void)ratio_clip_commit(r, l, rp, ca, r_prev, coeff_c, one_m_thr, one_p_thr, r_min, r_max);
+}
+
 __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restrict__ seg_max,
                                                             const int* __restrict__ layer_seg0,
                                                             const float* __restrict__ c_avg,
@@ -1061,23 +1097,8 @@ __global__ __launch_bounds__(FBLOCK) void k_ratios_finalize(const float* __restr
   __shared__ float lds[FBLOCK / WAVE];
   const int l = blockIdx.x;
   if (done_elsewhere && done_elsewhere[l]) return;  // the kernel with the per-layer barrier finishes it
-  const int s0 = layer_seg0[l], s1 = layer_seg0[l + 1];
-  const float rp = r_prev[l], ca = c_avg[l];
-  float r = 0.0f;
-  // four loads in flight per thread: a tensor too large for the kernel with the per-layer barrier
-  // has tens of thousands of segments, and this one workgroup walks them alone (the maxima are
-  // >= +0 or NaN, so the zeros that stand in for missing ones change nothing)
-  for (int s = s0 + threadIdx.x; s < s1; s += 4 * FBLOCK) {
-    float q[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) q[u] = (s + u * FBLOCK < s1) ? seg_max[s + u * FBLOCK] : 0.0f;
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (q[u] > r) r = q[u];
-  }
-  r = block_max<FBLOCK>(r, lds);
-  if (threadIdx.x == 0)
-    (void)ratio_clip_commit(r, l, rp, ca, r_prev, coeff_c, one_m_thr, one_p_thr, r_min, r_max);
+  ratios_finalize_layer<FBLOCK>(l, seg_max, layer_seg0, c_avg, r_prev, coeff_c, one_m_thr, one_p_thr, r_min, r_max,
+                                lds);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1263,16 +1284,19 @@ struct LayerSync {
   float* r_prev;
   float* coeff_c;
   float one_m_thr, one_p_thr, r_min, r_max;
+  int n_lead;                   // k_ratios_apply_hist: leading workgroups of the launch, one per layer, that
+                                // finish the layers without listed tiles (0: a kernel of its own has done that)
 };
 
-// Publishes the maximum r of the workgroup's listed tile (of layer l) and arrives; if this was the
+// Publishes the maximum r of the workgroup's listed tile (of layer l; bid: its position in
+// tile_list) and arrives; if this was the
 // layer's last listed tile, finishes the layer.  All threads call; r is valid in thread 0.
 // lp, rp, ca: the layer's ranges, r_prev[l] and c_avg[l], read at the start of the kernel.
-__device__ __forceinline__ void layer_arrive(const LayerSync& ls, int l, const LayerParts& lp, float rp,
+__device__ __forceinline__ void layer_arrive(const LayerSync& ls, int bid, int l, const LayerParts& lp, float rp,
                                              float ca, float r, float* lds, unsigned long long* bc) {
   unsigned long long* counter = &ls.counter[(int64_t)l * CTR_STRIDE];
   if (threadIdx.x == 0) {
-    __hip_atomic_store(&ls.listed_max[blockIdx.x], r, __ATOMIC_RELAXED, OB_AGENT);
+    __hip_atomic_store(&ls.listed_max[bid], r, __ATOMIC_RELAXED, OB_AGENT);
     payload_before_arrival();
     *bc = barrier_arrive(counter, lp.nl);
   }
@@ -1338,7 +1362,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
   rt.load(ra, p);
   float r = rt.template uniform_pass<true>(ra, p, ss, s_prev, kt);
   r = block_max(r, lds);
-  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);   // before the stores of v_fresh: nothing to wait for
+  layer_arrive(ls, (int)blockIdx.x, l0, lp, rp, ca, r, lds, &bc);   // before the stores of v_fresh: nothing to wait for
   rt.store_v_fresh(ra, p);
   v4f X[U];
 #pragma unroll
@@ -1450,7 +1474,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_stream(
     }
   }
   r = block_max(r, lds);
-  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);
+  layer_arrive(ls, (int)blockIdx.x, l0, lp, rp, ca, r, lds, &bc);
 #pragma unroll
   for (int j = 0; j < G; ++j) {
     const int o = (U - G + j) * SPAN + o0;
@@ -1565,10 +1589,9 @@ struct VTerms {
 __device__ __forceinline__ int pair_of(const VTerms& vt, int c, int l) { return vt.pair_base[c] + l - vt.pair_lfirst[c]; }
 
 template <bool HAS_K>
-__global__ __launch_bounds__(BLOCK) void k_variance_terms(RatioArgs ra, VfHist h, VTerms vt,
-                                                          const float* __restrict__ mom_scale,
-                                                          float* __restrict__ out /* = vt.t */) {
-  const int pr = blockIdx.x * BLOCK + threadIdx.x;
+__device__ __forceinline__ void variance_terms_of_pair(const RatioArgs& ra, const VfHist& h, const VTerms& vt,
+                                                       const float* __restrict__ mom_scale,
+                                                       float* __restrict__ out /* = vt.t */, int pr) {
   if (pr >= vt.n_pairs) return;
   const int c = vt.pair_c[pr], l = vt.pair_l[pr];
   const float kt = HAS_K ? mom_scale[l] : 1.0f;
@@ -1583,6 +1606,32 @@ __global__ __launch_bounds__(BLOCK) void k_variance_terms(RatioArgs ra, VfHist h
       o[1] = t_diff;
     }
   }
+}
+
+template <bool HAS_K>
+__global__ __launch_bounds__(BLOCK) void k_variance_terms(RatioArgs ra, VfHist h, VTerms vt,
+                                                          const float* __restrict__ mom_scale,
+                                                          float* __restrict__ out /* = vt.t */) {
+  variance_terms_of_pair<HAS_K>(ra, h, vt, mom_scale, out, (int)(blockIdx.x * BLOCK + threadIdx.x));
+}
+
+// k_variance_terms and k_ratios_pass (momentum in 1-bit form, tile list) in one launch: the first n_lead
+// workgroups form the terms, the others run the plain ratio pass of tile_list[blockIdx.x - n_lead].
+// Neither reads what the other writes; both are over before the kernels that use the terms start.
+template <int U, bool HAS_K>
+__global__ __launch_bounds__(BLOCK) void k_ratios_pass_vterms(RatioArgs ra, float* __restrict__ seg_max,
+                                                              int64_t n_c, int tpc, LayerTab lt,
+                                                              const int* __restrict__ tile_seg0,
+                                                              const int* __restrict__ seg_layer,
+                                                              const int* __restrict__ tile_list, VfHist h,
+                                                              VTerms vt, float* __restrict__ vt_out, int n_lead) {
+  __shared__ float lds[BLOCK / WAVE];
+  const int bid = (int)blockIdx.x - n_lead;
+  if (bid < 0) {
+    variance_terms_of_pair<HAS_K>(ra, h, vt, lt.mom_scale, vt_out, (int)(blockIdx.x * BLOCK + threadIdx.x));
+    return;
+  }
+  ratios_pass_tile<U, HAS_K, true>(ra, seg_max, n_c, tpc, lt, tile_seg0, seg_layer, tile_list[bid], lds);
 }
 
 // Dense view of a variance held in deferred form, over the 1024-element tiles inside the tiles of
@@ -1712,8 +1761,19 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
   constexpr int TILE = SPAN * U;
   __shared__ float lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
+  const int bid = (int)blockIdx.x - ls.n_lead;   // position in tile_list
+  if (bid < 0) {
+    // a leading workgroup: lines 18-20 for layer blockIdx.x if it has no listed tile (its segment maxima
+    // were left by earlier kernels and nothing in this launch reads what is written here), in the shadow of
+    // this launch instead of in a launch of its own
+    const int l = (int)blockIdx.x;
+    if (ls.lt.n_listed[l] == 0)
+      ratios_finalize_layer<BLOCK>(l, ls.seg_max, ls.lt.layer_seg0, ls.c_avg, ls.r_prev, ls.coeff_c, ls.one_m_thr,
+                                   ls.one_p_thr, ls.r_min, ls.r_max, lds);
+    return;
+  }
   const int tpc = ls.lt.tpc;
-  const TilePos p = tile_pos<TILE>(ls.lt.n_c, tpc, ls.lt.tile_list[blockIdx.x]);
+  const TilePos p = tile_pos<TILE>(ls.lt.n_c, tpc, ls.lt.tile_list[bid]);
   const int sp0 = p.c * ls.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span
   const int l0 = lt.first_layer[sp0];  // the layer the tile lies in (lt.first_layer: of the 1024-element tiling)
   const float kt = HAS_K ? lt.mom_scale[l0] : 1.0f;
@@ -1783,7 +1843,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
     }
   }
   r = block_max(r, lds);
-  layer_arrive(ls, l0, lp, rp, ca, r, lds, &bc);   // before any store: nothing to wait for
+  layer_arrive(ls, bid, l0, lp, rp, ca, r, lds, &bc);   // before any store: nothing to wait for
   if (h.write_v) {   // uniform
 #pragma unroll
     for (int u = 0; u < U; ++u) {

@@ -1237,6 +1237,7 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
+  ls.n_lead = 0;
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
 #if OB_LB_STREAM
     OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
@@ -1344,25 +1345,37 @@ ob_status ob_lamb_ratios_apply_hist_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st
   // its launch shape, not by the bytes it moves).  Without the barrier kernel (OB_CFG_NO_FUSED_APPLY)
   // every layer with enough whole tiles counts as too large: no wait anywhere, and still no rewrite
   // of the array at every step.
-  launch_variance_terms(la, ctx, st, ra, vh);
+  // launch 1: the two values of every (chunk, layer) pair and step of the history (leading workgroups)
+  // and the plain ratio pass outside the tiles that work from the history
+  const int n_lead_vt = (ctx->n_pairs + BLOCK - 1) / BLOCK;
+  dispatch1(st->mom_scale != nullptr, [&](auto hk) {
+    OB_LAUNCH(la, KID_RATIOS_PASS, (k_ratios_pass_vterms<U_MAIN, decltype(hk)::value>),
+              sp.n_rest_ratio_tiles + n_lead_vt, ra, ctx->d_seg_max, ctx->n_c, ctx->tpc, lt, ctx->d_tile_seg0,
+              ctx->d_seg_layer, sp.d_rest_ratio_tiles, vh, vterms(ctx), ctx->d_vterms, n_lead_vt);
+  });
+  // launch 2: ratio pass of the layers that are too large for the barrier kernel, from the history
   if (sp.big_on)
     OB_LAUNCH(la, KID_RATIOS_BIG_HIST, k_ratios_big_hist, sp.n_big_tiles, ra, vh, vterms(ctx), ctx->d_seg_max,
               sp.d_big_tiles, ctx->n_c, sp.tpc, ctx->tpc, lt, ctx->d_tile_seg0);
-  launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_ratio_tiles, sp.n_rest_ratio_tiles,
-                sp.on ? sp.d_has_listed : nullptr, sp.on ? sp.n_layers < ctx->L : true);
   if (!sp.on) {
+    OB_LAUNCH_B(la, KID_RATIOS_FINALIZE, k_ratios_finalize, (int)ctx->L, FBLOCK, ctx->d_seg_max,
+                ctx->d_layer_seg0, st->c_avg, st->r_prev, st->coeff_c, ctx->one_m_thr, ctx->one_p_thr,
+                ctx->r_min, ctx->r_max, (const unsigned char*)nullptr);
     launch_apply(la, ctx, st, packed_all, server_scales, lr, nullptr, ctx->n_tiles, xl);
     return la.ok ? OB_OK : OB_ERR_HIP;
   }
+  // launch 3: the barrier kernel; its leading workgroups finish the layers without listed tiles (lines
+  // 18-20 from the segment maxima that launches 1 and 2 left), the others the listed tiles
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
   ls.counter = sp.d_counter; ls.flag = sp.d_flag; ls.errflag = ctx->d_errflag;
   ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
+  ls.n_lead = (sp.n_layers < ctx->L) ? (int)ctx->L : 0;
   dispatch2(st->mom_scale != nullptr, xl.p != nullptr, [&](auto k_, auto lx) {
     OB_LAUNCH(la, KID_RATIOS_APPLY_HIST, (k_ratios_apply_hist<decltype(k_)::value, decltype(lx)::value>),
-              sp.n_fused_tiles, ra, vh, vterms(ctx), aa, ls, lt);
+              sp.n_fused_tiles + ls.n_lead, ra, vh, vterms(ctx), aa, ls, lt);
   });
   launch_apply(la, ctx, st, packed_all, server_scales, lr, sp.d_rest_tiles, sp.n_rest_tiles, xl);
   return la.ok ? OB_OK : OB_ERR_HIP;
