@@ -1284,7 +1284,7 @@ struct LayerSync {
   float* r_prev;
   float* coeff_c;
   float one_m_thr, one_p_thr, r_min, r_max;
-  int n_lead;                   // k_ratios_apply_hist: leading workgroups of the launch, one per layer, that
+  int n_lead;                   // leading workgroups of the launch, one per layer, that
                                 // finish the layers without listed tiles (0: a kernel of its own has done that)
 };
 
@@ -1333,6 +1333,16 @@ __device__ __forceinline__ float layer_wait(const LayerSync& ls, int l, unsigned
   return __uint_as_float((unsigned int)(*bc & 0xffffffffull));
 }
 
+// A leading workgroup of a barrier kernel's launch (blockIdx.x < ls.n_lead, one per layer): lines 18-20 for
+// layer blockIdx.x if it has no listed tile -- its segment maxima were left by earlier kernels and nothing
+// in this launch reads what is written here -- in the shadow of this launch instead of in a launch of its own.
+__device__ __forceinline__ void lead_finalize(const LayerSync& ls, float* lds) {
+  const int l = (int)blockIdx.x;
+  if (ls.lt.n_listed[l] == 0)
+    ratios_finalize_layer<BLOCK>(l, ls.seg_max, ls.lt.layer_seg0, ls.c_avg, ls.r_prev, ls.coeff_c, ls.one_m_thr,
+                                 ls.one_p_thr, ls.r_min, ls.r_max, lds);
+}
+
 // Instantiated for the momentum in 1-bit form only: with a dense momentum the extra array the
 // tile must hold costs more (spills or occupancy) than the second read of v_frozen saves, so the
 // host then takes the two-kernel path.  5 workgroups per CU (<= 96 VGPRs at U = 8) measured best:
@@ -1347,9 +1357,14 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
   constexpr int TILE = SPAN * U;
   __shared__ float lds[BLOCK / WAVE];
   __shared__ unsigned long long bc;
+  const int bid = (int)blockIdx.x - ls.n_lead;   // position in tile_list
+  if (bid < 0) {
+    lead_finalize(ls, lds);
+    return;
+  }
   const int64_t n_c = ls.lt.n_c;
   const int tpc = ls.lt.tpc;
-  const TilePos p = tile_pos<TILE>(n_c, tpc, ls.lt.tile_list[blockIdx.x]);
+  const TilePos p = tile_pos<TILE>(n_c, tpc, ls.lt.tile_list[bid]);
   const int sp0 = p.c * ls.lt.tpc_span + (p.t - p.c * tpc) * U;  // the tile's first span
   const int l0 = lt.first_layer[sp0];  // the layer the tile lies in
   const float ss = ra.sscales[p.c];
@@ -1362,7 +1377,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_resident(
   rt.load(ra, p);
   float r = rt.template uniform_pass<true>(ra, p, ss, s_prev, kt);
   r = block_max(r, lds);
-  layer_arrive(ls, (int)blockIdx.x, l0, lp, rp, ca, r, lds, &bc);   // before the stores of v_fresh: nothing to wait for
+  layer_arrive(ls, bid, l0, lp, rp, ca, r, lds, &bc);   // before the stores of v_fresh: nothing to wait for
   rt.store_v_fresh(ra, p);
   v4f X[U];
 #pragma unroll
@@ -1763,13 +1778,7 @@ __global__ __launch_bounds__(BLOCK, OB_LB_MINW) void k_ratios_apply_hist(
   __shared__ unsigned long long bc;
   const int bid = (int)blockIdx.x - ls.n_lead;   // position in tile_list
   if (bid < 0) {
-    // a leading workgroup: lines 18-20 for layer blockIdx.x if it has no listed tile (its segment maxima
-    // were left by earlier kernels and nothing in this launch reads what is written here), in the shadow of
-    // this launch instead of in a launch of its own
-    const int l = (int)blockIdx.x;
-    if (ls.lt.n_listed[l] == 0)
-      ratios_finalize_layer<BLOCK>(l, ls.seg_max, ls.lt.layer_seg0, ls.c_avg, ls.r_prev, ls.coeff_c, ls.one_m_thr,
-                                   ls.one_p_thr, ls.r_min, ls.r_max, lds);
+    lead_finalize(ls, lds);
     return;
   }
   const int tpc = ls.lt.tpc;

@@ -1225,11 +1225,16 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   const ApplyArgs aa = apply_args(ctx, st, packed_all, server_scales, lr, xl);
   const bool hk = st->mom_scale != nullptr;  // (here the momentum is in 1-bit form and st->m is NULL)
   const LayerTab lt = layer_tab(ctx, st, ctx->d_first_layer);
-  // 1. ratio pass over everything outside the listed tiles; the layers without listed tiles are
-  //    finished here (the ratio of an empty layer, 0, still goes through the clips), the maxima of
-  //    the others wait in seg_max for the layer barrier
+  // 1. ratio pass over everything outside the listed tiles; its segment maxima wait in seg_max: of
+  //    the layers with listed tiles for the layer barrier, of the others (the ratio of an empty layer,
+  //    0, still goes through the clips) for the leading workgroups of the same launch
+#if OB_LB_STREAM
+  const int n_lead = 0;
+#else
+  const int n_lead = (sp.n_layers < ctx->L) ? (int)ctx->L : 0;   // (finished by the barrier kernel's leading workgroups)
+#endif
   launch_ratios(la, ctx, st, packed_all, server_scales, packed_m, pm, sp.d_rest_tiles, sp.n_rest_tiles,
-                sp.d_has_listed, sp.n_layers < ctx->L);
+                sp.d_has_listed, n_lead == 0 && sp.n_layers < ctx->L);
   // 2. the listed tiles: ratio pass, layer barrier, update
   LayerSync ls;
   ls.seg_max = ctx->d_seg_max; ls.listed_max = sp.d_listed_max; ls.lt = listed_tiles(ctx, sp);
@@ -1237,7 +1242,7 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
   ls.spin_limit = ctx->spin_limit;
   ls.c_avg = st->c_avg; ls.r_prev = st->r_prev; ls.coeff_c = st->coeff_c;
   ls.one_m_thr = ctx->one_m_thr; ls.one_p_thr = ctx->one_p_thr; ls.r_min = ctx->r_min; ls.r_max = ctx->r_max;
-  ls.n_lead = 0;
+  ls.n_lead = n_lead;
   dispatch2(hk, xl.p != nullptr, [&](auto k_, auto lx) {
 #if OB_LB_STREAM
     OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
@@ -1245,8 +1250,8 @@ ob_status ob_lamb_ratios_apply_lp(ob_lamb_ctx* ctx, const ob_lamb_state* st, con
               ra, aa, ls, lt);
 #else
     OB_LAUNCH(la, KID_RATIOS_APPLY_RESIDENT,
-              (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), sp.n_fused_tiles, ra,
-              aa, ls, lt);
+              (k_ratios_apply_resident<U_LB, decltype(k_)::value, decltype(lx)::value>), sp.n_fused_tiles + n_lead,
+              ra, aa, ls, lt);
 #endif
   });
   // 3. update of everything outside the listed tiles, with the coefficients of steps 1 and 2
