@@ -86,6 +86,10 @@ CONFIGS = {
     "bert_large_w256": dict(plist=lambda: bert_shaped(1024, 4096, 24, 30528, fused_qkv=False,
                                                       name="bert_large"),
                             W=256, grad="student_t3", steps=100),
+    # the same model with Q, K and V in one tensor per block: 302 tensors, the count Appendix A.5.1 gives
+    "bert_large_fused_qkv": dict(plist=lambda: bert_shaped(1024, 4096, 24, 30528, fused_qkv=True,
+                                                           name="bert_large_fused_qkv"),
+                                 W=64, grad="student_t3", steps=100),
     "gpt_1p3b": dict(plist=lambda: gpt_shaped(2048, 8192, 24, 50304, 2048, name="gpt_1p3b"),
                      W=128, grad="normal_sparse_layers", steps=50),
     # not a benchmark configuration: the GPT-1.3B block repeated until the flat buffer is longer than
